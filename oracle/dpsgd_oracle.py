@@ -1,0 +1,168 @@
+"""ctypes wrapper of the CPU oracle (dpsgd_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+May be imported by tests/, by the smoke check and by the benchmark's cpu_baseline
+leg, and by nothing else.  It imports nothing from the GPU package.  Models are
+the plain dict descriptions the callers pass in (duck-typed; see the keys read
+in `_to_c_model`).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dpsgd_oracle.c")
+_LIB = os.path.join(_HERE, "libdpsgd_oracle.so")
+
+_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4}
+_ACT = {"none": 0, "relu": 1, "tanh": 2}
+
+
+class _Layer(C.Structure):
+    _fields_ = [(n, C.c_int) for n in
+                ("kind", "act", "d_in", "d_out", "c_in", "c_out", "kh", "kw", "stride", "pad", "vocab", "dim")]
+
+
+class _Model(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("layers", C.POINTER(_Layer)), ("in_c", C.c_int), ("in_h", C.c_int),
+                ("in_w", C.c_int), ("seq_len", C.c_int), ("n_classes", C.c_int)]
+
+
+def build(force=False):
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        L.oracle_num_params.restype = C.c_long
+        L.oracle_num_params.argtypes = [C.POINTER(_Model)]
+        L.oracle_example_loss.restype = C.c_double
+        L.oracle_example_loss.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_int]
+        L.oracle_example_grad.restype = C.c_double
+        L.oracle_example_grad.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                          C.POINTER(C.c_long)]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_noise.restype = None
+        L.oracle_noise.argtypes = [C.c_uint64, C.c_long, C.c_void_p]
+        L.oracle_dp_step.restype = C.c_int
+        L.oracle_dp_step.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_double,
+                                     C.c_double, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.POINTER(C.c_long), C.c_int]
+        L.oracle_max_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _to_c_model(m):
+    layers = m["layers"]
+    arr = (_Layer * len(layers))()
+    for i, L in enumerate(layers):
+        c = arr[i]
+        c.kind = _KIND[L["kind"]]
+        c.act = _ACT[L.get("act", "none")]
+        if L["kind"] == "dense":
+            c.d_in, c.d_out = L["d_in"], L["d_out"]
+        elif L["kind"] == "conv2d":
+            c.c_in, c.c_out, c.kh, c.kw, c.stride, c.pad = (L["c_in"], L["c_out"], L["kh"], L["kw"], L["stride"],
+                                                            L["pad"])
+        elif L["kind"] == "maxpool2d":
+            c.kh = c.kw = L["k"]
+            c.stride = L["stride"]
+        elif L["kind"] == "embedding":
+            c.vocab, c.dim = L["vocab"], L["dim"]
+        elif L["kind"] == "lstm_last":
+            c.d_in, c.d_out = L["d_in"], L["hidden"]
+    cm = _Model()
+    cm.n_layers = len(layers)
+    cm.layers = C.cast(arr, C.POINTER(_Layer))
+    inp = m["input"]
+    if inp["kind"] == "image":
+        cm.in_c, cm.in_h, cm.in_w, cm.seq_len = inp["c"], inp["h"], inp["w"], 0
+    else:
+        cm.in_c = cm.in_h = cm.in_w = 1
+        cm.seq_len = inp["seq_len"]
+    cm.n_classes = m["n_classes"]
+    cm._keep = arr
+    return cm
+
+
+def _x_array(m, x):
+    if m["input"]["kind"] == "image":
+        return np.ascontiguousarray(x, dtype=np.float32)
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def num_params(m):
+    cm = _to_c_model(m)
+    return int(lib().oracle_num_params(C.byref(cm)))
+
+
+def example_loss(m, theta64, x_i, y_i):
+    """Loss of one example; theta64 is an fp64 parameter vector."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(theta64, dtype=np.float64)
+    xi = _x_array(m, x_i)
+    return float(lib().oracle_example_loss(C.byref(cm), th.ctypes.data, xi.ctypes.data, int(y_i)))
+
+
+def example_grad(m, theta64, x_i, y_i):
+    """(loss, g[P] fp64, tied pool windows) for one example."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(theta64, dtype=np.float64)
+    xi = _x_array(m, x_i)
+    g = np.empty(th.size, dtype=np.float64)
+    ties = C.c_long(0)
+    loss = lib().oracle_example_grad(C.byref(cm), th.ctypes.data, xi.ctypes.data, int(y_i), g.ctypes.data,
+                                     C.byref(ties))
+    return float(loss), g, int(ties.value)
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.empty(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+    return out
+
+
+def noise(seed, n):
+    """n standard normals (fp64) of the stream keyed by the 64-bit seed."""
+    z = np.empty(int(n), dtype=np.float64)
+    lib().oracle_noise(C.c_uint64(int(seed)), int(n), z.ctypes.data)
+    return z
+
+
+def dp_step(m, params, x, y, clip_c, sigma, seed, clip=True, n_threads=0):
+    """One private step.  Returns dict(out fp32[P], norms fp64[B], clipped_sum fp64[P], ties)."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(params, dtype=np.float32)
+    xa = _x_array(m, x)
+    ya = np.ascontiguousarray(y, dtype=np.int32)
+    B = int(ya.shape[0])
+    P = th.size
+    out = np.empty(P, dtype=np.float32)
+    norms = np.empty(B, dtype=np.float64)
+    csum = np.empty(P, dtype=np.float64)
+    ties = C.c_long(0)
+    rc = lib().oracle_dp_step(C.byref(cm), th.ctypes.data, xa.ctypes.data, ya.ctypes.data, B, float(clip_c),
+                              float(sigma), C.c_uint64(int(seed)), 1 if clip else 0, out.ctypes.data,
+                              norms.ctypes.data, csum.ctypes.data, C.byref(ties), int(n_threads))
+    assert rc == 0
+    return dict(out=out, norms=norms, clipped_sum=csum, ties=int(ties.value))
+
+
+def max_threads():
+    return int(lib().oracle_max_threads())

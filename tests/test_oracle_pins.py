@@ -1,0 +1,289 @@
+"""Pins for the CPU oracle: every check here is against something other than the
+oracle itself -- published known answers, finite differences, PyTorch-CPU autograd,
+closed forms and invariants of the method (paper, Section 1, DPSGD items 2-3)."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import dp_workloads as W
+from oracle import dpsgd_oracle as O
+from tests import torch_ref as TR
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+TINY = W.tiny_models()
+
+
+def _tiny_case(name, batch, seed=3, bias=0.3):
+    m = TINY[name]
+    rng = np.random.default_rng(seed)
+    x, y = W.make_inputs(m, batch, rng, x_dist="normal" if m["input"]["kind"] == "image" else "uniform",
+                         zipf_exponent=0.3)
+    theta = W.init_params(m, rng, bias_scale=bias)
+    if m["input"]["kind"] == "tokens":  # larger embeddings so that the LSTM is not near-linear
+        theta = theta * 4
+    return m, x, y, theta
+
+
+# ----------------------------------------------------------------- architecture wiring
+
+def test_param_counts():
+    # 26,010 and the LSTM formula are the counts the paper prints (Section 3, architectures paragraph).
+    assert O.num_params(W.cfg1_logistic()) == 7850
+    assert O.num_params(W.cfg2_mlp()) == 407050
+    assert O.num_params(W.cfg3_small_cnn()) == 26010
+    assert O.num_params(W.cfg4_cifar_cnn()) == 550570
+    assert O.num_params(W.cfg5_lstm()) == 1080602
+    assert O.num_params(W.cfg5_lstm(vocab=10004)) == 1081002
+    for name, m in list(TINY.items()):
+        assert O.num_params(m) == W.num_params(m)
+
+
+# ----------------------------------------------------------------- Philox and the normal transform
+
+def test_philox_known_answers():
+    n = 0
+    for line in open(os.path.join(GOLD, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        v = [int(t, 16) for t in line.split()]
+        out = O.philox4x32_10(v[:4], v[4:6])
+        assert [int(o) for o in out] == v[6:]
+        n += 1
+    assert n == 3
+
+
+def test_philox_python_bigint_twin():
+    # second, independently written implementation (Python integers)
+    def ref(ctr, key):
+        c, k = list(ctr), list(key)
+        for _ in range(10):
+            p0, p1 = 0xD2511F53 * c[0], 0xCD9E8D57 * c[2]
+            c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & 0xFFFFFFFF, (p0 >> 32) ^ c[3] ^ k[1], p0 & 0xFFFFFFFF]
+            k = [(k[0] + 0x9E3779B9) & 0xFFFFFFFF, (k[1] + 0xBB67AE85) & 0xFFFFFFFF]
+        return c
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        ctr = [int(v) for v in rng.integers(0, 2**32, size=4)]
+        key = [int(v) for v in rng.integers(0, 2**32, size=2)]
+        assert [int(o) for o in O.philox4x32_10(ctr, key)] == ref(ctr, key)
+
+
+def test_noise_layout_matches_philox_blocks():
+    # coordinate j uses block j // 4, key = (seed lo, seed hi), counter = (block, 0, 0, 0)
+    seed = (0x12345678 << 32) | 0x9ABCDEF0
+    z = O.noise(seed, 11)
+    for blk in range(3):
+        r = O.philox4x32_10([blk, 0, 0, 0], [seed & 0xFFFFFFFF, seed >> 32])
+        u = [((int(v) >> 9) + 0.5) / 2**23 for v in r]
+        exp = [math.sqrt(-2 * math.log(u[0])) * math.cos(2 * math.pi * u[1]),
+               math.sqrt(-2 * math.log(u[0])) * math.sin(2 * math.pi * u[1]),
+               math.sqrt(-2 * math.log(u[2])) * math.cos(2 * math.pi * u[3]),
+               math.sqrt(-2 * math.log(u[2])) * math.sin(2 * math.pi * u[3])]
+        for q in range(4):
+            j = blk * 4 + q
+            if j < 11:
+                assert abs(z[j] - exp[q]) < 1e-12
+
+
+def test_noise_is_standard_normal():
+    from scipy import stats
+    n = 4_000_000
+    z = O.noise(7, n)
+    assert abs(z.mean()) < 4 / math.sqrt(n)
+    assert abs(z.var() - 1) < 0.01
+    assert np.abs(z).max() <= math.sqrt(2 * 24 * math.log(2)) + 1e-9  # smallest uniform is 2^-24
+    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 4 / math.sqrt(n)
+    ks = stats.kstest(z[:500_000], "norm")
+    assert ks.pvalue > 1e-3
+    # streams of different seeds are different, same seed is reproducible
+    assert np.array_equal(O.noise(7, 64), z[:64])
+    assert not np.allclose(O.noise(8, 64), z[:64])
+
+
+# ----------------------------------------------------------------- per-example gradients
+
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_gradient_vs_finite_differences(name):
+    m, x, y, theta = _tiny_case(name, 3)
+    th = theta.astype(np.float64)
+    for i in range(x.shape[0]):
+        _, g, _ = O.example_grad(m, th, x[i], y[i])
+        num = np.zeros_like(g)
+        eps = 1e-6
+        for j in range(th.size):
+            tp, tm = th.copy(), th.copy()
+            tp[j] += eps
+            tm[j] -= eps
+            num[j] = (O.example_loss(m, tp, x[i], y[i]) - O.example_loss(m, tm, x[i], y[i])) / (2 * eps)
+        assert np.linalg.norm(g - num) <= 1e-6 * max(1.0, np.linalg.norm(num)), name
+        assert np.linalg.norm(g) > 0
+
+
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_gradient_vs_torch_autograd_tiny(name):
+    m, x, y, theta = _tiny_case(name, 4)
+    th = theta.astype(np.float64)
+    G = TR.per_example_grads(m, th, x, y)
+    for i in range(x.shape[0]):
+        _, g, _ = O.example_grad(m, th, x[i], y[i])
+        assert np.linalg.norm(g - G[i]) <= 1e-10 * max(1.0, np.linalg.norm(G[i]))
+
+
+def _reduced(name):
+    """The five benchmark architectures at their real layer shapes, small batch
+    (the LSTM with a shorter sequence so that the loop oracle stays fast)."""
+    if name == "cfg5_lstm":
+        m = W.cfg5_lstm(vocab=300, seq_len=12, dim=100, hidden=100)
+        rng = np.random.default_rng(1)
+        x, y = W.make_inputs(m, 3, rng)
+        theta = W.init_params(m, rng, bias_scale=0.2)
+        return m, x, y, theta
+    wl = W.make_workload(name, batch=3, seed=1, bias_scale=0.2)
+    return wl["model"], wl["x"], wl["y"], wl["params"]
+
+
+@pytest.mark.parametrize("name", sorted(W.CONFIGS))
+def test_gradient_vs_torch_autograd_benchmark_shapes(name):
+    m, x, y, theta = _reduced(name)
+    th = theta.astype(np.float64)
+    G = TR.per_example_grads(m, th, x, y)
+    for i in range(x.shape[0]):
+        _, g, ties = O.example_grad(m, th, x[i], y[i])
+        assert ties == 0
+        assert np.linalg.norm(g - G[i]) <= 1e-10 * max(1.0, np.linalg.norm(G[i]))
+
+
+# ----------------------------------------------------------------- the step
+
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_no_clip_no_noise_is_the_summed_gradient(name):
+    m, x, y, theta = _tiny_case(name, 6)
+    r = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
+    ref = TR.summed_grad(m, theta.astype(np.float64), x, y)
+    assert np.linalg.norm(r["clipped_sum"] - ref) <= 1e-10 * np.linalg.norm(ref)
+    assert np.array_equal(r["out"], r["clipped_sum"].astype(np.float32))
+    # the non-private switch gives the same thing even with a tiny C
+    r2 = O.dp_step(m, theta, x, y, 1e-3, 0.0, 0, clip=False)
+    assert np.array_equal(r2["out"], r["out"])
+
+
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_batch_of_one_is_a_single_clipped_gradient(name):
+    m, x, y, theta = _tiny_case(name, 1)
+    G = TR.per_example_grads(m, theta.astype(np.float64), x, y)[0]
+    n = np.linalg.norm(G)
+    for Cc in (0.5 * n, 2.0 * n):
+        r = O.dp_step(m, theta, x, y, Cc, 0.0, 0)
+        exp = G * min(1.0, Cc / n)
+        assert np.linalg.norm(r["clipped_sum"] - exp) <= 1e-10 * np.linalg.norm(exp)
+        assert abs(r["norms"][0] - n) <= 1e-10 * n
+
+
+@pytest.mark.parametrize("name", sorted(TINY))
+def test_clip_invariants(name):
+    m, x, y, theta = _tiny_case(name, 8)
+    B = x.shape[0]
+    G = TR.per_example_grads(m, theta.astype(np.float64), x, y)
+    norms = np.linalg.norm(G, axis=1)
+    r0 = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
+    assert np.allclose(r0["norms"], norms, rtol=1e-10)
+    # (a) each clipped gradient has norm <= C; (b) the whole sum has norm <= B*C
+    Cmed = float(np.median(norms))
+    r = O.dp_step(m, theta, x, y, Cmed, 0.0, 0)
+    s = np.minimum(1.0, Cmed / norms)
+    assert np.all(np.linalg.norm(G * s[:, None], axis=1) <= Cmed * (1 + 1e-12))
+    assert np.linalg.norm(r["clipped_sum"]) <= B * Cmed * (1 + 1e-12)
+    exp = (G * s[:, None]).sum(0)
+    assert np.linalg.norm(r["clipped_sum"] - exp) <= 1e-10 * np.linalg.norm(exp)
+    assert (s < 1).any() and (s == 1).any()
+    # (c) C above every norm: nothing is clipped
+    r = O.dp_step(m, theta, x, y, float(norms.max()) * 1.01, 0.0, 0)
+    assert np.allclose(r["clipped_sum"], r0["clipped_sum"], rtol=1e-12, atol=0)
+    # (d) C below every norm: the result is linear in C
+    Clow = 0.1 * float(norms.min())
+    ra = O.dp_step(m, theta, x, y, Clow, 0.0, 0)["clipped_sum"]
+    rb = O.dp_step(m, theta, x, y, 2 * Clow, 0.0, 0)["clipped_sum"]
+    assert np.linalg.norm(rb - 2 * ra) <= 1e-12 * np.linalg.norm(rb)
+
+
+def test_batch_order_invariance_and_thread_count():
+    m, x, y, theta = _tiny_case("tiny_conv2", 9)
+    perm = np.random.default_rng(0).permutation(9)
+    a = O.dp_step(m, theta, x, y, 0.7, 0.0, 0, n_threads=1)["clipped_sum"]
+    b = O.dp_step(m, theta, x[perm], y[perm], 0.7, 0.0, 0, n_threads=3)["clipped_sum"]
+    assert np.linalg.norm(a - b) <= 1e-12 * np.linalg.norm(a)
+
+
+def test_noise_term_of_the_step():
+    m, x, y, theta = _tiny_case("tiny_dense", 5)
+    P = theta.size
+    seed, Cc, sigma = 1234567890123, 0.8, 1.1
+    r0 = O.dp_step(m, theta, x, y, Cc, 0.0, seed)
+    r1 = O.dp_step(m, theta, x, y, Cc, sigma, seed)
+    z = O.noise(seed, P)
+    exp = (r0["clipped_sum"] + sigma * Cc * z).astype(np.float32)
+    assert np.array_equal(r1["out"], exp)
+    # empty batch: pure noise
+    r2 = O.dp_step(m, theta, x[:0], y[:0], Cc, sigma, seed)
+    assert np.array_equal(r2["out"], (sigma * Cc * z).astype(np.float32))
+
+
+def test_logistic_closed_form():
+    # W = 0, b = 0: softmax is uniform, delta = 1/10 - onehot, ||delta||^2 = 0.9,
+    # ||g_i|| = sqrt(0.9 (||x_i||^2 + 1)) and the step is sum_i (C/||g_i||) [x_i; 1] (x) delta_i.
+    wl = W.make_workload("cfg1_logistic", batch=16, seed=5)
+    m, x, y = wl["model"], wl["x"].reshape(16, 784), wl["y"]
+    theta = np.zeros(7850, dtype=np.float32)
+    r = O.dp_step(m, theta, x, y, 1.0, 0.0, 0)
+    xd = x.astype(np.float64)
+    delta = np.full((16, 10), 0.1)
+    delta[np.arange(16), y] -= 1.0
+    n = np.sqrt(0.9 * ((xd ** 2).sum(1) + 1))
+    assert np.allclose(r["norms"], n, rtol=1e-12)
+    s = np.minimum(1.0, 1.0 / n)
+    gW = np.einsum("bi,bo->io", xd * s[:, None], delta)
+    gb = (delta * s[:, None]).sum(0)
+    exp = np.concatenate([gW.ravel(), gb])
+    assert np.linalg.norm(r["clipped_sum"] - exp) <= 1e-12 * np.linalg.norm(exp)
+
+
+def test_dense_norm_identity():
+    # Section 1 (per-example norms for fully-connected layers): ||a (x) delta||_F = ||a|| ||delta||.
+    m, x, y, theta = _tiny_case("tiny_dense_tanh", 4)
+    th = theta.astype(np.float64)
+    for i in range(4):
+        _, g, _ = O.example_grad(m, th, x[i], y[i])
+        total = 0.0
+        acts = [x[i].reshape(-1).astype(np.float64)]
+        # recompute activations with numpy to get ||a|| for each layer
+        for li, name, shp, off in W.param_tensors(m):
+            if name == "W":
+                Wm = th[off:off + shp[0] * shp[1]].reshape(shp)
+                b = th[off + shp[0] * shp[1]: off + shp[0] * shp[1] + shp[1]]
+                z = acts[-1] @ Wm + b
+                act = m["layers"][li]["act"]
+                acts.append(np.tanh(z) if act == "tanh" else np.maximum(z, 0) if act == "relu" else z)
+                gW = g[off:off + shp[0] * shp[1]]
+                gb = g[off + shp[0] * shp[1]: off + shp[0] * shp[1] + shp[1]]
+                # delta is the bias gradient
+                assert abs(np.linalg.norm(gW) - np.linalg.norm(acts[-2]) * np.linalg.norm(gb)) <= 1e-12
+                total += (np.linalg.norm(acts[-2]) ** 2 + 1) * np.linalg.norm(gb) ** 2
+        assert abs(math.sqrt(total) - np.linalg.norm(g)) <= 1e-12
+
+
+def test_embedding_duplicates_are_summed_before_the_norm():
+    m = TINY["tiny_lstm"]
+    rng = np.random.default_rng(2)
+    theta = (W.init_params(m, rng, bias_scale=0.3) * 4).astype(np.float64)
+    E = 7 * 3
+    x_same = np.full(5, 2, dtype=np.int32)
+    _, g, _ = O.example_grad(m, theta, x_same, 1)
+    gE = g[:E].reshape(7, 3)
+    assert np.count_nonzero(np.abs(gE).sum(1)) == 1          # one row holds the sum over all steps
+    x_distinct = np.array([0, 1, 2, 3, 4], dtype=np.int32)
+    _, g2, _ = O.example_grad(m, theta, x_distinct, 1)
+    assert np.count_nonzero(np.abs(g2[:E].reshape(7, 3)).sum(1)) == 5
+    G = TR.per_example_grads(m, theta, np.stack([x_same, x_distinct]), np.array([1, 1]))
+    assert np.allclose(G[0], g, atol=1e-12) and np.allclose(G[1], g2, atol=1e-12)
