@@ -1,0 +1,143 @@
+/*
+ * dp_step.h -- C ABI of the MI355X (gfx950) private gradient step of DPSGD.
+ *
+ * One call to dp_step performs items 2-3 of the DPSGD procedure enumerated in
+ * Section 1 of the paper (arxiv 2010.09063) for one minibatch:
+ *   2(a) per-example gradient g_i of the example's own loss, for every layer;
+ *   2(b) clip: g_i <- g_i * min(1, C / ||g_i||_2), one L2 norm over all parameters;
+ *   3    sum the clipped gradients over the batch and add N(0, sigma^2 C^2 I).
+ * Drawing the minibatch (item 1) and the parameter update (item 4) stay with the
+ * caller.  The per-example gradients are never written out: dense layers use
+ * the norm identity ||a (x) delta|| = ||a|| ||delta|| (Section 1, the
+ * fully-connected per-example norm trick), convolution / recurrent layers
+ * contract each example's activations with its backprops tile by tile and keep
+ * only the squared norm; the clipped sum is the contraction A^T diag(s) Delta.
+ *
+ * Pointers marked "device" are HIP device memory owned by the caller (the
+ * library never frees them and keeps no reference after the call's stream
+ * work); pointers marked "host" are ordinary host memory.  All functions return
+ * DP_OK (0) or a negative dp_status; no C++ exception crosses this boundary.
+ * After an error the contents of out_grad are unspecified.
+ */
+#ifndef DP_STEP_H
+#define DP_STEP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dp_ctx dp_ctx; /* opaque; owned by the library */
+
+typedef enum {
+  DP_OK = 0,
+  DP_EINVAL = -1, /* null pointer, bad shape, batch > max_batch, C <= 0, sigma < 0, NaN */
+  DP_ENOMEM = -2, /* workspace allocation failed */
+  DP_EHIP = -3,   /* a HIP runtime call failed; see dp_step_strerror */
+  DP_EUNSUPPORTED = -4 /* layer sequence the kernels do not cover */
+} dp_status;
+
+typedef enum {
+  DP_DENSE = 0,     /* z = a W + b,   W[in_features][out_features] row-major, b[out_features] */
+  DP_CONV2D = 1,    /* cross-correlation, zero padding, W[out_ch][in_ch][kh][kw], b[out_ch]   */
+  DP_MAXPOOL2D = 2, /* window kh x kw, stride, no padding; gradient goes to the first maximum */
+  DP_EMBEDDING = 3, /* E[vocab][embed_dim]; input int32 token ids [B, seq_len]                */
+  DP_LSTM_LAST = 4  /* one-layer LSTM, returns the last hidden state; W_ih[in_features][4H],
+                       W_hh[H][4H], b[4H]; 4H axis ordered i, f, g, o; h_0 = c_0 = 0          */
+} dp_layer_kind;
+
+typedef enum { DP_ACT_NONE = 0, DP_ACT_RELU = 1, DP_ACT_TANH = 2 } dp_act;
+
+typedef struct {
+  int kind;                                 /* dp_layer_kind                       */
+  int act;                                  /* dp_act, applied to dense / conv out */
+  int in_features, out_features;            /* dense; lstm: input width, (unused)  */
+  int in_ch, out_ch, kh, kw, stride, pad;   /* conv; pool uses kh, kw, stride      */
+  int vocab, embed_dim;                     /* embedding                           */
+  int hidden;                               /* lstm                                */
+} dp_layer_desc;
+
+typedef struct {
+  int n_layers;
+  const dp_layer_desc *layers; /* host; read during dp_step_init only                    */
+  int in_c, in_h, in_w;        /* image input NCHW (a feature vector is in_c x 1 x 1)    */
+  int seq_len;                 /* > 0: the input is int32 token ids [B, seq_len]         */
+  int n_classes;               /* width of the last layer; loss = softmax cross-entropy  */
+} dp_model_desc;
+
+/*
+ * dp_step_init -- fixes every shape, allocates all workspace for batches up to
+ * max_batch and returns a context (the static-shape specialisation that Section
+ * 2.2, "Just-In-Time Compilation", credits for buffer reuse: shapes are known
+ * before the first step so nothing is allocated afterwards).
+ *   model      host; copied.
+ *   hip_stream a hipStream_t (NULL = the default stream); every later call
+ *              enqueues its work there.
+ *   out        host; receives the context.
+ * Flat parameter layout: layers in order, each weight tensor then its bias, in
+ * the layouts named at dp_layer_kind.
+ */
+int dp_step_init(const dp_model_desc *model, int max_batch, void *hip_stream, dp_ctx **out);
+
+/* Number of fp32 parameters P of the model (0 if ctx is NULL). */
+size_t dp_step_num_params(const dp_ctx *ctx);
+
+/* Bytes of device workspace the context holds. */
+size_t dp_step_workspace_bytes(const dp_ctx *ctx);
+
+/*
+ * dp_step -- the private step (Section 1, DPSGD items 2-3).
+ *   params   device fp32[P]
+ *   x        device fp32[batch, in_c, in_h, in_w] or int32[batch, seq_len]
+ *   y        device int32[batch], class ids in [0, n_classes)
+ *   batch    0 <= batch <= max_batch (0 yields pure noise)
+ *   C        clip norm, > 0; +INFINITY disables clipping (then sigma must be 0)
+ *   sigma    noise multiplier, >= 0; 0 adds exactly nothing
+ *   seed     key of the Philox4x32-10 stream; coordinate j takes lane j%4 of block
+ *            j/4, counter (block lo, block hi, 0, 0); uniforms are
+ *            ((r >> 9) + 1/2) 2^-23, two Box-Muller pairs per block
+ *   out_grad device fp32[P] = sum_i g_i min(1, C/||g_i||) + sigma C z   (a sum, not a mean)
+ * Asynchronous: work is enqueued on the context's stream; no host sync, no
+ * allocation.  Token ids and labels out of range are undefined behaviour.
+ */
+int dp_step(dp_ctx *ctx, const float *params, const void *x, const int32_t *y, int batch, float C, float sigma,
+            uint64_t seed, float *out_grad);
+
+/*
+ * dp_step_nonprivate -- the ordinary summed gradient sum_i g_i with the same
+ * forward / backward kernels and no norms, clipping or noise (the comparator of
+ * the paper's private / non-private runtime ratio, Table 1).
+ */
+int dp_step_nonprivate(dp_ctx *ctx, const float *params, const void *x, const int32_t *y, int batch,
+                       float *out_grad);
+
+/*
+ * dp_step_last_norms -- copies the unclipped per-example norms ||g_i|| of the
+ * most recent dp_step into norms_out (device fp32[batch of that step]);
+ * enqueued on the context's stream.  Test hook for the clipping invariant.
+ */
+int dp_step_last_norms(dp_ctx *ctx, float *norms_out);
+
+/*
+ * Per-kernel timing.  With profiling on, every kernel launch of later steps is
+ * bracketed by HIP events on the context's stream.  dp_step_profile_read
+ * synchronises the stream and returns, for up to `cap` distinct kernel labels
+ * in launch order: the label (pointer into the context, valid until free), the
+ * number of launches since the last reset and the summed milliseconds.
+ * Returns the number of labels (or a negative dp_status).
+ */
+int dp_step_profile(dp_ctx *ctx, int enable);
+int dp_step_profile_read(dp_ctx *ctx, int cap, const char **labels, int *launches, float *total_ms, int reset);
+
+/* Static description of a status code, plus the last HIP error text for DP_EHIP. */
+const char *dp_step_strerror(int code);
+
+/* Releases the context and its workspace (NULL is a no-op). */
+void dp_step_free(dp_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DP_STEP_H */

@@ -1,0 +1,696 @@
+// C-ABI library of the private gradient step (see include/dp_step.h).
+// Plan at init (all shapes static, all workspace allocated once), then every
+// dp_step only enqueues kernels on the context's stream.
+#include "../../include/dp_step.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <type_traits>
+#include <vector>
+
+#include "gemm_tile.h"
+#include "kernels_misc.h"
+#include "kernels_seq.h"
+#include "operands.h"
+
+static thread_local char g_hip_err[256] = "";
+
+#define HIP_TRY(expr)                                                                                \
+  do {                                                                                               \
+    hipError_t e_ = (expr);                                                                          \
+    if (e_ != hipSuccess) {                                                                          \
+      snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return DP_EHIP;                                                                                \
+    }                                                                                                \
+  } while (0)
+
+// ---------------------------------------------------------------- epilogues / problems
+
+template <class A_, class B_>
+struct ProbBase {
+  typedef A_ A;
+  typedef B_ B;
+  int M, N, K, k_chunk, tiles_n;
+  A a;
+  B b;
+};
+
+// out[m*ld + n] = act(acc + bias[n])                                  (dense forward, LSTM input projection)
+template <class A_, class B_>
+struct ProbBiasAct : ProbBase<A_, B_> {
+  static constexpr bool kReduce = false;
+  float *out; const float *bias; int ld, act;
+  DEVI void store(int, int, int m, int n, float v) const { out[(long)m * ld + n] = act_apply(act, v + bias[n]); }
+};
+
+// out[m*ld + n] = acc * act'(a_prev[m*ld + n])                        (dense backward-data)
+template <class A_, class B_>
+struct ProbBwdAct : ProbBase<A_, B_> {
+  static constexpr bool kReduce = false;
+  float *out; const float *a_prev; int ld, act;
+  DEVI void store(int, int, int m, int n, float v) const {
+    long o = (long)m * ld + n;
+    out[o] = act ? v * act_deriv_from_out(act, a_prev[o]) : v;
+  }
+};
+
+// conv forward: m = output channel, n = pixel (b, p): out[b, m, p] = act(acc + bias[m])
+template <class A_, class B_>
+struct ProbConvFwd : ProbBase<A_, B_> {
+  static constexpr bool kReduce = false;
+  float *out; const float *bias; int D, P, act; FastDiv dP;
+  DEVI void store(int, int, int m, int n, float v) const {
+    int b = (int)dP.div(n), p = n - b * P;
+    out[((long)b * D + m) * P + p] = act_apply(act, v + bias[m]);
+  }
+};
+
+// conv backward-data: m = input channel, n = input pixel (b, ih*W+iw): out[b, m, hw] = acc * act'(a_prev)
+template <class A_, class B_>
+struct ProbConvBwd : ProbBase<A_, B_> {
+  static constexpr bool kReduce = false;
+  float *out; const float *a_prev; int C, HW, act; FastDiv dHW;
+  DEVI void store(int, int, int m, int n, float v) const {
+    int b = (int)dHW.div(n), r = n - b * HW;
+    long o = ((long)b * C + m) * HW + r;
+    out[o] = act ? v * act_deriv_from_out(act, a_prev[o]) : v;
+  }
+};
+
+// split-K partial of a clipped sum: part[split*stride + m*ldm + n]; if bias_col >= 0 the column
+// n == bias_col goes to bias_off + m instead (conv: bias gradient is the ones-tap column).
+template <class A_, class B_>
+struct ProbPartial : ProbBase<A_, B_> {
+  static constexpr bool kReduce = false;
+  float *part; long stride; int ldm, bias_col; long bias_off;
+  DEVI void store(int, int split, int m, int n, float v) const {
+    long o = (n == bias_col) ? bias_off + m : (long)m * ldm + n;
+    part[split * stride + o] = v;
+  }
+};
+
+// per-example weight-gradient tile, squared and summed: slot[(slot0 + tile)*slot_stride + z]
+template <class A_, class B_>
+struct ProbSqNorm : ProbBase<A_, B_> {
+  static constexpr bool kReduce = true;
+  float *slots; long slot_stride; int slot0;
+  DEVI float contrib(int, int, int, float v) const { return v * v; }
+  DEVI void store_tile(int z, int tile, float s) const { slots[(long)(slot0 + tile) * slot_stride + z] = s; }
+};
+
+// ---------------------------------------------------------------- context
+
+struct Layer {
+  dp_layer_desc d;
+  int inC, inH, inW, outC, outH, outW; // chw view; vectors are C x 1 x 1; sequences: C = T, H = D
+  long in_size, out_size;              // floats per example
+  long p_off, p_count;
+  float *a = nullptr; // output activations [maxB, out_size]
+  float *g = nullptr; // gradient w.r.t. pre-activation (w.r.t. output where the layer has no activation)
+  uint8_t *arg = nullptr;
+  float *part = nullptr; // split-K partials of the clipped sum [max_split][p_count]
+  int max_split = 0;
+  int max_slots = 0;
+  ConvGeom geom;
+  // lstm
+  float *gates = nullptr, *cs = nullptr, *hs = nullptr;
+  int T = 0, Din = 0, H = 0;
+};
+
+struct ProfRec { int label; hipEvent_t e0, e1; };
+
+struct dp_ctx {
+  dp_model_desc m;
+  std::vector<Layer> L;
+  int maxB = 0;
+  long P = 0;
+  hipStream_t stream = nullptr;
+  std::vector<void *> allocs;
+  size_t ws_bytes = 0;
+  float *slots = nullptr; int max_slots = 0;
+  float *norms = nullptr, *s = nullptr;
+  int last_batch = -1;
+  // profiling
+  bool prof = false;
+  std::vector<const char *> labels; // string literals
+  std::vector<int> label_launches;
+  std::vector<float> label_ms;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+  size_t pool_used = 0;
+  int err = 0;
+};
+
+static int label_id(dp_ctx *c, const char *name) {
+  for (size_t i = 0; i < c->labels.size(); ++i)
+    if (strcmp(c->labels[i], name) == 0) return (int)i;
+  c->labels.push_back(name);
+  c->label_launches.push_back(0);
+  c->label_ms.push_back(0.f);
+  return (int)c->labels.size() - 1;
+}
+
+// Brackets a launch with events when profiling is on.
+struct Launcher {
+  dp_ctx *c;
+  template <class F>
+  void operator()(const char *label, dim3, dim3, F &&f) const {
+    if (c->prof && c->pool_used + 2 <= c->pool.size()) {
+      ProfRec r;
+      r.label = label_id(c, label);
+      r.e0 = c->pool[c->pool_used++];
+      r.e1 = c->pool[c->pool_used++];
+      (void)hipEventRecord(r.e0, c->stream);
+      f(c->stream);
+      (void)hipEventRecord(r.e1, c->stream);
+      c->recs.push_back(r);
+    } else {
+      f(c->stream);
+    }
+  }
+};
+
+template <class T>
+static int dev_alloc(dp_ctx *c, T **p, size_t n) {
+  void *q = nullptr;
+  size_t bytes = (n ? n : 1) * sizeof(T);
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
+    return DP_ENOMEM;
+  }
+  c->allocs.push_back(q);
+  c->ws_bytes += bytes;
+  *p = (T *)q;
+  return DP_OK;
+}
+
+static ConvGeom make_geom(const Layer &l) {
+  ConvGeom g;
+  g.C = l.inC; g.H = l.inH; g.W = l.inW; g.D = l.outC; g.OH = l.outH; g.OW = l.outW;
+  g.KH = l.d.kh; g.KW = l.d.kw; g.S = l.d.stride; g.PAD = l.d.pad;
+  g.CKK = g.C * g.KH * g.KW; g.P = g.OH * g.OW;
+  g.dP.init(g.P); g.dOW.init(g.OW); g.dKK.init(g.KH * g.KW); g.dKW.init(g.KW); g.dHW.init(g.H * g.W); g.dW.init(g.W);
+  return g;
+}
+
+#define DP_MAX_SPLIT 64
+
+// ---------------------------------------------------------------- init / free
+
+extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip_stream, dp_ctx **out) {
+  if (!model || !out || max_batch < 1 || model->n_layers < 1 || !model->layers) return DP_EINVAL;
+  dp_ctx *c = new (std::nothrow) dp_ctx();
+  if (!c) return DP_ENOMEM;
+  c->m = *model;
+  c->m.layers = nullptr;
+  c->maxB = max_batch;
+  c->stream = (hipStream_t)hip_stream;
+  int rc = DP_OK;
+  int curC = model->in_c, curH = model->in_h, curW = model->in_w;
+  bool is_tok = model->seq_len > 0, is_seq = false;
+  long off = 0;
+  int total_slots = 0;
+  for (int i = 0; i < model->n_layers && rc == DP_OK; ++i) {
+    Layer l;
+    l.d = model->layers[i];
+    l.inC = curC; l.inH = curH; l.inW = curW;
+    l.p_off = off;
+    l.p_count = 0;
+    switch (l.d.kind) {
+    case DP_DENSE:
+      if (is_tok || is_seq || l.d.in_features != curC * curH * curW || l.d.out_features < 1) { rc = DP_EINVAL; break; }
+      l.outC = l.d.out_features; l.outH = l.outW = 1;
+      l.p_count = (long)l.d.in_features * l.d.out_features + l.d.out_features;
+      l.max_slots = 1;
+      break;
+    case DP_CONV2D:
+      if (is_tok || is_seq || l.d.in_ch != curC || l.d.kh < 1 || l.d.kw < 1 || l.d.stride < 1 || l.d.pad < 0) { rc = DP_EINVAL; break; }
+      l.outC = l.d.out_ch;
+      l.outH = (curH + 2 * l.d.pad - l.d.kh) / l.d.stride + 1;
+      l.outW = (curW + 2 * l.d.pad - l.d.kw) / l.d.stride + 1;
+      if (l.outH < 1 || l.outW < 1) { rc = DP_EINVAL; break; }
+      l.p_count = (long)l.d.out_ch * l.d.in_ch * l.d.kh * l.d.kw + l.d.out_ch;
+      l.max_slots = ceil_div(l.d.out_ch, 32) * ceil_div(l.d.in_ch * l.d.kh * l.d.kw + 1, 32);
+      break;
+    case DP_MAXPOOL2D:
+      if (is_tok || is_seq || i == 0 || l.d.kh < 1 || l.d.kw < 1 || l.d.stride < 1 || l.d.kh * l.d.kw > 255) { rc = DP_EINVAL; break; }
+      if (model->layers[i - 1].kind != DP_CONV2D) { rc = DP_EUNSUPPORTED; break; }
+      l.outC = curC;
+      l.outH = (curH - l.d.kh) / l.d.stride + 1;
+      l.outW = (curW - l.d.kw) / l.d.stride + 1;
+      if (l.outH < 1 || l.outW < 1) { rc = DP_EINVAL; break; }
+      break;
+    case DP_EMBEDDING:
+      if (!is_tok || i != 0 || l.d.vocab < 1 || l.d.vocab > (1 << 21) || l.d.embed_dim < 1 || model->seq_len > EMB_TMAX) { rc = DP_EINVAL; break; }
+      l.inC = model->seq_len; l.inH = l.inW = 1;
+      l.outC = model->seq_len; l.outH = l.d.embed_dim; l.outW = 1;
+      l.p_count = (long)l.d.vocab * l.d.embed_dim;
+      l.max_slots = 1;
+      is_tok = false; is_seq = true;
+      break;
+    case DP_LSTM_LAST:
+      if (!is_seq || l.d.hidden < 1 || l.d.in_features != curH) { rc = DP_EINVAL; break; }
+      if (l.d.hidden > 128 || i == 0 || model->layers[i - 1].kind != DP_EMBEDDING) { rc = DP_EUNSUPPORTED; break; }
+      l.T = curC; l.Din = curH; l.H = l.d.hidden;
+      l.outC = l.H; l.outH = l.outW = 1;
+      l.p_count = (long)l.Din * 4 * l.H + (long)l.H * 4 * l.H + 4 * l.H;
+      l.max_slots = ceil_div(l.Din + l.H + 1, 32) * ceil_div(4 * l.H, 32);
+      is_seq = false;
+      break;
+    default: rc = DP_EINVAL;
+    }
+    if (rc != DP_OK) break;
+    l.in_size = (long)l.inC * l.inH * l.inW;
+    l.out_size = (long)l.outC * l.outH * l.outW;
+    if (l.d.kind == DP_CONV2D) l.geom = make_geom(l);
+    off += l.p_count;
+    total_slots += l.max_slots;
+    curC = l.outC; curH = l.outH; curW = l.outW;
+    c->L.push_back(l);
+  }
+  if (rc == DP_OK) {
+    const Layer &last = c->L.back();
+    if (is_tok || is_seq || last.out_size != model->n_classes || last.d.kind != DP_DENSE || last.d.act != DP_ACT_NONE)
+      rc = DP_EINVAL;
+    int nparam = 0;
+    for (auto &l : c->L) nparam += l.p_count > 0;
+    if (nparam > DP_MAX_SEG) rc = DP_EUNSUPPORTED;
+  }
+  if (rc != DP_OK) { delete c; return rc; }
+  c->P = off;
+  c->max_slots = total_slots;
+  const long mb = max_batch;
+  for (auto &l : c->L) {
+    if (rc != DP_OK) break;
+    const bool emb = l.d.kind == DP_EMBEDDING;
+    // the embedding's "activation" is never written (the lookup is fused into the next contraction)
+    if (!emb) rc = dev_alloc(c, &l.a, mb * l.out_size);
+    if (rc == DP_OK) rc = dev_alloc(c, &l.g, mb * l.out_size);
+    if (rc == DP_OK && l.d.kind == DP_MAXPOOL2D) rc = dev_alloc(c, &l.arg, mb * l.out_size);
+    if (rc == DP_OK && l.p_count > 0) {
+      l.max_split = emb ? 1 : DP_MAX_SPLIT;
+      rc = dev_alloc(c, &l.part, (size_t)l.max_split * l.p_count);
+    }
+    if (rc == DP_OK && l.d.kind == DP_LSTM_LAST) {
+      rc = dev_alloc(c, &l.gates, mb * l.T * 4 * l.H);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.cs, mb * l.T * l.H);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.hs, mb * l.T * l.H);
+    }
+  }
+  if (rc == DP_OK) rc = dev_alloc(c, &c->slots, (size_t)c->max_slots * mb);
+  if (rc == DP_OK) rc = dev_alloc(c, &c->norms, mb);
+  if (rc == DP_OK) rc = dev_alloc(c, &c->s, mb);
+  if (rc != DP_OK) { dp_step_free(c); return rc; }
+  *out = c;
+  return DP_OK;
+}
+
+extern "C" void dp_step_free(dp_ctx *c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (void *p : c->allocs) (void)hipFree(p);
+  for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
+  delete c;
+}
+
+extern "C" size_t dp_step_num_params(const dp_ctx *c) { return c ? (size_t)c->P : 0; }
+extern "C" size_t dp_step_workspace_bytes(const dp_ctx *c) { return c ? c->ws_bytes : 0; }
+
+extern "C" const char *dp_step_strerror(int code) {
+  switch (code) {
+  case DP_OK: return "ok";
+  case DP_EINVAL: return "invalid argument";
+  case DP_ENOMEM: return g_hip_err[0] ? g_hip_err : "out of device memory";
+  case DP_EHIP: return g_hip_err[0] ? g_hip_err : "HIP runtime error";
+  case DP_EUNSUPPORTED: return "layer sequence or size not supported by the kernels";
+  default: return "unknown status";
+  }
+}
+
+// ---------------------------------------------------------------- the step
+
+static inline dim3 grid1d(long n, int block) { return dim3((unsigned)((n + block - 1) / block)); }
+
+template <int HP>
+static void launch_lstm_fwd(const Launcher &Ln, Layer &l, const float *Whh, int B) {
+  dim3 grid(ceil_div(B, LSTM_NE)), block(256);
+  Ln("lstm_fwd", grid, block, [&](hipStream_t st) {
+    hipLaunchKernelGGL(lstm_fwd_kernel<HP>, grid, block, 0, st, l.gates, Whh, l.hs, l.cs, l.a, B, l.T, l.H);
+  });
+}
+template <int HP>
+static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int B) {
+  dim3 grid(ceil_div(B, LSTM_NE)), block(256);
+  Ln("lstm_bwd", grid, block, [&](hipStream_t st) {
+    hipLaunchKernelGGL(lstm_bwd_kernel<HP>, grid, block, 0, st, l.gates, (const float *)l.cs, Whh, (const float *)l.g, B, l.T, l.H);
+  });
+}
+#define LSTM_DISPATCH(fn, H, ...)                 \
+  do {                                            \
+    if ((H) <= 4) fn<4>(__VA_ARGS__);             \
+    else if ((H) <= 8) fn<8>(__VA_ARGS__);        \
+    else if ((H) <= 16) fn<16>(__VA_ARGS__);      \
+    else if ((H) <= 32) fn<32>(__VA_ARGS__);      \
+    else if ((H) <= 64) fn<64>(__VA_ARGS__);      \
+    else if ((H) <= 100) fn<100>(__VA_ARGS__);    \
+    else fn<128>(__VA_ARGS__);                    \
+  } while (0)
+
+static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t *y, int B, bool priv, float C,
+                    float sigma, uint64_t seed, float *out) {
+  Launcher Ln{c};
+  const int nL = (int)c->L.size();
+  const long slot_stride = c->maxB;
+  int slot_next = 0;
+  FinalizeArgs fa;
+  fa.nseg = 0;
+
+  if (B > 0) {
+    // ------------------------------------------------------------ forward
+    const float *in = (const float *)x;
+    for (int i = 0; i < nL; ++i) {
+      Layer &l = c->L[i];
+      const float *W = params + l.p_off;
+      switch (l.d.kind) {
+      case DP_DENSE: {
+        typedef ProbBiasAct<OpRowMajor, OpKMajor> Pb;
+        Pb p{};
+        p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
+        p.a.ptr = in; p.a.zstride = 0; p.a.ld = l.d.in_features;
+        p.b.ptr = W; p.b.zstride = 0; p.b.ld = l.d.out_features; p.b.scale = nullptr; p.b.scale_div.init(1);
+        p.b.ones_row = 0; p.b.by_z = 0;
+        p.out = l.a; p.bias = W + (long)l.d.in_features * l.d.out_features; p.ld = l.d.out_features; p.act = l.d.act;
+        launch_gemm(p, 1, Ln, "dense_fwd");
+      } break;
+      case DP_CONV2D: {
+        typedef ProbConvFwd<OpRowMajor, OpConvPatch<true>> Pb;
+        Pb p{};
+        const ConvGeom &g = l.geom;
+        p.M = g.D; p.N = B * g.P; p.K = g.CKK;
+        p.a.ptr = W; p.a.zstride = 0; p.a.ld = g.CKK;
+        p.b.x = in; p.b.g = g; p.b.has_ones = 0; p.b.by_z = 0;
+        p.out = l.a; p.bias = W + (long)g.D * g.CKK; p.D = g.D; p.P = g.P; p.act = l.d.act; p.dP = g.dP;
+        launch_gemm(p, 1, Ln, "conv_fwd");
+      } break;
+      case DP_MAXPOOL2D: {
+        long total = (long)B * l.out_size;
+        dim3 grid = grid1d(total, 256), block(256);
+        Ln("maxpool_fwd", grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(maxpool_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
+                             l.outW, l.d.kh, l.d.kw, l.d.stride);
+        });
+      } break;
+      case DP_EMBEDDING: break; // lookup is fused into the LSTM input projection
+      case DP_LSTM_LAST: {
+        const Layer &emb = c->L[i - 1];
+        const float *E = params + emb.p_off;
+        const int G = 4 * l.H;
+        typedef ProbBiasAct<OpGatherRows, OpKMajor> Pb;
+        Pb p{};
+        p.M = B * l.T; p.N = G; p.K = l.Din;
+        p.a.table = E; p.a.idx = (const int *)x; p.a.ld = l.Din;
+        p.b.ptr = W; p.b.zstride = 0; p.b.ld = G; p.b.scale = nullptr; p.b.scale_div.init(1); p.b.ones_row = 0; p.b.by_z = 0;
+        p.out = l.gates; p.bias = W + (long)l.Din * G + (long)l.H * G; p.ld = G; p.act = DP_ACT_NONE;
+        launch_gemm(p, 1, Ln, "lstm_xproj");
+        const float *Whh = W + (long)l.Din * G;
+        LSTM_DISPATCH(launch_lstm_fwd, l.H, Ln, l, Whh, B);
+      } break;
+      }
+      in = l.a;
+    }
+    // ------------------------------------------------------------ loss gradient
+    {
+      Layer &l = c->L[nL - 1];
+      dim3 grid = grid1d(B, 128), block(128);
+      Ln("softmax_xent_grad", grid, block, [&](hipStream_t st) {
+        hipLaunchKernelGGL(softmax_xent_grad_kernel, grid, block, 0, st, (const float *)l.a, (const int *)y, l.g, B,
+                           c->m.n_classes);
+      });
+    }
+    // ------------------------------------------------------------ backward: data gradients and per-example norms
+    for (int i = nL - 1; i >= 0; --i) {
+      Layer &l = c->L[i];
+      const float *W = params + l.p_off;
+      const float *lin = i > 0 ? c->L[i - 1].a : (const float *)x;
+      Layer *prev = i > 0 ? &c->L[i - 1] : nullptr;
+      const int prev_act = (prev && (prev->d.kind == DP_DENSE || prev->d.kind == DP_CONV2D)) ? prev->d.act : DP_ACT_NONE;
+      switch (l.d.kind) {
+      case DP_DENSE: {
+        if (priv) {
+          dim3 grid = grid1d((long)B * 64, 256), block(256);
+          float *slot = c->slots + (long)slot_next * slot_stride;
+          slot_next += 1;
+          Ln("dense_norm", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(dense_norm_kernel, grid, block, 0, st, lin, l.d.in_features, (const float *)l.g,
+                               l.d.out_features, slot, B);
+          });
+        }
+        if (prev) {
+          typedef ProbBwdAct<OpRowMajor, OpRowMajor> Pb;
+          Pb p{};
+          p.M = B; p.N = l.d.in_features; p.K = l.d.out_features;
+          p.a.ptr = l.g; p.a.zstride = 0; p.a.ld = l.d.out_features;
+          p.b.ptr = W; p.b.zstride = 0; p.b.ld = l.d.out_features;
+          p.out = prev->g; p.a_prev = prev->a; p.ld = l.d.in_features; p.act = prev_act;
+          launch_gemm(p, 1, Ln, "dense_bwd_data");
+        }
+      } break;
+      case DP_CONV2D: {
+        const ConvGeom &g = l.geom;
+        if (priv) {
+          typedef ProbSqNorm<OpRowMajor, OpConvPatch<false>> Pb;
+          Pb p{};
+          p.M = g.D; p.N = g.CKK + 1; p.K = g.P;
+          p.a.ptr = l.g; p.a.zstride = (long)g.D * g.P; p.a.ld = g.P;
+          p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 1;
+          p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
+          GemmShape s = launch_gemm(p, B, Ln, "conv_wgrad_norm");
+          slot_next += s.tiles_m * s.tiles_n;
+        }
+        if (prev) {
+          typedef ProbConvBwd<OpConvWeightT, OpConvDeltaGather> Pb;
+          Pb p{};
+          p.M = g.C; p.N = B * g.H * g.W; p.K = g.D * g.KH * g.KW;
+          p.a.w = W; p.a.g = g;
+          p.b.delta = l.g; p.b.g = g;
+          p.out = prev->g; p.a_prev = prev->a; p.C = g.C; p.HW = g.H * g.W; p.act = prev_act; p.dHW = g.dHW;
+          launch_gemm(p, 1, Ln, "conv_bwd_data");
+        }
+      } break;
+      case DP_MAXPOOL2D: {
+        long total = (long)B * l.in_size;
+        dim3 grid = grid1d(total, 256), block(256);
+        Ln("maxpool_bwd", grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(maxpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
+                             (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
+                             l.d.stride, prev_act);
+        });
+      } break;
+      case DP_LSTM_LAST: {
+        const int G = 4 * l.H;
+        const float *Whh = W + (long)l.Din * G;
+        LSTM_DISPATCH(launch_lstm_bwd, l.H, Ln, l, Whh, B);
+        if (priv) {
+          typedef ProbSqNorm<OpLstmIn, OpKMajor> Pb;
+          Pb p{};
+          p.M = l.Din + l.H + 1; p.N = G; p.K = l.T;
+          p.a.table = params + prev->p_off; p.a.tok = (const int *)x; p.a.xin = nullptr; p.a.hs = l.hs;
+          p.a.scale = nullptr; p.a.Din = l.Din; p.a.H = l.H; p.a.T = l.T; p.a.by_z = 1; p.a.dT.init(l.T);
+          p.b.ptr = l.gates; p.b.zstride = (long)l.T * G; p.b.ld = G; p.b.scale = nullptr; p.b.scale_div.init(1);
+          p.b.ones_row = 0; p.b.by_z = 1;
+          p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
+          GemmShape s = launch_gemm(p, B, Ln, "lstm_wgrad_norm");
+          slot_next += s.tiles_m * s.tiles_n;
+        }
+        { // dx = dgates W_ih^T: gradient w.r.t. the embedding outputs
+          typedef ProbBwdAct<OpRowMajor, OpRowMajor> Pb;
+          Pb p{};
+          p.M = B * l.T; p.N = l.Din; p.K = G;
+          p.a.ptr = l.gates; p.a.zstride = 0; p.a.ld = G;
+          p.b.ptr = W; p.b.zstride = 0; p.b.ld = G;
+          p.out = prev->g; p.a_prev = nullptr; p.ld = l.Din; p.act = DP_ACT_NONE;
+          launch_gemm(p, 1, Ln, "lstm_dx");
+        }
+      } break;
+      case DP_EMBEDDING: {
+        if (priv) {
+          int TP = 2;
+          while (TP < l.outC) TP <<= 1;
+          dim3 grid(B), block(256);
+          float *slot = c->slots + (long)slot_next * slot_stride;
+          slot_next += 1;
+          Ln("emb_norm", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_norm_kernel, grid, block, 0, st, (const int *)x, (const float *)l.g, slot, l.outC,
+                               TP, l.d.embed_dim);
+          });
+        }
+      } break;
+      }
+    }
+    // ------------------------------------------------------------ clip factors
+    if (priv) {
+      dim3 grid = grid1d(B, 128), block(128);
+      const int ns = slot_next;
+      Ln("clip_factor", grid, block, [&](hipStream_t st) {
+        hipLaunchKernelGGL(clip_factor_kernel, grid, block, 0, st, (const float *)c->slots, ns, slot_stride, C,
+                           c->norms, c->s, B);
+      });
+    }
+    const float *sc = priv ? c->s : nullptr;
+    // ------------------------------------------------------------ clipped sums (split-K partials)
+    for (int i = 0; i < nL; ++i) {
+      Layer &l = c->L[i];
+      if (l.p_count == 0) continue;
+      const float *lin = i > 0 ? c->L[i - 1].a : (const float *)x;
+      int nsplit = 1;
+      switch (l.d.kind) {
+      case DP_DENSE: {
+        typedef ProbPartial<OpKMajor, OpKMajor> Pb;
+        Pb p{};
+        p.M = l.d.in_features + 1; p.N = l.d.out_features; p.K = B;
+        p.a.ptr = lin; p.a.zstride = 0; p.a.ld = l.d.in_features; p.a.scale = sc; p.a.scale_div.init(1);
+        p.a.ones_row = 1; p.a.by_z = 0;
+        p.b.ptr = l.g; p.b.zstride = 0; p.b.ld = l.d.out_features; p.b.scale = nullptr; p.b.scale_div.init(1);
+        p.b.ones_row = 0; p.b.by_z = 0;
+        p.part = l.part; p.stride = l.p_count; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
+        nsplit = launch_gemm_split(p, l.max_split, Ln, "dense_clipped_sum");
+      } break;
+      case DP_CONV2D: {
+        const ConvGeom &g = l.geom;
+        typedef ProbPartial<OpChanPix, OpConvPatch<false>> Pb;
+        Pb p{};
+        p.M = g.D; p.N = g.CKK + 1; p.K = B * g.P;
+        p.a.t = l.g; p.a.scale = sc; p.a.D = g.D; p.a.P = g.P; p.a.by_z = 0; p.a.dP = g.dP;
+        p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 0;
+        p.part = l.part; p.stride = l.p_count; p.ldm = g.CKK; p.bias_col = g.CKK; p.bias_off = (long)g.D * g.CKK;
+        nsplit = launch_gemm_split(p, l.max_split, Ln, "conv_clipped_sum");
+      } break;
+      case DP_LSTM_LAST: {
+        const int G = 4 * l.H;
+        typedef ProbPartial<OpLstmIn, OpKMajor> Pb;
+        Pb p{};
+        p.M = l.Din + l.H + 1; p.N = G; p.K = B * l.T;
+        p.a.table = params + c->L[i - 1].p_off; p.a.tok = (const int *)x; p.a.xin = nullptr; p.a.hs = l.hs;
+        p.a.scale = sc; p.a.Din = l.Din; p.a.H = l.H; p.a.T = l.T; p.a.by_z = 0; p.a.dT.init(l.T);
+        p.b.ptr = l.gates; p.b.zstride = 0; p.b.ld = G; p.b.scale = nullptr; p.b.scale_div.init(1);
+        p.b.ones_row = 0; p.b.by_z = 0;
+        p.part = l.part; p.stride = l.p_count; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
+        nsplit = launch_gemm_split(p, l.max_split, Ln, "lstm_clipped_sum");
+      } break;
+      case DP_EMBEDDING: {
+        {
+          dim3 grid = grid1d(l.p_count, 256), block(256);
+          Ln("fill_zero", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count);
+          });
+        }
+        long rows = (long)B * l.outC;
+        dim3 grid = grid1d(rows * l.d.embed_dim, 256), block(256);
+        Ln("emb_scatter", grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(emb_scatter_kernel, grid, block, 0, st, (const int *)x, (const float *)l.g, sc, l.part,
+                             rows, l.outC, l.d.embed_dim);
+        });
+        nsplit = 1;
+      } break;
+      default: break;
+      }
+      FinalizeSeg &sg = fa.seg[fa.nseg++];
+      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = l.part; sg.stride = l.p_count; sg.nsplit = nsplit;
+    }
+  } else {
+    for (auto &l : c->L) {
+      if (l.p_count == 0) continue;
+      FinalizeSeg &sg = fa.seg[fa.nseg++];
+      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = l.part; sg.stride = l.p_count; sg.nsplit = 0;
+    }
+  }
+  // ------------------------------------------------------------ final write with fused noise
+  {
+    const float noise_std = (priv && sigma > 0.f) ? sigma * C : 0.f;
+    long nblk = (c->P + 3) / 4;
+    dim3 grid = grid1d(nblk, 256), block(256);
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    Ln("finalize_noise", grid, block, [&](hipStream_t st) {
+      hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, c->P, noise_std, k0, k1);
+    });
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "kernel launch: %s", hipGetErrorString(e));
+    return DP_EHIP;
+  }
+  if (priv) c->last_batch = B;
+  return DP_OK;
+}
+
+extern "C" int dp_step(dp_ctx *c, const float *params, const void *x, const int32_t *y, int batch, float C, float sigma,
+                       uint64_t seed, float *out_grad) {
+  if (!c || !params || !out_grad || batch < 0 || batch > c->maxB) return DP_EINVAL;
+  if (batch > 0 && (!x || !y)) return DP_EINVAL;
+  if (!(C > 0.f) || !(sigma >= 0.f) || std::isnan(C) || std::isinf(sigma)) return DP_EINVAL;
+  if (std::isinf(C) && sigma > 0.f) return DP_EINVAL;
+  return run_step(c, params, x, y, batch, true, C, sigma, seed, out_grad);
+}
+
+extern "C" int dp_step_nonprivate(dp_ctx *c, const float *params, const void *x, const int32_t *y, int batch,
+                                  float *out_grad) {
+  if (!c || !params || !out_grad || batch < 0 || batch > c->maxB) return DP_EINVAL;
+  if (batch > 0 && (!x || !y)) return DP_EINVAL;
+  return run_step(c, params, x, y, batch, false, INFINITY, 0.f, 0, out_grad);
+}
+
+extern "C" int dp_step_last_norms(dp_ctx *c, float *norms_out) {
+  if (!c || !norms_out || c->last_batch < 0) return DP_EINVAL;
+  if (c->last_batch == 0) return DP_OK;
+  HIP_TRY(hipMemcpyAsync(norms_out, c->norms, sizeof(float) * c->last_batch, hipMemcpyDeviceToDevice, c->stream));
+  return DP_OK;
+}
+
+// ---------------------------------------------------------------- profiling
+
+static int drain_profile(dp_ctx *c) {
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  for (auto &r : c->recs) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.e0, r.e1));
+    c->label_launches[r.label] += 1;
+    c->label_ms[r.label] += ms;
+  }
+  c->recs.clear();
+  c->pool_used = 0;
+  return DP_OK;
+}
+
+extern "C" int dp_step_profile(dp_ctx *c, int enable) {
+  if (!c) return DP_EINVAL;
+  if (enable && c->pool.empty()) {
+    c->pool.resize(16384);
+    for (auto &e : c->pool) HIP_TRY(hipEventCreate(&e));
+  }
+  if (!enable && c->prof) {
+    int rc = drain_profile(c);
+    if (rc != DP_OK) return rc;
+  }
+  c->prof = enable != 0;
+  return DP_OK;
+}
+
+extern "C" int dp_step_profile_read(dp_ctx *c, int cap, const char **labels, int *launches, float *total_ms, int reset) {
+  if (!c || cap < 0) return DP_EINVAL;
+  int rc = drain_profile(c);
+  if (rc != DP_OK) return rc;
+  int n = (int)c->labels.size();
+  for (int i = 0; i < n && i < cap; ++i) {
+    if (labels) labels[i] = c->labels[i];
+    if (launches) launches[i] = c->label_launches[i];
+    if (total_ms) total_ms[i] = c->label_ms[i];
+  }
+  if (reset)
+    for (int i = 0; i < n; ++i) { c->label_launches[i] = 0; c->label_ms[i] = 0.f; }
+  return n;
+}

@@ -1,0 +1,181 @@
+// Small kernels of the private step: loss gradient, pooling, dense per-example
+// norms, clip factors, and the final write with fused Philox noise.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define DP_ACT_NONE_ 0
+#define DP_ACT_RELU_ 1
+#define DP_ACT_TANH_ 2
+
+__device__ __forceinline__ float act_apply(int act, float z) {
+  if (act == DP_ACT_RELU_) return z > 0.f ? z : 0.f;
+  if (act == DP_ACT_TANH_) return tanhf(z);
+  return z;
+}
+// derivative expressed through the activation's output a = act(z)
+__device__ __forceinline__ float act_deriv_from_out(int act, float a) {
+  if (act == DP_ACT_RELU_) return a > 0.f ? 1.f : 0.f;
+  if (act == DP_ACT_TANH_) return 1.f - a * a;
+  return 1.f;
+}
+
+// delta_i = softmax(logits_i) - onehot(y_i): gradient of one example's own
+// cross-entropy (DPSGD item 2a: the objective at (x_i, y_i), not a batch mean).
+__global__ void softmax_xent_grad_kernel(const float *__restrict__ logits, const int *__restrict__ y,
+                                         float *__restrict__ g, int B, int K) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const float *z = logits + (long)b * K;
+  float mx = z[0];
+  for (int k = 1; k < K; ++k) mx = fmaxf(mx, z[k]);
+  float se = 0.f;
+  for (int k = 0; k < K; ++k) se += expf(z[k] - mx);
+  float inv = 1.f / se;
+  int yy = y[b];
+  for (int k = 0; k < K; ++k) g[(long)b * K + k] = expf(z[k] - mx) * inv - (k == yy ? 1.f : 0.f);
+}
+
+// max-pool forward; arg = window offset kh*KW+kw of the first maximum
+__global__ void maxpool_fwd_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                   uint8_t *__restrict__ arg, long total, int H, int W, int OH, int OW,
+                                   int KH, int KW, int S) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int ow = (int)(i % OW);
+  long r = i / OW;
+  int oh = (int)(r % OH);
+  long bc = r / OH;
+  const float *p = in + (bc * H + (long)oh * S) * W + (long)ow * S;
+  float best = p[0];
+  int bi = 0;
+  for (int kh = 0; kh < KH; ++kh)
+    for (int kw = 0; kw < KW; ++kw) {
+      float v = p[kh * W + kw];
+      if (v > best) { best = v; bi = kh * KW + kw; }
+    }
+  out[i] = best;
+  arg[i] = (uint8_t)bi;
+}
+
+// max-pool backward in gather form (no atomics): every input position sums the
+// output gradients of the windows whose recorded maximum it is, then applies the
+// derivative of the activation that produced the pool's input.
+__global__ void maxpool_bwd_kernel(const float *__restrict__ gout, const uint8_t *__restrict__ arg,
+                                   const float *__restrict__ a_in, float *__restrict__ gin, long total, int H,
+                                   int W, int OH, int OW, int KH, int KW, int S, int act) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int iw = (int)(i % W);
+  long r = i / W;
+  int ih = (int)(r % H);
+  long bc = r / H;
+  float acc = 0.f;
+  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (oh_lo + S - 1) / S : 0;
+  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (ow_lo + S - 1) / S : 0;
+  int oh_hi = min(ih / S, OH - 1), ow_hi = min(iw / S, OW - 1);
+  for (int oh = oh_lo; oh <= oh_hi; ++oh)
+    for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+      long o = (bc * OH + oh) * OW + ow;
+      int want = (ih - oh * S) * KW + (iw - ow * S);
+      if ((int)arg[o] == want) acc += gout[o];
+    }
+  gin[i] = acc * act_deriv_from_out(act, a_in[i]);
+}
+
+// Dense layer: ||g_i||^2 = (||a_i||^2 + 1) ||delta_i||^2 without forming the outer
+// product (Section 1: per-example norms for fully-connected layers).  One wave per example.
+__global__ void dense_norm_kernel(const float *__restrict__ a, int d_in, const float *__restrict__ delta, int d_out,
+                                  float *__restrict__ slot, int B) {
+  int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  if (wave >= B) return;
+  float sa = 0.f, sd = 0.f;
+  for (int k = lane; k < d_in; k += 64) { float v = a[(long)wave * d_in + k]; sa += v * v; }
+  for (int k = lane; k < d_out; k += 64) { float v = delta[(long)wave * d_out + k]; sd += v * v; }
+  for (int o = 32; o > 0; o >>= 1) { sa += __shfl_xor(sa, o, 64); sd += __shfl_xor(sd, o, 64); }
+  if (lane == 0) slot[wave] = (sa + 1.f) * sd;
+}
+
+// n_i = sqrt(sum over all layers' partial squared norms); s_i = min(1, C / n_i)  (DPSGD item 2b)
+__global__ void clip_factor_kernel(const float *__restrict__ slots, int n_slots, long slot_stride, float C,
+                                   float *__restrict__ norms, float *__restrict__ s, int B) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  float n2 = 0.f;
+  for (int k = 0; k < n_slots; ++k) n2 += slots[k * slot_stride + b];
+  float n = sqrtf(n2);
+  norms[b] = n;
+  s[b] = fminf(1.f, C / n); // n == 0: C/0 = +inf -> 1
+}
+
+__global__ void fill_zero_kernel(float *__restrict__ p, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// ---------------------------------------------------------------- noise
+
+// Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// four standard normals of block `blk`: uniforms ((r >> 9) + 1/2) 2^-23 (exact in
+// fp32, never 0 or 1), two Box-Muller pairs.
+__device__ __forceinline__ void normal4(uint64_t blk, uint32_t k0, uint32_t k1, float z[4]) {
+  uint32_t r[4];
+  philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), 0u, 0u, k0, k1, r);
+  float u[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) u[q] = ((float)(r[q] >> 9) + 0.5f) * (1.0f / 8388608.0f);
+  float r0 = sqrtf(-2.f * logf(u[0])), r1 = sqrtf(-2.f * logf(u[2]));
+  float s, c;
+  sincospif(2.f * u[1], &s, &c);
+  z[0] = r0 * c; z[1] = r0 * s;
+  sincospif(2.f * u[3], &s, &c);
+  z[2] = r1 * c; z[3] = r1 * s;
+}
+
+// Final write (DPSGD item 3): out[j] = sum over split-K partials of the clipped
+// sum + sigma*C*z_j.  One thread per Philox block of four coordinates.
+#define DP_MAX_SEG 24
+struct FinalizeSeg {
+  long p_off, n;     // segment [p_off, p_off + n) of the flat parameter vector
+  const float *part; // [nsplit][stride]
+  long stride;
+  int nsplit;
+};
+struct FinalizeArgs {
+  int nseg;
+  FinalizeSeg seg[DP_MAX_SEG];
+};
+
+__global__ void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P, float noise_std,
+                                uint32_t k0, uint32_t k1) {
+  long blk = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  long j0 = blk * 4;
+  if (j0 >= P) return;
+  float z[4] = {0.f, 0.f, 0.f, 0.f};
+  if (noise_std > 0.f) normal4((uint64_t)blk, k0, k1, z);
+  int si = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    long j = j0 + q;
+    if (j >= P) break;
+    while (si < fa.nseg - 1 && j >= fa.seg[si].p_off + fa.seg[si].n) ++si;
+    const FinalizeSeg &sg = fa.seg[si];
+    float acc = 0.f;
+    long loc = j - sg.p_off;
+    for (int s = 0; s < sg.nsplit; ++s) acc += sg.part[s * sg.stride + loc];
+    out[j] = noise_std > 0.f ? acc + noise_std * z[q] : acc;
+  }
+}

@@ -1,0 +1,141 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element on
+the same seeded inputs.  Bar: relative L2 <= 1e-4 on the aggregated fp32 gradient at
+sigma = 0; <= 1e-5 absolute on the noise term for the same Philox stream."""
+import math
+
+import numpy as np
+import pytest
+
+import dp_workloads as W
+from oracle import dpsgd_oracle as O
+from tests.gpu_util import rel_l2, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+TINY = W.tiny_models()
+
+
+def _case(m, batch, seed, x_dist="normal", bias=0.3, scale=1.0, zipf=0.3):
+    rng = np.random.default_rng(seed)
+    x, y = W.make_inputs(m, batch, rng, x_dist=x_dist, zipf_exponent=zipf)
+    theta = W.init_params(m, rng, bias_scale=bias) * np.float32(scale)
+    return x, y, theta
+
+
+def _check_all_regimes(m, x, y, theta, label):
+    ref_inf = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
+    norms = ref_inf["norms"]
+    regimes = [math.inf, float(np.median(norms)), 0.1 * float(norms.min())]
+    for Cc in regimes:
+        ref = ref_inf if math.isinf(Cc) else O.dp_step(m, theta, x, y, Cc, 0.0, 0)
+        out, gn = run_gpu(m, theta, x, y, Cc, 0.0, 0)
+        print(f"{label} C={Cc:.4g} rel_l2={rel_l2(out, ref['clipped_sum']):.3e}", flush=True)
+        assert np.isfinite(out).all()
+        assert rel_l2(out, ref["clipped_sum"]) <= TOL, (label, Cc)
+        assert np.allclose(gn, norms, rtol=1e-4, atol=1e-7), (label, Cc)
+        if not math.isinf(Cc):
+            s = np.minimum(1.0, Cc / gn.astype(np.float64))
+            assert np.all(s * norms <= Cc * (1 + 1e-5))
+    ref_np = O.dp_step(m, theta, x, y, 1.0, 0.0, 0, clip=False)
+    out, _ = run_gpu(m, theta, x, y, 1.0, 0.0, 0, private=False)
+    assert rel_l2(out, ref_np["clipped_sum"]) <= TOL, (label, "nonprivate")
+
+
+@pytest.mark.parametrize("name", sorted(TINY))
+@pytest.mark.parametrize("batch", [1, 7, 70])
+def test_tiny_models(name, batch):
+    m = TINY[name]
+    scale = 4.0 if m["input"]["kind"] == "tokens" else 1.0
+    x, y, theta = _case(m, batch, seed=11 + batch, scale=scale)
+    _check_all_regimes(m, x, y, theta, f"{name}/B{batch}")
+
+
+# real layer shapes, batches that span several tiles and leave a ragged tail
+REDUCED = {"cfg1_logistic": 100, "cfg2_mlp": 77, "cfg3_small_cnn": 37, "cfg4_cifar_cnn": 5, "cfg5_lstm": 6}
+
+
+@pytest.mark.parametrize("name", sorted(REDUCED))
+def test_benchmark_architectures_reduced_batch(name):
+    wl = W.make_workload(name, batch=REDUCED[name], seed=2, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], name)
+
+
+@pytest.mark.parametrize("name", ["cfg1_logistic", "cfg2_mlp", "cfg3_small_cnn", "cfg5_lstm", "cfg4_cifar_cnn"])
+def test_benchmark_full_size(name):
+    """Full batch, benchmark launch configuration (C = 1, then a C that clips about half)."""
+    wl = W.make_workload(name, seed=0)
+    m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    ref = O.dp_step(m, theta, x, y, wl["C"], 0.0, 0)
+    assert ref["ties"] == 0
+    out, gn = run_gpu(m, theta, x, y, wl["C"], 0.0, 0)
+    print(f"{name} full: rel_l2={rel_l2(out, ref['clipped_sum']):.3e} clipped={(ref['norms'] > wl['C']).mean():.2f}",
+          flush=True)
+    assert rel_l2(out, ref["clipped_sum"]) <= TOL
+    assert np.allclose(gn, ref["norms"], rtol=1e-4, atol=1e-7)
+    Cmed = float(np.median(ref["norms"]))
+    ref2 = O.dp_step(m, theta, x, y, Cmed, 0.0, 0)
+    out2, _ = run_gpu(m, theta, x, y, Cmed, 0.0, 0)
+    assert rel_l2(out2, ref2["clipped_sum"]) <= TOL
+    assert np.linalg.norm(out2) <= len(y) * Cmed * (1 + 1e-5)
+
+
+@pytest.mark.parametrize("name,batch", [("tiny_dense", 5), ("tiny_lstm", 3), ("cfg3_small_cnn", 16), ("cfg5_lstm", 2)])
+def test_noise_term(name, batch):
+    if name in TINY:
+        m = TINY[name]
+        x, y, theta = _case(m, batch, seed=5)
+    else:
+        wl = W.make_workload(name, batch=batch, seed=5)
+        m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    Cc, sigma = 1.0, 1.1
+    for seed in (0, 0x1234567887654321):
+        out0, _ = run_gpu(m, theta, x, y, Cc, 0.0, seed)
+        out1, _ = run_gpu(m, theta, x, y, Cc, sigma, seed)
+        z = O.noise(seed, theta.size)
+        err = np.abs((out1.astype(np.float64) - out0.astype(np.float64)) - sigma * Cc * z).max()
+        print(f"{name} seed={seed:#x} noise abs err {err:.2e}", flush=True)
+        assert err <= 1e-5
+        ref = O.dp_step(m, theta, x, y, Cc, sigma, seed)
+        assert np.abs(out1.astype(np.float64) - ref["out"]).max() <= 1e-5 + 1e-4 * np.abs(ref["out"]).max()
+        # empty batch: pure noise
+        outz, _ = run_gpu(m, theta, x[:0], y[:0], Cc, sigma, seed, max_batch=4)
+        assert np.abs(outz - sigma * Cc * z).max() <= 1e-5
+
+
+def test_context_reuse_and_smaller_batches():
+    """One context serves batches of different sizes, private and non-private, in any order."""
+    from paper_2010_09063_amd import DpStep
+    m = W.cfg3_small_cnn()
+    st = DpStep(m, 48)
+    for batch in (48, 5, 33):
+        wl = W.make_workload("cfg3_small_cnn", batch=batch, seed=batch, bias_scale=0.1)
+        ref = O.dp_step(m, wl["params"], wl["x"], wl["y"], 0.5, 0.0, 0)
+        out, gn = run_gpu(m, wl["params"], wl["x"], wl["y"], 0.5, 0.0, 0, stepper=st)
+        assert rel_l2(out, ref["clipped_sum"]) <= TOL
+        refn = O.dp_step(m, wl["params"], wl["x"], wl["y"], 0.5, 0.0, 0, clip=False)
+        outn, _ = run_gpu(m, wl["params"], wl["x"], wl["y"], 0.5, 0.0, 0, private=False, stepper=st)
+        assert rel_l2(outn, refn["clipped_sum"]) <= TOL
+    st.dp_step_free()
+
+
+def test_argument_errors():
+    import torch
+    from paper_2010_09063_amd import DpStep, DpStepError
+    m = TINY["tiny_dense"]
+    st = DpStep(m, 4)
+    dev = torch.device("cuda:0")
+    p = torch.zeros(st.num_params, device=dev)
+    x = torch.zeros(4, 5, device=dev)
+    y = torch.zeros(4, dtype=torch.int32, device=dev)
+    o = torch.zeros(st.num_params, device=dev)
+    for args in [(p, x, y, 5, 1.0, 0.0, 0, o), (p, x, y, 4, 0.0, 0.0, 0, o), (p, x, y, 4, -1.0, 0.0, 0, o),
+                 (p, x, y, 4, 1.0, -0.1, 0, o), (p, x, y, 4, float("nan"), 0.0, 0, o),
+                 (p, x, y, 4, float("inf"), 1.0, 0, o), (None, x, y, 4, 1.0, 0.0, 0, o), (p, None, y, 4, 1.0, 0.0, 0, o)]:
+        with pytest.raises(DpStepError) as e:
+            st.dp_step(*args)
+        assert e.value.code == -1
+    st.dp_step_free()
+    bad = W.model(W.image_input(5), [W.dense(6, 3)], 3)
+    with pytest.raises(DpStepError):
+        DpStep(bad, 4)
