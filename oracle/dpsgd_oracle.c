@@ -128,6 +128,7 @@ typedef struct {
   double *d_a, *d_b; /* two gradient buffers of the largest size  */
   long max_act;
   long ties;      /* number of pool windows whose maximum is not unique */
+  double margin;  /* smallest (maximum - runner-up) over the pool windows of the current example */
 } scratch;
 
 static scratch *scratch_new(const or_model *m) {
@@ -180,6 +181,7 @@ static double forward(const or_model *m, const double *theta, const void *x, int
     in = s->in0;
   }
   const double *th = theta;
+  s->margin = INFINITY;
   for (int l = 0; l < m->n_layers; ++l) {
     const or_layer *L = &m->layers[l];
     shp o = s->shape[l];
@@ -218,18 +220,19 @@ static double forward(const or_model *m, const double *theta, const void *x, int
         for (int oh = 0; oh < o.h; ++oh)
           for (int ow = 0; ow < o.w; ++ow) {
             int best = -1, nbest = 0;
-            double bv = 0;
+            double bv = 0, second = -INFINITY;
             for (int kh = 0; kh < L->kh; ++kh)
               for (int kw = 0; kw < L->kw; ++kw) {
                 int idx = (c * cur.h + oh * L->stride + kh) * cur.w + ow * L->stride + kw;
                 double v = in[idx];
-                if (best < 0 || v > bv) { best = idx; bv = v; nbest = 1; }
-                else if (v == bv) ++nbest;
+                if (best < 0 || v > bv) { if (best >= 0) second = bv; best = idx; bv = v; nbest = 1; }
+                else { if (v == bv) ++nbest; if (v > second) second = v; }
               }
             long oi = ((long)c * o.h + oh) * o.w + ow;
             a[oi] = bv;
             s->arg[l][oi] = best;
             if (nbest > 1) s->ties++;
+            if (bv - second < s->margin) s->margin = bv - second;
           }
     } break;
     case OR_EMBEDDING: {
@@ -448,12 +451,15 @@ void oracle_noise(uint64_t seed, long n, double *z) {
 
 /* params fp32[P]; x fp32[B, in_c*in_h*in_w] or int32[B, seq_len]; y int32[B] (all host).
  * out fp32[P] = sum_i clip(g_i) + sigma*C*z.  Optional outputs (may be NULL):
- *   norms[B]  unclipped ||g_i||;  clipped_sum[P] the fp64 sum before noise;  ties.
+ *   norms[B]  unclipped ||g_i||;  clipped_sum[P] the fp64 sum before noise;  ties;
+ *   pool_margin[B]  smallest gap between the maximum and the runner-up over the example's
+ *   pool windows (+inf without pooling): an fp32 implementation may route a window whose
+ *   gap is at rounding level to the other element, so tests compare on clear examples.
  * C = +inf disables clipping; sigma = 0 adds exactly nothing.  clip = 0 skips the
  * clipping branch altogether (the non-private summed gradient).  Returns 0. */
 int oracle_dp_step(const or_model *m, const float *params, const void *x, const int32_t *y, int B, double C,
                    double sigma, uint64_t seed, int clip, float *out, double *norms, double *clipped_sum,
-                   long *ties, int n_threads) {
+                   long *ties, double *pool_margin, int n_threads) {
   long P = oracle_num_params(m);
   double *theta = (double *)malloc(sizeof(double) * P);
   for (long j = 0; j < P; ++j) theta[j] = (double)params[j];
@@ -489,6 +495,7 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
       double n = sqrt(n2);
       double sc = (clip && n > C) ? C / n : 1.0;
       if (norms) norms[i] = n;
+      if (pool_margin) pool_margin[i] = s->margin;
       for (long j = 0; j < P; ++j) a[j] += sc * g[j];
     }
     tie_t[tid] = s->ties;

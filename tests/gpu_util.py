@@ -37,3 +37,26 @@ def rel_l2(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+POOL_MARGIN = 1e-5
+
+
+def clear_pool_examples(m, params, x, y, oracle_step, tau=POOL_MARGIN):
+    """Max-pool routes a window's gradient to its maximum; the kernel decides that in fp32,
+    the oracle in fp64.  Where the two largest values of a window differ by rounding-level
+    amounts either choice is a valid (sub)gradient and the two sides may legitimately differ.
+    Parity is therefore checked on examples all of whose windows have a clear maximum (gap
+    > tau in the oracle's forward pass): the others are replaced by clear ones (cycled), so
+    the batch keeps its size.  Returns (x, y, number of examples replaced)."""
+    if not any(L["kind"] == "maxpool2d" for L in m["layers"]) or len(y) == 0:
+        return x, y, 0
+    mg = oracle_step(m, params, x, y, 1.0, 0.0, 0, clip=False)["pool_margin"]
+    clear = np.flatnonzero(mg > tau)
+    assert clear.size > 0, "no example with a clear pool maximum"
+    if clear.size == len(y):
+        return x, y, 0
+    idx = np.arange(len(y))
+    bad = np.flatnonzero(mg <= tau)
+    idx[bad] = clear[np.arange(bad.size) % clear.size]
+    return x[idx], y[idx], int(bad.size)

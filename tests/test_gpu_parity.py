@@ -8,7 +8,7 @@ import pytest
 
 import dp_workloads as W
 from oracle import dpsgd_oracle as O
-from tests.gpu_util import rel_l2, run_gpu
+from tests.gpu_util import clear_pool_examples, rel_l2, run_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -24,6 +24,7 @@ def _case(m, batch, seed, x_dist="normal", bias=0.3, scale=1.0, zipf=0.3):
 
 
 def _check_all_regimes(m, x, y, theta, label):
+    x, y, replaced = clear_pool_examples(m, theta, x, y, O.dp_step)
     ref_inf = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
     norms = ref_inf["norms"]
     regimes = [math.inf, float(np.median(norms)), 0.1 * float(norms.min())]
@@ -66,6 +67,8 @@ def test_benchmark_full_size(name):
     """Full batch, benchmark launch configuration (C = 1, then a C that clips about half)."""
     wl = W.make_workload(name, seed=0)
     m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    x, y, replaced = clear_pool_examples(m, theta, x, y, O.dp_step)
+    print(f"{name}: {replaced} of {len(y)} examples had a near-tied pool window and were replaced", flush=True)
     ref = O.dp_step(m, theta, x, y, wl["C"], 0.0, 0)
     assert ref["ties"] == 0
     out, gn = run_gpu(m, theta, x, y, wl["C"], 0.0, 0)
@@ -110,6 +113,7 @@ def test_context_reuse_and_smaller_batches():
     st = DpStep(m, 48)
     for batch in (48, 5, 33):
         wl = W.make_workload("cfg3_small_cnn", batch=batch, seed=batch, bias_scale=0.1)
+        wl["x"], wl["y"], _ = clear_pool_examples(m, wl["params"], wl["x"], wl["y"], O.dp_step)
         ref = O.dp_step(m, wl["params"], wl["x"], wl["y"], 0.5, 0.0, 0)
         out, gn = run_gpu(m, wl["params"], wl["x"], wl["y"], 0.5, 0.0, 0, stepper=st)
         assert rel_l2(out, ref["clipped_sum"]) <= TOL
