@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the private gradient step on one MI355X.
+
+A step is one dp_step call (forward, backward-data, per-example norms, clip
+factors, clipped sums, Philox noise) over one synthetic batch already resident
+in HBM.  Prints ONE JSON line: private examples/s for the headline workload,
+the same-run non-private step time and ratio, the roofline of the dominant
+kernel (timed with HIP events on the library's stream) and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import dp_workloads as W  # noqa: E402
+
+PEAK_MFMA_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+DEFAULT_WORKLOAD = "cfg4_cifar_cnn"
+
+
+def label_work(m, B):
+    """Algorithmic work per kernel label for one step: {label: (flops, bytes)}.
+    Contractions: 2*M*N*K of the mathematical operation (no padding, no bias column).
+    Bytes: compulsory HBM traffic of the operation (operands read once, result written once)."""
+    shapes = W.layer_shapes(m)
+    inp = m["input"]
+    cur = ("chw", inp["c"], inp["h"], inp["w"]) if inp["kind"] == "image" else ("tok", inp["seq_len"])
+    out = {}
+
+    def add(label, flops, nbytes):
+        f, b = out.get(label, (0.0, 0.0))
+        out[label] = (f + flops, b + nbytes)
+
+    for li, L in enumerate(m["layers"]):
+        o = shapes[li]
+        k = L["kind"]
+        if k == "dense":
+            di, do = L["d_in"], L["d_out"]
+            fl = 2.0 * B * di * do
+            add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))
+            if li > 0:
+                add("dense_bwd_data", fl, 4.0 * (B * do + di * do + 2 * B * di))
+            add("dense_norm", 2.0 * B * (di + do), 4.0 * B * (di + do))
+            add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
+        elif k == "conv2d":
+            C_, H_, W_ = cur[1], cur[2], cur[3]
+            D_, OH, OW = o[1], o[2], o[3]
+            ckk = C_ * L["kh"] * L["kw"]
+            fl = 2.0 * B * D_ * ckk * OH * OW
+            xin, xout, wts = B * C_ * H_ * W_, B * D_ * OH * OW, D_ * ckk
+            add("conv_fwd", fl, 4.0 * (xin + wts + xout))
+            if li > 0:
+                add("conv_bwd_data", fl, 4.0 * (xout + wts + 2 * xin))
+            add("conv_wgrad_norm", fl, 4.0 * (xin + xout))
+            add("conv_clipped_sum", fl, 4.0 * (xin + xout + wts))
+        elif k == "maxpool2d":
+            n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]
+            add("maxpool_fwd", 0.0, 4.0 * n_in + 5.0 * n_out)
+            add("maxpool_bwd", 0.0, 8.0 * n_in + 5.0 * n_out)
+        elif k == "embedding":
+            T, D_ = inp["seq_len"], L["dim"]
+            add("emb_norm", 2.0 * B * T * D_, 4.0 * B * T * (D_ + 1))
+            add("emb_scatter", 2.0 * B * T * D_, 4.0 * (B * T * (D_ + 1) + L["vocab"] * D_))
+        elif k == "lstm_last":
+            T, Din, H = cur[1], L["d_in"], L["hidden"]
+            G = 4 * H
+            add("lstm_xproj", 2.0 * B * T * Din * G, 4.0 * (B * T * G + Din * G))
+            add("lstm_fwd", 2.0 * B * T * H * G, 4.0 * B * T * (2 * G + 2 * H))
+            add("lstm_bwd", 2.0 * B * T * H * G, 4.0 * B * T * (2 * G + H))
+            add("lstm_wgrad_norm", 2.0 * B * T * (Din + H) * G, 4.0 * B * T * (G + H + Din))
+            add("lstm_dx", 2.0 * B * T * Din * G, 4.0 * B * T * (G + Din))
+            add("lstm_clipped_sum", 2.0 * B * T * (Din + H) * G, 4.0 * B * T * (G + H + Din))
+        cur = o
+    P = W.num_params(m)
+    add("finalize_noise", 0.0, 8.0 * P)
+    return out
+
+
+def step_flops(m, B, private=True):
+    w = label_work(m, B)
+    skip = () if private else ("dense_norm", "conv_wgrad_norm", "lstm_wgrad_norm", "emb_norm")
+    return sum(f for lab, (f, _) in w.items() if lab not in skip)
+
+
+def time_steps(fn, steps, warmup):
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def run_workload(name, steps, warmup, profile):
+    import torch
+    from paper_2010_09063_amd import DpStep
+    wl = W.make_workload(name, seed=0)
+    m, B = wl["model"], wl["batch"]
+    dev = torch.device("cuda:0")
+    st = DpStep(m, B)
+    tp = torch.from_numpy(wl["params"]).to(dev)
+    tx = torch.from_numpy(wl["x"]).to(dev)
+    ty = torch.from_numpy(wl["y"]).to(dev)
+    out = torch.empty(st.num_params, dtype=torch.float32, device=dev)
+    Cc, sigma = wl["C"], wl["sigma"]
+
+    ms_priv = time_steps(lambda i: st.dp_step(tp, tx, ty, B, Cc, sigma, i, out), steps, warmup)
+    assert bool(torch.isfinite(out).all()), "non-finite gradient"
+    ms_np = time_steps(lambda i: st.dp_step_nonprivate(tp, tx, ty, B, out), steps, warmup)
+    res = dict(workload=name, batch=B, params=st.num_params, ms_private=ms_priv, ms_nonprivate=ms_np,
+               examples_per_s=B / (ms_priv * 1e-3), ratio=ms_priv / ms_np, workspace_mb=st.workspace_bytes / 2**20,
+               tflops=step_flops(m, B) / (ms_priv * 1e-3) / 1e12)
+    if profile:
+        # the same K steps again with every kernel launch bracketed by HIP events on the library's stream
+        st.dp_step_profile(True)
+        ms_prof = time_steps(lambda i: st.dp_step(tp, tx, ty, B, Cc, sigma, i, out), steps, 0)
+        rows = st.dp_step_profile_read(reset=True)
+        st.dp_step_profile(False)
+        work = label_work(m, B)
+        kern = []
+        for label, launches, ms in rows:
+            if launches == 0:
+                continue
+            fl, by = work.get(label, (0.0, 0.0))
+            per_step_ms = ms / steps
+            kern.append(dict(kernel=label, launches_per_step=launches / steps, ms_per_step=per_step_ms,
+                             avg_launch_us=1e3 * ms / launches,
+                             tflops=(fl / (per_step_ms * 1e-3) / 1e12) if per_step_ms > 0 else 0.0,
+                             gbs=(by / (per_step_ms * 1e-3) / 1e9) if per_step_ms > 0 else 0.0,
+                             flops_per_step=fl, bytes_per_step=by))
+        kern.sort(key=lambda r: -r["ms_per_step"])
+        res["ms_private_profiled"] = ms_prof
+        res["kernels"] = kern
+    st.dp_step_free()
+    return res, wl
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands on the host cores, on a bounded sample of the same workload."""
+    from oracle import dpsgd_oracle as O
+    m = wl["model"]
+    cores = O.max_threads()
+    n0 = min(wl["batch"], max(cores, 2 * cores if wl["batch"] >= 2 * cores else cores))
+    t0 = time.perf_counter()
+    O.dp_step(m, wl["params"], wl["x"][:n0], wl["y"][:n0], wl["C"], wl["sigma"], 0)
+    dt = time.perf_counter() - t0
+    rate = n0 / dt
+    n = int(min(wl["batch"], max(n0, (rate * budget_s) // cores * cores)))
+    t0 = time.perf_counter()
+    O.dp_step(m, wl["params"], wl["x"][:n], wl["y"][:n], wl["C"], wl["sigma"], 0)
+    dt = time.perf_counter() - t0
+    return dict(value=n / dt, unit="examples/s", cores=cores, kind="oracle",
+                sample=f"first {n} of {wl['batch']} examples of {wl['name']}, one step, {dt:.1f} s wall, "
+                       f"gcc -O2 -fopenmp fp64 loop oracle")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(W.CONFIGS))
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--kernels", action="store_true", help="print the per-kernel table to stderr")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (nothing in it uses a second); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible (the HIP path has no CPU fallback)", file=sys.stderr)
+        sys.exit(3)
+
+    res, wl = run_workload(a.workload, a.steps, a.warmup, profile=True)
+    kern = res["kernels"]
+    dom = kern[0]
+    mfma_bound = dom["flops_per_step"] > 0 and dom["flops_per_step"] / max(dom["bytes_per_step"], 1.0) > 20.0
+    if mfma_bound:
+        roof = dict(bound="mfma", achieved=dom["tflops"], peak=PEAK_MFMA_FP32_TFLOPS, unit="TFLOP/s",
+                    frac=dom["tflops"] / PEAK_MFMA_FP32_TFLOPS, traffic=None)
+    else:
+        roof = dict(bound="hbm", achieved=dom["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
+                    frac=dom["gbs"] / PEAK_HBM_GBS, traffic=None)
+    roof.update(kernel=dom["kernel"], avg_launch_us=dom["avg_launch_us"], launches_per_step=dom["launches_per_step"],
+                share_of_step=dom["ms_per_step"] / max(res["ms_private_profiled"], 1e-9),
+                step_tflops=res["tflops"], step_frac_of_mfma_fp32_peak=res["tflops"] / PEAK_MFMA_FP32_TFLOPS)
+    if a.kernels:
+        for r in kern:
+            print(f"{r['kernel']:20s} {r['launches_per_step']:5.1f}/step {r['ms_per_step']*1e3:10.1f} us/step "
+                  f"{r['tflops']:8.2f} TFLOP/s {r['gbs']:9.1f} GB/s", file=sys.stderr)
+
+    others = []
+    if not a.no_others:
+        for name in sorted(W.CONFIGS):
+            if name == a.workload:
+                continue
+            r, _ = run_workload(name, max(10, a.steps // 2), max(3, a.warmup // 2), profile=False)
+            others.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()})
+
+    cpu = None if a.no_cpu else cpu_baseline(wl)
+
+    line = {
+        "metric": "private examples/sec per DPSGD step on 1 MI355X; private/non-private step ratio",
+        "value": res["examples_per_s"], "unit": "examples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": res["ms_private"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": a.workload, "batch": res["batch"], "params": res["params"], "C": wl["C"],
+                   "sigma": wl["sigma"], "inputs": "resident in HBM"},
+        "nonprivate_ms_per_step": res["ms_nonprivate"], "private_over_nonprivate": res["ratio"],
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                     if k in ("kernel", "launches_per_step", "ms_per_step", "tflops", "gbs")} for r in kern],
+        "other_workloads": others,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -232,7 +232,7 @@ static double forward(const or_model *m, const double *theta, const void *x, int
             a[oi] = bv;
             s->arg[l][oi] = best;
             if (nbest > 1) s->ties++;
-            if (bv - second < s->margin) s->margin = bv - second;
+            if (bv > second && bv - second < s->margin) s->margin = bv - second; /* exact ties follow the first-maximum rule */
           }
     } break;
     case OR_EMBEDDING: {
@@ -452,8 +452,8 @@ void oracle_noise(uint64_t seed, long n, double *z) {
 /* params fp32[P]; x fp32[B, in_c*in_h*in_w] or int32[B, seq_len]; y int32[B] (all host).
  * out fp32[P] = sum_i clip(g_i) + sigma*C*z.  Optional outputs (may be NULL):
  *   norms[B]  unclipped ||g_i||;  clipped_sum[P] the fp64 sum before noise;  ties;
- *   pool_margin[B]  smallest gap between the maximum and the runner-up over the example's
- *   pool windows (+inf without pooling): an fp32 implementation may route a window whose
+ *   pool_margin[B]  smallest non-zero gap between the maximum and the runner-up over the example's
+ *   pool windows (+inf without pooling; exact ties go to the first maximum on every implementation): an fp32 implementation may route a window whose
  *   gap is at rounding level to the other element, so tests compare on clear examples.
  * C = +inf disables clipping; sigma = 0 adds exactly nothing.  clip = 0 skips the
  * clipping branch altogether (the non-private summed gradient).  Returns 0. */

@@ -198,7 +198,9 @@ static ConvGeom make_geom(const Layer &l) {
   return g;
 }
 
-#define DP_MAX_SPLIT 64
+// split-K partials: at most 1024 splits and 16 M floats per parameter tensor
+#define DP_MAX_SPLIT 1024
+#define DP_MAX_PART_FLOATS (16l << 20)
 
 // ---------------------------------------------------------------- init / free
 
@@ -293,7 +295,11 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     if (rc == DP_OK) rc = dev_alloc(c, &l.g, mb * l.out_size);
     if (rc == DP_OK && l.d.kind == DP_MAXPOOL2D) rc = dev_alloc(c, &l.arg, mb * l.out_size);
     if (rc == DP_OK && l.p_count > 0) {
-      l.max_split = emb ? 1 : DP_MAX_SPLIT;
+      l.max_split = 1;
+      if (!emb) {
+        long ms = DP_MAX_PART_FLOATS / l.p_count;
+        l.max_split = (int)(ms < 8 ? 8 : (ms > DP_MAX_SPLIT ? DP_MAX_SPLIT : ms));
+      }
       rc = dev_alloc(c, &l.part, (size_t)l.max_split * l.p_count);
     }
     if (rc == DP_OK && l.d.kind == DP_LSTM_LAST) {
@@ -612,8 +618,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
   // ------------------------------------------------------------ final write with fused noise
   {
     const float noise_std = (priv && sigma > 0.f) ? sigma * C : 0.f;
-    long nblk = (c->P + 3) / 4;
-    dim3 grid = grid1d(nblk, 256), block(256);
+    dim3 grid = grid1d(c->P, 16), block(256);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     Ln("finalize_noise", grid, block, [&](hipStream_t st) {
       hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, c->P, noise_std, k0, k1);

@@ -146,7 +146,9 @@ __device__ __forceinline__ void normal4(uint64_t blk, uint32_t k0, uint32_t k1, 
 }
 
 // Final write (DPSGD item 3): out[j] = sum over split-K partials of the clipped
-// sum + sigma*C*z_j.  One thread per Philox block of four coordinates.
+// sum + sigma*C*z_j.  A workgroup owns 16 consecutive coordinates (four Philox
+// blocks); its 256 threads split the partials 16 ways, so a tensor cut into
+// many splits is still reduced with short dependent chains, in a fixed order.
 #define DP_MAX_SEG 24
 struct FinalizeSeg {
   long p_off, n;     // segment [p_off, p_off + n) of the flat parameter vector
@@ -159,23 +161,38 @@ struct FinalizeArgs {
   FinalizeSeg seg[DP_MAX_SEG];
 };
 
-__global__ void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P, float noise_std,
-                                uint32_t k0, uint32_t k1) {
-  long blk = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  long j0 = blk * 4;
-  if (j0 >= P) return;
-  float z[4] = {0.f, 0.f, 0.f, 0.f};
-  if (noise_std > 0.f) normal4((uint64_t)blk, k0, k1, z);
-  int si = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    long j = j0 + q;
-    if (j >= P) break;
+__global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P,
+                                                        float noise_std, uint32_t k0, uint32_t k1) {
+  __shared__ float red[16][17];
+  const int cj = threadIdx.x & 15, sg = threadIdx.x >> 4;
+  const long j = (long)blockIdx.x * 16 + cj;
+  float acc = 0.f;
+  if (j < P) {
+    int si = 0;
     while (si < fa.nseg - 1 && j >= fa.seg[si].p_off + fa.seg[si].n) ++si;
-    const FinalizeSeg &sg = fa.seg[si];
-    float acc = 0.f;
-    long loc = j - sg.p_off;
-    for (int s = 0; s < sg.nsplit; ++s) acc += sg.part[s * sg.stride + loc];
-    out[j] = noise_std > 0.f ? acc + noise_std * z[q] : acc;
+    const FinalizeSeg &g = fa.seg[si];
+    const float *p = g.part + (j - g.p_off);
+    const long st = g.stride;
+    const int ns = g.nsplit;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    int s = sg;
+    for (; s + 48 < ns; s += 64) {
+      a0 += p[s * st]; a1 += p[(s + 16) * st]; a2 += p[(s + 32) * st]; a3 += p[(s + 48) * st];
+    }
+    for (; s < ns; s += 16) a0 += p[s * st];
+    acc = (a0 + a1) + (a2 + a3);
+  }
+  red[sg][cj] = acc;
+  __syncthreads();
+  if (threadIdx.x < 16 && j < P) {
+    float tot = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) tot += red[q][cj];
+    if (noise_std > 0.f) {
+      float z[4];
+      normal4((uint64_t)(j >> 2), k0, k1, z);
+      tot += noise_std * z[j & 3];
+    }
+    out[j] = tot;
   }
 }
