@@ -175,6 +175,8 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--kernels", action="store_true", help="print the per-kernel table to stderr")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference point for rocprofv3 --pmc byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (nothing in it uses a second); use --gpus 1", file=sys.stderr)
@@ -184,6 +186,12 @@ def main():
         print("bench.py: no GPU visible (the HIP path has no CPU fallback)", file=sys.stderr)
         sys.exit(3)
 
+    if a.calib_copy:
+        src = torch.ones(64 * 2**20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     res, wl = run_workload(a.workload, a.steps, a.warmup, profile=True)
     kern = res["kernels"]
     dom = kern[0]
