@@ -1,0 +1,363 @@
+// Stride-1 convolution kernels with the input tile staged once in LDS ("LDS-staged
+// im2col"): the MFMA operands are read straight from the staged image tile with a
+// per-tap offset, so no im2col matrix exists anywhere and a pixel is fetched from
+// HBM/L2 about 1.5 times instead of KH*KW times.
+//
+//   conv_s1_kernel        forward  (bias + activation epilogue) and backward-data
+//                         (the same correlation with transposed, flipped weights and
+//                         an activation-derivative epilogue)
+//   conv_s1_wgrad_kernel  weight gradient  G[d, c, tap] = sum_p Delta[d, p] x[c, p + tap]
+//                         per example with its squares reduced to the per-example norm
+//                         (never written), or summed over a range of examples with the
+//                         clip factor applied to Delta while staging (split partial of
+//                         the clipped sum, DPSGD item 3).
+//
+// MFMA mapping (v_mfma_f32_32x32x2_f32): forward  M = output channel, N = pixel,
+// K = input-channel pair for one tap;  wgrad  M = output channel d, N = input channel c
+// for one tap, K = pixel pair.  Lanes of the B operand walk pixels (forward) or
+// channels with an odd plane stride (wgrad), lanes of the A operand walk channels:
+// all LDS operand reads are conflict-free 4-byte reads with uniform offsets.
+#pragma once
+#include "gemm_tile.h"
+#include "kernels_misc.h"
+
+struct ConvTile {
+  int TR, NIMG;       // tile = NIMG images x TR output rows x OW columns
+  int row_tiles;      // ceil(OH / TR)            (1 when NIMG > 1)
+  int LDW, IMGPL;     // staged row length OW+KW-1; floats per staged image = (TR+KH-1)*LDW
+  int XPLANE;         // floats per staged channel (>= NIMG*IMGPL)
+  FastDiv dOW, dTROW, dLDW, dIMGPL, dXPLANE, dRT;
+};
+
+struct ConvS1Args {
+  const float *x;      // input  [B, Cin, H, W]
+  const float *wt;     // weights laid out [Cin][KK][M] (see conv_weight_layout_kernel)
+  const float *bias;   // forward: bias[M]; backward-data: null
+  const float *a_prev; // backward-data: output of the activation whose derivative multiplies the result
+  float *out;          // [B, M, OH, OW]
+  int B, Cin, H, W, M, OH, OW, pad;
+  int act;
+  ConvTile t;
+};
+
+// Re-lays a conv weight W[D][C][KK] for the two correlations that use it:
+//   wt_f[(c*KK + tap)*D + d] = W[d][c][tap]            forward       (M = D, Cin = C)
+//   wt_b[(d*KK + tap)*C + c] = W[d][c][KK-1-tap]       backward-data (M = C, Cin = D)
+// so that a chunk of input channels is one contiguous block that is copied
+// straight into LDS in the order the MFMA A operand reads it.
+__global__ void conv_weight_layout_kernel(const float *__restrict__ w, float *__restrict__ wt_f,
+                                          float *__restrict__ wt_b, int D, int C, int KK) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= D * C * KK) return;
+  int d = i / (C * KK), r = i - d * C * KK;
+  int c = r / KK, tap = r - c * KK;
+  float v = w[i];
+  wt_f[((long)c * KK + tap) * D + d] = v;
+  wt_b[((long)d * KK + (KK - 1 - tap)) * C + c] = v;
+}
+
+#define CONV_CC 8     // input channels staged per chunk
+#define CONV_XCNT 14  // staged input elements per thread and chunk (CC * XPLANE <= 14 * 256)
+
+template <int KH, int KW, int DT, int NPW>
+__global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
+  constexpr int KK = KH * KW, CC = CONV_CC, DB = DT / 32, PB = NPW / 32;
+  constexpr int WROWS = CC * KK;                     // weight rows per chunk
+  constexpr int WV = (WROWS * DT / 4 + 255) / 256;   // float4 weight registers per thread
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  float *Wl = smem;                 // [WROWS][DT]
+  float *Xl = smem + WROWS * DT;    // [CC][XPLANE]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
+  const int m0 = blockIdx.y * DT;
+  // tile -> first image and first row
+  int b0, r0;
+  if (a.t.NIMG > 1) { b0 = blockIdx.x * a.t.NIMG; r0 = 0; }
+  else { b0 = (int)a.t.dRT.div(blockIdx.x); r0 = (blockIdx.x - b0 * a.t.row_tiles) * a.t.TR; }
+  const int HW = a.H * a.W, OHW = a.OH * a.OW;
+
+  // this lane's pixels (one per 32-pixel block of the wave)
+  int xoff[PB];
+  long ooff[PB]; // offset of the pixel in out for channel 0, or -1
+#pragma unroll
+  for (int pb = 0; pb < PB; ++pb) {
+    const int lp = wave * NPW + pb * 32 + li;
+    const int img = (int)a.t.dTROW.div(lp), rem = lp - img * a.t.TR * a.OW;
+    const int r = (int)a.t.dOW.div(rem), col = rem - r * a.OW;
+    const bool ok = img < a.t.NIMG && (b0 + img) < a.B && (r0 + r) < a.OH;
+    xoff[pb] = (ok ? img * a.t.IMGPL + r * a.t.LDW + col : 0) + lk * a.t.XPLANE;
+    ooff[pb] = ok ? ((long)(b0 + img) * a.M) * OHW + (long)(r0 + r) * a.OW + col : -1;
+  }
+  // staged-input descriptors of this thread: LDS element e = tid + j*256 = (c, img, rr, cc)
+  int goff[CONV_XCNT]; // offset inside x for channel chunk 0, or -1 (halo / outside the batch)
+  int gch[CONV_XCNT];  // channel within the chunk
+  const int xtotal = CC * a.t.XPLANE;
+#pragma unroll
+  for (int j = 0; j < CONV_XCNT; ++j) {
+    const int e = tid + j * 256;
+    goff[j] = -1; gch[j] = 0;
+    if (e < xtotal) {
+      const int c = (int)a.t.dXPLANE.div(e), rem = e - c * a.t.XPLANE;
+      const int img = (int)a.t.dIMGPL.div(rem), rem2 = rem - img * a.t.IMGPL;
+      const int rr = (int)a.t.dLDW.div(rem2), cc = rem2 - rr * a.t.LDW;
+      const int ih = r0 + rr - a.pad, iw = cc - a.pad;
+      gch[j] = c;
+      if (img < a.t.NIMG && (b0 + img) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+        goff[j] = ((b0 + img) * a.Cin + c) * HW + ih * a.W + iw;
+    }
+  }
+  // weight descriptors: float4 q = tid + j*256 covers row q / (DT/4), columns 4*(q % (DT/4)) ..+3
+  const bool wvec = (a.M & 3) == 0;
+
+  f32x16 acc[DB][PB];
+#pragma unroll
+  for (int i = 0; i < DB; ++i)
+#pragma unroll
+    for (int j = 0; j < PB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float xr[CONV_XCNT];
+  float4 wr[WV];
+  auto prefetch = [&](int c0) {
+#pragma unroll
+    for (int j = 0; j < CONV_XCNT; ++j) {
+      float v = 0.f;
+      if (goff[j] >= 0 && c0 + gch[j] < a.Cin) v = a.x[(long)goff[j] + (long)c0 * HW];
+      xr[j] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < WV; ++j) {
+      const int q = tid + j * 256;
+      const int row = q / (DT / 4), m = m0 + 4 * (q - row * (DT / 4));
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < WROWS && c0 * KK + row < a.Cin * KK) {
+        const float *src = a.wt + (long)(c0 * KK + row) * a.M + m;
+        if (wvec) { if (m < a.M) v = *reinterpret_cast<const float4 *>(src); }
+        else {
+          if (m < a.M) v.x = src[0];
+          if (m + 1 < a.M) v.y = src[1];
+          if (m + 2 < a.M) v.z = src[2];
+          if (m + 3 < a.M) v.w = src[3];
+        }
+      }
+      wr[j] = v;
+    }
+  };
+
+  prefetch(0);
+  for (int c0 = 0; c0 < a.Cin; c0 += CC) {
+    __syncthreads(); // the previous chunk has been consumed
+#pragma unroll
+    for (int j = 0; j < CONV_XCNT; ++j) {
+      const int e = tid + j * 256;
+      if (e < xtotal) Xl[e] = xr[j];
+    }
+#pragma unroll
+    for (int j = 0; j < WV; ++j) {
+      const int q = tid + j * 256;
+      if (q < WROWS * DT / 4) *reinterpret_cast<float4 *>(&Wl[4 * q]) = wr[j];
+    }
+    __syncthreads();
+    if (c0 + CC < a.Cin) prefetch(c0 + CC); // in flight while this chunk is multiplied
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp) {
+#pragma unroll
+      for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+        for (int kw = 0; kw < KW; ++kw) {
+          float av[DB], bv[PB];
+          const int wrow = ((2 * cp + lk) * KK + kh * KW + kw) * DT;
+#pragma unroll
+          for (int i = 0; i < DB; ++i) av[i] = Wl[wrow + i * 32 + li];
+          const int xo = 2 * cp * a.t.XPLANE + kh * a.t.LDW + kw;
+#pragma unroll
+          for (int j = 0; j < PB; ++j) bv[j] = Xl[xoff[j] + xo];
+#pragma unroll
+          for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int j = 0; j < PB; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+    }
+  }
+
+#pragma unroll
+  for (int j = 0; j < PB; ++j) {
+    if (ooff[j] < 0) continue;
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+        if (m < a.M) {
+          const long o = ooff[j] + (long)m * OHW;
+          float v = acc[i][j][r];
+          if (a.bias) v = act_apply(a.act, v + a.bias[m]);
+          else if (a.act) v *= act_deriv_from_out(a.act, a.a_prev[o]);
+          a.out[o] = v;
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------- weight gradient
+
+struct ConvWgArgs {
+  const float *x;     // layer input [B, C, H, W]
+  const float *delta; // [B, D, OH, OW]
+  const float *scale; // clip factors s[b] (clipped mode; null = 1)
+  float *out;         // norm mode: slots base; clipped mode: partials base
+  int B, C, H, W, D, OH, OW, pad;
+  int mode;           // 0: per-example squared norm; 1: sum over the block's examples
+  int ex_per_block;   // clipped mode
+  int PCH, LDP;       // pixels per K-chunk (= NIMG*TR*OW) and padded (odd) row length of the staged Delta
+  FastDiv dPCH;
+  long slot_stride; int slot0; // norm: slots[(slot0 + cblock)*slot_stride + b]
+  long part_stride;   // clipped: part[split*part_stride + (d*C + c)*KK + tap]; bias at D*C*KK + d
+  ConvTile t;         // XPLANE odd
+};
+
+// DB = number of 32-row blocks of output channels (D <= 32*DB); the block owns one
+// group of 32 input channels; the KH*KW taps are its N blocks.
+template <int KH, int KW, int DB>
+__global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
+  constexpr int KK = KH * KW;
+  constexpr int WD = DB >= 4 ? 4 : DB, WN = 4 / WD; // waves along d and along taps
+  constexpr int DBW = DB / WD, NBW = (KK + WN - 1) / WN;
+  extern __shared__ float smem[];
+  float *Xl = smem;                     // [32][XPLANE]
+  float *Dl = smem + 32 * a.t.XPLANE;   // [32*DB][LDP]
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
+  const int wd = wave / WN, wn = wave - wd * WN;
+  const int cb = blockIdx.x, c0 = cb * 32;
+  const int HW = a.H * a.W, OHW = a.OH * a.OW;
+  int bbeg, bend;
+  if (a.mode == 0) { bbeg = blockIdx.y; bend = bbeg + 1; }
+  else { bbeg = blockIdx.y * a.ex_per_block; bend = min(a.B, bbeg + a.ex_per_block); }
+
+  f32x16 acc[DBW][NBW];
+#pragma unroll
+  for (int i = 0; i < DBW; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  float rowsum = 0.f; // thread d < D of channel group 0: sum_p Delta[d, p] (bias gradient)
+
+  // tap offsets of this wave's N blocks (uniform), lane bases
+  const int xlane = li * a.t.XPLANE + lk;
+  const int dlane = li * a.LDP + lk;
+  const int nimg_max = a.mode == 0 ? 1 : a.t.NIMG;
+  int tapoff[NBW];
+  bool tapok[NBW];
+#pragma unroll
+  for (int j = 0; j < NBW; ++j) {
+    const int tap = wn * NBW + j;
+    const int kh = tap / KW, kw = tap - kh * KW;
+    tapok[j] = tap < KK;
+    tapoff[j] = tapok[j] ? kh * a.t.LDW + kw : 0;
+  }
+
+  for (int b = bbeg; b < bend; b += nimg_max) {
+    const int nimg = min(nimg_max, bend - b);
+    for (int rt = 0; rt < a.t.row_tiles; ++rt) {
+      const int r0 = rt * a.t.TR;
+      const int rows = min(a.t.TR, a.OH - r0);
+      __syncthreads();
+      // stage x: 32 channels x nimg images x (rows+KH-1) x LDW with zero halo
+      {
+        const int per_ch = nimg * a.t.IMGPL;
+        for (int e = tid; e < 32 * per_ch; e += 256) {
+          const int c = e / per_ch, rem = e - c * per_ch; // per_ch is uniform: scalar division
+          const int img = (int)a.t.dIMGPL.div(rem), rem2 = rem - img * a.t.IMGPL;
+          const int rr = (int)a.t.dLDW.div(rem2), cc = rem2 - rr * a.t.LDW;
+          const int ih = r0 + rr - a.pad, iw = cc - a.pad;
+          float v = 0.f;
+          if (c0 + c < a.C && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
+            v = a.x[((long)(b + img) * a.C + c0 + c) * HW + ih * a.W + iw];
+          Xl[c * a.t.XPLANE + rem] = v;
+        }
+      }
+      // stage Delta (times the clip factor): rows d, columns (img, r, col) of the chunk; pad columns are zero
+      {
+        const int per_img = a.t.TR * a.OW;
+        for (int e = tid; e < 32 * DB * a.PCH; e += 256) {
+          const int d = (int)a.dPCH.div(e), p = e - d * a.PCH;
+          const int img = (int)a.t.dTROW.div(p), rem = p - img * per_img;
+          const int r = (int)a.t.dOW.div(rem);
+          float v = 0.f;
+          if (d < a.D && img < nimg && r < rows) {
+            v = a.delta[((long)(b + img) * a.D + d) * OHW + (long)r0 * a.OW + rem];
+            if (a.scale) v *= a.scale[b + img];
+          }
+          Dl[d * a.LDP + p] = v;
+        }
+      }
+      __syncthreads();
+      if (cb == 0 && tid < a.D) {
+        float s = 0.f;
+        for (int p = 0; p < a.PCH; ++p) s += Dl[tid * a.LDP + p];
+        rowsum += s;
+      }
+      // K loop over pixel pairs of the chunk (OW is even: a pair never straddles a row)
+      for (int img = 0; img < nimg; ++img)
+        for (int r = 0; r < rows; ++r) {
+          const int pbase = (img * a.t.TR + r) * a.OW;
+          const int xbase = img * a.t.IMGPL + r * a.t.LDW;
+          for (int col = 0; col < a.OW; col += 2) {
+            float av[DBW], bv[NBW];
+#pragma unroll
+            for (int i = 0; i < DBW; ++i) av[i] = Dl[dlane + ((wd * DBW + i) * 32) * a.LDP + pbase + col];
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) {
+              bv[j] = Xl[xlane + xbase + col + tapoff[j]];
+              if (!tapok[j]) bv[j] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < DBW; ++i)
+#pragma unroll
+              for (int j = 0; j < NBW; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+          }
+        }
+    }
+  }
+
+  // accumulator: lane column = input channel c0 + li; rows = output channels
+  const int c = c0 + li;
+  if (a.mode == 0) {
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < DBW; ++i)
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) {
+        const int tap = wn * NBW + j;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+          if (tap < KK && c < a.C && d < a.D) part += acc[i][j][r] * acc[i][j][r];
+        }
+      }
+    if (cb == 0 && tid < a.D) part += rowsum * rowsum;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    if (tid == 0) a.out[(long)(a.slot0 + cb) * a.slot_stride + bbeg] = red[0] + red[1] + red[2] + red[3];
+  } else {
+    float *part = a.out + (long)blockIdx.y * a.part_stride;
+#pragma unroll
+    for (int i = 0; i < DBW; ++i)
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) {
+        const int tap = wn * NBW + j;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+          if (tap < KK && c < a.C && d < a.D) part[((long)d * a.C + c) * KK + tap] = acc[i][j][r];
+        }
+      }
+    if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = rowsum;
+  }
+}

@@ -7,12 +7,14 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <type_traits>
 #include <vector>
 
 #include "gemm_tile.h"
+#include "conv_direct.h"
 #include "kernels_misc.h"
 #include "kernels_seq.h"
 #include "operands.h"
@@ -116,6 +118,11 @@ struct Layer {
   int max_split = 0;
   int max_slots = 0;
   ConvGeom geom;
+  // stride-1 3x3 convolutions: LDS-staged direct kernels (otherwise the generic contraction)
+  bool dir_fwd = false, dir_bwd = false, dir_wg = false;
+  int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
+  ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
+  float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
   // lstm
   float *gates = nullptr, *cs = nullptr, *hs = nullptr;
   int T = 0, Din = 0, H = 0;
@@ -198,6 +205,98 @@ static ConvGeom make_geom(const Layer &l) {
   return g;
 }
 
+
+// ---------------------------------------------------------------- direct convolution planning
+
+static bool make_conv_tile(ConvTile &t, int OH, int OW, int KH, int KW, int np_max, bool odd_plane, int nimg_cap) {
+  if (OW > np_max || OW < 1) return false;
+  if (OH * OW <= np_max) {
+    t.NIMG = np_max / (OH * OW);
+    if (t.NIMG > nimg_cap) t.NIMG = nimg_cap;
+    t.TR = OH; t.row_tiles = 1;
+  } else {
+    t.NIMG = 1; t.TR = np_max / OW; t.row_tiles = ceil_div(OH, t.TR);
+  }
+  t.LDW = OW + KW - 1;
+  t.IMGPL = (t.TR + KH - 1) * t.LDW;
+  t.XPLANE = t.NIMG * t.IMGPL;
+  if (odd_plane && (t.XPLANE & 1) == 0) t.XPLANE += 1;
+  t.dOW.init(OW); t.dTROW.init(t.TR * OW); t.dLDW.init(t.LDW); t.dIMGPL.init(t.IMGPL);
+  t.dXPLANE.init(t.XPLANE); t.dRT.init(t.row_tiles);
+  return true;
+}
+
+static void plan_direct_conv(Layer &l, int maxB, bool allow) {
+  const ConvGeom &g = l.geom;
+  if (!allow || g.S != 1 || g.KH != 3 || g.KW != 3 || g.PAD > 2) return;
+  if ((long)maxB * g.C * g.H * g.W >= (1l << 31) || (long)maxB * g.D * g.P >= (1l << 31)) return;
+  // forward: output OH x OW
+  {
+    int npw = ((long)maxB * g.P / 256 >= 512) ? 64 : 32;
+    if (make_conv_tile(l.t_fwd, g.OH, g.OW, 3, 3, 4 * npw, false, 1 << 20) &&
+        CONV_CC * l.t_fwd.XPLANE <= CONV_XCNT * 256) { l.dir_fwd = true; l.fwd_npw = npw; }
+  }
+  // backward-data: correlation of Delta (OH x OW) with flipped weights, output H x W, pad' = 2 - pad
+  {
+    int npw = ((long)maxB * g.H * g.W / 256 >= 512) ? 64 : 32;
+    if (make_conv_tile(l.t_bwd, g.H, g.W, 3, 3, 4 * npw, false, 1 << 20) &&
+        CONV_CC * l.t_bwd.XPLANE <= CONV_XCNT * 256) { l.dir_bwd = true; l.bwd_npw = npw; }
+  }
+  // weight gradient
+  if (g.C >= 16 && g.D <= 128 && (g.OW & 1) == 0) {
+    int db = g.D <= 32 ? 1 : (g.D <= 64 ? 2 : 4);
+    int pch_max = db <= 2 ? 128 : 64;
+    bool ok = make_conv_tile(l.t_wgn, g.OH, g.OW, 3, 3, pch_max, true, 1) &&
+              make_conv_tile(l.t_wgc, g.OH, g.OW, 3, 3, pch_max, true, 1 << 20);
+    if (ok) {
+      long lds_n = 32l * l.t_wgn.XPLANE + 32l * db * ((l.t_wgn.NIMG * l.t_wgn.TR * g.OW) | 1);
+      long lds_c = 32l * l.t_wgc.XPLANE + 32l * db * ((l.t_wgc.NIMG * l.t_wgc.TR * g.OW) | 1);
+      if (lds_n * 4 <= 64 * 1024 && lds_c * 4 <= 64 * 1024) { l.dir_wg = true; l.wg_db = db; }
+    }
+  }
+}
+
+template <class LN>
+static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a, int npw) {
+  const int dt = a.M <= 32 ? 32 : (a.M <= 64 ? 64 : 128);
+  dim3 grid(a.t.NIMG > 1 ? ceil_div(a.B, a.t.NIMG) : a.B * a.t.row_tiles, ceil_div(a.M, dt)), block(256);
+  size_t smem = sizeof(float) * ((size_t)CONV_CC * a.t.XPLANE + (size_t)CONV_CC * 9 * dt);
+#define DP_CONV_CASE(dt_, npw_)                                                                      \
+  if (dt == dt_ && npw == npw_) {                                                                    \
+    Ln(label, grid, block, [&](hipStream_t st) {                                                     \
+      hipLaunchKernelGGL((conv_s1_kernel<3, 3, dt_, npw_>), grid, block, smem, st, a);               \
+    });                                                                                              \
+    return;                                                                                          \
+  }
+  DP_CONV_CASE(32, 64) DP_CONV_CASE(64, 64) DP_CONV_CASE(128, 64)
+  DP_CONV_CASE(32, 32) DP_CONV_CASE(64, 32) DP_CONV_CASE(128, 32)
+#undef DP_CONV_CASE
+}
+
+template <class LN>
+static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs &a, int db, int groups) {
+  dim3 grid(ceil_div(a.C, 32), groups), block(256);
+  size_t smem = sizeof(float) * (32 * (size_t)a.t.XPLANE + 32 * (size_t)db * a.LDP);
+#define DP_WG_CASE(db_)                                                                              \
+  if (db == db_) {                                                                                   \
+    Ln(label, grid, block, [&](hipStream_t st) {                                                     \
+      hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_>), grid, block, smem, st, a);               \
+    });                                                                                              \
+    return;                                                                                          \
+  }
+  DP_WG_CASE(1) DP_WG_CASE(2) DP_WG_CASE(4)
+#undef DP_WG_CASE
+}
+
+static ConvWgArgs make_wg_args(const Layer &l, const float *x, int B, const ConvTile &t) {
+  const ConvGeom &g = l.geom;
+  ConvWgArgs a{};
+  a.x = x; a.delta = l.g; a.B = B; a.C = g.C; a.H = g.H; a.W = g.W; a.D = g.D; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
+  a.t = t;
+  a.PCH = t.NIMG * t.TR * g.OW; a.LDP = a.PCH | 1; a.dPCH.init(a.PCH);
+  return a;
+}
+
 // split-K partials: at most 1024 splits and 16 M floats per parameter tensor
 #define DP_MAX_SPLIT 1024
 #define DP_MAX_PART_FLOATS (16l << 20)
@@ -269,7 +368,11 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     if (rc != DP_OK) break;
     l.in_size = (long)l.inC * l.inH * l.inW;
     l.out_size = (long)l.outC * l.outH * l.outW;
-    if (l.d.kind == DP_CONV2D) l.geom = make_geom(l);
+    if (l.d.kind == DP_CONV2D) {
+      l.geom = make_geom(l);
+      const char *env = getenv("DP_STEP_GENERIC_CONV"); // "1": keep every convolution on the generic contraction
+      plan_direct_conv(l, max_batch, !(env && env[0] == '1'));
+    }
     off += l.p_count;
     total_slots += l.max_slots;
     curC = l.outC; curH = l.outH; curW = l.outW;
@@ -301,6 +404,10 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
         l.max_split = (int)(ms < 8 ? 8 : (ms > DP_MAX_SPLIT ? DP_MAX_SPLIT : ms));
       }
       rc = dev_alloc(c, &l.part, (size_t)l.max_split * l.p_count);
+    }
+    if (rc == DP_OK && (l.dir_fwd || l.dir_bwd)) {
+      rc = dev_alloc(c, &l.wt_f, (size_t)l.geom.D * l.geom.CKK);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, (size_t)l.geom.D * l.geom.CKK);
     }
     if (rc == DP_OK && l.d.kind == DP_LSTM_LAST) {
       rc = dev_alloc(c, &l.gates, mb * l.T * 4 * l.H);
@@ -394,6 +501,23 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         launch_gemm(p, 1, Ln, "dense_fwd");
       } break;
       case DP_CONV2D: {
+        if (l.dir_fwd || l.dir_bwd) {
+          const ConvGeom &g = l.geom;
+          const int n = g.D * g.CKK;
+          dim3 grid = grid1d(n, 256), block(256);
+          Ln("conv_weight_layout", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, W, l.wt_f, l.wt_b, g.D, g.C, 9);
+          });
+        }
+        if (l.dir_fwd) {
+          const ConvGeom &g = l.geom;
+          ConvS1Args a{};
+          a.x = in; a.wt = l.wt_f; a.bias = W + (long)g.D * g.CKK; a.a_prev = nullptr; a.out = l.a;
+          a.B = B; a.Cin = g.C; a.H = g.H; a.W = g.W; a.M = g.D; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
+          a.act = l.d.act; a.t = l.t_fwd;
+          launch_conv_s1(Ln, "conv_fwd", a, l.fwd_npw);
+          break;
+        }
         typedef ProbConvFwd<OpRowMajor, OpConvPatch<true>> Pb;
         Pb p{};
         const ConvGeom &g = l.geom;
@@ -468,7 +592,13 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
-        if (priv) {
+        if (priv && l.dir_wg) {
+          ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn);
+          a.scale = nullptr; a.out = c->slots; a.mode = 0; a.ex_per_block = 1;
+          a.slot_stride = slot_stride; a.slot0 = slot_next;
+          slot_next += ceil_div(g.C, 32);
+          launch_conv_wgrad(Ln, "conv_wgrad_norm", a, l.wg_db, B);
+        } else if (priv) {
           typedef ProbSqNorm<OpRowMajor, OpConvPatch<false>> Pb;
           Pb p{};
           p.M = g.D; p.N = g.CKK + 1; p.K = g.P;
@@ -478,7 +608,13 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           GemmShape s = launch_gemm(p, B, Ln, "conv_wgrad_norm");
           slot_next += s.tiles_m * s.tiles_n;
         }
-        if (prev) {
+        if (prev && l.dir_bwd) {
+          ConvS1Args a{};
+          a.x = l.g; a.wt = l.wt_b; a.bias = nullptr; a.a_prev = prev->a; a.out = prev->g;
+          a.B = B; a.Cin = g.D; a.H = g.OH; a.W = g.OW; a.M = g.C; a.OH = g.H; a.OW = g.W; a.pad = 2 - g.PAD;
+          a.act = prev_act; a.t = l.t_bwd;
+          launch_conv_s1(Ln, "conv_bwd_data", a, l.bwd_npw);
+        } else if (prev) {
           typedef ProbConvBwd<OpConvWeightT, OpConvDeltaGather> Pb;
           Pb p{};
           p.M = g.C; p.N = B * g.H * g.W; p.K = g.D * g.KH * g.KW;
@@ -568,6 +704,18 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
+        if (l.dir_wg) {
+          ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc);
+          const int cblocks = ceil_div(g.C, 32);
+          int want = ceil_div(1024, cblocks);
+          if (want > l.max_split) want = l.max_split;
+          int epb = ceil_div(B, want);
+          epb = ceil_div(epb, a.t.NIMG) * a.t.NIMG;
+          nsplit = ceil_div(B, epb);
+          a.scale = sc; a.out = l.part; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
+          launch_conv_wgrad(Ln, "conv_clipped_sum", a, l.wg_db, nsplit);
+          break;
+        }
         typedef ProbPartial<OpChanPix, OpConvPatch<false>> Pb;
         Pb p{};
         p.M = g.D; p.N = g.CKK + 1; p.K = B * g.P;

@@ -110,14 +110,21 @@ def test_gradient_vs_finite_differences(name):
     th = theta.astype(np.float64)
     for i in range(x.shape[0]):
         _, g, _ = O.example_grad(m, th, x[i], y[i])
-        num = np.zeros_like(g)
+        # every coordinate of small models; for larger ones a seeded sample that covers every tensor
+        if th.size <= 400:
+            idx = np.arange(th.size)
+        else:
+            rs = np.random.default_rng(i)
+            idx = np.unique(np.concatenate(
+                [off + rs.integers(0, int(np.prod(shp)), size=24) for _, _, shp, off in W.param_tensors(m)]))
+        num = np.zeros(idx.size)
         eps = 1e-6
-        for j in range(th.size):
+        for k, j in enumerate(idx):
             tp, tm = th.copy(), th.copy()
             tp[j] += eps
             tm[j] -= eps
-            num[j] = (O.example_loss(m, tp, x[i], y[i]) - O.example_loss(m, tm, x[i], y[i])) / (2 * eps)
-        assert np.linalg.norm(g - num) <= 1e-6 * max(1.0, np.linalg.norm(num)), name
+            num[k] = (O.example_loss(m, tp, x[i], y[i]) - O.example_loss(m, tm, x[i], y[i])) / (2 * eps)
+        assert np.linalg.norm(g[idx] - num) <= 1e-6 * max(1.0, np.linalg.norm(num)), name
         assert np.linalg.norm(g) > 0
 
 
