@@ -255,9 +255,11 @@ def tiny_models():
             conv2d(2, 3, 3, stride=1, pad=1, act="tanh"), conv2d(3, 4, 2, stride=1, pad=0, act="relu"),
             maxpool2d(2, 2), dense(4 * 3 * 2, 5, "tanh"), dense(5, 3)], 3),
         # 3x3 stride-1 convolutions with channel counts that exercise the LDS-staged kernels:
-        # ragged channel groups (20, 40, 70), pads 1 / 0 / 2, non-square images
+        # ragged channel groups (20, 40, 70), a non-square image, pad 1 (all direct kernels) and
+        # pad 0 (direct forward / backward-data, generic weight gradient)
         "tiny_conv3": model(image_input(3, 9, 8), [
-            conv2d(3, 20, 3, stride=1, pad=1, act="tanh"), conv2d(20, 40, 3, stride=1, pad=0, act="tanh"),
-            conv2d(40, 70, 3, stride=1, pad=2, act="tanh"), maxpool2d(2, 2), dense(70 * 4 * 4, 3)], 3),
+            conv2d(3, 20, 3, stride=1, pad=1, act="tanh"), conv2d(20, 40, 3, stride=1, pad=1, act="tanh"),
+            conv2d(40, 70, 3, stride=1, pad=1, act="tanh"), conv2d(70, 24, 3, stride=1, pad=0, act="tanh"),
+            maxpool2d(2, 2), dense(24 * 3 * 3, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
     }

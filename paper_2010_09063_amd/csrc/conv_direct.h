@@ -211,23 +211,33 @@ struct ConvWgArgs {
   int mode;           // 0: per-example squared norm; 1: sum over the block's examples
   int ex_per_block;   // clipped mode
   int PCH, LDP;       // pixels per K-chunk (= NIMG*TR*OW) and padded (odd) row length of the staged Delta
-  FastDiv dPCH;
+  int WQ, ROWS;       // W/4 float4 groups per input row; staged rows per image = TR + KH - 1
+  FastDiv dWQ, dROWS, dNIMG, dPQ; // item decoding (PQ = PCH/4)
   long slot_stride; int slot0; // norm: slots[(slot0 + cblock)*slot_stride + b]
   long part_stride;   // clipped: part[split*part_stride + (d*C + c)*KK + tap]; bias at D*C*KK + d
   ConvTile t;         // XPLANE odd
 };
 
+#define CONV_WG_XV 7  // float4 input items per thread and chunk: 32*NIMG*ROWS*W/4 <= 7*256
+
 // DB = number of 32-row blocks of output channels (D <= 32*DB); the block owns one
-// group of 32 input channels; the KH*KW taps are its N blocks.
+// group of 32 input channels; the KH*KW taps are its N blocks.  W and OW must be
+// multiples of 4: rows are moved as float4 items.  The items of the next K-chunk
+// are fetched into registers while the current chunk is multiplied.
 template <int KH, int KW, int DB>
 __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
   constexpr int KK = KH * KW;
   constexpr int WD = DB >= 4 ? 4 : DB, WN = 4 / WD; // waves along d and along taps
   constexpr int DBW = DB / WD, NBW = (KK + WN - 1) / WN;
+  constexpr int DT = 32 * DB;
+  constexpr int XV = CONV_WG_XV;
+  constexpr int DV = DB == 1 ? 4 : 8;               // float4 Delta items per thread: DT*PCH/4 <= DV*256
+  constexpr int NSL = 256 / DT;                     // row-sum slices
   extern __shared__ float smem[];
   float *Xl = smem;                     // [32][XPLANE]
-  float *Dl = smem + 32 * a.t.XPLANE;   // [32*DB][LDP]
+  float *Dl = smem + 32 * a.t.XPLANE;   // [DT][LDP]
   __shared__ float red[4];
+  __shared__ float rsum[256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
   const int wd = wave / WN, wn = wave - wd * WN;
   const int cb = blockIdx.x, c0 = cb * 32;
@@ -235,6 +245,38 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
   int bbeg, bend;
   if (a.mode == 0) { bbeg = blockIdx.y; bend = bbeg + 1; }
   else { bbeg = blockIdx.y * a.ex_per_block; bend = min(a.B, bbeg + a.ex_per_block); }
+  const int nimg_max = a.mode == 0 ? 1 : a.t.NIMG;
+
+  // zero the staged input once: the left / right halo columns are never written again
+  for (int e = tid; e < 32 * a.t.XPLANE; e += 256) Xl[e] = 0.f;
+
+  // static item descriptors.  Input item it = ((c*NIMG + img)*ROWS + rr)*WQ + q
+  int x_lds[XV], x_goff[XV], x_ir[XV];
+#pragma unroll
+  for (int j = 0; j < XV; ++j) {
+    const int it = tid + j * 256;
+    const int t1 = (int)a.dWQ.div(it), q = it - t1 * a.WQ;
+    const int t2 = (int)a.dROWS.div(t1), rr = t1 - t2 * a.ROWS;
+    const int c = (int)a.dNIMG.div(t2), img = t2 - c * a.t.NIMG;
+    const bool ok = c < 32 && c0 + c < a.C;
+    x_lds[j] = ok ? c * a.t.XPLANE + img * a.t.IMGPL + rr * a.t.LDW + a.pad + 4 * q : -1;
+    x_goff[j] = (img * a.C + c) * HW + (rr - a.pad) * a.W + 4 * q;
+    x_ir[j] = (img << 16) | rr;
+  }
+  // Delta item it = d*PQ + p4: pixels 4*p4..4*p4+3 of the chunk (same output row)
+  const int PQ = a.PCH >> 2;
+  int d_lds[DV], d_goff[DV], d_ir[DV];
+#pragma unroll
+  for (int j = 0; j < DV; ++j) {
+    const int it = tid + j * 256;
+    const int d = (int)a.dPQ.div(it), p = 4 * (it - d * PQ);
+    const int img = (int)a.t.dTROW.div(p), rem = p - img * a.t.TR * a.OW;
+    const int r = (int)a.t.dOW.div(rem);
+    const bool ok = d < DT;
+    d_lds[j] = ok ? d * a.LDP + p : -1;
+    d_goff[j] = (d < a.D) ? (img * a.D + d) * OHW + rem : -1;
+    d_ir[j] = (img << 16) | r;
+  }
 
   f32x16 acc[DBW][NBW];
 #pragma unroll
@@ -243,12 +285,10 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
     for (int j = 0; j < NBW; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  float rowsum = 0.f; // thread d < D of channel group 0: sum_p Delta[d, p] (bias gradient)
+  float rowsum = 0.f; // partial sum_p Delta[d, p] of row tid % DT over this thread's slice (bias gradient)
 
-  // tap offsets of this wave's N blocks (uniform), lane bases
   const int xlane = li * a.t.XPLANE + lk;
   const int dlane = li * a.LDP + lk;
-  const int nimg_max = a.mode == 0 ? 1 : a.t.NIMG;
   int tapoff[NBW];
   bool tapok[NBW];
 #pragma unroll
@@ -259,71 +299,99 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
     tapoff[j] = tapok[j] ? kh * a.t.LDW + kw : 0;
   }
 
-  for (int b = bbeg; b < bend; b += nimg_max) {
-    const int nimg = min(nimg_max, bend - b);
-    for (int rt = 0; rt < a.t.row_tiles; ++rt) {
-      const int r0 = rt * a.t.TR;
-      const int rows = min(a.t.TR, a.OH - r0);
-      __syncthreads();
-      // stage x: 32 channels x nimg images x (rows+KH-1) x LDW with zero halo
-      {
-        const int per_ch = nimg * a.t.IMGPL;
-        for (int e = tid; e < 32 * per_ch; e += 256) {
-          const int c = e / per_ch, rem = e - c * per_ch; // per_ch is uniform: scalar division
-          const int img = (int)a.t.dIMGPL.div(rem), rem2 = rem - img * a.t.IMGPL;
-          const int rr = (int)a.t.dLDW.div(rem2), cc = rem2 - rr * a.t.LDW;
-          const int ih = r0 + rr - a.pad, iw = cc - a.pad;
-          float v = 0.f;
-          if (c0 + c < a.C && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-            v = a.x[((long)(b + img) * a.C + c0 + c) * HW + ih * a.W + iw];
-          Xl[c * a.t.XPLANE + rem] = v;
-        }
-      }
-      // stage Delta (times the clip factor): rows d, columns (img, r, col) of the chunk; pad columns are zero
-      {
-        const int per_img = a.t.TR * a.OW;
-        for (int e = tid; e < 32 * DB * a.PCH; e += 256) {
-          const int d = (int)a.dPCH.div(e), p = e - d * a.PCH;
-          const int img = (int)a.t.dTROW.div(p), rem = p - img * per_img;
-          const int r = (int)a.t.dOW.div(rem);
-          float v = 0.f;
-          if (d < a.D && img < nimg && r < rows) {
-            v = a.delta[((long)(b + img) * a.D + d) * OHW + (long)r0 * a.OW + rem];
-            if (a.scale) v *= a.scale[b + img];
-          }
-          Dl[d * a.LDP + p] = v;
-        }
-      }
-      __syncthreads();
-      if (cb == 0 && tid < a.D) {
-        float s = 0.f;
-        for (int p = 0; p < a.PCH; ++p) s += Dl[tid * a.LDP + p];
-        rowsum += s;
-      }
-      // K loop over pixel pairs of the chunk (OW is even: a pair never straddles a row)
-      for (int img = 0; img < nimg; ++img)
-        for (int r = 0; r < rows; ++r) {
-          const int pbase = (img * a.t.TR + r) * a.OW;
-          const int xbase = img * a.t.IMGPL + r * a.t.LDW;
-          for (int col = 0; col < a.OW; col += 2) {
-            float av[DBW], bv[NBW];
+  float4 xr[XV], dr[DV];
+  auto prefetch = [&](int b, int nimg, int r0, int rows) {
+    const long xb = ((long)b * a.C + c0) * HW + (long)r0 * a.W;
 #pragma unroll
-            for (int i = 0; i < DBW; ++i) av[i] = Dl[dlane + ((wd * DBW + i) * 32) * a.LDP + pbase + col];
-#pragma unroll
-            for (int j = 0; j < NBW; ++j) {
-              bv[j] = Xl[xlane + xbase + col + tapoff[j]];
-              if (!tapok[j]) bv[j] = 0.f;
-            }
-#pragma unroll
-            for (int i = 0; i < DBW; ++i)
-#pragma unroll
-              for (int j = 0; j < NBW; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-          }
-        }
+    for (int j = 0; j < XV; ++j) {
+      const int img = x_ir[j] >> 16, rr = x_ir[j] & 0xffff;
+      const int ih = r0 + rr - a.pad;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (x_lds[j] >= 0 && img < nimg && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H)
+        v = *reinterpret_cast<const float4 *>(a.x + xb + x_goff[j]);
+      xr[j] = v;
     }
+    const long db_ = (long)b * a.D * OHW + (long)r0 * a.OW;
+#pragma unroll
+    for (int j = 0; j < DV; ++j) {
+      const int img = d_ir[j] >> 16, r = d_ir[j] & 0xffff;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (d_goff[j] >= 0 && img < nimg && r < rows) {
+        v = *reinterpret_cast<const float4 *>(a.delta + db_ + d_goff[j]);
+        if (a.scale) { const float s = a.scale[b + img]; v.x *= s; v.y *= s; v.z *= s; v.w *= s; }
+      }
+      dr[j] = v;
+    }
+  };
+
+  const int n_chunks = ((bend - bbeg + nimg_max - 1) / nimg_max) * a.t.row_tiles;
+  int cb_b = bbeg, cb_rt = 0; // chunk being fetched
+  if (n_chunks > 0) prefetch(cb_b, min(nimg_max, bend - cb_b), 0, min(a.t.TR, a.OH));
+  for (int ci = 0; ci < n_chunks; ++ci) {
+    const int b = cb_b, r0 = cb_rt * a.t.TR;
+    const int nimg = min(nimg_max, bend - b), rows = min(a.t.TR, a.OH - r0);
+    __syncthreads(); // previous chunk consumed
+#pragma unroll
+    for (int j = 0; j < XV; ++j)
+      if (x_lds[j] >= 0) {
+        float *d = Xl + x_lds[j];
+        d[0] = xr[j].x; d[1] = xr[j].y; d[2] = xr[j].z; d[3] = xr[j].w;
+      }
+#pragma unroll
+    for (int j = 0; j < DV; ++j)
+      if (d_lds[j] >= 0) {
+        float *d = Dl + d_lds[j];
+        d[0] = dr[j].x; d[1] = dr[j].y; d[2] = dr[j].z; d[3] = dr[j].w;
+      }
+    __syncthreads();
+    // advance to the next chunk and start fetching it
+    if (++cb_rt == a.t.row_tiles) { cb_rt = 0; cb_b += nimg_max; }
+    if (ci + 1 < n_chunks) {
+      const int r0n = cb_rt * a.t.TR;
+      prefetch(cb_b, min(nimg_max, bend - cb_b), r0n, min(a.t.TR, a.OH - r0n));
+    }
+    if (cb == 0) { // bias gradient: row sums of the staged Delta, NSL slices per row
+      const int d = tid % DT, sl = tid / DT;
+      const int per = (a.PCH + NSL - 1) / NSL;
+      const int p1 = min(a.PCH, (sl + 1) * per);
+      float s = 0.f;
+      for (int p = sl * per; p < p1; ++p) s += Dl[d * a.LDP + p];
+      rowsum += s;
+    }
+    // K loop over pixel pairs of the chunk (OW is even: a pair never straddles a row)
+    for (int img = 0; img < nimg; ++img)
+      for (int r = 0; r < rows; ++r) {
+        const int pbase = (img * a.t.TR + r) * a.OW;
+        const int xbase = img * a.t.IMGPL + r * a.t.LDW;
+#pragma unroll 4
+        for (int col = 0; col < a.OW; col += 2) {
+          float av[DBW], bv[NBW];
+#pragma unroll
+          for (int i = 0; i < DBW; ++i) av[i] = Dl[dlane + ((wd * DBW + i) * 32) * a.LDP + pbase + col];
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) {
+            bv[j] = Xl[xlane + xbase + col + tapoff[j]];
+            if (!tapok[j]) bv[j] = 0.f;
+          }
+#pragma unroll
+          for (int i = 0; i < DBW; ++i)
+#pragma unroll
+            for (int j = 0; j < NBW; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+      }
   }
 
+  // bias gradient: combine the slices
+  float bias_d = 0.f;
+  if (cb == 0) {
+    rsum[tid] = rowsum;
+    __syncthreads();
+    if (tid < DT) {
+#pragma unroll
+      for (int s = 0; s < NSL; ++s) bias_d += rsum[s * DT + tid];
+    }
+  }
   // accumulator: lane column = input channel c0 + li; rows = output channels
   const int c = c0 + li;
   if (a.mode == 0) {
@@ -339,7 +407,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
           if (tap < KK && c < a.C && d < a.D) part += acc[i][j][r] * acc[i][j][r];
         }
       }
-    if (cb == 0 && tid < a.D) part += rowsum * rowsum;
+    if (cb == 0 && tid < a.D) part += bias_d * bias_d;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
     if (lane == 0) red[wave] = part;
@@ -358,6 +426,6 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
           if (tap < KK && c < a.C && d < a.D) part[((long)d * a.C + c) * KK + tap] = acc[i][j][r];
         }
       }
-    if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = rowsum;
+    if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = bias_d;
   }
 }

@@ -115,6 +115,7 @@ struct Layer {
   float *g = nullptr; // gradient w.r.t. pre-activation (w.r.t. output where the layer has no activation)
   uint8_t *arg = nullptr;
   float *part = nullptr; // split-K partials of the clipped sum [max_split][p_count]
+  float *fpart = nullptr; int fsplit = 1; // dense forward: split-K partials [fsplit][maxB*d_out] when the output is small
   int max_split = 0;
   int max_slots = 0;
   ConvGeom geom;
@@ -243,7 +244,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
         CONV_CC * l.t_bwd.XPLANE <= CONV_XCNT * 256) { l.dir_bwd = true; l.bwd_npw = npw; }
   }
   // weight gradient
-  if (g.C >= 16 && g.D <= 128 && (g.OW & 1) == 0) {
+  if (g.C >= 16 && g.D <= 128 && (g.OW & 3) == 0 && (g.W & 3) == 0) {
     int db = g.D <= 32 ? 1 : (g.D <= 64 ? 2 : 4);
     int pch_max = db <= 2 ? 128 : 64;
     bool ok = make_conv_tile(l.t_wgn, g.OH, g.OW, 3, 3, pch_max, true, 1) &&
@@ -251,7 +252,14 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
     if (ok) {
       long lds_n = 32l * l.t_wgn.XPLANE + 32l * db * ((l.t_wgn.NIMG * l.t_wgn.TR * g.OW) | 1);
       long lds_c = 32l * l.t_wgc.XPLANE + 32l * db * ((l.t_wgc.NIMG * l.t_wgc.TR * g.OW) | 1);
-      if (lds_n * 4 <= 64 * 1024 && lds_c * 4 <= 64 * 1024) { l.dir_wg = true; l.wg_db = db; }
+      bool fits = lds_n * 4 <= 64 * 1024 && lds_c * 4 <= 64 * 1024;
+      for (const ConvTile *t : {&l.t_wgn, &l.t_wgc}) {
+        const int pch = t->NIMG * t->TR * g.OW;
+        if (32l * t->NIMG * (t->TR + 2) * (g.W / 4) > CONV_WG_XV * 256) fits = false; // input items per thread
+        if (32l * db * pch / 4 > (db == 1 ? 4 : 8) * 256) fits = false;               // Delta items per thread
+        if ((pch & 3) != 0) fits = false;
+      }
+      if (fits) { l.dir_wg = true; l.wg_db = db; }
     }
   }
 }
@@ -293,7 +301,9 @@ static ConvWgArgs make_wg_args(const Layer &l, const float *x, int B, const Conv
   ConvWgArgs a{};
   a.x = x; a.delta = l.g; a.B = B; a.C = g.C; a.H = g.H; a.W = g.W; a.D = g.D; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
   a.t = t;
-  a.PCH = t.NIMG * t.TR * g.OW; a.LDP = a.PCH | 1; a.dPCH.init(a.PCH);
+  a.PCH = t.NIMG * t.TR * g.OW; a.LDP = a.PCH | 1;
+  a.WQ = g.W / 4; a.ROWS = t.TR + 2;
+  a.dWQ.init(a.WQ); a.dROWS.init(a.ROWS); a.dNIMG.init(t.NIMG); a.dPQ.init(a.PCH / 4);
   return a;
 }
 
@@ -405,6 +415,18 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       }
       rc = dev_alloc(c, &l.part, (size_t)l.max_split * l.p_count);
     }
+    if (rc == DP_OK && l.d.kind == DP_DENSE) {
+      // a small output with a long K would leave most CUs idle and expose every load's latency: split K
+      GemmShape sh = pick_tile(max_batch, l.d.out_features, 1);
+      long tiles = (long)sh.tiles_m * sh.tiles_n;
+      int by_k = l.d.in_features / 64;
+      if (tiles < 512 && by_k >= 2) {
+        long want = (1024 + tiles - 1) / tiles;
+        l.fsplit = (int)(want < by_k ? want : by_k);
+        if (l.fsplit > 64) l.fsplit = 64;
+        rc = dev_alloc(c, &l.fpart, (size_t)l.fsplit * mb * l.out_size);
+      }
+    }
     if (rc == DP_OK && (l.dir_fwd || l.dir_bwd)) {
       rc = dev_alloc(c, &l.wt_f, (size_t)l.geom.D * l.geom.CKK);
       if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, (size_t)l.geom.D * l.geom.CKK);
@@ -491,6 +513,25 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       const float *W = params + l.p_off;
       switch (l.d.kind) {
       case DP_DENSE: {
+        if (l.fsplit > 1) {
+          typedef ProbPartial<OpRowMajor, OpKMajor> Pb;
+          Pb p{};
+          p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
+          p.a.ptr = in; p.a.zstride = 0; p.a.ld = l.d.in_features;
+          p.b.ptr = W; p.b.zstride = 0; p.b.ld = l.d.out_features; p.b.scale = nullptr; p.b.scale_div.init(1);
+          p.b.ones_row = 0; p.b.by_z = 0;
+          const long stride = (long)c->maxB * l.out_size;
+          p.part = l.fpart; p.stride = stride; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
+          const int ns = launch_gemm_split(p, l.fsplit, Ln, "dense_fwd");
+          const long total = (long)B * l.out_size;
+          dim3 grid = grid1d(total, 256), block(256);
+          const float *bias = W + (long)l.d.in_features * l.d.out_features;
+          Ln("dense_fwd_epilogue", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(bias_act_reduce_kernel, grid, block, 0, st, (const float *)l.fpart, ns, stride, bias,
+                               l.d.act, l.a, total, l.d.out_features);
+          });
+          break;
+        }
         typedef ProbBiasAct<OpRowMajor, OpKMajor> Pb;
         Pb p{};
         p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
@@ -707,7 +748,10 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         if (l.dir_wg) {
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc);
           const int cblocks = ceil_div(g.C, 32);
-          int want = ceil_div(1024, cblocks);
+          // one full round of resident workgroups (256 CUs x workgroups per CU) avoids a ragged tail
+          const int occ = l.wg_db == 1 ? 3 : (l.wg_db == 2 ? 2 : 1);
+          int want = (256 * occ) / cblocks;
+          if (want < 1) want = 1;
           if (want > l.max_split) want = l.max_split;
           int epb = ceil_div(B, want);
           epb = ceil_div(epb, a.t.NIMG) * a.t.NIMG;

@@ -108,6 +108,19 @@ __global__ void clip_factor_kernel(const float *__restrict__ slots, int n_slots,
   s[b] = fminf(1.f, C / n); // n == 0: C/0 = +inf -> 1
 }
 
+// out[i] = act(sum_s part[s*stride + i] + bias[i % N]): epilogue of a split-K dense forward
+__global__ void bias_act_reduce_kernel(const float *__restrict__ part, int nsplit, long stride,
+                                       const float *__restrict__ bias, int act, float *__restrict__ out, long total,
+                                       int N) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  float a0 = 0.f, a1 = 0.f;
+  int s = 0;
+  for (; s + 1 < nsplit; s += 2) { a0 += part[s * stride + i]; a1 += part[(s + 1) * stride + i]; }
+  if (s < nsplit) a0 += part[s * stride + i];
+  out[i] = act_apply(act, a0 + a1 + bias[i % N]);
+}
+
 __global__ void fill_zero_kernel(float *__restrict__ p, long n) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0.f;
