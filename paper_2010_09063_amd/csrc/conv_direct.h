@@ -159,25 +159,29 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
     }
     __syncthreads();
     if (c0 + CC < a.Cin) prefetch(c0 + CC); // in flight while this chunk is multiplied
+    // (channel pair, tap) steps; the LDS operands of step s+1 are read before the MFMAs of step s
+    {
+      constexpr int NS = (CC / 2) * KK;
+      float av[2][DB], bv[2][PB];
+      auto ld = [&](int s, float *pa, float *pb) {
+        const int cp = s / KK, tap = s - cp * KK, kh = tap / KW, kw = tap - kh * KW;
+        const int wrow = ((2 * cp + lk) * KK + tap) * DT;
 #pragma unroll
-    for (int cp = 0; cp < CC / 2; ++cp) {
+        for (int i = 0; i < DB; ++i) pa[i] = Wl[wrow + i * 32 + li];
+        const int xo = 2 * cp * a.t.XPLANE + kh * a.t.LDW + kw;
 #pragma unroll
-      for (int kh = 0; kh < KH; ++kh)
+        for (int j = 0; j < PB; ++j) pb[j] = Xl[xoff[j] + xo];
+      };
+      ld(0, av[0], bv[0]);
 #pragma unroll
-        for (int kw = 0; kw < KW; ++kw) {
-          float av[DB], bv[PB];
-          const int wrow = ((2 * cp + lk) * KK + kh * KW + kw) * DT;
+      for (int s = 0; s < NS; ++s) {
+        if (s + 1 < NS) ld(s + 1, av[(s + 1) & 1], bv[(s + 1) & 1]);
 #pragma unroll
-          for (int i = 0; i < DB; ++i) av[i] = Wl[wrow + i * 32 + li];
-          const int xo = 2 * cp * a.t.XPLANE + kh * a.t.LDW + kw;
+        for (int i = 0; i < DB; ++i)
 #pragma unroll
-          for (int j = 0; j < PB; ++j) bv[j] = Xl[xoff[j] + xo];
-#pragma unroll
-          for (int i = 0; i < DB; ++i)
-#pragma unroll
-            for (int j = 0; j < PB; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
+          for (int j = 0; j < PB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s & 1][i], bv[s & 1][j], acc[i][j], 0, 0, 0);
+      }
     }
   }
 

@@ -14,9 +14,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kernels_misc.h"
+
 #define LSTM_NE 2
 
-__device__ __forceinline__ float sigmoidf_(float v) { return 1.f / (1.f + expf(-v)); }
+__device__ __forceinline__ float sigmoidf_(float v) { return fast_sigmoid(v); }
 
 // Forward.  gates: in  x_t W_ih + b for every (b, t); out activated i, f, g, o.
 // hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T.
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void lstm_fwd_kernel(float *__restrict__ gates
 #pragma unroll
       for (int e = 0; e < LSTM_NE; ++e) {
         const float v0 = sigmoidf_(acc[e][0]);
-        const float v1 = c1_is_g ? tanhf(acc[e][1]) : sigmoidf_(acc[e][1]);
+        const float v1 = c1_is_g ? fast_tanh(acc[e][1]) : sigmoidf_(acc[e][1]);
         gact[e][c0] = v0; gact[e][c1] = v1;
         if (b0 + e < B) {
           gates[((long)(b0 + e) * T + t) * G + c0] = v0;
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(256) void lstm_fwd_kernel(float *__restrict__ gates
     if (upd_thread) {
       const float gi = gact[ue][ur], gf = gact[ue][H + ur], gg = gact[ue][2 * H + ur], go = gact[ue][3 * H + ur];
       c_reg = gf * c_reg + gi * gg;
-      const float h = go * tanhf(c_reg);
+      const float h = go * fast_tanh(c_reg);
       h_s[ue][ur] = h;
       const long o = ((long)(b0 + ue) * T + t) * H + ur;
       hs[o] = h; cs[o] = c_reg;
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_kernel(float *__restrict__ gates
   for (int t = T - 1; t >= 0; --t) {
     if (upd_thread) {
       const float dh = (t == T - 1) ? dh_last[ub * H + ur] : part_s[ue][0][ur] + part_s[ue][1][ur];
-      const float tc = tanhf(ct);
+      const float tc = fast_tanh(ct);
       const float dct = dc + dh * go * (1.f - tc * tc);
       const float d_o = dh * tc * go * (1.f - go);
       const float d_i = dct * gg * gi * (1.f - gi);
