@@ -517,9 +517,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           typedef ProbPartial<OpRowMajor, OpKMajor> Pb;
           Pb p{};
           p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
-          p.a.ptr = in; p.a.zstride = 0; p.a.ld = l.d.in_features;
-          p.b.ptr = W; p.b.zstride = 0; p.b.ld = l.d.out_features; p.b.scale = nullptr; p.b.scale_div.init(1);
-          p.b.ones_row = 0; p.b.by_z = 0;
+          p.a.set(in, l.d.in_features);
+          p.b.set(W, l.d.out_features);
           const long stride = (long)c->maxB * l.out_size;
           p.part = l.fpart; p.stride = stride; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
           const int ns = launch_gemm_split(p, l.fsplit, Ln, "dense_fwd");
@@ -535,9 +534,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         typedef ProbBiasAct<OpRowMajor, OpKMajor> Pb;
         Pb p{};
         p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
-        p.a.ptr = in; p.a.zstride = 0; p.a.ld = l.d.in_features;
-        p.b.ptr = W; p.b.zstride = 0; p.b.ld = l.d.out_features; p.b.scale = nullptr; p.b.scale_div.init(1);
-        p.b.ones_row = 0; p.b.by_z = 0;
+        p.a.set(in, l.d.in_features);
+        p.b.set(W, l.d.out_features);
         p.out = l.a; p.bias = W + (long)l.d.in_features * l.d.out_features; p.ld = l.d.out_features; p.act = l.d.act;
         launch_gemm(p, 1, Ln, "dense_fwd");
       } break;
@@ -563,7 +561,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         Pb p{};
         const ConvGeom &g = l.geom;
         p.M = g.D; p.N = B * g.P; p.K = g.CKK;
-        p.a.ptr = W; p.a.zstride = 0; p.a.ld = g.CKK;
+        p.a.set(W, g.CKK);
         p.b.x = in; p.b.g = g; p.b.has_ones = 0; p.b.by_z = 0;
         p.out = l.a; p.bias = W + (long)g.D * g.CKK; p.D = g.D; p.P = g.P; p.act = l.d.act; p.dP = g.dP;
         launch_gemm(p, 1, Ln, "conv_fwd");
@@ -584,8 +582,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         typedef ProbBiasAct<OpGatherRows, OpKMajor> Pb;
         Pb p{};
         p.M = B * l.T; p.N = G; p.K = l.Din;
-        p.a.table = E; p.a.idx = (const int *)x; p.a.ld = l.Din;
-        p.b.ptr = W; p.b.zstride = 0; p.b.ld = G; p.b.scale = nullptr; p.b.scale_div.init(1); p.b.ones_row = 0; p.b.by_z = 0;
+        p.a.set(E, (const int *)x, l.Din);
+        p.b.set(W, G);
         p.out = l.gates; p.bias = W + (long)l.Din * G + (long)l.H * G; p.ld = G; p.act = DP_ACT_NONE;
         launch_gemm(p, 1, Ln, "lstm_xproj");
         const float *Whh = W + (long)l.Din * G;
@@ -625,8 +623,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           typedef ProbBwdAct<OpRowMajor, OpRowMajor> Pb;
           Pb p{};
           p.M = B; p.N = l.d.in_features; p.K = l.d.out_features;
-          p.a.ptr = l.g; p.a.zstride = 0; p.a.ld = l.d.out_features;
-          p.b.ptr = W; p.b.zstride = 0; p.b.ld = l.d.out_features;
+          p.a.set(l.g, l.d.out_features);
+          p.b.set(W, l.d.out_features);
           p.out = prev->g; p.a_prev = prev->a; p.ld = l.d.in_features; p.act = prev_act;
           launch_gemm(p, 1, Ln, "dense_bwd_data");
         }
@@ -643,7 +641,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           typedef ProbSqNorm<OpRowMajor, OpConvPatch<false>> Pb;
           Pb p{};
           p.M = g.D; p.N = g.CKK + 1; p.K = g.P;
-          p.a.ptr = l.g; p.a.zstride = (long)g.D * g.P; p.a.ld = g.P;
+          p.a.set(l.g, g.P, (long)g.D * g.P);
           p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 1;
           p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
           GemmShape s = launch_gemm(p, B, Ln, "conv_wgrad_norm");
@@ -682,10 +680,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           typedef ProbSqNorm<OpLstmIn, OpKMajor> Pb;
           Pb p{};
           p.M = l.Din + l.H + 1; p.N = G; p.K = l.T;
-          p.a.table = params + prev->p_off; p.a.tok = (const int *)x; p.a.xin = nullptr; p.a.hs = l.hs;
-          p.a.scale = nullptr; p.a.Din = l.Din; p.a.H = l.H; p.a.T = l.T; p.a.by_z = 1; p.a.dT.init(l.T);
-          p.b.ptr = l.gates; p.b.zstride = (long)l.T * G; p.b.ld = G; p.b.scale = nullptr; p.b.scale_div.init(1);
-          p.b.ones_row = 0; p.b.by_z = 1;
+          p.a.set(params + prev->p_off, (const int *)x, l.hs, nullptr, l.Din, l.H, l.T, 1);
+          p.b.set(l.gates, G, (long)l.T * G); p.b.by_z = 1;
           p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
           GemmShape s = launch_gemm(p, B, Ln, "lstm_wgrad_norm");
           slot_next += s.tiles_m * s.tiles_n;
@@ -694,8 +690,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           typedef ProbBwdAct<OpRowMajor, OpRowMajor> Pb;
           Pb p{};
           p.M = B * l.T; p.N = l.Din; p.K = G;
-          p.a.ptr = l.gates; p.a.zstride = 0; p.a.ld = G;
-          p.b.ptr = W; p.b.zstride = 0; p.b.ld = G;
+          p.a.set(l.gates, G);
+          p.b.set(W, G);
           p.out = prev->g; p.a_prev = nullptr; p.ld = l.Din; p.act = DP_ACT_NONE;
           launch_gemm(p, 1, Ln, "lstm_dx");
         }
@@ -736,10 +732,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         typedef ProbPartial<OpKMajor, OpKMajor> Pb;
         Pb p{};
         p.M = l.d.in_features + 1; p.N = l.d.out_features; p.K = B;
-        p.a.ptr = lin; p.a.zstride = 0; p.a.ld = l.d.in_features; p.a.scale = sc; p.a.scale_div.init(1);
-        p.a.ones_row = 1; p.a.by_z = 0;
-        p.b.ptr = l.g; p.b.zstride = 0; p.b.ld = l.d.out_features; p.b.scale = nullptr; p.b.scale_div.init(1);
-        p.b.ones_row = 0; p.b.by_z = 0;
+        p.a.set(lin, l.d.in_features); p.a.scale = sc; p.a.ones_row = 1;
+        p.b.set(l.g, l.d.out_features);
         p.part = l.part; p.stride = l.p_count; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
         nsplit = launch_gemm_split(p, l.max_split, Ln, "dense_clipped_sum");
       } break;
@@ -773,10 +767,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         typedef ProbPartial<OpLstmIn, OpKMajor> Pb;
         Pb p{};
         p.M = l.Din + l.H + 1; p.N = G; p.K = B * l.T;
-        p.a.table = params + c->L[i - 1].p_off; p.a.tok = (const int *)x; p.a.xin = nullptr; p.a.hs = l.hs;
-        p.a.scale = sc; p.a.Din = l.Din; p.a.H = l.H; p.a.T = l.T; p.a.by_z = 0; p.a.dT.init(l.T);
-        p.b.ptr = l.gates; p.b.zstride = 0; p.b.ld = G; p.b.scale = nullptr; p.b.scale_div.init(1);
-        p.b.ones_row = 0; p.b.by_z = 0;
+        p.a.set(params + c->L[i - 1].p_off, (const int *)x, l.hs, sc, l.Din, l.H, l.T, 0);
+        p.b.set(l.gates, G);
         p.part = l.part; p.stride = l.p_count; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
         nsplit = launch_gemm_split(p, l.max_split, Ln, "lstm_clipped_sum");
       } break;

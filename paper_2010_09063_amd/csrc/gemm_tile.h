@@ -10,7 +10,7 @@
 // im2col patches, gathered embedding rows, [x; h; 1] LSTM inputs and the clip
 // factor s_i are applied while the tile is staged into LDS and never written out.
 //
-// Tile: BM x BN x 16, WM x WN wavefronts of 64 lanes; each wave owns a
+// Tile: BM x BN x 32, WM x WN wavefronts of 64 lanes; each wave owns a
 // (BM/WM) x (BN/WN) sub-tile made of 32x32 blocks of v_mfma_f32_32x32x2_f32.
 // LDS holds A and B tiles k-major (tile[k][row]) so the MFMA operand read
 // (32 consecutive rows for one k) is conflict-free; rows are padded by 2 words
@@ -38,23 +38,33 @@ struct FastDiv {
 
 template <int BM_, int BN_, int WM_, int WN_>
 struct TileCfg {
-  static constexpr int BM = BM_, BN = BN_, BK = 16, WM = WM_, WN = WN_;
+  static constexpr int BM = BM_, BN = BN_, BK = 32, WM = WM_, WN = WN_;
   static constexpr int THREADS = 64 * WM * WN;
   static constexpr int TM = BM / WM, TN = BN / WN; // wave sub-tile
   static constexpr int MB = TM / 32, NB = TN / 32; // 32x32 MFMA blocks per wave
-  static constexpr int LDA = BM + 2, LDB = BN + 2;
   static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(THREADS % BK == 0 && THREADS % BM == 0 && THREADS % BN == 0, "loader mapping");
   static_assert((BM * BK) % THREADS == 0 && (BN * BK) % THREADS == 0, "loader mapping");
 };
 
-// Stages one operand tile (ROWS x BK) from its functor into registers and LDS.
-template <class Op, int ROWS, int LD, int THREADS, int BK, bool LANES_K = Op::kLanesAlongK>
+DEVI float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+
+// Stages one operand tile (ROWS x BK) from its functor into registers, then into LDS
+// laid out k-major: tile[k*LD + row].  Four variants: lanes walk k or the fixed
+// dimension (whichever is contiguous in memory), one float or one float4 per item.
+enum { LOAD_SCALAR_K = 0, LOAD_SCALAR_F = 1, LOAD_VEC_K = 2, LOAD_VEC_F = 3 };
+template <class Op>
+struct LoaderKind {
+  static constexpr int value = Op::kVec ? (Op::kLanesAlongK ? LOAD_VEC_K : LOAD_VEC_F)
+                                        : (Op::kLanesAlongK ? LOAD_SCALAR_K : LOAD_SCALAR_F);
+};
+template <class Op, int ROWS, int THREADS, int BK, int KIND = LoaderKind<Op>::value>
 struct TileLoader;
 
 // lanes run along k: a thread owns one k of the tile and CNT fixed rows
-template <class Op, int ROWS, int LD, int THREADS, int BK>
-struct TileLoader<Op, ROWS, LD, THREADS, BK, true> {
+template <class Op, int ROWS, int THREADS, int BK>
+struct TileLoader<Op, ROWS, THREADS, BK, LOAD_SCALAR_K> {
+  static constexpr int LD = ROWS + 2;
   static constexpr int CNT = ROWS * BK / THREADS, RSTEP = THREADS / BK;
   typename Op::FC fc[CNT];
   float r[CNT];
@@ -77,8 +87,9 @@ struct TileLoader<Op, ROWS, LD, THREADS, BK, true> {
 };
 
 // lanes run along the fixed dimension: a thread owns one row and CNT k's of the tile
-template <class Op, int ROWS, int LD, int THREADS, int BK>
-struct TileLoader<Op, ROWS, LD, THREADS, BK, false> {
+template <class Op, int ROWS, int THREADS, int BK>
+struct TileLoader<Op, ROWS, THREADS, BK, LOAD_SCALAR_F> {
+  static constexpr int LD = ROWS + 2;
   static constexpr int CNT = ROWS * BK / THREADS, KSTEP = THREADS / ROWS;
   typename Op::FC fc;
   float r[CNT];
@@ -101,18 +112,79 @@ struct TileLoader<Op, ROWS, LD, THREADS, BK, false> {
   }
 };
 
+// float4 along k (k-contiguous operand): a thread owns one group of 4 k's and CNT rows;
+// the store into the k-major tile transposes (4 scalar LDS writes per item)
+template <class Op, int ROWS, int THREADS, int BK>
+struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_K> {
+  static constexpr int LD = ROWS + 2;
+  static constexpr int KG = BK / 4, RSTEP = THREADS / KG, CNT = ROWS / RSTEP;
+  static_assert(ROWS % RSTEP == 0 && CNT >= 1, "vec-k loader mapping");
+  typename Op::FC fc[CNT];
+  float4 r[CNT];
+  int kg, r0;
+  DEVI void init(const Op &op, int z, int row0, int nrows) {
+    kg = threadIdx.x % KG;
+    r0 = threadIdx.x / KG;
+#pragma unroll
+    for (int j = 0; j < CNT; ++j) fc[j] = op.fctx(z, row0 + r0 + j * RSTEP, nrows);
+  }
+  DEVI void fetch(const Op &op, int z, int k0, int kend) {
+    typename Op::KC4 kc = op.kctx4(z, k0 + 4 * kg, kend);
+#pragma unroll
+    for (int j = 0; j < CNT; ++j) r[j] = op.load4(fc[j], kc);
+  }
+  DEVI void stash(float *tile) const {
+#pragma unroll
+    for (int j = 0; j < CNT; ++j) {
+      float *d = tile + (4 * kg) * LD + r0 + j * RSTEP;
+      d[0] = r[j].x; d[LD] = r[j].y; d[2 * LD] = r[j].z; d[3 * LD] = r[j].w;
+    }
+  }
+};
+
+// float4 along the fixed dimension (f-contiguous operand): a thread owns one group of
+// 4 rows and CNT k's; one 16-byte LDS write per item
+template <class Op, int ROWS, int THREADS, int BK>
+struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_F> {
+  static constexpr int LD = ROWS + 4;
+  static constexpr int FG = ROWS / 4, KSTEP = THREADS / FG, CNT = BK / KSTEP;
+  static_assert(THREADS % FG == 0 && BK % KSTEP == 0 && CNT >= 1, "vec-f loader mapping");
+  typename Op::FC4 fc;
+  float4 r[CNT];
+  int fg, kq;
+  DEVI void init(const Op &op, int z, int row0, int nrows) {
+    fg = threadIdx.x % FG;
+    kq = threadIdx.x / FG;
+    fc = op.fctx4(z, row0 + 4 * fg, nrows);
+  }
+  DEVI void fetch(const Op &op, int z, int k0, int kend) {
+#pragma unroll
+    for (int j = 0; j < CNT; ++j) {
+      typename Op::KC kc = op.kctx(z, k0 + kq + j * KSTEP, kend);
+      r[j] = op.load4(fc, kc);
+    }
+  }
+  DEVI void stash(float *tile) const {
+#pragma unroll
+    for (int j = 0; j < CNT; ++j)
+      *reinterpret_cast<float4 *>(tile + (kq + j * KSTEP) * LD + 4 * fg) = r[j];
+  }
+};
+
 // Problem P provides:
-//   int M, N, K, k_chunk (multiple of 16), tiles_n;
-//   A a; B b;               operand functors (FC, KC, fctx, kctx, load, kLanesAlongK)
+//   int M, N, K, k_chunk (multiple of 32), tiles_n;
+//   A a; B b;               operand functors (kLanesAlongK, kVec; FC/KC contexts, load or load4)
 //   static constexpr bool kReduce;
 //   kReduce == false:  void store(int z, int split, int m, int n, float acc) const;
 //   kReduce == true:   float contrib(int z, int m, int n, float acc) const;
 //                      void store_tile(int z, int tile, float sum) const;
 template <class Cfg, class P>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
-  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LDA = Cfg::LDA, LDB = Cfg::LDB;
-  __shared__ float As[BK * LDA];
-  __shared__ float Bs[BK * LDB];
+  typedef TileLoader<typename P::A, Cfg::BM, Cfg::THREADS, Cfg::BK> LoadA;
+  typedef TileLoader<typename P::B, Cfg::BN, Cfg::THREADS, Cfg::BK> LoadB;
+  constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, LDA = LoadA::LD, LDB = LoadB::LD;
+  __shared__ __attribute__((aligned(16))) float As[BK * LDA];
+  __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
   __shared__ float red[Cfg::WM * Cfg::WN];
 
   const int z = blockIdx.z, split = blockIdx.y;
@@ -122,8 +194,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
   const int kbeg = split * p.k_chunk;
   const int kend = min(p.K, kbeg + p.k_chunk);
 
-  TileLoader<typename P::A, BM, LDA, Cfg::THREADS, BK> la;
-  TileLoader<typename P::B, BN, LDB, Cfg::THREADS, BK> lb;
+  LoadA la;
+  LoadB lb;
   la.init(p.a, z, m0, p.M);
   lb.init(p.b, z, n0, p.N);
 
@@ -252,7 +324,7 @@ static inline void launch_gemm_shape(P p, GemmShape s, int batch, int splits, La
 template <class P, class Launcher>
 static inline GemmShape launch_gemm(P p, int batch, Launcher &&L, const char *label) {
   GemmShape s = pick_tile(p.M, p.N, batch);
-  p.k_chunk = (p.K + 15) / 16 * 16;
+  p.k_chunk = (p.K + 31) / 32 * 32;
   launch_gemm_shape(p, s, batch, 1, L, label);
   return s;
 }
@@ -267,7 +339,7 @@ static inline int launch_gemm_split(P p, int max_split, Launcher &&L, const char
   long tiles = (long)s.tiles_m * s.tiles_n;
   long want = (1024 + tiles - 1) / tiles;
   int nsplit = (int)(want < by_k ? want : by_k);
-  p.k_chunk = ceil_div(ceil_div(p.K, nsplit), 16) * 16;
+  p.k_chunk = ceil_div(ceil_div(p.K, nsplit), 32) * 32;
   nsplit = ceil_div(p.K, p.k_chunk);
   launch_gemm_shape(p, s, 1, nsplit, L, label);
   return nsplit;

@@ -9,36 +9,66 @@
 #include "gemm_tile.h"
 
 // ---------------------------------------------------------------- plain matrices
+//
+// Vector operands (kVec) are staged as float4 items along their contiguous
+// dimension: kctx4 / fctx4 give the context of a group of four consecutive
+// indices (first index a multiple of 4) and load4 returns the four elements.
+// `vec` is set on the host when base pointer, leading dimension and batch
+// stride keep every group 16-byte aligned; otherwise load4 falls back to four
+// guarded scalar loads.
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // element (f, k) = ptr[z*zstride + f*ld + k]            (k contiguous)
 struct OpRowMajor {
-  static constexpr bool kLanesAlongK = true;
+  static constexpr bool kLanesAlongK = true, kVec = true;
   const float *ptr;
   long zstride;
-  int ld;
+  int ld, vec;
+  void set(const float *p, int ld_, long zs = 0) {
+    ptr = p; ld = ld_; zstride = zs;
+    vec = aligned16(p) && (ld_ & 3) == 0 && (zs & 3) == 0;
+  }
   struct FC { const float *row; };
-  struct KC { int k; };
+  struct KC4 { int k, n; };
   DEVI FC fctx(int z, int f, int F) const {
     FC c; c.row = f < F ? ptr + z * zstride + (long)f * ld : nullptr; return c;
   }
-  DEVI KC kctx(int, int k, int kend) const { KC c; c.k = k < kend ? k : -1; return c; }
-  DEVI float load(const FC &f, const KC &k) const { return (f.row && k.k >= 0) ? f.row[k.k] : 0.f; }
+  DEVI KC4 kctx4(int, int k, int kend) const { KC4 c; c.k = k; c.n = min(4, kend - k); return c; }
+  DEVI float4 load4(const FC &f, const KC4 &k) const {
+    if (!f.row || k.n <= 0) return f4zero();
+    if (vec && k.n == 4) return *reinterpret_cast<const float4 *>(f.row + k.k);
+    float4 v = f4zero();
+    v.x = f.row[k.k];
+    if (k.n > 1) v.y = f.row[k.k + 1];
+    if (k.n > 2) v.z = f.row[k.k + 2];
+    if (k.n > 3) v.w = f.row[k.k + 3];
+    return v;
+  }
 };
 
 // element (f, k) = ptr[z*zstride + k*ld + f] * scale[k / scale_div]    (f contiguous);
 // with ones_row, f == F-1 is a row of ones (times the scale): the bias column.
 struct OpKMajor {
-  static constexpr bool kLanesAlongK = false;
+  static constexpr bool kLanesAlongK = false, kVec = true;
   const float *ptr;
   long zstride;
-  int ld;
+  int ld, vec;
   const float *scale; // nullable; indexed by z when by_z, else by k / scale_div
   FastDiv scale_div;
   int ones_row, by_z;
-  struct FC { int f; int one; };
+  void set(const float *p, int ld_, long zs = 0) {
+    ptr = p; ld = ld_; zstride = zs; scale = nullptr; scale_div.init(1); ones_row = 0; by_z = 0;
+    vec = aligned16(p) && (ld_ & 3) == 0 && (zs & 3) == 0;
+  }
+  struct FC4 { int f, n, one; }; // n real rows in the group, index of the ones row within it (or -1)
   struct KC { const float *row; float s; };
-  DEVI FC fctx(int, int f, int F) const {
-    FC c; c.one = (ones_row && f == F - 1); c.f = (f < F && !c.one) ? f : -1; return c;
+  DEVI FC4 fctx4(int, int f, int F) const {
+    FC4 c; c.f = f;
+    const int real = F - (ones_row ? 1 : 0);
+    c.n = max(0, min(4, real - f));
+    c.one = (ones_row && F - 1 >= f && F - 1 < f + 4) ? F - 1 - f : -1;
+    return c;
   }
   DEVI KC kctx(int z, int k, int kend) const {
     KC c;
@@ -48,26 +78,44 @@ struct OpKMajor {
     } else { c.row = nullptr; c.s = 0.f; }
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    if (!k.row) return 0.f;
-    if (f.one) return k.s;
-    return f.f >= 0 ? k.row[f.f] * k.s : 0.f;
+  DEVI float4 load4(const FC4 &f, const KC &k) const {
+    if (!k.row) return f4zero();
+    float4 v;
+    if (vec && f.n == 4) v = *reinterpret_cast<const float4 *>(k.row + f.f);
+    else {
+      v.x = f.n > 0 ? k.row[f.f] : (f.one == 0 ? 1.f : 0.f);
+      v.y = f.n > 1 ? k.row[f.f + 1] : (f.one == 1 ? 1.f : 0.f);
+      v.z = f.n > 2 ? k.row[f.f + 2] : (f.one == 2 ? 1.f : 0.f);
+      v.w = f.n > 3 ? k.row[f.f + 3] : (f.one == 3 ? 1.f : 0.f);
+    }
+    v.x *= k.s; v.y *= k.s; v.z *= k.s; v.w *= k.s;
+    return v;
   }
 };
 
 // element (f, k) = table[idx[f]*ld + k]: gathered rows (embedding lookup fused into the operand)
 struct OpGatherRows {
-  static constexpr bool kLanesAlongK = true;
+  static constexpr bool kLanesAlongK = true, kVec = true;
   const float *table;
   const int *idx;
-  int ld;
+  int ld, vec;
+  void set(const float *t, const int *i, int ld_) { table = t; idx = i; ld = ld_; vec = aligned16(t) && (ld_ & 3) == 0; }
   struct FC { const float *row; };
-  struct KC { int k; };
+  struct KC4 { int k, n; };
   DEVI FC fctx(int, int f, int F) const {
     FC c; c.row = f < F ? table + (long)idx[f] * ld : nullptr; return c;
   }
-  DEVI KC kctx(int, int k, int kend) const { KC c; c.k = k < kend ? k : -1; return c; }
-  DEVI float load(const FC &f, const KC &k) const { return (f.row && k.k >= 0) ? f.row[k.k] : 0.f; }
+  DEVI KC4 kctx4(int, int k, int kend) const { KC4 c; c.k = k; c.n = min(4, kend - k); return c; }
+  DEVI float4 load4(const FC &f, const KC4 &k) const {
+    if (!f.row || k.n <= 0) return f4zero();
+    if (vec && k.n == 4) return *reinterpret_cast<const float4 *>(f.row + k.k);
+    float4 v = f4zero();
+    v.x = f.row[k.k];
+    if (k.n > 1) v.y = f.row[k.k + 1];
+    if (k.n > 2) v.z = f.row[k.k + 2];
+    if (k.n > 3) v.w = f.row[k.k + 3];
+    return v;
+  }
 };
 
 // ---------------------------------------------------------------- convolution
@@ -87,7 +135,7 @@ struct ConvGeom {
 // In batched launches (by_z) pixel q is local to image z.
 template <bool PIX_FIXED>
 struct OpConvPatch {
-  static constexpr bool kLanesAlongK = !PIX_FIXED; // lanes always walk pixels
+  static constexpr bool kLanesAlongK = !PIX_FIXED, kVec = false; // lanes always walk pixels
   const float *x;
   ConvGeom g;
   int has_ones, by_z;
@@ -135,7 +183,7 @@ struct OpConvPatch {
 
 // element (d, q) = T[b, d, p] * scale[b]  for pixel q = (b, p); T is [B, D, P].  Lanes walk pixels.
 struct OpChanPix {
-  static constexpr bool kLanesAlongK = true;
+  static constexpr bool kLanesAlongK = true, kVec = false;
   const float *t;
   const float *scale; // nullable
   int D, P, by_z;
@@ -158,7 +206,7 @@ struct OpChanPix {
 
 // backward-data A operand: element (c, k=(d,kh,kw)) = W[d, c, kh, kw]
 struct OpConvWeightT {
-  static constexpr bool kLanesAlongK = true;
+  static constexpr bool kLanesAlongK = true, kVec = false;
   const float *w;
   ConvGeom g;
   struct FC { int off; };
@@ -176,7 +224,7 @@ struct OpConvWeightT {
 // backward-data B operand: fixed = input pixel (b, ih, iw), k = (d, kh, kw):
 //   Delta[b, d, (ih+PAD-kh)/S, (iw+PAD-kw)/S] where the divisions are exact and in range.
 struct OpConvDeltaGather {
-  static constexpr bool kLanesAlongK = false;
+  static constexpr bool kLanesAlongK = false, kVec = false;
   const float *delta;
   ConvGeom g;
   struct FC { const float *base; int ihp, iwp; };
@@ -220,32 +268,51 @@ struct OpConvDeltaGather {
 //   r == Din + H   1               (bias)
 // all times scale[b].  In batched launches (by_z) k = t within example z.
 struct OpLstmIn {
-  static constexpr bool kLanesAlongK = false;
-  const float *table; const int *tok; const float *xin;
+  static constexpr bool kLanesAlongK = false, kVec = true;
+  const float *table; const int *tok;
   const float *hs;
   const float *scale;
-  int Din, H, T, by_z;
+  int Din, H, T, by_z, vec;
   FastDiv dT;
-  struct FC { int r; };
+  void set(const float *table_, const int *tok_, const float *hs_, const float *scale_, int Din_, int H_, int T_,
+           int by_z_) {
+    table = table_; tok = tok_; hs = hs_; scale = scale_; Din = Din_; H = H_; T = T_; by_z = by_z_; dT.init(T_);
+    vec = aligned16(table_) && aligned16(hs_) && (Din_ & 3) == 0 && (H_ & 3) == 0;
+  }
+  struct FC4 { int r, n; };
   struct KC { const float *xrow; const float *hrow; float s; int valid; };
-  DEVI FC fctx(int, int f, int F) const { FC c; c.r = f < F ? f : -1; return c; }
+  DEVI FC4 fctx4(int, int f, int F) const { FC4 c; c.r = f; c.n = max(0, min(4, F - f)); return c; }
   DEVI KC kctx(int z, int k, int kend) const {
     KC c;
     if (k < kend) {
       int b = by_z ? z : (int)dT.div(k);
       int t = by_z ? k : k - b * T;
       long bt = (long)b * T + t;
-      c.xrow = table ? table + (long)tok[bt] * Din : xin + bt * Din;
+      c.xrow = table + (long)tok[bt] * Din;
       c.hrow = t > 0 ? hs + (bt - 1) * H : nullptr;
       c.s = scale ? scale[b] : 1.f;
       c.valid = 1;
     } else { c.xrow = c.hrow = nullptr; c.s = 0.f; c.valid = 0; }
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    if (!k.valid || f.r < 0) return 0.f;
-    if (f.r < Din) return k.xrow[f.r] * k.s;
-    if (f.r < Din + H) return k.hrow ? k.hrow[f.r - Din] * k.s : 0.f;
-    return k.s;
+  DEVI float one(int r, const KC &k) const {
+    if (r < Din) return k.xrow[r];
+    if (r < Din + H) return k.hrow ? k.hrow[r - Din] : 0.f;
+    return 1.f;
+  }
+  DEVI float4 load4(const FC4 &f, const KC &k) const {
+    if (!k.valid || f.n <= 0) return f4zero();
+    float4 v;
+    if (vec && f.r + 3 < Din) v = *reinterpret_cast<const float4 *>(k.xrow + f.r);
+    else if (vec && f.r >= Din && f.r + 3 < Din + H)
+      v = k.hrow ? *reinterpret_cast<const float4 *>(k.hrow + (f.r - Din)) : f4zero();
+    else {
+      v.x = one(f.r, k);
+      v.y = f.n > 1 ? one(f.r + 1, k) : 0.f;
+      v.z = f.n > 2 ? one(f.r + 2, k) : 0.f;
+      v.w = f.n > 3 ? one(f.r + 3, k) : 0.f;
+    }
+    v.x *= k.s; v.y *= k.s; v.z *= k.s; v.w *= k.s;
+    return v;
   }
 };
