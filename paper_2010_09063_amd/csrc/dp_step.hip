@@ -124,6 +124,8 @@ struct Layer {
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
   ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
   float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
+  // embedding: counting-sort workspace of the clipped sum
+  int *e_count = nullptr, *e_start = nullptr, *e_chunk0 = nullptr, *e_cursor = nullptr, *e_list = nullptr;
   // lstm
   float *gates = nullptr, *cs = nullptr, *hs = nullptr;
   int T = 0, Din = 0, H = 0;
@@ -430,6 +432,14 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     if (rc == DP_OK && (l.dir_fwd || l.dir_bwd)) {
       rc = dev_alloc(c, &l.wt_f, (size_t)l.geom.D * l.geom.CKK);
       if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, (size_t)l.geom.D * l.geom.CKK);
+    }
+    if (rc == DP_OK && emb) {
+      const size_t V = l.d.vocab;
+      rc = dev_alloc(c, &l.e_count, V + 1);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.e_start, V + 1);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.e_chunk0, V + 1);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.e_cursor, V + 1);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.e_list, (size_t)mb * l.outC);
     }
     if (rc == DP_OK && l.d.kind == DP_LSTM_LAST) {
       rc = dev_alloc(c, &l.gates, mb * l.T * 4 * l.H);
@@ -779,12 +789,38 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count);
           });
         }
-        long rows = (long)B * l.outC;
-        dim3 grid = grid1d(rows * l.d.embed_dim, 256), block(256);
-        Ln("emb_scatter", grid, block, [&](hipStream_t st) {
-          hipLaunchKernelGGL(emb_scatter_kernel, grid, block, 0, st, (const int *)x, (const float *)l.g, sc, l.part,
-                             rows, l.outC, l.d.embed_dim);
-        });
+        const long rows = (long)B * l.outC;
+        const int V = l.d.vocab;
+        {
+          dim3 grid = grid1d(V + 1, 256), block(256);
+          Ln("fill_zero", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, (float *)l.e_count, (long)(V + 1));
+          });
+        }
+        {
+          dim3 grid = grid1d(rows, 1024), block(1024);
+          const size_t smem = V <= EMB_LDS_V ? sizeof(int) * V : 0;
+          Ln("emb_bucket", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_count_kernel, grid, block, smem, st, (const int *)x, l.e_count, rows, V);
+          });
+          Ln("emb_bucket", dim3(1), dim3(1024), [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, st, (const int *)l.e_count, l.e_start,
+                               l.e_chunk0, l.e_cursor, V);
+          });
+          Ln("emb_bucket", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_fill_kernel, grid, block, smem, st, (const int *)x, (const int *)l.e_start,
+                               l.e_cursor, l.e_list, rows, V);
+          });
+        }
+        {
+          // every token has at most ceil(count/EMB_CH) chunks: rows/EMB_CH + V bounds their number
+          dim3 grid((unsigned)(rows / EMB_CH + V + 1)), block(256);
+          Ln("emb_scatter", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_reduce_kernel, grid, block, 0, st, (const int *)l.e_start,
+                               (const int *)l.e_chunk0, (const int *)l.e_list, (const float *)l.g, sc, l.part, V,
+                               l.outC, l.d.embed_dim);
+          });
+        }
         nsplit = 1;
       } break;
       default: break;

@@ -16,7 +16,7 @@
 
 #include "kernels_misc.h"
 
-#define LSTM_NE 2
+#define LSTM_NE 1
 
 __device__ __forceinline__ float sigmoidf_(float v) { return fast_sigmoid(v); }
 
@@ -219,15 +219,118 @@ __global__ __launch_bounds__(256) void emb_norm_kernel(const int *__restrict__ t
   if (tid == 0) slot[b] = red[0] + red[1] + red[2] + red[3];
 }
 
-// Clipped sum of the embedding gradient: acc[tok[b,t], :] += s_b * dx[b, t, :]
-// (hardware fp32 atomics; acc is zeroed before the launch).
-__global__ void emb_scatter_kernel(const int *__restrict__ tok, const float *__restrict__ dx,
-                                   const float *__restrict__ scale, float *__restrict__ acc, long rows, int T,
-                                   int D) {
+// Clipped sum of the embedding gradient, G_E[v, :] = sum over steps (b, t) with
+// tok[b, t] = v of s_b * dx[b, t, :], as a segmented reduction instead of one float
+// atomic per element: the steps are bucketed by token with a counting sort (integer
+// atomics only), every bucket is cut into chunks of EMB_CH steps, and one workgroup
+// sums one chunk.  A token that fits in one chunk is written with plain stores; only
+// the few hot tokens that span several chunks combine with fp32 atomics.
+#define EMB_CH 64
+
+#define EMB_LDS_V 12288 // vocabularies up to this size get a per-workgroup LDS histogram
+
+// count[v] += occurrences of v.  A Zipf-distributed batch sends a large share of its
+// steps to a handful of tokens, and same-address global atomics serialise, so each
+// workgroup of 1024 steps first counts in LDS and issues one global atomic per
+// distinct token it saw (the thread that hit the LDS bin first owns the flush).
+__global__ __launch_bounds__(1024) void emb_count_kernel(const int *__restrict__ tok, int *__restrict__ count, long n,
+                                                          int V) {
+  extern __shared__ int bins[];
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= rows * D) return;
-  long row = i / D;
-  int e = (int)(i - row * D);
-  float s = scale ? scale[row / T] : 1.f;
-  unsafeAtomicAdd(&acc[(long)tok[row] * D + e], s * dx[i]);
+  if (V > EMB_LDS_V) { if (i < n) atomicAdd(&count[tok[i]], 1); return; }
+  for (int v = threadIdx.x; v < V; v += 1024) bins[v] = 0;
+  __syncthreads();
+  int t = -1, old = -1;
+  if (i < n) { t = tok[i]; old = atomicAdd(&bins[t], 1); }
+  __syncthreads();
+  if (old == 0) atomicAdd(&count[t], bins[t]);
+}
+
+// one workgroup of 1024: exclusive scans of count[v] (-> start[v]) and of the chunk
+// counts ceil(count[v]/EMB_CH) (-> chunk0[v]); start[V], chunk0[V] hold the totals;
+// cursor[v] is reset to 0 for the fill pass.
+__global__ __launch_bounds__(1024) void emb_scan_kernel(const int *__restrict__ count, int *__restrict__ start,
+                                                         int *__restrict__ chunk0, int *__restrict__ cursor, int V) {
+  __shared__ int sa[1024], sb[1024];
+  const int tid = threadIdx.x;
+  const int per = (V + 1023) / 1024;
+  const int lo = min(V, tid * per), hi = min(V, lo + per);
+  int a = 0, b = 0;
+  for (int v = lo; v < hi; ++v) { a += count[v]; b += (count[v] + EMB_CH - 1) / EMB_CH; }
+  sa[tid] = a; sb[tid] = b;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int xa = tid >= o ? sa[tid - o] : 0, xb = tid >= o ? sb[tid - o] : 0;
+    __syncthreads();
+    sa[tid] += xa; sb[tid] += xb;
+    __syncthreads();
+  }
+  int ra = sa[tid] - a, rb = sb[tid] - b; // exclusive prefix of this thread's range
+  for (int v = lo; v < hi; ++v) {
+    start[v] = ra; chunk0[v] = rb; cursor[v] = 0;
+    ra += count[v]; rb += (count[v] + EMB_CH - 1) / EMB_CH;
+  }
+  if (tid == 1023) { start[V] = sa[1023]; chunk0[V] = sb[1023]; }
+}
+
+// list[start[v] + rank] = step index, rank unique within the bucket: the workgroup reserves a
+// range of its bucket with one global atomic per distinct token, steps take their rank in LDS.
+__global__ __launch_bounds__(1024) void emb_fill_kernel(const int *__restrict__ tok, const int *__restrict__ start,
+                                                         int *__restrict__ cursor, int *__restrict__ list, long n,
+                                                         int V) {
+  extern __shared__ int bins[];
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (V > EMB_LDS_V) {
+    if (i < n) { const int v = tok[i]; list[start[v] + atomicAdd(&cursor[v], 1)] = (int)i; }
+    return;
+  }
+  for (int v = threadIdx.x; v < V; v += 1024) bins[v] = 0;
+  __syncthreads();
+  int t = -1, old = -1;
+  if (i < n) { t = tok[i]; old = atomicAdd(&bins[t], 1); }
+  __syncthreads();
+  if (old == 0) bins[t] = atomicAdd(&cursor[t], bins[t]); // the bin now holds this workgroup's base rank
+  __syncthreads();
+  if (i < n) list[start[t] + bins[t] + old] = (int)i;
+}
+
+// one workgroup per chunk; workgroups past the last chunk exit.  acc must be zero
+// on entry (rows of tokens that do not occur stay zero).
+__global__ __launch_bounds__(256) void emb_reduce_kernel(const int *__restrict__ start, const int *__restrict__ chunk0,
+                                                          const int *__restrict__ list, const float *__restrict__ dx,
+                                                          const float *__restrict__ scale, float *__restrict__ acc,
+                                                          int V, int T, int D) {
+  __shared__ int ent[EMB_CH];
+  __shared__ float sc[EMB_CH];
+  __shared__ float part[256];
+  const int chunk = blockIdx.x;
+  if (chunk >= chunk0[V]) return;
+  // token whose chunk range contains `chunk`: last v with chunk0[v] <= chunk
+  int lo = 0, hi = V;
+  while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (chunk0[mid] <= chunk) lo = mid; else hi = mid; }
+  const int v = lo, ci = chunk - chunk0[v];
+  const int cnt = start[v + 1] - start[v];
+  const int e0 = ci * EMB_CH, n = min(EMB_CH, cnt - e0);
+  const int tid = threadIdx.x;
+  if (tid < n) {
+    const int en = list[start[v] + e0 + tid];
+    ent[tid] = en;
+    sc[tid] = scale ? scale[en / T] : 1.f;
+  }
+  __syncthreads();
+  // two groups of 128 threads each take every other step; thread e < D of a group owns coordinate e
+  const int grp = tid >> 7, e = tid & 127;
+  for (int ebase = 0; ebase < D; ebase += 128) {
+    float a = 0.f;
+    if (ebase + e < D)
+      for (int i = grp; i < n; i += 2) a += sc[i] * dx[(long)ent[i] * D + ebase + e];
+    part[tid] = a;
+    __syncthreads();
+    if (grp == 0 && ebase + e < D) {
+      const float tot = part[e] + part[128 + e];
+      float *dst = acc + (long)v * D + ebase + e;
+      if (cnt <= EMB_CH) *dst = tot; else unsafeAtomicAdd(dst, tot);
+    }
+    __syncthreads();
+  }
 }
