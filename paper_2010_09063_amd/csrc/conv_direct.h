@@ -228,22 +228,27 @@ struct ConvWgArgs {
 // group of 32 input channels; the KH*KW taps are its N blocks.  W and OW must be
 // multiples of 4: rows are moved as float4 items.  The items of the next K-chunk
 // are fetched into registers while the current chunk is multiplied.
-template <int KH, int KW, int DB>
+// FLATC (first layers, C*KH*KW <= 32, DB == 1): the single N block holds the flattened
+// (channel, tap) pairs, one per lane, and the four waves split the pixel pairs instead;
+// their accumulators are summed through LDS at the end.
+template <int KH, int KW, int DB, bool FLATC>
 __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
   constexpr int KK = KH * KW;
-  constexpr int WD = DB >= 4 ? 4 : DB, WN = 4 / WD; // waves along d and along taps
-  constexpr int DBW = DB / WD, NBW = (KK + WN - 1) / WN;
+  constexpr int WD = FLATC ? 1 : (DB >= 4 ? 4 : DB), WN = FLATC ? 1 : 4 / WD; // waves along d and along taps
+  constexpr int DBW = DB / WD, NBW = FLATC ? 1 : (KK + WN - 1) / WN;
   constexpr int DT = 32 * DB;
   constexpr int XV = CONV_WG_XV;
-  constexpr int DV = DB == 1 ? 4 : 8;               // float4 Delta items per thread: DT*PCH/4 <= DV*256
+  constexpr int DV = (DB == 1 && !FLATC) ? 4 : 8;   // float4 Delta items per thread: DT*PCH/4 <= DV*256
   constexpr int NSL = 256 / DT;                     // row-sum slices
+  static_assert(!FLATC || DB == 1, "flattened (channel, tap) block needs D <= 32");
   extern __shared__ float smem[];
-  float *Xl = smem;                     // [32][XPLANE]
-  float *Dl = smem + 32 * a.t.XPLANE;   // [DT][LDP]
+  const int xch = FLATC ? a.C : 32;     // staged input channels
+  float *Xl = smem;                     // [xch][XPLANE]
+  float *Dl = smem + xch * a.t.XPLANE;  // [DT][LDP]
   __shared__ float red[4];
   __shared__ float rsum[256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
-  const int wd = wave / WN, wn = wave - wd * WN;
+  const int wd = FLATC ? 0 : wave / WN, wn = FLATC ? 0 : wave - wd * WN;
   const int cb = blockIdx.x, c0 = cb * 32;
   const int HW = a.H * a.W, OHW = a.OH * a.OW;
   int bbeg, bend;
@@ -252,7 +257,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
   const int nimg_max = a.mode == 0 ? 1 : a.t.NIMG;
 
   // zero the staged input once: the left / right halo columns are never written again
-  for (int e = tid; e < 32 * a.t.XPLANE; e += 256) Xl[e] = 0.f;
+  for (int e = tid; e < xch * a.t.XPLANE; e += 256) Xl[e] = 0.f;
 
   // static item descriptors.  Input item it = ((c*NIMG + img)*ROWS + rr)*WQ + q
   int x_lds[XV], x_goff[XV], x_ir[XV];
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
     const int t1 = (int)a.dWQ.div(it), q = it - t1 * a.WQ;
     const int t2 = (int)a.dROWS.div(t1), rr = t1 - t2 * a.ROWS;
     const int c = (int)a.dNIMG.div(t2), img = t2 - c * a.t.NIMG;
-    const bool ok = c < 32 && c0 + c < a.C;
+    const bool ok = c < xch && c0 + c < a.C;
     x_lds[j] = ok ? c * a.t.XPLANE + img * a.t.IMGPL + rr * a.t.LDW + a.pad + 4 * q : -1;
     x_goff[j] = (img * a.C + c) * HW + (rr - a.pad) * a.W + 4 * q;
     x_ir[j] = (img << 16) | rr;
@@ -291,7 +296,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   float rowsum = 0.f; // partial sum_p Delta[d, p] of row tid % DT over this thread's slice (bias gradient)
 
-  const int xlane = li * a.t.XPLANE + lk;
+  int xlane = li * a.t.XPLANE + lk;
   const int dlane = li * a.LDP + lk;
   int tapoff[NBW];
   bool tapok[NBW];
@@ -302,6 +307,13 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
     tapok[j] = tap < KK;
     tapoff[j] = tapok[j] ? kh * a.t.LDW + kw : 0;
   }
+  if (FLATC) { // lane = (channel, tap)
+    const int ch = li / KK, tap = li - ch * KK, kh = tap / KW, kw = tap - kh * KW;
+    tapok[0] = li < a.C * KK;
+    tapoff[0] = 0;
+    xlane = (tapok[0] ? ch * a.t.XPLANE + kh * a.t.LDW + kw : 0) + lk;
+  }
+  const int col0 = FLATC ? 2 * wave : 0, colstep = FLATC ? 8 : 2;
 
   float4 xr[XV], dr[DV];
   auto prefetch = [&](int b, int nimg, int r0, int rows) {
@@ -368,7 +380,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
         const int pbase = (img * a.t.TR + r) * a.OW;
         const int xbase = img * a.t.IMGPL + r * a.t.LDW;
 #pragma unroll 4
-        for (int col = 0; col < a.OW; col += 2) {
+        for (int col = col0; col < a.OW; col += colstep) {
           float av[DBW], bv[NBW];
 #pragma unroll
           for (int i = 0; i < DBW; ++i) av[i] = Dl[dlane + ((wd * DBW + i) * 32) * a.LDP + pbase + col];
@@ -396,8 +408,48 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
       for (int s = 0; s < NSL; ++s) bias_d += rsum[s * DT + tid];
     }
   }
-  // accumulator: lane column = input channel c0 + li; rows = output channels
+  if (FLATC) { // sum the four waves' accumulators (each saw a quarter of the pixel pairs) into wave 0
+    __syncthreads();
+    float *xs = smem; // [3][16][64], reusing the staging area
+    if (wave > 0)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xs[((wave - 1) * 16 + r) * 64 + lane] = acc[0][0][r];
+    __syncthreads();
+    if (wave == 0)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[0][0][r] += xs[r * 64 + lane] + xs[(16 + r) * 64 + lane] + xs[(32 + r) * 64 + lane];
+    else
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
+  }
+  // accumulator: lane column = input channel c0 + li (FLATC: flattened channel*KK + tap); rows = output channels
   const int c = c0 + li;
+  if (FLATC) {
+    const int CKK = a.C * KK;
+    if (a.mode == 0) {
+      float part = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
+        if (wave == 0 && li < CKK && d < a.D) part += acc[0][0][r] * acc[0][0][r];
+      }
+      if (tid < a.D) part += bias_d * bias_d;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+      if (lane == 0) red[wave] = part;
+      __syncthreads();
+      if (tid == 0) a.out[(long)a.slot0 * a.slot_stride + bbeg] = red[0] + red[1] + red[2] + red[3];
+    } else {
+      float *part = a.out + (long)blockIdx.y * a.part_stride;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
+        if (wave == 0 && li < CKK && d < a.D) part[(long)d * CKK + li] = acc[0][0][r];
+      }
+      if (tid < a.D) part[(long)a.D * CKK + tid] = bias_d;
+    }
+    return;
+  }
   if (a.mode == 0) {
     float part = 0.f;
 #pragma unroll

@@ -120,7 +120,7 @@ struct Layer {
   int max_slots = 0;
   ConvGeom geom;
   // stride-1 3x3 convolutions: LDS-staged direct kernels (otherwise the generic contraction)
-  bool dir_fwd = false, dir_bwd = false, dir_wg = false;
+  bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
   ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
   float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
@@ -246,22 +246,25 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
         CONV_CC * l.t_bwd.XPLANE <= CONV_XCNT * 256) { l.dir_bwd = true; l.bwd_npw = npw; }
   }
   // weight gradient
-  if (g.C >= 16 && g.D <= 128 && (g.OW & 3) == 0 && (g.W & 3) == 0) {
+  const bool flat = g.C * 9 <= 32 && g.D <= 32;
+  if ((g.C >= 16 || flat) && g.D <= 128 && (g.OW & 3) == 0 && (g.W & 3) == 0) {
     int db = g.D <= 32 ? 1 : (g.D <= 64 ? 2 : 4);
-    int pch_max = db <= 2 ? 128 : 64;
+    int pch_max = flat ? 256 : (db <= 2 ? 128 : 64);
+    const int xch = flat ? g.C : 32;
     bool ok = make_conv_tile(l.t_wgn, g.OH, g.OW, 3, 3, pch_max, true, 1) &&
               make_conv_tile(l.t_wgc, g.OH, g.OW, 3, 3, pch_max, true, 1 << 20);
     if (ok) {
-      long lds_n = 32l * l.t_wgn.XPLANE + 32l * db * ((l.t_wgn.NIMG * l.t_wgn.TR * g.OW) | 1);
-      long lds_c = 32l * l.t_wgc.XPLANE + 32l * db * ((l.t_wgc.NIMG * l.t_wgc.TR * g.OW) | 1);
+      long lds_n = (long)xch * l.t_wgn.XPLANE + 32l * db * ((l.t_wgn.NIMG * l.t_wgn.TR * g.OW) | 1);
+      long lds_c = (long)xch * l.t_wgc.XPLANE + 32l * db * ((l.t_wgc.NIMG * l.t_wgc.TR * g.OW) | 1);
       bool fits = lds_n * 4 <= 64 * 1024 && lds_c * 4 <= 64 * 1024;
+      if (flat && (lds_n < 3 * 16 * 64 || lds_c < 3 * 16 * 64)) fits = false; // room for the cross-wave sum
       for (const ConvTile *t : {&l.t_wgn, &l.t_wgc}) {
         const int pch = t->NIMG * t->TR * g.OW;
-        if (32l * t->NIMG * (t->TR + 2) * (g.W / 4) > CONV_WG_XV * 256) fits = false; // input items per thread
-        if (32l * db * pch / 4 > (db == 1 ? 4 : 8) * 256) fits = false;               // Delta items per thread
+        if ((long)xch * t->NIMG * (t->TR + 2) * (g.W / 4) > CONV_WG_XV * 256) fits = false; // input items per thread
+        if (32l * db * pch / 4 > ((db == 1 && !flat) ? 4 : 8) * 256) fits = false;          // Delta items per thread
         if ((pch & 3) != 0) fits = false;
       }
-      if (fits) { l.dir_wg = true; l.wg_db = db; }
+      if (fits) { l.dir_wg = true; l.wg_db = db; l.wg_flat = flat; }
     }
   }
 }
@@ -284,17 +287,17 @@ static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a,
 }
 
 template <class LN>
-static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs &a, int db, int groups) {
-  dim3 grid(ceil_div(a.C, 32), groups), block(256);
-  size_t smem = sizeof(float) * (32 * (size_t)a.t.XPLANE + 32 * (size_t)db * a.LDP);
-#define DP_WG_CASE(db_)                                                                              \
-  if (db == db_) {                                                                                   \
+static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs &a, int db, bool flat, int groups) {
+  dim3 grid(flat ? 1 : ceil_div(a.C, 32), groups), block(256);
+  size_t smem = sizeof(float) * ((size_t)(flat ? a.C : 32) * a.t.XPLANE + 32 * (size_t)db * a.LDP);
+#define DP_WG_CASE(db_, flat_)                                                                       \
+  if (db == db_ && flat == flat_) {                                                                  \
     Ln(label, grid, block, [&](hipStream_t st) {                                                     \
-      hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_>), grid, block, smem, st, a);               \
+      hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_, flat_>), grid, block, smem, st, a);        \
     });                                                                                              \
     return;                                                                                          \
   }
-  DP_WG_CASE(1) DP_WG_CASE(2) DP_WG_CASE(4)
+  DP_WG_CASE(1, false) DP_WG_CASE(2, false) DP_WG_CASE(4, false) DP_WG_CASE(1, true)
 #undef DP_WG_CASE
 }
 
@@ -579,6 +582,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_MAXPOOL2D: {
         long total = (long)B * l.out_size;
         dim3 grid = grid1d(total, 256), block(256);
+        const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
+        if (p22) {
+          Ln("maxpool_fwd", grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(maxpool2x2_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.outW, l.inW);
+          });
+        } else
         Ln("maxpool_fwd", grid, block, [&](hipStream_t st) {
           hipLaunchKernelGGL(maxpool_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
                              l.outW, l.d.kh, l.d.kw, l.d.stride);
@@ -645,8 +654,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn);
           a.scale = nullptr; a.out = c->slots; a.mode = 0; a.ex_per_block = 1;
           a.slot_stride = slot_stride; a.slot0 = slot_next;
-          slot_next += ceil_div(g.C, 32);
-          launch_conv_wgrad(Ln, "conv_wgrad_norm", a, l.wg_db, B);
+          slot_next += l.wg_flat ? 1 : ceil_div(g.C, 32);
+          launch_conv_wgrad(Ln, "conv_wgrad_norm", a, l.wg_db, l.wg_flat, B);
         } else if (priv) {
           typedef ProbSqNorm<OpRowMajor, OpConvPatch<false>> Pb;
           Pb p{};
@@ -676,6 +685,15 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_MAXPOOL2D: {
         long total = (long)B * l.in_size;
         dim3 grid = grid1d(total, 256), block(256);
+        const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
+        if (p22) {
+          const long nwin = (long)B * l.out_size;
+          dim3 g2 = grid1d(nwin, 256);
+          Ln("maxpool_bwd", g2, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(maxpool2x2_bwd_kernel, g2, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
+                               (const float *)prev->a, prev->g, nwin, l.outW, l.inW, prev_act);
+          });
+        } else
         Ln("maxpool_bwd", grid, block, [&](hipStream_t st) {
           hipLaunchKernelGGL(maxpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
                              (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
@@ -751,7 +769,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         const ConvGeom &g = l.geom;
         if (l.dir_wg) {
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc);
-          const int cblocks = ceil_div(g.C, 32);
+          const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
           // one full round of resident workgroups (256 CUs x workgroups per CU) avoids a ragged tail
           const int occ = l.wg_db == 1 ? 3 : (l.wg_db == 2 ? 2 : 1);
           int want = (256 * occ) / cblocks;
@@ -761,7 +779,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           epb = ceil_div(epb, a.t.NIMG) * a.t.NIMG;
           nsplit = ceil_div(B, epb);
           a.scale = sc; a.out = l.part; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
-          launch_conv_wgrad(Ln, "conv_clipped_sum", a, l.wg_db, nsplit);
+          launch_conv_wgrad(Ln, "conv_clipped_sum", a, l.wg_db, l.wg_flat, nsplit);
           break;
         }
         typedef ProbPartial<OpChanPix, OpConvPatch<false>> Pb;

@@ -96,6 +96,45 @@ __global__ void maxpool_bwd_kernel(const float *__restrict__ gout, const uint8_t
   gin[i] = acc * act_deriv_from_out(act, a_in[i]);
 }
 
+// 2x2 / stride-2 pooling with even H and W (the common case): one thread per window,
+// 8-byte accesses to the two input rows, no divisions by the window geometry.
+__global__ void maxpool2x2_fwd_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                      uint8_t *__restrict__ arg, long total, int OW, int W) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const long row = i / OW;           // (b, c, oh) flattened: input rows 2*row and 2*row+1
+  const int ow = (int)(i - row * OW);
+  const float2 t = *reinterpret_cast<const float2 *>(in + (2 * row) * W + 2 * ow);
+  const float2 u = *reinterpret_cast<const float2 *>(in + (2 * row + 1) * W + 2 * ow);
+  float best = t.x; int bi = 0;
+  if (t.y > best) { best = t.y; bi = 1; }
+  if (u.x > best) { best = u.x; bi = 2; }
+  if (u.y > best) { best = u.y; bi = 3; }
+  out[i] = best;
+  arg[i] = (uint8_t)bi;
+}
+
+__global__ void maxpool2x2_bwd_kernel(const float *__restrict__ gout, const uint8_t *__restrict__ arg,
+                                      const float *__restrict__ a_in, float *__restrict__ gin, long total, int OW,
+                                      int W, int act) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const long row = i / OW;
+  const int ow = (int)(i - row * OW);
+  const float g = gout[i];
+  const int bi = arg[i];
+  const long o0 = (2 * row) * W + 2 * ow, o1 = o0 + W;
+  const float2 t = *reinterpret_cast<const float2 *>(a_in + o0);
+  const float2 u = *reinterpret_cast<const float2 *>(a_in + o1);
+  float2 r0, r1;
+  r0.x = bi == 0 ? g * act_deriv_from_out(act, t.x) : 0.f;
+  r0.y = bi == 1 ? g * act_deriv_from_out(act, t.y) : 0.f;
+  r1.x = bi == 2 ? g * act_deriv_from_out(act, u.x) : 0.f;
+  r1.y = bi == 3 ? g * act_deriv_from_out(act, u.y) : 0.f;
+  *reinterpret_cast<float2 *>(gin + o0) = r0;
+  *reinterpret_cast<float2 *>(gin + o1) = r1;
+}
+
 // Dense layer: ||g_i||^2 = (||a_i||^2 + 1) ||delta_i||^2 without forming the outer
 // product (Section 1: per-example norms for fully-connected layers).  One wave per example.
 __global__ void dense_norm_kernel(const float *__restrict__ a, int d_in, const float *__restrict__ delta, int d_out,
