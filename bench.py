@@ -37,8 +37,9 @@ def label_work(m, B):
     out = {}
 
     def add(label, flops, nbytes):
-        f, b = out.get(label, (0.0, 0.0))
-        out[label] = (f + flops, b + nbytes)
+        for key in (label, f"{label}#{li}"):   # per kernel kind and per (kind, layer)
+            f, b = out.get(key, (0.0, 0.0))
+            out[key] = (f + flops, b + nbytes)
 
     for li, L in enumerate(m["layers"]):
         o = shapes[li]
@@ -81,14 +82,14 @@ def label_work(m, B):
             add("lstm_clipped_sum", 2.0 * B * T * (Din + H) * G, 4.0 * B * T * (G + H + Din))
         cur = o
     P = W.num_params(m)
-    add("finalize_noise", 0.0, 8.0 * P)
+    out["finalize_noise"] = (0.0, 8.0 * P)
     return out
 
 
 def step_flops(m, B, private=True):
     w = label_work(m, B)
     skip = () if private else ("dense_norm", "conv_wgrad_norm", "lstm_wgrad_norm", "emb_norm")
-    return sum(f for lab, (f, _) in w.items() if lab not in skip)
+    return sum(f for lab, (f, _) in w.items() if "#" not in lab and lab not in skip)
 
 
 def time_steps(fn, steps, warmup):
@@ -129,20 +130,31 @@ def run_workload(name, steps, warmup, profile):
         rows = st.dp_step_profile_read(reset=True)
         st.dp_step_profile(False)
         work = label_work(m, B)
-        kern = []
-        for label, launches, ms in rows:
-            if launches == 0:
-                continue
-            fl, by = work.get(label, (0.0, 0.0))
-            per_step_ms = ms / steps
-            kern.append(dict(kernel=label, launches_per_step=launches / steps, ms_per_step=per_step_ms,
-                             avg_launch_us=1e3 * ms / launches,
-                             tflops=(fl / (per_step_ms * 1e-3) / 1e12) if per_step_ms > 0 else 0.0,
-                             gbs=(by / (per_step_ms * 1e-3) / 1e9) if per_step_ms > 0 else 0.0,
-                             flops_per_step=fl, bytes_per_step=by))
-        kern.sort(key=lambda r: -r["ms_per_step"])
+
+        def table(items):
+            out = []
+            for label, (launches, ms) in items.items():
+                if launches == 0:
+                    continue
+                fl, by = work.get(label, (0.0, 0.0))
+                per_step_ms = ms / steps
+                out.append(dict(kernel=label, launches_per_step=launches / steps, ms_per_step=per_step_ms,
+                                avg_launch_us=1e3 * ms / launches,
+                                tflops=(fl / (per_step_ms * 1e-3) / 1e12) if per_step_ms > 0 else 0.0,
+                                gbs=(by / (per_step_ms * 1e-3) / 1e9) if per_step_ms > 0 else 0.0,
+                                flops_per_step=fl, bytes_per_step=by))
+            out.sort(key=lambda r: -r["ms_per_step"])
+            return out
+
+        per_layer = {label: (launches, ms) for label, launches, ms in rows}
+        per_kind = {}
+        for label, launches, ms in rows:  # the library labels launches "<kind>#<layer>"
+            k = label.split("#")[0]
+            a, b = per_kind.get(k, (0, 0.0))
+            per_kind[k] = (a + launches, b + ms)
         res["ms_private_profiled"] = ms_prof
-        res["kernels"] = kern
+        res["kernels"] = table(per_kind)
+        res["kernels_per_layer"] = table(per_layer)
     st.dp_step_free()
     return res, wl
 
@@ -206,6 +218,9 @@ def main():
                 share_of_step=dom["ms_per_step"] / max(res["ms_private_profiled"], 1e-9),
                 step_tflops=res["tflops"], step_frac_of_mfma_fp32_peak=res["tflops"] / PEAK_MFMA_FP32_TFLOPS)
     if a.kernels:
+        for r in res["kernels_per_layer"]:
+            print(f"  {r['kernel']:22s} {r['avg_launch_us']:9.1f} us {r['tflops']:8.2f} TFLOP/s {r['gbs']:9.1f} GB/s",
+                  file=sys.stderr)
         for r in kern:
             print(f"{r['kernel']:20s} {r['launches_per_step']:5.1f}/step {r['ms_per_step']*1e3:10.1f} us/step "
                   f"{r['tflops']:8.2f} TFLOP/s {r['gbs']:9.1f} GB/s", file=sys.stderr)

@@ -124,6 +124,7 @@ struct Layer {
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
   ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
   float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
+  std::vector<std::string> lab; // profiling labels "<kernel>#<layer index>" (stable after init)
   // embedding: counting-sort workspace of the clipped sum
   int *e_count = nullptr, *e_start = nullptr, *e_chunk0 = nullptr, *e_cursor = nullptr, *e_list = nullptr;
   // lstm
@@ -132,6 +133,18 @@ struct Layer {
 };
 
 struct ProfRec { int label; hipEvent_t e0, e1; };
+
+// label "<name>#<layer index>", created once per layer and name (pointer stays valid until free)
+static const char *layer_label(Layer &l, int li, const char *name) {
+  std::string want = std::string(name) + "#" + std::to_string(li);
+  for (auto &s : l.lab)
+    if (s == want) return s.c_str();
+  return nullptr;
+}
+static const char *const kLayerLabels[] = {"dense_fwd", "dense_fwd_epilogue", "dense_norm", "dense_bwd_data", "dense_clipped_sum",
+                                           "conv_weight_layout", "conv_fwd", "conv_wgrad_norm", "conv_bwd_data", "conv_clipped_sum",
+                                           "maxpool_fwd", "maxpool_bwd", "lstm_xproj", "lstm_fwd", "lstm_bwd", "lstm_wgrad_norm",
+                                           "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_bucket", "emb_scatter", "fill_zero"};
 
 struct dp_ctx {
   dp_model_desc m;
@@ -404,6 +417,10 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   if (rc != DP_OK) { delete c; return rc; }
   c->P = off;
   c->max_slots = total_slots;
+  for (size_t i = 0; i < c->L.size(); ++i) {
+    c->L[i].lab.reserve(sizeof(kLayerLabels) / sizeof(kLayerLabels[0]));
+    for (const char *nm : kLayerLabels) c->L[i].lab.push_back(std::string(nm) + "#" + std::to_string(i));
+  }
   const long mb = max_batch;
   for (auto &l : c->L) {
     if (rc != DP_OK) break;
@@ -485,16 +502,16 @@ extern "C" const char *dp_step_strerror(int code) {
 static inline dim3 grid1d(long n, int block) { return dim3((unsigned)((n + block - 1) / block)); }
 
 template <int HP>
-static void launch_lstm_fwd(const Launcher &Ln, Layer &l, const float *Whh, int B) {
+static void launch_lstm_fwd(const Launcher &Ln, Layer &l, const float *Whh, int B, const char *label) {
   dim3 grid(ceil_div(B, LSTM_NE)), block(256);
-  Ln("lstm_fwd", grid, block, [&](hipStream_t st) {
+  Ln(label, grid, block, [&](hipStream_t st) {
     hipLaunchKernelGGL(lstm_fwd_kernel<HP>, grid, block, 0, st, l.gates, Whh, l.hs, l.cs, l.a, B, l.T, l.H);
   });
 }
 template <int HP>
-static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int B) {
+static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int B, const char *label) {
   dim3 grid(ceil_div(B, LSTM_NE)), block(256);
-  Ln("lstm_bwd", grid, block, [&](hipStream_t st) {
+  Ln(label, grid, block, [&](hipStream_t st) {
     hipLaunchKernelGGL(lstm_bwd_kernel<HP>, grid, block, 0, st, l.gates, (const float *)l.cs, Whh, (const float *)l.g, B, l.T, l.H);
   });
 }
@@ -509,6 +526,7 @@ static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int 
     else fn<128>(__VA_ARGS__);                    \
   } while (0)
 
+#define LL(name) layer_label(l, i, name)
 static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t *y, int B, bool priv, float C,
                     float sigma, uint64_t seed, float *out) {
   Launcher Ln{c};
@@ -534,11 +552,11 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.b.set(W, l.d.out_features);
           const long stride = (long)c->maxB * l.out_size;
           p.part = l.fpart; p.stride = stride; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
-          const int ns = launch_gemm_split(p, l.fsplit, Ln, "dense_fwd");
+          const int ns = launch_gemm_split(p, l.fsplit, Ln, LL("dense_fwd"));
           const long total = (long)B * l.out_size;
           dim3 grid = grid1d(total, 256), block(256);
           const float *bias = W + (long)l.d.in_features * l.d.out_features;
-          Ln("dense_fwd_epilogue", grid, block, [&](hipStream_t st) {
+          Ln(LL("dense_fwd_epilogue"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(bias_act_reduce_kernel, grid, block, 0, st, (const float *)l.fpart, ns, stride, bias,
                                l.d.act, l.a, total, l.d.out_features);
           });
@@ -550,14 +568,14 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.a.set(in, l.d.in_features);
         p.b.set(W, l.d.out_features);
         p.out = l.a; p.bias = W + (long)l.d.in_features * l.d.out_features; p.ld = l.d.out_features; p.act = l.d.act;
-        launch_gemm(p, 1, Ln, "dense_fwd");
+        launch_gemm(p, 1, Ln, LL("dense_fwd"));
       } break;
       case DP_CONV2D: {
         if (l.dir_fwd || l.dir_bwd) {
           const ConvGeom &g = l.geom;
           const int n = g.D * g.CKK;
           dim3 grid = grid1d(n, 256), block(256);
-          Ln("conv_weight_layout", grid, block, [&](hipStream_t st) {
+          Ln(LL("conv_weight_layout"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, W, l.wt_f, l.wt_b, g.D, g.C, 9);
           });
         }
@@ -567,7 +585,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           a.x = in; a.wt = l.wt_f; a.bias = W + (long)g.D * g.CKK; a.a_prev = nullptr; a.out = l.a;
           a.B = B; a.Cin = g.C; a.H = g.H; a.W = g.W; a.M = g.D; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
           a.act = l.d.act; a.t = l.t_fwd;
-          launch_conv_s1(Ln, "conv_fwd", a, l.fwd_npw);
+          launch_conv_s1(Ln, LL("conv_fwd"), a, l.fwd_npw);
           break;
         }
         typedef ProbConvFwd<OpRowMajor, OpConvPatch<true>> Pb;
@@ -577,18 +595,18 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.a.set(W, g.CKK);
         p.b.x = in; p.b.g = g; p.b.has_ones = 0; p.b.by_z = 0;
         p.out = l.a; p.bias = W + (long)g.D * g.CKK; p.D = g.D; p.P = g.P; p.act = l.d.act; p.dP = g.dP;
-        launch_gemm(p, 1, Ln, "conv_fwd");
+        launch_gemm(p, 1, Ln, LL("conv_fwd"));
       } break;
       case DP_MAXPOOL2D: {
         long total = (long)B * l.out_size;
         dim3 grid = grid1d(total, 256), block(256);
         const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
         if (p22) {
-          Ln("maxpool_fwd", grid, block, [&](hipStream_t st) {
+          Ln(LL("maxpool_fwd"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(maxpool2x2_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.outW, l.inW);
           });
         } else
-        Ln("maxpool_fwd", grid, block, [&](hipStream_t st) {
+        Ln(LL("maxpool_fwd"), grid, block, [&](hipStream_t st) {
           hipLaunchKernelGGL(maxpool_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
                              l.outW, l.d.kh, l.d.kw, l.d.stride);
         });
@@ -604,9 +622,9 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.a.set(E, (const int *)x, l.Din);
         p.b.set(W, G);
         p.out = l.gates; p.bias = W + (long)l.Din * G + (long)l.H * G; p.ld = G; p.act = DP_ACT_NONE;
-        launch_gemm(p, 1, Ln, "lstm_xproj");
+        launch_gemm(p, 1, Ln, LL("lstm_xproj"));
         const float *Whh = W + (long)l.Din * G;
-        LSTM_DISPATCH(launch_lstm_fwd, l.H, Ln, l, Whh, B);
+        LSTM_DISPATCH(launch_lstm_fwd, l.H, Ln, l, Whh, B, LL("lstm_fwd"));
       } break;
       }
       in = l.a;
@@ -633,7 +651,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           dim3 grid = grid1d((long)B * 64, 256), block(256);
           float *slot = c->slots + (long)slot_next * slot_stride;
           slot_next += 1;
-          Ln("dense_norm", grid, block, [&](hipStream_t st) {
+          Ln(LL("dense_norm"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(dense_norm_kernel, grid, block, 0, st, lin, l.d.in_features, (const float *)l.g,
                                l.d.out_features, slot, B);
           });
@@ -645,7 +663,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.a.set(l.g, l.d.out_features);
           p.b.set(W, l.d.out_features);
           p.out = prev->g; p.a_prev = prev->a; p.ld = l.d.in_features; p.act = prev_act;
-          launch_gemm(p, 1, Ln, "dense_bwd_data");
+          launch_gemm(p, 1, Ln, LL("dense_bwd_data"));
         }
       } break;
       case DP_CONV2D: {
@@ -655,7 +673,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           a.scale = nullptr; a.out = c->slots; a.mode = 0; a.ex_per_block = 1;
           a.slot_stride = slot_stride; a.slot0 = slot_next;
           slot_next += l.wg_flat ? 1 : ceil_div(g.C, 32);
-          launch_conv_wgrad(Ln, "conv_wgrad_norm", a, l.wg_db, l.wg_flat, B);
+          launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, B);
         } else if (priv) {
           typedef ProbSqNorm<OpRowMajor, OpConvPatch<false>> Pb;
           Pb p{};
@@ -663,7 +681,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.a.set(l.g, g.P, (long)g.D * g.P);
           p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 1;
           p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
-          GemmShape s = launch_gemm(p, B, Ln, "conv_wgrad_norm");
+          GemmShape s = launch_gemm(p, B, Ln, LL("conv_wgrad_norm"));
           slot_next += s.tiles_m * s.tiles_n;
         }
         if (prev && l.dir_bwd) {
@@ -671,7 +689,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           a.x = l.g; a.wt = l.wt_b; a.bias = nullptr; a.a_prev = prev->a; a.out = prev->g;
           a.B = B; a.Cin = g.D; a.H = g.OH; a.W = g.OW; a.M = g.C; a.OH = g.H; a.OW = g.W; a.pad = 2 - g.PAD;
           a.act = prev_act; a.t = l.t_bwd;
-          launch_conv_s1(Ln, "conv_bwd_data", a, l.bwd_npw);
+          launch_conv_s1(Ln, LL("conv_bwd_data"), a, l.bwd_npw);
         } else if (prev) {
           typedef ProbConvBwd<OpConvWeightT, OpConvDeltaGather> Pb;
           Pb p{};
@@ -679,7 +697,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.a.w = W; p.a.g = g;
           p.b.delta = l.g; p.b.g = g;
           p.out = prev->g; p.a_prev = prev->a; p.C = g.C; p.HW = g.H * g.W; p.act = prev_act; p.dHW = g.dHW;
-          launch_gemm(p, 1, Ln, "conv_bwd_data");
+          launch_gemm(p, 1, Ln, LL("conv_bwd_data"));
         }
       } break;
       case DP_MAXPOOL2D: {
@@ -689,12 +707,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         if (p22) {
           const long nwin = (long)B * l.out_size;
           dim3 g2 = grid1d(nwin, 256);
-          Ln("maxpool_bwd", g2, block, [&](hipStream_t st) {
+          Ln(LL("maxpool_bwd"), g2, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(maxpool2x2_bwd_kernel, g2, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
                                (const float *)prev->a, prev->g, nwin, l.outW, l.inW, prev_act);
           });
         } else
-        Ln("maxpool_bwd", grid, block, [&](hipStream_t st) {
+        Ln(LL("maxpool_bwd"), grid, block, [&](hipStream_t st) {
           hipLaunchKernelGGL(maxpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
                              (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
                              l.d.stride, prev_act);
@@ -703,7 +721,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_LSTM_LAST: {
         const int G = 4 * l.H;
         const float *Whh = W + (long)l.Din * G;
-        LSTM_DISPATCH(launch_lstm_bwd, l.H, Ln, l, Whh, B);
+        LSTM_DISPATCH(launch_lstm_bwd, l.H, Ln, l, Whh, B, LL("lstm_bwd"));
         if (priv) {
           typedef ProbSqNorm<OpLstmIn, OpKMajor> Pb;
           Pb p{};
@@ -711,7 +729,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.a.set(params + prev->p_off, (const int *)x, l.hs, nullptr, l.Din, l.H, l.T, 1);
           p.b.set(l.gates, G, (long)l.T * G); p.b.by_z = 1;
           p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
-          GemmShape s = launch_gemm(p, B, Ln, "lstm_wgrad_norm");
+          GemmShape s = launch_gemm(p, B, Ln, LL("lstm_wgrad_norm"));
           slot_next += s.tiles_m * s.tiles_n;
         }
         { // dx = dgates W_ih^T: gradient w.r.t. the embedding outputs
@@ -721,7 +739,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.a.set(l.gates, G);
           p.b.set(W, G);
           p.out = prev->g; p.a_prev = nullptr; p.ld = l.Din; p.act = DP_ACT_NONE;
-          launch_gemm(p, 1, Ln, "lstm_dx");
+          launch_gemm(p, 1, Ln, LL("lstm_dx"));
         }
       } break;
       case DP_EMBEDDING: {
@@ -731,7 +749,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           dim3 grid(B), block(256);
           float *slot = c->slots + (long)slot_next * slot_stride;
           slot_next += 1;
-          Ln("emb_norm", grid, block, [&](hipStream_t st) {
+          Ln(LL("emb_norm"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(emb_norm_kernel, grid, block, 0, st, (const int *)x, (const float *)l.g, slot, l.outC,
                                TP, l.d.embed_dim);
           });
@@ -763,7 +781,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.a.set(lin, l.d.in_features); p.a.scale = sc; p.a.ones_row = 1;
         p.b.set(l.g, l.d.out_features);
         p.part = l.part; p.stride = l.p_count; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
-        nsplit = launch_gemm_split(p, l.max_split, Ln, "dense_clipped_sum");
+        nsplit = launch_gemm_split(p, l.max_split, Ln, LL("dense_clipped_sum"));
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
@@ -779,7 +797,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           epb = ceil_div(epb, a.t.NIMG) * a.t.NIMG;
           nsplit = ceil_div(B, epb);
           a.scale = sc; a.out = l.part; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
-          launch_conv_wgrad(Ln, "conv_clipped_sum", a, l.wg_db, l.wg_flat, nsplit);
+          launch_conv_wgrad(Ln, LL("conv_clipped_sum"), a, l.wg_db, l.wg_flat, nsplit);
           break;
         }
         typedef ProbPartial<OpChanPix, OpConvPatch<false>> Pb;
@@ -788,7 +806,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.a.t = l.g; p.a.scale = sc; p.a.D = g.D; p.a.P = g.P; p.a.by_z = 0; p.a.dP = g.dP;
         p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 0;
         p.part = l.part; p.stride = l.p_count; p.ldm = g.CKK; p.bias_col = g.CKK; p.bias_off = (long)g.D * g.CKK;
-        nsplit = launch_gemm_split(p, l.max_split, Ln, "conv_clipped_sum");
+        nsplit = launch_gemm_split(p, l.max_split, Ln, LL("conv_clipped_sum"));
       } break;
       case DP_LSTM_LAST: {
         const int G = 4 * l.H;
@@ -798,12 +816,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.a.set(params + c->L[i - 1].p_off, (const int *)x, l.hs, sc, l.Din, l.H, l.T, 0);
         p.b.set(l.gates, G);
         p.part = l.part; p.stride = l.p_count; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
-        nsplit = launch_gemm_split(p, l.max_split, Ln, "lstm_clipped_sum");
+        nsplit = launch_gemm_split(p, l.max_split, Ln, LL("lstm_clipped_sum"));
       } break;
       case DP_EMBEDDING: {
         {
           dim3 grid = grid1d(l.p_count, 256), block(256);
-          Ln("fill_zero", grid, block, [&](hipStream_t st) {
+          Ln(LL("fill_zero"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count);
           });
         }
@@ -811,21 +829,21 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         const int V = l.d.vocab;
         {
           dim3 grid = grid1d(V + 1, 256), block(256);
-          Ln("fill_zero", grid, block, [&](hipStream_t st) {
+          Ln(LL("fill_zero"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, (float *)l.e_count, (long)(V + 1));
           });
         }
         {
           dim3 grid = grid1d(rows, 1024), block(1024);
           const size_t smem = V <= EMB_LDS_V ? sizeof(int) * V : 0;
-          Ln("emb_bucket", grid, block, [&](hipStream_t st) {
+          Ln(LL("emb_bucket"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(emb_count_kernel, grid, block, smem, st, (const int *)x, l.e_count, rows, V);
           });
-          Ln("emb_bucket", dim3(1), dim3(1024), [&](hipStream_t st) {
+          Ln(LL("emb_bucket"), dim3(1), dim3(1024), [&](hipStream_t st) {
             hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, st, (const int *)l.e_count, l.e_start,
                                l.e_chunk0, l.e_cursor, V);
           });
-          Ln("emb_bucket", grid, block, [&](hipStream_t st) {
+          Ln(LL("emb_bucket"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(emb_fill_kernel, grid, block, smem, st, (const int *)x, (const int *)l.e_start,
                                l.e_cursor, l.e_list, rows, V);
           });
@@ -833,7 +851,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         {
           // every token has at most ceil(count/EMB_CH) chunks: rows/EMB_CH + V bounds their number
           dim3 grid((unsigned)(rows / EMB_CH + V + 1)), block(256);
-          Ln("emb_scatter", grid, block, [&](hipStream_t st) {
+          Ln(LL("emb_scatter"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(emb_reduce_kernel, grid, block, 0, st, (const int *)l.e_start,
                                (const int *)l.e_chunk0, (const int *)l.e_list, (const float *)l.g, sc, l.part, V,
                                l.outC, l.d.embed_dim);
