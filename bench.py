@@ -69,6 +69,7 @@ def label_work(m, B):
             add("maxpool_bwd", 0.0, 8.0 * n_in + 5.0 * n_out)
         elif k == "embedding":
             T, D_ = inp["seq_len"], L["dim"]
+            add("emb_gather", 0.0, 4.0 * B * T * (2 * D_ + 1))
             add("emb_norm", 2.0 * B * T * D_, 4.0 * B * T * (D_ + 1))
             add("emb_scatter", 2.0 * B * T * D_, 4.0 * (B * T * (D_ + 1) + L["vocab"] * D_))
         elif k == "lstm_last":

@@ -31,37 +31,40 @@ struct ConvTile {
 
 struct ConvS1Args {
   const float *x;      // input  [B, Cin, H, W]
-  const float *wt;     // weights laid out [Cin][KK][M] (see conv_weight_layout_kernel)
+  const float *wt;     // weights laid out [Cin][KK][Mpad], Mpad = M rounded up to 4, pad columns zero
   const float *bias;   // forward: bias[M]; backward-data: null
   const float *a_prev; // backward-data: output of the activation whose derivative multiplies the result
   float *out;          // [B, M, OH, OW]
-  int B, Cin, H, W, M, OH, OW, pad;
+  int B, Cin, H, W, M, Mpad, OH, OW, pad;
   int act;
   ConvTile t;
 };
 
 // Re-lays a conv weight W[D][C][KK] for the two correlations that use it:
-//   wt_f[(c*KK + tap)*D + d] = W[d][c][tap]            forward       (M = D, Cin = C)
-//   wt_b[(d*KK + tap)*C + c] = W[d][c][KK-1-tap]       backward-data (M = C, Cin = D)
-// so that a chunk of input channels is one contiguous block that is copied
-// straight into LDS in the order the MFMA A operand reads it.
+//   wt_f[(c*KK + tap)*Dp + d] = W[d][c][tap]            forward       (M = D, Cin = C)
+//   wt_b[(d*KK + tap)*Cp + c] = W[d][c][KK-1-tap]       backward-data (M = C, Cin = D)
+// (Dp, Cp = D, C rounded up to 4; the pad columns stay zero from the allocation) so that a
+// chunk of input channels is copied into LDS with aligned 16-byte loads in the order the
+// MFMA A operand reads it.
 __global__ void conv_weight_layout_kernel(const float *__restrict__ w, float *__restrict__ wt_f,
-                                          float *__restrict__ wt_b, int D, int C, int KK) {
+                                          float *__restrict__ wt_b, int D, int C, int KK, int Dp, int Cp) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= D * C * KK) return;
   int d = i / (C * KK), r = i - d * C * KK;
   int c = r / KK, tap = r - c * KK;
   float v = w[i];
-  wt_f[((long)c * KK + tap) * D + d] = v;
-  wt_b[((long)d * KK + (KK - 1 - tap)) * C + c] = v;
+  wt_f[((long)c * KK + tap) * Dp + d] = v;
+  wt_b[((long)d * KK + (KK - 1 - tap)) * Cp + c] = v;
 }
 
-#define CONV_CC 8     // input channels staged per chunk
-#define CONV_XCNT 14  // staged input elements per thread and chunk (CC * XPLANE <= 14 * 256)
+#define CONV_XPLANE_MAX 448 // staged floats per channel: a thread stages at most CC*448/256 elements per chunk
 
-template <int KH, int KW, int DT, int NPW>
+// CC = input channels staged per chunk (8 or 16): a longer chunk amortises the two barriers
+// and gives the prefetch of the next chunk more multiply time to hide behind.
+template <int KH, int KW, int DT, int NPW, int CC>
 __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
-  constexpr int KK = KH * KW, CC = CONV_CC, DB = DT / 32, PB = NPW / 32;
+  constexpr int KK = KH * KW, DB = DT / 32, PB = NPW / 32;
+  constexpr int XP = (CONV_XPLANE_MAX + 255) / 256; // staged positions per thread within a channel plane
   constexpr int WROWS = CC * KK;                     // weight rows per chunk
   constexpr int WV = (WROWS * DT / 4 + 255) / 256;   // float4 weight registers per thread
   extern __shared__ __attribute__((aligned(16))) float smem[];
@@ -87,26 +90,22 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
     xoff[pb] = (ok ? img * a.t.IMGPL + r * a.t.LDW + col : 0) + lk * a.t.XPLANE;
     ooff[pb] = ok ? ((long)(b0 + img) * a.M) * OHW + (long)(r0 + r) * a.OW + col : -1;
   }
-  // staged-input descriptors of this thread: LDS element e = tid + j*256 = (c, img, rr, cc)
-  int goff[CONV_XCNT]; // offset inside x for channel chunk 0, or -1 (halo / outside the batch)
-  int gch[CONV_XCNT];  // channel within the chunk
-  const int xtotal = CC * a.t.XPLANE;
+  // staged input: a thread owns up to XP positions of the channel plane (img, rr, cc) and stages
+  // them for every channel of the chunk, so one offset per position is all it keeps
+  int goff[XP]; // offset inside x of channel 0 for the position, or -1 (halo / outside the batch / past the plane)
 #pragma unroll
-  for (int j = 0; j < CONV_XCNT; ++j) {
-    const int e = tid + j * 256;
-    goff[j] = -1; gch[j] = 0;
-    if (e < xtotal) {
-      const int c = (int)a.t.dXPLANE.div(e), rem = e - c * a.t.XPLANE;
-      const int img = (int)a.t.dIMGPL.div(rem), rem2 = rem - img * a.t.IMGPL;
+  for (int j = 0; j < XP; ++j) {
+    const int pos = tid + j * 256;
+    goff[j] = -1;
+    if (pos < a.t.XPLANE) {
+      const int img = (int)a.t.dIMGPL.div(pos), rem2 = pos - img * a.t.IMGPL;
       const int rr = (int)a.t.dLDW.div(rem2), cc = rem2 - rr * a.t.LDW;
       const int ih = r0 + rr - a.pad, iw = cc - a.pad;
-      gch[j] = c;
       if (img < a.t.NIMG && (b0 + img) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-        goff[j] = ((b0 + img) * a.Cin + c) * HW + ih * a.W + iw;
+        goff[j] = (b0 + img) * a.Cin * HW + ih * a.W + iw;
     }
   }
-  // weight descriptors: float4 q = tid + j*256 covers row q / (DT/4), columns 4*(q % (DT/4)) ..+3
-  const bool wvec = (a.M & 3) == 0;
+  // weight items: float4 q = tid + j*256 covers row q / (DT/4), columns 4*(q % (DT/4)) ..+3
 
   f32x16 acc[DB][PB];
 #pragma unroll
@@ -116,31 +115,26 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  float xr[CONV_XCNT];
+  float xr[XP][CC];
   float4 wr[WV];
   auto prefetch = [&](int c0) {
+    // every load is unconditional (an invalid item reads element 0 and is zeroed afterwards): a load
+    // under a branch would make the compiler drain all outstanding loads at each join
 #pragma unroll
-    for (int j = 0; j < CONV_XCNT; ++j) {
-      float v = 0.f;
-      if (goff[j] >= 0 && c0 + gch[j] < a.Cin) v = a.x[(long)goff[j] + (long)c0 * HW];
-      xr[j] = v;
-    }
+    for (int j = 0; j < XP; ++j)
+#pragma unroll
+      for (int c = 0; c < CC; ++c) {
+        const bool ok = goff[j] >= 0 && c0 + c < a.Cin;
+        const float v = a.x[ok ? (long)goff[j] + (long)(c0 + c) * HW : 0];
+        xr[j][c] = ok ? v : 0.f;
+      }
 #pragma unroll
     for (int j = 0; j < WV; ++j) {
       const int q = tid + j * 256;
       const int row = q / (DT / 4), m = m0 + 4 * (q - row * (DT / 4));
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (row < WROWS && c0 * KK + row < a.Cin * KK) {
-        const float *src = a.wt + (long)(c0 * KK + row) * a.M + m;
-        if (wvec) { if (m < a.M) v = *reinterpret_cast<const float4 *>(src); }
-        else {
-          if (m < a.M) v.x = src[0];
-          if (m + 1 < a.M) v.y = src[1];
-          if (m + 2 < a.M) v.z = src[2];
-          if (m + 3 < a.M) v.w = src[3];
-        }
-      }
-      wr[j] = v;
+      const bool ok = row < WROWS && c0 * KK + row < a.Cin * KK && m < a.Mpad;
+      const float4 v = *reinterpret_cast<const float4 *>(a.wt + (ok ? (long)(c0 * KK + row) * a.Mpad + m : 0));
+      wr[j] = ok ? v : f4zero();
     }
   };
 
@@ -148,9 +142,11 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
   for (int c0 = 0; c0 < a.Cin; c0 += CC) {
     __syncthreads(); // the previous chunk has been consumed
 #pragma unroll
-    for (int j = 0; j < CONV_XCNT; ++j) {
-      const int e = tid + j * 256;
-      if (e < xtotal) Xl[e] = xr[j];
+    for (int j = 0; j < XP; ++j) {
+      const int pos = tid + j * 256;
+      if (pos < a.t.XPLANE)
+#pragma unroll
+        for (int c = 0; c < CC; ++c) Xl[c * a.t.XPLANE + pos] = xr[j][c];
     }
 #pragma unroll
     for (int j = 0; j < WV; ++j) {
@@ -209,7 +205,7 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
 struct ConvWgArgs {
   const float *x;     // layer input [B, C, H, W]
   const float *delta; // [B, D, OH, OW]
-  const float *scale; // clip factors s[b] (clipped mode; null = 1)
+  const float *scale; // clip factors s[b]; always valid (a vector of ones when nothing is clipped)
   float *out;         // norm mode: slots base; clipped mode: partials base
   int B, C, H, W, D, OH, OW, pad;
   int mode;           // 0: per-example squared norm; 1: sum over the block's examples
@@ -231,7 +227,8 @@ struct ConvWgArgs {
 // FLATC (first layers, C*KH*KW <= 32, DB == 1): the single N block holds the flattened
 // (channel, tap) pairs, one per lane, and the four waves split the pixel pairs instead;
 // their accumulators are summed through LDS at the end.
-template <int KH, int KW, int DB, bool FLATC>
+// CLIP: the clipped-sum mode (a.mode == 1); the norm mode never touches the clip factors.
+template <int KH, int KW, int DB, bool FLATC, bool CLIP>
 __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
   constexpr int KK = KH * KW;
   constexpr int WD = FLATC ? 1 : (DB >= 4 ? 4 : DB), WN = FLATC ? 1 : 4 / WD; // waves along d and along taps
@@ -252,9 +249,9 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
   const int cb = blockIdx.x, c0 = cb * 32;
   const int HW = a.H * a.W, OHW = a.OH * a.OW;
   int bbeg, bend;
-  if (a.mode == 0) { bbeg = blockIdx.y; bend = bbeg + 1; }
+  if (!CLIP) { bbeg = blockIdx.y; bend = bbeg + 1; }
   else { bbeg = blockIdx.y * a.ex_per_block; bend = min(a.B, bbeg + a.ex_per_block); }
-  const int nimg_max = a.mode == 0 ? 1 : a.t.NIMG;
+  const int nimg_max = !CLIP ? 1 : a.t.NIMG;
 
   // zero the staged input once: the left / right halo columns are never written again
   for (int e = tid; e < xch * a.t.XPLANE; e += 256) Xl[e] = 0.f;
@@ -318,25 +315,26 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
   float4 xr[XV], dr[DV];
   auto prefetch = [&](int b, int nimg, int r0, int rows) {
     const long xb = ((long)b * a.C + c0) * HW + (long)r0 * a.W;
+    // unconditional loads with a safe address for invalid items (see conv_s1_kernel)
 #pragma unroll
     for (int j = 0; j < XV; ++j) {
       const int img = x_ir[j] >> 16, rr = x_ir[j] & 0xffff;
       const int ih = r0 + rr - a.pad;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (x_lds[j] >= 0 && img < nimg && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H)
-        v = *reinterpret_cast<const float4 *>(a.x + xb + x_goff[j]);
-      xr[j] = v;
+      const bool ok = x_lds[j] >= 0 && img < nimg && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H;
+      const float4 v = *reinterpret_cast<const float4 *>(a.x + (ok ? xb + x_goff[j] : 0));
+      xr[j] = ok ? v : f4zero();
     }
     const long db_ = (long)b * a.D * OHW + (long)r0 * a.OW;
 #pragma unroll
     for (int j = 0; j < DV; ++j) {
       const int img = d_ir[j] >> 16, r = d_ir[j] & 0xffff;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (d_goff[j] >= 0 && img < nimg && r < rows) {
-        v = *reinterpret_cast<const float4 *>(a.delta + db_ + d_goff[j]);
-        if (a.scale) { const float s = a.scale[b + img]; v.x *= s; v.y *= s; v.z *= s; v.w *= s; }
-      }
-      dr[j] = v;
+      const bool ok = d_goff[j] >= 0 && img < nimg && r < rows;
+      const float4 v = *reinterpret_cast<const float4 *>(a.delta + (ok ? db_ + d_goff[j] : 0));
+      float sv = 1.f;
+      if (CLIP) sv = a.scale[ok ? b + img : 0];
+      float4 w = f4zero();
+      if (ok) { w.x = v.x * sv; w.y = v.y * sv; w.z = v.z * sv; w.w = v.w * sv; }
+      dr[j] = w;
     }
   };
 
@@ -426,7 +424,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
   const int c = c0 + li;
   if (FLATC) {
     const int CKK = a.C * KK;
-    if (a.mode == 0) {
+    if (!CLIP) {
       float part = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -450,7 +448,7 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
     }
     return;
   }
-  if (a.mode == 0) {
+  if (!CLIP) {
     float part = 0.f;
 #pragma unroll
     for (int i = 0; i < DBW; ++i)

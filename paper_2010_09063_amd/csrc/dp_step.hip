@@ -144,7 +144,7 @@ static const char *layer_label(Layer &l, int li, const char *name) {
 static const char *const kLayerLabels[] = {"dense_fwd", "dense_fwd_epilogue", "dense_norm", "dense_bwd_data", "dense_clipped_sum",
                                            "conv_weight_layout", "conv_fwd", "conv_wgrad_norm", "conv_bwd_data", "conv_clipped_sum",
                                            "maxpool_fwd", "maxpool_bwd", "lstm_xproj", "lstm_fwd", "lstm_bwd", "lstm_wgrad_norm",
-                                           "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_bucket", "emb_scatter", "fill_zero"};
+                                           "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_gather", "emb_bucket", "emb_scatter", "fill_zero"};
 
 struct dp_ctx {
   dp_model_desc m;
@@ -156,6 +156,7 @@ struct dp_ctx {
   size_t ws_bytes = 0;
   float *slots = nullptr; int max_slots = 0;
   float *norms = nullptr, *s = nullptr;
+  float *ones = nullptr; // [maxB] of 1.0: the clip factors of a step that clips nothing
   int last_batch = -1;
   // profiling
   bool prof = false;
@@ -250,13 +251,13 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
   {
     int npw = ((long)maxB * g.P / 256 >= 512) ? 64 : 32;
     if (make_conv_tile(l.t_fwd, g.OH, g.OW, 3, 3, 4 * npw, false, 1 << 20) &&
-        CONV_CC * l.t_fwd.XPLANE <= CONV_XCNT * 256) { l.dir_fwd = true; l.fwd_npw = npw; }
+        l.t_fwd.XPLANE <= CONV_XPLANE_MAX) { l.dir_fwd = true; l.fwd_npw = npw; }
   }
   // backward-data: correlation of Delta (OH x OW) with flipped weights, output H x W, pad' = 2 - pad
   {
     int npw = ((long)maxB * g.H * g.W / 256 >= 512) ? 64 : 32;
     if (make_conv_tile(l.t_bwd, g.H, g.W, 3, 3, 4 * npw, false, 1 << 20) &&
-        CONV_CC * l.t_bwd.XPLANE <= CONV_XCNT * 256) { l.dir_bwd = true; l.bwd_npw = npw; }
+        l.t_bwd.XPLANE <= CONV_XPLANE_MAX) { l.dir_bwd = true; l.bwd_npw = npw; }
   }
   // weight gradient
   const bool flat = g.C * 9 <= 32 && g.D <= 32;
@@ -285,17 +286,18 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
 template <class LN>
 static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a, int npw) {
   const int dt = a.M <= 32 ? 32 : (a.M <= 64 ? 64 : 128);
+  const int cc = 8;
   dim3 grid(a.t.NIMG > 1 ? ceil_div(a.B, a.t.NIMG) : a.B * a.t.row_tiles, ceil_div(a.M, dt)), block(256);
-  size_t smem = sizeof(float) * ((size_t)CONV_CC * a.t.XPLANE + (size_t)CONV_CC * 9 * dt);
-#define DP_CONV_CASE(dt_, npw_)                                                                      \
-  if (dt == dt_ && npw == npw_) {                                                                    \
+  size_t smem = sizeof(float) * ((size_t)cc * a.t.XPLANE + (size_t)cc * 9 * dt);
+#define DP_CONV_CASE(dt_, npw_, cc_)                                                                 \
+  if (dt == dt_ && npw == npw_ && cc == cc_) {                                                       \
     Ln(label, grid, block, [&](hipStream_t st) {                                                     \
-      hipLaunchKernelGGL((conv_s1_kernel<3, 3, dt_, npw_>), grid, block, smem, st, a);               \
+      hipLaunchKernelGGL((conv_s1_kernel<3, 3, dt_, npw_, cc_>), grid, block, smem, st, a);          \
     });                                                                                              \
     return;                                                                                          \
   }
-  DP_CONV_CASE(32, 64) DP_CONV_CASE(64, 64) DP_CONV_CASE(128, 64)
-  DP_CONV_CASE(32, 32) DP_CONV_CASE(64, 32) DP_CONV_CASE(128, 32)
+  DP_CONV_CASE(32, 64, 8) DP_CONV_CASE(64, 64, 8) DP_CONV_CASE(128, 64, 8)
+  DP_CONV_CASE(32, 32, 8) DP_CONV_CASE(64, 32, 8) DP_CONV_CASE(128, 32, 8)
 #undef DP_CONV_CASE
 }
 
@@ -306,7 +308,10 @@ static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs 
 #define DP_WG_CASE(db_, flat_)                                                                       \
   if (db == db_ && flat == flat_) {                                                                  \
     Ln(label, grid, block, [&](hipStream_t st) {                                                     \
-      hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_, flat_>), grid, block, smem, st, a);        \
+      if (a.mode == 0)                                                                               \
+        hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_, flat_, false>), grid, block, smem, st, a); \
+      else                                                                                           \
+        hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_, flat_, true>), grid, block, smem, st, a);  \
     });                                                                                              \
     return;                                                                                          \
   }
@@ -425,8 +430,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   for (auto &l : c->L) {
     if (rc != DP_OK) break;
     const bool emb = l.d.kind == DP_EMBEDDING;
-    // the embedding's "activation" is never written (the lookup is fused into the next contraction)
-    if (!emb) rc = dev_alloc(c, &l.a, mb * l.out_size);
+    rc = dev_alloc(c, &l.a, mb * l.out_size); // embedding: the gathered rows x[B, T, D]
     if (rc == DP_OK) rc = dev_alloc(c, &l.g, mb * l.out_size);
     if (rc == DP_OK && l.d.kind == DP_MAXPOOL2D) rc = dev_alloc(c, &l.arg, mb * l.out_size);
     if (rc == DP_OK && l.p_count > 0) {
@@ -450,8 +454,11 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       }
     }
     if (rc == DP_OK && (l.dir_fwd || l.dir_bwd)) {
-      rc = dev_alloc(c, &l.wt_f, (size_t)l.geom.D * l.geom.CKK);
-      if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, (size_t)l.geom.D * l.geom.CKK);
+      const size_t nf = (size_t)l.geom.C * 9 * ((l.geom.D + 3) & ~3), nb = (size_t)l.geom.D * 9 * ((l.geom.C + 3) & ~3);
+      rc = dev_alloc(c, &l.wt_f, nf);
+      if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, nb);
+      if (rc == DP_OK && (hipMemset(l.wt_f, 0, nf * sizeof(float)) != hipSuccess ||
+                          hipMemset(l.wt_b, 0, nb * sizeof(float)) != hipSuccess)) rc = DP_EHIP;
     }
     if (rc == DP_OK && emb) {
       const size_t V = l.d.vocab;
@@ -470,6 +477,11 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   if (rc == DP_OK) rc = dev_alloc(c, &c->slots, (size_t)c->max_slots * mb);
   if (rc == DP_OK) rc = dev_alloc(c, &c->norms, mb);
   if (rc == DP_OK) rc = dev_alloc(c, &c->s, mb);
+  if (rc == DP_OK) rc = dev_alloc(c, &c->ones, mb);
+  if (rc == DP_OK) {
+    std::vector<float> one(mb, 1.f);
+    if (hipMemcpy(c->ones, one.data(), sizeof(float) * mb, hipMemcpyHostToDevice) != hipSuccess) rc = DP_EHIP;
+  }
   if (rc != DP_OK) { dp_step_free(c); return rc; }
   *out = c;
   return DP_OK;
@@ -527,6 +539,12 @@ static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int 
   } while (0)
 
 #define LL(name) layer_label(l, i, name)
+// runs body(tag) with tag = std::true_type when the operands can be staged as float4, else std::false_type
+template <class F>
+static inline void vec_dispatch(bool cond, F &&body) {
+  if (cond) body(std::true_type{});
+  else body(std::false_type{});
+}
 static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t *y, int B, bool priv, float C,
                     float sigma, uint64_t seed, float *out) {
   Launcher Ln{c};
@@ -545,14 +563,20 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       switch (l.d.kind) {
       case DP_DENSE: {
         if (l.fsplit > 1) {
-          typedef ProbPartial<OpRowMajor, OpKMajor> Pb;
-          Pb p{};
-          p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
-          p.a.set(in, l.d.in_features);
-          p.b.set(W, l.d.out_features);
           const long stride = (long)c->maxB * l.out_size;
-          p.part = l.fpart; p.stride = stride; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
-          const int ns = launch_gemm_split(p, l.fsplit, Ln, LL("dense_fwd"));
+          int ns = 1;
+          auto run = [&](auto vt) {
+            constexpr bool V = decltype(vt)::value;
+            typedef ProbPartial<OpRowMajor<V>, OpKMajor<V, false>> Pb;
+            Pb p{};
+            p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
+            p.a.set(in, l.d.in_features);
+            p.b.set(W, l.d.out_features);
+            p.part = l.fpart; p.stride = stride; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
+            ns = launch_gemm_split(p, l.fsplit, Ln, LL("dense_fwd"));
+          };
+          vec_dispatch(OpRowMajor<true>::can_vec(in, l.d.in_features, 0, l.d.in_features) &&
+                              OpKMajor<true, false>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
           const long total = (long)B * l.out_size;
           dim3 grid = grid1d(total, 256), block(256);
           const float *bias = W + (long)l.d.in_features * l.d.out_features;
@@ -562,13 +586,18 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
           break;
         }
-        typedef ProbBiasAct<OpRowMajor, OpKMajor> Pb;
-        Pb p{};
-        p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
-        p.a.set(in, l.d.in_features);
-        p.b.set(W, l.d.out_features);
-        p.out = l.a; p.bias = W + (long)l.d.in_features * l.d.out_features; p.ld = l.d.out_features; p.act = l.d.act;
-        launch_gemm(p, 1, Ln, LL("dense_fwd"));
+        auto run = [&](auto vt) {
+          constexpr bool V = decltype(vt)::value;
+          typedef ProbBiasAct<OpRowMajor<V>, OpKMajor<V, false>> Pb;
+          Pb p{};
+          p.M = B; p.N = l.d.out_features; p.K = l.d.in_features;
+          p.a.set(in, l.d.in_features);
+          p.b.set(W, l.d.out_features);
+          p.out = l.a; p.bias = W + (long)l.d.in_features * l.d.out_features; p.ld = l.d.out_features; p.act = l.d.act;
+          launch_gemm(p, 1, Ln, LL("dense_fwd"));
+        };
+        vec_dispatch(OpRowMajor<true>::can_vec(in, l.d.in_features, 0, l.d.in_features) &&
+                            OpKMajor<true, false>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
       } break;
       case DP_CONV2D: {
         if (l.dir_fwd || l.dir_bwd) {
@@ -576,26 +605,31 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           const int n = g.D * g.CKK;
           dim3 grid = grid1d(n, 256), block(256);
           Ln(LL("conv_weight_layout"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, W, l.wt_f, l.wt_b, g.D, g.C, 9);
+            hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, W, l.wt_f, l.wt_b, g.D, g.C, 9,
+                               (g.D + 3) & ~3, (g.C + 3) & ~3);
           });
         }
         if (l.dir_fwd) {
           const ConvGeom &g = l.geom;
           ConvS1Args a{};
           a.x = in; a.wt = l.wt_f; a.bias = W + (long)g.D * g.CKK; a.a_prev = nullptr; a.out = l.a;
-          a.B = B; a.Cin = g.C; a.H = g.H; a.W = g.W; a.M = g.D; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
+          a.B = B; a.Cin = g.C; a.H = g.H; a.W = g.W; a.M = g.D; a.Mpad = (g.D + 3) & ~3; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
           a.act = l.d.act; a.t = l.t_fwd;
           launch_conv_s1(Ln, LL("conv_fwd"), a, l.fwd_npw);
           break;
         }
-        typedef ProbConvFwd<OpRowMajor, OpConvPatch<true>> Pb;
-        Pb p{};
         const ConvGeom &g = l.geom;
-        p.M = g.D; p.N = B * g.P; p.K = g.CKK;
-        p.a.set(W, g.CKK);
-        p.b.x = in; p.b.g = g; p.b.has_ones = 0; p.b.by_z = 0;
-        p.out = l.a; p.bias = W + (long)g.D * g.CKK; p.D = g.D; p.P = g.P; p.act = l.d.act; p.dP = g.dP;
-        launch_gemm(p, 1, Ln, LL("conv_fwd"));
+        auto run = [&](auto vt) {
+          constexpr bool V = decltype(vt)::value;
+          typedef ProbConvFwd<OpRowMajor<V>, OpConvPatch<true>> Pb;
+          Pb p{};
+          p.M = g.D; p.N = B * g.P; p.K = g.CKK;
+          p.a.set(W, g.CKK);
+          p.b.x = in; p.b.g = g; p.b.has_ones = 0; p.b.by_z = 0;
+          p.out = l.a; p.bias = W + (long)g.D * g.CKK; p.D = g.D; p.P = g.P; p.act = l.d.act; p.dP = g.dP;
+          launch_gemm(p, 1, Ln, LL("conv_fwd"));
+        };
+        vec_dispatch(OpRowMajor<true>::can_vec(W, g.CKK, 0, g.CKK), run);
       } break;
       case DP_MAXPOOL2D: {
         long total = (long)B * l.out_size;
@@ -611,18 +645,27 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
                              l.outW, l.d.kh, l.d.kw, l.d.stride);
         });
       } break;
-      case DP_EMBEDDING: break; // lookup is fused into the LSTM input projection
+      case DP_EMBEDDING: {
+        const long n = (long)B * l.out_size;
+        dim3 grid = grid1d(n, 256), block(256);
+        Ln(LL("emb_gather"), grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(emb_gather_kernel, grid, block, 0, st, (const int *)x, W, l.a, (long)B * l.outC,
+                             l.d.embed_dim);
+        });
+      } break;
       case DP_LSTM_LAST: {
-        const Layer &emb = c->L[i - 1];
-        const float *E = params + emb.p_off;
         const int G = 4 * l.H;
-        typedef ProbBiasAct<OpGatherRows, OpKMajor> Pb;
-        Pb p{};
-        p.M = B * l.T; p.N = G; p.K = l.Din;
-        p.a.set(E, (const int *)x, l.Din);
-        p.b.set(W, G);
-        p.out = l.gates; p.bias = W + (long)l.Din * G + (long)l.H * G; p.ld = G; p.act = DP_ACT_NONE;
-        launch_gemm(p, 1, Ln, LL("lstm_xproj"));
+        auto run = [&](auto vt) {
+          constexpr bool V = decltype(vt)::value;
+          typedef ProbBiasAct<OpRowMajor<V>, OpKMajor<V, false>> Pb;
+          Pb p{};
+          p.M = B * l.T; p.N = G; p.K = l.Din;
+          p.a.set(in, l.Din);
+          p.b.set(W, G);
+          p.out = l.gates; p.bias = W + (long)l.Din * G + (long)l.H * G; p.ld = G; p.act = DP_ACT_NONE;
+          launch_gemm(p, 1, Ln, LL("lstm_xproj"));
+        };
+        vec_dispatch(OpRowMajor<true>::can_vec(in, l.Din, 0, l.Din) && OpKMajor<true, false>::can_vec(W, G, 0, G), run);
         const float *Whh = W + (long)l.Din * G;
         LSTM_DISPATCH(launch_lstm_fwd, l.H, Ln, l, Whh, B, LL("lstm_fwd"));
       } break;
@@ -657,37 +700,46 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
         }
         if (prev) {
-          typedef ProbBwdAct<OpRowMajor, OpRowMajor> Pb;
-          Pb p{};
-          p.M = B; p.N = l.d.in_features; p.K = l.d.out_features;
-          p.a.set(l.g, l.d.out_features);
-          p.b.set(W, l.d.out_features);
-          p.out = prev->g; p.a_prev = prev->a; p.ld = l.d.in_features; p.act = prev_act;
-          launch_gemm(p, 1, Ln, LL("dense_bwd_data"));
+          auto run = [&](auto vt) {
+            constexpr bool V = decltype(vt)::value;
+            typedef ProbBwdAct<OpRowMajor<V>, OpRowMajor<V>> Pb;
+            Pb p{};
+            p.M = B; p.N = l.d.in_features; p.K = l.d.out_features;
+            p.a.set(l.g, l.d.out_features);
+            p.b.set(W, l.d.out_features);
+            p.out = prev->g; p.a_prev = prev->a; p.ld = l.d.in_features; p.act = prev_act;
+            launch_gemm(p, 1, Ln, LL("dense_bwd_data"));
+          };
+          vec_dispatch(OpRowMajor<true>::can_vec(l.g, l.d.out_features, 0, l.d.out_features) &&
+                              OpRowMajor<true>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
         }
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
-        if (priv && l.dir_wg) {
+        if (priv && l.dir_wg && aligned16(lin)) {
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn);
-          a.scale = nullptr; a.out = c->slots; a.mode = 0; a.ex_per_block = 1;
+          a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = 1;
           a.slot_stride = slot_stride; a.slot0 = slot_next;
           slot_next += l.wg_flat ? 1 : ceil_div(g.C, 32);
           launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, B);
         } else if (priv) {
-          typedef ProbSqNorm<OpRowMajor, OpConvPatch<false>> Pb;
-          Pb p{};
-          p.M = g.D; p.N = g.CKK + 1; p.K = g.P;
-          p.a.set(l.g, g.P, (long)g.D * g.P);
-          p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 1;
-          p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
-          GemmShape s = launch_gemm(p, B, Ln, LL("conv_wgrad_norm"));
-          slot_next += s.tiles_m * s.tiles_n;
+          auto run = [&](auto vt) {
+            constexpr bool V = decltype(vt)::value;
+            typedef ProbSqNorm<OpRowMajor<V>, OpConvPatch<false>> Pb;
+            Pb p{};
+            p.M = g.D; p.N = g.CKK + 1; p.K = g.P;
+            p.a.set(l.g, g.P, (long)g.D * g.P);
+            p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 1;
+            p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
+            GemmShape s = launch_gemm(p, B, Ln, LL("conv_wgrad_norm"));
+            slot_next += s.tiles_m * s.tiles_n;
+          };
+          vec_dispatch(OpRowMajor<true>::can_vec(l.g, g.P, (long)g.D * g.P, g.P), run);
         }
         if (prev && l.dir_bwd) {
           ConvS1Args a{};
           a.x = l.g; a.wt = l.wt_b; a.bias = nullptr; a.a_prev = prev->a; a.out = prev->g;
-          a.B = B; a.Cin = g.D; a.H = g.OH; a.W = g.OW; a.M = g.C; a.OH = g.H; a.OW = g.W; a.pad = 2 - g.PAD;
+          a.B = B; a.Cin = g.D; a.H = g.OH; a.W = g.OW; a.M = g.C; a.Mpad = (g.C + 3) & ~3; a.OH = g.H; a.OW = g.W; a.pad = 2 - g.PAD;
           a.act = prev_act; a.t = l.t_bwd;
           launch_conv_s1(Ln, LL("conv_bwd_data"), a, l.bwd_npw);
         } else if (prev) {
@@ -695,7 +747,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           Pb p{};
           p.M = g.C; p.N = B * g.H * g.W; p.K = g.D * g.KH * g.KW;
           p.a.w = W; p.a.g = g;
-          p.b.delta = l.g; p.b.g = g;
+          p.b.delta = l.g; p.b.g = g; p.b.dS.init(g.S);
           p.out = prev->g; p.a_prev = prev->a; p.C = g.C; p.HW = g.H * g.W; p.act = prev_act; p.dHW = g.dHW;
           launch_gemm(p, 1, Ln, LL("conv_bwd_data"));
         }
@@ -723,23 +775,32 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         const float *Whh = W + (long)l.Din * G;
         LSTM_DISPATCH(launch_lstm_bwd, l.H, Ln, l, Whh, B, LL("lstm_bwd"));
         if (priv) {
-          typedef ProbSqNorm<OpLstmIn, OpKMajor> Pb;
-          Pb p{};
-          p.M = l.Din + l.H + 1; p.N = G; p.K = l.T;
-          p.a.set(params + prev->p_off, (const int *)x, l.hs, nullptr, l.Din, l.H, l.T, 1);
-          p.b.set(l.gates, G, (long)l.T * G); p.b.by_z = 1;
-          p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
-          GemmShape s = launch_gemm(p, B, Ln, LL("lstm_wgrad_norm"));
-          slot_next += s.tiles_m * s.tiles_n;
+          auto run = [&](auto vt) {
+            constexpr bool V = decltype(vt)::value;
+            typedef ProbSqNorm<OpLstmIn<V>, OpKMajor<V, false>> Pb;
+            Pb p{};
+            p.M = l.Din + l.H + 1; p.N = G; p.K = l.T;
+            p.a.set(lin, l.hs, c->ones, l.Din, l.H, l.T, 1);
+            p.b.set(l.gates, G, (long)l.T * G); p.b.by_z = 1;
+            p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
+            GemmShape s = launch_gemm(p, B, Ln, LL("lstm_wgrad_norm"));
+            slot_next += s.tiles_m * s.tiles_n;
+          };
+          vec_dispatch(OpLstmIn<true>::can_vec(lin, l.hs, l.Din, l.H) &&
+                              OpKMajor<true, false>::can_vec(l.gates, G, (long)l.T * G, G), run);
         }
         { // dx = dgates W_ih^T: gradient w.r.t. the embedding outputs
-          typedef ProbBwdAct<OpRowMajor, OpRowMajor> Pb;
-          Pb p{};
-          p.M = B * l.T; p.N = l.Din; p.K = G;
-          p.a.set(l.gates, G);
-          p.b.set(W, G);
-          p.out = prev->g; p.a_prev = nullptr; p.ld = l.Din; p.act = DP_ACT_NONE;
-          launch_gemm(p, 1, Ln, LL("lstm_dx"));
+          auto run = [&](auto vt) {
+            constexpr bool V = decltype(vt)::value;
+            typedef ProbBwdAct<OpRowMajor<V>, OpRowMajor<V>> Pb;
+            Pb p{};
+            p.M = B * l.T; p.N = l.Din; p.K = G;
+            p.a.set(l.gates, G);
+            p.b.set(W, G);
+            p.out = prev->g; p.a_prev = nullptr; p.ld = l.Din; p.act = DP_ACT_NONE;
+            launch_gemm(p, 1, Ln, LL("lstm_dx"));
+          };
+          vec_dispatch(OpRowMajor<true>::can_vec(l.gates, G, 0, G) && OpRowMajor<true>::can_vec(W, G, 0, G), run);
         }
       } break;
       case DP_EMBEDDING: {
@@ -766,7 +827,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
                            c->norms, c->s, B);
       });
     }
-    const float *sc = priv ? c->s : nullptr;
+    const float *sc = priv ? c->s : c->ones;
     // ------------------------------------------------------------ clipped sums (split-K partials)
     for (int i = 0; i < nL; ++i) {
       Layer &l = c->L[i];
@@ -775,17 +836,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       int nsplit = 1;
       switch (l.d.kind) {
       case DP_DENSE: {
-        typedef ProbPartial<OpKMajor, OpKMajor> Pb;
-        Pb p{};
-        p.M = l.d.in_features + 1; p.N = l.d.out_features; p.K = B;
-        p.a.set(lin, l.d.in_features); p.a.scale = sc; p.a.ones_row = 1;
-        p.b.set(l.g, l.d.out_features);
-        p.part = l.part; p.stride = l.p_count; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
-        nsplit = launch_gemm_split(p, l.max_split, Ln, LL("dense_clipped_sum"));
+        auto run = [&](auto vt) {
+          constexpr bool V = decltype(vt)::value;
+          typedef ProbPartial<OpKMajor<V, true>, OpKMajor<V, false>> Pb;
+          Pb p{};
+          p.M = l.d.in_features + 1; p.N = l.d.out_features; p.K = B;
+          p.a.set(lin, l.d.in_features); p.a.scale = sc; p.a.ones_row = 1;
+          p.b.set(l.g, l.d.out_features);
+          p.part = l.part; p.stride = l.p_count; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
+          nsplit = launch_gemm_split(p, l.max_split, Ln, LL("dense_clipped_sum"));
+        };
+        vec_dispatch(OpKMajor<true, true>::can_vec(lin, l.d.in_features, 0, l.d.in_features) &&
+                            OpKMajor<true, false>::can_vec(l.g, l.d.out_features, 0, l.d.out_features), run);
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
-        if (l.dir_wg) {
+        if (l.dir_wg && aligned16(lin)) {
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc);
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
           // one full round of resident workgroups (256 CUs x workgroups per CU) avoids a ragged tail
@@ -810,13 +876,17 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_LSTM_LAST: {
         const int G = 4 * l.H;
-        typedef ProbPartial<OpLstmIn, OpKMajor> Pb;
-        Pb p{};
-        p.M = l.Din + l.H + 1; p.N = G; p.K = B * l.T;
-        p.a.set(params + c->L[i - 1].p_off, (const int *)x, l.hs, sc, l.Din, l.H, l.T, 0);
-        p.b.set(l.gates, G);
-        p.part = l.part; p.stride = l.p_count; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
-        nsplit = launch_gemm_split(p, l.max_split, Ln, LL("lstm_clipped_sum"));
+        auto run = [&](auto vt) {
+          constexpr bool V = decltype(vt)::value;
+          typedef ProbPartial<OpLstmIn<V>, OpKMajor<V, false>> Pb;
+          Pb p{};
+          p.M = l.Din + l.H + 1; p.N = G; p.K = B * l.T;
+          p.a.set(lin, l.hs, sc, l.Din, l.H, l.T, 0);
+          p.b.set(l.gates, G);
+          p.part = l.part; p.stride = l.p_count; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
+          nsplit = launch_gemm_split(p, l.max_split, Ln, LL("lstm_clipped_sum"));
+        };
+        vec_dispatch(OpLstmIn<true>::can_vec(lin, l.hs, l.Din, l.H) && OpKMajor<true, false>::can_vec(l.gates, G, 0, G), run);
       } break;
       case DP_EMBEDDING: {
         {

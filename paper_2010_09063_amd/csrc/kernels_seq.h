@@ -18,6 +18,18 @@
 
 #define LSTM_NE 1
 
+// x_{b,t} = E[tok[b,t]]: the embedding lookup, written once per step so that the three
+// contractions that read it (input projection, per-example and clipped weight gradient)
+// address it directly instead of chasing the token id first.
+__global__ void emb_gather_kernel(const int *__restrict__ tok, const float *__restrict__ table,
+                                  float *__restrict__ xseq, long rows, int D) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * D) return;
+  long r = i / D;
+  int e = (int)(i - r * D);
+  xseq[i] = table[(long)tok[r] * D + e];
+}
+
 __device__ __forceinline__ float sigmoidf_(float v) { return fast_sigmoid(v); }
 
 // Forward.  gates: in  x_t W_ih + b for every (b, t); out activated i, f, g, o.

@@ -1,119 +1,114 @@
 // Operand functors for gemm_tile_kernel.  An operand names element (f, k) where f is
 // the fixed dimension (row m of A or column n of B) and k the contracted one.
-//   FC fctx(z, f, F)    context of fixed index f (invalid if f >= F)
-//   KC kctx(z, k, kend) context of contracted index k (invalid if k >= kend)
-//   float load(FC, KC)  the element, 0 where invalid / padded
-// kLanesAlongK tells the tile loader which index consecutive lanes should walk so
-// that global loads coalesce.
+//   scalar staging:  FC fctx(z, f, F), KC kctx(z, k, kend), float load(FC, KC)
+//   float4 staging:  groups of four consecutive indices along the contiguous dimension
+//                    (first index a multiple of 4): fctx4 / kctx4 and float4 load4
+// Elements outside the operand read as 0.  kLanesAlongK tells the tile loader which
+// index consecutive lanes should walk so that global loads coalesce; kVec selects the
+// float4 loaders.
+//
+// Every load here is UNCONDITIONAL: an invalid element selects a safe address (the
+// operand's base) and the value is discarded afterwards.  A load under a branch makes
+// the compiler wait for all outstanding loads where the paths join, which serialises
+// the whole tile fetch; with selects the fetch of a tile stays one burst of loads.
+// For the same reason float4 vs. scalar staging is a template parameter chosen on the
+// host (`can_vec`: 16-byte aligned base, sizes multiples of 4), not a run-time branch.
 #pragma once
+#include <type_traits>
+
 #include "gemm_tile.h"
 
-// ---------------------------------------------------------------- plain matrices
-//
-// Vector operands (kVec) are staged as float4 items along their contiguous
-// dimension: kctx4 / fctx4 give the context of a group of four consecutive
-// indices (first index a multiple of 4) and load4 returns the four elements.
-// `vec` is set on the host when base pointer, leading dimension and batch
-// stride keep every group 16-byte aligned; otherwise load4 falls back to four
-// guarded scalar loads.
-
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+DEVI float4 f4scale(float4 v, float s) { v.x *= s; v.y *= s; v.z *= s; v.w *= s; return v; }
+
+// ---------------------------------------------------------------- plain matrices
 
 // element (f, k) = ptr[z*zstride + f*ld + k]            (k contiguous)
+template <bool VEC>
 struct OpRowMajor {
-  static constexpr bool kLanesAlongK = true, kVec = true;
+  static constexpr bool kLanesAlongK = true, kVec = VEC;
   const float *ptr;
   long zstride;
-  int ld, vec;
-  void set(const float *p, int ld_, long zs = 0) {
-    ptr = p; ld = ld_; zstride = zs;
-    vec = aligned16(p) && (ld_ & 3) == 0 && (zs & 3) == 0;
+  int ld;
+  static bool can_vec(const float *p, int ld_, long zs, int K) {
+    return aligned16(p) && (ld_ & 3) == 0 && (zs & 3) == 0 && (K & 3) == 0;
   }
+  void set(const float *p, int ld_, long zs = 0) { ptr = p; ld = ld_; zstride = zs; }
   struct FC { const float *row; };
-  struct KC4 { int k, n; };
+  struct KC { int k; };
+  typedef KC KC4;
   DEVI FC fctx(int z, int f, int F) const {
     FC c; c.row = f < F ? ptr + z * zstride + (long)f * ld : nullptr; return c;
   }
-  DEVI KC4 kctx4(int, int k, int kend) const { KC4 c; c.k = k; c.n = min(4, kend - k); return c; }
+  DEVI KC kctx(int, int k, int kend) const { KC c; c.k = k < kend ? k : -1; return c; }
+  DEVI KC4 kctx4(int, int k, int kend) const { KC c; c.k = k < kend ? k : -1; return c; } // K % 4 == 0
+  DEVI float load(const FC &f, const KC &k) const {
+    const bool ok = f.row && k.k >= 0;
+    const float v = *(ok ? f.row + k.k : ptr);
+    return ok ? v : 0.f;
+  }
   DEVI float4 load4(const FC &f, const KC4 &k) const {
-    if (!f.row || k.n <= 0) return f4zero();
-    if (vec && k.n == 4) return *reinterpret_cast<const float4 *>(f.row + k.k);
-    float4 v = f4zero();
-    v.x = f.row[k.k];
-    if (k.n > 1) v.y = f.row[k.k + 1];
-    if (k.n > 2) v.z = f.row[k.k + 2];
-    if (k.n > 3) v.w = f.row[k.k + 3];
-    return v;
+    const bool ok = f.row && k.k >= 0;
+    const float4 v = *reinterpret_cast<const float4 *>(ok ? f.row + k.k : ptr);
+    return ok ? v : f4zero();
   }
 };
 
 // element (f, k) = ptr[z*zstride + k*ld + f] * scale[k / scale_div]    (f contiguous);
 // with ones_row, f == F-1 is a row of ones (times the scale): the bias column.
+// SCALED operands always carry a valid scale pointer (a vector of ones when nothing is clipped).
+template <bool VEC, bool SCALED>
 struct OpKMajor {
-  static constexpr bool kLanesAlongK = false, kVec = true;
+  static constexpr bool kLanesAlongK = false, kVec = VEC;
   const float *ptr;
   long zstride;
-  int ld, vec;
-  const float *scale; // nullable; indexed by z when by_z, else by k / scale_div
+  int ld;
+  const float *scale; // indexed by z when by_z, else by k / scale_div
   FastDiv scale_div;
   int ones_row, by_z;
+  // real = number of rows that live in memory (F minus the ones row)
+  static bool can_vec(const float *p, int ld_, long zs, int real) {
+    return aligned16(p) && (ld_ & 3) == 0 && (zs & 3) == 0 && (real & 3) == 0;
+  }
   void set(const float *p, int ld_, long zs = 0) {
     ptr = p; ld = ld_; zstride = zs; scale = nullptr; scale_div.init(1); ones_row = 0; by_z = 0;
-    vec = aligned16(p) && (ld_ & 3) == 0 && (zs & 3) == 0;
   }
-  struct FC4 { int f, n, one; }; // n real rows in the group, index of the ones row within it (or -1)
+  struct FC { int f, one; };
+  struct FC4 { int f, n, one; }; // n = 4 (whole group in memory) or 0; index of the ones row within the group or -1
   struct KC { const float *row; float s; };
+  DEVI FC fctx(int, int f, int F) const {
+    FC c; c.one = (ones_row && f == F - 1); c.f = (f < F && !c.one) ? f : -1; return c;
+  }
   DEVI FC4 fctx4(int, int f, int F) const {
     FC4 c; c.f = f;
     const int real = F - (ones_row ? 1 : 0);
-    c.n = max(0, min(4, real - f));
+    c.n = f + 3 < real ? 4 : 0; // real % 4 == 0: a group is whole or empty
     c.one = (ones_row && F - 1 >= f && F - 1 < f + 4) ? F - 1 - f : -1;
     return c;
   }
   DEVI KC kctx(int z, int k, int kend) const {
     KC c;
-    if (k < kend) {
-      c.row = ptr + z * zstride + (long)k * ld;
-      c.s = scale ? scale[by_z ? z : (int)scale_div.div((uint32_t)k)] : 1.f;
-    } else { c.row = nullptr; c.s = 0.f; }
+    const bool ok = k < kend;
+    c.row = ok ? ptr + z * zstride + (long)k * ld : nullptr;
+    if (SCALED) {
+      const float sv = scale[ok ? (by_z ? z : (int)scale_div.div((uint32_t)k)) : 0];
+      c.s = ok ? sv : 0.f;
+    } else c.s = ok ? 1.f : 0.f;
     return c;
   }
+  DEVI float load(const FC &f, const KC &k) const {
+    const bool ok = k.row && f.f >= 0;
+    const float v = *(ok ? k.row + f.f : ptr);
+    return ok ? v * k.s : (f.one ? k.s : 0.f); // k.s is 0 for an invalid k
+  }
   DEVI float4 load4(const FC4 &f, const KC &k) const {
-    if (!k.row) return f4zero();
-    float4 v;
-    if (vec && f.n == 4) v = *reinterpret_cast<const float4 *>(k.row + f.f);
-    else {
-      v.x = f.n > 0 ? k.row[f.f] : (f.one == 0 ? 1.f : 0.f);
-      v.y = f.n > 1 ? k.row[f.f + 1] : (f.one == 1 ? 1.f : 0.f);
-      v.z = f.n > 2 ? k.row[f.f + 2] : (f.one == 2 ? 1.f : 0.f);
-      v.w = f.n > 3 ? k.row[f.f + 3] : (f.one == 3 ? 1.f : 0.f);
-    }
-    v.x *= k.s; v.y *= k.s; v.z *= k.s; v.w *= k.s;
-    return v;
-  }
-};
-
-// element (f, k) = table[idx[f]*ld + k]: gathered rows (embedding lookup fused into the operand)
-struct OpGatherRows {
-  static constexpr bool kLanesAlongK = true, kVec = true;
-  const float *table;
-  const int *idx;
-  int ld, vec;
-  void set(const float *t, const int *i, int ld_) { table = t; idx = i; ld = ld_; vec = aligned16(t) && (ld_ & 3) == 0; }
-  struct FC { const float *row; };
-  struct KC4 { int k, n; };
-  DEVI FC fctx(int, int f, int F) const {
-    FC c; c.row = f < F ? table + (long)idx[f] * ld : nullptr; return c;
-  }
-  DEVI KC4 kctx4(int, int k, int kend) const { KC4 c; c.k = k; c.n = min(4, kend - k); return c; }
-  DEVI float4 load4(const FC &f, const KC4 &k) const {
-    if (!f.row || k.n <= 0) return f4zero();
-    if (vec && k.n == 4) return *reinterpret_cast<const float4 *>(f.row + k.k);
-    float4 v = f4zero();
-    v.x = f.row[k.k];
-    if (k.n > 1) v.y = f.row[k.k + 1];
-    if (k.n > 2) v.z = f.row[k.k + 2];
-    if (k.n > 3) v.w = f.row[k.k + 3];
+    const bool ok = k.row && f.n == 4;
+    float4 v = *reinterpret_cast<const float4 *>(ok ? k.row + f.f : ptr);
+    v = ok ? f4scale(v, k.s) : f4zero();
+    if (f.one == 0) v.x = k.s;
+    if (f.one == 1) v.y = k.s;
+    if (f.one == 2) v.z = k.s;
+    if (f.one == 3) v.w = k.s;
     return v;
   }
 };
@@ -171,10 +166,10 @@ struct OpConvPatch {
     if constexpr (PIX_FIXED) return tap(k, kend); else return pix(z, k, kend);
   }
   DEVI float ld(const Pix &p, const Tap &t) const {
-    if (!p.base || t.off == -2) return 0.f;
-    if (t.off == -1) return 1.f;
-    int ih = p.ih0 + t.kh, iw = p.iw0 + t.kw;
-    return ((unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W) ? p.base[t.off] : 0.f;
+    const int ih = p.ih0 + t.kh, iw = p.iw0 + t.kw;
+    const bool ok = p.base && t.off >= 0 && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+    const float v = *(ok ? p.base + t.off : x);
+    return ok ? v : ((p.base && t.off == -1) ? 1.f : 0.f);
   }
   DEVI float load(const FC &f, const KC &k) const {
     if constexpr (PIX_FIXED) return ld(f, k); else return ld(k, f);
@@ -185,7 +180,7 @@ struct OpConvPatch {
 struct OpChanPix {
   static constexpr bool kLanesAlongK = true, kVec = false;
   const float *t;
-  const float *scale; // nullable
+  const float *scale; // always valid (ones when nothing is clipped)
   int D, P, by_z;
   FastDiv dP;
   struct FC { int off; };
@@ -193,15 +188,20 @@ struct OpChanPix {
   DEVI FC fctx(int, int f, int F) const { FC c; c.off = f < F ? f * P : -1; return c; }
   DEVI KC kctx(int z, int k, int kend) const {
     KC c;
-    if (k < kend) {
-      int b = by_z ? z : (int)dP.div(k);
-      int p = by_z ? k : k - b * P;
-      c.base = t + (long)b * D * P + p;
-      c.s = scale ? scale[b] : 1.f;
-    } else { c.base = nullptr; c.s = 0.f; }
+    const bool ok = k < kend;
+    const int kk = ok ? k : 0;
+    const int b = by_z ? z : (int)dP.div(kk);
+    const int p = by_z ? kk : kk - b * P;
+    c.base = ok ? t + (long)b * D * P + p : nullptr;
+    const float sv = scale[ok ? b : 0];
+    c.s = ok ? sv : 0.f;
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const { return (k.base && f.off >= 0) ? k.base[f.off] * k.s : 0.f; }
+  DEVI float load(const FC &f, const KC &k) const {
+    const bool ok = k.base && f.off >= 0;
+    const float v = *(ok ? k.base + f.off : t);
+    return ok ? v * k.s : 0.f;
+  }
 };
 
 // backward-data A operand: element (c, k=(d,kh,kw)) = W[d, c, kh, kw]
@@ -218,7 +218,11 @@ struct OpConvWeightT {
     else c.off = -1;
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const { return (f.off >= 0 && k.off >= 0) ? w[f.off + k.off] : 0.f; }
+  DEVI float load(const FC &f, const KC &k) const {
+    const bool ok = f.off >= 0 && k.off >= 0;
+    const float v = w[ok ? f.off + k.off : 0];
+    return ok ? v : 0.f;
+  }
 };
 
 // backward-data B operand: fixed = input pixel (b, ih, iw), k = (d, kh, kw):
@@ -227,6 +231,7 @@ struct OpConvDeltaGather {
   static constexpr bool kLanesAlongK = false, kVec = false;
   const float *delta;
   ConvGeom g;
+  FastDiv dS; // stride
   struct FC { const float *base; int ihp, iwp; };
   struct KC { int off, kh, kw; };
   DEVI FC fctx(int, int f, int F) const {
@@ -247,72 +252,75 @@ struct OpConvDeltaGather {
     return c;
   }
   DEVI float load(const FC &f, const KC &k) const {
-    if (!f.base || k.off < 0) return 0.f;
-    int th = f.ihp - k.kh, tw = f.iwp - k.kw;
-    if (th < 0 || tw < 0) return 0.f;
+    const int th = f.ihp - k.kh, tw = f.iwp - k.kw;
     int oh = th, ow = tw;
-    if (g.S != 1) {
-      oh = th / g.S; ow = tw / g.S;
-      if (oh * g.S != th || ow * g.S != tw) return 0.f;
+    bool ok = f.base && k.off >= 0 && th >= 0 && tw >= 0;
+    if (g.S != 1) { // uniform
+      oh = (int)dS.div((uint32_t)max(th, 0)); ow = (int)dS.div((uint32_t)max(tw, 0));
+      ok = ok && oh * g.S == th && ow * g.S == tw;
     }
-    if (oh >= g.OH || ow >= g.OW) return 0.f;
-    return f.base[k.off + oh * g.OW + ow];
+    ok = ok && oh < g.OH && ow < g.OW;
+    const float v = *(ok ? f.base + k.off + oh * g.OW + ow : delta);
+    return ok ? v : 0.f;
   }
 };
 
 // ---------------------------------------------------------------- LSTM
 
 // weight-gradient A operand of the LSTM: fixed r in [0, Din+H], k = step (b, t):
-//   r < Din        x_{b,t}[r]      = table[tok[b,t]*Din + r]   (or xin[(b,t)*Din + r] if no table)
+//   r < Din        x_{b,t}[r]      = xin[(b,t)*Din + r]   (the gathered embedding rows)
 //   r < Din + H    h_{b,t-1}[r-Din] (0 at t = 0), hs is [B, T, H]
 //   r == Din + H   1               (bias)
-// all times scale[b].  In batched launches (by_z) k = t within example z.
+// all times scale[b] (always a valid pointer).  In batched launches (by_z) k = t within example z.
+// float4 staging needs Din % 4 == 0 and H % 4 == 0: a group then lies inside x, inside h,
+// or is the tail group that starts with the ones row.
+template <bool VEC>
 struct OpLstmIn {
-  static constexpr bool kLanesAlongK = false, kVec = true;
-  const float *table; const int *tok;
+  static constexpr bool kLanesAlongK = false, kVec = VEC;
+  const float *xin;
   const float *hs;
   const float *scale;
-  int Din, H, T, by_z, vec;
+  int Din, H, T, by_z;
   FastDiv dT;
-  void set(const float *table_, const int *tok_, const float *hs_, const float *scale_, int Din_, int H_, int T_,
-           int by_z_) {
-    table = table_; tok = tok_; hs = hs_; scale = scale_; Din = Din_; H = H_; T = T_; by_z = by_z_; dT.init(T_);
-    vec = aligned16(table_) && aligned16(hs_) && (Din_ & 3) == 0 && (H_ & 3) == 0;
+  static bool can_vec(const float *x, const float *h, int Din_, int H_) {
+    return aligned16(x) && aligned16(h) && (Din_ & 3) == 0 && (H_ & 3) == 0;
   }
-  struct FC4 { int r, n; };
-  struct KC { const float *xrow; const float *hrow; float s; int valid; };
-  DEVI FC4 fctx4(int, int f, int F) const { FC4 c; c.r = f; c.n = max(0, min(4, F - f)); return c; }
+  void set(const float *xin_, const float *hs_, const float *scale_, int Din_, int H_, int T_, int by_z_) {
+    xin = xin_; hs = hs_; scale = scale_; Din = Din_; H = H_; T = T_; by_z = by_z_; dT.init(T_);
+  }
+  struct FC { int r; };
+  typedef FC FC4;
+  struct KC { const float *xrow; const float *hrow; float s; };
+  DEVI FC fctx(int, int f, int F) const { FC c; c.r = f < F ? f : -1; return c; }
+  DEVI FC4 fctx4(int, int f, int F) const { FC c; c.r = f < F ? f : -1; return c; }
   DEVI KC kctx(int z, int k, int kend) const {
     KC c;
-    if (k < kend) {
-      int b = by_z ? z : (int)dT.div(k);
-      int t = by_z ? k : k - b * T;
-      long bt = (long)b * T + t;
-      c.xrow = table + (long)tok[bt] * Din;
-      c.hrow = t > 0 ? hs + (bt - 1) * H : nullptr;
-      c.s = scale ? scale[b] : 1.f;
-      c.valid = 1;
-    } else { c.xrow = c.hrow = nullptr; c.s = 0.f; c.valid = 0; }
+    const bool ok = k < kend;
+    const int kk = ok ? k : 0;
+    const int b = by_z ? z : (int)dT.div(kk);
+    const int t = by_z ? kk : kk - b * T;
+    const long bt = (long)b * T + t;
+    c.xrow = ok ? xin + bt * Din : nullptr;
+    c.hrow = (ok && t > 0) ? hs + (bt - 1) * H : nullptr;
+    const float sv = scale[ok ? b : 0];
+    c.s = ok ? sv : 0.f;
     return c;
   }
-  DEVI float one(int r, const KC &k) const {
-    if (r < Din) return k.xrow[r];
-    if (r < Din + H) return k.hrow ? k.hrow[r - Din] : 0.f;
-    return 1.f;
+  DEVI float load(const FC &f, const KC &k) const {
+    const bool isx = k.xrow && f.r >= 0 && f.r < Din;
+    const bool ish = k.hrow && f.r >= Din && f.r < Din + H;
+    const float *p = isx ? k.xrow + f.r : (ish ? k.hrow + (f.r - Din) : xin);
+    float v = *p;
+    v = (isx || ish) ? v : ((k.xrow && f.r == Din + H) ? 1.f : 0.f);
+    return v * k.s;
   }
   DEVI float4 load4(const FC4 &f, const KC &k) const {
-    if (!k.valid || f.n <= 0) return f4zero();
-    float4 v;
-    if (vec && f.r + 3 < Din) v = *reinterpret_cast<const float4 *>(k.xrow + f.r);
-    else if (vec && f.r >= Din && f.r + 3 < Din + H)
-      v = k.hrow ? *reinterpret_cast<const float4 *>(k.hrow + (f.r - Din)) : f4zero();
-    else {
-      v.x = one(f.r, k);
-      v.y = f.n > 1 ? one(f.r + 1, k) : 0.f;
-      v.z = f.n > 2 ? one(f.r + 2, k) : 0.f;
-      v.w = f.n > 3 ? one(f.r + 3, k) : 0.f;
-    }
-    v.x *= k.s; v.y *= k.s; v.z *= k.s; v.w *= k.s;
-    return v;
+    const bool isx = k.xrow && f.r >= 0 && f.r + 3 < Din;
+    const bool ish = k.hrow && f.r >= Din && f.r + 3 < Din + H;
+    const float *p = isx ? k.xrow + f.r : (ish ? k.hrow + (f.r - Din) : xin);
+    float4 v = *reinterpret_cast<const float4 *>(p);
+    if (!(isx || ish)) v = f4zero();
+    if (k.xrow && f.r == Din + H) v.x = 1.f; // the ones row opens the tail group
+    return f4scale(v, k.s);
   }
 };
