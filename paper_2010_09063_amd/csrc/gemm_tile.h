@@ -50,7 +50,12 @@ struct TileCfg {
 DEVI float4 f4zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
 
 // Stages one operand tile (ROWS x BK) from its functor into registers, then into LDS
-// laid out k-major: tile[k*LD + row].  Four variants: lanes walk k or the fixed
+// laid out k-major: tile[k*LD + row].  A functor splits an element access in three:
+//   post(fc, kc)        what to do with the value (validity, scale, constant), from the contexts alone
+//   raw(fc, kc, post)   the load itself, unconditional, from a safe address when the element is invalid
+//   finish(raw, post)   the element value
+// fetch() only issues raw loads; finish() runs in stash(), after the MFMAs of the previous
+// tile, so nothing touches a loaded register (and forces a wait) while the loads are in flight.  Four variants: lanes walk k or the fixed
 // dimension (whichever is contiguous in memory), one float or one float4 per item.
 enum { LOAD_SCALAR_K = 0, LOAD_SCALAR_F = 1, LOAD_VEC_K = 2, LOAD_VEC_F = 3 };
 template <class Op>
@@ -67,6 +72,7 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_SCALAR_K> {
   static constexpr int LD = ROWS + 2;
   static constexpr int CNT = ROWS * BK / THREADS, RSTEP = THREADS / BK;
   typename Op::FC fc[CNT];
+  typename Op::Post post[CNT];
   float r[CNT];
   int kk, r0;
   DEVI void init(const Op &op, int z, int row0, int nrows) {
@@ -78,11 +84,11 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_SCALAR_K> {
   DEVI void fetch(const Op &op, int z, int k0, int kend) {
     typename Op::KC kc = op.kctx(z, k0 + kk, kend);
 #pragma unroll
-    for (int j = 0; j < CNT; ++j) r[j] = op.load(fc[j], kc);
+    for (int j = 0; j < CNT; ++j) { post[j] = op.post(fc[j], kc); r[j] = op.raw(fc[j], kc, post[j]); }
   }
-  DEVI void stash(float *tile) const {
+  DEVI void stash(const Op &op, float *tile) const {
 #pragma unroll
-    for (int j = 0; j < CNT; ++j) tile[kk * LD + r0 + j * RSTEP] = r[j];
+    for (int j = 0; j < CNT; ++j) tile[kk * LD + r0 + j * RSTEP] = op.finish(r[j], post[j]);
   }
 };
 
@@ -92,6 +98,7 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_SCALAR_F> {
   static constexpr int LD = ROWS + 2;
   static constexpr int CNT = ROWS * BK / THREADS, KSTEP = THREADS / ROWS;
   typename Op::FC fc;
+  typename Op::Post post[CNT];
   float r[CNT];
   int rr, kq;
   DEVI void init(const Op &op, int z, int row0, int nrows) {
@@ -103,12 +110,13 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_SCALAR_F> {
 #pragma unroll
     for (int j = 0; j < CNT; ++j) {
       typename Op::KC kc = op.kctx(z, k0 + kq + j * KSTEP, kend);
-      r[j] = op.load(fc, kc);
+      post[j] = op.post(fc, kc);
+      r[j] = op.raw(fc, kc, post[j]);
     }
   }
-  DEVI void stash(float *tile) const {
+  DEVI void stash(const Op &op, float *tile) const {
 #pragma unroll
-    for (int j = 0; j < CNT; ++j) tile[(kq + j * KSTEP) * LD + rr] = r[j];
+    for (int j = 0; j < CNT; ++j) tile[(kq + j * KSTEP) * LD + rr] = op.finish(r[j], post[j]);
   }
 };
 
@@ -120,6 +128,7 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_K> {
   static constexpr int KG = BK / 4, RSTEP = THREADS / KG, CNT = ROWS / RSTEP;
   static_assert(ROWS % RSTEP == 0 && CNT >= 1, "vec-k loader mapping");
   typename Op::FC fc[CNT];
+  typename Op::Post4 post[CNT];
   float4 r[CNT];
   int kg, r0;
   DEVI void init(const Op &op, int z, int row0, int nrows) {
@@ -131,13 +140,14 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_K> {
   DEVI void fetch(const Op &op, int z, int k0, int kend) {
     typename Op::KC4 kc = op.kctx4(z, k0 + 4 * kg, kend);
 #pragma unroll
-    for (int j = 0; j < CNT; ++j) r[j] = op.load4(fc[j], kc);
+    for (int j = 0; j < CNT; ++j) { post[j] = op.post4(fc[j], kc); r[j] = op.raw4(fc[j], kc, post[j]); }
   }
-  DEVI void stash(float *tile) const {
+  DEVI void stash(const Op &op, float *tile) const {
 #pragma unroll
     for (int j = 0; j < CNT; ++j) {
+      const float4 v = op.finish4(r[j], post[j]);
       float *d = tile + (4 * kg) * LD + r0 + j * RSTEP;
-      d[0] = r[j].x; d[LD] = r[j].y; d[2 * LD] = r[j].z; d[3 * LD] = r[j].w;
+      d[0] = v.x; d[LD] = v.y; d[2 * LD] = v.z; d[3 * LD] = v.w;
     }
   }
 };
@@ -150,6 +160,7 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_F> {
   static constexpr int FG = ROWS / 4, KSTEP = THREADS / FG, CNT = BK / KSTEP;
   static_assert(THREADS % FG == 0 && BK % KSTEP == 0 && CNT >= 1, "vec-f loader mapping");
   typename Op::FC4 fc;
+  typename Op::Post4 post[CNT];
   float4 r[CNT];
   int fg, kq;
   DEVI void init(const Op &op, int z, int row0, int nrows) {
@@ -161,13 +172,14 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_F> {
 #pragma unroll
     for (int j = 0; j < CNT; ++j) {
       typename Op::KC kc = op.kctx(z, k0 + kq + j * KSTEP, kend);
-      r[j] = op.load4(fc, kc);
+      post[j] = op.post4(fc, kc);
+      r[j] = op.raw4(fc, kc, post[j]);
     }
   }
-  DEVI void stash(float *tile) const {
+  DEVI void stash(const Op &op, float *tile) const {
 #pragma unroll
     for (int j = 0; j < CNT; ++j)
-      *reinterpret_cast<float4 *>(tile + (kq + j * KSTEP) * LD + 4 * fg) = r[j];
+      *reinterpret_cast<float4 *>(tile + (kq + j * KSTEP) * LD + 4 * fg) = op.finish4(r[j], post[j]);
   }
 };
 
@@ -216,8 +228,8 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
     lb.fetch(p.b, z, kbeg, kend);
   }
   for (int k0 = kbeg; k0 < kend; k0 += BK) {
-    la.stash(As);
-    lb.stash(Bs);
+    la.stash(p.a, As);
+    lb.stash(p.b, Bs);
     __syncthreads();
     if (k0 + BK < kend) {
       la.fetch(p.a, z, k0 + BK, kend);

@@ -42,16 +42,16 @@ struct OpRowMajor {
   }
   DEVI KC kctx(int, int k, int kend) const { KC c; c.k = k < kend ? k : -1; return c; }
   DEVI KC4 kctx4(int, int k, int kend) const { KC c; c.k = k < kend ? k : -1; return c; } // K % 4 == 0
-  DEVI float load(const FC &f, const KC &k) const {
-    const bool ok = f.row && k.k >= 0;
-    const float v = *(ok ? f.row + k.k : ptr);
-    return ok ? v : 0.f;
+  typedef bool Post;
+  typedef bool Post4;
+  DEVI Post post(const FC &f, const KC &k) const { return f.row && k.k >= 0; }
+  DEVI Post4 post4(const FC &f, const KC4 &k) const { return f.row && k.k >= 0; }
+  DEVI float raw(const FC &f, const KC &k, Post ok) const { return *(ok ? f.row + k.k : ptr); }
+  DEVI float4 raw4(const FC &f, const KC4 &k, Post4 ok) const {
+    return *reinterpret_cast<const float4 *>(ok ? f.row + k.k : ptr);
   }
-  DEVI float4 load4(const FC &f, const KC4 &k) const {
-    const bool ok = f.row && k.k >= 0;
-    const float4 v = *reinterpret_cast<const float4 *>(ok ? f.row + k.k : ptr);
-    return ok ? v : f4zero();
-  }
+  DEVI float finish(float v, Post ok) const { return ok ? v : 0.f; }
+  DEVI float4 finish4(float4 v, Post4 ok) const { return ok ? v : f4zero(); }
 };
 
 // element (f, k) = ptr[z*zstride + k*ld + f] * scale[k / scale_div]    (f contiguous);
@@ -96,19 +96,27 @@ struct OpKMajor {
     } else c.s = ok ? 1.f : 0.f;
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    const bool ok = k.row && f.f >= 0;
-    const float v = *(ok ? k.row + f.f : ptr);
-    return ok ? v * k.s : (f.one ? k.s : 0.f); // k.s is 0 for an invalid k
+  struct Post { float s; int mode; };  // mode 1: value * s; 2: the ones row (= s); 0: zero
+  struct Post4 { float s; int ok, one; };
+  DEVI Post post(const FC &f, const KC &k) const {
+    Post p; p.s = k.s; // 0 for an invalid k
+    p.mode = (k.row && f.f >= 0) ? 1 : (f.one ? 2 : 0);
+    return p;
   }
-  DEVI float4 load4(const FC4 &f, const KC &k) const {
-    const bool ok = k.row && f.n == 4;
-    float4 v = *reinterpret_cast<const float4 *>(ok ? k.row + f.f : ptr);
-    v = ok ? f4scale(v, k.s) : f4zero();
-    if (f.one == 0) v.x = k.s;
-    if (f.one == 1) v.y = k.s;
-    if (f.one == 2) v.z = k.s;
-    if (f.one == 3) v.w = k.s;
+  DEVI Post4 post4(const FC4 &f, const KC &k) const {
+    Post4 p; p.s = k.s; p.ok = k.row && f.n == 4; p.one = f.one; return p;
+  }
+  DEVI float raw(const FC &f, const KC &k, const Post &p) const { return *(p.mode == 1 ? k.row + f.f : ptr); }
+  DEVI float4 raw4(const FC4 &f, const KC &k, const Post4 &p) const {
+    return *reinterpret_cast<const float4 *>(p.ok ? k.row + f.f : ptr);
+  }
+  DEVI float finish(float v, const Post &p) const { return p.mode == 1 ? v * p.s : (p.mode == 2 ? p.s : 0.f); }
+  DEVI float4 finish4(float4 v, const Post4 &p) const {
+    v = p.ok ? f4scale(v, p.s) : f4zero();
+    if (p.one == 0) v.x = p.s;
+    if (p.one == 1) v.y = p.s;
+    if (p.one == 2) v.z = p.s;
+    if (p.one == 3) v.w = p.s;
     return v;
   }
 };
@@ -165,15 +173,19 @@ struct OpConvPatch {
   DEVI KC kctx(int z, int k, int kend) const {
     if constexpr (PIX_FIXED) return tap(k, kend); else return pix(z, k, kend);
   }
-  DEVI float ld(const Pix &p, const Tap &t) const {
+  typedef int Post; // 1: the pixel; 2: the constant 1 of the bias tap; 0: zero
+  DEVI Post pst(const Pix &p, const Tap &t) const {
     const int ih = p.ih0 + t.kh, iw = p.iw0 + t.kw;
     const bool ok = p.base && t.off >= 0 && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
-    const float v = *(ok ? p.base + t.off : x);
-    return ok ? v : ((p.base && t.off == -1) ? 1.f : 0.f);
+    return ok ? 1 : ((p.base && t.off == -1) ? 2 : 0);
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    if constexpr (PIX_FIXED) return ld(f, k); else return ld(k, f);
+  DEVI Post post(const FC &f, const KC &k) const {
+    if constexpr (PIX_FIXED) return pst(f, k); else return pst(k, f);
   }
+  DEVI float raw(const FC &f, const KC &k, Post m) const {
+    if constexpr (PIX_FIXED) return *(m == 1 ? f.base + k.off : x); else return *(m == 1 ? k.base + f.off : x);
+  }
+  DEVI float finish(float v, Post m) const { return m == 1 ? v : (m == 2 ? 1.f : 0.f); }
 };
 
 // element (d, q) = T[b, d, p] * scale[b]  for pixel q = (b, p); T is [B, D, P].  Lanes walk pixels.
@@ -197,11 +209,10 @@ struct OpChanPix {
     c.s = ok ? sv : 0.f;
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    const bool ok = k.base && f.off >= 0;
-    const float v = *(ok ? k.base + f.off : t);
-    return ok ? v * k.s : 0.f;
-  }
+  struct Post { float s; int ok; };
+  DEVI Post post(const FC &f, const KC &k) const { Post p; p.s = k.s; p.ok = k.base && f.off >= 0; return p; }
+  DEVI float raw(const FC &f, const KC &k, const Post &p) const { return *(p.ok ? k.base + f.off : t); }
+  DEVI float finish(float v, const Post &p) const { return p.ok ? v * p.s : 0.f; }
 };
 
 // backward-data A operand: element (c, k=(d,kh,kw)) = W[d, c, kh, kw]
@@ -218,11 +229,10 @@ struct OpConvWeightT {
     else c.off = -1;
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    const bool ok = f.off >= 0 && k.off >= 0;
-    const float v = w[ok ? f.off + k.off : 0];
-    return ok ? v : 0.f;
-  }
+  typedef bool Post;
+  DEVI Post post(const FC &f, const KC &k) const { return f.off >= 0 && k.off >= 0; }
+  DEVI float raw(const FC &f, const KC &k, Post ok) const { return w[ok ? f.off + k.off : 0]; }
+  DEVI float finish(float v, Post ok) const { return ok ? v : 0.f; }
 };
 
 // backward-data B operand: fixed = input pixel (b, ih, iw), k = (d, kh, kw):
@@ -251,18 +261,17 @@ struct OpConvDeltaGather {
     } else { c.off = -1; c.kh = c.kw = 0; }
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
+  typedef int Post; // offset of the element inside delta's image block, or -1
+  DEVI Post post(const FC &f, const KC &k) const {
     const int th = f.ihp - k.kh, tw = f.iwp - k.kw;
-    int oh = th, ow = tw;
-    bool ok = f.base && k.off >= 0 && th >= 0 && tw >= 0;
-    if (g.S != 1) { // uniform
-      oh = (int)dS.div((uint32_t)max(th, 0)); ow = (int)dS.div((uint32_t)max(tw, 0));
-      ok = ok && oh * g.S == th && ow * g.S == tw;
-    }
-    ok = ok && oh < g.OH && ow < g.OW;
-    const float v = *(ok ? f.base + k.off + oh * g.OW + ow : delta);
-    return ok ? v : 0.f;
+    // S == 1 divides trivially; the multiply-shift division is exact for any S
+    const int oh = (int)dS.div((uint32_t)max(th, 0)), ow = (int)dS.div((uint32_t)max(tw, 0));
+    const bool ok = f.base && k.off >= 0 && th >= 0 && tw >= 0 && oh * g.S == th && ow * g.S == tw &&
+                    oh < g.OH && ow < g.OW;
+    return ok ? k.off + oh * g.OW + ow : -1;
   }
+  DEVI float raw(const FC &f, const KC &, Post o) const { return *(o >= 0 ? f.base + o : delta); }
+  DEVI float finish(float v, Post o) const { return o >= 0 ? v : 0.f; }
 };
 
 // ---------------------------------------------------------------- LSTM
@@ -306,21 +315,34 @@ struct OpLstmIn {
     c.s = ok ? sv : 0.f;
     return c;
   }
-  DEVI float load(const FC &f, const KC &k) const {
-    const bool isx = k.xrow && f.r >= 0 && f.r < Din;
-    const bool ish = k.hrow && f.r >= Din && f.r < Din + H;
-    const float *p = isx ? k.xrow + f.r : (ish ? k.hrow + (f.r - Din) : xin);
-    float v = *p;
-    v = (isx || ish) ? v : ((k.xrow && f.r == Din + H) ? 1.f : 0.f);
-    return v * k.s;
+  struct Post { float s; int mode; }; // mode 1: x row; 2: h row; 3: the ones row; 0: zero
+  typedef Post Post4;
+  DEVI Post post(const FC &f, const KC &k) const {
+    Post p; p.s = k.s;
+    p.mode = (k.xrow && f.r >= 0 && f.r < Din) ? 1
+           : ((k.hrow && f.r >= Din && f.r < Din + H) ? 2 : ((k.xrow && f.r == Din + H) ? 3 : 0));
+    return p;
   }
-  DEVI float4 load4(const FC4 &f, const KC &k) const {
-    const bool isx = k.xrow && f.r >= 0 && f.r + 3 < Din;
-    const bool ish = k.hrow && f.r >= Din && f.r + 3 < Din + H;
-    const float *p = isx ? k.xrow + f.r : (ish ? k.hrow + (f.r - Din) : xin);
-    float4 v = *reinterpret_cast<const float4 *>(p);
-    if (!(isx || ish)) v = f4zero();
-    if (k.xrow && f.r == Din + H) v.x = 1.f; // the ones row opens the tail group
-    return f4scale(v, k.s);
+  DEVI Post4 post4(const FC4 &f, const KC &k) const {
+    Post p; p.s = k.s;
+    p.mode = (k.xrow && f.r >= 0 && f.r + 3 < Din) ? 1
+           : ((k.hrow && f.r >= Din && f.r + 3 < Din + H) ? 2 : ((k.xrow && f.r == Din + H) ? 3 : 0));
+    return p; // mode 3: the ones row opens the tail group, the other three are past the operand
+  }
+  DEVI const float *addr(int r, const KC &k, int mode) const {
+    return mode == 1 ? k.xrow + r : (mode == 2 ? k.hrow + (r - Din) : xin);
+  }
+  DEVI float raw(const FC &f, const KC &k, const Post &p) const { return *addr(f.r, k, p.mode); }
+  DEVI float4 raw4(const FC4 &f, const KC &k, const Post4 &p) const {
+    return *reinterpret_cast<const float4 *>(addr(f.r, k, p.mode));
+  }
+  DEVI float finish(float v, const Post &p) const {
+    return (p.mode == 1 || p.mode == 2) ? v * p.s : (p.mode == 3 ? p.s : 0.f);
+  }
+  DEVI float4 finish4(float4 v, const Post4 &p) const {
+    if (p.mode == 1 || p.mode == 2) return f4scale(v, p.s);
+    float4 z = f4zero();
+    if (p.mode == 3) z.x = p.s;
+    return z;
   }
 };
