@@ -181,22 +181,33 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
     }
   }
 
+  // epilogue: bias + activation (forward) or the derivative of the producing activation
+  // (backward-data).  The 16 side loads of a block (bias / a_prev) are issued together from
+  // safe addresses before any of them is used.
+  const bool fwd = a.bias != nullptr;
+  const float *side = fwd ? a.bias : (a.act ? a.a_prev : a.x);
 #pragma unroll
   for (int j = 0; j < PB; ++j) {
-    if (ooff[j] < 0) continue;
 #pragma unroll
-    for (int i = 0; i < DB; ++i)
+    for (int i = 0; i < DB; ++i) {
+      float sv[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (m < a.M) {
-          const long o = ooff[j] + (long)m * OHW;
+        const bool ok = ooff[j] >= 0 && m < a.M;
+        sv[r] = side[ok ? (fwd ? (long)m : ooff[j] + (long)m * OHW) : 0];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+        if (ooff[j] >= 0 && m < a.M) {
           float v = acc[i][j][r];
-          if (a.bias) v = act_apply(a.act, v + a.bias[m]);
-          else if (a.act) v *= act_deriv_from_out(a.act, a.a_prev[o]);
-          a.out[o] = v;
+          if (fwd) v = act_apply(a.act, v + sv[r]);
+          else if (a.act) v *= act_deriv_from_out(a.act, sv[r]);
+          a.out[ooff[j] + (long)m * OHW] = v;
         }
       }
+    }
   }
 }
 
@@ -229,7 +240,7 @@ struct ConvWgArgs {
 // their accumulators are summed through LDS at the end.
 // CLIP: the clipped-sum mode (a.mode == 1); the norm mode never touches the clip factors.
 template <int KH, int KW, int DB, bool FLATC, bool CLIP>
-__global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
+__global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
   constexpr int KK = KH * KW;
   constexpr int WD = FLATC ? 1 : (DB >= 4 ? 4 : DB), WN = FLATC ? 1 : 4 / WD; // waves along d and along taps
   constexpr int DBW = DB / WD, NBW = FLATC ? 1 : (KK + WN - 1) / WN;
@@ -313,6 +324,8 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
   const int col0 = FLATC ? 2 * wave : 0, colstep = FLATC ? 8 : 2;
 
   float4 xr[XV], dr[DV];
+  float dsv[DV];        // clip factor of each Delta item (CLIP), applied when the item is written to LDS
+  unsigned xok = 0, dok = 0; // validity bits of the fetched items: nothing touches a loaded register before the stash
   auto prefetch = [&](int b, int nimg, int r0, int rows) {
     const long xb = ((long)b * a.C + c0) * HW + (long)r0 * a.W;
     // unconditional loads with a safe address for invalid items (see conv_s1_kernel)
@@ -321,20 +334,17 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
       const int img = x_ir[j] >> 16, rr = x_ir[j] & 0xffff;
       const int ih = r0 + rr - a.pad;
       const bool ok = x_lds[j] >= 0 && img < nimg && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H;
-      const float4 v = *reinterpret_cast<const float4 *>(a.x + (ok ? xb + x_goff[j] : 0));
-      xr[j] = ok ? v : f4zero();
+      xr[j] = *reinterpret_cast<const float4 *>(a.x + (ok ? xb + x_goff[j] : 0));
+      xok = ok ? (xok | (1u << j)) : (xok & ~(1u << j));
     }
     const long db_ = (long)b * a.D * OHW + (long)r0 * a.OW;
 #pragma unroll
     for (int j = 0; j < DV; ++j) {
       const int img = d_ir[j] >> 16, r = d_ir[j] & 0xffff;
       const bool ok = d_goff[j] >= 0 && img < nimg && r < rows;
-      const float4 v = *reinterpret_cast<const float4 *>(a.delta + (ok ? db_ + d_goff[j] : 0));
-      float sv = 1.f;
-      if (CLIP) sv = a.scale[ok ? b + img : 0];
-      float4 w = f4zero();
-      if (ok) { w.x = v.x * sv; w.y = v.y * sv; w.z = v.z * sv; w.w = v.w * sv; }
-      dr[j] = w;
+      dr[j] = *reinterpret_cast<const float4 *>(a.delta + (ok ? db_ + d_goff[j] : 0));
+      if (CLIP) dsv[j] = a.scale[ok ? b + img : 0];
+      dok = ok ? (dok | (1u << j)) : (dok & ~(1u << j));
     }
   };
 
@@ -348,14 +358,17 @@ __global__ __launch_bounds__(256) void conv_s1_wgrad_kernel(const ConvWgArgs a) 
 #pragma unroll
     for (int j = 0; j < XV; ++j)
       if (x_lds[j] >= 0) {
+        const float4 v = ((xok >> j) & 1u) ? xr[j] : f4zero();
         float *d = Xl + x_lds[j];
-        d[0] = xr[j].x; d[1] = xr[j].y; d[2] = xr[j].z; d[3] = xr[j].w;
+        d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
       }
 #pragma unroll
     for (int j = 0; j < DV; ++j)
       if (d_lds[j] >= 0) {
+        const float sv = ((dok >> j) & 1u) ? (CLIP ? dsv[j] : 1.f) : 0.f;
+        const float4 v = ((dok >> j) & 1u) ? dr[j] : f4zero();
         float *d = Dl + d_lds[j];
-        d[0] = dr[j].x; d[1] = dr[j].y; d[2] = dr[j].z; d[3] = dr[j].w;
+        d[0] = v.x * sv; d[1] = v.y * sv; d[2] = v.z * sv; d[3] = v.w * sv;
       }
     __syncthreads();
     // advance to the next chunk and start fetching it
