@@ -242,8 +242,13 @@ struct ConvWgArgs {
 template <int KH, int KW, int DB, bool FLATC, bool CLIP>
 __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(const ConvWgArgs a) {
   constexpr int KK = KH * KW;
-  constexpr int WD = FLATC ? 1 : (DB >= 4 ? 4 : DB), WN = FLATC ? 1 : 4 / WD; // waves along d and along taps
+  // the four waves: WD along output-channel blocks, WN along taps, WK interleaved over pixel pairs
+  // (waves that share (wd, wn) see disjoint pixel pairs; their accumulators are summed through LDS)
+  constexpr int WD = FLATC ? 1 : (DB >= 4 ? 4 : DB);
+  constexpr int WN = FLATC ? 1 : (DB >= 4 ? 1 : 2);
+  constexpr int WK = 4 / (WD * WN);
   constexpr int DBW = DB / WD, NBW = FLATC ? 1 : (KK + WN - 1) / WN;
+  static_assert(WD * WN * WK == 4 && DBW == 1, "wave decomposition");
   constexpr int DT = 32 * DB;
   constexpr int XV = CONV_WG_XV;
   constexpr int DV = (DB == 1 && !FLATC) ? 4 : 8;   // float4 Delta items per thread: DT*PCH/4 <= DV*256
@@ -256,7 +261,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
   __shared__ float red[4];
   __shared__ float rsum[256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
-  const int wd = FLATC ? 0 : wave / WN, wn = FLATC ? 0 : wave - wd * WN;
+  const int wd = wave / (WN * WK), wn = (wave / WK) % WN, wk = wave % WK;
   const int cb = blockIdx.x, c0 = cb * 32;
   const int HW = a.H * a.W, OHW = a.OH * a.OW;
   int bbeg, bend;
@@ -321,7 +326,8 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
     tapoff[0] = 0;
     xlane = (tapok[0] ? ch * a.t.XPLANE + kh * a.t.LDW + kw : 0) + lk;
   }
-  const int col0 = FLATC ? 2 * wave : 0, colstep = FLATC ? 8 : 2;
+  const int col0 = 2 * wk;
+  constexpr int colstep = 2 * WK;
 
   float4 xr[XV], dr[DV];
   float dsv[DV];        // clip factor of each Delta item (CLIP), applied when the item is written to LDS
@@ -419,19 +425,26 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       for (int s = 0; s < NSL; ++s) bias_d += rsum[s * DT + tid];
     }
   }
-  if (FLATC) { // sum the four waves' accumulators (each saw a quarter of the pixel pairs) into wave 0
+  if (WK > 1) { // sum the accumulators of the waves that split the pixel pairs into the wk == 0 wave
     __syncthreads();
-    float *xs = smem; // [3][16][64], reusing the staging area
-    if (wave > 0)
+    float *xs = smem; // [(WD*WN) groups][WK-1][NBW*16][64], reusing the staging area
+    const int grp = wave / WK;
+    if (wk > 0)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) xs[((wave - 1) * 16 + r) * 64 + lane] = acc[0][0][r];
+      for (int j = 0; j < NBW; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          xs[(((grp * (WK - 1) + wk - 1) * NBW + j) * 16 + r) * 64 + lane] = acc[0][j][r];
     __syncthreads();
-    if (wave == 0)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[0][0][r] += xs[r * 64 + lane] + xs[(16 + r) * 64 + lane] + xs[(32 + r) * 64 + lane];
-    else
+    for (int j = 0; j < NBW; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
+      for (int r = 0; r < 16; ++r) {
+        if (wk == 0) {
+#pragma unroll
+          for (int q = 0; q < WK - 1; ++q) acc[0][j][r] += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
+        } else acc[0][j][r] = 0.f;
+      }
   }
   // accumulator: lane column = input channel c0 + li (FLATC: flattened channel*KK + tap); rows = output channels
   const int c = c0 + li;
@@ -442,7 +455,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (wave == 0 && li < CKK && d < a.D) part += acc[0][0][r] * acc[0][0][r];
+        if (wk == 0 && li < CKK && d < a.D) part += acc[0][0][r] * acc[0][0][r];
       }
       if (tid < a.D) part += bias_d * bias_d;
 #pragma unroll
@@ -455,7 +468,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (wave == 0 && li < CKK && d < a.D) part[(long)d * CKK + li] = acc[0][0][r];
+        if (wk == 0 && li < CKK && d < a.D) part[(long)d * CKK + li] = acc[0][0][r];
       }
       if (tid < a.D) part[(long)a.D * CKK + tid] = bias_d;
     }
@@ -471,7 +484,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-          if (tap < KK && c < a.C && d < a.D) part += acc[i][j][r] * acc[i][j][r];
+          if (wk == 0 && tap < KK && c < a.C && d < a.D) part += acc[i][j][r] * acc[i][j][r];
         }
       }
     if (cb == 0 && tid < a.D) part += bias_d * bias_d;
@@ -490,7 +503,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-          if (tap < KK && c < a.C && d < a.D) part[((long)d * a.C + c) * KK + tap] = acc[i][j][r];
+          if (wk == 0 && tap < KK && c < a.C && d < a.D) part[((long)d * a.C + c) * KK + tap] = acc[i][j][r];
         }
       }
     if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = bias_d;

@@ -271,7 +271,9 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       long lds_n = (long)xch * l.t_wgn.XPLANE + 32l * db * ((l.t_wgn.NIMG * l.t_wgn.TR * g.OW) | 1);
       long lds_c = (long)xch * l.t_wgc.XPLANE + 32l * db * ((l.t_wgc.NIMG * l.t_wgc.TR * g.OW) | 1);
       bool fits = lds_n * 4 <= 64 * 1024 && lds_c * 4 <= 64 * 1024;
-      if (flat && (lds_n < 3 * 16 * 64 || lds_c < 3 * 16 * 64)) fits = false; // room for the cross-wave sum
+      // room in the staging area for the cross-wave sum of the waves that split the pixel pairs
+      const long xs = flat ? 3l * 16 * 64 : (db == 1 ? 2l * 5 * 16 * 64 : 0);
+      if (lds_n < xs || lds_c < xs) fits = false;
       for (const ConvTile *t : {&l.t_wgn, &l.t_wgc}) {
         const int pch = t->NIMG * t->TR * g.OW;
         if ((long)xch * t->NIMG * (t->TR + 2) * (g.W / 4) > CONV_WG_XV * 256) fits = false; // input items per thread
