@@ -143,3 +143,92 @@ def test_argument_errors():
     bad = W.model(W.image_input(5), [W.dense(6, 3)], 3)
     with pytest.raises(DpStepError):
         DpStep(bad, 4)
+
+
+def test_generic_convolution_path_matches_too(monkeypatch):
+    """DP_STEP_GENERIC_CONV=1 keeps 3x3 stride-1 convolutions on the functor contraction
+    (the path every other kernel size / stride takes)."""
+    monkeypatch.setenv("DP_STEP_GENERIC_CONV", "1")
+    m = TINY["tiny_conv3"]
+    x, y, theta = _case(m, 9, seed=21)
+    _check_all_regimes(m, x, y, theta, "tiny_conv3/generic")
+    wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/generic")
+
+
+def test_large_vocabulary_embedding_path():
+    """Vocabularies above the LDS-histogram limit take the plain-atomic bucket kernels."""
+    m = W.cfg5_lstm(vocab=20000, seq_len=24, dim=20, hidden=33)
+    rng = np.random.default_rng(8)
+    x, y = W.make_inputs(m, 11, rng)
+    theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
+    _check_all_regimes(m, x, y, theta, "lstm/V20000/H33")
+
+
+@pytest.mark.parametrize("hidden", [7, 64, 128])
+def test_lstm_hidden_sizes(hidden):
+    m = W.cfg5_lstm(vocab=50, seq_len=9, dim=12, hidden=hidden)
+    rng = np.random.default_rng(hidden)
+    x, y = W.make_inputs(m, 5, rng, zipf_exponent=0.5)
+    theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
+    _check_all_regimes(m, x, y, theta, f"lstm/H{hidden}")
+
+
+def test_unaligned_device_pointers():
+    """params / x that are not 16-byte aligned fall back to scalar operand staging."""
+    import torch
+    from paper_2010_09063_amd import DpStep
+    for name, batch in (("cfg2_mlp", 33), ("tiny_conv3", 6)):
+        if name in TINY:
+            m = TINY[name]
+            x, y, theta = _case(m, batch, seed=3)
+        else:
+            wl = W.make_workload(name, batch=batch, seed=3, bias_scale=0.2)
+            m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+        x, y, _ = clear_pool_examples(m, theta, x, y, O.dp_step)
+        ref = O.dp_step(m, theta, x, y, 0.7, 0.0, 0)
+        dev = torch.device("cuda:0")
+        st = DpStep(m, batch)
+        pbuf = torch.zeros(theta.size + 1, device=dev)
+        xbuf = torch.zeros(x.size + 1, device=dev)
+        pbuf[1:] = torch.from_numpy(theta).to(dev)
+        xbuf[1:] = torch.from_numpy(x.reshape(-1)).to(dev)
+        tp, tx = pbuf[1:], xbuf[1:]
+        assert tp.data_ptr() % 16 != 0 and tx.data_ptr() % 16 != 0
+        ty = torch.from_numpy(y).to(dev)
+        out = torch.empty(theta.size, device=dev)
+        st.dp_step(tp, tx, ty, batch, 0.7, 0.0, 0, out)
+        torch.cuda.synchronize()
+        assert rel_l2(out.cpu().numpy(), ref["clipped_sum"]) <= TOL, name
+        st.dp_step_free()
+
+
+def test_repeatable_and_profile_hook():
+    """Two calls give bit-identical results (fixed reduction order; no float atomics outside the
+    embedding's hot tokens), and the per-kernel timing hook reports every launch."""
+    import torch
+    from paper_2010_09063_amd import DpStep
+    wl = W.make_workload("cfg3_small_cnn", batch=64, seed=9)
+    m = wl["model"]
+    dev = torch.device("cuda:0")
+    st = DpStep(m, 64)
+    tp = torch.from_numpy(wl["params"]).to(dev)
+    tx = torch.from_numpy(wl["x"]).to(dev)
+    ty = torch.from_numpy(wl["y"]).to(dev)
+    o1 = torch.empty(st.num_params, device=dev)
+    o2 = torch.empty(st.num_params, device=dev)
+    st.dp_step(tp, tx, ty, 64, 1.0, 1.1, 7, o1)
+    st.dp_step_profile(True)
+    st.dp_step(tp, tx, ty, 64, 1.0, 1.1, 7, o2)
+    rows = st.dp_step_profile_read()
+    st.dp_step_profile(False)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    names = {r[0].split("#")[0] for r in rows}
+    assert {"conv_fwd", "conv_wgrad_norm", "conv_clipped_sum", "dense_fwd", "clip_factor", "finalize_noise"} <= names
+    assert all(r[1] >= 1 and r[2] > 0 for r in rows)
+    # a different seed changes the noise, the same seed does not
+    st.dp_step(tp, tx, ty, 64, 1.0, 1.1, 8, o2)
+    torch.cuda.synchronize()
+    assert not torch.equal(o1, o2)
+    st.dp_step_free()
