@@ -36,7 +36,7 @@ template <class A_, class B_>
 struct ProbBase {
   typedef A_ A;
   typedef B_ B;
-  int M, N, K, k_chunk, tiles_n;
+  int M, N, K, k_chunk, tiles_n, tiles, splits, groups;
   A a;
   B b;
 };

@@ -184,7 +184,7 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_F> {
 };
 
 // Problem P provides:
-//   int M, N, K, k_chunk (multiple of 32), tiles_n;
+//   int M, N, K, k_chunk (multiple of 32), tiles_n, tiles, splits, groups (set by the launcher);
 //   A a; B b;               operand functors (kLanesAlongK, kVec; FC/KC contexts, load or load4)
 //   static constexpr bool kReduce;
 //   kReduce == false:  void store(int z, int split, int m, int n, float acc) const;
@@ -199,8 +199,29 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
   __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
   __shared__ float red[Cfg::WM * Cfg::WN];
 
-  const int z = blockIdx.z, split = blockIdx.y;
-  const int tile = blockIdx.x;
+  // XCD-aware placement.  Workgroups go round-robin to the 8 XCDs (each with its own L2) in
+  // order of their linear id, so id % 8 names the XCD.  All tiles of one (batch item, K split)
+  // read the same operand data: they are given to ONE XCD, back to back, so that data comes
+  // from HBM once and from that L2 afterwards.  With fewer than 8 such groups the tiles of a
+  // group are cut into 8 contiguous bands instead (neighbouring tiles share an operand).
+  int z, split, tile;
+  {
+    const int L = blockIdx.x, xcd = L & 7, j = L >> 3;
+    const int ngroups = p.groups;
+    if (ngroups >= 8) {
+      const int q = j / p.tiles;
+      const int g = q * 8 + xcd;
+      tile = j - q * p.tiles;
+      if (g >= ngroups) return;
+      z = g / p.splits; split = g - z * p.splits;
+    } else {
+      const int band = (p.tiles + 7) >> 3;
+      const int g = j / band;
+      tile = xcd * band + (j - g * band);
+      if (g >= ngroups || tile >= p.tiles) return;
+      z = g / p.splits; split = g - z * p.splits;
+    }
+  }
   const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
   const int m0 = tm * BM, n0 = tn * BN;
   const int kbeg = split * p.k_chunk;
@@ -276,7 +297,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
     if (threadIdx.x == 0) {
       float s = 0.f;
       for (int w = 0; w < Cfg::WM * Cfg::WN; ++w) s += red[w];
-      p.store_tile(z, split * gridDim.x + tile, s);
+      p.store_tile(z, split * p.tiles + tile, s);
     }
   }
 }
@@ -313,7 +334,13 @@ static inline GemmShape pick_tile(int M, int N, long other_blocks) {
 template <class P, class Launcher>
 static inline void launch_gemm_shape(P p, GemmShape s, int batch, int splits, Launcher &&L, const char *label) {
   p.tiles_n = s.tiles_n;
-  dim3 grid(s.tiles_m * s.tiles_n, splits, batch);
+  p.tiles = s.tiles_m * s.tiles_n;
+  p.splits = splits;
+  p.groups = splits * batch;
+  // ngroups >= 8: ceil(groups/8) rounds of 8 groups x tiles; else groups x 8 bands of ceil(tiles/8)
+  const long nblk = p.groups >= 8 ? (long)ceil_div(p.groups, 8) * 8 * p.tiles
+                                  : (long)p.groups * 8 * ceil_div(p.tiles, 8);
+  dim3 grid((unsigned)nblk);
 #define DP_GEMM_CASE(bm_, bn_, wm_, wn_)                                                    \
   if (s.bm == bm_ && s.bn == bn_) {                                                         \
     typedef TileCfg<bm_, bn_, wm_, wn_> Cfg;                                                \
