@@ -264,9 +264,9 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
   const int wd = wave / (WN * WK), wn = (wave / WK) % WN, wk = wave % WK;
   const int cb = blockIdx.x, c0 = cb * 32;
   const int HW = a.H * a.W, OHW = a.OH * a.OW;
-  int bbeg, bend;
-  if (!CLIP) { bbeg = blockIdx.y; bend = bbeg + 1; }
-  else { bbeg = blockIdx.y * a.ex_per_block; bend = min(a.B, bbeg + a.ex_per_block); }
+  // examples bbeg .. bend-1 belong to this block: summed into one partial (CLIP), or one after the
+  // other with a squared-norm epilogue each, the next example's data in flight meanwhile (norm mode)
+  const int bbeg = blockIdx.y * a.ex_per_block, bend = min(a.B, bbeg + a.ex_per_block);
   const int nimg_max = !CLIP ? 1 : a.t.NIMG;
 
   // zero the staged input once: the left / right halo columns are never written again
@@ -354,6 +354,103 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
     }
   };
 
+  // bias gradient of the examples summed so far: combine the slices
+  auto bias_total = [&]() {
+    float bias_d = 0.f;
+    if (cb == 0) {
+      rsum[tid] = rowsum;
+      __syncthreads();
+      if (tid < DT) {
+#pragma unroll
+        for (int s = 0; s < NSL; ++s) bias_d += rsum[s * DT + tid];
+      }
+    }
+    return bias_d;
+  };
+  // sum the accumulators of the waves that split the pixel pairs into the wk == 0 wave (the others end at zero)
+  auto wave_total = [&]() {
+    if (WK > 1) {
+      __syncthreads(); // staging area no longer read
+      float *xs = smem; // [(WD*WN) groups][WK-1][NBW*16][64], reusing the staging area
+      const int grp = wave / WK;
+      if (wk > 0)
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            xs[(((grp * (WK - 1) + wk - 1) * NBW + j) * 16 + r) * 64 + lane] = acc[0][j][r];
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (wk == 0) {
+#pragma unroll
+            for (int q = 0; q < WK - 1; ++q) acc[0][j][r] += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
+          } else acc[0][j][r] = 0.f;
+        }
+        __builtin_amdgcn_sched_barrier(0); // one block of 16 loads in flight at a time (register pressure)
+      }
+    }
+  };
+  // accumulator: lane column = input channel c0 + li (FLATC: flattened channel*KK + tap); rows = output channels
+  const int c = c0 + li;
+  // norm mode, end of example b: squared norm of this block's share into its slot, accumulators back to zero.
+  // Waves that split the pixel pairs (WK > 1) hand their accumulators to the wk == 0 wave through the
+  // staging area; that wave squares the sums as it reads them.
+  auto norm_epilogue = [&](int b) {
+    const float bias_d = bias_total();
+    const float *xs = smem; // [(WD*WN) groups][WK-1][NBW*16][64]
+    const int grp = wave / WK;
+    if (WK > 1) {
+      __syncthreads(); // staging area no longer read
+      if (wk > 0) {
+        float *dst = smem + ((grp * (WK - 1) + wk - 1) * NBW * 16) * 64 + lane;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[(j * 16 + r) * 64] = acc[0][j][r];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __syncthreads();
+    }
+    float part = 0.f;
+    if (wk == 0) {
+      const int CKK = a.C * KK;
+#pragma unroll
+      for (int i = 0; i < DBW; ++i)
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+          const int tap = wn * NBW + j;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+            float v = acc[i][j][r];
+#pragma unroll
+            for (int q = 0; q < WK - 1; ++q) v += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
+            const bool ok = FLATC ? (li < CKK && d < a.D) : (tap < KK && c < a.C && d < a.D);
+            if (ok) part += v * v;
+          }
+          if (WK > 1) __builtin_amdgcn_sched_barrier(0); // one block of 16 loads in flight at a time (register pressure)
+        }
+    }
+    if (cb == 0 && tid < a.D) part += bias_d * bias_d;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    if (lane == 0) red[wave] = part;
+    __syncthreads();
+    // red[] is next written after two more barriers (top of the chunk loop), so this read cannot race
+    if (tid == 0) a.out[(long)(a.slot0 + cb) * a.slot_stride + b] = red[0] + red[1] + red[2] + red[3];
+#pragma unroll
+    for (int i = 0; i < DBW; ++i)
+#pragma unroll
+      for (int j = 0; j < NBW; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    rowsum = 0.f;
+  };
+
   const int n_chunks = ((bend - bbeg + nimg_max - 1) / nimg_max) * a.t.row_tiles;
   int cb_b = bbeg, cb_rt = 0; // chunk being fetched
   if (n_chunks > 0) prefetch(cb_b, min(nimg_max, bend - cb_b), 0, min(a.t.TR, a.OH));
@@ -413,99 +510,34 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
         }
       }
+    if (!CLIP && r0 + rows >= a.OH) norm_epilogue(b); // last row tile of example b (one image per chunk)
   }
 
-  // bias gradient: combine the slices
-  float bias_d = 0.f;
-  if (cb == 0) {
-    rsum[tid] = rowsum;
-    __syncthreads();
-    if (tid < DT) {
-#pragma unroll
-      for (int s = 0; s < NSL; ++s) bias_d += rsum[s * DT + tid];
-    }
-  }
-  if (WK > 1) { // sum the accumulators of the waves that split the pixel pairs into the wk == 0 wave
-    __syncthreads();
-    float *xs = smem; // [(WD*WN) groups][WK-1][NBW*16][64], reusing the staging area
-    const int grp = wave / WK;
-    if (wk > 0)
-#pragma unroll
-      for (int j = 0; j < NBW; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          xs[(((grp * (WK - 1) + wk - 1) * NBW + j) * 16 + r) * 64 + lane] = acc[0][j][r];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < NBW; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (wk == 0) {
-#pragma unroll
-          for (int q = 0; q < WK - 1; ++q) acc[0][j][r] += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
-        } else acc[0][j][r] = 0.f;
-      }
-  }
-  // accumulator: lane column = input channel c0 + li (FLATC: flattened channel*KK + tap); rows = output channels
-  const int c = c0 + li;
+  if (!CLIP) return; // every example already went through norm_epilogue
+  const float bias_d = bias_total();
+  wave_total();
+  float *part = a.out + (long)blockIdx.y * a.part_stride;
   if (FLATC) {
     const int CKK = a.C * KK;
-    if (!CLIP) {
-      float part = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (wk == 0 && li < CKK && d < a.D) part += acc[0][0][r] * acc[0][0][r];
-      }
-      if (tid < a.D) part += bias_d * bias_d;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
-      if (lane == 0) red[wave] = part;
-      __syncthreads();
-      if (tid == 0) a.out[(long)a.slot0 * a.slot_stride + bbeg] = red[0] + red[1] + red[2] + red[3];
-    } else {
-      float *part = a.out + (long)blockIdx.y * a.part_stride;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (wk == 0 && li < CKK && d < a.D) part[(long)d * CKK + li] = acc[0][0][r];
-      }
-      if (tid < a.D) part[(long)a.D * CKK + tid] = bias_d;
+    for (int r = 0; r < 16; ++r) {
+      const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
+      if (wk == 0 && li < CKK && d < a.D) part[(long)d * CKK + li] = acc[0][0][r];
     }
+    if (tid < a.D) part[(long)a.D * CKK + tid] = bias_d;
     return;
   }
-  if (!CLIP) {
-    float part = 0.f;
+  // taps innermost: the stores of one (row, lane) are consecutive words, so the 32 lanes fill whole
+  // cache lines within a few instructions and the L2 merges them before it writes them back
 #pragma unroll
-    for (int i = 0; i < DBW; ++i)
+  for (int i = 0; i < DBW; ++i)
 #pragma unroll
-      for (int j = 0; j < NBW; ++j) {
-        const int tap = wn * NBW + j;
+    for (int r = 0; r < 16; ++r) {
+      const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+      float *row = part + ((long)d * a.C + c) * KK + wn * NBW;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-          if (wk == 0 && tap < KK && c < a.C && d < a.D) part += acc[i][j][r] * acc[i][j][r];
-        }
-      }
-    if (cb == 0 && tid < a.D) part += bias_d * bias_d;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
-    if (lane == 0) red[wave] = part;
-    __syncthreads();
-    if (tid == 0) a.out[(long)(a.slot0 + cb) * a.slot_stride + bbeg] = red[0] + red[1] + red[2] + red[3];
-  } else {
-    float *part = a.out + (long)blockIdx.y * a.part_stride;
-#pragma unroll
-    for (int i = 0; i < DBW; ++i)
-#pragma unroll
-      for (int j = 0; j < NBW; ++j) {
-        const int tap = wn * NBW + j;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int d = (wd * DBW + i) * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-          if (wk == 0 && tap < KK && c < a.C && d < a.D) part[((long)d * a.C + c) * KK + tap] = acc[i][j][r];
-        }
-      }
-    if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = bias_d;
-  }
+      for (int j = 0; j < NBW; ++j)
+        if (wk == 0 && wn * NBW + j < KK && c < a.C && d < a.D) row[j] = acc[i][j][r];
+    }
+  if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = bias_d;
 }

@@ -720,10 +720,15 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         const ConvGeom &g = l.geom;
         if (priv && l.dir_wg && aligned16(lin)) {
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn);
-          a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = 1;
+          // one round of resident workgroups, each walking through its run of examples: the next
+          // example's tiles are fetched while the current one is multiplied and reduced
+          const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
+          const int resident = 256 * (l.wg_db <= 2 ? 2 : 1);
+          int epb = ceil_div(B, std::max(1, resident / cblocks));
+          a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = epb;
           a.slot_stride = slot_stride; a.slot0 = slot_next;
-          slot_next += l.wg_flat ? 1 : ceil_div(g.C, 32);
-          launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, B);
+          slot_next += cblocks;
+          launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, ceil_div(B, epb));
         } else if (priv) {
           auto run = [&](auto vt) {
             constexpr bool V = decltype(vt)::value;
