@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
   float *Dl = smem + xch * a.t.XPLANE;  // [DT][LDP]
   __shared__ float red[4];
   __shared__ float rsum[256];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), li = lane & 31, lk = lane >> 5;
   const int wd = wave / (WN * WK), wn = (wave / WK) % WN, wk = wave % WK;
   const int cb = blockIdx.x, c0 = cb * 32;
   const int HW = a.H * a.W, OHW = a.OH * a.OW;
@@ -488,28 +488,45 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       for (int p = sl * per; p < p1; ++p) s += Dl[d * a.LDP + p];
       rowsum += s;
     }
-    // K loop over pixel pairs of the chunk (OW is even: a pair never straddles a row)
-    for (int img = 0; img < nimg; ++img)
-      for (int r = 0; r < rows; ++r) {
-        const int pbase = (img * a.t.TR + r) * a.OW;
-        const int xbase = img * a.t.IMGPL + r * a.t.LDW;
-#pragma unroll 4
-        for (int col = col0; col < a.OW; col += colstep) {
-          float av[DBW], bv[NBW];
+    // K loop: one step = one pixel pair of the chunk (OW is even: a pair never straddles a row); this wave
+    // takes the pairs at columns col0, col0 + colstep, ... of every row.  Two-stage pipeline: the LDS
+    // reads of step s+1 are issued before the MFMAs of step s.  All loop state is wave-uniform (scalar).
+    {
+      const int spr = (a.OW - col0 + colstep - 1) / colstep; // steps per row
+      const int nsteps = nimg * rows * spr;
+      const float *Dw = Dl + dlane + (wd * 32) * a.LDP;
+      const float *Xw = Xl + xlane;
+      const int d_skip = (a.t.TR - rows) * a.OW, x_skip = a.t.IMGPL - rows * a.t.LDW; // to the next image
+      int col = col0, r = 0, doff = 0, xoff = 0;
+      auto fetch = [&](bool valid, float &av, float (&bv)[NBW]) {
+        const int dc = valid ? doff + col : 0, xc = valid ? xoff + col : 0;
+        av = Dw[dc];
 #pragma unroll
-          for (int i = 0; i < DBW; ++i) av[i] = Dl[dlane + ((wd * DBW + i) * 32) * a.LDP + pbase + col];
-#pragma unroll
-          for (int j = 0; j < NBW; ++j) {
-            bv[j] = Xl[xlane + xbase + col + tapoff[j]];
-            if (!tapok[j]) bv[j] = 0.f;
-          }
-#pragma unroll
-          for (int i = 0; i < DBW; ++i)
-#pragma unroll
-            for (int j = 0; j < NBW; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NBW; ++j) bv[j] = Xw[xc + tapoff[j]];
+        col += colstep;
+        if (col >= a.OW) {
+          col = col0; doff += a.OW; xoff += a.t.LDW;
+          if (++r == rows) { r = 0; doff += d_skip; xoff += x_skip; }
         }
+      };
+      auto mma = [&](float av, float (&bv)[NBW]) {
+        if (FLATC && !tapok[0]) bv[0] = 0.f; // lanes beyond the C*KK flattened columns
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+          if (FLATC || j + 1 < NBW || tapok[NBW - 1]) // the last tap slot of the last wave may be empty (wave-uniform)
+            acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[j], acc[0][j], 0, 0, 0);
+      };
+      float a0, b0[NBW], a1, b1[NBW];
+      fetch(nsteps > 0, a0, b0);
+      int s = 0;
+      for (; s + 2 <= nsteps; s += 2) {
+        fetch(true, a1, b1);
+        mma(a0, b0);
+        fetch(s + 2 < nsteps, a0, b0);
+        mma(a1, b1);
       }
+      if (s < nsteps) mma(a0, b0);
+    }
     if (!CLIP && r0 + rows >= a.OH) norm_epilogue(b); // last row tile of example b (one image per chunk)
   }
 
