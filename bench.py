@@ -179,6 +179,20 @@ def cpu_baseline(wl, budget_s=12.0):
                        f"gcc -O2 -fopenmp fp64 loop oracle")
 
 
+def hbm_traffic(workload, label):
+    """HBM bytes per launch of the kernel behind `label` ("<kind>#<layer>"), from the rocprofv3 --pmc runs summarised
+    under profiles/ (FETCH_SIZE and WRITE_SIZE, already scaled by what a plain copy of known size reads); None when
+    that launch has not been measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)
+        e = t[workload][label]
+        return float(e["fetch_bytes"]) + float(e["write_bytes"]), e.get("kernel")
+    except (OSError, KeyError, ValueError, TypeError):
+        return None, None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,15 +221,22 @@ def main():
         del src, dst
     res, wl = run_workload(a.workload, a.steps, a.warmup, profile=True)
     kern = res["kernels"]
-    dom = kern[0]
+    # roofline of the dominant kernel: the single launch (kernel kind, layer) with the largest share of the step
+    dom = res["kernels_per_layer"][0]
     mfma_bound = dom["flops_per_step"] > 0 and dom["flops_per_step"] / max(dom["bytes_per_step"], 1.0) > 20.0
+    lps = max(dom["launches_per_step"], 1e-9)
+    traffic, hip_kernel = hbm_traffic(a.workload, dom["kernel"])
     if mfma_bound:
-        roof = dict(bound="mfma", achieved=dom["tflops"], peak=PEAK_MFMA_FP32_TFLOPS, unit="TFLOP/s",
-                    frac=dom["tflops"] / PEAK_MFMA_FP32_TFLOPS, traffic=None)
+        ach = dom["flops_per_step"] / lps / (dom["avg_launch_us"] * 1e-6) / 1e12
+        roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_FP32_TFLOPS, unit="TFLOP/s",
+                    frac=ach / PEAK_MFMA_FP32_TFLOPS, traffic=traffic)
     else:
-        roof = dict(bound="hbm", achieved=dom["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
-                    frac=dom["gbs"] / PEAK_HBM_GBS, traffic=None)
-    roof.update(kernel=dom["kernel"], avg_launch_us=dom["avg_launch_us"], launches_per_step=dom["launches_per_step"],
+        ach = dom["bytes_per_step"] / lps / (dom["avg_launch_us"] * 1e-6) / 1e9
+        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+                    traffic=traffic)
+    roof.update(kernel=dom["kernel"], hip_kernel=hip_kernel, avg_launch_us=dom["avg_launch_us"], launches_per_step=dom["launches_per_step"],
+                algorithmic_flops_per_launch=dom["flops_per_step"] / lps,
+                algorithmic_bytes_per_launch=dom["bytes_per_step"] / lps,
                 share_of_step=dom["ms_per_step"] / max(res["ms_private_profiled"], 1e-9),
                 step_tflops=res["tflops"], step_frac_of_mfma_fp32_peak=res["tflops"] / PEAK_MFMA_FP32_TFLOPS)
     if a.kernels:
@@ -248,6 +269,8 @@ def main():
         "cpu_baseline": cpu,
         "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
                      if k in ("kernel", "launches_per_step", "ms_per_step", "tflops", "gbs")} for r in kern],
+        "kernels_per_layer": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                               if k in ("kernel", "avg_launch_us", "tflops", "gbs")} for r in res["kernels_per_layer"][:16]],
         "other_workloads": others,
     }
     print(json.dumps(line))

@@ -951,7 +951,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
   // ------------------------------------------------------------ final write with fused noise
   {
     const float noise_std = (priv && sigma > 0.f) ? sigma * C : 0.f;
-    dim3 grid = grid1d(c->P, 16), block(256);
+    dim3 grid = grid1d(c->P, DP_FIN_CO), block(256);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     Ln("finalize_noise", grid, block, [&](hipStream_t st) {
       hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, c->P, noise_std, k0, k1);

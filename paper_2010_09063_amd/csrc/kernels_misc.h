@@ -211,9 +211,11 @@ __device__ __forceinline__ void normal4(uint64_t blk, uint32_t k0, uint32_t k1, 
 }
 
 // Final write (DPSGD item 3): out[j] = sum over split-K partials of the clipped
-// sum + sigma*C*z_j.  A workgroup owns 16 consecutive coordinates (four Philox
-// blocks); its 256 threads split the partials 16 ways, so a tensor cut into
-// many splits is still reduced with short dependent chains, in a fixed order.
+// sum + sigma*C*z_j.  A workgroup owns 32 consecutive coordinates (one 128-byte line
+// per partial row, eight Philox blocks); its 256 threads split the partials 8 ways, so a
+// tensor cut into many splits is still reduced with short dependent chains, in a fixed order.
+#define DP_FIN_CO 32
+#define DP_FIN_SG 8
 #define DP_MAX_SEG 24
 struct FinalizeSeg {
   long p_off, n;     // segment [p_off, p_off + n) of the flat parameter vector
@@ -228,9 +230,9 @@ struct FinalizeArgs {
 
 __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P,
                                                         float noise_std, uint32_t k0, uint32_t k1) {
-  __shared__ float red[16][17];
-  const int cj = threadIdx.x & 15, sg = threadIdx.x >> 4;
-  const long j = (long)blockIdx.x * 16 + cj;
+  __shared__ float red[DP_FIN_SG][DP_FIN_CO + 1];
+  const int cj = threadIdx.x % DP_FIN_CO, sg = threadIdx.x / DP_FIN_CO;
+  const long j = (long)blockIdx.x * DP_FIN_CO + cj;
   float acc = 0.f;
   if (j < P) {
     int si = 0;
@@ -241,18 +243,18 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, fl
     const int ns = g.nsplit;
     float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
     int s = sg;
-    for (; s + 48 < ns; s += 64) {
-      a0 += p[s * st]; a1 += p[(s + 16) * st]; a2 += p[(s + 32) * st]; a3 += p[(s + 48) * st];
+    for (; s + 3 * DP_FIN_SG < ns; s += 4 * DP_FIN_SG) {
+      a0 += p[s * st]; a1 += p[(s + DP_FIN_SG) * st]; a2 += p[(s + 2 * DP_FIN_SG) * st]; a3 += p[(s + 3 * DP_FIN_SG) * st];
     }
-    for (; s < ns; s += 16) a0 += p[s * st];
+    for (; s < ns; s += DP_FIN_SG) a0 += p[s * st];
     acc = (a0 + a1) + (a2 + a3);
   }
   red[sg][cj] = acc;
   __syncthreads();
-  if (threadIdx.x < 16 && j < P) {
+  if (threadIdx.x < DP_FIN_CO && j < P) {
     float tot = 0.f;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) tot += red[q][cj];
+    for (int q = 0; q < DP_FIN_SG; ++q) tot += red[q][cj];
     if (noise_std > 0.f) {
       float z[4];
       normal4((uint64_t)(j >> 2), k0, k1, z);
