@@ -18,6 +18,7 @@
 // channels with an odd plane stride (wgrad), lanes of the A operand walk channels:
 // all LDS operand reads are conflict-free 4-byte reads with uniform offsets.
 #pragma once
+#include <type_traits>
 #include "gemm_tile.h"
 #include "kernels_misc.h"
 
@@ -489,43 +490,65 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       rowsum += s;
     }
     // K loop: one step = one pixel pair of the chunk (OW is even: a pair never straddles a row); this wave
-    // takes the pairs at columns col0, col0 + colstep, ... of every row.  Two-stage pipeline: the LDS
-    // reads of step s+1 are issued before the MFMAs of step s.  All loop state is wave-uniform (scalar).
+    // takes the pairs at columns col0, col0 + colstep, ... of every row, in groups of four steps.  Inside a
+    // group the operand addresses are immediate offsets from one pointer per operand (six address adds per
+    // group instead of per step), the LDS reads of step s+1 are issued before the MFMAs of step s, and the
+    // only branches are the wave-uniform skips of steps past the row's end and of an empty last tap slot.
+    // All loop state is wave-uniform (scalar).
     {
-      const int spr = (a.OW - col0 + colstep - 1) / colstep; // steps per row
-      const int nsteps = nimg * rows * spr;
-      const float *Dw = Dl + dlane + (wd * 32) * a.LDP;
-      const float *Xw = Xl + xlane;
       const int d_skip = (a.t.TR - rows) * a.OW, x_skip = a.t.IMGPL - rows * a.t.LDW; // to the next image
-      int col = col0, r = 0, doff = 0, xoff = 0;
-      auto fetch = [&](bool valid, float &av, float (&bv)[NBW]) {
-        const int dc = valid ? doff + col : 0, xc = valid ? xoff + col : 0;
-        av = Dw[dc];
+      const int spr = (a.OW - col0 + colstep - 1) / colstep; // steps per row
+      const int gpr = (spr + 3) >> 2;                        // groups per row
+      const int ngroups = nimg * rows * gpr;
+      const int back = 4 * colstep * (gpr - 1);              // from a row's last group back to its first column
+      const bool last_ok = FLATC || tapok[NBW - 1];
+      const float *dp = Dl + dlane + (wd * 32) * a.LDP + col0;
+      const float *xp[NBW];
 #pragma unroll
-        for (int j = 0; j < NBW; ++j) bv[j] = Xw[xc + tapoff[j]];
-        col += colstep;
-        if (col >= a.OW) {
-          col = col0; doff += a.OW; xoff += a.t.LDW;
-          if (++r == rows) { r = 0; doff += d_skip; xoff += x_skip; }
+      for (int j = 0; j < NBW; ++j) xp[j] = Xl + xlane + col0 + tapoff[j];
+      float av[2], bv[2][NBW];
+      av[0] = dp[0];
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) bv[0][j] = xp[j][0];
+      int gi = 0, r = 0;
+      for (int g = 0; g < ngroups; ++g) {
+        const int nv = spr - 4 * gi; // steps of this group inside the row (>= 4: all)
+        // pointers of the next group (the last group re-reads its own first step: in bounds, unused)
+        int dd = 4 * colstep, dx = 4 * colstep;
+        if (++gi == gpr) {
+          gi = 0; dd = a.OW - back; dx = a.t.LDW - back;
+          if (++r == rows) { r = 0; dd += d_skip; dx += x_skip; }
         }
-      };
-      auto mma = [&](float av, float (&bv)[NBW]) {
-        if (FLATC && !tapok[0]) bv[0] = 0.f; // lanes beyond the C*KK flattened columns
+        if (g + 1 == ngroups) { dd = 0; dx = 0; }
+        const float *dpn = dp + dd;
+        const float *xpn[NBW];
 #pragma unroll
-        for (int j = 0; j < NBW; ++j)
-          if (FLATC || j + 1 < NBW || tapok[NBW - 1]) // the last tap slot of the last wave may be empty (wave-uniform)
-            acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[j], acc[0][j], 0, 0, 0);
-      };
-      float a0, b0[NBW], a1, b1[NBW];
-      fetch(nsteps > 0, a0, b0);
-      int s = 0;
-      for (; s + 2 <= nsteps; s += 2) {
-        fetch(true, a1, b1);
-        mma(a0, b0);
-        fetch(s + 2 < nsteps, a0, b0);
-        mma(a1, b1);
+        for (int j = 0; j < NBW; ++j) xpn[j] = xp[j] + dx;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int cur = u & 1, nxt = cur ^ 1;
+          if (u < 3) {
+            av[nxt] = dp[(u + 1) * colstep];
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) bv[nxt][j] = xp[j][(u + 1) * colstep];
+          } else {
+            av[nxt] = dpn[0];
+#pragma unroll
+            for (int j = 0; j < NBW; ++j) bv[nxt][j] = xpn[j][0];
+          }
+          if (u < nv) {
+            if (FLATC && !tapok[0]) bv[cur][0] = 0.f; // lanes beyond the C*KK flattened columns
+#pragma unroll
+            for (int j = 0; j + 1 < NBW; ++j)
+              acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur], bv[cur][j], acc[0][j], 0, 0, 0);
+            if (last_ok) // the last tap slot of the last wave may be empty
+              acc[0][NBW - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur], bv[cur][NBW - 1], acc[0][NBW - 1], 0, 0, 0);
+          }
+        }
+        dp = dpn;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) xp[j] = xpn[j];
       }
-      if (s < nsteps) mma(a0, b0);
     }
     if (!CLIP && r0 + rows >= a.OH) norm_epilogue(b); // last row tile of example b (one image per chunk)
   }

@@ -270,7 +270,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
     if (ok) {
       long lds_n = (long)xch * l.t_wgn.XPLANE + 32l * db * ((l.t_wgn.NIMG * l.t_wgn.TR * g.OW) | 1);
       long lds_c = (long)xch * l.t_wgc.XPLANE + 32l * db * ((l.t_wgc.NIMG * l.t_wgc.TR * g.OW) | 1);
-      bool fits = lds_n * 4 <= 64 * 1024 && lds_c * 4 <= 64 * 1024;
+      bool fits = (lds_n + 64) * 4 <= 64 * 1024 && (lds_c + 64) * 4 <= 64 * 1024;
       // room in the staging area for the cross-wave sum of the waves that split the pixel pairs
       const long xs = flat ? 3l * 16 * 64 : (db == 1 ? 2l * 5 * 16 * 64 : 0);
       if (lds_n < xs || lds_c < xs) fits = false;
@@ -306,7 +306,8 @@ static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a,
 template <class LN>
 static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs &a, int db, bool flat, int groups) {
   dim3 grid(flat ? 1 : ceil_div(a.C, 32), groups), block(256);
-  size_t smem = sizeof(float) * ((size_t)(flat ? a.C : 32) * a.t.XPLANE + 32 * (size_t)db * a.LDP);
+  // + 64 floats: the K loop's look-ahead reads of skipped steps may run past the last staged row
+  size_t smem = sizeof(float) * ((size_t)(flat ? a.C : 32) * a.t.XPLANE + 32 * (size_t)db * a.LDP + 64);
 #define DP_WG_CASE(db_, flat_)                                                                       \
   if (db == db_ && flat == flat_) {                                                                  \
     Ln(label, grid, block, [&](hipStream_t st) {                                                     \
