@@ -485,9 +485,13 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       const int d = tid % DT, sl = tid / DT;
       const int per = (a.PCH + NSL - 1) / NSL;
       const int p1 = min(a.PCH, (sl + 1) * per);
-      float s = 0.f;
-      for (int p = sl * per; p < p1; ++p) s += Dl[d * a.LDP + p];
-      rowsum += s;
+      // four independent partial sums: the LDS reads of a slice are issued together, not one per add
+      const float *row = Dl + d * a.LDP;
+      float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+      int p = sl * per;
+      for (; p + 4 <= p1; p += 4) { s0 += row[p]; s1 += row[p + 1]; s2 += row[p + 2]; s3 += row[p + 3]; }
+      for (; p < p1; ++p) s0 += row[p];
+      rowsum += (s0 + s1) + (s2 + s3);
     }
     // K loop: one step = one pixel pair of the chunk (OW is even: a pair never straddles a row); this wave
     // takes the pairs at columns col0, col0 + colstep, ... of every row, in groups of four steps.  Inside a
