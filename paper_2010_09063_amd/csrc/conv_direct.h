@@ -430,8 +430,9 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
             float v = acc[i][j][r];
 #pragma unroll
             for (int q = 0; q < WK - 1; ++q) v += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
-            const bool ok = FLATC ? (li < CKK && d < a.D) : (tap < KK && c < a.C && d < a.D);
-            if (ok) part += v * v;
+            // entries outside the real (d, c, tap) range are exact zeros (zero-filled operands, skipped
+            // tap slots), so every accumulator is squared without a range test
+            part += v * v;
           }
           if (WK > 1) __builtin_amdgcn_sched_barrier(0); // one block of 16 loads in flight at a time (register pressure)
         }
@@ -584,4 +585,359 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
         if (wk == 0 && wn * NBW + j < KK && c < a.C && d < a.D) row[j] = acc[i][j][r];
     }
   if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = bias_d;
+}
+
+// ---------------------------------------------------------------- weight gradient, specialised waves
+//
+// Same contraction as conv_s1_wgrad_kernel, with the work of a workgroup split by role:
+// waves 0-3 only multiply (K loop, epilogues), waves 4-7 only stage (global -> registers -> LDS),
+// one chunk ahead, into the other of two LDS buffers.  In the kernel above a wave alternates both
+// roles, and while the other wave of its SIMD streams MFMAs every staging instruction waits about
+// one MFMA slot, so the staging phase costs tens of percent of the wave's time; here the staging
+// waves are off the multiplying waves' critical path as long as they finish a chunk within one K
+// loop.  The two roles are two separate code paths (so each gets the register file to itself:
+// accumulators on one side, in-flight tiles and item descriptors on the other) that walk the same
+// chunk schedule and execute the same sequence of workgroup barriers:
+//   Z (buffers zeroed), F (buffer 0 staged), then per chunk [E1 (WK > 1), E2 at the end of an
+//   example in norm mode], I (chunk consumed / next chunk staged), and after the last chunk in
+//   clipped mode [E1 (WK > 1)], S (bias sums complete).
+// LDS: [buffer 0][buffer 1][cross-wave area (WK > 1)], each buffer = [xch][XPLANE] input + [DT][LDP] Delta.
+template <int KH, int KW, int DB, bool FLATC, bool CLIP>
+__global__ __launch_bounds__(512, 1) void conv_s1_wgrad_ws_kernel(const ConvWgArgs a) {
+  constexpr int KK = KH * KW;
+  constexpr int WD = FLATC ? 1 : (DB >= 4 ? 4 : DB);
+  constexpr int WN = FLATC ? 1 : (DB >= 4 ? 1 : 2);
+  constexpr int WK = 4 / (WD * WN);
+  constexpr int NBW = FLATC ? 1 : (KK + WN - 1) / WN;
+  static_assert(WD * WN * WK == 4, "wave decomposition");
+  constexpr int DT = 32 * DB;
+  constexpr int XV = CONV_WG_XV;
+  constexpr int DV = (DB == 1 && !FLATC) ? 4 : 8;
+  extern __shared__ float smem[];
+  const int xch = FLATC ? a.C : 32;
+  const int XS = xch * a.t.XPLANE, BUF = XS + DT * a.LDP;  // a buffer: input planes, then Delta rows
+  float *xs = smem + 2 * BUF;                               // [(WD*WN) groups][WK-1][NBW*16][64]
+  __shared__ float red[4];
+  __shared__ float rsum[2][128]; // bias gradient of the example being staged / being reduced (norm mode: by parity)
+  const int tid = threadIdx.x;
+  const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cb = blockIdx.x, c0 = cb * 32;
+  const int HW = a.H * a.W, OHW = a.OH * a.OW;
+  const int bbeg = blockIdx.y * a.ex_per_block, bend = min(a.B, bbeg + a.ex_per_block);
+  const int nimg_max = !CLIP ? 1 : a.t.NIMG;
+  const int n_chunks = ((bend - bbeg + nimg_max - 1) / nimg_max) * a.t.row_tiles;
+
+  // zero both buffers once: the halo columns of the input planes are never written again
+  for (int e = tid; e < 2 * BUF; e += 512) smem[e] = 0.f;
+  if (tid < 256) rsum[tid >> 7][tid & 127] = 0.f;
+  __syncthreads(); // Z
+
+  if (wave8 >= 4) {
+    // ================================================================ staging waves
+    const int ptid = tid & 255;
+    // static item descriptors (same item order as conv_s1_wgrad_kernel, 256 staging threads)
+    int x_lds[XV], x_goff[XV], x_ir[XV];
+#pragma unroll
+    for (int j = 0; j < XV; ++j) {
+      const int it = ptid + j * 256;
+      const int t1 = (int)a.dWQ.div(it), q = it - t1 * a.WQ;
+      const int t2 = (int)a.dROWS.div(t1), rr = t1 - t2 * a.ROWS;
+      const int c = (int)a.dNIMG.div(t2), img = t2 - c * a.t.NIMG;
+      const bool ok = c < xch && c0 + c < a.C;
+      x_lds[j] = ok ? c * a.t.XPLANE + img * a.t.IMGPL + rr * a.t.LDW + a.pad + 4 * q : -1;
+      x_goff[j] = (img * a.C + c) * HW + (rr - a.pad) * a.W + 4 * q;
+      x_ir[j] = (img << 16) | rr;
+    }
+    const int PQ = a.PCH >> 2;
+    int d_lds[DV], d_goff[DV], d_ir[DV];
+#pragma unroll
+    for (int j = 0; j < DV; ++j) {
+      const int it = ptid + j * 256;
+      const int d = (int)a.dPQ.div(it), p = 4 * (it - d * PQ);
+      const int img = (int)a.t.dTROW.div(p), rem = p - img * a.t.TR * a.OW;
+      const int r = (int)a.t.dOW.div(rem);
+      const bool ok = d < DT;
+      d_lds[j] = ok ? d * a.LDP + p : -1;
+      d_goff[j] = (d < a.D) ? (img * a.D + d) * OHW + rem : -1;
+      d_ir[j] = (img << 16) | r;
+    }
+    float rowsum[DV]; // bias gradient: sum of the staged (scaled) Delta of item j's row, this thread's pixels
+#pragma unroll
+    for (int j = 0; j < DV; ++j) rowsum[j] = 0.f;
+    float4 xr[XV], dr[DV];
+    float dsv[DV];
+    unsigned xok = 0, dok = 0;
+    auto prefetch = [&](int b, int nimg, int r0, int rows) {
+      const long xb = ((long)b * a.C + c0) * HW + (long)r0 * a.W;
+#pragma unroll
+      for (int j = 0; j < XV; ++j) {
+        const int img = x_ir[j] >> 16, rr = x_ir[j] & 0xffff;
+        const int ih = r0 + rr - a.pad;
+        const bool ok = x_lds[j] >= 0 && img < nimg && rr < rows + KH - 1 && (unsigned)ih < (unsigned)a.H;
+        xr[j] = *reinterpret_cast<const float4 *>(a.x + (ok ? xb + x_goff[j] : 0));
+        xok = ok ? (xok | (1u << j)) : (xok & ~(1u << j));
+      }
+      const long db_ = (long)b * a.D * OHW + (long)r0 * a.OW;
+#pragma unroll
+      for (int j = 0; j < DV; ++j) {
+        const int img = d_ir[j] >> 16, r = d_ir[j] & 0xffff;
+        const bool ok = d_goff[j] >= 0 && img < nimg && r < rows;
+        dr[j] = *reinterpret_cast<const float4 *>(a.delta + (ok ? db_ + d_goff[j] : 0));
+        if (CLIP) dsv[j] = a.scale[ok ? b + img : 0];
+        dok = ok ? (dok | (1u << j)) : (dok & ~(1u << j));
+      }
+    };
+    auto flush_rows = [&](int par) { // this thread's row sums into rsum[par]
+#pragma unroll
+      for (int j = 0; j < DV; ++j) {
+        const int d = (int)a.dPQ.div(ptid + j * 256);
+        if (d_lds[j] >= 0) atomicAdd(&rsum[par][d], rowsum[j]);
+        rowsum[j] = 0.f;
+      }
+    };
+    // registers -> LDS buffer; `last`: the chunk ends its example (norm mode), whose bias sums go to rsum[par]
+    auto stash = [&](float *buf, bool last, int par) {
+      float *Xl = buf, *Dl = buf + XS;
+#pragma unroll
+      for (int j = 0; j < XV; ++j)
+        if (x_lds[j] >= 0) {
+          const float4 v = ((xok >> j) & 1u) ? xr[j] : f4zero();
+          float *d = Xl + x_lds[j];
+          d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+        }
+#pragma unroll
+      for (int j = 0; j < DV; ++j)
+        if (d_lds[j] >= 0) {
+          const float sv = ((dok >> j) & 1u) ? (CLIP ? dsv[j] : 1.f) : 0.f;
+          const float4 v = ((dok >> j) & 1u) ? dr[j] : f4zero();
+          float *d = Dl + d_lds[j];
+          const float w0 = v.x * sv, w1 = v.y * sv, w2 = v.z * sv, w3 = v.w * sv;
+          d[0] = w0; d[1] = w1; d[2] = w2; d[3] = w3;
+          if (cb == 0) rowsum[j] += (w0 + w1) + (w2 + w3);
+        }
+      if (cb == 0 && last) flush_rows(par);
+    };
+    int f_b = bbeg, f_rt = 0, f_ex = 0; // chunk held in registers (example ordinal f_ex)
+    auto f_prefetch = [&]() {
+      const int r0 = f_rt * a.t.TR;
+      prefetch(f_b, min(nimg_max, bend - f_b), r0, min(a.t.TR, a.OH - r0));
+    };
+    auto f_stash = [&](float *buf) {
+      stash(buf, !CLIP && f_rt == a.t.row_tiles - 1, f_ex & 1);
+      if (++f_rt == a.t.row_tiles) { f_rt = 0; f_b += nimg_max; ++f_ex; }
+    };
+    if (n_chunks > 0) {
+      f_prefetch();
+      f_stash(smem);
+      if (n_chunks > 1) f_prefetch();
+    }
+    __syncthreads(); // F
+    int m_rt = 0; // row tile of the chunk being multiplied by the other waves
+    for (int ci = 0; ci < n_chunks; ++ci) {
+      if (ci + 1 < n_chunks) { // registers hold chunk ci+1
+        f_stash(smem + ((ci + 1) & 1) * BUF);
+        if (ci + 2 < n_chunks) f_prefetch();
+      }
+      if (!CLIP && m_rt == a.t.row_tiles - 1) {
+        if (WK > 1) __syncthreads(); // E1
+        __syncthreads();             // E2
+      }
+      if (++m_rt == a.t.row_tiles) m_rt = 0;
+      __syncthreads(); // I
+    }
+    if (!CLIP) return;
+    if (cb == 0) flush_rows(0);
+    if (WK > 1) __syncthreads(); // E1
+    __syncthreads();             // S
+    return;
+  }
+
+  // ================================================================ multiplying waves
+  const int lane = tid & 63, li = lane & 31, lk = lane >> 5, wave = wave8;
+  const int wd = wave / (WN * WK), wn = (wave / WK) % WN, wk = wave % WK;
+  f32x16 acc[NBW];
+#pragma unroll
+  for (int j = 0; j < NBW; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  int xlane = li * a.t.XPLANE + lk;
+  const int dlane = li * a.LDP + lk;
+  int tapoff[NBW];
+  bool tapok[NBW];
+#pragma unroll
+  for (int j = 0; j < NBW; ++j) {
+    const int tap = wn * NBW + j;
+    const int kh = tap / KW, kw = tap - kh * KW;
+    tapok[j] = tap < KK;
+    tapoff[j] = tapok[j] ? kh * a.t.LDW + kw : 0;
+  }
+  if (FLATC) { // lane = (channel, tap)
+    const int ch = li / KK, tap = li - ch * KK, kh = tap / KW, kw = tap - kh * KW;
+    tapok[0] = li < a.C * KK;
+    tapoff[0] = 0;
+    xlane = (tapok[0] ? ch * a.t.XPLANE + kh * a.t.LDW + kw : 0) + lk;
+  }
+  const int col0 = 2 * wk;
+  constexpr int colstep = 2 * WK;
+  const int c = c0 + li;
+  const int grp = wave / WK;
+
+  // hand the accumulators of the waves that split the pixel pairs to the wk == 0 wave (barrier E1)
+  auto publish = [&]() {
+    if (WK > 1) {
+      if (wk > 0) {
+        float *dst = xs + ((grp * (WK - 1) + wk - 1) * NBW * 16) * 64 + lane;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[(j * 16 + r) * 64] = acc[j][r];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      __syncthreads(); // E1
+    }
+  };
+  auto gathered = [&](int j, int r) { // on wk == 0 waves after publish()
+    float v = acc[j][r];
+#pragma unroll
+    for (int q = 0; q < WK - 1; ++q) v += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
+    return v;
+  };
+  const int spr = (a.OW - col0 + colstep - 1) / colstep; // steps per row
+  const int gpr = (spr + 3) >> 2;                        // groups of four steps per row
+  const int back = 4 * colstep * (gpr - 1);              // from a row's last group back to its first column
+
+  // The whole chunk loop, compiled once per (ALL4: every group has four steps in the row, LAST: the wave's last
+  // tap slot holds a tap), so that the K loop has no branch between its MFMAs.
+  auto consume = [&](auto all4_c, auto last_c) {
+    constexpr bool ALL4 = decltype(all4_c)::value;
+    constexpr int NT = (FLATC || decltype(last_c)::value) ? NBW : NBW - 1;
+    int m_b = bbeg, m_rt = 0, m_ex = 0; // chunk being multiplied
+    for (int ci = 0; ci < n_chunks; ++ci) {
+      const int r0 = m_rt * a.t.TR;
+      const int nimg = min(nimg_max, bend - m_b), rows = min(a.t.TR, a.OH - r0);
+      {
+        // K loop: groups of four pixel-pair steps; operand addresses are immediate offsets from one pointer
+        // per operand, the LDS reads of step s+1 are issued before the MFMAs of step s
+        const float *buf = smem + (ci & 1) * BUF;
+        const int d_skip = (a.t.TR - rows) * a.OW, x_skip = a.t.IMGPL - rows * a.t.LDW; // to the next image
+        const int ngroups = nimg * rows * gpr;
+        const float *dp = buf + XS + dlane + (wd * 32) * a.LDP + col0;
+        const float *xp[NT];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) xp[j] = buf + xlane + col0 + tapoff[j];
+        float av[2], bv[2][NT];
+        av[0] = dp[0];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) bv[0][j] = xp[j][0];
+        int gi = 0, r = 0;
+        for (int g = 0; g < ngroups; ++g) {
+          const int nv = spr - 4 * gi; // steps of this group inside the row
+          int dd = 4 * colstep, dx = 4 * colstep;
+          if (++gi == gpr) {
+            gi = 0; dd = a.OW - back; dx = a.t.LDW - back;
+            if (++r == rows) { r = 0; dd += d_skip; dx += x_skip; }
+          }
+          if (g + 1 == ngroups) { dd = 0; dx = 0; } // the last group re-reads its own first step: in bounds, unused
+          const float *dpn = dp + dd;
+          const float *xpn[NT];
+#pragma unroll
+          for (int j = 0; j < NT; ++j) xpn[j] = xp[j] + dx;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int cur = u & 1, nxt = cur ^ 1;
+            if (u < 3) {
+              av[nxt] = dp[(u + 1) * colstep];
+#pragma unroll
+              for (int j = 0; j < NT; ++j) bv[nxt][j] = xp[j][(u + 1) * colstep];
+            } else {
+              av[nxt] = dpn[0];
+#pragma unroll
+              for (int j = 0; j < NT; ++j) bv[nxt][j] = xpn[j][0];
+            }
+            if (ALL4 || u < nv) {
+              if (FLATC && !tapok[0]) bv[cur][0] = 0.f; // lanes beyond the C*KK flattened columns
+#pragma unroll
+              for (int j = 0; j < NT; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur], bv[cur][j], acc[j], 0, 0, 0);
+            }
+          }
+          dp = dpn;
+#pragma unroll
+          for (int j = 0; j < NT; ++j) xp[j] = xpn[j];
+        }
+      }
+      if (!CLIP && m_rt == a.t.row_tiles - 1) {
+        // end of example m_b: squared norm of this block's share into its slot, accumulators back to zero
+        publish();
+        float part = 0.f;
+        if (wk == 0) {
+          const int CKK = a.C * KK;
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) {
+            const int tap = wn * NBW + j;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int d = wd * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+              const float v = gathered(j, r);
+              part += v * v; // entries outside the real (d, c, tap) range are exact zeros
+            }
+            if (WK > 1) __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        if (cb == 0 && tid < DT) { // staged one chunk ahead: this example's sums were complete a barrier ago
+          const float bias_d = rsum[m_ex & 1][tid];
+          rsum[m_ex & 1][tid] = 0.f;
+          if (tid < a.D) part += bias_d * bias_d;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+        if (lane == 0) red[wave] = part;
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+        __syncthreads(); // E2
+        if (tid == 0) a.out[(long)(a.slot0 + cb) * a.slot_stride + m_b] = red[0] + red[1] + red[2] + red[3];
+      }
+      if (++m_rt == a.t.row_tiles) { m_rt = 0; m_b += nimg_max; ++m_ex; }
+      __syncthreads(); // I
+    }
+  };
+
+  __syncthreads(); // F
+  {
+    const bool all4 = (spr & 3) == 0, last_ok = FLATC || tapok[NBW - 1];
+    if (all4 && last_ok) consume(std::true_type{}, std::true_type{});
+    else if (all4) consume(std::true_type{}, std::false_type{});
+    else if (last_ok) consume(std::false_type{}, std::true_type{});
+    else consume(std::false_type{}, std::false_type{});
+  }
+  if (!CLIP) return;
+
+  // clipped mode: one partial for the block's examples
+  publish();       // E1 (WK > 1)
+  __syncthreads(); // S
+  float *part = a.out + (long)blockIdx.y * a.part_stride;
+  if (FLATC) {
+    const int CKK = a.C * KK;
+    if (wk == 0)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
+        if (li < CKK && d < a.D) part[(long)d * CKK + li] = gathered(0, r);
+      }
+    if (tid < a.D) part[(long)a.D * CKK + tid] = rsum[0][tid];
+    return;
+  }
+  if (wk == 0)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int d = wd * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+      float *row = part + ((long)d * a.C + c) * KK + wn * NBW;
+#pragma unroll
+      for (int j = 0; j < NBW; ++j)
+        if (wn * NBW + j < KK && c < a.C && d < a.D) row[j] = gathered(j, r);
+    }
+  if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = rsum[0][tid];
 }

@@ -121,6 +121,7 @@ struct Layer {
   ConvGeom geom;
   // stride-1 3x3 convolutions: LDS-staged direct kernels (otherwise the generic contraction)
   bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
+  bool wg_ws = false; // weight gradient with specialised staging / multiplying waves (two LDS buffers)
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
   ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
   float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
@@ -281,6 +282,12 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
         if ((pch & 3) != 0) fits = false;
       }
       if (fits) { l.dir_wg = true; l.wg_db = db; l.wg_flat = flat; }
+      // specialised-wave variant: two staging buffers + the cross-wave area must fit one CU's LDS
+      // (measured: pays where the single-buffer kernel runs one workgroup per CU, i.e. 128 output channels)
+      if (fits && (db == 4 || getenv("DP_STEP_WS_ALL") != nullptr)) {
+        const long ws = 2 * std::max(lds_n, lds_c) + xs + 64;
+        l.wg_ws = ws * 4 + 2048 <= 160 * 1024 && getenv("DP_STEP_NO_WS") == nullptr;
+      }
     }
   }
 }
@@ -303,13 +310,32 @@ static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a,
 #undef DP_CONV_CASE
 }
 
+static size_t conv_wgrad_ws_smem(const ConvWgArgs &a, int db, bool flat) {
+  const size_t buf = (size_t)(flat ? a.C : 32) * a.t.XPLANE + 32 * (size_t)db * a.LDP;
+  const size_t xs = flat ? 3 * 16 * 64 : (db == 1 ? 2 * 5 * 16 * 64 : 0);
+  return sizeof(float) * (2 * buf + xs + 64); // + 64: look-ahead reads of skipped steps past the last staged row
+}
+
+// the specialised-wave kernels use more than the default 64 KB of dynamic LDS
+static bool conv_wgrad_ws_enable() {
+  bool ok = true;
+#define DP_WS_ATTR(db_, flat_, clip_)                                                                          \
+  ok = ok && hipFuncSetAttribute((const void *)conv_s1_wgrad_ws_kernel<3, 3, db_, flat_, clip_>,               \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048) == hipSuccess;
+  DP_WS_ATTR(1, false, false) DP_WS_ATTR(1, false, true) DP_WS_ATTR(2, false, false) DP_WS_ATTR(2, false, true)
+  DP_WS_ATTR(1, true, false) DP_WS_ATTR(1, true, true) DP_WS_ATTR(4, false, false) DP_WS_ATTR(4, false, true)
+#undef DP_WS_ATTR
+  return ok;
+}
+
 template <class LN>
-static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs &a, int db, bool flat, int groups) {
-  dim3 grid(flat ? 1 : ceil_div(a.C, 32), groups), block(256);
+static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs &a, int db, bool flat, bool ws, int groups) {
+  dim3 grid(flat ? 1 : ceil_div(a.C, 32), groups), block(ws ? 512 : 256);
   // + 64 floats: the K loop's look-ahead reads of skipped steps may run past the last staged row
-  size_t smem = sizeof(float) * ((size_t)(flat ? a.C : 32) * a.t.XPLANE + 32 * (size_t)db * a.LDP + 64);
+  size_t smem = ws ? conv_wgrad_ws_smem(a, db, flat)
+                   : sizeof(float) * ((size_t)(flat ? a.C : 32) * a.t.XPLANE + 32 * (size_t)db * a.LDP + 64);
 #define DP_WG_CASE(db_, flat_)                                                                       \
-  if (db == db_ && flat == flat_) {                                                                  \
+  if (!ws && db == db_ && flat == flat_) {                                                           \
     Ln(label, grid, block, [&](hipStream_t st) {                                                     \
       if (a.mode == 0)                                                                               \
         hipLaunchKernelGGL((conv_s1_wgrad_kernel<3, 3, db_, flat_, false>), grid, block, smem, st, a); \
@@ -320,6 +346,18 @@ static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs 
   }
   DP_WG_CASE(1, false) DP_WG_CASE(2, false) DP_WG_CASE(4, false) DP_WG_CASE(1, true)
 #undef DP_WG_CASE
+#define DP_WS_CASE(db_, flat_)                                                                       \
+  if (ws && db == db_ && flat == flat_) {                                                            \
+    Ln(label, grid, block, [&](hipStream_t st) {                                                     \
+      if (a.mode == 0)                                                                               \
+        hipLaunchKernelGGL((conv_s1_wgrad_ws_kernel<3, 3, db_, flat_, false>), grid, block, smem, st, a); \
+      else                                                                                           \
+        hipLaunchKernelGGL((conv_s1_wgrad_ws_kernel<3, 3, db_, flat_, true>), grid, block, smem, st, a);  \
+    });                                                                                              \
+    return;                                                                                          \
+  }
+  DP_WS_CASE(1, false) DP_WS_CASE(2, false) DP_WS_CASE(4, false) DP_WS_CASE(1, true)
+#undef DP_WS_CASE
 }
 
 static ConvWgArgs make_wg_args(const Layer &l, const float *x, int B, const ConvTile &t) {
@@ -423,6 +461,14 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     if (nparam > DP_MAX_SEG) rc = DP_EUNSUPPORTED;
   }
   if (rc != DP_OK) { delete c; return rc; }
+  {
+    bool any_ws = false;
+    for (auto &l : c->L) any_ws = any_ws || l.wg_ws;
+    if (any_ws && !conv_wgrad_ws_enable()) { // large dynamic LDS refused: keep the single-buffer kernels
+      (void)hipGetLastError();
+      for (auto &l : c->L) l.wg_ws = false;
+    }
+  }
   c->P = off;
   c->max_slots = total_slots;
   for (size_t i = 0; i < c->L.size(); ++i) {
@@ -724,12 +770,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           // one round of resident workgroups, each walking through its run of examples: the next
           // example's tiles are fetched while the current one is multiplied and reduced
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
-          const int resident = 256 * (l.wg_db <= 2 ? 2 : 1);
+          const int resident = 256 * (l.wg_ws ? 1 : (l.wg_db <= 2 ? 2 : 1));
           int epb = ceil_div(B, std::max(1, resident / cblocks));
           a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = epb;
           a.slot_stride = slot_stride; a.slot0 = slot_next;
           slot_next += cblocks;
-          launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, ceil_div(B, epb));
+          launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, l.wg_ws, ceil_div(B, epb));
         } else if (priv) {
           auto run = [&](auto vt) {
             constexpr bool V = decltype(vt)::value;
@@ -863,7 +909,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc);
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
           // one full round of resident workgroups (256 CUs x workgroups per CU) avoids a ragged tail
-          const int occ = l.wg_db == 1 ? 3 : (l.wg_db == 2 ? 2 : 1);
+          const int occ = l.wg_ws ? 1 : (l.wg_db == 1 ? 3 : (l.wg_db == 2 ? 2 : 1));
           int want = (256 * occ) / cblocks;
           if (want < 1) want = 1;
           if (want > l.max_split) want = l.max_split;
@@ -871,7 +917,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           epb = ceil_div(epb, a.t.NIMG) * a.t.NIMG;
           nsplit = ceil_div(B, epb);
           a.scale = sc; a.out = l.part; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
-          launch_conv_wgrad(Ln, LL("conv_clipped_sum"), a, l.wg_db, l.wg_flat, nsplit);
+          launch_conv_wgrad(Ln, LL("conv_clipped_sum"), a, l.wg_db, l.wg_flat, l.wg_ws, nsplit);
           break;
         }
         typedef ProbPartial<OpChanPix, OpConvPatch<false>> Pb;
