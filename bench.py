@@ -71,7 +71,12 @@ def label_work(m, B):
             T, D_ = inp["seq_len"], L["dim"]
             add("emb_gather", 0.0, 4.0 * B * T * (2 * D_ + 1))
             add("emb_norm", 2.0 * B * T * D_, 4.0 * B * T * (D_ + 1))
+            add("emb_bucket", 0.0, 4.0 * (4 * B * T + 4 * L["vocab"]))  # counting sort: tokens read 3x, list written
             add("emb_scatter", 2.0 * B * T * D_, 4.0 * (B * T * (D_ + 1) + L["vocab"] * D_))
+        elif k == "seq_mean":
+            T, D_ = cur[1], cur[2]
+            add("seq_mean_fwd", 1.0 * B * T * D_, 4.0 * B * (T * D_ + D_))
+            add("seq_mean_bwd", 1.0 * B * T * D_, 4.0 * B * (T * D_ + D_))
         elif k == "lstm_last":
             T, Din, H = cur[1], L["d_in"], L["hidden"]
             G = 4 * H
@@ -105,10 +110,10 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def run_workload(name, steps, warmup, profile):
+def run_workload(name, steps, warmup, profile, batch=None):
     import torch
     from paper_2010_09063_amd import DpStep
-    wl = W.make_workload(name, seed=0)
+    wl = W.make_workload(name, batch=batch, seed=0)
     m, B = wl["model"], wl["batch"]
     dev = torch.device("cuda:0")
     st = DpStep(m, B)
@@ -202,6 +207,9 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--kernels", action="store_true", help="print the per-kernel table to stderr")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also run the workload at batch sizes 16 ... 4096 (workspace bytes, examples/s, ratio): the "
+                         "paper's batch-size and memory study (Section 3 figures, Section 4 memory table)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference point for rocprofv3 --pmc byte counters)")
     a = ap.parse_args()
@@ -255,6 +263,15 @@ def main():
             r, _ = run_workload(name, max(10, a.steps // 2), max(3, a.warmup // 2), profile=False)
             others.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()})
 
+    sweep = []
+    if a.batch_sweep:
+        for bsz in (16, 32, 64, 128, 256, 512, 1024, 2048, 4096):
+            r, _ = run_workload(a.workload, max(10, a.steps // 2), max(3, a.warmup // 2), profile=False, batch=bsz)
+            sweep.append({k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()
+                          if k in ("batch", "ms_private", "ms_nonprivate", "examples_per_s", "ratio", "workspace_mb")})
+            print(f"  B={bsz:5d}  {r['ms_private']:8.3f} ms  {r['examples_per_s']:12.0f} ex/s  ratio {r['ratio']:.3f}  "
+                  f"workspace {r['workspace_mb']:9.1f} MB", file=sys.stderr)
+
     cpu = None if a.no_cpu else cpu_baseline(wl)
 
     line = {
@@ -273,6 +290,8 @@ def main():
                                if k in ("kernel", "avg_launch_us", "tflops", "gbs")} for r in res["kernels_per_layer"][:16]],
         "other_workloads": others,
     }
+    if sweep:
+        line["batch_sweep"] = sweep
     print(json.dumps(line))
 
 

@@ -14,6 +14,7 @@ Model description: {"input": {...}, "layers": [ {...}, ... ], "n_classes": k}
          {"kind": "maxpool2d", "k", "stride"}
          {"kind": "embedding", "vocab", "dim"}
          {"kind": "lstm_last", "d_in", "hidden"}
+         {"kind": "seq_mean"}                           mean over the T steps of a sequence
   act    "none" | "relu" | "tanh"
 
 Flat parameter layout (both implementations follow it): layers in order, each
@@ -21,7 +22,7 @@ weight tensor then its bias.  dense W[d_in][d_out], b[d_out]; conv
 W[c_out][c_in][kh][kw], b[c_out]; embedding E[vocab][dim]; lstm W_ih[d_in][4H],
 W_hh[H][4H], b[4H] with the 4H axis ordered i, f, g, o.
 
-The five named configurations reproduce the shapes of the paper's model
+The first five named configurations reproduce the shapes of the paper's model
 families (Section "Architectures", Appendix B) at the batch sizes, clip norm and
 noise multiplier the benchmark fixes; the records of MNIST / CIFAR10 / IMDb /
 Adult are not used, inputs are random with the same shapes and value ranges.
@@ -51,6 +52,10 @@ def embedding(vocab, dim):
 
 def lstm_last(d_in, hidden):
     return {"kind": "lstm_last", "d_in": int(d_in), "hidden": int(hidden)}
+
+
+def seq_mean():
+    return {"kind": "seq_mean"}
 
 
 def image_input(c, h=1, w=1):
@@ -98,6 +103,9 @@ def layer_shapes(m):
         elif k == "lstm_last":
             assert cur[0] == "seq" and cur[2] == L["d_in"], (cur, L)
             cur = ("vec", L["hidden"])
+        elif k == "seq_mean":
+            assert cur[0] == "seq", (cur, L)
+            cur = ("vec", cur[2])
         else:
             raise ValueError(k)
         out.append(cur)
@@ -221,12 +229,18 @@ def cfg5_lstm(vocab=10000, seq_len=256, dim=100, hidden=100):
     return model(token_input(seq_len), [embedding(vocab, dim), lstm_last(dim, hidden), dense(hidden, 2)], 2)
 
 
+def cfg6_embedding(vocab=10000, seq_len=256, dim=16):
+    """The paper's embedding network (Appendix B): embedding, mean over the sequence, linear classifier."""
+    return model(token_input(seq_len), [embedding(vocab, dim), seq_mean(), dense(dim, 2)], 2)
+
+
 CONFIGS = {
     "cfg1_logistic": dict(build=cfg1_logistic, batch=256, x_dist="uniform"),
     "cfg2_mlp": dict(build=cfg2_mlp, batch=512, x_dist="uniform"),
     "cfg3_small_cnn": dict(build=cfg3_small_cnn, batch=1024, x_dist="uniform"),
     "cfg4_cifar_cnn": dict(build=cfg4_cifar_cnn, batch=1024, x_dist="normal"),
     "cfg5_lstm": dict(build=cfg5_lstm, batch=512, x_dist="uniform"),
+    "cfg6_embedding": dict(build=cfg6_embedding, batch=512, x_dist="uniform"),
 }
 CLIP_C = 1.0
 SIGMA = 1.1
@@ -262,4 +276,5 @@ def tiny_models():
             conv2d(40, 70, 3, stride=1, pad=1, act="tanh"), conv2d(70, 24, 3, stride=1, pad=0, act="tanh"),
             maxpool2d(2, 2), dense(24 * 3 * 3, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
+        "tiny_emb": model(token_input(6), [embedding(7, 3), seq_mean(), dense(3, 2)], 2),
     }

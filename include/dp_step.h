@@ -44,8 +44,10 @@ typedef enum {
   DP_CONV2D = 1,    /* cross-correlation, zero padding, W[out_ch][in_ch][kh][kw], b[out_ch]   */
   DP_MAXPOOL2D = 2, /* window kh x kw, stride, no padding; gradient goes to the first maximum */
   DP_EMBEDDING = 3, /* E[vocab][embed_dim]; input int32 token ids [B, seq_len]                */
-  DP_LSTM_LAST = 4  /* one-layer LSTM, returns the last hidden state; W_ih[in_features][4H],
+  DP_LSTM_LAST = 4, /* one-layer LSTM, returns the last hidden state; W_ih[in_features][4H],
                        W_hh[H][4H], b[4H]; 4H axis ordered i, f, g, o; h_0 = c_0 = 0          */
+  DP_SEQ_MEAN = 5   /* mean over the seq_len step vectors of an embedding's output (the embedding
+                       network of the paper's Appendix B); no parameters, no fields used       */
 } dp_layer_kind;
 
 typedef enum { DP_ACT_NONE = 0, DP_ACT_RELU = 1, DP_ACT_TANH = 2 } dp_act;

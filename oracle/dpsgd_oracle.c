@@ -42,7 +42,7 @@
 #include <omp.h>
 #endif
 
-enum { OR_DENSE = 0, OR_CONV2D = 1, OR_MAXPOOL2D = 2, OR_EMBEDDING = 3, OR_LSTM_LAST = 4 };
+enum { OR_DENSE = 0, OR_CONV2D = 1, OR_MAXPOOL2D = 2, OR_EMBEDDING = 3, OR_LSTM_LAST = 4, OR_SEQ_MEAN = 5 };
 enum { OR_ACT_NONE = 0, OR_ACT_RELU = 1, OR_ACT_TANH = 2 };
 
 typedef struct {
@@ -81,6 +81,7 @@ static shp out_shape(const or_layer *L, shp in, int seq_len) {
     break;
   case OR_EMBEDDING: o.c = seq_len; o.h = L->dim; o.w = 1; break;
   case OR_LSTM_LAST: o.c = L->d_out; o.h = o.w = 1; break;
+  case OR_SEQ_MEAN: o.c = in.h; o.h = o.w = 1; break; /* [T, D] -> [D] */
   }
   return o;
 }
@@ -239,6 +240,14 @@ static double forward(const or_model *m, const double *theta, const void *x, int
       for (int t = 0; t < m->seq_len; ++t)
         for (int e = 0; e < L->dim; ++e) a[(long)t * L->dim + e] = th[(long)tok[t] * L->dim + e];
     } break;
+    case OR_SEQ_MEAN: { /* the embedding network of Appendix B: mean of the T step vectors */
+      int T = cur.c, D = cur.h;
+      for (int e = 0; e < D; ++e) {
+        double acc = 0;
+        for (int t = 0; t < T; ++t) acc += in[(long)t * D + e];
+        a[e] = acc / T;
+      }
+    } break;
     case OR_LSTM_LAST: {
       int T = cur.c, D = L->d_in, H = L->d_out;
       const double *Wih = th, *Whh = th + (long)D * 4 * H, *b = Whh + (long)H * 4 * H;
@@ -352,6 +361,11 @@ static void backward(const or_model *m, const double *theta, const void *x, int 
     case OR_EMBEDDING: {
       for (int t = 0; t < m->seq_len; ++t)
         for (int e = 0; e < L->dim; ++e) gl[(long)tok[t] * L->dim + e] += dout[(long)t * L->dim + e];
+    } break;
+    case OR_SEQ_MEAN: {
+      int T = ishp.c, D = ishp.h;
+      for (int t = 0; t < T; ++t)
+        for (int e = 0; e < D; ++e) din[(long)t * D + e] = dout[e] / T;
     } break;
     case OR_LSTM_LAST: {
       int T = ishp.c, D = L->d_in, H = L->d_out;

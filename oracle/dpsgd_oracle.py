@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dpsgd_oracle.c")
 _LIB = os.path.join(_HERE, "libdpsgd_oracle.so")
 
-_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4}
+_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 

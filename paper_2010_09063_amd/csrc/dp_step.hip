@@ -145,7 +145,8 @@ static const char *layer_label(Layer &l, int li, const char *name) {
 static const char *const kLayerLabels[] = {"dense_fwd", "dense_fwd_epilogue", "dense_norm", "dense_bwd_data", "dense_clipped_sum",
                                            "conv_weight_layout", "conv_fwd", "conv_wgrad_norm", "conv_bwd_data", "conv_clipped_sum",
                                            "maxpool_fwd", "maxpool_bwd", "lstm_xproj", "lstm_fwd", "lstm_bwd", "lstm_wgrad_norm",
-                                           "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_gather", "emb_bucket", "emb_scatter", "fill_zero"};
+                                           "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_gather", "emb_bucket", "emb_scatter", "fill_zero",
+                                           "seq_mean_fwd", "seq_mean_bwd"};
 
 struct dp_ctx {
   dp_model_desc m;
@@ -437,6 +438,13 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       l.max_slots = ceil_div(l.Din + l.H + 1, 32) * ceil_div(4 * l.H, 32);
       is_seq = false;
       break;
+    case DP_SEQ_MEAN:
+      if (!is_seq) { rc = DP_EINVAL; break; }
+      if (i == 0 || model->layers[i - 1].kind != DP_EMBEDDING) { rc = DP_EUNSUPPORTED; break; }
+      l.T = curC; l.Din = curH;
+      l.outC = curH; l.outH = l.outW = 1;
+      is_seq = false;
+      break;
     default: rc = DP_EINVAL;
     }
     if (rc != DP_OK) break;
@@ -702,6 +710,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
                              l.d.embed_dim);
         });
       } break;
+      case DP_SEQ_MEAN: {
+        dim3 grid(B), block(256);
+        Ln(LL("seq_mean_fwd"), grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(seq_mean_fwd_kernel, grid, block, 0, st, in, l.a, l.T, l.Din);
+        });
+      } break;
       case DP_LSTM_LAST: {
         const int G = 4 * l.H;
         auto run = [&](auto vt) {
@@ -856,6 +870,13 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           };
           vec_dispatch(OpRowMajor<true>::can_vec(l.gates, G, 0, G) && OpRowMajor<true>::can_vec(W, G, 0, G), run);
         }
+      } break;
+      case DP_SEQ_MEAN: {
+        const long n = (long)B * l.in_size;
+        dim3 grid = grid1d(n, 256), block(256);
+        Ln(LL("seq_mean_bwd"), grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(seq_mean_bwd_kernel, grid, block, 0, st, (const float *)l.g, prev->g, n, l.T, l.Din);
+        });
       } break;
       case DP_EMBEDDING: {
         if (priv) {

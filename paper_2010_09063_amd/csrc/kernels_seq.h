@@ -32,6 +32,42 @@ __global__ void emb_gather_kernel(const int *__restrict__ tok, const float *__re
 
 __device__ __forceinline__ float sigmoidf_(float v) { return fast_sigmoid(v); }
 
+// Mean over the T step vectors of a sequence (embedding network, Appendix B): out[b, e] = (1/T) sum_t in[b, t, e].
+// One workgroup per example: thread (tl, e) sums the steps tl, tl + ntl, ... of coordinate e (consecutive threads
+// read consecutive coordinates of one step), the ntl partial sums of a coordinate are added in a fixed order.
+__global__ __launch_bounds__(256) void seq_mean_fwd_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                                            int T, int D) {
+  __shared__ float part[256];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int dp = D < 256 ? D : 256, ntl = 256 / dp;
+  const int e_l = tid % dp, tl = tid / dp;
+  const float *p = in + (long)b * T * D;
+  for (int e0 = 0; e0 < D; e0 += dp) {
+    const int e = e0 + e_l;
+    float s = 0.f;
+    if (tl < ntl && e < D)
+      for (int t = tl; t < T; t += ntl) s += p[(long)t * D + e];
+    part[tid] = s;
+    __syncthreads();
+    if (tl == 0 && e < D) {
+      float tot = 0.f;
+      for (int q = 0; q < ntl; ++q) tot += part[q * dp + e_l];
+      out[(long)b * D + e] = tot / (float)T;
+    }
+    __syncthreads();
+  }
+}
+
+// ... and its gradient: every step receives g[b, e] / T.  One thread per (b, t, e).
+__global__ void seq_mean_bwd_kernel(const float *__restrict__ g, float *__restrict__ gin, long n, int T, int D) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const long bt = i / D;
+  const int e = (int)(i - bt * D);
+  const long b = bt / T;
+  gin[i] = g[b * D + e] / (float)T;
+}
+
 // Forward.  gates: in  x_t W_ih + b for every (b, t); out activated i, f, g, o.
 // hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T.
 // Thread j < 2H owns columns j and j + 2H of W_hh (H <= 128, HP = H rounded up to 4).

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdpstep.so")
 
 DP_OK, DP_EINVAL, DP_ENOMEM, DP_EHIP, DP_EUNSUPPORTED = 0, -1, -2, -3, -4
-_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4}
+_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 EXPORTS = ["dp_step_init", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_nonprivate",

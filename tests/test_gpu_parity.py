@@ -53,7 +53,8 @@ def test_tiny_models(name, batch):
 
 
 # real layer shapes, batches that span several tiles and leave a ragged tail
-REDUCED = {"cfg1_logistic": 100, "cfg2_mlp": 77, "cfg3_small_cnn": 37, "cfg4_cifar_cnn": 5, "cfg5_lstm": 6}
+REDUCED = {"cfg1_logistic": 100, "cfg2_mlp": 77, "cfg3_small_cnn": 37, "cfg4_cifar_cnn": 5, "cfg5_lstm": 6,
+           "cfg6_embedding": 45}
 
 
 @pytest.mark.parametrize("name", sorted(REDUCED))
@@ -62,7 +63,8 @@ def test_benchmark_architectures_reduced_batch(name):
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], name)
 
 
-@pytest.mark.parametrize("name", ["cfg1_logistic", "cfg2_mlp", "cfg3_small_cnn", "cfg5_lstm", "cfg4_cifar_cnn"])
+@pytest.mark.parametrize("name", ["cfg1_logistic", "cfg2_mlp", "cfg3_small_cnn", "cfg5_lstm", "cfg6_embedding",
+                                  "cfg4_cifar_cnn"])
 def test_benchmark_full_size(name):
     """Full batch, benchmark launch configuration (C = 1, then a C that clips about half)."""
     wl = W.make_workload(name, seed=0)

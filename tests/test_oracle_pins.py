@@ -294,3 +294,25 @@ def test_embedding_duplicates_are_summed_before_the_norm():
     assert np.count_nonzero(np.abs(g2[:E].reshape(7, 3)).sum(1)) == 5
     G = TR.per_example_grads(m, theta, np.stack([x_same, x_distinct]), np.array([1, 1]))
     assert np.allclose(G[0], g, atol=1e-12) and np.allclose(G[1], g2, atol=1e-12)
+
+
+def test_embedding_mean_pool_norm_closed_form():
+    """Embedding network (Appendix B): with a mean over T steps every step receives g/T, so row v of the embedding
+    gradient is (count_v / T) g and its squared norm sum_v (count_v / T)^2 |g|^2, whatever the classifier does."""
+    m = W.model(W.token_input(9), [W.embedding(6, 4), W.seq_mean(), W.dense(4, 3)], 3)
+    rng = np.random.default_rng(3)
+    theta = W.init_params(m, rng, bias_scale=0.3).astype(np.float64)
+    tok = np.array([0, 2, 2, 5, 2, 0, 1, 5, 5], dtype=np.int32)
+    _, g, _ = O.example_grad(m, theta, tok, 1)
+    gE = g[:24].reshape(6, 4)
+    counts = np.bincount(tok, minlength=6).astype(np.float64)
+    # rows are parallel to one vector u = g_pooled / T: recover it from the row of token 1 (count 1)
+    u = gE[1]
+    assert np.allclose(gE, counts[:, None] * u[None, :], rtol=1e-12, atol=1e-15)
+    assert np.isclose((gE ** 2).sum(), (counts ** 2).sum() * (u ** 2).sum(), rtol=1e-12)
+    # and u is W delta / T with delta = softmax - onehot of the classifier on the mean embedding
+    E, Wd, bd = theta[:24].reshape(6, 4), theta[24:36].reshape(4, 3), theta[36:39]
+    z = E[tok].mean(axis=0) @ Wd + bd
+    p = np.exp(z - z.max()); p /= p.sum()
+    delta = p - np.eye(3)[1]
+    assert np.allclose(u, Wd @ delta / 9.0, rtol=1e-12, atol=1e-15)

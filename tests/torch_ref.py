@@ -51,6 +51,8 @@ def logits(m, theta, x):
                       "bias_ih_l0": p[(li, "b")], "bias_hh_l0": torch.zeros(4 * H, dtype=torch.float64)}
             out, _ = torch.func.functional_call(lstm, params, (h,))
             h = out[:, -1, :]
+        elif k == "seq_mean":
+            h = h.mean(dim=1)
     return h
 
 
