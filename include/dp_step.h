@@ -108,6 +108,18 @@ int dp_step(dp_ctx *ctx, const float *params, const void *x, const int32_t *y, i
             uint64_t seed, float *out_grad);
 
 /*
+ * dp_step_sgd -- dp_step followed by the parameter update of the same procedure (Section 1,
+ * item 4: "update the parameters by a step against the noised aggregate"), fused into the
+ * final write:   params[j] -= (lr / batch) * (clipped_sum[j] + sigma*C*z_j).
+ *   params     device, [num_params], read by the step and UPDATED IN PLACE by its last kernel.
+ *   lr         learning rate; the aggregate is a sum over the batch, so the step uses lr / batch.
+ *   out_grad   device, [num_params] or NULL: where given, also receives the noised sum as dp_step writes it.
+ *   batch      1 .. max_batch.  Other arguments, ownership and errors as for dp_step.
+ */
+int dp_step_sgd(dp_ctx *ctx, float *params, const void *x, const int32_t *y, int batch, float C, float sigma,
+                uint64_t seed, float lr, float *out_grad);
+
+/*
  * dp_step_nonprivate -- the ordinary summed gradient sum_i g_i with the same
  * forward / backward kernels and no norms, clipping or noise (the comparator of
  * the paper's private / non-private runtime ratio, Table 1).

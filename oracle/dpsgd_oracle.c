@@ -535,6 +535,28 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
   return 0;
 }
 
+/* DPSGD item 4 after items 2-3 (Section 1): theta <- theta - (lr / B) * (clipped sum + sigma*C*z), the step taken
+ * in double from the double-precision aggregate and rounded once to float.  theta_new may alias nothing. */
+int oracle_sgd_step(const or_model *m, const float *params, const void *x, const int32_t *y, int B, double C,
+                    double sigma, uint64_t seed, double lr, float *theta_new, int n_threads) {
+  long P = oracle_num_params(m);
+  if (B < 1) return -1;
+  float *out = (float *)malloc(sizeof(float) * P);
+  double *csum = (double *)malloc(sizeof(double) * P);
+  double *z = (double *)malloc(sizeof(double) * P);
+  int rc = (out && csum && z) ? 0 : -1;
+  if (rc == 0) rc = oracle_dp_step(m, params, x, y, B, C, 0.0, seed, 1, out, NULL, csum, NULL, NULL, n_threads);
+  if (rc == 0) {
+    if (sigma > 0) oracle_noise(seed, P, z);
+    for (long j = 0; j < P; ++j) {
+      double agg = csum[j] + (sigma > 0 ? sigma * C * z[j] : 0.0);
+      theta_new[j] = (float)((double)params[j] - lr / B * agg);
+    }
+  }
+  free(out); free(csum); free(z);
+  return rc;
+}
+
 int oracle_max_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

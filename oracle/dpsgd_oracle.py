@@ -61,6 +61,9 @@ def lib():
         L.oracle_dp_step.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_double,
                                      C.c_double, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                      C.POINTER(C.c_long), C.c_void_p, C.c_int]
+        L.oracle_sgd_step.restype = C.c_int
+        L.oracle_sgd_step.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_double,
+                                      C.c_double, C.c_uint64, C.c_double, C.c_void_p, C.c_int]
         L.oracle_max_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -163,6 +166,20 @@ def dp_step(m, params, x, y, clip_c, sigma, seed, clip=True, n_threads=0):
                               norms.ctypes.data, csum.ctypes.data, C.byref(ties), margin.ctypes.data, int(n_threads))
     assert rc == 0
     return dict(out=out, norms=norms, clipped_sum=csum, ties=int(ties.value), pool_margin=margin)
+
+
+def sgd_step(m, params, x, y, clip_c, sigma, seed, lr, n_threads=0):
+    """One private step followed by the parameter update: theta - (lr / B) * (clipped sum + sigma*C*z), fp32[P]."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(params, dtype=np.float32)
+    xa = _x_array(m, x)
+    ya = np.ascontiguousarray(y, dtype=np.int32)
+    new = np.empty(th.size, dtype=np.float32)
+    rc = lib().oracle_sgd_step(C.byref(cm), th.ctypes.data, xa.ctypes.data, ya.ctypes.data, int(ya.shape[0]),
+                               float(clip_c), float(sigma), C.c_uint64(int(seed)), float(lr), new.ctypes.data,
+                               int(n_threads))
+    assert rc == 0
+    return new
 
 
 def max_threads():

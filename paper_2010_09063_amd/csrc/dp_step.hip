@@ -603,7 +603,7 @@ static inline void vec_dispatch(bool cond, F &&body) {
   else body(std::false_type{});
 }
 static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t *y, int B, bool priv, float C,
-                    float sigma, uint64_t seed, float *out) {
+                    float sigma, uint64_t seed, float *out, float *theta_update = nullptr, float update_step = 0.f) {
   Launcher Ln{c};
   const int nL = (int)c->L.size();
   const long slot_stride = c->maxB;
@@ -1022,7 +1022,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     dim3 grid = grid1d(c->P, DP_FIN_CO), block(256);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     Ln("finalize_noise", grid, block, [&](hipStream_t st) {
-      hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, c->P, noise_std, k0, k1);
+      hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, c->P, noise_std, k0, k1, theta_update, update_step);
     });
   }
   hipError_t e = hipGetLastError();
@@ -1041,6 +1041,15 @@ extern "C" int dp_step(dp_ctx *c, const float *params, const void *x, const int3
   if (!(C > 0.f) || !(sigma >= 0.f) || std::isnan(C) || std::isinf(sigma)) return DP_EINVAL;
   if (std::isinf(C) && sigma > 0.f) return DP_EINVAL;
   return run_step(c, params, x, y, batch, true, C, sigma, seed, out_grad);
+}
+
+extern "C" int dp_step_sgd(dp_ctx *c, float *params, const void *x, const int32_t *y, int batch, float C, float sigma,
+                           uint64_t seed, float lr, float *out_grad) {
+  if (!c || !params || batch < 1 || batch > c->maxB || !x || !y) return DP_EINVAL;
+  if (!(C > 0.f) || !(sigma >= 0.f) || std::isnan(C) || std::isinf(sigma) || std::isnan(lr) || std::isinf(lr)) return DP_EINVAL;
+  if (std::isinf(C) && sigma > 0.f) return DP_EINVAL;
+  // every kernel of the step reads params before the final write, which is the last launch on the stream
+  return run_step(c, params, x, y, batch, true, C, sigma, seed, out_grad, params, lr / (float)batch);
 }
 
 extern "C" int dp_step_nonprivate(dp_ctx *c, const float *params, const void *x, const int32_t *y, int batch,

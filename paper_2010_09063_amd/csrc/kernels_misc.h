@@ -228,8 +228,11 @@ struct FinalizeArgs {
   FinalizeSeg seg[DP_MAX_SEG];
 };
 
+// theta != null: the parameter update of DPSGD item 4 is fused into the same write,
+// theta[j] -= step * (sum + noise) with step = learning rate / batch; out may then be null.
 __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P,
-                                                        float noise_std, uint32_t k0, uint32_t k1) {
+                                                        float noise_std, uint32_t k0, uint32_t k1,
+                                                        float *__restrict__ theta, float step) {
   __shared__ float red[DP_FIN_SG][DP_FIN_CO + 1];
   const int cj = threadIdx.x % DP_FIN_CO, sg = threadIdx.x / DP_FIN_CO;
   const long j = (long)blockIdx.x * DP_FIN_CO + cj;
@@ -260,6 +263,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, fl
       normal4((uint64_t)(j >> 2), k0, k1, z);
       tot += noise_std * z[j & 3];
     }
-    out[j] = tot;
+    if (out) out[j] = tot;
+    if (theta) theta[j] -= step * tot;
   }
 }

@@ -16,7 +16,7 @@ DP_OK, DP_EINVAL, DP_ENOMEM, DP_EHIP, DP_EUNSUPPORTED = 0, -1, -2, -3, -4
 _KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
-EXPORTS = ["dp_step_init", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_nonprivate",
+EXPORTS = ["dp_step_init", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
            "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
 
 
@@ -50,6 +50,9 @@ def load_library():
         L.dp_step.restype = C.c_int
         L.dp_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_float,
                               C.c_uint64, C.c_void_p]
+        L.dp_step_sgd.restype = C.c_int
+        L.dp_step_sgd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_float,
+                                  C.c_uint64, C.c_float, C.c_void_p]
         L.dp_step_nonprivate.restype = C.c_int
         L.dp_step_nonprivate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         L.dp_step_last_norms.restype = C.c_int
@@ -138,6 +141,12 @@ class DpStep:
     def dp_step(self, params, x, y, batch, C_, sigma, seed, out_grad):
         _check(self._lib.dp_step(self._ctx, _ptr(params), _ptr(x), _ptr(y), int(batch), float(C_), float(sigma),
                                  C.c_uint64(int(seed) & (2**64 - 1)), _ptr(out_grad)))
+
+    # -- dp_step_sgd
+    def dp_step_sgd(self, params, x, y, batch, C_, sigma, seed, lr, out_grad=None):
+        _check(self._lib.dp_step_sgd(self._ctx, _ptr(params), _ptr(x), _ptr(y), int(batch), float(C_), float(sigma),
+                                     C.c_uint64(int(seed) & (2**64 - 1)), float(lr),
+                                     _ptr(out_grad) if out_grad is not None else None))
 
     # -- dp_step_nonprivate
     def dp_step_nonprivate(self, params, x, y, batch, out_grad):

@@ -234,3 +234,41 @@ def test_repeatable_and_profile_hook():
     torch.cuda.synchronize()
     assert not torch.equal(o1, o2)
     st.dp_step_free()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,batch", [("tiny_dense", 9), ("tiny_conv3", 5), ("tiny_lstm", 4), ("tiny_emb", 7),
+                                        ("cfg3_small_cnn", 33)])
+def test_fused_sgd_update(name, batch):
+    """dp_step_sgd: the update of Section 1 item 4 fused into the final write, against the oracle's step."""
+    import torch
+    from paper_2010_09063_amd import DpStep
+    if name in TINY:
+        m = TINY[name]
+        x, y, theta = _case(m, batch, seed=21)
+    else:
+        wl = W.make_workload(name, batch=batch, seed=21, bias_scale=0.2)
+        m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    x, y, _ = clear_pool_examples(m, theta, x, y, O.dp_step)
+    norms = O.dp_step(m, theta, x, y, 1.0, 0.0, 0)["norms"]
+    Cc, sigma, seed, lr = float(np.median(norms)), 0.7, 77, 0.25 * batch
+    want = O.sgd_step(m, theta, x, y, Cc, sigma, seed, lr)
+    dev = torch.device("cuda:0")
+    st = DpStep(m, batch)
+    tp = torch.from_numpy(theta.copy()).to(dev)
+    tx, ty = torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)
+    out = torch.empty(st.num_params, dtype=torch.float32, device=dev)
+    st.dp_step_sgd(tp, tx, ty, batch, Cc, sigma, seed, lr, out)
+    torch.cuda.synchronize()
+    got, g = tp.cpu().numpy(), out.cpu().numpy()
+    ref = O.dp_step(m, theta, x, y, Cc, sigma, seed)
+    upd_got, upd_want = got.astype(np.float64) - theta, want.astype(np.float64) - theta
+    print(f"{name}: update rel_l2 {rel_l2(upd_got, upd_want):.2e}", flush=True)
+    assert rel_l2(g, ref["out"]) <= 2e-4          # the noised sum is still delivered
+    assert rel_l2(upd_got, upd_want) <= 2e-4      # fp32 subtraction on top of the 1e-4 bar of the sum
+    # a second call without out_grad continues from the updated parameters
+    st.dp_step_sgd(tp, tx, ty, batch, Cc, sigma, seed + 1, lr)
+    torch.cuda.synchronize()
+    want2 = O.sgd_step(m, got, x, y, Cc, sigma, seed + 1, lr)
+    assert rel_l2(tp.cpu().numpy().astype(np.float64) - got, want2.astype(np.float64) - got) <= 2e-4
+    st.dp_step_free()

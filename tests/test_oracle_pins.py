@@ -316,3 +316,28 @@ def test_embedding_mean_pool_norm_closed_form():
     p = np.exp(z - z.max()); p /= p.sum()
     delta = p - np.eye(3)[1]
     assert np.allclose(u, Wd @ delta / 9.0, rtol=1e-12, atol=1e-15)
+
+
+@pytest.mark.parametrize("name", ["tiny_dense_tanh", "tiny_conv2", "tiny_lstm", "tiny_emb"])
+def test_sgd_step_reduces_to_plain_sgd(name):
+    """Section 1, item 4 after items 2-3: with no clipping and no noise the private update is one step of ordinary
+    SGD on the mean loss (torch.optim.SGD on an independent autograd model)."""
+    import torch
+    m = TINY[name]
+    rng = np.random.default_rng(17)
+    x, y = W.make_inputs(m, 6, rng)
+    theta = W.init_params(m, rng, bias_scale=0.3)
+    lr = 0.37
+    new = O.sgd_step(m, theta, x, y, float("inf"), 0.0, 0, lr)
+    G = TR.per_example_grads(m, theta.astype(np.float64), x, y)   # [B, P] from autograd
+    t = torch.nn.Parameter(torch.from_numpy(theta.astype(np.float64)))
+    opt = torch.optim.SGD([t], lr=lr)
+    t.grad = torch.from_numpy(G.mean(axis=0))
+    opt.step()
+    assert np.allclose(new, t.detach().numpy().astype(np.float32), rtol=0, atol=2e-7)
+    # and with clipping + noise it is theta - lr/B * out of the step itself
+    ref = O.dp_step(m, theta, x, y, 0.5, 1.1, 9)
+    new2 = O.sgd_step(m, theta, x, y, 0.5, 1.1, 9, lr)
+    z = O.noise(9, theta.size)
+    want = theta.astype(np.float64) - lr / 6 * (ref["clipped_sum"] + 1.1 * 0.5 * z)
+    assert np.array_equal(new2, want.astype(np.float32))
