@@ -59,11 +59,20 @@ __global__ void conv_weight_layout_kernel(const float *__restrict__ w, float *__
 }
 
 #define CONV_XPLANE_MAX 448 // staged floats per channel: a thread stages at most CC*448/256 elements per chunk
+#define CONV_CC 8           // input channels staged per chunk
 
 // CC = input channels staged per chunk (8 or 16): a longer chunk amortises the two barriers
 // and gives the prefetch of the next chunk more multiply time to hide behind.
+// While another wave of the SIMD streams MFMAs, every other instruction of this kernel takes about
+// one MFMA slot to issue, so the phases around the K loop are written for instruction count: global
+// addresses are a wave-uniform pointer (scalar arithmetic) plus a 32-bit lane offset fixed for the
+// tile, validity is folded into that offset (an invalid item reads a valid address and is zeroed when
+// staged), the re-laid weights are padded so that no weight load needs a test, and the epilogue uses
+// one pointer per output row with a lane offset per pixel.
+// (the waves-per-SIMD ceiling keeps the compiler from spilling the prefetched tiles to reach a higher occupancy)
 template <int KH, int KW, int DT, int NPW, int CC>
-__global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (DT * NPW <= 32 * 64 ? 3 : 2))))
+void conv_s1_kernel(const ConvS1Args a) {
   constexpr int KK = KH * KW, DB = DT / 32, PB = NPW / 32;
   constexpr int XP = (CONV_XPLANE_MAX + 255) / 256; // staged positions per thread within a channel plane
   constexpr int WROWS = CC * KK;                     // weight rows per chunk
@@ -71,7 +80,8 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
   extern __shared__ __attribute__((aligned(16))) float smem[];
   float *Wl = smem;                 // [WROWS][DT]
   float *Xl = smem + WROWS * DT;    // [CC][XPLANE]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 31, lk = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m0 = blockIdx.y * DT;
   // tile -> first image and first row
   int b0, r0;
@@ -81,32 +91,43 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
 
   // this lane's pixels (one per 32-pixel block of the wave)
   int xoff[PB];
-  long ooff[PB]; // offset of the pixel in out for channel 0, or -1
+  unsigned ooff[PB]; // lane byte offset of the pixel in out relative to the tile's first image / row, row 4*lk of a block
+  bool pix_ok[PB];
 #pragma unroll
   for (int pb = 0; pb < PB; ++pb) {
     const int lp = wave * NPW + pb * 32 + li;
     const int img = (int)a.t.dTROW.div(lp), rem = lp - img * a.t.TR * a.OW;
     const int r = (int)a.t.dOW.div(rem), col = rem - r * a.OW;
     const bool ok = img < a.t.NIMG && (b0 + img) < a.B && (r0 + r) < a.OH;
+    pix_ok[pb] = ok;
     xoff[pb] = (ok ? img * a.t.IMGPL + r * a.t.LDW + col : 0) + lk * a.t.XPLANE;
-    ooff[pb] = ok ? ((long)(b0 + img) * a.M) * OHW + (long)(r0 + r) * a.OW + col : -1;
+    ooff[pb] = ok ? 4u * (unsigned)((img * a.M + 4 * lk) * OHW + r * a.OW + col) : 0u; // bytes
   }
-  // staged input: a thread owns up to XP positions of the channel plane (img, rr, cc) and stages
-  // them for every channel of the chunk, so one offset per position is all it keeps
-  int goff[XP]; // offset inside x of channel 0 for the position, or -1 (halo / outside the batch / past the plane)
+  // staged input: a thread owns up to XP positions of the channel plane (img, rr, cc) and stages them for every
+  // channel of the chunk.  xg = lane offset in x relative to xtile (below); positions that hold no input (halo,
+  // outside the batch, past the plane) point at element (0, 0) of the channel and are zeroed when staged.
+  unsigned xg[XP];
+  bool xv[XP];
 #pragma unroll
   for (int j = 0; j < XP; ++j) {
     const int pos = tid + j * 256;
-    goff[j] = -1;
-    if (pos < a.t.XPLANE) {
-      const int img = (int)a.t.dIMGPL.div(pos), rem2 = pos - img * a.t.IMGPL;
-      const int rr = (int)a.t.dLDW.div(rem2), cc = rem2 - rr * a.t.LDW;
-      const int ih = r0 + rr - a.pad, iw = cc - a.pad;
-      if (img < a.t.NIMG && (b0 + img) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W)
-        goff[j] = (b0 + img) * a.Cin * HW + ih * a.W + iw;
-    }
+    const int img = (int)a.t.dIMGPL.div(pos), rem2 = pos - img * a.t.IMGPL;
+    const int rr = (int)a.t.dLDW.div(rem2), cc = rem2 - rr * a.t.LDW;
+    const int ih = r0 + rr - a.pad, iw = cc - a.pad;
+    xv[j] = pos < a.t.XPLANE && img < a.t.NIMG && (b0 + img) < a.B && (unsigned)ih < (unsigned)a.H &&
+            (unsigned)iw < (unsigned)a.W;
+    xg[j] = xv[j] ? 4u * (unsigned)(img * a.Cin * HW + ih * a.W + iw) : 0u; // bytes
   }
-  // weight items: float4 q = tid + j*256 covers row q / (DT/4), columns 4*(q % (DT/4)) ..+3
+  const float *xtile = a.x + (long)b0 * a.Cin * HW; // channel 0 of the tile's first image
+  // weight items: float4 q = tid + j*256 covers row q / (DT/4), columns 4*(q % (DT/4)) ..+3 (rows past the
+  // chunk and columns past Mpad read the zero padding of the re-laid weights or finite values nobody uses)
+  unsigned wg[WV];
+#pragma unroll
+  for (int j = 0; j < WV; ++j) {
+    const int q = tid + j * 256;
+    const int row = q / (DT / 4);
+    wg[j] = 4u * (unsigned)(row * a.Mpad + 4 * (q - row * (DT / 4))); // bytes
+  }
 
   f32x16 acc[DB][PB];
 #pragma unroll
@@ -119,23 +140,17 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
   float xr[XP][CC];
   float4 wr[WV];
   auto prefetch = [&](int c0) {
-    // every load is unconditional (an invalid item reads element 0 and is zeroed afterwards): a load
-    // under a branch would make the compiler drain all outstanding loads at each join
 #pragma unroll
-    for (int j = 0; j < XP; ++j)
+    for (int c = 0; c < CC; ++c) {
+      const float *xc = xtile + (long)min(c0 + c, a.Cin - 1) * HW; // a channel past Cin re-reads the last one
 #pragma unroll
-      for (int c = 0; c < CC; ++c) {
-        const bool ok = goff[j] >= 0 && c0 + c < a.Cin;
-        const float v = a.x[ok ? (long)goff[j] + (long)(c0 + c) * HW : 0];
-        xr[j][c] = ok ? v : 0.f;
-      }
+      for (int j = 0; j < XP; ++j) xr[j][c] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xc) + xg[j]);
+    }
+    const float *wc = a.wt + ((long)c0 * KK * a.Mpad + m0);
 #pragma unroll
     for (int j = 0; j < WV; ++j) {
-      const int q = tid + j * 256;
-      const int row = q / (DT / 4), m = m0 + 4 * (q - row * (DT / 4));
-      const bool ok = row < WROWS && c0 * KK + row < a.Cin * KK && m < a.Mpad;
-      const float4 v = *reinterpret_cast<const float4 *>(a.wt + (ok ? (long)(c0 * KK + row) * a.Mpad + m : 0));
-      wr[j] = ok ? v : f4zero();
+      const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(wc) + wg[j]);
+      wr[j] = make_float4(v.x, v.y, v.z, v.w);
     }
   };
 
@@ -147,7 +162,7 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
       const int pos = tid + j * 256;
       if (pos < a.t.XPLANE)
 #pragma unroll
-        for (int c = 0; c < CC; ++c) Xl[c * a.t.XPLANE + pos] = xr[j][c];
+        for (int c = 0; c < CC; ++c) Xl[c * a.t.XPLANE + pos] = (xv[j] && c0 + c < a.Cin) ? xr[j][c] : 0.f;
     }
 #pragma unroll
     for (int j = 0; j < WV; ++j) {
@@ -182,31 +197,44 @@ __global__ __launch_bounds__(256) void conv_s1_kernel(const ConvS1Args a) {
     }
   }
 
-  // epilogue: bias + activation (forward) or the derivative of the producing activation
-  // (backward-data).  The 16 side loads of a block (bias / a_prev) are issued together from
-  // safe addresses before any of them is used.
+  // epilogue: bias + activation (forward) or the derivative of the producing activation (backward-data).
+  // Output row m = m0 + 32*i + 8*(r/4) + 4*lk + r%4 of pixel j lives at
+  //   (uniform pointer of row m0 + 32*i + 8*(r/4) + r%4 of the tile's first image) + ooff[j].
   const bool fwd = a.bias != nullptr;
-  const float *side = fwd ? a.bias : (a.act ? a.a_prev : a.x);
+  const long tile_off = (long)b0 * a.M * OHW + (long)r0 * a.OW;
+  const int mrem = a.M - m0 - 4 * lk; // rows i*32 + 8*(r/4) + r%4 below mrem exist for this lane
 #pragma unroll
-  for (int j = 0; j < PB; ++j) {
-#pragma unroll
-    for (int i = 0; i < DB; ++i) {
-      float sv[16];
+  for (int i = 0; i < DB; ++i) {
+    float bias_v[16]; // forward: the bias of the lane's 16 rows (backward-data loads x[0..] here and ignores it)
+    {
+      const float *bsrc = fwd ? a.bias : a.x;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        const bool ok = ooff[j] >= 0 && m < a.M;
-        sv[r] = side[ok ? (fwd ? (long)m : ooff[j] + (long)m * OHW) : 0];
+        const int mu = i * 32 + 8 * (r >> 2) + (r & 3);
+        bias_v[r] = bsrc[fwd ? min(m0 + mu + 4 * lk, a.M - 1) : 0];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < PB; ++j) {
+      if (!pix_ok[j]) continue;
+      const float *side = (fwd || !a.act) ? a.x : a.a_prev; // backward-data: the producing activation's output
+      float sv[16];
+      const bool need_side = !fwd && a.act;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int mu = i * 32 + 8 * (r >> 2) + (r & 3);
+        // (a row past M is not read: the pointer stays on the last real row and the lane offset is dropped)
+        const float *row = need_side ? side + (tile_off + (long)(m0 + min(mu, a.M - 1 - m0)) * OHW) : a.x;
+        sv[r] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(row) + ((need_side && mu < mrem) ? ooff[j] : 0u));
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
-        if (ooff[j] >= 0 && m < a.M) {
-          float v = acc[i][j][r];
-          if (fwd) v = act_apply(a.act, v + sv[r]);
-          else if (a.act) v *= act_deriv_from_out(a.act, sv[r]);
-          a.out[ooff[j] + (long)m * OHW] = v;
-        }
+        const int mu = i * 32 + 8 * (r >> 2) + (r & 3);
+        float v = acc[i][j][r];
+        if (fwd) v = act_apply(a.act, v + bias_v[r]);
+        else if (a.act) v *= act_deriv_from_out(a.act, sv[r]);
+        float *row = a.out + (tile_off + (long)(m0 + mu) * OHW);
+        if (mu < mrem) *reinterpret_cast<float *>(reinterpret_cast<char *>(row) + ooff[j]) = v;
       }
     }
   }

@@ -511,7 +511,10 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       }
     }
     if (rc == DP_OK && (l.dir_fwd || l.dir_bwd)) {
-      const size_t nf = (size_t)l.geom.C * 9 * ((l.geom.D + 3) & ~3), nb = (size_t)l.geom.D * 9 * ((l.geom.C + 3) & ~3);
+      // rows rounded up to whole chunks plus one spare chunk, and 128 spare floats: the kernels load weight
+      // tiles without range tests and read this zero padding instead
+      const size_t rf = (size_t)(ceil_div(l.geom.C, CONV_CC) + 1) * CONV_CC * 9, rb = (size_t)(ceil_div(l.geom.D, CONV_CC) + 1) * CONV_CC * 9;
+      const size_t nf = rf * ((l.geom.D + 3) & ~3) + 128, nb = rb * ((l.geom.C + 3) & ~3) + 128;
       rc = dev_alloc(c, &l.wt_f, nf);
       if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, nb);
       if (rc == DP_OK && (hipMemset(l.wt_f, 0, nf * sizeof(float)) != hipSuccess ||
