@@ -296,7 +296,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
 template <class LN>
 static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a, int npw) {
   const int dt = a.M <= 32 ? 32 : (a.M <= 64 ? 64 : 128);
-  const int cc = 8;
+  const int cc = a.Cin <= 4 ? 4 : 8; // first layers: a chunk of four channels covers the whole input
   dim3 grid(a.t.NIMG > 1 ? ceil_div(a.B, a.t.NIMG) : a.B * a.t.row_tiles, ceil_div(a.M, dt)), block(256);
   size_t smem = sizeof(float) * ((size_t)cc * a.t.XPLANE + (size_t)cc * 9 * dt);
 #define DP_CONV_CASE(dt_, npw_, cc_)                                                                 \
@@ -308,6 +308,8 @@ static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a,
   }
   DP_CONV_CASE(32, 64, 8) DP_CONV_CASE(64, 64, 8) DP_CONV_CASE(128, 64, 8)
   DP_CONV_CASE(32, 32, 8) DP_CONV_CASE(64, 32, 8) DP_CONV_CASE(128, 32, 8)
+  DP_CONV_CASE(32, 64, 4) DP_CONV_CASE(64, 64, 4) DP_CONV_CASE(128, 64, 4)
+  DP_CONV_CASE(32, 32, 4) DP_CONV_CASE(64, 32, 4) DP_CONV_CASE(128, 32, 4)
 #undef DP_CONV_CASE
 }
 
