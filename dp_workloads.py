@@ -58,6 +58,16 @@ def seq_mean():
     return {"kind": "seq_mean"}
 
 
+def lstm_seq(d_in, hidden):
+    """LSTM whose output is the hidden state of every time step, [T, hidden]."""
+    return {"kind": "lstm_seq", "d_in": int(d_in), "hidden": int(hidden)}
+
+
+def avgpool2d(k, stride):
+    """Mean over k x k windows; k = stride = the whole plane is a global average pool."""
+    return {"kind": "avgpool2d", "k": int(k), "stride": int(stride)}
+
+
 def image_input(c, h=1, w=1):
     return {"kind": "image", "c": int(c), "h": int(h), "w": int(w)}
 
@@ -93,7 +103,7 @@ def layer_shapes(m):
             assert cur[0] == "chw" and cur[1] == L["c_in"], (cur, L)
             cur = ("chw", L["c_out"], conv_out(cur[2], L["kh"], L["stride"], L["pad"]),
                    conv_out(cur[3], L["kw"], L["stride"], L["pad"]))
-        elif k == "maxpool2d":
+        elif k in ("maxpool2d", "avgpool2d"):
             assert cur[0] == "chw"
             cur = ("chw", cur[1], conv_out(cur[2], L["k"], L["stride"], 0),
                    conv_out(cur[3], L["k"], L["stride"], 0))
@@ -106,10 +116,13 @@ def layer_shapes(m):
         elif k == "seq_mean":
             assert cur[0] == "seq", (cur, L)
             cur = ("vec", cur[2])
+        elif k == "lstm_seq":
+            assert cur[0] == "seq" and cur[2] == L["d_in"], (cur, L)
+            cur = ("seq", cur[1], L["hidden"])
         else:
             raise ValueError(k)
         out.append(cur)
-    assert cur == ("vec", m["n_classes"]), cur
+    assert cur in (("vec", m["n_classes"]), ("chw", m["n_classes"], 1, 1)), cur
     return out
 
 
@@ -124,7 +137,7 @@ def param_tensors(m):
             shapes = [("W", (L["c_out"], L["c_in"], L["kh"], L["kw"])), ("b", (L["c_out"],))]
         elif k == "embedding":
             shapes = [("E", (L["vocab"], L["dim"]))]
-        elif k == "lstm_last":
+        elif k in ("lstm_last", "lstm_seq"):
             H = L["hidden"]
             shapes = [("W_ih", (L["d_in"], 4 * H)), ("W_hh", (H, 4 * H)), ("b", (4 * H,))]
         else:
@@ -234,6 +247,40 @@ def cfg6_embedding(vocab=10000, seq_len=256, dim=16):
     return model(token_input(seq_len), [embedding(vocab, dim), seq_mean(), dense(dim, 2)], 2)
 
 
+# The architectures exactly as Appendix B tabulates them (ReLU after every linear layer but the last,
+# average pools, the LSTM returning its whole output sequence, vocabulary 10,004).  The MNIST table lists a
+# third convolution and stride 1 for the second one, which cannot produce the 512 features its first fully
+# connected layer takes; stride 2 and two convolutions do, and that is what cfg3 / paper_mnist_cnn use.
+def paper_ffnn():
+    return model(image_input(104), [dense(104, 50, "relu"), dense(50, 10)], 10)
+
+
+def paper_mnist_cnn():
+    return model(image_input(1, 28, 28), [
+        conv2d(1, 16, 8, stride=2, pad=3, act="relu"), maxpool2d(2, 1),
+        conv2d(16, 32, 4, stride=2, pad=0, act="relu"), maxpool2d(2, 1),
+        dense(512, 32, "relu"), dense(32, 10)], 10)
+
+
+def paper_cifar_cnn():
+    L = []
+    c_in = 3
+    for width in (32, 64, 128):
+        L += [conv2d(c_in, width, 3, 1, 1, "relu"), conv2d(width, width, 3, 1, 1, "relu"), avgpool2d(2, 2)]
+        c_in = width
+    L += [conv2d(128, 256, 3, 1, 1, "relu"), conv2d(256, 10, 3, 1, 1), avgpool2d(4, 4)]
+    return model(image_input(3, 32, 32), L, 10)
+
+
+def paper_embedding():
+    return cfg6_embedding(vocab=10004)
+
+
+def paper_lstm(vocab=10004, seq_len=256, dim=100, hidden=100):
+    return model(token_input(seq_len), [embedding(vocab, dim), lstm_seq(dim, hidden), seq_mean(),
+                                        dense(hidden, 2)], 2)
+
+
 CONFIGS = {
     "cfg1_logistic": dict(build=cfg1_logistic, batch=256, x_dist="uniform"),
     "cfg2_mlp": dict(build=cfg2_mlp, batch=512, x_dist="uniform"),
@@ -241,6 +288,12 @@ CONFIGS = {
     "cfg4_cifar_cnn": dict(build=cfg4_cifar_cnn, batch=1024, x_dist="normal"),
     "cfg5_lstm": dict(build=cfg5_lstm, batch=512, x_dist="uniform"),
     "cfg6_embedding": dict(build=cfg6_embedding, batch=512, x_dist="uniform"),
+    # Appendix B architectures at the largest batch size of the paper's sweep
+    "paper_ffnn": dict(build=paper_ffnn, batch=256, x_dist="uniform"),
+    "paper_mnist_cnn": dict(build=paper_mnist_cnn, batch=256, x_dist="uniform"),
+    "paper_cifar_cnn": dict(build=paper_cifar_cnn, batch=256, x_dist="normal"),
+    "paper_embedding": dict(build=paper_embedding, batch=256, x_dist="uniform"),
+    "paper_lstm": dict(build=paper_lstm, batch=256, x_dist="uniform"),
 }
 CLIP_C = 1.0
 SIGMA = 1.1
@@ -277,4 +330,11 @@ def tiny_models():
             maxpool2d(2, 2), dense(24 * 3 * 3, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
         "tiny_emb": model(token_input(6), [embedding(7, 3), seq_mean(), dense(3, 2)], 2),
+        "tiny_lstm_seq": model(token_input(5), [embedding(7, 3), lstm_seq(3, 4), seq_mean(), dense(4, 2)], 2),
+        # average pools between and after convolutions; the last one is global and yields the logits
+        "tiny_avgpool": model(image_input(2, 8, 8), [
+            conv2d(2, 5, 3, stride=1, pad=1, act="relu"), avgpool2d(2, 2),
+            conv2d(5, 3, 3, stride=1, pad=1), avgpool2d(4, 4)], 3),
+        "tiny_avgpool_dense": model(image_input(2, 7, 6), [
+            conv2d(2, 4, 3, stride=1, pad=1, act="tanh"), avgpool2d(3, 2), dense(4 * 3 * 2, 3)], 3),
     }

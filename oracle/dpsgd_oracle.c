@@ -29,7 +29,10 @@
  *   - ReLU'(0) = 0; max-pool sends the gradient to the first maximum in
  *     row-major window order;
  *   - LSTM: i,f,o = sigmoid, g = tanh, c_t = f*c_{t-1} + i*g, h_t = o*tanh(c_t),
- *     h_0 = c_0 = 0, one bias of size 4H, gate order i,f,g,o;
+ *     h_0 = c_0 = 0, one bias of size 4H, gate order i,f,g,o; the layer's output is h_T
+ *     or, for the sequence variant of Appendix B, every h_t;
+ *   - average pools (Appendix B) take the plain mean of a window, no padding; the global one
+ *     is the window that covers the whole plane;
  *   - noise: Philox4x32-10 (Salmon et al., SC'11), key = seed (lo, hi),
  *     counter = (block lo, block hi, 0, 0); four normals per block from two
  *     Box-Muller pairs; uniform u = ((r >> 9) + 1/2) * 2^-23.
@@ -42,7 +45,8 @@
 #include <omp.h>
 #endif
 
-enum { OR_DENSE = 0, OR_CONV2D = 1, OR_MAXPOOL2D = 2, OR_EMBEDDING = 3, OR_LSTM_LAST = 4, OR_SEQ_MEAN = 5 };
+enum { OR_DENSE = 0, OR_CONV2D = 1, OR_MAXPOOL2D = 2, OR_EMBEDDING = 3, OR_LSTM_LAST = 4, OR_SEQ_MEAN = 5,
+       OR_LSTM_SEQ = 6, OR_AVGPOOL2D = 7 };
 enum { OR_ACT_NONE = 0, OR_ACT_RELU = 1, OR_ACT_TANH = 2 };
 
 typedef struct {
@@ -76,12 +80,14 @@ static shp out_shape(const or_layer *L, shp in, int seq_len) {
     o.w = (in.w + 2 * L->pad - L->kw) / L->stride + 1;
     break;
   case OR_MAXPOOL2D:
+  case OR_AVGPOOL2D:
     o.h = (in.h - L->kh) / L->stride + 1;
     o.w = (in.w - L->kw) / L->stride + 1;
     break;
   case OR_EMBEDDING: o.c = seq_len; o.h = L->dim; o.w = 1; break;
   case OR_LSTM_LAST: o.c = L->d_out; o.h = o.w = 1; break;
   case OR_SEQ_MEAN: o.c = in.h; o.h = o.w = 1; break; /* [T, D] -> [D] */
+  case OR_LSTM_SEQ: o.c = in.c; o.h = L->d_out; o.w = 1; break; /* [T, D] -> [T, H] */
   }
   return o;
 }
@@ -91,7 +97,8 @@ static long layer_params(const or_layer *L) {
   case OR_DENSE: return (long)L->d_in * L->d_out + L->d_out;
   case OR_CONV2D: return (long)L->c_out * L->c_in * L->kh * L->kw + L->c_out;
   case OR_EMBEDDING: return (long)L->vocab * L->dim;
-  case OR_LSTM_LAST: return (long)L->d_in * 4 * L->d_out + (long)L->d_out * 4 * L->d_out + 4 * L->d_out;
+  case OR_LSTM_LAST:
+  case OR_LSTM_SEQ: return (long)L->d_in * 4 * L->d_out + (long)L->d_out * 4 * L->d_out + 4 * L->d_out;
   default: return 0;
   }
 }
@@ -153,7 +160,7 @@ static scratch *scratch_new(const or_model *m) {
     s->a[l] = (double *)calloc(n, sizeof(double));
     if (ly->kind == OR_DENSE || ly->kind == OR_CONV2D) s->z[l] = (double *)calloc(n, sizeof(double));
     if (ly->kind == OR_MAXPOOL2D) s->arg[l] = (int *)calloc(n, sizeof(int));
-    if (ly->kind == OR_LSTM_LAST) s->lstm[l] = (double *)calloc((long)cur.c * 6 * ly->d_out, sizeof(double));
+    if (ly->kind == OR_LSTM_LAST || ly->kind == OR_LSTM_SEQ) s->lstm[l] = (double *)calloc((long)cur.c * 6 * ly->d_out, sizeof(double));
     cur = o;
   }
   s->max_act = mx;
@@ -248,7 +255,19 @@ static double forward(const or_model *m, const double *theta, const void *x, int
         a[e] = acc / T;
       }
     } break;
-    case OR_LSTM_LAST: {
+    case OR_AVGPOOL2D: { /* Appendix B, CIFAR10 network: the mean of every window */
+      for (int c = 0; c < o.c; ++c)
+        for (int oh = 0; oh < o.h; ++oh)
+          for (int ow = 0; ow < o.w; ++ow) {
+            double acc = 0;
+            for (int kh = 0; kh < L->kh; ++kh)
+              for (int kw = 0; kw < L->kw; ++kw)
+                acc += in[(c * cur.h + oh * L->stride + kh) * cur.w + ow * L->stride + kw];
+            a[((long)c * o.h + oh) * o.w + ow] = acc / (L->kh * L->kw);
+          }
+    } break;
+    case OR_LSTM_LAST:
+    case OR_LSTM_SEQ: {
       int T = cur.c, D = L->d_in, H = L->d_out;
       const double *Wih = th, *Whh = th + (long)D * 4 * H, *b = Whh + (long)H * 4 * H;
       double *st = s->lstm[l];
@@ -271,7 +290,12 @@ static double forward(const or_model *m, const double *theta, const void *x, int
           h[r] = go[r] * tanh(c[r]);
         }
       }
-      for (int r = 0; r < H; ++r) a[r] = st[((long)(T - 1) * 6 + 5) * H + r];
+      if (L->kind == OR_LSTM_SEQ) { /* Appendix B, LSTM network: the output is the whole sequence of h_t */
+        for (int t = 0; t < T; ++t)
+          for (int r = 0; r < H; ++r) a[(long)t * H + r] = st[((long)t * 6 + 5) * H + r];
+      } else {
+        for (int r = 0; r < H; ++r) a[r] = st[((long)(T - 1) * 6 + 5) * H + r];
+      }
     } break;
     }
     th += layer_params(L);
@@ -367,15 +391,31 @@ static void backward(const or_model *m, const double *theta, const void *x, int 
       for (int t = 0; t < T; ++t)
         for (int e = 0; e < D; ++e) din[(long)t * D + e] = dout[e] / T;
     } break;
-    case OR_LSTM_LAST: {
+    case OR_AVGPOOL2D: {
+      for (long j = 0; j < n_in; ++j) din[j] = 0;
+      for (int c = 0; c < o.c; ++c)
+        for (int oh = 0; oh < o.h; ++oh)
+          for (int ow = 0; ow < o.w; ++ow) {
+            double share = dout[((long)c * o.h + oh) * o.w + ow] / (L->kh * L->kw);
+            for (int kh = 0; kh < L->kh; ++kh)
+              for (int kw = 0; kw < L->kw; ++kw)
+                din[(c * ishp.h + oh * L->stride + kh) * ishp.w + ow * L->stride + kw] += share;
+          }
+    } break;
+    case OR_LSTM_LAST:
+    case OR_LSTM_SEQ: {
       int T = ishp.c, D = L->d_in, H = L->d_out;
+      const int seq = L->kind == OR_LSTM_SEQ;
       const double *Wih = th, *Whh = th + (long)D * 4 * H;
       double *gWih = gl, *gWhh = gl + (long)D * 4 * H, *gb = gWhh + (long)H * 4 * H;
       const double *st = s->lstm[l];
       double *dh = (double *)calloc(H, sizeof(double)), *dc = (double *)calloc(H, sizeof(double));
       double *dg = (double *)calloc(4 * H, sizeof(double)), *dhp = (double *)calloc(H, sizeof(double));
-      for (int r = 0; r < H; ++r) dh[r] = dout[r];
+      /* dh = dL/dh_t: what the later steps send back through W_hh, plus the loss's direct share of h_t
+         (every step for the sequence output, the last step only otherwise) */
+      if (!seq) for (int r = 0; r < H; ++r) dh[r] = dout[r];
       for (int t = T - 1; t >= 0; --t) {
+        if (seq) for (int r = 0; r < H; ++r) dh[r] += dout[(long)t * H + r];
         const double *gi = st + ((long)t * 6 + 0) * H, *gf = gi + H, *gg = gf + H, *go = gg + H, *c = go + H;
         const double *hp = t ? st + ((long)(t - 1) * 6 + 5) * H : NULL;
         const double *cp = t ? st + ((long)(t - 1) * 6 + 4) * H : NULL;

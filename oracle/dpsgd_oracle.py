@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dpsgd_oracle.c")
 _LIB = os.path.join(_HERE, "libdpsgd_oracle.so")
 
-_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5}
+_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5,
+         "lstm_seq": 6, "avgpool2d": 7}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 
@@ -81,12 +82,12 @@ def _to_c_model(m):
         elif L["kind"] == "conv2d":
             c.c_in, c.c_out, c.kh, c.kw, c.stride, c.pad = (L["c_in"], L["c_out"], L["kh"], L["kw"], L["stride"],
                                                             L["pad"])
-        elif L["kind"] == "maxpool2d":
+        elif L["kind"] in ("maxpool2d", "avgpool2d"):
             c.kh = c.kw = L["k"]
             c.stride = L["stride"]
         elif L["kind"] == "embedding":
             c.vocab, c.dim = L["vocab"], L["dim"]
-        elif L["kind"] == "lstm_last":
+        elif L["kind"] in ("lstm_last", "lstm_seq"):
             c.d_in, c.d_out = L["d_in"], L["hidden"]
     cm = _Model()
     cm.n_layers = len(layers)

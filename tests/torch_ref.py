@@ -1,7 +1,7 @@
 """PyTorch-CPU autograd model built from the same dict description.
 
 Used only to pin the oracle: it is a library routine (autograd over torch's own
-linear / conv2d / max_pool2d / embedding / nn.LSTM), independent of the oracle's
+linear / conv2d / max_pool2d / avg_pool2d / embedding / nn.LSTM), independent of the oracle's
 explicit backprop.  fp64 throughout.
 """
 import numpy as np
@@ -43,17 +43,19 @@ def logits(m, theta, x):
             h = F.max_pool2d(h, L["k"], L["stride"])
         elif k == "embedding":
             h = F.embedding(h, p[(li, "E")])
-        elif k == "lstm_last":
+        elif k == "avgpool2d":
+            h = F.avg_pool2d(h, L["k"], L["stride"])
+        elif k in ("lstm_last", "lstm_seq"):
             H = L["hidden"]
             lstm = torch.nn.LSTM(L["d_in"], H, batch_first=True).double()
             # torch: weight_ih_l0 [4H, D] with rows ordered i, f, g, o; two biases that add.
             params = {"weight_ih_l0": p[(li, "W_ih")].t(), "weight_hh_l0": p[(li, "W_hh")].t(),
                       "bias_ih_l0": p[(li, "b")], "bias_hh_l0": torch.zeros(4 * H, dtype=torch.float64)}
             out, _ = torch.func.functional_call(lstm, params, (h,))
-            h = out[:, -1, :]
+            h = out if k == "lstm_seq" else out[:, -1, :]
         elif k == "seq_mean":
             h = h.mean(dim=1)
-    return h
+    return h.reshape(h.shape[0], -1)
 
 
 def to_torch_x(m, x):
