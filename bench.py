@@ -67,6 +67,10 @@ def label_work(m, B):
             n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]
             add("maxpool_fwd", 0.0, 4.0 * n_in + 5.0 * n_out)
             add("maxpool_bwd", 0.0, 8.0 * n_in + 5.0 * n_out)
+        elif k == "avgpool2d":
+            n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]
+            add("avgpool_fwd", 1.0 * n_in, 4.0 * (n_in + n_out))
+            add("avgpool_bwd", 1.0 * n_in, 4.0 * (2 * n_in + n_out))
         elif k == "embedding":
             T, D_ = inp["seq_len"], L["dim"]
             add("emb_gather", 0.0, 4.0 * B * T * (2 * D_ + 1))
@@ -77,7 +81,7 @@ def label_work(m, B):
             T, D_ = cur[1], cur[2]
             add("seq_mean_fwd", 1.0 * B * T * D_, 4.0 * B * (T * D_ + D_))
             add("seq_mean_bwd", 1.0 * B * T * D_, 4.0 * B * (T * D_ + D_))
-        elif k == "lstm_last":
+        elif k in ("lstm_last", "lstm_seq"):
             T, Din, H = cur[1], L["d_in"], L["hidden"]
             G = 4 * H
             add("lstm_xproj", 2.0 * B * T * Din * G, 4.0 * (B * T * G + Din * G))
@@ -204,6 +208,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(W.CONFIGS))
+    ap.add_argument("--batch", type=int, default=None, help="batch size of the main workload (default: the configuration's own)")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--kernels", action="store_true", help="print the per-kernel table to stderr")
@@ -227,7 +232,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    res, wl = run_workload(a.workload, a.steps, a.warmup, profile=True)
+    res, wl = run_workload(a.workload, a.steps, a.warmup, profile=True, batch=a.batch)
     kern = res["kernels"]
     # roofline of the dominant kernel: the single launch (kernel kind, layer) with the largest share of the step
     dom = res["kernels_per_layer"][0]

@@ -46,8 +46,14 @@ typedef enum {
   DP_EMBEDDING = 3, /* E[vocab][embed_dim]; input int32 token ids [B, seq_len]                */
   DP_LSTM_LAST = 4, /* one-layer LSTM, returns the last hidden state; W_ih[in_features][4H],
                        W_hh[H][4H], b[4H]; 4H axis ordered i, f, g, o; h_0 = c_0 = 0          */
-  DP_SEQ_MEAN = 5   /* mean over the seq_len step vectors of an embedding's output (the embedding
-                       network of the paper's Appendix B); no parameters, no fields used       */
+  DP_SEQ_MEAN = 5,  /* mean over the seq_len step vectors of an embedding's or a DP_LSTM_SEQ's output
+                       (the embedding and LSTM networks of the paper's Appendix B); no parameters,
+                       no fields used                                                          */
+  DP_LSTM_SEQ = 6,  /* DP_LSTM_LAST's layer, but the output is every hidden state, [seq_len][H] (the
+                       LSTM network of Appendix B); must be followed by DP_SEQ_MEAN              */
+  DP_AVGPOOL2D = 7  /* mean over kh x kw windows, stride, no padding (the CIFAR10 network of Appendix B);
+                       a window covering the whole plane is the global average pool.  It may be the
+                       last layer when it leaves n_classes values, which are then the logits     */
 } dp_layer_kind;
 
 typedef enum { DP_ACT_NONE = 0, DP_ACT_RELU = 1, DP_ACT_TANH = 2 } dp_act;
@@ -66,7 +72,8 @@ typedef struct {
   const dp_layer_desc *layers; /* host; read during dp_step_init only                    */
   int in_c, in_h, in_w;        /* image input NCHW (a feature vector is in_c x 1 x 1)    */
   int seq_len;                 /* > 0: the input is int32 token ids [B, seq_len]         */
-  int n_classes;               /* width of the last layer; loss = softmax cross-entropy  */
+  int n_classes;               /* width of the last layer (dense without activation, or an average pool); loss =
+                                  softmax cross-entropy of its output */
 } dp_model_desc;
 
 /*

@@ -146,7 +146,7 @@ static const char *const kLayerLabels[] = {"dense_fwd", "dense_fwd_epilogue", "d
                                            "conv_weight_layout", "conv_fwd", "conv_wgrad_norm", "conv_bwd_data", "conv_clipped_sum",
                                            "maxpool_fwd", "maxpool_bwd", "lstm_xproj", "lstm_fwd", "lstm_bwd", "lstm_wgrad_norm",
                                            "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_gather", "emb_bucket", "emb_scatter", "fill_zero",
-                                           "seq_mean_fwd", "seq_mean_bwd"};
+                                           "seq_mean_fwd", "seq_mean_bwd", "avgpool_fwd", "avgpool_bwd"};
 
 struct dp_ctx {
   dp_model_desc m;
@@ -416,6 +416,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       l.max_slots = ceil_div(l.d.out_ch, 32) * ceil_div(l.d.in_ch * l.d.kh * l.d.kw + 1, 32);
       break;
     case DP_MAXPOOL2D:
+    case DP_AVGPOOL2D:
       if (is_tok || is_seq || i == 0 || l.d.kh < 1 || l.d.kw < 1 || l.d.stride < 1 || l.d.kh * l.d.kw > 255) { rc = DP_EINVAL; break; }
       if (model->layers[i - 1].kind != DP_CONV2D) { rc = DP_EUNSUPPORTED; break; }
       l.outC = curC;
@@ -432,17 +433,23 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       is_tok = false; is_seq = true;
       break;
     case DP_LSTM_LAST:
+    case DP_LSTM_SEQ:
       if (!is_seq || l.d.hidden < 1 || l.d.in_features != curH) { rc = DP_EINVAL; break; }
       if (l.d.hidden > 128 || i == 0 || model->layers[i - 1].kind != DP_EMBEDDING) { rc = DP_EUNSUPPORTED; break; }
       l.T = curC; l.Din = curH; l.H = l.d.hidden;
-      l.outC = l.H; l.outH = l.outW = 1;
       l.p_count = (long)l.Din * 4 * l.H + (long)l.H * 4 * l.H + 4 * l.H;
       l.max_slots = ceil_div(l.Din + l.H + 1, 32) * ceil_div(4 * l.H, 32);
-      is_seq = false;
+      if (l.d.kind == DP_LSTM_SEQ) {
+        if (i + 1 >= model->n_layers || model->layers[i + 1].kind != DP_SEQ_MEAN) { rc = DP_EUNSUPPORTED; break; }
+        l.outC = l.T; l.outH = l.H; l.outW = 1; // stays a sequence
+      } else {
+        l.outC = l.H; l.outH = l.outW = 1;
+        is_seq = false;
+      }
       break;
     case DP_SEQ_MEAN:
       if (!is_seq) { rc = DP_EINVAL; break; }
-      if (i == 0 || model->layers[i - 1].kind != DP_EMBEDDING) { rc = DP_EUNSUPPORTED; break; }
+      if (i == 0 || (model->layers[i - 1].kind != DP_EMBEDDING && model->layers[i - 1].kind != DP_LSTM_SEQ)) { rc = DP_EUNSUPPORTED; break; }
       l.T = curC; l.Din = curH;
       l.outC = curH; l.outH = l.outW = 1;
       is_seq = false;
@@ -464,8 +471,8 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   }
   if (rc == DP_OK) {
     const Layer &last = c->L.back();
-    if (is_tok || is_seq || last.out_size != model->n_classes || last.d.kind != DP_DENSE || last.d.act != DP_ACT_NONE)
-      rc = DP_EINVAL;
+    const bool logits_ok = (last.d.kind == DP_DENSE && last.d.act == DP_ACT_NONE) || last.d.kind == DP_AVGPOOL2D;
+    if (is_tok || is_seq || last.out_size != model->n_classes || !logits_ok) rc = DP_EINVAL;
     int nparam = 0;
     for (auto &l : c->L) nparam += l.p_count > 0;
     if (nparam > DP_MAX_SEG) rc = DP_EUNSUPPORTED;
@@ -530,10 +537,11 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       if (rc == DP_OK) rc = dev_alloc(c, &l.e_cursor, V + 1);
       if (rc == DP_OK) rc = dev_alloc(c, &l.e_list, (size_t)mb * l.outC);
     }
-    if (rc == DP_OK && l.d.kind == DP_LSTM_LAST) {
+    if (rc == DP_OK && (l.d.kind == DP_LSTM_LAST || l.d.kind == DP_LSTM_SEQ)) {
       rc = dev_alloc(c, &l.gates, mb * l.T * 4 * l.H);
       if (rc == DP_OK) rc = dev_alloc(c, &l.cs, mb * l.T * l.H);
-      if (rc == DP_OK) rc = dev_alloc(c, &l.hs, mb * l.T * l.H);
+      if (l.d.kind == DP_LSTM_SEQ) l.hs = l.a; // the hidden states are the layer's output
+      else if (rc == DP_OK) rc = dev_alloc(c, &l.hs, mb * l.T * l.H);
     }
   }
   if (rc == DP_OK) rc = dev_alloc(c, &c->slots, (size_t)c->max_slots * mb);
@@ -579,14 +587,18 @@ template <int HP>
 static void launch_lstm_fwd(const Launcher &Ln, Layer &l, const float *Whh, int B, const char *label) {
   dim3 grid(ceil_div(B, LSTM_NE)), block(256);
   Ln(label, grid, block, [&](hipStream_t st) {
-    hipLaunchKernelGGL(lstm_fwd_kernel<HP>, grid, block, 0, st, l.gates, Whh, l.hs, l.cs, l.a, B, l.T, l.H);
+    hipLaunchKernelGGL(lstm_fwd_kernel<HP>, grid, block, 0, st, l.gates, Whh, l.hs, l.cs,
+                       l.d.kind == DP_LSTM_SEQ ? (float *)nullptr : l.a, B, l.T, l.H);
   });
 }
 template <int HP>
 static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int B, const char *label) {
   dim3 grid(ceil_div(B, LSTM_NE)), block(256);
   Ln(label, grid, block, [&](hipStream_t st) {
-    hipLaunchKernelGGL(lstm_bwd_kernel<HP>, grid, block, 0, st, l.gates, (const float *)l.cs, Whh, (const float *)l.g, B, l.T, l.H);
+    if (l.d.kind == DP_LSTM_SEQ)
+      hipLaunchKernelGGL((lstm_bwd_kernel<HP, true>), grid, block, 0, st, l.gates, (const float *)l.cs, Whh, (const float *)l.g, B, l.T, l.H);
+    else
+      hipLaunchKernelGGL((lstm_bwd_kernel<HP, false>), grid, block, 0, st, l.gates, (const float *)l.cs, Whh, (const float *)l.g, B, l.T, l.H);
   });
 }
 #define LSTM_DISPATCH(fn, H, ...)                 \
@@ -721,7 +733,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           hipLaunchKernelGGL(seq_mean_fwd_kernel, grid, block, 0, st, in, l.a, l.T, l.Din);
         });
       } break;
-      case DP_LSTM_LAST: {
+      case DP_AVGPOOL2D: {
+        long total = (long)B * l.out_size;
+        dim3 grid = grid1d(total, 256), block(256);
+        const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
+        if (p22) {
+          Ln(LL("avgpool_fwd"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(avgpool2x2_fwd_kernel, grid, block, 0, st, in, l.a, total, l.outW, l.inW);
+          });
+        } else
+        Ln(LL("avgpool_fwd"), grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(avgpool_fwd_kernel, grid, block, 0, st, in, l.a, total, l.inH, l.inW, l.outH, l.outW,
+                             l.d.kh, l.d.kw, l.d.stride);
+        });
+      } break;
+      case DP_LSTM_LAST:
+      case DP_LSTM_SEQ: {
         const int G = 4 * l.H;
         auto run = [&](auto vt) {
           constexpr bool V = decltype(vt)::value;
@@ -843,7 +870,25 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
                              l.d.stride, prev_act);
         });
       } break;
-      case DP_LSTM_LAST: {
+      case DP_AVGPOOL2D: {
+        long total = (long)B * l.in_size;
+        dim3 grid = grid1d(total, 256), block(256);
+        const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
+        if (p22) {
+          const long nwin = (long)B * l.out_size;
+          dim3 g2 = grid1d(nwin, 256);
+          Ln(LL("avgpool_bwd"), g2, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(avgpool2x2_bwd_kernel, g2, block, 0, st, (const float *)l.g, (const float *)prev->a,
+                               prev->g, nwin, l.outW, l.inW, prev_act);
+          });
+        } else
+        Ln(LL("avgpool_bwd"), grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(avgpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const float *)prev->a,
+                             prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw, l.d.stride, prev_act);
+        });
+      } break;
+      case DP_LSTM_LAST:
+      case DP_LSTM_SEQ: {
         const int G = 4 * l.H;
         const float *Whh = W + (long)l.Din * G;
         LSTM_DISPATCH(launch_lstm_bwd, l.H, Ln, l, Whh, B, LL("lstm_bwd"));
@@ -954,7 +999,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.part = l.part; p.stride = l.p_count; p.ldm = g.CKK; p.bias_col = g.CKK; p.bias_off = (long)g.D * g.CKK;
         nsplit = launch_gemm_split(p, l.max_split, Ln, LL("conv_clipped_sum"));
       } break;
-      case DP_LSTM_LAST: {
+      case DP_LSTM_LAST:
+      case DP_LSTM_SEQ: {
         const int G = 4 * l.H;
         auto run = [&](auto vt) {
           constexpr bool V = decltype(vt)::value;

@@ -135,6 +135,72 @@ __global__ void maxpool2x2_bwd_kernel(const float *__restrict__ gout, const uint
   *reinterpret_cast<float2 *>(gin + o1) = r1;
 }
 
+// Average pool (Appendix B, CIFAR10 network): the plain mean of a KH x KW window, no padding.  A window that
+// covers the whole plane is the global average pool.
+__global__ void avgpool_fwd_kernel(const float *__restrict__ in, float *__restrict__ out, long total, int H, int W,
+                                   int OH, int OW, int KH, int KW, int S) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int ow = (int)(i % OW);
+  long r = i / OW;
+  int oh = (int)(r % OH);
+  long bc = r / OH;
+  const float *p = in + (bc * H + (long)oh * S) * W + (long)ow * S;
+  float acc = 0.f;
+  for (int kh = 0; kh < KH; ++kh)
+    for (int kw = 0; kw < KW; ++kw) acc += p[kh * W + kw];
+  out[i] = acc / (float)(KH * KW);
+}
+
+// Gather form of the backward pass: an input position sums 1/(KH*KW) of the gradient of every window that
+// holds it, then applies the derivative of the activation that produced the pool's input.
+__global__ void avgpool_bwd_kernel(const float *__restrict__ gout, const float *__restrict__ a_in,
+                                   float *__restrict__ gin, long total, int H, int W, int OH, int OW, int KH, int KW,
+                                   int S, int act) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int iw = (int)(i % W);
+  long r = i / W;
+  int ih = (int)(r % H);
+  long bc = r / H;
+  float acc = 0.f;
+  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (oh_lo + S - 1) / S : 0;
+  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (ow_lo + S - 1) / S : 0;
+  int oh_hi = min(ih / S, OH - 1), ow_hi = min(iw / S, OW - 1);
+  for (int oh = oh_lo; oh <= oh_hi; ++oh)
+    for (int ow = ow_lo; ow <= ow_hi; ++ow) acc += gout[(bc * OH + oh) * OW + ow];
+  gin[i] = acc / (float)(KH * KW) * act_deriv_from_out(act, a_in[i]);
+}
+
+// 2x2 / stride-2 average pool with even H and W: one thread per window, 8-byte accesses.
+__global__ void avgpool2x2_fwd_kernel(const float *__restrict__ in, float *__restrict__ out, long total, int OW,
+                                      int W) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const long row = i / OW;
+  const int ow = (int)(i - row * OW);
+  const float2 t = *reinterpret_cast<const float2 *>(in + (2 * row) * W + 2 * ow);
+  const float2 u = *reinterpret_cast<const float2 *>(in + (2 * row + 1) * W + 2 * ow);
+  out[i] = ((t.x + t.y) + (u.x + u.y)) * 0.25f;
+}
+
+__global__ void avgpool2x2_bwd_kernel(const float *__restrict__ gout, const float *__restrict__ a_in,
+                                      float *__restrict__ gin, long total, int OW, int W, int act) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const long row = i / OW;
+  const int ow = (int)(i - row * OW);
+  const float g = gout[i] * 0.25f;
+  const long o0 = (2 * row) * W + 2 * ow, o1 = o0 + W;
+  const float2 t = *reinterpret_cast<const float2 *>(a_in + o0);
+  const float2 u = *reinterpret_cast<const float2 *>(a_in + o1);
+  float2 r0, r1;
+  r0.x = g * act_deriv_from_out(act, t.x); r0.y = g * act_deriv_from_out(act, t.y);
+  r1.x = g * act_deriv_from_out(act, u.x); r1.y = g * act_deriv_from_out(act, u.y);
+  *reinterpret_cast<float2 *>(gin + o0) = r0;
+  *reinterpret_cast<float2 *>(gin + o1) = r1;
+}
+
 // Dense layer: ||g_i||^2 = (||a_i||^2 + 1) ||delta_i||^2 without forming the outer
 // product (Section 1: per-example norms for fully-connected layers).  One wave per example.
 __global__ void dense_norm_kernel(const float *__restrict__ a, int d_in, const float *__restrict__ delta, int d_out,

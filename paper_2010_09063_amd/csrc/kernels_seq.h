@@ -69,7 +69,7 @@ __global__ void seq_mean_bwd_kernel(const float *__restrict__ g, float *__restri
 }
 
 // Forward.  gates: in  x_t W_ih + b for every (b, t); out activated i, f, g, o.
-// hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T.
+// hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T (null: not wanted).
 // Thread j < 2H owns columns j and j + 2H of W_hh (H <= 128, HP = H rounded up to 4).
 template <int HP>
 __global__ __launch_bounds__(256) void lstm_fwd_kernel(float *__restrict__ gates, const float *__restrict__ Whh,
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void lstm_fwd_kernel(float *__restrict__ gates
       h_s[ue][ur] = h;
       const long o = ((long)(b0 + ue) * T + t) * H + ur;
       hs[o] = h; cs[o] = c_reg;
-      if (t == T - 1) hlast[(long)(b0 + ue) * H + ur] = h;
+      if (hlast != nullptr && t == T - 1) hlast[(long)(b0 + ue) * H + ur] = h;
     }
     __syncthreads();
   }
@@ -156,10 +156,12 @@ __global__ __launch_bounds__(256) void lstm_fwd_kernel(float *__restrict__ gates
 
 // Back-propagation through time.  gates: in activated gates, out d(loss)/d(gate
 // pre-activations).  Thread (k = tid % 128, q = tid / 128) owns W_hh[k][q*2H .. q*2H+2H).
-template <int HP>
+// SEQ = false: the loss sees h_T only, dh_out is [B, H].  SEQ = true: the layer's output is every h_t,
+// dh_out is [B, T, H] and step t adds its own share to what the later steps send back.
+template <int HP, bool SEQ>
 __global__ __launch_bounds__(256) void lstm_bwd_kernel(float *__restrict__ gates, const float *__restrict__ cs,
                                                         const float *__restrict__ Whh,
-                                                        const float *__restrict__ dh_last, int B, int T, int H) {
+                                                        const float *__restrict__ dh_out, int B, int T, int H) {
   constexpr int DG_LD = 2 * HP; // per half, padded so that float4 reads stay aligned
   __shared__ __attribute__((aligned(16))) float dg_s[LSTM_NE][2 * DG_LD];
   __shared__ float part_s[LSTM_NE][2][128];
@@ -175,16 +177,18 @@ __global__ __launch_bounds__(256) void lstm_bwd_kernel(float *__restrict__ gates
   const bool upd_thread = tid < LSTM_NE * H && (b0 + ue) < B;
   const long ub = b0 + ue;
   float dc = 0.f;
-  float gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, ct = 0.f, cp = 0.f;
+  float gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, ct = 0.f, cp = 0.f, dh_own = 0.f;
   if (upd_thread) {
     const long o = (ub * T + (T - 1));
+    dh_own = SEQ ? dh_out[o * H + ur] : dh_out[ub * H + ur];
     gi = gates[o * G + ur]; gf = gates[o * G + H + ur]; gg = gates[o * G + 2 * H + ur]; go = gates[o * G + 3 * H + ur];
     ct = cs[o * H + ur]; cp = T > 1 ? cs[(o - 1) * H + ur] : 0.f;
   }
   __syncthreads();
   for (int t = T - 1; t >= 0; --t) {
     if (upd_thread) {
-      const float dh = (t == T - 1) ? dh_last[ub * H + ur] : part_s[ue][0][ur] + part_s[ue][1][ur];
+      float dh = (t == T - 1) ? 0.f : part_s[ue][0][ur] + part_s[ue][1][ur];
+      if (SEQ || t == T - 1) dh += dh_own;
       const float tc = fast_tanh(ct);
       const float dct = dc + dh * go * (1.f - tc * tc);
       const float d_o = dh * tc * go * (1.f - go);
@@ -202,6 +206,7 @@ __global__ __launch_bounds__(256) void lstm_bwd_kernel(float *__restrict__ gates
         gi = gates[on * G + ur]; gf = gates[on * G + H + ur]; gg = gates[on * G + 2 * H + ur];
         go = gates[on * G + 3 * H + ur];
         ct = cp; cp = t > 1 ? cs[(on - 1) * H + ur] : 0.f;
+        if (SEQ) dh_own = dh_out[on * H + ur];
       }
     }
     __syncthreads();

@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdpstep.so")
 
 DP_OK, DP_EINVAL, DP_ENOMEM, DP_EHIP, DP_EUNSUPPORTED = 0, -1, -2, -3, -4
-_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5}
+_KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5,
+         "lstm_seq": 6, "avgpool2d": 7}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 EXPORTS = ["dp_step_init", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
@@ -94,12 +95,12 @@ def model_desc(m):
         elif L["kind"] == "conv2d":
             d.in_ch, d.out_ch, d.kh, d.kw, d.stride, d.pad = (L["c_in"], L["c_out"], L["kh"], L["kw"], L["stride"],
                                                               L["pad"])
-        elif L["kind"] == "maxpool2d":
+        elif L["kind"] in ("maxpool2d", "avgpool2d"):
             d.kh = d.kw = L["k"]
             d.stride = L["stride"]
         elif L["kind"] == "embedding":
             d.vocab, d.embed_dim = L["vocab"], L["dim"]
-        elif L["kind"] == "lstm_last":
+        elif L["kind"] in ("lstm_last", "lstm_seq"):
             d.in_features, d.hidden = L["d_in"], L["hidden"]
     md = dp_model_desc()
     md.n_layers = len(layers)
