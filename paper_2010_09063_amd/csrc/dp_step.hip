@@ -295,9 +295,13 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
 
 template <class LN>
 static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a, int npw) {
-  const int dt = a.M <= 32 ? 32 : (a.M <= 64 ? 64 : 128);
+  int dt = a.M <= 32 ? 32 : (a.M <= 64 ? 64 : 128);
   const int cc = a.Cin <= 4 ? 4 : 8; // first layers: a chunk of four channels covers the whole input
-  dim3 grid(a.t.NIMG > 1 ? ceil_div(a.B, a.t.NIMG) : a.B * a.t.row_tiles, ceil_div(a.M, dt)), block(256);
+  const int pix_blocks = a.t.NIMG > 1 ? ceil_div(a.B, a.t.NIMG) : a.B * a.t.row_tiles;
+  // a small batch of small planes leaves CUs idle with wide output tiles: narrow them until the grid fills the chip
+  static const int min_blocks = getenv("DP_CONV_MINBLOCKS") ? atoi(getenv("DP_CONV_MINBLOCKS")) : 512;
+  while (dt > 32 && pix_blocks * ceil_div(a.M, dt) < min_blocks) dt >>= 1;
+  dim3 grid(pix_blocks, ceil_div(a.M, dt)), block(256);
   size_t smem = sizeof(float) * ((size_t)cc * a.t.XPLANE + (size_t)cc * 9 * dt);
 #define DP_CONV_CASE(dt_, npw_, cc_)                                                                 \
   if (dt == dt_ && npw == npw_ && cc == cc_) {                                                       \
@@ -585,7 +589,7 @@ static inline dim3 grid1d(long n, int block) { return dim3((unsigned)((n + block
 
 template <int HP>
 static void launch_lstm_fwd(const Launcher &Ln, Layer &l, const float *Whh, int B, const char *label) {
-  dim3 grid(ceil_div(B, LSTM_NE)), block(256);
+  dim3 grid(B), block(LSTM_THREADS);
   Ln(label, grid, block, [&](hipStream_t st) {
     hipLaunchKernelGGL(lstm_fwd_kernel<HP>, grid, block, 0, st, l.gates, Whh, l.hs, l.cs,
                        l.d.kind == DP_LSTM_SEQ ? (float *)nullptr : l.a, B, l.T, l.H);
@@ -593,7 +597,7 @@ static void launch_lstm_fwd(const Launcher &Ln, Layer &l, const float *Whh, int 
 }
 template <int HP>
 static void launch_lstm_bwd(const Launcher &Ln, Layer &l, const float *Whh, int B, const char *label) {
-  dim3 grid(ceil_div(B, LSTM_NE)), block(256);
+  dim3 grid(B), block(LSTM_THREADS);
   Ln(label, grid, block, [&](hipStream_t st) {
     if (l.d.kind == DP_LSTM_SEQ)
       hipLaunchKernelGGL((lstm_bwd_kernel<HP, true>), grid, block, 0, st, l.gates, (const float *)l.cs, Whh, (const float *)l.g, B, l.T, l.H);

@@ -3,10 +3,12 @@
 //
 // The recurrence is a chain of T dependent (examples x H)*(H x 4H) products; per
 // step it is far too small for a tiled contraction, and examples are
-// independent.  Each workgroup therefore owns LSTM_NE examples for the whole
-// sequence and keeps W_hh in registers (two gate columns per thread forward, half
-// a row per thread backward), so a step costs no weight traffic at all: only the
-// hidden state goes through LDS (broadcast reads).  The input projection
+// independent.  Each workgroup of LSTM_THREADS threads therefore owns one example for the
+// whole sequence and keeps W_hh in registers (one gate column per thread forward, one gate's
+// quarter of a row per thread backward), so a step costs no weight traffic at all: only the
+// hidden state goes through LDS (broadcast reads).  A step is a chain of dependent phases, so
+// what bounds it is latency: eight waves per example (two per SIMD) overlap each other's LDS
+// reads, and every global load is issued a whole step before its value is used.  The input projection
 // x_t W_ih + b and the input / weight gradients are hoisted out of the loop into
 // the tiled MFMA contraction.  The [B, T, 4H] buffer is reused in place: input
 // projection -> activated gates (forward) -> gate gradients (backward).
@@ -16,7 +18,7 @@
 
 #include "kernels_misc.h"
 
-#define LSTM_NE 1
+#define LSTM_THREADS 512
 
 // x_{b,t} = E[tok[b,t]]: the embedding lookup, written once per step so that the three
 // contractions that read it (input projection, per-example and clipped weight gradient)
@@ -68,163 +70,165 @@ __global__ void seq_mean_bwd_kernel(const float *__restrict__ g, float *__restri
   gin[i] = g[b * D + e] / (float)T;
 }
 
+// Lane-relative access on a uniform base pointer with an unsigned byte offset: one address register per access
+// (a signed or pre-scaled index would be widened to 64 bits per lane).
+__device__ __forceinline__ float &lane_at(float *base, unsigned byte_off) {
+  return *reinterpret_cast<float *>(reinterpret_cast<char *>(base) + byte_off);
+}
+__device__ __forceinline__ float lane_ld(const float *base, unsigned byte_off) {
+  return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + byte_off);
+}
+
 // Forward.  gates: in  x_t W_ih + b for every (b, t); out activated i, f, g, o.
 // hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T (null: not wanted).
-// Thread j < 2H owns columns j and j + 2H of W_hh (H <= 128, HP = H rounded up to 4).
+// One workgroup per example; thread j < 4H owns column j of W_hh (H <= 128, HP = H rounded up to 4).
 template <int HP>
-__global__ __launch_bounds__(256) void lstm_fwd_kernel(float *__restrict__ gates, const float *__restrict__ Whh,
-                                                        float *__restrict__ hs, float *__restrict__ cs,
-                                                        float *__restrict__ hlast, int B, int T, int H) {
-  __shared__ __attribute__((aligned(16))) float h_s[LSTM_NE][HP];
-  __shared__ float gact[LSTM_NE][4 * HP];
+__global__ __launch_bounds__(LSTM_THREADS) void lstm_fwd_kernel(float *__restrict__ gates, const float *__restrict__ Whh,
+                                                                 float *__restrict__ hs, float *__restrict__ cs,
+                                                                 float *__restrict__ hlast, int B, int T, int H) {
+  __shared__ __attribute__((aligned(16))) float h_s[HP];
+  __shared__ float gact[4 * HP];
   const int tid = threadIdx.x;
-  const int b0 = blockIdx.x * LSTM_NE;
+  const int b = blockIdx.x; // the grid is exactly B workgroups
   const int G = 4 * H;
-  const bool col_thread = tid < 2 * H;
-  const int c0 = tid, c1 = tid + 2 * H;
-  float w0[HP], w1[HP];
+  const bool col_thread = tid < G;
+  const int col = col_thread ? tid : 0;
+  float w[HP];
 #pragma unroll
-  for (int k = 0; k < HP; ++k) {
-    w0[k] = (col_thread && k < H) ? Whh[(long)k * G + c0] : 0.f;
-    w1[k] = (col_thread && k < H) ? Whh[(long)k * G + c1] : 0.f;
-  }
-  for (int i = tid; i < LSTM_NE * HP; i += 256) (&h_s[0][0])[i] = 0.f;
-  // cell-update role: thread (e, r)
-  const int ue = tid / H, ur = tid - ue * H;
-  const bool upd_thread = tid < LSTM_NE * H && (b0 + ue) < B;
+  for (int k = 0; k < HP; ++k) w[k] = (col_thread && k < H) ? Whh[(long)k * G + col] : 0.f;
+  for (int i = tid; i < HP; i += LSTM_THREADS) h_s[i] = 0.f;
+  const bool upd_thread = tid < H;
+  const int ur = upd_thread ? tid : 0;
+  const bool is_tanh = col >= 2 * H && col < 3 * H; // columns [0,H) i, [H,2H) f, [2H,3H) g, [3H,4H) o
   float c_reg = 0.f;
-  float xp[LSTM_NE][2];
-#pragma unroll
-  for (int e = 0; e < LSTM_NE; ++e) {
-    const bool ok = col_thread && (b0 + e) < B;
-    xp[e][0] = ok ? gates[((long)(b0 + e) * T) * G + c0] : 0.f;
-    xp[e][1] = ok ? gates[((long)(b0 + e) * T) * G + c1] : 0.f;
-  }
+  const unsigned colb = 4u * col, urb = 4u * ur;
+  float *const grow0 = gates + (long)b * T * G;
+  float *const hrow0 = hs + (long)b * T * H, *const crow0 = cs + (long)b * T * H;
+  // the weight loads end here: a wait that the compiler places at their first use would sit inside the loop
+  // and hold every step until that step's own stores had drained
+  __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0), other counters untouched
   __syncthreads();
-  for (int t = 0; t < T; ++t) {
-    float acc[LSTM_NE][2];
+  // One step.  xcur: this step's input projection, loaded one step earlier; xnext receives the next step's (row
+  // clamped at the last step), so its latency hides behind a whole step.  The caller alternates two registers:
+  // a loaded value copied into a loop-carried variable would be waited for at the copy.
+  auto step = [&](const int t, const float xcur, float &xnext) {
+    // (lane offsets re-materialised inside the loop: hoisted out of it they would be widened to 64 bits)
+    unsigned colx = colb, urx = urb;
+    asm volatile("" : "+v"(colx), "+v"(urx));
+    xnext = lane_ld(grow0 + (long)min(t + 1, T - 1) * G, colx);
+    // h_0 = 0 sits in h_s at the first step, so every step runs the same product
+    float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-    for (int e = 0; e < LSTM_NE; ++e) { acc[e][0] = xp[e][0]; acc[e][1] = xp[e][1]; }
-    if (t + 1 < T) {
-#pragma unroll
-      for (int e = 0; e < LSTM_NE; ++e) {
-        const bool ok = col_thread && (b0 + e) < B;
-        xp[e][0] = ok ? gates[((long)(b0 + e) * T + t + 1) * G + c0] : 0.f;
-        xp[e][1] = ok ? gates[((long)(b0 + e) * T + t + 1) * G + c1] : 0.f;
-      }
+    for (int k = 0; k < HP; k += 4) {
+      const float4 h4 = *reinterpret_cast<const float4 *>(&h_s[k]);
+      acc0 = fmaf(h4.x, w[k], acc0); acc1 = fmaf(h4.y, w[k + 1], acc1);
+      acc0 = fmaf(h4.z, w[k + 2], acc0); acc1 = fmaf(h4.w, w[k + 3], acc1);
     }
-    if (t > 0) {
-#pragma unroll
-      for (int k = 0; k < HP; k += 4) {
-#pragma unroll
-        for (int e = 0; e < LSTM_NE; ++e) {
-          const float4 h4 = *reinterpret_cast<const float4 *>(&h_s[e][k]);
-          acc[e][0] = fmaf(h4.x, w0[k], acc[e][0]); acc[e][1] = fmaf(h4.x, w1[k], acc[e][1]);
-          acc[e][0] = fmaf(h4.y, w0[k + 1], acc[e][0]); acc[e][1] = fmaf(h4.y, w1[k + 1], acc[e][1]);
-          acc[e][0] = fmaf(h4.z, w0[k + 2], acc[e][0]); acc[e][1] = fmaf(h4.z, w1[k + 2], acc[e][1]);
-          acc[e][0] = fmaf(h4.w, w0[k + 3], acc[e][0]); acc[e][1] = fmaf(h4.w, w1[k + 3], acc[e][1]);
-        }
-      }
-    }
+    const float pre = (acc0 + acc1) + xcur;
+    const float v = is_tanh ? fast_tanh(pre) : sigmoidf_(pre);
     if (col_thread) {
-      // columns [0,H) i, [H,2H) f, [2H,3H) g, [3H,4H) o: c0 < 2H is i or f, c1 = c0+2H is g or o
-      const bool c1_is_g = c1 < 3 * H;
-#pragma unroll
-      for (int e = 0; e < LSTM_NE; ++e) {
-        const float v0 = sigmoidf_(acc[e][0]);
-        const float v1 = c1_is_g ? fast_tanh(acc[e][1]) : sigmoidf_(acc[e][1]);
-        gact[e][c0] = v0; gact[e][c1] = v1;
-        if (b0 + e < B) {
-          gates[((long)(b0 + e) * T + t) * G + c0] = v0;
-          gates[((long)(b0 + e) * T + t) * G + c1] = v1;
-        }
-      }
+      gact[col] = v;
+      lane_at(grow0 + (long)t * G, colx) = v;
     }
     __syncthreads();
     if (upd_thread) {
-      const float gi = gact[ue][ur], gf = gact[ue][H + ur], gg = gact[ue][2 * H + ur], go = gact[ue][3 * H + ur];
+      const float gi = gact[ur], gf = gact[H + ur], gg = gact[2 * H + ur], go = gact[3 * H + ur];
       c_reg = gf * c_reg + gi * gg;
       const float h = go * fast_tanh(c_reg);
-      h_s[ue][ur] = h;
-      const long o = ((long)(b0 + ue) * T + t) * H + ur;
-      hs[o] = h; cs[o] = c_reg;
-      if (hlast != nullptr && t == T - 1) hlast[(long)(b0 + ue) * H + ur] = h;
+      h_s[ur] = h;
+      lane_at(hrow0 + (long)t * H, urx) = h;
+      lane_at(crow0 + (long)t * H, urx) = c_reg;
+      if (hlast != nullptr && t == T - 1) lane_at(hlast + (long)b * H, urx) = h;
     }
     __syncthreads();
+  };
+  float xa = lane_ld(grow0, colb), xb;
+  int t = 0;
+  for (; t + 1 < T; t += 2) {
+    step(t, xa, xb);
+    step(t + 1, xb, xa);
   }
+  if (t < T) step(t, xa, xb);
 }
 
-// Back-propagation through time.  gates: in activated gates, out d(loss)/d(gate
-// pre-activations).  Thread (k = tid % 128, q = tid / 128) owns W_hh[k][q*2H .. q*2H+2H).
+// Back-propagation through time.  gates: in activated gates, out d(loss)/d(gate pre-activations).
+// One workgroup per example; thread (k = tid % 128, q = tid / 128) owns W_hh[k][qH .. qH + H), the columns of
+// gate q, and computes that gate's share of dL/dh_{t-1}[k].
 // SEQ = false: the loss sees h_T only, dh_out is [B, H].  SEQ = true: the layer's output is every h_t,
 // dh_out is [B, T, H] and step t adds its own share to what the later steps send back.
 template <int HP, bool SEQ>
-__global__ __launch_bounds__(256) void lstm_bwd_kernel(float *__restrict__ gates, const float *__restrict__ cs,
-                                                        const float *__restrict__ Whh,
-                                                        const float *__restrict__ dh_out, int B, int T, int H) {
-  constexpr int DG_LD = 2 * HP; // per half, padded so that float4 reads stay aligned
-  __shared__ __attribute__((aligned(16))) float dg_s[LSTM_NE][2 * DG_LD];
-  __shared__ float part_s[LSTM_NE][2][128];
+__global__ __launch_bounds__(LSTM_THREADS, (HP <= 100 ? 4 : 2)) void lstm_bwd_kernel(float *__restrict__ gates, const float *__restrict__ cs,
+                                                                 const float *__restrict__ Whh,
+                                                                 const float *__restrict__ dh_out, int B, int T, int H) {
+  __shared__ __attribute__((aligned(16))) float dg_s[4 * HP]; // gate-major, each gate padded to HP (zeros)
+  __shared__ float part_s[4][128];
   const int tid = threadIdx.x;
-  const int b0 = blockIdx.x * LSTM_NE;
+  const int b = blockIdx.x; // the grid is exactly B workgroups
   const int G = 4 * H;
   const int k = tid & 127, q = tid >> 7;
-  float w[DG_LD];
+  float w[HP];
 #pragma unroll
-  for (int j = 0; j < DG_LD; ++j) w[j] = (k < H && j < 2 * H) ? Whh[(long)k * G + q * 2 * H + j] : 0.f;
-  for (int i = tid; i < LSTM_NE * 2 * DG_LD; i += 256) (&dg_s[0][0])[i] = 0.f;
-  const int ue = tid / H, ur = tid - ue * H;
-  const bool upd_thread = tid < LSTM_NE * H && (b0 + ue) < B;
-  const long ub = b0 + ue;
+  for (int j = 0; j < HP; ++j) w[j] = (k < H && j < H) ? Whh[(long)k * G + q * H + j] : 0.f;
+  for (int i = tid; i < 4 * HP; i += LSTM_THREADS) dg_s[i] = 0.f;
+  for (int i = tid; i < 4 * 128; i += LSTM_THREADS) (&part_s[0][0])[i] = 0.f;
+  const bool upd_thread = tid < H;
+  const int ur = upd_thread ? tid : 0;
+  const unsigned urb = 4u * ur;
+  float *const grow0 = gates + (long)b * T * G;
+  const float *const crow0 = cs + (long)b * T * H;
+  const float *const drow0 = SEQ ? dh_out + (long)b * T * H : dh_out + (long)b * H;
+  // Operands of the step being processed, held by the cell-update threads only.  They are declared without a
+  // value and loaded and used inside the same branch: an initial value, a load under one branch used under
+  // another, or a loaded value copied into a second variable would each be waited for at once, not at the use.
+  float gi, gf, gg, go, cp, dh_own, ct;
   float dc = 0.f;
-  float gi = 0.f, gf = 0.f, gg = 0.f, go = 0.f, ct = 0.f, cp = 0.f, dh_own = 0.f;
   if (upd_thread) {
-    const long o = (ub * T + (T - 1));
-    dh_own = SEQ ? dh_out[o * H + ur] : dh_out[ub * H + ur];
-    gi = gates[o * G + ur]; gf = gates[o * G + H + ur]; gg = gates[o * G + 2 * H + ur]; go = gates[o * G + 3 * H + ur];
-    ct = cs[o * H + ur]; cp = T > 1 ? cs[(o - 1) * H + ur] : 0.f;
+    const float *g = grow0 + (long)(T - 1) * G;
+    gi = lane_ld(g, urb); gf = lane_ld(g + H, urb); gg = lane_ld(g + 2 * H, urb); go = lane_ld(g + 3 * H, urb);
+    ct = lane_ld(crow0 + (long)(T - 1) * H, urb);
+    cp = lane_ld(crow0 + (long)max(T - 2, 0) * H, urb); // c_{t-1}; unused at t = 0
+    dh_own = SEQ ? lane_ld(drow0 + (long)(T - 1) * H, urb) : lane_ld(drow0, urb);
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the weight loads end here, not at their first use inside the loop
   __syncthreads();
   for (int t = T - 1; t >= 0; --t) {
-    if (upd_thread) {
-      float dh = (t == T - 1) ? 0.f : part_s[ue][0][ur] + part_s[ue][1][ur];
+    if (upd_thread) { // (the waves without a cell-update thread skip this)
+      // (lane offset re-materialised inside the loop: hoisted out of it, it would be widened to 64 bits)
+      unsigned urx = urb;
+      asm volatile("" : "+v"(urx));
+      // what the later steps send back (zero at the last step: part_s starts cleared) plus the loss's own share
+      float dh = (part_s[0][ur] + part_s[1][ur]) + (part_s[2][ur] + part_s[3][ur]);
       if (SEQ || t == T - 1) dh += dh_own;
+      const float cprev = t > 0 ? cp : 0.f;
       const float tc = fast_tanh(ct);
       const float dct = dc + dh * go * (1.f - tc * tc);
       const float d_o = dh * tc * go * (1.f - go);
       const float d_i = dct * gg * gi * (1.f - gi);
-      const float d_f = dct * cp * gf * (1.f - gf);
+      const float d_f = dct * cprev * gf * (1.f - gf);
       const float d_g = dct * gi * (1.f - gg * gg);
       dc = dct * gf;
-      const long o = (ub * T + t) * G;
-      gates[o + ur] = d_i; gates[o + H + ur] = d_f; gates[o + 2 * H + ur] = d_g; gates[o + 3 * H + ur] = d_o;
-      // columns [0,2H) = i,f go to half 0; [2H,4H) = g,o to half 1
-      dg_s[ue][ur] = d_i; dg_s[ue][H + ur] = d_f;
-      dg_s[ue][DG_LD + ur] = d_g; dg_s[ue][DG_LD + H + ur] = d_o;
-      if (t > 0) { // operands of the next iteration; they land while the product below runs
-        const long on = (ub * T + (t - 1));
-        gi = gates[on * G + ur]; gf = gates[on * G + H + ur]; gg = gates[on * G + 2 * H + ur];
-        go = gates[on * G + 3 * H + ur];
-        ct = cp; cp = t > 1 ? cs[(on - 1) * H + ur] : 0.f;
-        if (SEQ) dh_own = dh_out[on * H + ur];
-      }
+      float *g = grow0 + (long)t * G;
+      lane_at(g, urx) = d_i; lane_at(g + H, urx) = d_f; lane_at(g + 2 * H, urx) = d_g; lane_at(g + 3 * H, urx) = d_o;
+      dg_s[ur] = d_i; dg_s[HP + ur] = d_f; dg_s[2 * HP + ur] = d_g; dg_s[3 * HP + ur] = d_o;
+      // operands of step t - 1 (row clamped at the first step) into the registers just freed; they land while
+      // the product below runs
+      const int tn = max(t - 1, 0);
+      const float *gn = grow0 + (long)tn * G;
+      gi = lane_ld(gn, urx); gf = lane_ld(gn + H, urx); gg = lane_ld(gn + 2 * H, urx); go = lane_ld(gn + 3 * H, urx);
+      ct = lane_ld(crow0 + (long)tn * H, urx); // (loaded again rather than copied from cp: see above)
+      cp = lane_ld(crow0 + (long)max(tn - 1, 0) * H, urx);
+      if (SEQ) dh_own = lane_ld(drow0 + (long)tn * H, urx);
     }
     __syncthreads();
     if (t > 0) {
-      float acc[LSTM_NE];
+      float acc = 0.f; // (two waves per SIMD alternate, which covers the latency of the dependent chain)
 #pragma unroll
-      for (int e = 0; e < LSTM_NE; ++e) acc[e] = 0.f;
-#pragma unroll
-      for (int j = 0; j < DG_LD; j += 4) {
-#pragma unroll
-        for (int e = 0; e < LSTM_NE; ++e) {
-          const float4 d4 = *reinterpret_cast<const float4 *>(&dg_s[e][q * DG_LD + j]);
-          acc[e] = fmaf(d4.x, w[j], acc[e]); acc[e] = fmaf(d4.y, w[j + 1], acc[e]);
-          acc[e] = fmaf(d4.z, w[j + 2], acc[e]); acc[e] = fmaf(d4.w, w[j + 3], acc[e]);
-        }
+      for (int j = 0; j < HP; j += 4) {
+        const float4 d4 = *reinterpret_cast<const float4 *>(&dg_s[q * HP + j]);
+        acc = fmaf(d4.x, w[j], acc); acc = fmaf(d4.y, w[j + 1], acc);
+        acc = fmaf(d4.z, w[j + 2], acc); acc = fmaf(d4.w, w[j + 3], acc);
       }
-#pragma unroll
-      for (int e = 0; e < LSTM_NE; ++e) part_s[e][q][k] = acc[e];
+      part_s[q][k] = acc;
     }
     __syncthreads();
   }
