@@ -328,6 +328,10 @@ def tiny_models():
             conv2d(3, 20, 3, stride=1, pad=1, act="tanh"), conv2d(20, 40, 3, stride=1, pad=1, act="tanh"),
             conv2d(40, 70, 3, stride=1, pad=1, act="tanh"), conv2d(70, 24, 3, stride=1, pad=0, act="tanh"),
             maxpool2d(2, 2), dense(24 * 3 * 3, 3)], 3),
+        # more than 128 output channels: the weight-gradient kernels take them in slices of 128 (here 128 + 2)
+        "tiny_conv_wide": model(image_input(3, 4, 4), [
+            conv2d(3, 20, 3, stride=1, pad=1, act="relu"), conv2d(20, 130, 3, stride=1, pad=1, act="tanh"),
+            avgpool2d(2, 2), dense(130 * 2 * 2, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
         "tiny_emb": model(token_input(6), [embedding(7, 3), seq_mean(), dense(3, 2)], 2),
         "tiny_lstm_seq": model(token_input(5), [embedding(7, 3), lstm_seq(3, 4), seq_mean(), dense(4, 2)], 2),

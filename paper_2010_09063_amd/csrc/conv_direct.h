@@ -247,14 +247,16 @@ struct ConvWgArgs {
   const float *delta; // [B, D, OH, OW]
   const float *scale; // clip factors s[b]; always valid (a vector of ones when nothing is clipped)
   float *out;         // norm mode: slots base; clipped mode: partials base
-  int B, C, H, W, D, OH, OW, pad;
+  int B, C, H, W, D, OH, OW, pad; // D: the output channels this launch covers (at most 128, a slice of the layer's)
+  int Dstride;        // output channels of the whole layer: Delta's per-example stride is Dstride*OH*OW
+  long bias_off;      // clipped mode: the slice's bias gradients go to part[bias_off + d]
   int mode;           // 0: per-example squared norm; 1: sum over the block's examples
   int ex_per_block;   // clipped mode
   int PCH, LDP;       // pixels per K-chunk (= NIMG*TR*OW) and padded (odd) row length of the staged Delta
   int WQ, ROWS;       // W/4 float4 groups per input row; staged rows per image = TR + KH - 1
   FastDiv dWQ, dROWS, dNIMG, dPQ; // item decoding (PQ = PCH/4)
   long slot_stride; int slot0; // norm: slots[(slot0 + cblock)*slot_stride + b]
-  long part_stride;   // clipped: part[split*part_stride + (d*C + c)*KK + tap]; bias at D*C*KK + d
+  long part_stride;   // clipped: part[split*part_stride + (d*C + c)*KK + tap]
   ConvTile t;         // XPLANE odd
 };
 
@@ -325,7 +327,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
     const int r = (int)a.t.dOW.div(rem);
     const bool ok = d < DT;
     d_lds[j] = ok ? d * a.LDP + p : -1;
-    d_goff[j] = (d < a.D) ? (img * a.D + d) * OHW + rem : -1;
+    d_goff[j] = (d < a.D) ? (img * a.Dstride + d) * OHW + rem : -1;
     d_ir[j] = (img << 16) | r;
   }
 
@@ -372,7 +374,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       xr[j] = *reinterpret_cast<const float4 *>(a.x + (ok ? xb + x_goff[j] : 0));
       xok = ok ? (xok | (1u << j)) : (xok & ~(1u << j));
     }
-    const long db_ = (long)b * a.D * OHW + (long)r0 * a.OW;
+    const long db_ = (long)b * a.Dstride * OHW + (long)r0 * a.OW;
 #pragma unroll
     for (int j = 0; j < DV; ++j) {
       const int img = d_ir[j] >> 16, r = d_ir[j] & 0xffff;
@@ -597,7 +599,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
       if (wk == 0 && li < CKK && d < a.D) part[(long)d * CKK + li] = acc[0][0][r];
     }
-    if (tid < a.D) part[(long)a.D * CKK + tid] = bias_d;
+    if (tid < a.D) part[a.bias_off + tid] = bias_d;
     return;
   }
   // taps innermost: the stores of one (row, lane) are consecutive words, so the 32 lanes fill whole
@@ -612,7 +614,7 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       for (int j = 0; j < NBW; ++j)
         if (wk == 0 && wn * NBW + j < KK && c < a.C && d < a.D) row[j] = acc[i][j][r];
     }
-  if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = bias_d;
+  if (cb == 0 && tid < a.D) part[a.bias_off + tid] = bias_d;
 }
 
 // ---------------------------------------------------------------- weight gradient, specialised waves
@@ -686,7 +688,7 @@ __global__ __launch_bounds__(512, 1) void conv_s1_wgrad_ws_kernel(const ConvWgAr
       const int r = (int)a.t.dOW.div(rem);
       const bool ok = d < DT;
       d_lds[j] = ok ? d * a.LDP + p : -1;
-      d_goff[j] = (d < a.D) ? (img * a.D + d) * OHW + rem : -1;
+      d_goff[j] = (d < a.D) ? (img * a.Dstride + d) * OHW + rem : -1;
       d_ir[j] = (img << 16) | r;
     }
     float rowsum[DV]; // bias gradient: sum of the staged (scaled) Delta of item j's row, this thread's pixels
@@ -705,7 +707,7 @@ __global__ __launch_bounds__(512, 1) void conv_s1_wgrad_ws_kernel(const ConvWgAr
         xr[j] = *reinterpret_cast<const float4 *>(a.x + (ok ? xb + x_goff[j] : 0));
         xok = ok ? (xok | (1u << j)) : (xok & ~(1u << j));
       }
-      const long db_ = (long)b * a.D * OHW + (long)r0 * a.OW;
+      const long db_ = (long)b * a.Dstride * OHW + (long)r0 * a.OW;
 #pragma unroll
       for (int j = 0; j < DV; ++j) {
         const int img = d_ir[j] >> 16, r = d_ir[j] & 0xffff;
@@ -955,7 +957,7 @@ __global__ __launch_bounds__(512, 1) void conv_s1_wgrad_ws_kernel(const ConvWgAr
         const int d = 8 * (r >> 2) + 4 * lk + (r & 3);
         if (li < CKK && d < a.D) part[(long)d * CKK + li] = gathered(0, r);
       }
-    if (tid < a.D) part[(long)a.D * CKK + tid] = rsum[0][tid];
+    if (tid < a.D) part[a.bias_off + tid] = rsum[0][tid];
     return;
   }
   if (wk == 0)
@@ -967,5 +969,5 @@ __global__ __launch_bounds__(512, 1) void conv_s1_wgrad_ws_kernel(const ConvWgAr
       for (int j = 0; j < NBW; ++j)
         if (wn * NBW + j < KK && c < a.C && d < a.D) row[j] = gathered(j, r);
     }
-  if (cb == 0 && tid < a.D) part[(long)a.D * a.C * KK + tid] = rsum[0][tid];
+  if (cb == 0 && tid < a.D) part[a.bias_off + tid] = rsum[0][tid];
 }

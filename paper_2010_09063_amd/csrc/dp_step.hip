@@ -263,7 +263,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
   }
   // weight gradient
   const bool flat = g.C * 9 <= 32 && g.D <= 32;
-  if ((g.C >= 16 || flat) && g.D <= 128 && (g.OW & 3) == 0 && (g.W & 3) == 0) {
+  if ((g.C >= 16 || flat) && (g.OW & 3) == 0 && (g.W & 3) == 0) {
     int db = g.D <= 32 ? 1 : (g.D <= 64 ? 2 : 4);
     int pch_max = flat ? 256 : (db <= 2 ? 128 : 64);
     const int xch = flat ? g.C : 32;
@@ -367,10 +367,15 @@ static void launch_conv_wgrad(const LN &Ln, const char *label, const ConvWgArgs 
 #undef DP_WS_CASE
 }
 
-static ConvWgArgs make_wg_args(const Layer &l, const float *x, int B, const ConvTile &t) {
+// Arguments for the slice of at most 128 output channels that starts at channel d0 (layers with more output
+// channels take one launch per slice: Delta and the clipped-mode output are offset to the slice).
+#define DP_WG_DSLICE 128
+static ConvWgArgs make_wg_args(const Layer &l, const float *x, int B, const ConvTile &t, int d0) {
   const ConvGeom &g = l.geom;
   ConvWgArgs a{};
-  a.x = x; a.delta = l.g; a.B = B; a.C = g.C; a.H = g.H; a.W = g.W; a.D = g.D; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
+  a.x = x; a.delta = l.g + (long)d0 * g.P; a.B = B; a.C = g.C; a.H = g.H; a.W = g.W; a.OH = g.OH; a.OW = g.OW; a.pad = g.PAD;
+  a.D = std::min(DP_WG_DSLICE, g.D - d0); a.Dstride = g.D;
+  a.bias_off = (long)g.D * g.CKK + d0 - (long)d0 * g.CKK; // relative to the slice's own output base
   a.t = t;
   a.PCH = t.NIMG * t.TR * g.OW; a.LDP = a.PCH | 1;
   a.WQ = g.W / 4; a.ROWS = t.TR + 2;
@@ -816,16 +821,18 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
         if (priv && l.dir_wg && aligned16(lin)) {
-          ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn);
           // one round of resident workgroups, each walking through its run of examples: the next
           // example's tiles are fetched while the current one is multiplied and reduced
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
           const int resident = 256 * (l.wg_ws ? 1 : (l.wg_db <= 2 ? 2 : 1));
-          int epb = ceil_div(B, std::max(1, resident / cblocks));
-          a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = epb;
-          a.slot_stride = slot_stride; a.slot0 = slot_next;
-          slot_next += cblocks;
-          launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, l.wg_ws, ceil_div(B, epb));
+          const int epb = ceil_div(B, std::max(1, resident / cblocks)); // per slice (measured: better than sharing one round)
+          for (int d0 = 0; d0 < g.D; d0 += DP_WG_DSLICE) {
+            ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn, d0);
+            a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = epb;
+            a.slot_stride = slot_stride; a.slot0 = slot_next;
+            slot_next += cblocks;
+            launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, l.wg_ws, ceil_div(B, epb));
+          }
         } else if (priv) {
           auto run = [&](auto vt) {
             constexpr bool V = decltype(vt)::value;
@@ -981,7 +988,6 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
         if (l.dir_wg && aligned16(lin)) {
-          ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc);
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
           // one full round of resident workgroups (256 CUs x workgroups per CU) avoids a ragged tail
           const int occ = l.wg_ws ? 1 : (l.wg_db == 1 ? 3 : (l.wg_db == 2 ? 2 : 1));
@@ -989,10 +995,13 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           if (want < 1) want = 1;
           if (want > l.max_split) want = l.max_split;
           int epb = ceil_div(B, want);
-          epb = ceil_div(epb, a.t.NIMG) * a.t.NIMG;
+          epb = ceil_div(epb, l.t_wgc.NIMG) * l.t_wgc.NIMG;
           nsplit = ceil_div(B, epb);
-          a.scale = sc; a.out = l.part; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
-          launch_conv_wgrad(Ln, LL("conv_clipped_sum"), a, l.wg_db, l.wg_flat, l.wg_ws, nsplit);
+          for (int d0 = 0; d0 < g.D; d0 += DP_WG_DSLICE) {
+            ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc, d0);
+            a.scale = sc; a.out = l.part + (long)d0 * g.CKK; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
+            launch_conv_wgrad(Ln, LL("conv_clipped_sum"), a, l.wg_db, l.wg_flat, l.wg_ws, nsplit);
+          }
           break;
         }
         typedef ProbPartial<OpChanPix, OpConvPatch<false>> Pb;
