@@ -61,7 +61,12 @@ def label_work(m, B):
             add("conv_fwd", fl, 4.0 * (xin + wts + xout))
             if li > 0:
                 add("conv_bwd_data", fl, 4.0 * (xout + wts + 2 * xin))
-            add("conv_wgrad_norm", fl, 4.0 * (xin + xout))
+            # small planes: the library takes the norm from the P x P Gram matrices of patches and of Delta
+            # (same rule as its planner), P^2 (9C + D) multiply-adds per example instead of 9 C D P
+            Pp = OH * OW
+            gram = (L["kh"] == 3 and L["kw"] == 3 and L["stride"] == 1 and L["pad"] == 1 and (OH, OW) in ((8, 8), (4, 4))
+                    and Pp * (ckk + D_) < D_ * ckk)
+            add("conv_wgrad_norm", 2.0 * B * Pp * Pp * (ckk + D_) if gram else fl, 4.0 * (xin + xout))
             add("conv_clipped_sum", fl, 4.0 * (xin + xout + wts))
         elif k == "maxpool2d":
             n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]

@@ -332,6 +332,11 @@ def tiny_models():
         "tiny_conv_wide": model(image_input(3, 4, 4), [
             conv2d(3, 20, 3, stride=1, pad=1, act="relu"), conv2d(20, 130, 3, stride=1, pad=1, act="tanh"),
             avgpool2d(2, 2), dense(130 * 2 * 2, 3)], 3),
+        # 8x8 and 4x4 planes with enough channels that the per-example norm goes through Gram matrices; channel
+        # counts that are no multiples of the 32-plane chunk
+        "tiny_conv_gram": model(image_input(3, 8, 8), [
+            conv2d(3, 40, 3, stride=1, pad=1, act="relu"), conv2d(40, 100, 3, stride=1, pad=1, act="tanh"),
+            avgpool2d(2, 2), conv2d(100, 70, 3, stride=1, pad=1, act="tanh"), dense(70 * 4 * 4, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
         "tiny_emb": model(token_input(6), [embedding(7, 3), seq_mean(), dense(3, 2)], 2),
         "tiny_lstm_seq": model(token_input(5), [embedding(7, 3), lstm_seq(3, 4), seq_mean(), dense(4, 2)], 2),

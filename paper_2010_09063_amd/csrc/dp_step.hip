@@ -15,6 +15,7 @@
 
 #include "gemm_tile.h"
 #include "conv_direct.h"
+#include "conv_gram.h"
 #include "kernels_misc.h"
 #include "kernels_seq.h"
 #include "operands.h"
@@ -122,6 +123,7 @@ struct Layer {
   // stride-1 3x3 convolutions: LDS-staged direct kernels (otherwise the generic contraction)
   bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
   bool wg_ws = false; // weight gradient with specialised staging / multiplying waves (two LDS buffers)
+  bool gram = false;  // per-example norm from the P x P Gram matrices (small planes)
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
   ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
   float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
@@ -261,6 +263,11 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
     if (make_conv_tile(l.t_bwd, g.H, g.W, 3, 3, 4 * npw, false, 1 << 20) &&
         l.t_bwd.XPLANE <= CONV_XPLANE_MAX) { l.dir_bwd = true; l.bwd_npw = npw; }
   }
+  // per-example norm from Gram matrices: P^2 (9C + D) multiply-adds instead of 9 C D P, for the two plane sizes
+  // the kernel is built for (pad 1, so the input plane equals the output plane)
+  if (g.PAD == 1 && g.H == g.OH && g.W == g.OW && ((g.OH == 8 && g.OW == 8) || (g.OH == 4 && g.OW == 4)) &&
+      (long)g.P * (g.CKK + g.D) < (long)g.D * g.CKK && getenv("DP_STEP_NO_GRAM") == nullptr)
+    l.gram = true;
   // weight gradient
   const bool flat = g.C * 9 <= 32 && g.D <= 32;
   if ((g.C >= 16 || flat) && (g.OW & 3) == 0 && (g.W & 3) == 0) {
@@ -820,7 +827,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
-        if (priv && l.dir_wg && aligned16(lin)) {
+        if (priv && l.gram && aligned16(lin)) {
+          ConvGramArgs ga{lin, l.g, c->slots + (long)slot_next * slot_stride, B, g.C, g.D};
+          slot_next += 1;
+          dim3 block(256);
+          if (g.OH == 8) {
+            dim3 grid(ceil_div(B, ConvGramGeom<8, 8>::NIMG));
+            Ln(LL("conv_wgrad_norm"), grid, block, [&](hipStream_t st) {
+              hipLaunchKernelGGL((conv_gram_norm_kernel<8, 8>), grid, block, 0, st, ga);
+            });
+          } else {
+            dim3 grid(ceil_div(B, ConvGramGeom<4, 4>::NIMG));
+            Ln(LL("conv_wgrad_norm"), grid, block, [&](hipStream_t st) {
+              hipLaunchKernelGGL((conv_gram_norm_kernel<4, 4>), grid, block, 0, st, ga);
+            });
+          }
+        } else if (priv && l.dir_wg && aligned16(lin)) {
           // one round of resident workgroups, each walking through its run of examples: the next
           // example's tiles are fetched while the current one is multiplied and reduced
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
