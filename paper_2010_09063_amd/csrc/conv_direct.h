@@ -257,6 +257,9 @@ struct ConvWgArgs {
   FastDiv dWQ, dROWS, dNIMG, dPQ; // item decoding (PQ = PCH/4)
   long slot_stride; int slot0; // norm: slots[(slot0 + cblock)*slot_stride + b]
   long part_stride;   // clipped: part[split*part_stride + (d*C + c)*KK + tap]
+  float *gstore;      // norm mode, optional (null: norms only): example b's gradient goes to gstore[b*gstride + ...]
+  long gstride;       // in accumulator order, [channel block][wave group][tap slot][16 registers][64 lanes], so
+  long gbias_off;     // that every store instruction writes 256 consecutive bytes; the bias follows at gbias_off
   ConvTile t;         // XPLANE odd
 };
 
@@ -447,7 +450,27 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
       __syncthreads();
     }
     float part = 0.f;
-    if (wk == 0) {
+    if (wk == 0 && a.gstore != nullptr) {
+      // the same sums, also written out as example b's gradient.  Taps innermost: the words one lane stores are
+      // consecutive, so whole cache lines fill within a few instructions.
+      float *gb = a.gstore + (long)b * a.gstride;
+      if (cb == 0 && tid < a.D) gb[a.gbias_off + tid] = bias_d;
+      // accumulator order: no range tests (slots outside the real ranges hold exact zeros) and no address that
+      // depends on more than the lane
+      float *gw = gb + ((long)(cb * (WD * WN) + grp) * NBW * 16) * 64 + lane;
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = acc[0][j][r];
+#pragma unroll
+          for (int q = 0; q < WK - 1; ++q) v += xs[(((grp * (WK - 1) + q) * NBW + j) * 16 + r) * 64 + lane];
+          part += v * v;
+          gw[(j * 16 + r) * 64] = v;
+        }
+        if (WK > 1) __builtin_amdgcn_sched_barrier(0); // one block of 16 loads in flight at a time (register pressure)
+      }
+    } else if (wk == 0) {
       const int CKK = a.C * KK;
 #pragma unroll
       for (int i = 0; i < DBW; ++i)
@@ -481,6 +504,18 @@ __global__ __launch_bounds__(256, (DB <= 2 ? 2 : 1)) void conv_s1_wgrad_kernel(c
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     rowsum = 0.f;
+    if (WK > 1) {
+      // the cross-wave area lies over the staged input: put the zeros back into the halo columns, which the
+      // staging of the next example does not write (every read of the area is behind the barrier above, and
+      // the next reads of the input are two barriers away)
+      const int halo = a.t.LDW - a.W, rows_l = xch * a.t.NIMG * a.ROWS; // halo = 2*pad cells per staged row
+      for (int e = tid; e < rows_l * halo; e += 256) {
+        const int rowi = e / halo, h = e - rowi * halo;
+        const int cimg = rowi / a.ROWS, rr = rowi - cimg * a.ROWS;
+        const int ch = cimg / a.t.NIMG, img = cimg - ch * a.t.NIMG;
+        Xl[ch * a.t.XPLANE + img * a.t.IMGPL + rr * a.t.LDW + (h < a.pad ? h : a.W + h)] = 0.f;
+      }
+    }
   };
 
   const int n_chunks = ((bend - bbeg + nimg_max - 1) / nimg_max) * a.t.row_tiles;

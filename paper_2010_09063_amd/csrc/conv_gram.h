@@ -110,11 +110,12 @@ __global__ __launch_bounds__(256) void conv_gram_norm_kernel(ConvGramArgs a) {
       const int nv = min(CH, NPL - c0); // planes past nv hold zeros (zero-filled above): whole pairs are skipped
 #pragma unroll
       for (int cp = 0; cp < CH / 2; ++cp) {
-        if (2 * cp >= nv) break;
+        if (2 * cp < nv) { // (a guard, not a break: the loop unrolls and every offset is a compile-time constant)
 #pragma unroll
-        for (int t = 0; t < TAPS; ++t) {
-          const int off = cp * 2 * XPL + (TAPS == 9 ? (t / 3) * LDW + (t % 3) : LDW + 1);
-          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[off], pb[off], acc, 0, 0, 0);
+          for (int t = 0; t < TAPS; ++t) {
+            const int off = cp * 2 * XPL + (TAPS == 9 ? (t / 3) * LDW + (t % 3) : LDW + 1);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(pa[off], pb[off], acc, 0, 0, 0);
+          }
         }
       }
     }

@@ -124,6 +124,8 @@ struct Layer {
   bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
   bool wg_ws = false; // weight gradient with specialised staging / multiplying waves (two LDS buffers)
   bool gram = false;  // per-example norm from the P x P Gram matrices (small planes)
+  float *gst = nullptr; // [maxB][gorder.n_w + D] per-example gradients written by the norm pass (large planes)
+  GradOrder gorder{};
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
   ConvTile t_fwd, t_bwd, t_wgn, t_wgc;
   float *wt_f = nullptr, *wt_b = nullptr; // re-laid weights for the direct kernels
@@ -148,7 +150,7 @@ static const char *const kLayerLabels[] = {"dense_fwd", "dense_fwd_epilogue", "d
                                            "conv_weight_layout", "conv_fwd", "conv_wgrad_norm", "conv_bwd_data", "conv_clipped_sum",
                                            "maxpool_fwd", "maxpool_bwd", "lstm_xproj", "lstm_fwd", "lstm_bwd", "lstm_wgrad_norm",
                                            "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_gather", "emb_bucket", "emb_scatter", "fill_zero",
-                                           "seq_mean_fwd", "seq_mean_bwd", "avgpool_fwd", "avgpool_bwd"};
+                                           "seq_mean_fwd", "seq_mean_bwd", "avgpool_fwd", "avgpool_bwd", "conv_weighted_sum"};
 
 struct dp_ctx {
   dp_model_desc m;
@@ -545,6 +547,21 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       if (rc == DP_OK && (hipMemset(l.wt_f, 0, nf * sizeof(float)) != hipSuccess ||
                           hipMemset(l.wt_b, 0, nb * sizeof(float)) != hipSuccess)) rc = DP_EHIP;
     }
+    // Large planes: the norm pass writes each example's gradient (8 bytes of traffic per coordinate, written and
+    // read once) and the clipped sum becomes a weighted sum of those rows; repeating the contraction instead costs
+    // 2 P flops per coordinate, which is more from P = 256 pixels on.
+    if (rc == DP_OK && l.d.kind == DP_CONV2D && l.dir_wg && !l.gram && !l.wg_ws && l.geom.D <= DP_WG_DSLICE &&
+        l.geom.P >= 256 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
+      // the order in which conv_s1_wgrad_kernel<3, 3, wg_db, wg_flat, false> holds the gradient in its accumulators
+      GradOrder &o = l.gorder;
+      o.C = l.geom.C; o.D = l.geom.D; o.KK = 9; o.flat = l.wg_flat ? 1 : 0;
+      o.WN = l.wg_flat ? 1 : 2;                       // wg_db is 1 or 2 here
+      o.NW = l.wg_flat ? 1 : (l.wg_db == 1 ? 2 : 4);
+      o.NBW = l.wg_flat ? 1 : 5;
+      const long cblocks = l.wg_flat ? 1 : ceil_div(l.geom.C, 32);
+      o.n_w = cblocks * o.NW * o.NBW * 1024;
+      rc = dev_alloc(c, &l.gst, (size_t)mb * (o.n_w + o.D));
+    }
     if (rc == DP_OK && emb) {
       const size_t V = l.d.vocab;
       rc = dev_alloc(c, &l.e_count, V + 1);
@@ -852,6 +869,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn, d0);
             a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = epb;
             a.slot_stride = slot_stride; a.slot0 = slot_next;
+            a.gstore = l.gst; a.gstride = l.gorder.n_w + g.D; a.gbias_off = l.gorder.n_w;
             slot_next += cblocks;
             launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, l.wg_ws, ceil_div(B, epb));
           }
@@ -1009,6 +1027,19 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
+        if (priv && l.gst && l.dir_wg && aligned16(lin)) {
+          // the norm pass of this step stored every example's gradient: weighted sum of the rows
+          const long gstride = l.gorder.n_w + g.D;
+          int want = (int)std::min<long>(l.max_split, std::max<long>(1, 4096 / ceil_div(gstride, 256)));
+          const int eps = std::max(4, ceil_div(B, want));
+          nsplit = ceil_div(B, eps);
+          dim3 grid((unsigned)ceil_div(gstride, 256), nsplit), block(256);
+          Ln(LL("conv_weighted_sum"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(weighted_sum_kernel, grid, block, 0, st, (const float *)l.gst, gstride, sc, l.part,
+                               l.p_count, l.gorder, B, eps);
+          });
+          break;
+        }
         if (l.dir_wg && aligned16(lin)) {
           const int cblocks = l.wg_flat ? 1 : ceil_div(g.C, 32);
           // one full round of resident workgroups (256 CUs x workgroups per CU) avoids a ragged tail

@@ -201,6 +201,56 @@ __global__ void avgpool2x2_bwd_kernel(const float *__restrict__ gout, const floa
   *reinterpret_cast<float2 *>(gin + o1) = r1;
 }
 
+// Clipped sum of stored per-example gradients (Section 1, items 2b-3): sum over a split's examples of
+// s[b] * g[b][n], where a row of g is in the accumulator order of the convolution weight-gradient kernel
+// ([channel block][wave group][tap slot][16 registers][64 lanes], then the bias).  Thread = one stored word n
+// (consecutive lanes read consecutive words), blockIdx.y = split; the result goes to the parameter layout
+// part[split][(d*C + c)*KK + tap] (bias: D*C*KK + d); padding slots are skipped.
+struct GradOrder {
+  int C, D, KK;       // layer shape
+  int NBW, WN, NW;    // tap slots per wave group, wave groups along the taps, wave groups per channel block
+  int flat;           // 1: one wave group whose lane column is the flattened (channel, tap) index
+  long n_w;           // stored words before the bias
+};
+__global__ __launch_bounds__(256) void weighted_sum_kernel(const float *__restrict__ g, long gstride,
+                                                           const float *__restrict__ s, float *__restrict__ part,
+                                                           long pstride, GradOrder o, int B, int ex_per_split) {
+  const long n = (long)blockIdx.x * 256 + threadIdx.x;
+  if (n >= o.n_w + o.D) return;
+  long p;
+  if (n >= o.n_w) {
+    p = (long)o.D * o.C * o.KK + (n - o.n_w);
+  } else {
+    const int lane = (int)(n & 63), r = (int)((n >> 6) & 15);
+    const long t = n >> 10;
+    const int j = (int)(t % o.NBW);
+    const long t2 = t / o.NBW;
+    const int grp = (int)(t2 % o.NW), cbi = (int)(t2 / o.NW);
+    const int wd = grp / o.WN, wn = grp % o.WN;
+    const int li = lane & 31, lk = lane >> 5;
+    const int d = wd * 32 + 8 * (r >> 2) + 4 * lk + (r & 3);
+    if (d >= o.D) return;
+    if (o.flat) {
+      if (li >= o.C * o.KK) return;
+      p = (long)d * o.C * o.KK + li;
+    } else {
+      const int c = cbi * 32 + li, tap = wn * o.NBW + j;
+      if (c >= o.C || tap >= o.KK) return;
+      p = ((long)d * o.C + c) * o.KK + tap;
+    }
+  }
+  const int b0 = blockIdx.y * ex_per_split, b1 = min(B, b0 + ex_per_split);
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int b = b0;
+  for (; b + 4 <= b1; b += 4) {
+    const float v0 = g[(long)b * gstride + n], v1 = g[(long)(b + 1) * gstride + n], v2 = g[(long)(b + 2) * gstride + n],
+                v3 = g[(long)(b + 3) * gstride + n];
+    a0 = fmaf(s[b], v0, a0); a1 = fmaf(s[b + 1], v1, a1); a2 = fmaf(s[b + 2], v2, a2); a3 = fmaf(s[b + 3], v3, a3);
+  }
+  for (; b < b1; ++b) a0 = fmaf(s[b], g[(long)b * gstride + n], a0);
+  part[(long)blockIdx.y * pstride + p] = (a0 + a1) + (a2 + a3);
+}
+
 // Dense layer: ||g_i||^2 = (||a_i||^2 + 1) ||delta_i||^2 without forming the outer
 // product (Section 1: per-example norms for fully-connected layers).  One wave per example.
 __global__ void dense_norm_kernel(const float *__restrict__ a, int d_in, const float *__restrict__ delta, int d_out,
