@@ -66,8 +66,17 @@ def label_work(m, B):
             Pp = OH * OW
             gram = (L["kh"] == 3 and L["kw"] == 3 and L["stride"] == 1 and L["pad"] == 1 and (OH, OW) in ((8, 8), (4, 4))
                     and Pp * (ckk + D_) < D_ * ckk)
-            add("conv_wgrad_norm", 2.0 * B * Pp * Pp * (ckk + D_) if gram else fl, 4.0 * (xin + xout))
-            add("conv_clipped_sum", fl, 4.0 * (xin + xout + wts))
+            # large planes: the norm pass also writes each example's gradient and the clipped sum is a weighted
+            # sum of those rows (same rule as the planner, for the shapes of these workloads)
+            flat = C_ * 9 <= 32 and D_ <= 32
+            store = (not gram and L["kh"] == 3 and L["kw"] == 3 and L["stride"] == 1 and Pp >= 256 and D_ <= 64
+                     and (C_ >= 16 or flat) and OW % 4 == 0 and W_ % 4 == 0)
+            add("conv_wgrad_norm", 2.0 * B * Pp * Pp * (ckk + D_) if gram else fl,
+                4.0 * (xin + xout + (B * (wts + D_) if store else 0)))
+            if store:
+                add("conv_weighted_sum", 2.0 * B * (wts + D_), 4.0 * (B * (wts + D_) + wts + D_))
+            else:
+                add("conv_clipped_sum", fl, 4.0 * (xin + xout + wts))
         elif k == "maxpool2d":
             n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]
             add("maxpool_fwd", 0.0, 4.0 * n_in + 5.0 * n_out)
@@ -92,9 +101,14 @@ def label_work(m, B):
             add("lstm_xproj", 2.0 * B * T * Din * G, 4.0 * (B * T * G + Din * G))
             add("lstm_fwd", 2.0 * B * T * H * G, 4.0 * B * T * (2 * G + 2 * H))
             add("lstm_bwd", 2.0 * B * T * H * G, 4.0 * B * T * (2 * G + H))
-            add("lstm_wgrad_norm", 2.0 * B * T * (Din + H) * G, 4.0 * B * T * (G + H + Din))
+            pc = (Din + H + 1) * G
+            store = T >= 128   # long sequences: per-example gradients written by the norm pass, then a weighted sum
+            add("lstm_wgrad_norm", 2.0 * B * T * (Din + H) * G, 4.0 * (B * T * (G + H + Din) + (B * pc if store else 0)))
             add("lstm_dx", 2.0 * B * T * Din * G, 4.0 * B * T * (G + Din))
-            add("lstm_clipped_sum", 2.0 * B * T * (Din + H) * G, 4.0 * B * T * (G + H + Din))
+            if store:
+                add("lstm_weighted_sum", 2.0 * B * pc, 4.0 * (B * pc + pc))
+            else:
+                add("lstm_clipped_sum", 2.0 * B * T * (Din + H) * G, 4.0 * B * T * (G + H + Din))
         cur = o
     P = W.num_params(m)
     out["finalize_noise"] = (0.0, 8.0 * P)

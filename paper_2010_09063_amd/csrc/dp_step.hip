@@ -101,7 +101,11 @@ template <class A_, class B_>
 struct ProbSqNorm : ProbBase<A_, B_> {
   static constexpr bool kReduce = true;
   float *slots; long slot_stride; int slot0;
-  DEVI float contrib(int, int, int, float v) const { return v * v; }
+  float *gstore; long gstride; // optional: example z's gradient is also written to gstore[z*gstride + m*N + n]
+  DEVI float contrib(int z, int m, int n, float v) const {
+    if (gstore) gstore[z * gstride + (long)m * this->N + n] = v;
+    return v * v;
+  }
   DEVI void store_tile(int z, int tile, float s) const { slots[(long)(slot0 + tile) * slot_stride + z] = s; }
 };
 
@@ -150,7 +154,7 @@ static const char *const kLayerLabels[] = {"dense_fwd", "dense_fwd_epilogue", "d
                                            "conv_weight_layout", "conv_fwd", "conv_wgrad_norm", "conv_bwd_data", "conv_clipped_sum",
                                            "maxpool_fwd", "maxpool_bwd", "lstm_xproj", "lstm_fwd", "lstm_bwd", "lstm_wgrad_norm",
                                            "lstm_dx", "lstm_clipped_sum", "emb_norm", "emb_gather", "emb_bucket", "emb_scatter", "fill_zero",
-                                           "seq_mean_fwd", "seq_mean_bwd", "avgpool_fwd", "avgpool_bwd", "conv_weighted_sum"};
+                                           "seq_mean_fwd", "seq_mean_bwd", "avgpool_fwd", "avgpool_bwd", "conv_weighted_sum", "lstm_weighted_sum"};
 
 struct dp_ctx {
   dp_model_desc m;
@@ -575,6 +579,14 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       if (rc == DP_OK) rc = dev_alloc(c, &l.cs, mb * l.T * l.H);
       if (l.d.kind == DP_LSTM_SEQ) l.hs = l.a; // the hidden states are the layer's output
       else if (rc == DP_OK) rc = dev_alloc(c, &l.hs, mb * l.T * l.H);
+      // long sequences: the norm contraction writes each example's gradient ([Din + H + 1][4H], which is the layer's
+      // parameter layout) and the clipped sum is a weighted sum of those rows: 8 bytes of traffic per coordinate
+      // against the 2 T flops of contracting it again
+      if (rc == DP_OK && l.T >= 128 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
+        l.gorder = GradOrder{};
+        l.gorder.flat = 2; l.gorder.n_w = l.p_count; l.gorder.D = 0;
+        rc = dev_alloc(c, &l.gst, (size_t)mb * l.p_count);
+      }
     }
   }
   if (rc == DP_OK) rc = dev_alloc(c, &c->slots, (size_t)c->max_slots * mb);
@@ -952,6 +964,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             p.a.set(lin, l.hs, c->ones, l.Din, l.H, l.T, 1);
             p.b.set(l.gates, G, (long)l.T * G); p.b.by_z = 1;
             p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
+            p.gstore = l.gst; p.gstride = l.p_count;
             GemmShape s = launch_gemm(p, B, Ln, LL("lstm_wgrad_norm"));
             slot_next += s.tiles_m * s.tiles_n;
           };
@@ -1068,6 +1081,17 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_LSTM_LAST:
       case DP_LSTM_SEQ: {
         const int G = 4 * l.H;
+        if (priv && l.gst) { // the norm pass of this step stored every example's gradient
+          int want = (int)std::min<long>(l.max_split, std::max<long>(1, 4096 / ceil_div(l.p_count, 256)));
+          const int eps = std::max(4, ceil_div(B, want));
+          nsplit = ceil_div(B, eps);
+          dim3 grid((unsigned)ceil_div(l.p_count, 256), nsplit), block(256);
+          Ln(LL("lstm_weighted_sum"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(weighted_sum_kernel, grid, block, 0, st, (const float *)l.gst, l.p_count, sc, l.part,
+                               l.p_count, l.gorder, B, eps);
+          });
+          break;
+        }
         auto run = [&](auto vt) {
           constexpr bool V = decltype(vt)::value;
           typedef ProbPartial<OpLstmIn<V>, OpKMajor<V, false>> Pb;

@@ -209,7 +209,8 @@ __global__ void avgpool2x2_bwd_kernel(const float *__restrict__ gout, const floa
 struct GradOrder {
   int C, D, KK;       // layer shape
   int NBW, WN, NW;    // tap slots per wave group, wave groups along the taps, wave groups per channel block
-  int flat;           // 1: one wave group whose lane column is the flattened (channel, tap) index
+  int flat;           // 1: one wave group whose lane column is the flattened (channel, tap) index;
+                      // 2: the rows are in the parameter layout already (n_w = their length, D = 0)
   long n_w;           // stored words before the bias
 };
 __global__ __launch_bounds__(256) void weighted_sum_kernel(const float *__restrict__ g, long gstride,
@@ -218,7 +219,9 @@ __global__ __launch_bounds__(256) void weighted_sum_kernel(const float *__restri
   const long n = (long)blockIdx.x * 256 + threadIdx.x;
   if (n >= o.n_w + o.D) return;
   long p;
-  if (n >= o.n_w) {
+  if (o.flat == 2) {
+    p = n;
+  } else if (n >= o.n_w) {
     p = (long)o.D * o.C * o.KK + (n - o.n_w);
   } else {
     const int lane = (int)(n & 63), r = (int)((n >> 6) & 15);

@@ -161,6 +161,25 @@ def test_generic_convolution_path_matches_too(monkeypatch):
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/generic")
 
 
+def test_many_examples_per_workgroup():
+    """Batches large enough that a workgroup of the convolution norm kernels walks through several examples (here
+    three): what one example's reduction leaves in LDS must not reach the next one.  16x16 planes, so the norm pass
+    also stores the per-example gradients that the clipped sum is formed from; both first-layer (flattened) and
+    32-channel-block kernels with at most 32 output channels, whose waves share a cross-wave area."""
+    m = W.model(W.image_input(3, 16, 16), [
+        W.conv2d(3, 16, 3, stride=1, pad=1, act="tanh"), W.conv2d(16, 24, 3, stride=1, pad=1, act="tanh"),
+        W.dense(24 * 16 * 16, 3)], 3)
+    x, y, theta = _case(m, 1100, seed=31)
+    ref = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
+    Cc = float(np.median(ref["norms"]))
+    ref_c = O.dp_step(m, theta, x, y, Cc, 0.0, 0)
+    out, gn = run_gpu(m, theta, x, y, Cc, 0.0, 0)
+    err = np.abs(gn / ref["norms"] - 1.0).max()
+    print(f"many examples per workgroup: rel_l2={rel_l2(out, ref_c['clipped_sum']):.3e} max norm err {err:.2e}", flush=True)
+    assert err <= 2e-5
+    assert rel_l2(out, ref_c["clipped_sum"]) <= TOL
+
+
 def test_large_vocabulary_embedding_path():
     """Vocabularies above the LDS-histogram limit take the plain-atomic bucket kernels."""
     m = W.cfg5_lstm(vocab=20000, seq_len=24, dim=20, hidden=33)
