@@ -337,6 +337,11 @@ def tiny_models():
         "tiny_conv_gram": model(image_input(3, 8, 8), [
             conv2d(3, 40, 3, stride=1, pad=1, act="relu"), conv2d(40, 100, 3, stride=1, pad=1, act="tanh"),
             avgpool2d(2, 2), conv2d(100, 70, 3, stride=1, pad=1, act="tanh"), dense(70 * 4 * 4, 3)], 3),
+        # 16x16 planes: the norm pass stores the per-example gradients and the clipped sum is a weighted sum of them;
+        # ragged channel blocks (20 and 40 input channels) in the kernels for up to 32 and up to 64 output channels
+        "tiny_conv_store": model(image_input(5, 16, 16), [
+            conv2d(5, 20, 3, stride=1, pad=1, act="tanh"), conv2d(20, 40, 3, stride=1, pad=1, act="relu"),
+            conv2d(40, 24, 3, stride=1, pad=1, act="tanh"), maxpool2d(2, 2), dense(24 * 8 * 8, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
         "tiny_emb": model(token_input(6), [embedding(7, 3), seq_mean(), dense(3, 2)], 2),
         "tiny_lstm_seq": model(token_input(5), [embedding(7, 3), lstm_seq(3, 4), seq_mean(), dense(4, 2)], 2),
