@@ -69,8 +69,9 @@ def label_work(m, B):
             # large planes: the norm pass also writes each example's gradient and the clipped sum is a weighted
             # sum of those rows (same rule as the planner, for the shapes of these workloads)
             flat = C_ * 9 <= 32 and D_ <= 32
-            store = (not gram and L["kh"] == 3 and L["kw"] == 3 and L["stride"] == 1 and Pp >= 256 and D_ <= 64
-                     and (C_ >= 16 or flat) and OW % 4 == 0 and W_ % 4 == 0)
+            direct = (L["kh"] == 3 and L["kw"] == 3 and L["stride"] == 1 and (C_ >= 16 or flat) and OW % 4 == 0
+                      and W_ % 4 == 0)
+            store = not gram and ((direct and Pp >= 256 and D_ <= 64) or (not direct and Pp >= 128))
             add("conv_wgrad_norm", 2.0 * B * Pp * Pp * (ckk + D_) if gram else fl,
                 4.0 * (xin + xout + (B * (wts + D_) if store else 0)))
             if store:

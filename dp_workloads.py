@@ -342,6 +342,10 @@ def tiny_models():
         "tiny_conv_store": model(image_input(5, 16, 16), [
             conv2d(5, 20, 3, stride=1, pad=1, act="tanh"), conv2d(20, 40, 3, stride=1, pad=1, act="relu"),
             conv2d(40, 24, 3, stride=1, pad=1, act="tanh"), maxpool2d(2, 2), dense(24 * 8 * 8, 3)], 3),
+        # a strided, non-square filter in the middle of the network (backward-data through columns + gather)
+        "tiny_conv_stride": model(image_input(2, 9, 8), [
+            conv2d(2, 3, 3, stride=1, pad=1, act="tanh"), conv2d(3, 5, 4, stride=2, pad=1, act="relu", kw=3),
+            conv2d(5, 4, 3, stride=3, pad=2, act="tanh"), dense(4 * 2 * 2, 3)], 3),
         "tiny_lstm": model(token_input(5), [embedding(7, 3), lstm_last(3, 4), dense(4, 2)], 2),
         "tiny_emb": model(token_input(6), [embedding(7, 3), seq_mean(), dense(3, 2)], 2),
         "tiny_lstm_seq": model(token_input(5), [embedding(7, 3), lstm_seq(3, 4), seq_mean(), dense(4, 2)], 2),

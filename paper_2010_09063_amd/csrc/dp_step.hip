@@ -50,6 +50,14 @@ struct ProbBiasAct : ProbBase<A_, B_> {
   DEVI void store(int, int, int m, int n, float v) const { out[(long)m * ld + n] = act_apply(act, v + bias[n]); }
 };
 
+// out[z*zstride + m*ld + n] = acc                                     (batched plain product)
+template <class A_, class B_>
+struct ProbBatchOut : ProbBase<A_, B_> {
+  static constexpr bool kReduce = false;
+  float *out; long zstride; int ld;
+  DEVI void store(int z, int, int m, int n, float v) const { out[z * zstride + (long)m * ld + n] = v; }
+};
+
 // out[m*ld + n] = acc * act'(a_prev[m*ld + n])                        (dense backward-data)
 template <class A_, class B_>
 struct ProbBwdAct : ProbBase<A_, B_> {
@@ -128,6 +136,7 @@ struct Layer {
   bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
   bool wg_ws = false; // weight gradient with specialised staging / multiplying waves (two LDS buffers)
   bool gram = false;  // per-example norm from the P x P Gram matrices (small planes)
+  float *cols = nullptr; // strided convolutions, backward-data: [maxB][C*KH*KW][OH*OW] products W^T Delta
   float *gst = nullptr; // [maxB][gorder.n_w + D] per-example gradients written by the norm pass (large planes)
   GradOrder gorder{};
   int fwd_npw = 64, bwd_npw = 64, wg_db = 1;
@@ -551,6 +560,12 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       if (rc == DP_OK && (hipMemset(l.wt_f, 0, nf * sizeof(float)) != hipSuccess ||
                           hipMemset(l.wt_b, 0, nb * sizeof(float)) != hipSuccess)) rc = DP_EHIP;
     }
+    // Strided convolutions (no direct kernel): backward-data as a plain per-example product into columns followed
+    // by a gather over the windows, instead of a contraction whose Delta operand is gathered element by element
+    // with most of the strided taps empty
+    if (rc == DP_OK && l.d.kind == DP_CONV2D && !l.dir_bwd && l.geom.S > 1 && &l != &c->L.front() &&
+        (size_t)mb * l.geom.CKK * l.geom.P <= ((size_t)1 << 28) && getenv("DP_STEP_NO_COLS") == nullptr)
+      rc = dev_alloc(c, &l.cols, (size_t)mb * l.geom.CKK * l.geom.P);
     // Large planes: the norm pass writes each example's gradient (8 bytes of traffic per coordinate, written and
     // read once) and the clipped sum becomes a weighted sum of those rows; repeating the contraction instead costs
     // 2 P flops per coordinate, which is more from P = 256 pixels on.
@@ -564,7 +579,18 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       o.NBW = l.wg_flat ? 1 : 5;
       const long cblocks = l.wg_flat ? 1 : ceil_div(l.geom.C, 32);
       o.n_w = cblocks * o.NW * o.NBW * 1024;
-      rc = dev_alloc(c, &l.gst, (size_t)mb * (o.n_w + o.D));
+      o.n_total = o.n_w + o.D;
+      rc = dev_alloc(c, &l.gst, (size_t)mb * o.n_total);
+    }
+    // the same route for convolutions on the generic contraction (other strides / filter sizes): its per-example
+    // tile is [D][C*KK + 1], the last column being the bias gradient
+    if (rc == DP_OK && l.d.kind == DP_CONV2D && !l.dir_wg && !l.gram && l.geom.P >= 128 &&
+        (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
+      GradOrder &o = l.gorder;
+      o = GradOrder{};
+      o.C = l.geom.C; o.D = l.geom.D; o.KK = l.geom.KH * l.geom.KW; o.flat = 3;
+      o.n_total = (long)o.D * (o.C * o.KK + 1);
+      rc = dev_alloc(c, &l.gst, (size_t)mb * o.n_total);
     }
     if (rc == DP_OK && emb) {
       const size_t V = l.d.vocab;
@@ -584,7 +610,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       // against the 2 T flops of contracting it again
       if (rc == DP_OK && l.T >= 128 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
         l.gorder = GradOrder{};
-        l.gorder.flat = 2; l.gorder.n_w = l.p_count; l.gorder.D = 0;
+        l.gorder.flat = 2; l.gorder.n_total = l.p_count;
         rc = dev_alloc(c, &l.gst, (size_t)mb * l.p_count);
       }
     }
@@ -881,7 +907,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgn, d0);
             a.scale = c->ones; a.out = c->slots; a.mode = 0; a.ex_per_block = epb;
             a.slot_stride = slot_stride; a.slot0 = slot_next;
-            a.gstore = l.gst; a.gstride = l.gorder.n_w + g.D; a.gbias_off = l.gorder.n_w;
+            a.gstore = l.gst; a.gstride = l.gorder.n_total; a.gbias_off = l.gorder.n_w;
             slot_next += cblocks;
             launch_conv_wgrad(Ln, LL("conv_wgrad_norm"), a, l.wg_db, l.wg_flat, l.wg_ws, ceil_div(B, epb));
           }
@@ -894,6 +920,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             p.a.set(l.g, g.P, (long)g.D * g.P);
             p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 1;
             p.slots = c->slots; p.slot_stride = slot_stride; p.slot0 = slot_next;
+            if (!l.dir_wg) { p.gstore = l.gst; p.gstride = l.gorder.n_total; } // ([D][CKK + 1] rows)
             GemmShape s = launch_gemm(p, B, Ln, LL("conv_wgrad_norm"));
             slot_next += s.tiles_m * s.tiles_n;
           };
@@ -905,6 +932,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           a.B = B; a.Cin = g.D; a.H = g.OH; a.W = g.OW; a.M = g.C; a.Mpad = (g.C + 3) & ~3; a.OH = g.H; a.OW = g.W; a.pad = 2 - g.PAD;
           a.act = prev_act; a.t = l.t_bwd;
           launch_conv_s1(Ln, LL("conv_bwd_data"), a, l.bwd_npw);
+        } else if (prev && l.cols) {
+          {
+            typedef ProbBatchOut<OpKMajor<false, false>, OpKMajor<false, false>> Pb;
+            Pb p{};
+            p.M = g.CKK; p.N = g.P; p.K = g.D;
+            p.a.set(W, g.CKK);                       // (ckk, d) = W[d*CKK + ckk]
+            p.b.set(l.g, g.P, (long)g.D * g.P);      // (p, d) of example z = Delta[z][d][p]
+            p.out = l.cols; p.zstride = (long)g.CKK * g.P; p.ld = g.P;
+            launch_gemm(p, B, Ln, LL("conv_bwd_data"));
+          }
+          const long total = (long)B * l.in_size;
+          dim3 grid = grid1d(total, 256), block(256);
+          Ln(LL("conv_bwd_data"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(conv_col2im_kernel, grid, block, 0, st, (const float *)l.cols, (const float *)prev->a,
+                               prev->g, total, g.C, g.H, g.W, g.OH, g.OW, g.KH, g.KW, g.S, g.PAD, prev_act);
+          });
         } else if (prev) {
           typedef ProbConvBwd<OpConvWeightT, OpConvDeltaGather> Pb;
           Pb p{};
@@ -1040,9 +1083,9 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_CONV2D: {
         const ConvGeom &g = l.geom;
-        if (priv && l.gst && l.dir_wg && aligned16(lin)) {
+        if (priv && l.gst && (!l.dir_wg || aligned16(lin))) {
           // the norm pass of this step stored every example's gradient: weighted sum of the rows
-          const long gstride = l.gorder.n_w + g.D;
+          const long gstride = l.gorder.n_total;
           int want = (int)std::min<long>(l.max_split, std::max<long>(1, 4096 / ceil_div(gstride, 256)));
           const int eps = std::max(4, ceil_div(B, want));
           nsplit = ceil_div(B, eps);

@@ -135,6 +135,36 @@ __global__ void maxpool2x2_bwd_kernel(const float *__restrict__ gout, const uint
   *reinterpret_cast<float2 *>(gin + o1) = r1;
 }
 
+// Backward-data of a strided convolution, second half: the first half is the per-example product
+// cols[b][(c, kh, kw)][p] = sum_d W[d][c][kh][kw] Delta[b][d][p] (a plain contraction, no gather).  Here every
+// input position sums the columns of the windows that hold it (gather form, no atomics) and applies the derivative
+// of the activation that produced the layer's input.  One thread per input element.
+__global__ void conv_col2im_kernel(const float *__restrict__ cols, const float *__restrict__ a_in,
+                                   float *__restrict__ gin, long total, int C, int H, int W, int OH, int OW, int KH,
+                                   int KW, int S, int PAD, int act) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int iw = (int)(i % W);
+  long r = i / W;
+  const int ih = (int)(r % H);
+  r /= H;
+  const int c = (int)(r % C);
+  const long b = r / C;
+  const int P = OH * OW, KK = KH * KW;
+  const float *cb = cols + ((long)b * C + c) * KK * P;
+  float acc = 0.f;
+  for (int kh = 0; kh < KH; ++kh) {
+    const int th = ih + PAD - kh;
+    if (th < 0 || th % S != 0 || th / S >= OH) continue;
+    for (int kw = 0; kw < KW; ++kw) {
+      const int tw = iw + PAD - kw;
+      if (tw < 0 || tw % S != 0 || tw / S >= OW) continue;
+      acc += cb[(long)(kh * KW + kw) * P + (th / S) * OW + tw / S];
+    }
+  }
+  gin[i] = a_in != nullptr ? acc * act_deriv_from_out(act, a_in[i]) : acc;
+}
+
 // Average pool (Appendix B, CIFAR10 network): the plain mean of a KH x KW window, no padding.  A window that
 // covers the whole plane is the global average pool.
 __global__ void avgpool_fwd_kernel(const float *__restrict__ in, float *__restrict__ out, long total, int H, int W,
@@ -210,17 +240,24 @@ struct GradOrder {
   int C, D, KK;       // layer shape
   int NBW, WN, NW;    // tap slots per wave group, wave groups along the taps, wave groups per channel block
   int flat;           // 1: one wave group whose lane column is the flattened (channel, tap) index;
-                      // 2: the rows are in the parameter layout already (n_w = their length, D = 0)
-  long n_w;           // stored words before the bias
+                      // 2: the rows are in the parameter layout already;
+                      // 3: rows are [D][C*KK + 1], the bias gradient being the last column
+  long n_w;           // flat 0 / 1: stored words before the bias
+  long n_total;       // words per stored row
 };
 __global__ __launch_bounds__(256) void weighted_sum_kernel(const float *__restrict__ g, long gstride,
                                                            const float *__restrict__ s, float *__restrict__ part,
                                                            long pstride, GradOrder o, int B, int ex_per_split) {
   const long n = (long)blockIdx.x * 256 + threadIdx.x;
-  if (n >= o.n_w + o.D) return;
+  if (n >= o.n_total) return;
   long p;
   if (o.flat == 2) {
     p = n;
+  } else if (o.flat == 3) {
+    const int ckk = o.C * o.KK;
+    const long m = n / (ckk + 1);
+    const int col = (int)(n - m * (ckk + 1));
+    p = col < ckk ? m * ckk + col : (long)o.D * ckk + m;
   } else if (n >= o.n_w) {
     p = (long)o.D * o.C * o.KK + (n - o.n_w);
   } else {
