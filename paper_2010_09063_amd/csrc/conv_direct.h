@@ -47,15 +47,23 @@ struct ConvS1Args {
 // (Dp, Cp = D, C rounded up to 4; the pad columns stay zero from the allocation) so that a
 // chunk of input channels is copied into LDS with aligned 16-byte loads in the order the
 // MFMA A operand reads it.
-__global__ void conv_weight_layout_kernel(const float *__restrict__ w, float *__restrict__ wt_f,
-                                          float *__restrict__ wt_b, int D, int C, int KK, int Dp, int Cp) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= D * C * KK) return;
-  int d = i / (C * KK), r = i - d * C * KK;
-  int c = r / KK, tap = r - c * KK;
-  float v = w[i];
-  wt_f[((long)c * KK + tap) * Dp + d] = v;
-  wt_b[((long)d * KK + (KK - 1 - tap)) * Cp + c] = v;
+// One launch covers every such layer of the model: blockIdx.y = layer, the x grid is sized for the largest one.
+#define CONV_LAYOUT_MAX 16
+struct ConvLayoutArgs {
+  int n;
+  struct { long w_off; float *wt_f, *wt_b; int D, C, Dp, Cp; } l[CONV_LAYOUT_MAX];
+};
+__global__ void conv_weight_layout_kernel(const float *__restrict__ params, const ConvLayoutArgs a) {
+  constexpr int KK = 9;
+  const auto &L = a.l[blockIdx.y];
+  const int total = L.D * L.C * KK;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const int d = i / (L.C * KK), r = i - d * L.C * KK;
+    const int c = r / KK, tap = r - c * KK;
+    const float v = params[L.w_off + i];
+    L.wt_f[((long)c * KK + tap) * L.Dp + d] = v;
+    L.wt_b[((long)d * KK + (KK - 1 - tap)) * L.Cp + c] = v;
+  }
 }
 
 #define CONV_XPLANE_MAX 448 // staged floats per channel: a thread stages at most CC*448/256 elements per chunk

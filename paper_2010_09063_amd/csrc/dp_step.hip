@@ -700,6 +700,30 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
   fa.nseg = 0;
 
   if (B > 0) {
+    // ------------------------------------------------------------ re-laid weights of the direct convolutions
+    {
+      ConvLayoutArgs la{};
+      int biggest = 0;
+      auto flush = [&]() {
+        if (la.n == 0) return;
+        dim3 grid((unsigned)std::min(64, ceil_div(biggest, 256)), la.n), block(256);
+        Ln("conv_weight_layout", grid, block, [&](hipStream_t st) {
+          hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, params, la);
+        });
+        la.n = 0; biggest = 0;
+      };
+      for (int i = 0; i < nL; ++i) {
+        Layer &l = c->L[i];
+        if (l.d.kind != DP_CONV2D || !(l.dir_fwd || l.dir_bwd)) continue;
+        const ConvGeom &g = l.geom;
+        auto &e = la.l[la.n++];
+        e.w_off = l.p_off; e.wt_f = l.wt_f; e.wt_b = l.wt_b; e.D = g.D; e.C = g.C;
+        e.Dp = (g.D + 3) & ~3; e.Cp = (g.C + 3) & ~3;
+        biggest = std::max(biggest, g.D * g.CKK);
+        if (la.n == CONV_LAYOUT_MAX) flush();
+      }
+      flush();
+    }
     // ------------------------------------------------------------ forward
     const float *in = (const float *)x;
     for (int i = 0; i < nL; ++i) {
@@ -745,15 +769,6 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
                             OpKMajor<true, false>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
       } break;
       case DP_CONV2D: {
-        if (l.dir_fwd || l.dir_bwd) {
-          const ConvGeom &g = l.geom;
-          const int n = g.D * g.CKK;
-          dim3 grid = grid1d(n, 256), block(256);
-          Ln(LL("conv_weight_layout"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, W, l.wt_f, l.wt_b, g.D, g.C, 9,
-                               (g.D + 3) & ~3, (g.C + 3) & ~3);
-          });
-        }
         if (l.dir_fwd) {
           const ConvGeom &g = l.geom;
           ConvS1Args a{};
