@@ -79,7 +79,7 @@ __global__ void conv_weight_layout_kernel(const float *__restrict__ params, cons
 // one pointer per output row with a lane offset per pixel.
 // (the waves-per-SIMD ceiling keeps the compiler from spilling the prefetched tiles to reach a higher occupancy)
 template <int KH, int KW, int DT, int NPW, int CC>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (DT * NPW <= 32 * 64 ? 3 : 2))))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DT * NPW <= 32 * 64 ? 4 : 1), (DT * NPW <= 32 * 64 ? 4 : 2))))
 void conv_s1_kernel(const ConvS1Args a) {
   constexpr int KK = KH * KW, DB = DT / 32, PB = NPW / 32;
   constexpr int XP = (CONV_XPLANE_MAX + 255) / 256; // staged positions per thread within a channel plane
