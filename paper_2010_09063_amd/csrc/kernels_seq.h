@@ -308,26 +308,38 @@ __global__ __launch_bounds__(1024) void emb_count_kernel(const int *__restrict__
 // cursor[v] is reset to 0 for the fill pass.
 __global__ __launch_bounds__(1024) void emb_scan_kernel(const int *__restrict__ count, int *__restrict__ start,
                                                          int *__restrict__ chunk0, int *__restrict__ cursor, int V) {
-  __shared__ int sa[1024], sb[1024];
-  const int tid = threadIdx.x;
+  __shared__ int wa[16], wb[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per = (V + 1023) / 1024;
   const int lo = min(V, tid * per), hi = min(V, lo + per);
   int a = 0, b = 0;
   for (int v = lo; v < hi; ++v) { a += count[v]; b += (count[v] + EMB_CH - 1) / EMB_CH; }
-  sa[tid] = a; sb[tid] = b;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int xa = tid >= o ? sa[tid - o] : 0, xb = tid >= o ? sb[tid - o] : 0;
-    __syncthreads();
-    sa[tid] += xa; sb[tid] += xb;
-    __syncthreads();
+  // inclusive scan of the 1024 range totals: shuffles inside a wave, then the 16 wave totals
+  int ia = a, ib = b;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int xa = __shfl_up(ia, o, 64), xb = __shfl_up(ib, o, 64);
+    if (lane >= o) { ia += xa; ib += xb; }
   }
-  int ra = sa[tid] - a, rb = sb[tid] - b; // exclusive prefix of this thread's range
+  if (lane == 63) { wa[wave] = ia; wb[wave] = ib; }
+  __syncthreads();
+  if (wave == 0) {
+    int ta = lane < 16 ? wa[lane] : 0, tb = lane < 16 ? wb[lane] : 0;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const int xa = __shfl_up(ta, o, 64), xb = __shfl_up(tb, o, 64);
+      if (lane >= o) { ta += xa; tb += xb; }
+    }
+    if (lane < 16) { wa[lane] = ta; wb[lane] = tb; }
+  }
+  __syncthreads();
+  const int offa = wave > 0 ? wa[wave - 1] : 0, offb = wave > 0 ? wb[wave - 1] : 0;
+  int ra = offa + ia - a, rb = offb + ib - b; // exclusive prefix of this thread's range
   for (int v = lo; v < hi; ++v) {
     start[v] = ra; chunk0[v] = rb; cursor[v] = 0;
     ra += count[v]; rb += (count[v] + EMB_CH - 1) / EMB_CH;
   }
-  if (tid == 1023) { start[V] = sa[1023]; chunk0[V] = sb[1023]; }
+  if (tid == 1023) { start[V] = wa[15]; chunk0[V] = wb[15]; }
 }
 
 // list[start[v] + rank] = step index, rank unique within the bucket: the workgroup reserves a
