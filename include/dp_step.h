@@ -7,11 +7,16 @@
  *   2(b) clip: g_i <- g_i * min(1, C / ||g_i||_2), one L2 norm over all parameters;
  *   3    sum the clipped gradients over the batch and add N(0, sigma^2 C^2 I).
  * Drawing the minibatch (item 1) and the parameter update (item 4) stay with the
- * caller.  The per-example gradients are never written out: dense layers use
- * the norm identity ||a (x) delta|| = ||a|| ||delta|| (Section 1, the
- * fully-connected per-example norm trick), convolution / recurrent layers
- * contract each example's activations with its backprops tile by tile and keep
- * only the squared norm; the clipped sum is the contraction A^T diag(s) Delta.
+ * caller.  The per-example gradients never leave the library and are mostly
+ * never formed: dense layers use the norm identity ||a (x) delta|| = ||a|| ||delta||
+ * (Section 1, the fully-connected per-example norm trick), convolutions on small
+ * planes take the norm from Gram matrices, the other convolution / recurrent
+ * layers contract each example's activations with its backprops tile by tile
+ * and reduce the squares in the kernel; the clipped sum is the contraction
+ * A^T diag(s) Delta.  Only where writing and re-reading an example's gradient is
+ * cheaper than contracting it again (large planes, long sequences) does the
+ * workspace hold a [batch][layer parameters] block, summed with the clip
+ * factors afterwards.
  *
  * Pointers marked "device" are HIP device memory owned by the caller (the
  * library never frees them and keeps no reference after the call's stream

@@ -180,6 +180,37 @@ def test_many_examples_per_workgroup():
     assert rel_l2(out, ref_c["clipped_sum"]) <= TOL
 
 
+def test_recompute_routes_match_too(monkeypatch):
+    """With the Gram norms, the stored-gradient route and the column route of strided backward-data switched off,
+    the library takes the routes it otherwise keeps for shapes those do not cover (direct per-example contraction
+    for the norm, a second contraction for the clipped sum, the gathering backward-data contraction)."""
+    monkeypatch.setenv("DP_STEP_NO_GRAM", "1")
+    monkeypatch.setenv("DP_STEP_NO_GSTORE", "1")
+    monkeypatch.setenv("DP_STEP_NO_COLS", "1")
+    for name, batch in (("tiny_conv_gram", 9), ("tiny_conv_store", 6), ("tiny_conv_stride", 11), ("tiny_lstm_seq", 5)):
+        m = TINY[name]
+        x, y, theta = _case(m, batch, seed=41, scale=4.0 if m["input"]["kind"] == "tokens" else 1.0)
+        _check_all_regimes(m, x, y, theta, f"{name}/recompute")
+    wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/recompute")
+    m = W.paper_lstm(vocab=300, seq_len=140, dim=20, hidden=24)  # 140 steps: above the stored-gradient threshold
+    rng = np.random.default_rng(9)
+    x, y = W.make_inputs(m, 4, rng)
+    theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
+    _check_all_regimes(m, x, y, theta, "lstm_seq/T140/recompute")
+
+
+def test_long_sequence_stored_gradients():
+    """Sequences of 128 steps and more: the LSTM norm contraction stores each example's gradient and the clipped sum
+    is a weighted sum of the rows (both LSTM variants)."""
+    rng = np.random.default_rng(10)
+    for build in (W.paper_lstm, W.cfg5_lstm):
+        m = build(vocab=300, seq_len=140, dim=20, hidden=24)
+        x, y = W.make_inputs(m, 7, rng)
+        theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
+        _check_all_regimes(m, x, y, theta, f"{build.__name__}/T140")
+
+
 def test_large_vocabulary_embedding_path():
     """Vocabularies above the LDS-histogram limit take the plain-atomic bucket kernels."""
     m = W.cfg5_lstm(vocab=20000, seq_len=24, dim=20, hidden=33)
@@ -189,9 +220,10 @@ def test_large_vocabulary_embedding_path():
     _check_all_regimes(m, x, y, theta, "lstm/V20000/H33")
 
 
+@pytest.mark.parametrize("build", [W.cfg5_lstm, W.paper_lstm], ids=["last", "seq"])
 @pytest.mark.parametrize("hidden", [7, 64, 128])
-def test_lstm_hidden_sizes(hidden):
-    m = W.cfg5_lstm(vocab=50, seq_len=9, dim=12, hidden=hidden)
+def test_lstm_hidden_sizes(hidden, build):
+    m = build(vocab=50, seq_len=9, dim=12, hidden=hidden)
     rng = np.random.default_rng(hidden)
     x, y = W.make_inputs(m, 5, rng, zipf_exponent=0.5)
     theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
