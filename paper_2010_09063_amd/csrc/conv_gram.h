@@ -34,8 +34,14 @@ struct ConvGramGeom {
   static constexpr int P = OH * OW;
   static constexpr int SP = P <= 16 ? 16 : 64; // Gram rows reserved per example
   static constexpr int NIMG = 64 / SP;
-  static constexpr int LDW = OW + 2, IMGPL = (OH + 2) * LDW;
-  static constexpr int XPL = (NIMG * IMGPL) | 1; // odd plane stride: the two k-halves of a wave hit different banks
+  // Row and image strides chosen so that the 32 Gram rows a half-wave reads in one instruction fall into 32
+  // different LDS banks: 8-wide planes, four rows of 8 at stride 24 -> banks 0-7, 24-31, 16-23, 8-15; 4-wide
+  // planes, two images of four rows of 4 at row stride 8 and image stride 52 (= 20 mod 32).  Tap offsets shift
+  // all lanes alike.  (With the natural row stride OW + 2 the kernel measured more bank-conflict cycles than
+  // LDS instructions.)
+  static constexpr int LDW = OW == 8 ? 24 : (OW == 4 ? 8 : OW + 2);
+  static constexpr int IMGPL = (OH + 2) * LDW + (OW == 4 ? 4 : 0);
+  static constexpr int XPL = (NIMG * IMGPL) | 1; // odd plane stride (the two k-halves of a wave are separate passes)
   static constexpr int CH = 32;                  // planes per staged chunk
   static constexpr int WQ = OW / 4;
   static constexpr int ITEMS = CH * NIMG * OH * WQ; // float4 items per chunk
