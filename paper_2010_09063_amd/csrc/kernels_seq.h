@@ -1,17 +1,16 @@
 // Sequence kernels: the LSTM recurrence (forward and back-propagation through
 // time) and the embedding layer's per-example norm / clipped scatter-add.
 //
-// The recurrence is a chain of T dependent (examples x H)*(H x 4H) products; per
-// step it is far too small for a tiled contraction, and examples are
-// independent.  Each workgroup of LSTM_THREADS threads therefore owns one example for the
-// whole sequence and keeps W_hh in registers (one gate column per thread forward, one gate's
-// quarter of a row per thread backward), so a step costs no weight traffic at all: only the
-// hidden state goes through LDS (broadcast reads).  A step is a chain of dependent phases, so
-// what bounds it is latency: eight waves per example (two per SIMD) overlap each other's LDS
-// reads, and every global load is issued a whole step before its value is used.  The input projection
-// x_t W_ih + b and the input / weight gradients are hoisted out of the loop into
-// the tiled MFMA contraction.  The [B, T, 4H] buffer is reused in place: input
-// projection -> activated gates (forward) -> gate gradients (backward).
+// The recurrence is a chain of T dependent (examples x H)*(H x 4H) products; per step it is far too small for a
+// tiled contraction, and examples are independent.  Each workgroup of LSTM_THREADS threads therefore owns one
+// example for the whole sequence and keeps W_hh in registers (forward: a quarter of the rows for the four gate
+// columns of one hidden unit per thread, summed over a quad of lanes with DPP moves; backward: one gate's part
+// of a row per thread), so a step costs no weight traffic at all: only the hidden state goes through LDS
+// (broadcast reads).  A step is a chain of dependent phases, so what bounds it is latency: eight waves per
+// example (two per SIMD) overlap each other's LDS reads, and every global load is issued a whole step before its
+// value is used.  The input projection x_t W_ih + b and the input / weight gradients are hoisted out of the loop
+// into the tiled MFMA contraction.  The [B, T, 4H] buffer is reused in place: input projection -> activated
+// gates (forward) -> gate gradients (backward).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -79,76 +78,105 @@ __device__ __forceinline__ float lane_ld(const float *base, unsigned byte_off) {
   return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + byte_off);
 }
 
+// Quad-lane helpers: the four lanes 4u .. 4u+3 exchange values with DPP moves (no LDS, no barrier).
+__device__ __forceinline__ float quad_xor1(float v) { // lanes swap within pairs: quad_perm [1,0,3,2]
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_xor2(float v) { // pairs swap: quad_perm [2,3,0,1]
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+}
+template <int Q>
+__device__ __forceinline__ float quad_bcast(float v) { // every lane of the quad gets lane Q's value
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), Q * 0x55, 0xF, 0xF, true));
+}
+
 // Forward.  gates: in  x_t W_ih + b for every (b, t); out activated i, f, g, o.
-// hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T (null: not wanted).
-// One workgroup per example; thread j < 4H owns column j of W_hh (H <= 128, HP = H rounded up to 4).
+// hs, cs: [B, T, H] hidden and cell states; hlast [B, H] = h_T (null: not wanted).  H <= 128, HP >= H.
+// Thread (u = tid / 4, q = tid % 4) belongs to hidden unit u and holds, for all four gates
+// of that unit, the quarter q of the rows of W_hh (k in [q*QL, q*QL + QL)).  A step is then: quarter product (QL
+// broadcast words of h from LDS instead of all H), sum over the quad with two DPP exchanges per gate, lane q
+// activates and stores gate q, the quad shares the four activated gates, every lane updates the unit's cell
+// state, lane 0 publishes h.  h is double-buffered in LDS, so ONE barrier per step suffices: a step reads one
+// buffer and writes the other, and every wave has finished reading a buffer before the barrier after which it is
+// written again.
 template <int HP>
 __global__ __launch_bounds__(LSTM_THREADS) void lstm_fwd_kernel(float *__restrict__ gates, const float *__restrict__ Whh,
-                                                                 float *__restrict__ hs, float *__restrict__ cs,
-                                                                 float *__restrict__ hlast, int B, int T, int H) {
-  __shared__ __attribute__((aligned(16))) float h_s[HP];
-  __shared__ float gact[4 * HP];
+                                                                      float *__restrict__ hs, float *__restrict__ cs,
+                                                                      float *__restrict__ hlast, int B, int T, int H) {
+  constexpr int QL = (HP + 3) / 4;        // rows of W_hh per quarter
+  constexpr int QLP = (QL + 3) & ~3;      // the quarter's stride in LDS (16-byte aligned)
+  __shared__ __attribute__((aligned(16))) float h_s[2][4 * QLP];
   const int tid = threadIdx.x;
   const int b = blockIdx.x; // the grid is exactly B workgroups
   const int G = 4 * H;
-  const bool col_thread = tid < G;
-  const int col = col_thread ? tid : 0;
-  float w[HP];
+  const int u = tid >> 2, q = tid & 3;
+  const bool unit_ok = u < H;
+  const int ul = unit_ok ? u : 0;
+  float w[4][QL];
 #pragma unroll
-  for (int k = 0; k < HP; ++k) w[k] = (col_thread && k < H) ? Whh[(long)k * G + col] : 0.f;
-  for (int i = tid; i < HP; i += LSTM_THREADS) h_s[i] = 0.f;
-  const bool upd_thread = tid < H;
-  const int ur = upd_thread ? tid : 0;
-  const bool is_tanh = col >= 2 * H && col < 3 * H; // columns [0,H) i, [H,2H) f, [2H,3H) g, [3H,4H) o
+  for (int g = 0; g < 4; ++g)
+#pragma unroll
+    for (int i = 0; i < QL; ++i) {
+      const int k = q * QL + i;
+      w[g][i] = (unit_ok && k < H) ? Whh[(long)k * G + g * H + ul] : 0.f;
+    }
+  for (int i = tid; i < 2 * 4 * QLP; i += LSTM_THREADS) (&h_s[0][0])[i] = 0.f;
   float c_reg = 0.f;
-  const unsigned colb = 4u * col, urb = 4u * ur;
+  const unsigned colb = 4u * (q * H + ul), ub = 4u * ul;
+  const int hpos = (ul / QL) * QLP + ul % QL; // where unit u's h sits in a buffer
   float *const grow0 = gates + (long)b * T * G;
   float *const hrow0 = hs + (long)b * T * H, *const crow0 = cs + (long)b * T * H;
-  // the weight loads end here: a wait that the compiler places at their first use would sit inside the loop
-  // and hold every step until that step's own stores had drained
-  __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0), other counters untouched
+  __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the weight loads end here, not at their first use inside the loop
   __syncthreads();
-  // One step.  xcur: this step's input projection, loaded one step earlier; xnext receives the next step's (row
-  // clamped at the last step), so its latency hides behind a whole step.  The caller alternates two registers:
-  // a loaded value copied into a loop-carried variable would be waited for at the copy.
-  auto step = [&](const int t, const float xcur, float &xnext) {
-    // (lane offsets re-materialised inside the loop: hoisted out of it they would be widened to 64 bits)
-    unsigned colx = colb, urx = urb;
-    asm volatile("" : "+v"(colx), "+v"(urx));
+  auto step = [&](const int t, const float xcur, float &xnext, const float *hin, float *hout) {
+    unsigned colx = colb, ux = ub; // (re-materialised inside the loop: hoisted, they would be widened to 64 bits)
+    asm volatile("" : "+v"(colx), "+v"(ux));
     xnext = lane_ld(grow0 + (long)min(t + 1, T - 1) * G, colx);
-    // h_0 = 0 sits in h_s at the first step, so every step runs the same product
-    float acc0 = 0.f, acc1 = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const float *hq = hin + q * QLP;
 #pragma unroll
-    for (int k = 0; k < HP; k += 4) {
-      const float4 h4 = *reinterpret_cast<const float4 *>(&h_s[k]);
-      acc0 = fmaf(h4.x, w[k], acc0); acc1 = fmaf(h4.y, w[k + 1], acc1);
-      acc0 = fmaf(h4.z, w[k + 2], acc0); acc1 = fmaf(h4.w, w[k + 3], acc1);
+    for (int i = 0; i + 4 <= QL; i += 4) {
+      const float4 h4 = *reinterpret_cast<const float4 *>(hq + i);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        acc[g] = fmaf(h4.x, w[g][i], acc[g]); acc[g] = fmaf(h4.y, w[g][i + 1], acc[g]);
+        acc[g] = fmaf(h4.z, w[g][i + 2], acc[g]); acc[g] = fmaf(h4.w, w[g][i + 3], acc[g]);
+      }
     }
-    const float pre = (acc0 + acc1) + xcur;
-    const float v = is_tanh ? fast_tanh(pre) : sigmoidf_(pre);
-    if (col_thread) {
-      gact[col] = v;
-      lane_at(grow0 + (long)t * G, colx) = v;
+#pragma unroll
+    for (int i = QL & ~3; i < QL; ++i) {
+      const float hv = hq[i];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) acc[g] = fmaf(hv, w[g][i], acc[g]);
     }
-    __syncthreads();
-    if (upd_thread) {
-      const float gi = gact[ur], gf = gact[H + ur], gg = gact[2 * H + ur], go = gact[3 * H + ur];
-      c_reg = gf * c_reg + gi * gg;
-      const float h = go * fast_tanh(c_reg);
-      h_s[ur] = h;
-      lane_at(hrow0 + (long)t * H, urx) = h;
-      lane_at(crow0 + (long)t * H, urx) = c_reg;
-      if (hlast != nullptr && t == T - 1) lane_at(hlast + (long)b * H, urx) = h;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      acc[g] += quad_xor1(acc[g]);
+      acc[g] += quad_xor2(acc[g]);
+    }
+    // lane q activates gate q (order i, f, g, o: gate 2 is the tanh one)
+    const float mine = q == 0 ? acc[0] : (q == 1 ? acc[1] : (q == 2 ? acc[2] : acc[3]));
+    const float pre = mine + xcur;
+    const float v = q == 2 ? fast_tanh(pre) : sigmoidf_(pre);
+    if (unit_ok) lane_at(grow0 + (long)t * G, colx) = v;
+    const float gi = quad_bcast<0>(v), gf = quad_bcast<1>(v), gg = quad_bcast<2>(v), go = quad_bcast<3>(v);
+    c_reg = gf * c_reg + gi * gg;
+    const float h = go * fast_tanh(c_reg);
+    if (unit_ok && q == 0) {
+      hout[hpos] = h;
+      lane_at(hrow0 + (long)t * H, ux) = h;
+      lane_at(crow0 + (long)t * H, ux) = c_reg;
+      if (hlast != nullptr && t == T - 1) lane_at(hlast + (long)b * H, ux) = h;
     }
     __syncthreads();
   };
   float xa = lane_ld(grow0, colb), xb;
   int t = 0;
   for (; t + 1 < T; t += 2) {
-    step(t, xa, xb);
-    step(t + 1, xb, xa);
+    step(t, xa, xb, h_s[0], h_s[1]);
+    step(t + 1, xb, xa, h_s[1], h_s[0]);
   }
-  if (t < T) step(t, xa, xb);
+  if (t < T) step(t, xa, xb, h_s[0], h_s[1]);
 }
 
 // Back-propagation through time.  gates: in activated gates, out d(loss)/d(gate pre-activations).
