@@ -134,6 +134,20 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def per_call_ms(fn, stream, calls):
+    """Each call timed on its own with a pair of events on the library's stream: (median, p10, p90) in ms."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(calls)]
+    for i, (e0, e1) in enumerate(ev):
+        e0.record(stream)
+        fn(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    t = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    pick = lambda q: t[min(len(t) - 1, int(q * len(t)))]
+    return pick(0.5), pick(0.1), pick(0.9)
+
+
 def run_workload(name, steps, warmup, profile, batch=None):
     import torch
     from paper_2010_09063_amd import DpStep
@@ -154,6 +168,8 @@ def run_workload(name, steps, warmup, profile, batch=None):
                examples_per_s=B / (ms_priv * 1e-3), ratio=ms_priv / ms_np, workspace_mb=st.workspace_bytes / 2**20,
                tflops=step_flops(m, B) / (ms_priv * 1e-3) / 1e12)
     if profile:
+        med, p10, p90 = per_call_ms(lambda i: st.dp_step(tp, tx, ty, B, Cc, sigma, i, out), st.stream, max(steps, 100))
+        res["per_call_ms"] = dict(median=med, p10=p10, p90=p90, calls=max(steps, 100))
         # the same K steps again with every kernel launch bracketed by HIP events on the library's stream
         st.dp_step_profile(True)
         ms_prof = time_steps(lambda i: st.dp_step(tp, tx, ty, B, Cc, sigma, i, out), steps, 0)
@@ -307,6 +323,7 @@ def main():
         "config": {"workload": a.workload, "batch": res["batch"], "params": res["params"], "C": wl["C"],
                    "sigma": wl["sigma"], "inputs": "resident in HBM"},
         "nonprivate_ms_per_step": res["ms_nonprivate"], "private_over_nonprivate": res["ratio"],
+        "per_call_ms": {k: (round(v, 4) if isinstance(v, float) else v) for k, v in res.get("per_call_ms", {}).items()},
         "roofline": roof,
         "cpu_baseline": cpu,
         "kernels": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()

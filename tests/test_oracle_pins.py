@@ -338,6 +338,29 @@ def test_global_average_pool_closed_form():
     assert np.allclose(g[12:16], delta, rtol=1e-12, atol=1e-15)
 
 
+def test_conv_norm_from_gram_matrices():
+    """Squared norm of a convolution's per-example gradient from two P x P Gram matrices:
+    ||sum_p delta_p (x) patch_p||^2 + ||sum_p delta_p||^2 = sum_{p,q} (delta_p . delta_q)(patch_p . patch_q + 1).
+    With one 3x3 / pad-1 convolution under a global average pool, delta_p = (softmax - onehot) / P for every
+    pixel, so the right-hand side needs only numpy's im2col of the input."""
+    Cin, D, Hh = 3, 4, 4
+    m = W.model(W.image_input(Cin, Hh, Hh), [W.conv2d(Cin, D, 3, stride=1, pad=1), W.avgpool2d(Hh, Hh)], D)
+    rng = np.random.default_rng(12)
+    theta = W.init_params(m, rng, bias_scale=0.3).astype(np.float64)
+    x = rng.standard_normal((Cin, Hh, Hh)).astype(np.float32)
+    _, g, _ = O.example_grad(m, theta, x, 1)
+    xp = np.pad(x.astype(np.float64), ((0, 0), (1, 1), (1, 1)))
+    patches = np.stack([xp[:, i:i + 3, j:j + 3].reshape(-1) for i in range(Hh) for j in range(Hh)])  # [P, 9C]
+    Wc, b = theta[:D * Cin * 9].reshape(D, Cin * 9), theta[D * Cin * 9:]
+    z = (patches @ Wc.T + b).mean(axis=0)
+    p = np.exp(z - z.max()); p /= p.sum()
+    delta = np.tile((p - np.eye(D)[1]) / (Hh * Hh), (Hh * Hh, 1))                                      # [P, D]
+    Gx, Gd = patches @ patches.T, delta @ delta.T
+    assert np.isclose((g ** 2).sum(), (Gd * (Gx + 1.0)).sum(), rtol=1e-12)
+    # and the gradient itself, for good measure
+    assert np.allclose(g[:D * Cin * 9].reshape(D, Cin * 9), delta.T @ patches, rtol=1e-11, atol=1e-14)
+
+
 def test_average_pool_spreads_the_gradient_evenly():
     """An average pool with window k and stride k followed by a dense layer: every input pixel of a window gets
     1/k^2 of that window's gradient, so the first layer's bias gradient (sum over pixels of the backpropagated
