@@ -699,6 +699,9 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
   FinalizeArgs fa;
   fa.nseg = 0;
 
+  // the network ends in a dense layer of at most 64 classes: its bias, the loss gradient and its norm share a launch
+  const bool fused_head = c->L[nL - 1].d.kind == DP_DENSE && c->L[nL - 1].d.out_features <= 64;
+  int head_ns = 0; // forward split-K partials of the last layer still to be summed (0: its output is complete)
   if (B > 0) {
     // ------------------------------------------------------------ re-laid weights of the direct convolutions
     {
@@ -746,6 +749,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           };
           vec_dispatch(OpRowMajor<true>::can_vec(in, l.d.in_features, 0, l.d.in_features) &&
                               OpKMajor<true, false>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
+          if (i == nL - 1 && fused_head) { head_ns = ns; break; } // bias + loss gradient + norm in one launch below
           const long total = (long)B * l.out_size;
           dim3 grid = grid1d(total, 256), block(256);
           const float *bias = W + (long)l.d.in_features * l.d.out_features;
@@ -854,7 +858,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       in = l.a;
     }
     // ------------------------------------------------------------ loss gradient
-    {
+    if (fused_head) {
+      // the last dense layer's bias, the loss gradient and that layer's norm (the first slot of the backward
+      // pass) in one launch, one wave per example
+      Layer &l = c->L[nL - 1];
+      const float *Wl = params + l.p_off;
+      const float *lin = nL > 1 ? c->L[nL - 2].a : (const float *)x;
+      float *slot = priv ? c->slots + (long)slot_next * slot_stride : nullptr;
+      if (priv) slot_next += 1;
+      dim3 grid = grid1d((long)B * 64, 256), block(256);
+      Ln("logits_loss_norm", grid, block, [&](hipStream_t st) {
+        hipLaunchKernelGGL(logits_loss_norm_kernel, grid, block, 0, st,
+                           head_ns > 0 ? (const float *)l.fpart : (const float *)nullptr, head_ns,
+                           (long)c->maxB * l.out_size, Wl + (long)l.d.in_features * l.d.out_features, (const int *)y, lin,
+                           l.d.in_features, l.a, l.g, slot, B, l.d.out_features);
+      });
+    } else {
       Layer &l = c->L[nL - 1];
       dim3 grid = grid1d(B, 128), block(128);
       Ln("softmax_xent_grad", grid, block, [&](hipStream_t st) {
@@ -871,7 +890,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       const int prev_act = (prev && (prev->d.kind == DP_DENSE || prev->d.kind == DP_CONV2D)) ? prev->d.act : DP_ACT_NONE;
       switch (l.d.kind) {
       case DP_DENSE: {
-        if (priv) {
+        if (priv && !(i == nL - 1 && fused_head)) {
           dim3 grid = grid1d((long)B * 64, 256), block(256);
           float *slot = c->slots + (long)slot_next * slot_stride;
           slot_next += 1;

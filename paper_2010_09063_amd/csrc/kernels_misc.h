@@ -329,6 +329,49 @@ __global__ void bias_act_reduce_kernel(const float *__restrict__ part, int nspli
   out[i] = act_apply(act, a0 + a1 + bias[i % N]);
 }
 
+// Last dense layer (no activation, at most 64 classes), one wave per example, three small launches in one:
+//   logits   z[n] = sum of the forward split-K partials + bias[n]   (part == nullptr: z is already in a)
+//   loss     g = softmax(z) - onehot(y)                             (Section 1, item 2a: the example's own loss)
+//   norm     slot[b] = (||a_in||^2 + 1) ||g||^2                     (dense identity; slot == nullptr: skipped)
+__global__ __launch_bounds__(256) void logits_loss_norm_kernel(const float *__restrict__ part, int nsplit, long stride,
+                                                               const float *__restrict__ bias, const int *__restrict__ y,
+                                                               const float *__restrict__ a_in, int d_in,
+                                                               float *__restrict__ a, float *__restrict__ g,
+                                                               float *__restrict__ slot, int B, int N) {
+  const int b = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  if (b >= B) return;
+  const bool on = lane < N;
+  float z = 0.f;
+  if (on) {
+    const long i = (long)b * N + lane;
+    if (part != nullptr) {
+      float a0 = 0.f, a1 = 0.f;
+      int s = 0;
+      for (; s + 1 < nsplit; s += 2) { a0 += part[s * stride + i]; a1 += part[(s + 1) * stride + i]; }
+      if (s < nsplit) a0 += part[s * stride + i];
+      z = a0 + a1 + bias[lane];
+      a[i] = z;
+    } else {
+      z = a[i];
+    }
+  }
+  float mx = on ? z : -INFINITY;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  const float e = on ? expf(z - mx) : 0.f;
+  float se = e;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+  const float gv = on ? e * (1.f / se) - (lane == y[b] ? 1.f : 0.f) : 0.f;
+  if (on) g[(long)b * N + lane] = gv;
+  if (slot == nullptr) return;
+  float sd = gv * gv, sa = 0.f;
+  for (int k = lane; k < d_in; k += 64) { const float v = a_in[(long)b * d_in + k]; sa += v * v; }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { sd += __shfl_xor(sd, o, 64); sa += __shfl_xor(sa, o, 64); }
+  if (lane == 0) slot[b] = (sa + 1.f) * sd;
+}
+
 __global__ void fill_zero_kernel(float *__restrict__ p, long n) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0.f;
