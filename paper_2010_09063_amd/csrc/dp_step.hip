@@ -866,12 +866,14 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       const float *lin = nL > 1 ? c->L[nL - 2].a : (const float *)x;
       float *slot = priv ? c->slots + (long)slot_next * slot_stride : nullptr;
       if (priv) slot_next += 1;
+      const bool single_layer = priv && nL == 1; // this slot is the whole norm: the clip factors come along
       dim3 grid = grid1d((long)B * 64, 256), block(256);
       Ln("logits_loss_norm", grid, block, [&](hipStream_t st) {
         hipLaunchKernelGGL(logits_loss_norm_kernel, grid, block, 0, st,
                            head_ns > 0 ? (const float *)l.fpart : (const float *)nullptr, head_ns,
                            (long)c->maxB * l.out_size, Wl + (long)l.d.in_features * l.d.out_features, (const int *)y, lin,
-                           l.d.in_features, l.a, l.g, slot, B, l.d.out_features);
+                           l.d.in_features, l.a, l.g, slot, single_layer ? c->norms : (float *)nullptr,
+                           single_layer ? c->s : (float *)nullptr, C, B, l.d.out_features);
       });
     } else {
       Layer &l = c->L[nL - 1];
@@ -1085,7 +1087,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       }
     }
     // ------------------------------------------------------------ clip factors
-    if (priv) {
+    if (priv && !(fused_head && nL == 1)) {
       dim3 grid = grid1d(B, 128), block(128);
       const int ns = slot_next;
       Ln("clip_factor", grid, block, [&](hipStream_t st) {

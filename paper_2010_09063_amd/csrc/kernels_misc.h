@@ -333,11 +333,14 @@ __global__ void bias_act_reduce_kernel(const float *__restrict__ part, int nspli
 //   logits   z[n] = sum of the forward split-K partials + bias[n]   (part == nullptr: z is already in a)
 //   loss     g = softmax(z) - onehot(y)                             (Section 1, item 2a: the example's own loss)
 //   norm     slot[b] = (||a_in||^2 + 1) ||g||^2                     (dense identity; slot == nullptr: skipped)
+//   clip     norms[b], s[b] as clip_factor_kernel computes them      (only when this slot is the whole norm, i.e.
+//                                                                      the model is this one layer; else null)
 __global__ __launch_bounds__(256) void logits_loss_norm_kernel(const float *__restrict__ part, int nsplit, long stride,
                                                                const float *__restrict__ bias, const int *__restrict__ y,
                                                                const float *__restrict__ a_in, int d_in,
                                                                float *__restrict__ a, float *__restrict__ g,
-                                                               float *__restrict__ slot, int B, int N) {
+                                                               float *__restrict__ slot, float *__restrict__ norms,
+                                                               float *__restrict__ s_out, float C, int B, int N) {
   const int b = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   if (b >= B) return;
   const bool on = lane < N;
@@ -369,7 +372,15 @@ __global__ __launch_bounds__(256) void logits_loss_norm_kernel(const float *__re
   for (int k = lane; k < d_in; k += 64) { const float v = a_in[(long)b * d_in + k]; sa += v * v; }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) { sd += __shfl_xor(sd, o, 64); sa += __shfl_xor(sa, o, 64); }
-  if (lane == 0) slot[b] = (sa + 1.f) * sd;
+  if (lane == 0) {
+    const float n2 = (sa + 1.f) * sd;
+    slot[b] = n2;
+    if (s_out != nullptr) {
+      const float n = sqrtf(n2);
+      norms[b] = n;
+      s_out[b] = fminf(1.f, C / n); // n == 0: C/0 = +inf -> 1
+    }
+  }
 }
 
 __global__ void fill_zero_kernel(float *__restrict__ p, long n) {
