@@ -1184,18 +1184,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         vec_dispatch(OpLstmIn<true>::can_vec(lin, l.hs, l.Din, l.H) && OpKMajor<true, false>::can_vec(l.gates, G, 0, G), run);
       } break;
       case DP_EMBEDDING: {
-        {
-          dim3 grid = grid1d(l.p_count, 256), block(256);
-          Ln(LL("fill_zero"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count);
-          });
-        }
         const long rows = (long)B * l.outC;
         const int V = l.d.vocab;
         {
-          dim3 grid = grid1d(V + 1, 256), block(256);
+          dim3 grid = grid1d(l.p_count + V + 1, 256), block(256);
           Ln(LL("fill_zero"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, (float *)l.e_count, (long)(V + 1));
+            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count, (float *)l.e_count, (long)(V + 1));
           });
         }
         {

@@ -383,9 +383,11 @@ __global__ __launch_bounds__(256) void logits_loss_norm_kernel(const float *__re
   }
 }
 
-__global__ void fill_zero_kernel(float *__restrict__ p, long n) {
+// zeroes p[0:n] and q[0:m] (one launch for the two buffers the embedding's clipped sum starts from)
+__global__ void fill_zero_kernel(float *__restrict__ p, long n, float *__restrict__ q, long m) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0.f;
+  else if (i - n < m) q[i - n] = 0.f;
 }
 
 // ---------------------------------------------------------------- noise
