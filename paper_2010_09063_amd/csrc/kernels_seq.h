@@ -264,9 +264,10 @@ __global__ __launch_bounds__(LSTM_THREADS, (HP <= 100 ? 4 : 2)) void lstm_bwd_ke
 
 // Embedding layer, per-example squared norm: row v of g_i is the sum of dx_{i,t}
 // over the steps t whose token is v, so repeated tokens are added before squaring.
-// One workgroup per example: bitonic sort of (token, t) keys in LDS, then every
-// thread walks the sorted steps for its embedding coordinate(s).
+// One workgroup per example: bitonic sort of (token, t) keys in LDS, then a chunked
+// segmented sum over the sorted steps.
 #define EMB_TMAX 1024
+#define EMB_NC 16 // chunks of the sorted steps
 __global__ __launch_bounds__(256) void emb_norm_kernel(const int *__restrict__ tok, const float *__restrict__ dx,
                                                         float *__restrict__ slot, int T, int TP, int D) {
   __shared__ uint32_t key[EMB_TMAX];
@@ -286,17 +287,57 @@ __global__ __launch_bounds__(256) void emb_norm_kernel(const int *__restrict__ t
       }
       __syncthreads();
     }
+  // Segmented sum over the sorted steps, in a fixed order.  The T steps are cut into EMB_NC chunks; a work item
+  // (coordinate e, chunk c) walks its chunk: runs of one token that lie inside the chunk are squared at once, the
+  // part before the chunk's first run start (lead) and after its last one (tail) are left for the pass below,
+  // where one thread per coordinate stitches the chunks together.  (A single walk over all T steps per
+  // coordinate leaves all but D threads idle behind T dependent loads.)
+  constexpr int ET = 128;                 // coordinates per tile
+  __shared__ float lead[EMB_NC][ET], tail[EMB_NC][ET];
+  __shared__ int has_head[EMB_NC];
+  const int L = (T + EMB_NC - 1) / EMB_NC;
   float tot = 0.f;
-  for (int e = tid; e < D; e += 256) {
-    float acc = 0.f;
-    uint32_t prev = key[0] >> 10;
-    for (int p = 0; p < T; ++p) {
-      const uint32_t kk = key[p];
-      const uint32_t v = kk >> 10;
-      if (v != prev) { tot += acc * acc; acc = 0.f; prev = v; }
-      acc += dx[((long)b * T + (kk & 1023u)) * D + e];
+  for (int e0 = 0; e0 < D; e0 += ET) {
+    const int de = min(ET, D - e0);
+    for (int it = tid; it < de * EMB_NC; it += 256) {
+      const int c = it / de, e = e0 + (it - c * de);
+      const int p0 = c * L, p1 = min(T, p0 + L);
+      float acc = 0.f, ld = 0.f;
+      bool seen = false;
+      uint32_t prev = p0 > 0 && p0 < p1 ? key[p0 - 1] >> 10 : 0xFFFFFFFFu; // (no token has this value: step 0 is a head)
+      for (int pb = p0; pb < p1; pb += 8) { // eight loads in flight, then their sums in order
+        float v[8];
+        uint32_t kk[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          kk[j] = key[min(pb + j, p1 - 1)];
+          v[j] = dx[((long)b * T + (kk[j] & 1023u)) * D + e];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (pb + j < p1) {
+            const uint32_t tk = kk[j] >> 10;
+            if (tk != prev) {
+              if (seen) tot += acc * acc; else ld = acc;
+              acc = 0.f; seen = true; prev = tk;
+            }
+            acc += v[j];
+          }
+      }
+      lead[c][e - e0] = seen ? ld : acc;
+      tail[c][e - e0] = seen ? acc : 0.f;
+      if (e == e0) has_head[c] = seen;
     }
-    tot += acc * acc;
+    __syncthreads();
+    if (tid < de) {
+      float carry = 0.f;
+      for (int c = 0; c < EMB_NC; ++c) {
+        carry += lead[c][tid];
+        if (has_head[c]) { tot += carry * carry; carry = tail[c][tid]; }
+      }
+      tot += carry * carry;
+    }
+    __syncthreads();
   }
   for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o, 64);
   if ((tid & 63) == 0) red[tid >> 6] = tot;
