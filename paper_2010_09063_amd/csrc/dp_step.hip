@@ -1073,14 +1073,16 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_EMBEDDING: {
         if (priv) {
-          int TP = 2;
-          while (TP < l.outC) TP <<= 1;
           dim3 grid(B), block(256);
           float *slot = c->slots + (long)slot_next * slot_stride;
           slot_next += 1;
-          Ln(LL("emb_norm"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(emb_norm_kernel, grid, block, 0, st, (const int *)x, (const float *)l.g, slot, l.outC,
-                               TP, l.d.embed_dim);
+          Ln(LL("emb_norm"), grid, block, [&](hipStream_t st) { // keys per thread: sequence length rounded up to 256, 512 or 1024
+            if (l.outC <= 256)
+              hipLaunchKernelGGL(emb_norm_kernel<1>, grid, block, 0, st, (const int *)x, (const float *)l.g, slot, l.outC, l.d.embed_dim);
+            else if (l.outC <= 512)
+              hipLaunchKernelGGL(emb_norm_kernel<2>, grid, block, 0, st, (const int *)x, (const float *)l.g, slot, l.outC, l.d.embed_dim);
+            else
+              hipLaunchKernelGGL(emb_norm_kernel<4>, grid, block, 0, st, (const int *)x, (const float *)l.g, slot, l.outC, l.d.embed_dim);
           });
         }
       } break;

@@ -268,25 +268,60 @@ __global__ __launch_bounds__(LSTM_THREADS, (HP <= 100 ? 4 : 2)) void lstm_bwd_ke
 // segmented sum over the sorted steps.
 #define EMB_TMAX 1024
 #define EMB_NC 16 // chunks of the sorted steps
+// Bitonic sort of KPT*256 keys, element m*256 + tid in kr[m]: exchanges at distance >= 256 stay inside the thread,
+// distances 64 and 128 go through LDS (3 such passes for 256 keys), the shorter ones are wave shuffles.
+template <int KPT>
+__device__ __forceinline__ void emb_sort_keys(uint32_t (&kr)[KPT], uint32_t *key, const int tid) {
+  constexpr int N = KPT * 256;
+#pragma unroll
+  for (int k = 2; k <= N; k <<= 1) {
+#pragma unroll
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      if (j >= 256) {
+#pragma unroll
+        for (int m = 0; m < KPT; ++m) {
+          const int pm = m ^ (j >> 8);
+          if (pm > m) {
+            const bool up = (((m << 8) + tid) & k) == 0;
+            const uint32_t a = kr[m], c = kr[pm];
+            if ((a > c) == up) { kr[m] = c; kr[pm] = a; }
+          }
+        }
+      } else {
+        if (j >= 64) {
+#pragma unroll
+          for (int m = 0; m < KPT; ++m) key[(m << 8) + tid] = kr[m];
+          __syncthreads();
+        }
+#pragma unroll
+        for (int m = 0; m < KPT; ++m) {
+          const int i = (m << 8) + tid;
+          const uint32_t other = j >= 64 ? key[i ^ j] : (uint32_t)__shfl_xor((int)kr[m], j, 64);
+          const bool keep_min = ((i & j) == 0) == ((i & k) == 0);
+          kr[m] = keep_min ? min(kr[m], other) : max(kr[m], other);
+        }
+        if (j >= 64) __syncthreads();
+      }
+    }
+  }
+}
+
+template <int KPT>
 __global__ __launch_bounds__(256) void emb_norm_kernel(const int *__restrict__ tok, const float *__restrict__ dx,
-                                                        float *__restrict__ slot, int T, int TP, int D) {
+                                                        float *__restrict__ slot, int T, int D) {
   __shared__ uint32_t key[EMB_TMAX];
   __shared__ float red[4];
   const int b = blockIdx.x, tid = threadIdx.x;
-  for (int i = tid; i < TP; i += 256) key[i] = i < T ? (((uint32_t)tok[(long)b * T + i] << 10) | (uint32_t)i) : 0xFFFFFFFFu;
+  uint32_t kr[KPT];
+#pragma unroll
+  for (int m = 0; m < KPT; ++m) {
+    const int i = (m << 8) + tid;
+    kr[m] = i < T ? (((uint32_t)tok[(long)b * T + i] << 10) | (uint32_t)i) : 0xFFFFFFFFu;
+  }
+  emb_sort_keys<KPT>(kr, key, tid);
+#pragma unroll
+  for (int m = 0; m < KPT; ++m) key[(m << 8) + tid] = kr[m];
   __syncthreads();
-  for (int k = 2; k <= TP; k <<= 1)
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < TP; i += 256) {
-        int l = i ^ j;
-        if (l > i) {
-          uint32_t a = key[i], c = key[l];
-          bool up = (i & k) == 0;
-          if ((a > c) == up) { key[i] = c; key[l] = a; }
-        }
-      }
-      __syncthreads();
-    }
   // Segmented sum over the sorted steps, in a fixed order.  The T steps are cut into EMB_NC chunks; a work item
   // (coordinate e, chunk c) walks its chunk: runs of one token that lie inside the chunk are squared at once, the
   // part before the chunk's first run start (lead) and after its last one (tail) are left for the pass below,

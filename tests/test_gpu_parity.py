@@ -211,6 +211,17 @@ def test_long_sequence_stored_gradients():
         _check_all_regimes(m, x, y, theta, f"{build.__name__}/T140")
 
 
+@pytest.mark.parametrize("seq_len", [300, 700, 1024])
+def test_long_token_sequences(seq_len):
+    """Sequences above 256 and above 512 steps: the per-example sort of the embedding norm holds two or four keys
+    per thread (few distinct tokens, so every example has long runs of duplicates to add before squaring)."""
+    m = W.cfg6_embedding(vocab=37, seq_len=seq_len, dim=12)
+    rng = np.random.default_rng(seq_len)
+    x, y = W.make_inputs(m, 9, rng, zipf_exponent=0.7)
+    theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(4)
+    _check_all_regimes(m, x, y, theta, f"embedding/T{seq_len}")
+
+
 def test_large_vocabulary_embedding_path():
     """Vocabularies above the LDS-histogram limit take the plain-atomic bucket kernels."""
     m = W.cfg5_lstm(vocab=20000, seq_len=24, dim=20, hidden=33)
