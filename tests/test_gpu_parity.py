@@ -164,11 +164,12 @@ def test_generic_convolution_path_matches_too(monkeypatch):
 def test_many_examples_per_workgroup():
     """Batches large enough that a workgroup of the convolution norm kernels walks through several examples (here
     three): what one example's reduction leaves in LDS must not reach the next one.  16x16 planes, so the norm pass
-    also stores the per-example gradients that the clipped sum is formed from; both first-layer (flattened) and
-    32-channel-block kernels with at most 32 output channels, whose waves share a cross-wave area."""
+    also stores the per-example gradients that the clipped sum is formed from; the first-layer (flattened) kernel,
+    the 32-channel-block kernel with at most 32 output channels (their waves share a cross-wave area) and the one
+    for up to 64 output channels."""
     m = W.model(W.image_input(3, 16, 16), [
         W.conv2d(3, 16, 3, stride=1, pad=1, act="tanh"), W.conv2d(16, 24, 3, stride=1, pad=1, act="tanh"),
-        W.dense(24 * 16 * 16, 3)], 3)
+        W.conv2d(24, 40, 3, stride=1, pad=1, act="tanh"), W.dense(40 * 16 * 16, 3)], 3)
     x, y, theta = _case(m, 1100, seed=31)
     ref = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
     Cc = float(np.median(ref["norms"]))
