@@ -1,0 +1,244 @@
+// 3x3 / stride-1 / pad-1 convolution (forward and backward-data) by the minimal-filtering form F(2x2, 3x3):
+// every 2x2 block of outputs ("tile") is  Y = A^T [ sum_c U_c (.) V_c ] A  with  V_c = B^T d_c B  the transform of
+// the tile's 4x4 input patch and  U_c = G g_c G^T  the transform of the 3x3 filter.  The sum over input channels
+// is 16 independent contractions (one per transform component) of 16 multiplies per tile and channel instead of
+// the 36 of the direct form: the same convolution up to rounding (fp32, a few ulp more than the direct sum).
+//
+//   B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1]   G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]   A^T = [1 1 1 0; 0 1 -1 -1]
+//
+// One workgroup = 32 tiles (128 output pixels) x 32*DB output channels.  Per chunk of 8 input channels every thread
+// loads one (channel, tile) patch straight from global memory, transforms it in registers and writes its 16
+// components to LDS ([component][channel][tile], double-buffered: one barrier per chunk).  Wave w owns transform row
+// w (components 4w .. 4w+3): v_mfma_f32_32x32x2_f32 with M = output channel, N = tile, K = channel pair, the A
+// operand (transformed weights, [component][channel][Mpad] in global memory, zero rows / columns as padding) loaded
+// straight into registers one chunk ahead.  A wave therefore holds 4*DB accumulator tiles, so several workgroups
+// share a CU and hide one another's load and transform phases.  Epilogue: each wave folds its row with A (4
+// components -> 2 numbers), the four rows meet in LDS, and each wave finishes a quarter of the output channels:
+// bias + activation (forward) or the derivative of the producing activation (backward-data), 8-byte stores.
+#pragma once
+#include "gemm_tile.h"
+#include "kernels_misc.h"
+
+#define WINO_CC 8 // input channels per chunk
+
+struct ConvWinoArgs {
+  const float *x;      // input [B, Cin, H, W]
+  const float *u;      // transformed weights [16][Cpad][Mpad]; rows c >= Cin and columns m >= M are zero
+  const float *bias;   // forward: bias[M]; backward-data: null
+  const float *a_prev; // backward-data with act != 0: output of the activation whose derivative multiplies the result
+  float *out;          // [B, M, H, W]
+  int B, Cin, Cpad, H, W, M, Mpad; // Cpad: multiple of WINO_CC; Mpad: multiple of 32*DB times gridDim.y
+  int act;
+  int tw_shift, tpi_shift; // log2(W/2), log2((H/2)*(W/2)): tiles per row / per image are powers of two
+};
+
+// Weight transforms for one layer W[D][C][3][3]:
+//   uf[(comp*Cfp + c)*Dfp + d] = (G W[d][c] G^T)[comp]                 forward       (Cin = C, M = D)
+//   ub[(comp*Dbp + d)*Cbp + c] = (G flip(W[d][c]) G^T)[comp]           backward-data (Cin = D, M = C)
+// The padding rows / columns stay zero from the allocation.
+struct WinoLayoutArgs {
+  int n;
+  struct { long w_off; float *uf, *ub; int D, C, Cfp, Dfp, Dbp, Cbp; } l[16];
+};
+__global__ void wino_weight_kernel(const float *__restrict__ params, const WinoLayoutArgs a) {
+  const auto &L = a.l[blockIdx.y];
+  const int total = L.D * L.C;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const int d = i / L.C, c = i - d * L.C;
+    float g[3][3];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) g[k / 3][k % 3] = params[L.w_off + (long)i * 9 + k];
+#pragma unroll
+    for (int flip = 0; flip < 2; ++flip) {
+      float *dst = flip ? L.ub : L.uf;
+      if (dst == nullptr) continue;
+      float t[4][3]; // G g
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const float g0 = flip ? g[2][2 - j] : g[0][j], g1 = flip ? g[1][2 - j] : g[1][j], g2 = flip ? g[0][2 - j] : g[2][j];
+        t[0][j] = g0;
+        t[1][j] = 0.5f * (g0 + g1 + g2);
+        t[2][j] = 0.5f * (g0 - g1 + g2);
+        t[3][j] = g2;
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float u0 = t[r][0], u1 = 0.5f * (t[r][0] + t[r][1] + t[r][2]), u2 = 0.5f * (t[r][0] - t[r][1] + t[r][2]),
+                    u3 = t[r][2];
+        const float uu[4] = {u0, u1, u2, u3};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int comp = r * 4 + s;
+          if (flip) dst[((long)comp * L.Dbp + d) * L.Cbp + c] = uu[s];
+          else dst[((long)comp * L.Cfp + c) * L.Dfp + d] = uu[s];
+        }
+      }
+    }
+  }
+}
+
+template <int DB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DB == 1 ? 3 : 2, DB == 1 ? 3 : 2)))
+void conv_wino_kernel(const ConvWinoArgs a) {
+  constexpr int CC = WINO_CC;
+  __shared__ __attribute__((aligned(16))) float Vl[2 * 16 * CC * 32]; // [buf][comp][c][tile]; the epilogue reuses it
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = blockIdx.y * 32 * DB;
+  const int HW = a.H * a.W;
+  const int TW = 1 << a.tw_shift, TPI = 1 << a.tpi_shift;
+
+  // this lane's tile: the transform item (channel 2*wave + lk of the chunk) and the MFMA column / output tile
+  const int gt = blockIdx.x * 32 + li;
+  const int img0 = (blockIdx.x * 32) >> a.tpi_shift; // first image of the workgroup
+  const int img = gt >> a.tpi_shift, trem = gt & (TPI - 1);
+  const int ty = trem >> a.tw_shift, tx = trem & (TW - 1);
+  const bool img_ok = img < a.B;
+  const float *xblk = a.x + (long)img0 * a.Cin * HW;
+  unsigned poff[16];
+  bool pok[16];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int ih = 2 * ty - 1 + i, iw = 2 * tx - 1 + j;
+      const bool ok = img_ok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+      pok[i * 4 + j] = ok;
+      poff[i * 4 + j] = ok ? 4u * (unsigned)((img - img0) * a.Cin * HW + ih * a.W + iw) : 0u; // bytes; (0: a valid word)
+    }
+  const int cc = 2 * wave + lk;
+
+  // weights: lane (li, lk) of MFMA step (component 4*wave + jj, channel pair cp, block i) reads
+  //   u[((4*wave + jj)*Cpad + c0 + 2*cp + lk)*Mpad + m0 + 32*i + li]
+  const unsigned wlane = 4u * (unsigned)(lk * a.Mpad + li);
+  const float *ubase = a.u + ((long)(4 * wave) * a.Cpad) * a.Mpad + m0;
+
+  f32x16 acc[4][DB];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
+
+  float pr[16];
+  float wr[4][CC / 2][DB];
+  auto fetch_patch = [&](int c0) {
+    const unsigned choff = 4u * (unsigned)(min(c0 + cc, a.Cin - 1) * HW); // a channel past Cin meets zero weights
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      pr[k] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xblk) + (choff + poff[k]));
+  };
+  // (uniform pointer of the chunk + uniform row offset) + the lane's byte offset
+  auto w_ptr = [&](const float *uc, unsigned wl, int jj, int cp, int i) {
+    return reinterpret_cast<const float *>(
+        reinterpret_cast<const char *>(uc + ((long)jj * a.Cpad + 2 * cp) * a.Mpad + 32 * i) + wl);
+  };
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp)
+#pragma unroll
+      for (int i = 0; i < DB; ++i) wr[jj][cp][i] = *w_ptr(ubase, wlane, jj, cp, i);
+
+  fetch_patch(0);
+  int buf = 0;
+  for (int c0 = 0; c0 < a.Cin; c0 += CC) {
+    // transform the patch: t = B^T d (rows), v = t B (columns)
+    {
+      float d[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) d[k] = pok[k] ? pr[k] : 0.f;
+      float t[16];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        t[0 + j] = d[0 + j] - d[8 + j];
+        t[4 + j] = d[4 + j] + d[8 + j];
+        t[8 + j] = d[8 + j] - d[4 + j];
+        t[12 + j] = d[4 + j] - d[12 + j];
+      }
+      float *dst = Vl + buf * (16 * CC * 32) + cc * 32 + li;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        dst[(4 * i + 0) * CC * 32] = t[4 * i + 0] - t[4 * i + 2];
+        dst[(4 * i + 1) * CC * 32] = t[4 * i + 1] + t[4 * i + 2];
+        dst[(4 * i + 2) * CC * 32] = t[4 * i + 2] - t[4 * i + 1];
+        dst[(4 * i + 3) * CC * 32] = t[4 * i + 1] - t[4 * i + 3];
+      }
+    }
+    __syncthreads(); // the chunk's components are in place (the other buffer may still be read by slower waves)
+    // next chunk's loads (the last chunk re-reads itself: no branch around loads).  A weight register is reloaded
+    // right after the multiply that consumed it, so its latency hides behind the rest of this chunk.
+    const int cn = min(c0 + CC, a.Cpad - CC);
+    const float *un = ubase + (long)cn * a.Mpad;
+    unsigned wl = wlane;
+    asm volatile("" : "+v"(wl)); // keeps the weight addresses in the form uniform pointer + lane offset
+    fetch_patch(cn);
+    const float *vb = Vl + buf * (16 * CC * 32) + (4 * wave) * CC * 32 + lk * 32 + li;
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        const float bv = vb[(jj * CC + 2 * cp) * 32];
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+          acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[jj][cp][i], bv, acc[jj][i], 0, 0, 0);
+          wr[jj][cp][i] = *w_ptr(un, wl, jj, cp, i);
+        }
+      }
+    // instruction order: the patch loads first, then multiplies and weight reloads alternating
+    __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);
+#pragma unroll
+    for (int k = 0; k < 4 * (CC / 2); ++k) {
+      __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, DB, 0);
+    }
+    buf ^= 1;
+  }
+
+  // epilogue.  Row w of  M A:  t0 = m0 + m1 + m2,  t1 = m1 - m2 - m3;  then  Y[0][k] = T0 + T1 + T2,
+  // Y[1][k] = T1 - T2 - T3  over the four waves' rows.
+  const bool fwd = a.bias != nullptr;
+  const bool need_side = !fwd && a.act;
+  float *Tl = Vl; // [wave][k][r][lane]
+#pragma unroll
+  for (int i = 0; i < DB; ++i) {
+    __syncthreads(); // every wave is done with the LDS contents of the previous phase
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][i][r] + acc[1][i][r] + acc[2][i][r];
+      Tl[((wave * 2 + 1) * 16 + r) * 64 + lane] = acc[1][i][r] - acc[2][i][r] - acc[3][i][r];
+    }
+    __syncthreads();
+    if (!img_ok) continue;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+      if (m >= a.M) continue;
+      float T[4][2];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
+      float2 y0, y1;
+      y0.x = T[0][0] + T[1][0] + T[2][0];
+      y0.y = T[0][1] + T[1][1] + T[2][1];
+      y1.x = T[1][0] - T[2][0] - T[3][0];
+      y1.y = T[1][1] - T[2][1] - T[3][1];
+      const long o = ((long)img * a.M + m) * HW + (2 * ty) * a.W + 2 * tx;
+      if (fwd) {
+        const float bv = a.bias[m];
+        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
+        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
+      } else if (need_side) {
+        const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
+        const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + a.W);
+        y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
+        y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
+      }
+      *reinterpret_cast<float2 *>(a.out + o) = y0;
+      *reinterpret_cast<float2 *>(a.out + o + a.W) = y1;
+    }
+  }
+}

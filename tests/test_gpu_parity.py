@@ -201,6 +201,35 @@ def test_recompute_routes_match_too(monkeypatch):
     _check_all_regimes(m, x, y, theta, "lstm_seq/T140/recompute")
 
 
+def test_minimal_filtering_route(monkeypatch):
+    """Forward and backward-data of the pad-1 3x3 convolutions through the F(2x2, 3x3) kernel at sizes the oracle
+    covers element by element (the library keeps that kernel for launches that fill the chip; here it is forced):
+    4x4, 8x8 and 16x16 planes, channel counts that are no multiples of the 8-channel chunk or of the 32 / 64 output
+    channels of a workgroup, more than 64 output channels (several channel blocks), batches that end inside a
+    workgroup's 32 tiles, a 3-channel first layer.  (The full-size cases run it wherever the library selects it.)"""
+    cases = (("tiny_conv_gram", 9), ("tiny_conv_store", 6), ("tiny_conv_wide", 13), ("tiny_conv_wide", 1))
+    monkeypatch.setenv("DP_STEP_WINO_ALL", "1")
+    for name, batch in cases:
+        m = TINY[name]
+        x, y, theta = _case(m, batch, seed=43)
+        _check_all_regimes(m, x, y, theta, f"{name}/minimal-filtering")
+    wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/minimal-filtering")
+    wl = W.make_workload("paper_cifar_cnn", batch=5, seed=6, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "paper_cifar/minimal-filtering")
+    # full batch with that route switched off: the direct kernels in the launch shapes of the benchmark batch
+    monkeypatch.delenv("DP_STEP_WINO_ALL")
+    monkeypatch.setenv("DP_STEP_NO_WINO", "1")
+    wl = W.make_workload("cfg4_cifar_cnn", seed=0)
+    m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    x, y, _ = clear_pool_examples(m, theta, x, y, O.dp_step)
+    ref = O.dp_step(m, theta, x, y, wl["C"], 0.0, 0)
+    out, gn = run_gpu(m, theta, x, y, wl["C"], 0.0, 0)
+    print(f"cfg4 full batch, direct kernels: rel_l2={rel_l2(out, ref['clipped_sum']):.3e}", flush=True)
+    assert rel_l2(out, ref["clipped_sum"]) <= TOL
+    assert np.allclose(gn, ref["norms"], rtol=1e-4, atol=1e-7)
+
+
 def test_long_sequence_stored_gradients():
     """Sequences of 128 steps and more: the LSTM norm contraction stores each example's gradient and the clipped sum
     is a weighted sum of the rows (both LSTM variants)."""
