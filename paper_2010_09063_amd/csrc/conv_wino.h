@@ -6,16 +6,25 @@
 //
 //   B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1]   G = [1 0 0; .5 .5 .5; .5 -.5 .5; 0 0 1]   A^T = [1 1 1 0; 0 1 -1 -1]
 //
-// One workgroup = 32 tiles (128 output pixels) x 32*DB output channels.  Per chunk of 8 input channels every thread
-// loads one (channel, tile) patch straight from global memory, transforms it in registers and writes its 16
-// components to LDS ([component][channel][tile], double-buffered: one barrier per chunk).  Wave w owns transform row
-// w (components 4w .. 4w+3): v_mfma_f32_32x32x2_f32 with M = output channel, N = tile, K = channel pair, the A
-// operand (transformed weights, [component][channel][Mpad] in global memory, zero rows / columns as padding) loaded
-// straight into registers one chunk ahead.  A wave therefore holds 4*DB accumulator tiles, so several workgroups
-// share a CU and hide one another's load and transform phases.  Epilogue: each wave folds its row with A (4
-// components -> 2 numbers), the four rows meet in LDS, and each wave finishes a quarter of the output channels:
-// bias + activation (forward) or the derivative of the producing activation (backward-data), 8-byte stores.
+// One workgroup = 32 tiles (128 output pixels: whole rows of one image, or whole images) x 32*DB output channels.
+// The tiles' patches are windows of one haloed region of RS floats per channel.  Per chunk of 8 input channels the
+// 8 x RS floats are loaded once (about 1.3 fetches per input element), held in registers one chunk ahead, written to
+// a double-buffered LDS array, and every thread transforms one (channel, tile) patch from there into its 16
+// components ([component][channel][tile] in LDS, double-buffered as well).  One barrier per chunk:
+//   iteration n:  raw(n+1) registers -> Xr[(n+1)%2];  transform Xr[n%2] -> V[n%2];  barrier;  issue the loads of
+//                 raw(n+2);  multiply V[n%2], reloading every weight register for chunk n+1 right after its use
+// Wave w owns transform row w (components 4w .. 4w+3): v_mfma_f32_32x32x2_f32 with M = output channel, N = tile,
+// K = channel pair; the A operand (transformed weights, [component][channel][Mpad] in global memory, zero rows /
+// columns as padding) comes straight from global memory into registers.  A wave holds 4*DB accumulator tiles, so
+// two or three workgroups share a CU and fill one another's load and transform phases.  (Measured alternatives that
+// were no faster: patches loaded straight from global memory, two to four chunks of look-ahead, 16-byte weight
+// loads into a second register set.)
+// Epilogue: each wave folds its row with A (4 components -> 2 numbers), the four rows meet in LDS, and each wave
+// finishes a quarter of the output channels: bias + activation (forward) or the derivative of the producing
+// activation (backward-data), 8-byte stores.
 #pragma once
+#include <type_traits>
+
 #include "gemm_tile.h"
 #include "kernels_misc.h"
 
@@ -77,41 +86,64 @@ __global__ void wino_weight_kernel(const float *__restrict__ params, const WinoL
   }
 }
 
-template <int DB>
+struct ConvWinoRegion {
+  int NIMG, ROWS;     // images per workgroup (tiles per image < 32) or 1; pixel rows per workgroup
+  int LDW, IMGPL, RS; // W + 2; (ROWS + 2) * LDW; NIMG * IMGPL (all even)
+  FastDiv dRS, dIMGPL, dLDW;
+};
+
+template <int DB, int XI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DB == 1 ? 3 : 2, DB == 1 ? 3 : 2)))
-void conv_wino_kernel(const ConvWinoArgs a) {
+void conv_wino_kernel(const ConvWinoArgs a, const ConvWinoRegion rg) {
   constexpr int CC = WINO_CC;
-  __shared__ __attribute__((aligned(16))) float Vl[2 * 16 * CC * 32]; // [buf][comp][c][tile]; the epilogue reuses it
+  constexpr int VSZ = 16 * CC * 32;
+  extern __shared__ __attribute__((aligned(16))) float wino_smem[];
+  float *Vl = wino_smem;          // [2][comp][c][tile]; the epilogue reuses it
+  float *Xr = wino_smem + 2 * VSZ; // [2][CC * RS]
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m0 = blockIdx.y * 32 * DB;
   const int HW = a.H * a.W;
   const int TW = 1 << a.tw_shift, TPI = 1 << a.tpi_shift;
+  const int XSZ = CC * rg.RS;
 
-  // this lane's tile: the transform item (channel 2*wave + lk of the chunk) and the MFMA column / output tile
-  const int gt = blockIdx.x * 32 + li;
-  const int img0 = (blockIdx.x * 32) >> a.tpi_shift; // first image of the workgroup
+  // the workgroup's region and this lane's tile in it
+  const int g0 = blockIdx.x * 32;
+  const int img0 = g0 >> a.tpi_shift;
+  const int ty0 = (g0 & (TPI - 1)) >> a.tw_shift; // first tile row (0 when the workgroup holds whole images)
+  const int gt = g0 + li;
   const int img = gt >> a.tpi_shift, trem = gt & (TPI - 1);
   const int ty = trem >> a.tw_shift, tx = trem & (TW - 1);
   const bool img_ok = img < a.B;
-  const float *xblk = a.x + (long)img0 * a.Cin * HW;
-  unsigned poff[16];
-  bool pok[16];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int ih = 2 * ty - 1 + i, iw = 2 * tx - 1 + j;
-      const bool ok = img_ok && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
-      pok[i * 4 + j] = ok;
-      poff[i * 4 + j] = ok ? 4u * (unsigned)((img - img0) * a.Cin * HW + ih * a.W + iw) : 0u; // bytes; (0: a valid word)
-    }
+  // patch of (channel 2*wave + lk of the chunk, tile li): top-left word in a raw buffer
   const int cc = 2 * wave + lk;
+  const int pbase = cc * rg.RS + (img - img0) * rg.IMGPL + 2 * (ty - ty0) * rg.LDW + 2 * tx;
+
+  // staging items: flat index it = tid + j*256 = c * RS + pos  ->  byte offset from the chunk's first channel of the
+  // first image; items that hold no input (halo, past the batch) read word 0 and are zeroed
+  unsigned xg[XI];
+  int xc[XI];
+#pragma unroll
+  for (int j = 0; j < XI; ++j) {
+    const int it = tid + j * 256;
+    const int c = (int)rg.dRS.div(it), pos = it - c * rg.RS;
+    const int im = (int)rg.dIMGPL.div(pos), rem = pos - im * rg.IMGPL;
+    const int rr = (int)rg.dLDW.div(rem), col = rem - rr * rg.LDW;
+    const int ih = 2 * ty0 + rr - 1, iw = col - 1;
+    const bool ok = it < XSZ && (img0 + im) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+    xg[j] = ok ? 4u * (unsigned)((im * a.Cin + c) * HW + ih * a.W + iw) : 0u;
+    xc[j] = ok ? c : (1 << 30); // (an item that never holds input fails the channel test below)
+  }
+  const float *xblk = a.x + (long)img0 * a.Cin * HW;
 
   // weights: lane (li, lk) of MFMA step (component 4*wave + jj, channel pair cp, block i) reads
-  //   u[((4*wave + jj)*Cpad + c0 + 2*cp + lk)*Mpad + m0 + 32*i + li]
+  //   u[((4*wave + jj)*Cpad + c0 + 2*cp + lk)*Mpad + m0 + 32*i + li]  =  (uniform pointer) + the lane's byte offset
   const unsigned wlane = 4u * (unsigned)(lk * a.Mpad + li);
   const float *ubase = a.u + ((long)(4 * wave) * a.Cpad) * a.Mpad + m0;
+  auto w_ptr = [&](const float *uc, unsigned wl, int jj, int cp, int i) {
+    return reinterpret_cast<const float *>(
+        reinterpret_cast<const char *>(uc + ((long)jj * a.Cpad + 2 * cp) * a.Mpad + 32 * i) + wl);
+  };
 
   f32x16 acc[4][DB];
 #pragma unroll
@@ -121,34 +153,48 @@ void conv_wino_kernel(const ConvWinoArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
 
-  float pr[16];
+  float xr[XI];
   float wr[4][CC / 2][DB];
-  auto fetch_patch = [&](int c0) {
-    const unsigned choff = 4u * (unsigned)(min(c0 + cc, a.Cin - 1) * HW); // a channel past Cin meets zero weights
+  // raw loads of the chunk that starts at channel c0 (any c0: channels past Cin read word 0 and are zeroed)
+  auto fetch_raw = [&](int c0, float *dst) {
+    const float *xc0 = xblk + (long)min(c0, a.Cin - 1) * HW;
+    const int left = a.Cin - c0;
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
-      pr[k] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xblk) + (choff + poff[k]));
+    for (int j = 0; j < XI; ++j) {
+      const unsigned off = xc[j] < left ? xg[j] : 0u;
+      dst[j] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xc0) + off);
+    }
   };
-  // (uniform pointer of the chunk + uniform row offset) + the lane's byte offset
-  auto w_ptr = [&](const float *uc, unsigned wl, int jj, int cp, int i) {
-    return reinterpret_cast<const float *>(
-        reinterpret_cast<const char *>(uc + ((long)jj * a.Cpad + 2 * cp) * a.Mpad + 32 * i) + wl);
+  auto store_raw = [&](int c0, const float *src, float *xbuf) {
+    const int left = a.Cin - c0;
+#pragma unroll
+    for (int j = 0; j < XI; ++j)
+      if (tid + j * 256 < XSZ) xbuf[tid + j * 256] = xc[j] < left ? src[j] : 0.f;
   };
+
+  fetch_raw(0, xr);
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
     for (int cp = 0; cp < CC / 2; ++cp)
 #pragma unroll
       for (int i = 0; i < DB; ++i) wr[jj][cp][i] = *w_ptr(ubase, wlane, jj, cp, i);
+  store_raw(0, xr, Xr);
+  __syncthreads();
+  fetch_raw(CC, xr);
 
-  fetch_patch(0);
   int buf = 0;
   for (int c0 = 0; c0 < a.Cin; c0 += CC) {
-    // transform the patch: t = B^T d (rows), v = t B (columns)
-    {
+    store_raw(c0 + CC, xr, Xr + (buf ^ 1) * XSZ);
+    { // transform the patch: t = B^T d (rows), v = t B (columns)
+      const float *src = Xr + buf * XSZ + pbase;
       float d[16];
 #pragma unroll
-      for (int k = 0; k < 16; ++k) d[k] = pok[k] ? pr[k] : 0.f;
+      for (int i = 0; i < 4; ++i) {
+        const float2 p0 = *reinterpret_cast<const float2 *>(src + i * rg.LDW);
+        const float2 p1 = *reinterpret_cast<const float2 *>(src + i * rg.LDW + 2);
+        d[4 * i + 0] = p0.x; d[4 * i + 1] = p0.y; d[4 * i + 2] = p1.x; d[4 * i + 3] = p1.y;
+      }
       float t[16];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -157,7 +203,7 @@ void conv_wino_kernel(const ConvWinoArgs a) {
         t[8 + j] = d[8 + j] - d[4 + j];
         t[12 + j] = d[4 + j] - d[12 + j];
       }
-      float *dst = Vl + buf * (16 * CC * 32) + cc * 32 + li;
+      float *dst = Vl + buf * VSZ + cc * 32 + li;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         dst[(4 * i + 0) * CC * 32] = t[4 * i + 0] - t[4 * i + 2];
@@ -166,15 +212,15 @@ void conv_wino_kernel(const ConvWinoArgs a) {
         dst[(4 * i + 3) * CC * 32] = t[4 * i + 1] - t[4 * i + 3];
       }
     }
-    __syncthreads(); // the chunk's components are in place (the other buffer may still be read by slower waves)
-    // next chunk's loads (the last chunk re-reads itself: no branch around loads).  A weight register is reloaded
-    // right after the multiply that consumed it, so its latency hides behind the rest of this chunk.
+    __syncthreads(); // V[buf] and the next raw chunk are in place (slower waves may still read the other buffers)
+    fetch_raw(c0 + 2 * CC, xr);
+    // A weight register is reloaded for the next chunk right after the multiply that consumed it (the last chunk
+    // re-reads itself: no branch around loads).
     const int cn = min(c0 + CC, a.Cpad - CC);
     const float *un = ubase + (long)cn * a.Mpad;
     unsigned wl = wlane;
     asm volatile("" : "+v"(wl)); // keeps the weight addresses in the form uniform pointer + lane offset
-    fetch_patch(cn);
-    const float *vb = Vl + buf * (16 * CC * 32) + (4 * wave) * CC * 32 + lk * 32 + li;
+    const float *vb = Vl + buf * VSZ + (4 * wave) * CC * 32 + lk * 32 + li;
 #pragma unroll
     for (int cp = 0; cp < CC / 2; ++cp)
 #pragma unroll
@@ -186,8 +232,8 @@ void conv_wino_kernel(const ConvWinoArgs a) {
           wr[jj][cp][i] = *w_ptr(un, wl, jj, cp, i);
         }
       }
-    // instruction order: the patch loads first, then multiplies and weight reloads alternating
-    __builtin_amdgcn_sched_group_barrier(0x020, 16, 0);
+    // instruction order: the raw loads first, then multiplies and weight reloads alternating
+    __builtin_amdgcn_sched_group_barrier(0x020, XI, 0);
 #pragma unroll
     for (int k = 0; k < 4 * (CC / 2); ++k) {
       __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
@@ -196,14 +242,12 @@ void conv_wino_kernel(const ConvWinoArgs a) {
     buf ^= 1;
   }
 
-  // epilogue.  Row w of  M A:  t0 = m0 + m1 + m2,  t1 = m1 - m2 - m3;  then  Y[0][k] = T0 + T1 + T2,
-  // Y[1][k] = T1 - T2 - T3  over the four waves' rows.
   const bool fwd = a.bias != nullptr;
   const bool need_side = !fwd && a.act;
   float *Tl = Vl; // [wave][k][r][lane]
 #pragma unroll
   for (int i = 0; i < DB; ++i) {
-    __syncthreads(); // every wave is done with the LDS contents of the previous phase
+    __syncthreads();
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][i][r] + acc[1][i][r] + acc[2][i][r];
@@ -214,7 +258,7 @@ void conv_wino_kernel(const ConvWinoArgs a) {
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
       const int r = 4 * wave + rr;
-      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr;
       if (m >= a.M) continue;
       float T[4][2];
 #pragma unroll

@@ -270,6 +270,17 @@ static bool make_conv_tile(ConvTile &t, int OH, int OW, int KH, int KW, int np_m
 
 static bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
+// Region of the 32 tiles of a minimal-filtering workgroup (tiles per row and per image are powers of two): whole
+// tile rows of one image, or whole images.  Returns the staging items per thread for a chunk of 8 channels.
+static int make_wino_region(ConvWinoRegion &rg, int H, int W) {
+  const int TW = W / 2, TPI = (H / 2) * (W / 2);
+  if (TW > 32) return 1 << 20;
+  if (TPI >= 32) { rg.NIMG = 1; rg.ROWS = 2 * (32 / TW); } else { rg.NIMG = 32 / TPI; rg.ROWS = H; }
+  rg.LDW = W + 2; rg.IMGPL = (rg.ROWS + 2) * rg.LDW; rg.RS = rg.NIMG * rg.IMGPL;
+  rg.dRS.init(rg.RS); rg.dIMGPL.init(rg.IMGPL); rg.dLDW.init(rg.LDW);
+  return ceil_div(WINO_CC * rg.RS, 256);
+}
+
 static void plan_direct_conv(Layer &l, int maxB, bool allow) {
   const ConvGeom &g = l.geom;
   if (!allow || g.S != 1 || g.KH != 3 || g.KW != 3 || g.PAD > 2) return;
@@ -292,18 +303,23 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
   if (l.dir_fwd && l.dir_bwd && g.PAD == 1 && g.H == g.OH && g.W == g.OW && (g.H & 1) == 0 && (g.W & 1) == 0 &&
       is_pow2(g.W / 2) && is_pow2((g.H / 2) * (g.W / 2)) && getenv("DP_STEP_NO_WINO") == nullptr) {
     const bool all = getenv("DP_STEP_WINO_ALL") != nullptr; // tests: the kernel for every eligible shape
-    auto pick = [&](int Cin, int M) {
+    ConvWinoRegion rg;
+    const bool fits = make_wino_region(rg, g.H, g.W) <= 9; // staging items per thread the kernels are built for
+    auto pick = [&](int Cin, int M, bool bwd) {
       int db = M > 32 ? 2 : 1;
+      if (!fits) return 0;
       if (all) return db;
       if (Cin < 16) return 0;
       const long groups = ((long)maxB * (g.H / 2) * (g.W / 2) + 31) / 32;
       if (db == 2 && groups * ceil_div(M, 64) < 512) db = 1;
       if (groups * ceil_div(M, 32 * db) < 512) return 0;
-      if (db == 1 && Cin > 32) return 0;
+      // 32 output channels per workgroup: the transform is amortised over half the multiplies, and the epilogue
+      // over the channel loop only
+      if (db == 1 && Cin < (bwd ? 64 : 32)) return 0;
       return db;
     };
-    l.wino_f = pick(g.C, g.D);
-    l.wino_b = pick(g.D, g.C);
+    l.wino_f = pick(g.C, g.D, false);
+    l.wino_b = pick(g.D, g.C, true);
   }
   // per-example norm from Gram matrices: P^2 (9C + D) multiply-adds instead of 9 C D P, for the two plane sizes
   // the kernel is built for (pad 1, so the input plane equals the output plane)
@@ -372,12 +388,21 @@ template <class LN>
 static void launch_conv_wino(const LN &Ln, const char *label, ConvWinoArgs a, int db) {
   a.tw_shift = ilog2_exact(a.W / 2);
   a.tpi_shift = ilog2_exact((a.H / 2) * (a.W / 2));
+  ConvWinoRegion rg;
+  const int need = make_wino_region(rg, a.H, a.W);
+  const int xi = need <= 6 ? 6 : (need <= 7 ? 7 : 9);
   const long tiles = (long)a.B * (a.H / 2) * (a.W / 2);
   dim3 grid((unsigned)((tiles + 31) / 32), a.Mpad / (32 * db)), block(256);
-  Ln(label, grid, block, [&](hipStream_t st) {
-    if (db == 1) hipLaunchKernelGGL(conv_wino_kernel<1>, grid, block, 0, st, a);
-    else hipLaunchKernelGGL(conv_wino_kernel<2>, grid, block, 0, st, a);
-  });
+  const size_t smem = sizeof(float) * (2 * 16 * WINO_CC * 32 + 2 * WINO_CC * (size_t)rg.RS);
+#define DP_WINO_CASE(db_, xi_)                                                                    \
+  if (db == db_ && xi == xi_) {                                                                   \
+    Ln(label, grid, block, [&](hipStream_t st) {                                                  \
+      hipLaunchKernelGGL((conv_wino_kernel<db_, xi_>), grid, block, smem, st, a, rg);             \
+    });                                                                                           \
+    return;                                                                                       \
+  }
+  DP_WINO_CASE(1, 6) DP_WINO_CASE(1, 7) DP_WINO_CASE(1, 9) DP_WINO_CASE(2, 6) DP_WINO_CASE(2, 7) DP_WINO_CASE(2, 9)
+#undef DP_WINO_CASE
 }
 
 static size_t conv_wgrad_ws_smem(const ConvWgArgs &a, int db, bool flat) {
