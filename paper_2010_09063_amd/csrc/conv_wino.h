@@ -286,3 +286,218 @@ void conv_wino_kernel(const ConvWinoArgs a, const ConvWinoRegion rg) {
     }
   }
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Variant without the component array, for whole chunks of input channels (Cin a multiple of 8): every lane
+// transforms, for its own tile, the four channels whose products it feeds to the matrix unit (channel 2*cp + lk for
+// channel pair cp), and only the transform row of its wave -- the results are the B operands themselves.  LDS holds
+// the raw region only; the transform of chunk n+1 (16 reads and 32 vector operations per lane) is independent of
+// the multiplies of chunk n and is issued between them.
+//   iteration n:  raw(n+1) registers -> Xr[(n+1)%2];  barrier;  issue loads of raw(n+2);
+//                 { transform Xr[(n+1)%2] -> operands of chunk n+1 }  interleaved with  { multiply chunk n }
+// Plane geometries are compile-time (W_ columns, ROWS_ pixel rows and NIMG_ images per workgroup, LDS row length
+// LDW_ chosen so that the 16 lanes served together read 32 different banks).  Two operand sets and the accumulators
+// of 64 output channels fill the registers of a wave at two waves per SIMD; with 32 output channels per workgroup
+// the kernel above (three waves per SIMD) measured faster.
+template <int W_, int ROWS_, int NIMG_, int LDW_>
+struct WinoGeom {
+  static constexpr int W = W_, ROWS = ROWS_, NIMG = NIMG_, LDW = LDW_;
+  static constexpr int IMGPL = (ROWS + 2) * LDW, RS = NIMG * IMGPL;           // LDS floats per image / per channel
+  static constexpr int REAL_IMG = (ROWS + 2) * (W + 2), REAL = NIMG * REAL_IMG; // positions that are staged
+  static constexpr int TW = W / 2, TPG = (ROWS / 2) * TW; // tiles per row; tiles per image inside a workgroup
+  static_assert(NIMG * TPG == 32 && LDW >= W + 2 && LDW % 2 == 0, "a workgroup covers 32 tiles");
+};
+
+template <int DB, class G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void conv_wino_reg_kernel(const ConvWinoArgs a) {
+  constexpr int CC = WINO_CC, RS = G::RS, LDW = G::LDW, XSZ = CC * RS;
+  __shared__ __attribute__((aligned(16))) float smem[8192]; // raw buffers [2][CC * RS]; the epilogue uses all of it
+  static_assert(2 * XSZ <= 8192, "raw buffers fit");
+  float *Xr = smem;
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = blockIdx.y * 32 * DB;
+  const int HW = a.H * G::W;
+
+  // the workgroup's region: NIMG whole images, or ROWS pixel rows of one image
+  int img0, row0;
+  if (G::NIMG > 1) { img0 = blockIdx.x * G::NIMG; row0 = 0; }
+  else { const int per = a.H / G::ROWS; img0 = blockIdx.x / per; row0 = (blockIdx.x - img0 * per) * G::ROWS; }
+  // this lane's tile
+  const int iml = li / G::TPG, trem = li % G::TPG, tyl = trem / G::TW, tx = trem % G::TW;
+  const int img = img0 + iml;
+  const bool img_ok = img < a.B;
+  const int ty = row0 / 2 + tyl;
+  // first word of the tile's patch for channel lk of a buffer; channel pair cp adds 2*cp*RS, patch row r adds r*LDW
+  const float *pat = Xr + lk * RS + iml * G::IMGPL + 2 * tyl * LDW + 2 * tx;
+  // the wave's transform row:  t = d[r1] + s2 * d[r2]  (rows of B^T: d0 - d2, d1 + d2, d2 - d1, d1 - d3)
+  const int r1 = wave == 0 ? 0 : (wave == 2 ? 2 : 1);
+  const int r2 = wave == 0 ? 2 : (wave == 1 ? 2 : (wave == 2 ? 1 : 3));
+  const float s2 = wave == 1 ? 1.f : -1.f;
+
+  // staging: thread tid owns position tid of the region (image, row, column of the haloed plane) for all 8 channels
+  // of a chunk: one lane offset into x (the channel moves the uniform pointer) and one LDS word (the channel is an
+  // immediate).  Positions that hold no input read word 0 and are zeroed.
+  static_assert(G::REAL <= 256, "one position per thread");
+  unsigned xg;
+  int xl;
+  bool xok;
+  {
+    const int im = tid / G::REAL_IMG, rem = tid % G::REAL_IMG;
+    const int rr = rem / (G::W + 2), col = rem % (G::W + 2);
+    const int ih = row0 + rr - 1, iw = col - 1;
+    xok = tid < G::REAL && (img0 + im) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)G::W;
+    xg = xok ? 4u * (unsigned)(im * a.Cin * HW + ih * G::W + iw) : 0u;
+    xl = tid < G::REAL ? im * G::IMGPL + rr * LDW + col : -1;
+  }
+  const float *xblk = a.x + (long)img0 * a.Cin * HW;
+
+  const unsigned wlane = 4u * (unsigned)(lk * a.Mpad + li);
+  const float *ubase = a.u + ((long)(4 * wave) * a.Cpad) * a.Mpad + m0;
+  auto w_ptr = [&](const float *uc, unsigned wl, int jj, int cp, int i) {
+    return reinterpret_cast<const float *>(
+        reinterpret_cast<const char *>(uc + ((long)jj * a.Cpad + 2 * cp) * a.Mpad + 32 * i) + wl);
+  };
+
+  f32x16 acc[4][DB];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
+
+  float xr[CC];
+  float wr[4][CC / 2][DB];
+  auto fetch_raw = [&](int c0) {
+    const float *xc0 = xblk + (long)min(c0, a.Cin - CC) * HW; // (past the last chunk: re-reads it, unused)
+#pragma unroll
+    for (int c = 0; c < CC; ++c)
+      xr[c] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xc0 + (long)c * HW) + xg);
+  };
+  auto store_raw = [&](float *xbuf) {
+    if (xl >= 0) {
+#pragma unroll
+      for (int c = 0; c < CC; ++c) xbuf[xl + c * RS] = xok ? xr[c] : 0.f;
+    }
+  };
+  // B operands of one chunk from a raw buffer: bv[cp][jj] = component (wave, jj) of channel 2*cp + lk
+  auto transform = [&](const float *xbuf, float (*bv)[4]) {
+    const float *p = pat + (xbuf - Xr);
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp) {
+      const float *q = p + 2 * cp * RS;
+      const float2 a0 = *reinterpret_cast<const float2 *>(q + r1 * LDW);
+      const float2 a1 = *reinterpret_cast<const float2 *>(q + r1 * LDW + 2);
+      const float2 b0 = *reinterpret_cast<const float2 *>(q + r2 * LDW);
+      const float2 b1 = *reinterpret_cast<const float2 *>(q + r2 * LDW + 2);
+      const float t0 = fmaf(s2, b0.x, a0.x), t1 = fmaf(s2, b0.y, a0.y), t2 = fmaf(s2, b1.x, a1.x), t3 = fmaf(s2, b1.y, a1.y);
+      bv[cp][0] = t0 - t2;
+      bv[cp][1] = t1 + t2;
+      bv[cp][2] = t2 - t1;
+      bv[cp][3] = t1 - t3;
+    }
+  };
+
+  fetch_raw(0);
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp)
+#pragma unroll
+      for (int i = 0; i < DB; ++i) wr[jj][cp][i] = *w_ptr(ubase, wlane, jj, cp, i);
+  // (padding words of the rows are never read; halo words are rewritten as zeros with every chunk)
+  store_raw(Xr);
+  __syncthreads();
+  fetch_raw(CC);
+  float bA[CC / 2][4], bB[CC / 2][4];
+  transform(Xr, bA);
+
+  auto chunk = [&](int c0, int buf, float (*bcur)[4], float (*bnext)[4]) {
+    store_raw(Xr + (buf ^ 1) * XSZ);
+    __syncthreads(); // raw(n+1) is in place; every wave has finished reading the buffer that raw(n+2) will overwrite
+    fetch_raw(c0 + 2 * CC);
+    transform(Xr + (buf ^ 1) * XSZ, bnext);
+    const int cn = min(c0 + CC, a.Cpad - CC);
+    const float *un = ubase + (long)cn * a.Mpad;
+    unsigned wl = wlane;
+    asm volatile("" : "+v"(wl)); // keeps the weight addresses in the form uniform pointer + lane offset
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+          acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[jj][cp][i], bcur[cp][jj], acc[jj][i], 0, 0, 0);
+          wr[jj][cp][i] = *w_ptr(un, wl, jj, cp, i);
+        }
+    // instruction order: the raw loads first, then per multiply step its weight reloads, one LDS read and two vector
+    // operations of the next chunk's transform
+    __builtin_amdgcn_sched_group_barrier(0x020, CC, 0);
+#pragma unroll
+    for (int k = 0; k < 4 * (CC / 2); ++k) {
+      __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, DB, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+    }
+  };
+  int buf = 0;
+  for (int c0 = 0; c0 < a.Cin; c0 += 2 * CC) {
+    chunk(c0, buf, bA, bB);
+    buf ^= 1;
+    if (c0 + CC < a.Cin) {
+      chunk(c0 + CC, buf, bB, bA);
+      buf ^= 1;
+    }
+  }
+
+  const bool fwd = a.bias != nullptr;
+  const bool need_side = !fwd && a.act;
+  float *Tl = smem; // [wave][k][r][lane]
+#pragma unroll
+  for (int i = 0; i < DB; ++i) {
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][i][r] + acc[1][i][r] + acc[2][i][r];
+      Tl[((wave * 2 + 1) * 16 + r) * 64 + lane] = acc[1][i][r] - acc[2][i][r] - acc[3][i][r];
+    }
+    __syncthreads();
+    if (!img_ok) continue;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr;
+      if (m >= a.M) continue;
+      float T[4][2];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
+      float2 y0, y1;
+      y0.x = T[0][0] + T[1][0] + T[2][0];
+      y0.y = T[0][1] + T[1][1] + T[2][1];
+      y1.x = T[1][0] - T[2][0] - T[3][0];
+      y1.y = T[1][1] - T[2][1] - T[3][1];
+      const long o = ((long)img * a.M + m) * HW + (2 * ty) * G::W + 2 * tx;
+      if (fwd) {
+        const float bv = a.bias[m];
+        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
+        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
+      } else if (need_side) {
+        const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
+        const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + G::W);
+        y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
+        y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
+      }
+      *reinterpret_cast<float2 *>(a.out + o) = y0;
+      *reinterpret_cast<float2 *>(a.out + o + G::W) = y1;
+    }
+  }
+}
+
+typedef WinoGeom<32, 4, 1, 34> WinoG32;
+typedef WinoGeom<16, 8, 1, 24> WinoG16;
+typedef WinoGeom<8, 8, 2, 12> WinoG8;

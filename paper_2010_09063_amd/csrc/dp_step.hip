@@ -393,6 +393,19 @@ static void launch_conv_wino(const LN &Ln, const char *label, ConvWinoArgs a, in
   const int xi = need <= 6 ? 6 : (need <= 7 ? 7 : 9);
   const long tiles = (long)a.B * (a.H / 2) * (a.W / 2);
   dim3 grid((unsigned)((tiles + 31) / 32), a.Mpad / (32 * db)), block(256);
+  // 64 output channels per workgroup, whole chunks of input channels, one of the plane shapes the register-operand
+  // kernel is built for
+  if (db == 2 && a.Cin % WINO_CC == 0) {
+#define DP_WINO3_CASE(G_, cond_)                                                                  \
+  if (a.W == G_::W && (cond_)) {                                                                  \
+    Ln(label, grid, block, [&](hipStream_t st) {                                                  \
+      hipLaunchKernelGGL((conv_wino_reg_kernel<2, G_>), grid, block, 0, st, a);                   \
+    });                                                                                           \
+    return;                                                                                       \
+  }
+    DP_WINO3_CASE(WinoG32, a.H % 4 == 0) DP_WINO3_CASE(WinoG16, a.H % 8 == 0) DP_WINO3_CASE(WinoG8, a.H == 8)
+#undef DP_WINO3_CASE
+  }
   const size_t smem = sizeof(float) * (2 * 16 * WINO_CC * 32 + 2 * WINO_CC * (size_t)rg.RS);
 #define DP_WINO_CASE(db_, xi_)                                                                    \
   if (db == db_ && xi == xi_) {                                                                   \

@@ -213,6 +213,12 @@ def test_minimal_filtering_route(monkeypatch):
         m = TINY[name]
         x, y, theta = _case(m, batch, seed=43)
         _check_all_regimes(m, x, y, theta, f"{name}/minimal-filtering")
+    # 32x32 planes with 64 output channels per workgroup, forward (8 -> 40) and backward-data (16 -> 40)
+    m = W.model(W.image_input(8, 32, 32), [
+        W.conv2d(8, 40, 3, stride=1, pad=1, act="tanh"), W.conv2d(40, 16, 3, stride=1, pad=1, act="tanh"),
+        W.avgpool2d(8, 8), W.dense(16 * 4 * 4, 3)], 3)
+    x, y, theta = _case(m, 3, seed=44)
+    _check_all_regimes(m, x, y, theta, "planes32/minimal-filtering")
     wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/minimal-filtering")
     wl = W.make_workload("paper_cifar_cnn", batch=5, seed=6, bias_scale=0.2)
