@@ -36,6 +36,11 @@ struct ConvWinoArgs {
   const float *bias;   // forward: bias[M]; backward-data: null
   const float *a_prev; // backward-data with act != 0: output of the activation whose derivative multiplies the result
   float *out;          // [B, M, H, W]
+  // forward, optional: the 2x2 / stride-2 pool that follows the layer, taken in the epilogue (a tile is one pool
+  // window): pool = 1 maximum (first maximum in row-major order wins, its index 0..3 goes to pool_arg), 2 average
+  float *pool_out;     // [B, M, H/2, W/2]
+  uint8_t *pool_arg;   // [B, M, H/2, W/2] (maximum only)
+  int pool;
   int B, Cin, Cpad, H, W, M, Mpad; // Cpad: multiple of WINO_CC; Mpad: multiple of 32*DB times gridDim.y
   int act;
   int tw_shift, tpi_shift; // log2(W/2), log2((H/2)*(W/2)): tiles per row / per image are powers of two
@@ -275,6 +280,19 @@ void conv_wino_kernel(const ConvWinoArgs a, const ConvWinoRegion rg) {
         const float bv = a.bias[m];
         y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
         y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
+        if (a.pool) {
+          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (a.W >> 1) + tx;
+          if (a.pool == 1) {
+            float best = y0.x; int bi = 0;
+            if (y0.y > best) { best = y0.y; bi = 1; }
+            if (y1.x > best) { best = y1.x; bi = 2; }
+            if (y1.y > best) { best = y1.y; bi = 3; }
+            a.pool_out[po] = best;
+            a.pool_arg[po] = (uint8_t)bi;
+          } else {
+            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+          }
+        }
       } else if (need_side) {
         const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
         const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + a.W);
@@ -486,6 +504,19 @@ void conv_wino_reg_kernel(const ConvWinoArgs a) {
         const float bv = a.bias[m];
         y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
         y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
+        if (a.pool) {
+          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (G::W >> 1) + tx;
+          if (a.pool == 1) {
+            float best = y0.x; int bi = 0;
+            if (y0.y > best) { best = y0.y; bi = 1; }
+            if (y1.x > best) { best = y1.x; bi = 2; }
+            if (y1.y > best) { best = y1.y; bi = 3; }
+            a.pool_out[po] = best;
+            a.pool_arg[po] = (uint8_t)bi;
+          } else {
+            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+          }
+        }
       } else if (need_side) {
         const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
         const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + G::W);

@@ -844,6 +844,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     }
     // ------------------------------------------------------------ forward
     const float *in = (const float *)x;
+    int fused_pool = -1;
+    static const bool no_pool_fusion = getenv("DP_STEP_NO_POOL_FUSION") != nullptr;
     for (int i = 0; i < nL; ++i) {
       Layer &l = c->L[i];
       const float *W = params + l.p_off;
@@ -893,6 +895,13 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           ConvWinoArgs a{};
           a.x = in; a.u = l.u_f; a.bias = W + (long)g.D * g.CKK; a.a_prev = nullptr; a.out = l.a;
           a.B = B; a.Cin = g.C; a.Cpad = l.uf_cpad; a.H = g.H; a.W = g.W; a.M = g.D; a.Mpad = l.uf_mpad; a.act = l.d.act;
+          // a 2x2 / stride-2 pool right after the layer: one tile of the kernel is one pool window
+          if (i + 1 < nL && (c->L[i + 1].d.kind == DP_MAXPOOL2D || c->L[i + 1].d.kind == DP_AVGPOOL2D) &&
+              c->L[i + 1].d.kh == 2 && c->L[i + 1].d.kw == 2 && c->L[i + 1].d.stride == 2 && !no_pool_fusion) {
+            a.pool = c->L[i + 1].d.kind == DP_MAXPOOL2D ? 1 : 2;
+            a.pool_out = c->L[i + 1].a; a.pool_arg = c->L[i + 1].arg;
+            fused_pool = i + 1;
+          }
           launch_conv_wino(Ln, LL("conv_fwd"), a, l.wino_f);
           break;
         }
@@ -919,6 +928,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         vec_dispatch(OpRowMajor<true>::can_vec(W, g.CKK, 0, g.CKK), run);
       } break;
       case DP_MAXPOOL2D: {
+        if (i == fused_pool) break; // taken in the epilogue of the convolution before it
         long total = (long)B * l.out_size;
         dim3 grid = grid1d(total, 256), block(256);
         const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
@@ -947,6 +957,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         });
       } break;
       case DP_AVGPOOL2D: {
+        if (i == fused_pool) break; // taken in the epilogue of the convolution before it
         long total = (long)B * l.out_size;
         dim3 grid = grid1d(total, 256), block(256);
         const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
