@@ -146,6 +146,7 @@ struct Layer {
   // forward / backward-data by the F(2x2, 3x3) minimal-filtering kernel: output-channel blocks per workgroup (0: not
   // used), transformed weights [16][cpad][mpad]
   int wino_f = 0, wino_b = 0;
+  bool wino_wg = false; // clipped sum of the weight gradient in the F(3x3, 2x2) form (8x8 planes)
   float *u_f = nullptr, *u_b = nullptr;
   int uf_cpad = 0, uf_mpad = 0, ub_cpad = 0, ub_mpad = 0;
   std::vector<std::string> lab; // profiling labels "<kernel>#<layer index>" (stable after init)
@@ -318,6 +319,8 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       if (db == 1 && Cin < (bwd ? 64 : 32)) return 0;
       return db;
     };
+    // clipped sum of the weight gradient in the same form with the roles exchanged (kernel built for 8x8 planes)
+    l.wino_wg = g.H == 8 && g.W == 8 && g.C % 32 == 0 && g.D % 64 == 0 && getenv("DP_STEP_NO_WINO_WG") == nullptr;
     l.wino_f = pick(g.C, g.D, false);
     l.wino_b = pick(g.D, g.C, true);
   }
@@ -1270,6 +1273,20 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           Ln(LL("conv_weighted_sum"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(weighted_sum_kernel, grid, block, 0, st, (const float *)l.gst, gstride, sc, l.part,
                                l.p_count, l.gorder, B, eps);
+          });
+          break;
+        }
+        if (l.wino_wg && aligned16(lin) && aligned16(l.g)) {
+          const int tiles = (g.C / 32) * (g.D / 64);
+          int want = std::max(1, std::min(l.max_split, 512 / tiles));
+          const int eps = ceil_div(B, want);
+          nsplit = ceil_div(B, eps);
+          ConvWinoWgArgs a{};
+          a.x = lin; a.dy = l.g; a.scale = sc; a.part = l.part; a.part_stride = l.p_count;
+          a.B = B; a.C = g.C; a.D = g.D; a.ex_per_split = eps;
+          dim3 grid(g.C / 32, g.D / 64, nsplit), block(256);
+          Ln(LL("conv_clipped_sum"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(conv_wino_wgrad8_kernel, grid, block, 0, st, a);
           });
           break;
         }
