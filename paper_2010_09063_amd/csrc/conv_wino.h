@@ -706,3 +706,258 @@ void conv_wino_wgrad8_kernel(const ConvWinoWgArgs a) {
     }
   }
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// The same F(3x3, 2x2) contraction on larger planes, in two modes.
+// NORM (the norm pass, Section 1 item 2a: one gradient per example): after the last tile of an example the 16
+// components are transformed back, the example's gradient goes to its row of the stored-gradient buffer in the
+// parameter layout (W[d][c][3][3], then bias[d]), its squares are reduced in a fixed order into the example's slot of
+// this channel block, and the accumulators start again at zero.
+// Otherwise (sum over a run of examples, item 3): dy is scaled by the example's clip factor while it is staged, the
+// components are summed over the whole run and transformed back once into one split-K partial.
+// A unit of work is 16 tiles = 64 output pixels: TR tile rows of a W-wide plane (W = 32: one tile row, 16: two, 8:
+// the whole 8x8 plane); a unit's x band carries its own halo rows from the neighbouring bands (zero rows outside
+// the plane) and zero halo columns, all rewritten with every unit.  One workgroup = one block of 32 input channels
+// x all 32*DB output channels, for a run of examples.
+struct ConvWinoWgUnitArgs {
+  const float *x;      // layer input [B, C, H, W]
+  const float *dy;     // [B, D, H, W]
+  const float *scale;  // sum mode: clip factors s[b] (a vector of ones when nothing is clipped)
+  float *slots;        // NORM: squared norms, slots[(slot0 + channel block) * slot_stride + b]
+  float *gstore;       // NORM: [B][gstride], per-example gradients in the parameter layout
+  float *part;         // sum mode: the run blockIdx.y writes part + blockIdx.y * part_stride
+  long slot_stride, gstride, part_stride;
+  int slot0;
+  int B, C, D, H;      // C a multiple of 32, D = 32 * DB, H a multiple of 2 * TR
+  int ex_per_block;
+};
+
+template <int W_, int TR_, int DB, bool NORM>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
+  constexpr int W = W_, TW = W / 2, XR = 2 * TR_ + 2, LDW = W + 2;
+  constexpr int XS = ((XR * LDW + 3) / 4) * 4 + 2, DS = 66; // channel strides = 2 mod 4: conflict-free 8-byte lane reads
+  constexpr int XSZ = 32 * XS, DSZ = 32 * DB * DS, STAGE = XSZ + DSZ;
+  constexpr int SMEM = 2 * STAGE > 12288 ? 2 * STAGE : 12288;
+  constexpr int XITEMS = 32 * XR * (W / 4), XN = (XITEMS + 255) / 256, DN = 2 * DB;
+  constexpr int HITEMS = 32 * XR, HN = (HITEMS + 255) / 256; // halo-column rows
+  static_assert(TW * TR_ == 16, "a unit is 16 tiles");
+  __shared__ __attribute__((aligned(16))) float smem[SMEM];
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c0 = blockIdx.x * 32;
+  const int b0 = blockIdx.y * a.ex_per_block, b1 = min(b0 + a.ex_per_block, a.B);
+  const int UPI = (a.H / 2) / TR_; // units per image
+  const int HW = a.H * W;
+
+  // staging items of a unit: x float4 (channel, band row, column group), dy float4 (channel, 16-byte part of the 64 pixels)
+  int xs_l[XN], xs_rr[XN];
+  unsigned xs_g[XN];
+#pragma unroll
+  for (int j = 0; j < XN; ++j) {
+    const int q = tid + j * 256;
+    const int ch = q / (XR * (W / 4)), rem = q % (XR * (W / 4)), rr = rem / (W / 4), qq = rem % (W / 4);
+    xs_l[j] = q < XITEMS ? ch * XS + rr * LDW + 1 + 4 * qq : -1;
+    xs_rr[j] = rr;
+    xs_g[j] = 4u * (unsigned)(ch * HW + 4 * qq); // + row * W per unit
+  }
+  int ds_l[DN];
+  unsigned ds_g[DN];
+#pragma unroll
+  for (int j = 0; j < DN; ++j) {
+    const int q = tid + j * 256, ch = q >> 4, part = q & 15;
+    ds_l[j] = XSZ + ch * DS + 4 * part;
+    ds_g[j] = 4u * (unsigned)(ch * HW + 4 * part);
+  }
+  float4 xv[XN], dv[DN];
+  float sv = 1.f; // clip factor of the example whose unit is in the registers
+  // unit u = example u / UPI, band u % UPI
+  auto fetch = [&](int b, int band) {
+    if (!NORM) sv = a.scale[b];
+    const int r0 = band * 2 * TR_;
+    const float *xb = a.x + ((long)b * a.C + c0) * HW;
+    const float *db = a.dy + ((long)b * a.D) * HW + (long)r0 * W;
+#pragma unroll
+    for (int j = 0; j < XN; ++j) {
+      const int ih = r0 - 1 + xs_rr[j];
+      const bool ok = xs_l[j] >= 0 && (unsigned)ih < (unsigned)a.H;
+      const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(xb) + (ok ? xs_g[j] + 4u * (unsigned)(ih * W) : 0u));
+      xv[j] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < DN; ++j) dv[j] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(db) + ds_g[j]);
+  };
+  float bsum[DN];
+#pragma unroll
+  for (int j = 0; j < DN; ++j) bsum[j] = 0.f;
+  auto store = [&](float *st) {
+#pragma unroll
+    for (int j = 0; j < XN; ++j)
+      if (xs_l[j] >= 0) {
+        float *p = st + xs_l[j];
+        p[0] = xv[j].x; p[1] = xv[j].y; p[2] = xv[j].z; p[3] = xv[j].w;
+      }
+#pragma unroll
+    for (int j = 0; j < HN; ++j) { // zero halo columns of every band row
+      const int q = tid + j * 256;
+      if (q < HITEMS) {
+        float *p = st + (q / XR) * XS + (q % XR) * LDW;
+        p[0] = 0.f; p[W + 1] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < DN; ++j) {
+      const float4 v = NORM ? dv[j] : make_float4(dv[j].x * sv, dv[j].y * sv, dv[j].z * sv, dv[j].w * sv);
+      bsum[j] += (v.x + v.y) + (v.z + v.w);
+      float *p = st + ds_l[j];
+      *reinterpret_cast<float2 *>(p) = make_float2(v.x, v.y);
+      *reinterpret_cast<float2 *>(p + 2) = make_float2(v.z, v.w);
+    }
+  };
+
+  const int r1 = wave == 0 ? 0 : (wave == 2 ? 2 : 1);
+  const int r2 = wave == 0 ? 2 : (wave == 1 ? 2 : (wave == 2 ? 1 : 3));
+  const float s2 = wave == 1 ? 1.f : -1.f;
+  const float ga = wave == 3 ? 0.f : 1.f;
+  const float gb = wave == 0 ? 0.f : (wave == 1 ? 1.f : -1.f);
+  const float *xlane = smem + li * XS + 2 * lk;
+  const float *dlane = smem + XSZ + li * DS + 2 * lk;
+
+  f32x16 acc[4][DB];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
+
+  float *Tl = smem; // epilogue: [wave][k][r][lane]
+  if (b0 < b1) fetch(b0, 0);
+  int stage = 0;
+  for (int b = b0; b < b1; ++b) {
+    for (int band = 0; band < UPI; ++band) {
+      store(smem + stage * STAGE);
+      __syncthreads(); // the unit is in place; every wave has finished reading the stage the next store overwrites
+      {
+        int nb = b, nband = band + 1;
+        if (nband == UPI) { nband = 0; nb = min(b + 1, b1 - 1); } // (past the end: a unit is read again, unused)
+        fetch(nb, nband);
+      }
+      const float *xp = xlane + stage * STAGE, *dp = dlane + stage * STAGE;
+#pragma unroll
+      for (int kp = 0; kp < 8; ++kp) {
+        const int tyl = (2 * kp) / TW, cx = 2 * ((2 * kp) % TW);
+        float bv[4], av[DB][4];
+        {
+          const float2 p0 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r1) * LDW + cx);
+          const float2 p1 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r1) * LDW + cx + 2);
+          const float2 q0 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r2) * LDW + cx);
+          const float2 q1 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r2) * LDW + cx + 2);
+          const float t0 = fmaf(s2, q0.x, p0.x), t1 = fmaf(s2, q0.y, p0.y), t2 = fmaf(s2, q1.x, p1.x), t3 = fmaf(s2, q1.y, p1.y);
+          bv[0] = t0 - t2; bv[1] = t1 + t2; bv[2] = t2 - t1; bv[3] = t1 - t3;
+        }
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+          const float2 u0 = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * tyl) * W + cx);
+          const float2 u1 = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * tyl + 1) * W + cx);
+          const float e0 = fmaf(gb, u1.x, ga * u0.x), e1 = fmaf(gb, u1.y, ga * u0.y);
+          av[i][0] = e0; av[i][1] = e0 + e1; av[i][2] = e0 - e1; av[i][3] = -e1;
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+          for (int i = 0; i < DB; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][jj], bv[jj], acc[jj][i], 0, 0, 0);
+      }
+      stage ^= 1;
+    }
+    if (!NORM) continue;
+    // the example is complete: transform back, store, reduce the squares
+    float *gout = a.gstore + (long)b * a.gstride;
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < DB; ++i) {
+      __syncthreads(); // the last unit has been read by every wave (the area below lies over both stages)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float m0 = acc[0][i][r], m1 = acc[1][i][r], m2 = acc[2][i][r], m3 = acc[3][i][r];
+        const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
+        Tl[((wave * 3 + 0) * 16 + r) * 64 + lane] = m0 + hs;
+        Tl[((wave * 3 + 1) * 16 + r) * 64 + lane] = hd;
+        Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs + m3;
+        acc[0][i][r] = 0.f; acc[1][i][r] = 0.f; acc[2][i][r] = 0.f; acc[3][i][r] = 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = 4 * wave + rr;
+        const int d = 32 * i + 8 * wave + 4 * lk + rr;
+        float *o = gout + ((long)d * a.C + c0 + li) * 9;
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+          const float T0 = Tl[((0 * 3 + k) * 16 + r) * 64 + lane], T1 = Tl[((1 * 3 + k) * 16 + r) * 64 + lane];
+          const float T2 = Tl[((2 * 3 + k) * 16 + r) * 64 + lane], T3 = Tl[((3 * 3 + k) * 16 + r) * 64 + lane];
+          const float hs = 0.5f * (T1 + T2), hd = 0.5f * (T1 - T2);
+          const float y0 = T0 + hs, y1 = hd, y2 = hs + T3;
+          o[0 * 3 + k] = y0; o[1 * 3 + k] = y1; o[2 * 3 + k] = y2;
+          sq += y0 * y0 + y1 * y1 + y2 * y2;
+        }
+      }
+    }
+    // bias gradient of the example (first channel block only): 16 threads share an output channel
+#pragma unroll
+    for (int j = 0; j < DN; ++j) {
+      float s = bsum[j];
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 64);
+      if (blockIdx.x == 0 && (tid & 15) == 0) {
+        gout[(long)a.D * a.C * 9 + (tid >> 4) + 16 * j] = s;
+        sq += s * s;
+      }
+      bsum[j] = 0.f;
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) sq += __shfl_xor(sq, o, 64);
+    if (lane == 0) red[wave] = sq;
+    __syncthreads(); // also: every wave is done with the epilogue area before the next unit is stored over it
+    if (tid == 0) a.slots[(long)(a.slot0 + blockIdx.x) * a.slot_stride + b] = (red[0] + red[1]) + (red[2] + red[3]);
+  }
+  if (NORM) return;
+  // sum mode: one partial in the parameter layout
+  float *out = a.part + (long)blockIdx.y * a.part_stride;
+#pragma unroll
+  for (int i = 0; i < DB; ++i) {
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float m0 = acc[0][i][r], m1 = acc[1][i][r], m2 = acc[2][i][r], m3 = acc[3][i][r];
+      const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
+      Tl[((wave * 3 + 0) * 16 + r) * 64 + lane] = m0 + hs;
+      Tl[((wave * 3 + 1) * 16 + r) * 64 + lane] = hd;
+      Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs + m3;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int d = 32 * i + 8 * wave + 4 * lk + rr;
+      float *o = out + ((long)d * a.C + c0 + li) * 9;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const float T0 = Tl[((0 * 3 + k) * 16 + r) * 64 + lane], T1 = Tl[((1 * 3 + k) * 16 + r) * 64 + lane];
+        const float T2 = Tl[((2 * 3 + k) * 16 + r) * 64 + lane], T3 = Tl[((3 * 3 + k) * 16 + r) * 64 + lane];
+        const float hs = 0.5f * (T1 + T2), hd = 0.5f * (T1 - T2);
+        o[0 * 3 + k] = T0 + hs; o[1 * 3 + k] = hd; o[2 * 3 + k] = hs + T3;
+      }
+    }
+  }
+  if (blockIdx.x == 0) {
+#pragma unroll
+    for (int j = 0; j < DN; ++j) {
+      float s = bsum[j];
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 64);
+      if ((tid & 15) == 0) out[(long)a.D * a.C * 9 + (tid >> 4) + 16 * j] = s;
+    }
+  }
+}

@@ -147,6 +147,9 @@ struct Layer {
   // used), transformed weights [16][cpad][mpad]
   int wino_f = 0, wino_b = 0;
   bool wino_wg = false; // clipped sum of the weight gradient in the F(3x3, 2x2) form (8x8 planes)
+  bool u_f_planned = false; // pad-1 3x3 stride-1 layer with even planes: the minimal-filtering family applies
+  bool wino_wgu = false;    // weight gradient through conv_wino_wgrad_unit_kernel (16- and 32-wide planes)
+  bool wino_norm = false; // norm pass (with stored gradients) in the same form: 16- and 32-wide planes, 32 or 64 output channels
   float *u_f = nullptr, *u_b = nullptr;
   int uf_cpad = 0, uf_mpad = 0, ub_cpad = 0, ub_mpad = 0;
   std::vector<std::string> lab; // profiling labels "<kernel>#<layer index>" (stable after init)
@@ -303,6 +306,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
   // channels; with 32 it is ahead only for short channel loops; the grid must still fill the chip.
   if (l.dir_fwd && l.dir_bwd && g.PAD == 1 && g.H == g.OH && g.W == g.OW && (g.H & 1) == 0 && (g.W & 1) == 0 &&
       is_pow2(g.W / 2) && is_pow2((g.H / 2) * (g.W / 2)) && getenv("DP_STEP_NO_WINO") == nullptr) {
+    l.u_f_planned = true;
     const bool all = getenv("DP_STEP_WINO_ALL") != nullptr; // tests: the kernel for every eligible shape
     ConvWinoRegion rg;
     const bool fits = make_wino_region(rg, g.H, g.W) <= 9; // staging items per thread the kernels are built for
@@ -321,6 +325,10 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
     };
     // clipped sum of the weight gradient in the same form with the roles exchanged (kernel built for 8x8 planes)
     l.wino_wg = g.H == 8 && g.W == 8 && g.C % 32 == 0 && g.D % 64 == 0 && getenv("DP_STEP_NO_WINO_WG") == nullptr;
+    // and per band of 16 tiles on 16- and 32-wide planes: whole blocks of 32 input channels, 32 or 64 output channels
+    l.wino_wgu = g.C % 32 == 0 && (g.D == 32 || g.D == 64) &&
+                 ((g.W == 32 && g.D == 32 && g.H % 2 == 0) || (g.W == 16 && g.H % 4 == 0)) &&
+                 getenv("DP_STEP_NO_WINO_WG") == nullptr;
     l.wino_f = pick(g.C, g.D, false);
     l.wino_b = pick(g.D, g.C, true);
   }
@@ -667,6 +675,16 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
         l.geom.P >= 256 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
       // the order in which conv_s1_wgrad_kernel<3, 3, wg_db, wg_flat, false> holds the gradient in its accumulators
       GradOrder &o = l.gorder;
+      const ConvGeom &g = l.geom;
+      // per-example contraction in the F(3x3, 2x2) form (conv_wino_wgrad_norm_kernel): whole blocks of 32 input
+      // channels, 32 or 64 output channels, planes whose bands of 16 tiles the kernel is built for; its rows are in
+      // the parameter layout
+      l.wino_norm = l.wino_wgu;
+      if (l.wino_norm) {
+        o = GradOrder{};
+        o.C = g.C; o.D = g.D; o.KK = 9; o.flat = 2;
+        o.n_total = l.p_count;
+      } else {
       o.C = l.geom.C; o.D = l.geom.D; o.KK = 9; o.flat = l.wg_flat ? 1 : 0;
       o.WN = l.wg_flat ? 1 : 2;                       // wg_db is 1 or 2 here
       o.NW = l.wg_flat ? 1 : (l.wg_db == 1 ? 2 : 4);
@@ -674,6 +692,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       const long cblocks = l.wg_flat ? 1 : ceil_div(l.geom.C, 32);
       o.n_w = cblocks * o.NW * o.NBW * 1024;
       o.n_total = o.n_w + o.D;
+      }
       rc = dev_alloc(c, &l.gst, (size_t)mb * o.n_total);
     }
     // the same route for convolutions on the generic contraction (other strides / filter sizes): its per-example
@@ -1070,6 +1089,20 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
               hipLaunchKernelGGL((conv_gram_norm_kernel<4, 4>), grid, block, 0, st, ga);
             });
           }
+        } else if (priv && l.wino_norm && l.gst && aligned16(lin)) {
+          const int cblocks = g.C / 32;
+          ConvWinoWgUnitArgs a{};
+          a.x = lin; a.dy = l.g; a.slots = c->slots; a.gstore = l.gst; a.slot_stride = slot_stride;
+          a.gstride = l.gorder.n_total; a.slot0 = slot_next;
+          a.B = B; a.C = g.C; a.D = g.D; a.H = g.H;
+          a.ex_per_block = std::max(1, (int)((long)B * cblocks / 2048));
+          slot_next += cblocks;
+          dim3 grid(cblocks, ceil_div(B, a.ex_per_block)), block(256);
+          Ln(LL("conv_wgrad_norm"), grid, block, [&](hipStream_t st) {
+            if (g.W == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<32, 1, 1, true>), grid, block, 0, st, a);
+            else if (g.D == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 1, true>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 2, true>), grid, block, 0, st, a);
+          });
         } else if (priv && l.dir_wg && aligned16(lin)) {
           // one round of resident workgroups, each walking through its run of examples: the next
           // example's tiles are fetched while the current one is multiplied and reduced
@@ -1273,6 +1306,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           Ln(LL("conv_weighted_sum"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(weighted_sum_kernel, grid, block, 0, st, (const float *)l.gst, gstride, sc, l.part,
                                l.p_count, l.gorder, B, eps);
+          });
+          break;
+        }
+        if (l.wino_wgu && aligned16(lin) && aligned16(l.g)) {
+          const int cblocks = g.C / 32;
+          int want = std::max(1, std::min(l.max_split, 512 / cblocks));
+          const int eps = ceil_div(B, want);
+          nsplit = ceil_div(B, eps);
+          ConvWinoWgUnitArgs a{};
+          a.x = lin; a.dy = l.g; a.scale = sc; a.part = l.part; a.part_stride = l.p_count;
+          a.B = B; a.C = g.C; a.D = g.D; a.H = g.H; a.ex_per_block = eps;
+          dim3 grid(cblocks, nsplit), block(256);
+          Ln(LL("conv_clipped_sum"), grid, block, [&](hipStream_t st) {
+            if (g.W == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<32, 1, 1, false>), grid, block, 0, st, a);
+            else if (g.D == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 1, false>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 2, false>), grid, block, 0, st, a);
           });
           break;
         }
