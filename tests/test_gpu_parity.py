@@ -206,7 +206,10 @@ def test_minimal_filtering_route(monkeypatch):
     covers element by element (the library keeps that kernel for launches that fill the chip; here it is forced):
     4x4, 8x8 and 16x16 planes, channel counts that are no multiples of the 8-channel chunk or of the 32 / 64 output
     channels of a workgroup, more than 64 output channels (several channel blocks), batches that end inside a
-    workgroup's 32 tiles, a 3-channel first layer.  (The full-size cases run it wherever the library selects it.)"""
+    workgroup's 32 tiles, a 3-channel first layer.  (The full-size cases run it wherever the library selects it.)
+    The benchmark-shaped cases also take the weight-gradient kernels of the same family: per-example norm pass with
+    stored gradients on 16- and 32-wide planes, clipped sums on 8x8 planes, and the batch sums of the non-private
+    step; the last part switches the whole family off at full batch."""
     cases = (("tiny_conv_gram", 9), ("tiny_conv_store", 6), ("tiny_conv_wide", 13), ("tiny_conv_wide", 1))
     monkeypatch.setenv("DP_STEP_WINO_ALL", "1")
     for name, batch in cases:
