@@ -310,7 +310,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
     const bool all = getenv("DP_STEP_WINO_ALL") != nullptr; // tests: the kernel for every eligible shape
     ConvWinoRegion rg;
     const bool fits = make_wino_region(rg, g.H, g.W) <= 9; // staging items per thread the kernels are built for
-    auto pick = [&](int Cin, int M, bool bwd) {
+    auto pick = [&](int Cin, int M) {
       int db = M > 32 ? 2 : 1;
       if (!fits) return 0;
       if (all) return db;
@@ -320,7 +320,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       if (groups * ceil_div(M, 32 * db) < 512) return 0;
       // 32 output channels per workgroup: the transform is amortised over half the multiplies, and the epilogue
       // over the channel loop only
-      if (db == 1 && Cin < (bwd ? 64 : 32)) return 0;
+      if (db == 1 && Cin < 32) return 0;
       return db;
     };
     // clipped sum of the weight gradient in the same form with the roles exchanged (kernel built for 8x8 planes)
@@ -329,8 +329,8 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
     l.wino_wgu = g.C % 32 == 0 && (g.D == 32 || g.D == 64) &&
                  ((g.W == 32 && g.D == 32 && g.H % 2 == 0) || (g.W == 16 && g.H % 4 == 0)) &&
                  getenv("DP_STEP_NO_WINO_WG") == nullptr;
-    l.wino_f = pick(g.C, g.D, false);
-    l.wino_b = pick(g.D, g.C, true);
+    l.wino_f = pick(g.C, g.D);
+    l.wino_b = pick(g.D, g.C);
   }
   // per-example norm from Gram matrices: P^2 (9C + D) multiply-adds instead of 9 C D P, for the two plane sizes
   // the kernel is built for (pad 1, so the input plane equals the output plane)
