@@ -239,6 +239,29 @@ def test_minimal_filtering_route(monkeypatch):
     assert np.allclose(gn, ref["norms"], rtol=1e-4, atol=1e-7)
 
 
+def test_weight_gradients_in_minimal_filtering_form():
+    """Weight-gradient kernels of the F(3x3, 2x2) family at shapes the benchmark configurations do not have: 32
+    output channels on 16x16 planes (norm pass with stored gradients, and the batch sum of the non-private step), 64
+    on 16x16, and on 8x8 planes a layer whose norm does not come from Gram matrices, with one block of 64 output
+    channels; then the same network with these routes switched off."""
+    m = W.model(W.image_input(32, 16, 16), [
+        W.conv2d(32, 32, 3, stride=1, pad=1, act="tanh"), W.conv2d(32, 64, 3, stride=1, pad=1, act="tanh"),
+        W.maxpool2d(2, 2), W.conv2d(64, 64, 3, stride=1, pad=1, act="relu"), W.avgpool2d(2, 2),
+        W.dense(64 * 4 * 4, 3)], 3)
+    x, y, theta = _case(m, 5, seed=46)
+    _check_all_regimes(m, x, y, theta, "planes16x16+8x8/weight gradients")
+
+
+def test_weight_gradients_direct_kernels_on_the_same_network(monkeypatch):
+    monkeypatch.setenv("DP_STEP_NO_WINO_WG", "1")
+    m = W.model(W.image_input(32, 16, 16), [
+        W.conv2d(32, 32, 3, stride=1, pad=1, act="tanh"), W.conv2d(32, 64, 3, stride=1, pad=1, act="tanh"),
+        W.maxpool2d(2, 2), W.conv2d(64, 64, 3, stride=1, pad=1, act="relu"), W.avgpool2d(2, 2),
+        W.dense(64 * 4 * 4, 3)], 3)
+    x, y, theta = _case(m, 5, seed=46)
+    _check_all_regimes(m, x, y, theta, "planes16x16+8x8/direct weight gradients")
+
+
 def test_long_sequence_stored_gradients():
     """Sequences of 128 steps and more: the LSTM norm contraction stores each example's gradient and the clipped sum
     is a weighted sum of the rows (both LSTM variants)."""
