@@ -16,7 +16,9 @@
  * A^T diag(s) Delta.  Only where writing and re-reading an example's gradient is
  * cheaper than contracting it again (large planes, long sequences) does the
  * workspace hold a [batch][layer parameters] block, summed with the clip
- * factors afterwards.
+ * factors afterwards.  Pad-1 3x3 convolutions (Section 2.1) may be evaluated in
+ * the minimal-filtering form (fewer multiplies, the same sums up to fp32
+ * rounding); results are held to the same tolerance either way.
  *
  * Pointers marked "device" are HIP device memory owned by the caller (the
  * library never frees them and keeps no reference after the call's stream
