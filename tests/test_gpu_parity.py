@@ -128,6 +128,30 @@ def test_context_reuse_and_smaller_batches():
     st.dp_step_free()
 
 
+def test_context_reuse_with_minimal_filtering_kernels(monkeypatch):
+    """One context planned for the largest batch serves smaller ones: the minimal-filtering kernels (forward,
+    backward-data with the pool in the epilogue, weight gradients) size their grids and split counts from the batch
+    of the call, the plan from the batch of the context."""
+    from paper_2010_09063_amd import DpStep
+    monkeypatch.setenv("DP_STEP_WINO_ALL", "1")
+    m = W.model(W.image_input(32, 16, 16), [
+        W.conv2d(32, 32, 3, stride=1, pad=1, act="tanh"), W.conv2d(32, 64, 3, stride=1, pad=1, act="tanh"),
+        W.maxpool2d(2, 2), W.conv2d(64, 64, 3, stride=1, pad=1, act="relu"), W.avgpool2d(2, 2),
+        W.dense(64 * 4 * 4, 3)], 3)
+    st = DpStep(m, 9)
+    for batch in (9, 2, 7, 1):
+        x, y, theta = _case(m, batch, seed=50 + batch)
+        x, y, _ = clear_pool_examples(m, theta, x, y, O.dp_step)
+        ref = O.dp_step(m, theta, x, y, 5.0, 0.0, 0)
+        out, gn = run_gpu(m, theta, x, y, 5.0, 0.0, 0, stepper=st)
+        assert rel_l2(out, ref["clipped_sum"]) <= TOL, batch
+        assert np.allclose(gn, ref["norms"], rtol=1e-4, atol=1e-7)
+        refn = O.dp_step(m, theta, x, y, 5.0, 0.0, 0, clip=False)
+        outn, _ = run_gpu(m, theta, x, y, 5.0, 0.0, 0, private=False, stepper=st)
+        assert rel_l2(outn, refn["clipped_sum"]) <= TOL, batch
+    st.dp_step_free()
+
+
 def test_argument_errors():
     import torch
     from paper_2010_09063_amd import DpStep, DpStepError
