@@ -316,8 +316,10 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       if (all) return db;
       if (Cin < 16) return 0;
       const long groups = ((long)maxB * (g.H / 2) * (g.W / 2) + 31) / 32;
+      // 64 output channels per workgroup only where that still fills the chip; below about half a workgroup per CU
+      // the direct kernel with its narrower tiles measured as fast or faster
       if (db == 2 && groups * ceil_div(M, 64) < 512) db = 1;
-      if (groups * ceil_div(M, 32 * db) < 512) return 0;
+      if (groups * ceil_div(M, 32 * db) < 128) return 0;
       // 32 output channels per workgroup: the transform is amortised over half the multiplies, and the epilogue
       // over the channel loop only
       if (db == 1 && Cin < 32) return 0;
