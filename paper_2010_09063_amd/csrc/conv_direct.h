@@ -61,8 +61,8 @@ __global__ void conv_weight_layout_kernel(const float *__restrict__ params, cons
     const int d = i / (L.C * KK), r = i - d * L.C * KK;
     const int c = r / KK, tap = r - c * KK;
     const float v = params[L.w_off + i];
-    L.wt_f[((long)c * KK + tap) * L.Dp + d] = v;
-    L.wt_b[((long)d * KK + (KK - 1 - tap)) * L.Cp + c] = v;
+    if (L.wt_f) L.wt_f[((long)c * KK + tap) * L.Dp + d] = v; // (null: that correlation runs on another kernel)
+    if (L.wt_b) L.wt_b[((long)d * KK + (KK - 1 - tap)) * L.Cp + c] = v;
   }
 }
 

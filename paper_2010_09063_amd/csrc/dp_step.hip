@@ -833,9 +833,13 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       for (int i = 0; i < nL; ++i) {
         Layer &l = c->L[i];
         if (l.d.kind != DP_CONV2D || !(l.dir_fwd || l.dir_bwd)) continue;
+        // only the layouts a direct kernel of this step reads (the minimal-filtering kernels have their own)
+        float *need_f = (l.dir_fwd && !l.u_f) ? l.wt_f : nullptr;
+        float *need_b = (l.dir_bwd && !l.u_b && i > 0) ? l.wt_b : nullptr;
+        if (!need_f && !need_b) continue;
         const ConvGeom &g = l.geom;
         auto &e = la.l[la.n++];
-        e.w_off = l.p_off; e.wt_f = l.wt_f; e.wt_b = l.wt_b; e.D = g.D; e.C = g.C;
+        e.w_off = l.p_off; e.wt_f = need_f; e.wt_b = need_b; e.D = g.D; e.C = g.C;
         e.Dp = (g.D + 3) & ~3; e.Cp = (g.C + 3) & ~3;
         biggest = std::max(biggest, g.D * g.CKK);
         if (la.n == CONV_LAYOUT_MAX) flush();
