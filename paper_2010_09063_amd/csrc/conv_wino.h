@@ -534,191 +534,28 @@ typedef WinoGeom<16, 8, 1, 24> WinoG16;
 typedef WinoGeom<8, 8, 2, 12> WinoG8;
 
 // ---------------------------------------------------------------------------------------------------------------
-// Clipped sum of the weight gradient of a 3x3 / stride-1 / pad-1 layer on 8x8 planes in the minimal-filtering form
-// with the roles exchanged, F(3x3, 2x2): per tile the 3x3 block  G[ky][kx] = sum_{a,b} dy[a][b] xpatch[ky+a][kx+b]
-// is  A^T [ (G' dy G'^T) (.) (B^T xpatch B) ] A  with the same B^T as above and
+// Weight gradients of a 3x3 / stride-1 / pad-1 layer in the minimal-filtering form with the roles exchanged,
+// F(3x3, 2x2): per tile the 3x3 block  G[ky][kx] = sum_{a,b} dy[a][b] xpatch[ky+a][kx+b]  is
+//   A^T [ (G' dy G'^T) (.) (B^T xpatch B) ] A    with the same B^T as above and
 //   G' = [1 0; 1 1; 1 -1; 0 -1]      A^T = [1 .5 .5 0; 0 .5 -.5 0; 0 .5 .5 1]
 // (the transposed algorithm of F(2x2, 3x3)).  The 16 components are linear in the products, so they are summed over
-// all tiles of all examples of the workgroup's range -- with the clip factor s_b multiplied into dy while it is
-// staged (DPSGD item 3: sum of the clipped per-example gradients) -- and transformed back once, in the epilogue:
-// 16 instead of 36 multiplies per tile and (d, c) pair.  MFMA: M = output channel d (64 per workgroup), N = input
-// channel c (32 per workgroup), K = tile pair; wave w owns transform row w.  Every lane transforms its own
-// operands from the raw planes in LDS (x: haloed 10x10 planes at a channel stride of 102 words, dy: 8x8 planes at a
-// stride of 66 words -- lanes walk channels, and these strides put the 16 lanes served together on 32 different
-// banks).  One example per barrier (64 multiplies per wave), the next example's planes in registers meanwhile.
-// Output: one split-K partial in the parameter layout, W[d][c][3][3] then bias[d] (the bias gradient, sum of the
-// scaled dy, is accumulated while staging by the workgroups of the first channel block).
-struct ConvWinoWgArgs {
-  const float *x;     // layer input [B, C, 8, 8]
-  const float *dy;    // gradient w.r.t. the layer's pre-activation output [B, D, 8, 8]
-  const float *scale; // clip factors s[b] (a vector of ones when nothing is clipped)
-  float *part;        // partials: split s writes part + s * part_stride
-  long part_stride;
-  int B, C, D;        // C a multiple of 32, D a multiple of 64
-  int ex_per_split;
-};
-
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void conv_wino_wgrad8_kernel(const ConvWinoWgArgs a) {
-  constexpr int XS = 102, DS = 66, XSZ = 32 * XS, DSZ = 64 * DS, STAGE = XSZ + DSZ;
-  __shared__ __attribute__((aligned(16))) float smem[2 * STAGE]; // two stages; the epilogue uses 12288 words of it
-  static_assert(2 * STAGE >= 4 * 3 * 16 * 64, "epilogue area fits");
-  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int c0 = blockIdx.x * 32, d0 = blockIdx.y * 64;
-  const int b0 = blockIdx.z * a.ex_per_split, b1 = min(b0 + a.ex_per_split, a.B);
-
-  for (int i = tid; i < 2 * STAGE; i += 256) smem[i] = 0.f; // halo words stay zero
-  // staging items: x 2 x float4 (channel q/16, row (q%16)/2, half q%2), dy 4 x float4 (channel q/16, part q%16)
-  int xs_l[2], ds_l[4];
-  unsigned xs_g[2], ds_g[4];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int q = tid + j * 256, ch = q >> 4, row = (q & 15) >> 1, half = q & 1;
-    xs_l[j] = ch * XS + (row + 1) * 10 + 1 + 4 * half;
-    xs_g[j] = 4u * (unsigned)(ch * 64 + row * 8 + 4 * half);
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int q = tid + j * 256, ch = q >> 4, part = q & 15;
-    ds_l[j] = XSZ + ch * DS + 4 * part;
-    ds_g[j] = 4u * (unsigned)(ch * 64 + 4 * part);
-  }
-  float4 xv[2], dv[4];
-  auto fetch = [&](int b) {
-    const float *xb = a.x + ((long)b * a.C + c0) * 64;
-    const float *db = a.dy + ((long)b * a.D + d0) * 64;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) xv[j] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(xb) + xs_g[j]);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) dv[j] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(db) + ds_g[j]);
-  };
-  float bsum[4] = {0.f, 0.f, 0.f, 0.f};
-  auto store = [&](float *st, float s) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      float *p = st + xs_l[j];
-      p[0] = xv[j].x; p[1] = xv[j].y; p[2] = xv[j].z; p[3] = xv[j].w;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float4 v = make_float4(dv[j].x * s, dv[j].y * s, dv[j].z * s, dv[j].w * s);
-      bsum[j] += (v.x + v.y) + (v.z + v.w);
-      float *p = st + ds_l[j];
-      *reinterpret_cast<float2 *>(p) = make_float2(v.x, v.y);
-      *reinterpret_cast<float2 *>(p + 2) = make_float2(v.z, v.w);
-    }
-  };
-
-  // the wave's transform row:  x patch rows  t = d[r1] + s2 * d[r2];  dy rows  e = ga * dy[0] + gb * dy[1]
-  const int r1 = wave == 0 ? 0 : (wave == 2 ? 2 : 1);
-  const int r2 = wave == 0 ? 2 : (wave == 1 ? 2 : (wave == 2 ? 1 : 3));
-  const float s2 = wave == 1 ? 1.f : -1.f;
-  const float ga = wave == 3 ? 0.f : 1.f;
-  const float gb = wave == 0 ? 0.f : (wave == 1 ? 1.f : -1.f);
-  // tile 2*kp + lk:  tile row kp / 2, tile column 2 * (kp % 2) + lk
-  const float *xlane = smem + li * XS + 2 * lk;       // + stage + (2*ty + r) * 10 + 4 * (kp % 2) (+ 2)
-  const float *dlane = smem + XSZ + li * DS + 2 * lk; // + stage + 32*i*DS + (2*ty + row) * 8 + 4 * (kp % 2)
-
-  f32x16 acc[4][2];
-#pragma unroll
-  for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
-
-  if (b0 < b1) fetch(b0);
-  __syncthreads(); // the zero fill is complete
-  int stage = 0;
-  for (int b = b0; b < b1; ++b) {
-    store(smem + stage * STAGE, a.scale[b]);
-    __syncthreads(); // example b is in place; every wave has finished reading the stage the next store overwrites
-    fetch(min(b + 1, b1 - 1)); // (the last example is read again: no branch around loads)
-    const float *xp = xlane + stage * STAGE, *dp = dlane + stage * STAGE;
-#pragma unroll
-    for (int kp = 0; kp < 8; ++kp) {
-      const int ty = kp >> 1, cx = 4 * (kp & 1);
-      float bv[4], av[2][4];
-      {
-        const float2 p0 = *reinterpret_cast<const float2 *>(xp + (2 * ty + r1) * 10 + cx);
-        const float2 p1 = *reinterpret_cast<const float2 *>(xp + (2 * ty + r1) * 10 + cx + 2);
-        const float2 q0 = *reinterpret_cast<const float2 *>(xp + (2 * ty + r2) * 10 + cx);
-        const float2 q1 = *reinterpret_cast<const float2 *>(xp + (2 * ty + r2) * 10 + cx + 2);
-        const float t0 = fmaf(s2, q0.x, p0.x), t1 = fmaf(s2, q0.y, p0.y), t2 = fmaf(s2, q1.x, p1.x), t3 = fmaf(s2, q1.y, p1.y);
-        bv[0] = t0 - t2; bv[1] = t1 + t2; bv[2] = t2 - t1; bv[3] = t1 - t3;
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const float2 u0 = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * ty) * 8 + cx);
-        const float2 u1 = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * ty + 1) * 8 + cx);
-        const float e0 = fmaf(gb, u1.x, ga * u0.x), e1 = fmaf(gb, u1.y, ga * u0.y);
-        av[i][0] = e0; av[i][1] = e0 + e1; av[i][2] = e0 - e1; av[i][3] = -e1;
-      }
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][jj], bv[jj], acc[jj][i], 0, 0, 0);
-    }
-    stage ^= 1;
-  }
-
-  // epilogue per block of 32 output channels: fold the wave's row with A (4 components -> 3 numbers), meet in LDS,
-  //   Y[0][k] = T0 + (T1 + T2)/2,  Y[1][k] = (T1 - T2)/2,  Y[2][k] = (T1 + T2)/2 + T3
-  float *Tl = smem; // [wave][k][r][lane]
-  float *out = a.part + (long)blockIdx.z * a.part_stride;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float m0 = acc[0][i][r], m1 = acc[1][i][r], m2 = acc[2][i][r], m3 = acc[3][i][r];
-      const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
-      Tl[((wave * 3 + 0) * 16 + r) * 64 + lane] = m0 + hs;
-      Tl[((wave * 3 + 1) * 16 + r) * 64 + lane] = hd;
-      Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs + m3;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = 4 * wave + rr;
-      const int d = d0 + 32 * i + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
-      float *o = out + ((long)d * a.C + c0 + li) * 9;
-#pragma unroll
-      for (int k = 0; k < 3; ++k) {
-        const float T0 = Tl[((0 * 3 + k) * 16 + r) * 64 + lane], T1 = Tl[((1 * 3 + k) * 16 + r) * 64 + lane];
-        const float T2 = Tl[((2 * 3 + k) * 16 + r) * 64 + lane], T3 = Tl[((3 * 3 + k) * 16 + r) * 64 + lane];
-        const float hs = 0.5f * (T1 + T2), hd = 0.5f * (T1 - T2);
-        o[0 * 3 + k] = T0 + hs;
-        o[1 * 3 + k] = hd;
-        o[2 * 3 + k] = hs + T3;
-      }
-    }
-  }
-  // bias gradient: thread sums of the scaled dy, over the 16 threads that share an output channel
-  if (blockIdx.x == 0) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      float s = bsum[j];
-#pragma unroll
-      for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 64);
-      if ((tid & 15) == 0) out[(long)a.D * a.C * 9 + d0 + (tid >> 4) + 16 * j] = s;
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------------------------------------
-// The same F(3x3, 2x2) contraction on larger planes, in two modes.
+// tiles and transformed back once per example or once per run of examples: 16 instead of 36 multiplies per tile and
+// (d, c) pair.  MFMA: M = output channel d (32*DB per workgroup), N = input channel c (32 per workgroup), K = tile
+// pair; wave w owns transform row w.  Every lane transforms its own operands from the raw planes in LDS (lanes walk
+// channels; the planes sit at channel strides = 2 mod 4 words, which puts the 16 lanes served together on 32
+// different banks with 8-byte reads).  Two modes:
 // NORM (the norm pass, Section 1 item 2a: one gradient per example): after the last tile of an example the 16
 // components are transformed back, the example's gradient goes to its row of the stored-gradient buffer in the
 // parameter layout (W[d][c][3][3], then bias[d]), its squares are reduced in a fixed order into the example's slot of
 // this channel block, and the accumulators start again at zero.
 // Otherwise (sum over a run of examples, item 3): dy is scaled by the example's clip factor while it is staged, the
-// components are summed over the whole run and transformed back once into one split-K partial.
+// components are summed over the whole run and transformed back once into one split-K partial (parameter layout; the
+// bias gradient, the sum of the scaled dy, is accumulated while staging by the workgroups of the first channel block).
 // A unit of work is 16 tiles = 64 output pixels: TR tile rows of a W-wide plane (W = 32: one tile row, 16: two, 8:
 // the whole 8x8 plane); a unit's x band carries its own halo rows from the neighbouring bands (zero rows outside
-// the plane) and zero halo columns, all rewritten with every unit.  One workgroup = one block of 32 input channels
-// x all 32*DB output channels, for a run of examples.
+// the plane) and zero halo columns, all rewritten with every unit; one barrier per unit, the next unit's planes in
+// registers meanwhile.  One workgroup = one block of 32 input channels x one block of 32*DB output channels, for a
+// run of examples.
 struct ConvWinoWgUnitArgs {
   const float *x;      // layer input [B, C, H, W]
   const float *dy;     // [B, D, H, W]
@@ -728,7 +565,8 @@ struct ConvWinoWgUnitArgs {
   float *part;         // sum mode: the run blockIdx.y writes part + blockIdx.y * part_stride
   long slot_stride, gstride, part_stride;
   int slot0;
-  int B, C, D, H;      // C a multiple of 32, D = 32 * DB, H a multiple of 2 * TR
+  int B, C, D, H;      // C a multiple of 32; D a multiple of 32 * DB (NORM: D = 32 * DB), blockIdx.z = block of output
+                       // channels; H a multiple of 2 * TR
   int ex_per_block;
 };
 
@@ -746,7 +584,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
   __shared__ float red[4];
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int c0 = blockIdx.x * 32;
+  const int c0 = blockIdx.x * 32, d0 = blockIdx.z * 32 * DB; // (the norm pass runs with one block of output channels)
   const int b0 = blockIdx.y * a.ex_per_block, b1 = min(b0 + a.ex_per_block, a.B);
   const int UPI = (a.H / 2) / TR_; // units per image
   const int HW = a.H * W;
@@ -777,7 +615,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
     if (!NORM) sv = a.scale[b];
     const int r0 = band * 2 * TR_;
     const float *xb = a.x + ((long)b * a.C + c0) * HW;
-    const float *db = a.dy + ((long)b * a.D) * HW + (long)r0 * W;
+    const float *db = a.dy + ((long)b * a.D + d0) * HW + (long)r0 * W;
 #pragma unroll
     for (int j = 0; j < XN; ++j) {
       const int ih = r0 - 1 + xs_rr[j];
@@ -940,7 +778,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
       const int r = 4 * wave + rr;
-      const int d = 32 * i + 8 * wave + 4 * lk + rr;
+      const int d = d0 + 32 * i + 8 * wave + 4 * lk + rr;
       float *o = out + ((long)d * a.C + c0 + li) * 9;
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
@@ -957,7 +795,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
       float s = bsum[j];
 #pragma unroll
       for (int o = 1; o < 16; o <<= 1) s += __shfl_xor(s, o, 64);
-      if ((tid & 15) == 0) out[(long)a.D * a.C * 9 + (tid >> 4) + 16 * j] = s;
+      if ((tid & 15) == 0) out[(long)a.D * a.C * 9 + d0 + (tid >> 4) + 16 * j] = s;
     }
   }
 }

@@ -146,9 +146,9 @@ struct Layer {
   // forward / backward-data by the F(2x2, 3x3) minimal-filtering kernel: output-channel blocks per workgroup (0: not
   // used), transformed weights [16][cpad][mpad]
   int wino_f = 0, wino_b = 0;
-  bool wino_wg = false; // clipped sum of the weight gradient in the F(3x3, 2x2) form (8x8 planes)
+  bool wino_wg = false; // batch sum of the weight gradient in the F(3x3, 2x2) form on 8x8 planes (any multiple of 64 output channels)
   bool u_f_planned = false; // pad-1 3x3 stride-1 layer with even planes: the minimal-filtering family applies
-  bool wino_wgu = false;    // weight gradient through conv_wino_wgrad_unit_kernel (16- and 32-wide planes)
+  bool wino_wgu = false;    // per-example and batch weight gradient in that form on 16- and 32-wide planes (32 / 64 output channels)
   bool wino_norm = false; // norm pass (with stored gradients) in the same form: 16- and 32-wide planes, 32 or 64 output channels
   float *u_f = nullptr, *u_b = nullptr;
   int uf_cpad = 0, uf_mpad = 0, ub_cpad = 0, ub_mpad = 0;
@@ -325,7 +325,7 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       if (db == 1 && Cin < 32) return 0;
       return db;
     };
-    // clipped sum of the weight gradient in the same form with the roles exchanged (kernel built for 8x8 planes)
+    // weight gradients in the same form with the roles exchanged (conv_wino_wgrad_unit_kernel): batch sums on 8x8 planes
     l.wino_wg = g.H == 8 && g.W == 8 && g.C % 32 == 0 && g.D % 64 == 0 && getenv("DP_STEP_NO_WINO_WG") == nullptr;
     // and per band of 16 tiles on 16- and 32-wide planes: whole blocks of 32 input channels, 32 or 64 output channels
     l.wino_wgu = g.C % 32 == 0 && (g.D == 32 || g.D == 64) &&
@@ -1315,33 +1315,22 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
           break;
         }
-        if (l.wino_wgu && aligned16(lin) && aligned16(l.g)) {
-          const int cblocks = g.C / 32;
-          int want = std::max(1, std::min(l.max_split, 512 / cblocks));
+        if ((l.wino_wgu || l.wino_wg) && aligned16(lin) && aligned16(l.g)) {
+          // batch sum in the F(3x3, 2x2) form: blocks of 32 input x 32 or 64 output channels, splits over examples
+          const int db = (g.D % 64 == 0) ? 2 : 1;
+          const int tiles = (g.C / 32) * (g.D / (32 * db));
+          int want = std::max(1, std::min(l.max_split, 512 / tiles));
           const int eps = ceil_div(B, want);
           nsplit = ceil_div(B, eps);
           ConvWinoWgUnitArgs a{};
           a.x = lin; a.dy = l.g; a.scale = sc; a.part = l.part; a.part_stride = l.p_count;
           a.B = B; a.C = g.C; a.D = g.D; a.H = g.H; a.ex_per_block = eps;
-          dim3 grid(cblocks, nsplit), block(256);
+          dim3 grid(g.C / 32, nsplit, g.D / (32 * db)), block(256);
           Ln(LL("conv_clipped_sum"), grid, block, [&](hipStream_t st) {
-            if (g.W == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<32, 1, 1, false>), grid, block, 0, st, a);
-            else if (g.D == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 1, false>), grid, block, 0, st, a);
+            if (g.W == 8) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<8, 4, 2, false>), grid, block, 0, st, a);
+            else if (g.W == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<32, 1, 1, false>), grid, block, 0, st, a);
+            else if (db == 1) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 1, false>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 2, false>), grid, block, 0, st, a);
-          });
-          break;
-        }
-        if (l.wino_wg && aligned16(lin) && aligned16(l.g)) {
-          const int tiles = (g.C / 32) * (g.D / 64);
-          int want = std::max(1, std::min(l.max_split, 512 / tiles));
-          const int eps = ceil_div(B, want);
-          nsplit = ceil_div(B, eps);
-          ConvWinoWgArgs a{};
-          a.x = lin; a.dy = l.g; a.scale = sc; a.part = l.part; a.part_stride = l.p_count;
-          a.B = B; a.C = g.C; a.D = g.D; a.ex_per_split = eps;
-          dim3 grid(g.C / 32, g.D / 64, nsplit), block(256);
-          Ln(LL("conv_clipped_sum"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(conv_wino_wgrad8_kernel, grid, block, 0, st, a);
           });
           break;
         }
