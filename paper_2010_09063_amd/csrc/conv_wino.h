@@ -91,6 +91,73 @@ __global__ void wino_weight_kernel(const float *__restrict__ params, const WinoL
   }
 }
 
+// Output stage shared by the forward / backward-data kernels.  Row w of  M A:  t0 = m0 + m1 + m2,  t1 = m1 - m2 - m3
+// (each wave folds its own transform row); the four rows meet in LDS (Tl, [wave][k][r][lane], 32 KB) and
+// Y[0][k] = T0 + T1 + T2,  Y[1][k] = T1 - T2 - T3; wave w finishes accumulator rows 4w .. 4w+3 of every block of 32
+// output channels: bias + activation (and the 2x2 pool that follows, if any) or the derivative of the producing
+// activation, 8-byte stores.  (img, ty, tx): the lane's tile; lanes past the batch only take part in the barriers.
+template <int DB>
+DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)[4][DB], int wave, int lane, int m0,
+                           int img, bool img_ok, int ty, int tx, int W) {
+  const int lk = lane >> 5;
+  const int HW = a.H * W;
+  const bool fwd = a.bias != nullptr;
+  const bool need_side = !fwd && a.act;
+#pragma unroll
+  for (int i = 0; i < DB; ++i) {
+    __syncthreads(); // every wave is done with the LDS contents of the previous phase
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][i][r] + acc[1][i][r] + acc[2][i][r];
+      Tl[((wave * 2 + 1) * 16 + r) * 64 + lane] = acc[1][i][r] - acc[2][i][r] - acc[3][i][r];
+    }
+    __syncthreads();
+    if (!img_ok) continue;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+      if (m >= a.M) continue;
+      float T[4][2];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
+      float2 y0, y1;
+      y0.x = T[0][0] + T[1][0] + T[2][0];
+      y0.y = T[0][1] + T[1][1] + T[2][1];
+      y1.x = T[1][0] - T[2][0] - T[3][0];
+      y1.y = T[1][1] - T[2][1] - T[3][1];
+      const long o = ((long)img * a.M + m) * HW + (2 * ty) * W + 2 * tx;
+      if (fwd) {
+        const float bv = a.bias[m];
+        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
+        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
+        if (a.pool) {
+          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
+          if (a.pool == 1) {
+            float best = y0.x; int bi = 0;
+            if (y0.y > best) { best = y0.y; bi = 1; }
+            if (y1.x > best) { best = y1.x; bi = 2; }
+            if (y1.y > best) { best = y1.y; bi = 3; }
+            a.pool_out[po] = best;
+            a.pool_arg[po] = (uint8_t)bi;
+          } else {
+            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+          }
+        }
+      } else if (need_side) {
+        const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
+        const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
+        y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
+        y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
+      }
+      *reinterpret_cast<float2 *>(a.out + o) = y0;
+      *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+    }
+  }
+}
+
 struct ConvWinoRegion {
   int NIMG, ROWS;     // images per workgroup (tiles per image < 32) or 1; pixel rows per workgroup
   int LDW, IMGPL, RS; // W + 2; (ROWS + 2) * LDW; NIMG * IMGPL (all even)
@@ -247,62 +314,7 @@ void conv_wino_kernel(const ConvWinoArgs a, const ConvWinoRegion rg) {
     buf ^= 1;
   }
 
-  const bool fwd = a.bias != nullptr;
-  const bool need_side = !fwd && a.act;
-  float *Tl = Vl; // [wave][k][r][lane]
-#pragma unroll
-  for (int i = 0; i < DB; ++i) {
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][i][r] + acc[1][i][r] + acc[2][i][r];
-      Tl[((wave * 2 + 1) * 16 + r) * 64 + lane] = acc[1][i][r] - acc[2][i][r] - acc[3][i][r];
-    }
-    __syncthreads();
-    if (!img_ok) continue;
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = 4 * wave + rr;
-      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr;
-      if (m >= a.M) continue;
-      float T[4][2];
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-#pragma unroll
-        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
-      float2 y0, y1;
-      y0.x = T[0][0] + T[1][0] + T[2][0];
-      y0.y = T[0][1] + T[1][1] + T[2][1];
-      y1.x = T[1][0] - T[2][0] - T[3][0];
-      y1.y = T[1][1] - T[2][1] - T[3][1];
-      const long o = ((long)img * a.M + m) * HW + (2 * ty) * a.W + 2 * tx;
-      if (fwd) {
-        const float bv = a.bias[m];
-        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
-        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
-        if (a.pool) {
-          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (a.W >> 1) + tx;
-          if (a.pool == 1) {
-            float best = y0.x; int bi = 0;
-            if (y0.y > best) { best = y0.y; bi = 1; }
-            if (y1.x > best) { best = y1.x; bi = 2; }
-            if (y1.y > best) { best = y1.y; bi = 3; }
-            a.pool_out[po] = best;
-            a.pool_arg[po] = (uint8_t)bi;
-          } else {
-            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
-          }
-        }
-      } else if (need_side) {
-        const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
-        const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + a.W);
-        y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
-        y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
-      }
-      *reinterpret_cast<float2 *>(a.out + o) = y0;
-      *reinterpret_cast<float2 *>(a.out + o + a.W) = y1;
-    }
-  }
+  wino_store_tiles<DB>(a, Vl, acc, wave, lane, m0, img, img_ok, ty, tx, a.W);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -471,62 +483,7 @@ void conv_wino_reg_kernel(const ConvWinoArgs a) {
     }
   }
 
-  const bool fwd = a.bias != nullptr;
-  const bool need_side = !fwd && a.act;
-  float *Tl = smem; // [wave][k][r][lane]
-#pragma unroll
-  for (int i = 0; i < DB; ++i) {
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][i][r] + acc[1][i][r] + acc[2][i][r];
-      Tl[((wave * 2 + 1) * 16 + r) * 64 + lane] = acc[1][i][r] - acc[2][i][r] - acc[3][i][r];
-    }
-    __syncthreads();
-    if (!img_ok) continue;
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = 4 * wave + rr;
-      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr;
-      if (m >= a.M) continue;
-      float T[4][2];
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-#pragma unroll
-        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
-      float2 y0, y1;
-      y0.x = T[0][0] + T[1][0] + T[2][0];
-      y0.y = T[0][1] + T[1][1] + T[2][1];
-      y1.x = T[1][0] - T[2][0] - T[3][0];
-      y1.y = T[1][1] - T[2][1] - T[3][1];
-      const long o = ((long)img * a.M + m) * HW + (2 * ty) * G::W + 2 * tx;
-      if (fwd) {
-        const float bv = a.bias[m];
-        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
-        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
-        if (a.pool) {
-          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (G::W >> 1) + tx;
-          if (a.pool == 1) {
-            float best = y0.x; int bi = 0;
-            if (y0.y > best) { best = y0.y; bi = 1; }
-            if (y1.x > best) { best = y1.x; bi = 2; }
-            if (y1.y > best) { best = y1.y; bi = 3; }
-            a.pool_out[po] = best;
-            a.pool_arg[po] = (uint8_t)bi;
-          } else {
-            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
-          }
-        }
-      } else if (need_side) {
-        const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
-        const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + G::W);
-        y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
-        y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
-      }
-      *reinterpret_cast<float2 *>(a.out + o) = y0;
-      *reinterpret_cast<float2 *>(a.out + o + G::W) = y1;
-    }
-  }
+  wino_store_tiles<DB>(a, smem, acc, wave, lane, m0, img, img_ok, ty, tx, G::W);
 }
 
 typedef WinoGeom<32, 4, 1, 34> WinoG32;
