@@ -1161,9 +1161,11 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           }
           const long total = (long)B * l.in_size;
           dim3 grid = grid1d(total, 256), block(256);
+          Col2imDiv dv;
+          dv.dW.init(g.W); dv.dH.init(g.H); dv.dC.init(g.C); dv.dS.init(g.S);
           Ln(LL("conv_bwd_data"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(conv_col2im_kernel, grid, block, 0, st, (const float *)l.cols, (const float *)prev->a,
-                               prev->g, total, g.C, g.H, g.W, g.OH, g.OW, g.KH, g.KW, g.S, g.PAD, prev_act);
+                               prev->g, total, g.C, g.H, g.W, g.OH, g.OW, g.KH, g.KW, g.S, g.PAD, prev_act, dv);
           });
         } else if (prev) {
           typedef ProbConvBwd<OpConvWeightT, OpConvDeltaGather> Pb;

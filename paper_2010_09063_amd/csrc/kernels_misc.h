@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "gemm_tile.h" // FastDiv
+
 #define DP_ACT_NONE_ 0
 #define DP_ACT_RELU_ 1
 #define DP_ACT_TANH_ 2
@@ -139,27 +141,43 @@ __global__ void maxpool2x2_bwd_kernel(const float *__restrict__ gout, const uint
 // cols[b][(c, kh, kw)][p] = sum_d W[d][c][kh][kw] Delta[b][d][p] (a plain contraction, no gather).  Here every
 // input position sums the columns of the windows that hold it (gather form, no atomics) and applies the derivative
 // of the activation that produced the layer's input.  One thread per input element.
+struct Col2imDiv { FastDiv dW, dH, dC, dS; };
 __global__ void conv_col2im_kernel(const float *__restrict__ cols, const float *__restrict__ a_in,
                                    float *__restrict__ gin, long total, int C, int H, int W, int OH, int OW, int KH,
-                                   int KW, int S, int PAD, int act) {
+                                   int KW, int S, int PAD, int act, Col2imDiv dv) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  const int iw = (int)(i % W);
-  long r = i / W;
-  const int ih = (int)(r % H);
-  r /= H;
-  const int c = (int)(r % C);
-  const long b = r / C;
+  int iw, ih, c;
+  long b;
+  if (total < (1l << 31)) { // 32-bit index arithmetic with precomputed reciprocals
+    const unsigned u = (unsigned)i;
+    unsigned r = dv.dW.div(u);
+    iw = (int)(u - r * (unsigned)W);
+    unsigned r2 = dv.dH.div(r);
+    ih = (int)(r - r2 * (unsigned)H);
+    const unsigned r3 = dv.dC.div(r2);
+    c = (int)(r2 - r3 * (unsigned)C);
+    b = r3;
+  } else {
+    iw = (int)(i % W);
+    long r = i / W;
+    ih = (int)(r % H);
+    r /= H;
+    c = (int)(r % C);
+    b = r / C;
+  }
   const int P = OH * OW, KK = KH * KW;
   const float *cb = cols + ((long)b * C + c) * KK * P;
+  // only the taps whose window row / column lands on this position: kh = (ih + PAD) mod S, then every S-th
+  const int ihp = ih + PAD, iwp = iw + PAD;
+  const int qh = (int)dv.dS.div((unsigned)ihp), qw = (int)dv.dS.div((unsigned)iwp);
+  const int kh0 = ihp - qh * S, kw0 = iwp - qw * S;
   float acc = 0.f;
-  for (int kh = 0; kh < KH; ++kh) {
-    const int th = ih + PAD - kh;
-    if (th < 0 || th % S != 0 || th / S >= OH) continue;
-    for (int kw = 0; kw < KW; ++kw) {
-      const int tw = iw + PAD - kw;
-      if (tw < 0 || tw % S != 0 || tw / S >= OW) continue;
-      acc += cb[(long)(kh * KW + kw) * P + (th / S) * OW + tw / S];
+  for (int kh = kh0, oh = qh; kh < KH && oh >= 0; kh += S, --oh) {
+    if (oh >= OH) continue;
+    for (int kw = kw0, ow = qw; kw < KW && ow >= 0; kw += S, --ow) {
+      if (ow >= OW) continue;
+      acc += cb[(long)(kh * KW + kw) * P + oh * OW + ow];
     }
   }
   gin[i] = a_in != nullptr ? acc * act_deriv_from_out(act, a_in[i]) : acc;
