@@ -966,8 +966,9 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
         } else
         Ln(LL("maxpool_fwd"), grid, block, [&](hipStream_t st) {
+          Split3 dv; dv.dX.init(l.outW); dv.dY.init(l.outH);
           hipLaunchKernelGGL(maxpool_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
-                             l.outW, l.d.kh, l.d.kw, l.d.stride);
+                             l.outW, l.d.kh, l.d.kw, l.d.stride, dv);
         });
       } break;
       case DP_EMBEDDING: {
@@ -995,8 +996,9 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
         } else
         Ln(LL("avgpool_fwd"), grid, block, [&](hipStream_t st) {
+          Split3 dv; dv.dX.init(l.outW); dv.dY.init(l.outH);
           hipLaunchKernelGGL(avgpool_fwd_kernel, grid, block, 0, st, in, l.a, total, l.inH, l.inW, l.outH, l.outW,
-                             l.d.kh, l.d.kw, l.d.stride);
+                             l.d.kh, l.d.kw, l.d.stride, dv);
         });
       } break;
       case DP_LSTM_LAST:
@@ -1190,9 +1192,11 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
         } else
         Ln(LL("maxpool_bwd"), grid, block, [&](hipStream_t st) {
+          Split3 dv; dv.dX.init(l.inW); dv.dY.init(l.inH);
+          FastDiv dS; dS.init(l.d.stride);
           hipLaunchKernelGGL(maxpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
                              (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
-                             l.d.stride, prev_act);
+                             l.d.stride, prev_act, dv, dS);
         });
       } break;
       case DP_AVGPOOL2D: {
@@ -1208,8 +1212,10 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
         } else
         Ln(LL("avgpool_bwd"), grid, block, [&](hipStream_t st) {
+          Split3 dv; dv.dX.init(l.inW); dv.dY.init(l.inH);
+          FastDiv dS; dS.init(l.d.stride);
           hipLaunchKernelGGL(avgpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const float *)prev->a,
-                             prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw, l.d.stride, prev_act);
+                             prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw, l.d.stride, prev_act, dv, dS);
         });
       } break;
       case DP_LSTM_LAST:

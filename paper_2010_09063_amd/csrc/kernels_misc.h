@@ -35,6 +35,22 @@ __device__ __forceinline__ float act_deriv_from_out(int act, float a) {
   return 1.f;
 }
 
+// i = (z * Y + y) * X + x  ->  (x, y, z); 32-bit arithmetic with precomputed reciprocals when the range allows
+struct Split3 { FastDiv dX, dY; };
+__device__ __forceinline__ void split3(long i, long total, int X, int Y, const Split3 &d, int &x, int &y, long &z) {
+  if (total < (1l << 31)) {
+    const unsigned u = (unsigned)i, r = d.dX.div(u), r2 = d.dY.div(r);
+    x = (int)(u - r * (unsigned)X);
+    y = (int)(r - r2 * (unsigned)Y);
+    z = r2;
+  } else {
+    x = (int)(i % X);
+    const long r = i / X;
+    y = (int)(r % Y);
+    z = r / Y;
+  }
+}
+
 // delta_i = softmax(logits_i) - onehot(y_i): gradient of one example's own
 // cross-entropy (DPSGD item 2a: the objective at (x_i, y_i), not a batch mean).
 __global__ void softmax_xent_grad_kernel(const float *__restrict__ logits, const int *__restrict__ y,
@@ -54,13 +70,12 @@ __global__ void softmax_xent_grad_kernel(const float *__restrict__ logits, const
 // max-pool forward; arg = window offset kh*KW+kw of the first maximum
 __global__ void maxpool_fwd_kernel(const float *__restrict__ in, float *__restrict__ out,
                                    uint8_t *__restrict__ arg, long total, int H, int W, int OH, int OW,
-                                   int KH, int KW, int S) {
+                                   int KH, int KW, int S, Split3 dv) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  int ow = (int)(i % OW);
-  long r = i / OW;
-  int oh = (int)(r % OH);
-  long bc = r / OH;
+  int ow, oh;
+  long bc;
+  split3(i, total, OW, OH, dv, ow, oh, bc);
   const float *p = in + (bc * H + (long)oh * S) * W + (long)ow * S;
   float best = p[0];
   int bi = 0;
@@ -78,17 +93,16 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ in, float *__restri
 // derivative of the activation that produced the pool's input.
 __global__ void maxpool_bwd_kernel(const float *__restrict__ gout, const uint8_t *__restrict__ arg,
                                    const float *__restrict__ a_in, float *__restrict__ gin, long total, int H,
-                                   int W, int OH, int OW, int KH, int KW, int S, int act) {
+                                   int W, int OH, int OW, int KH, int KW, int S, int act, Split3 dv, FastDiv dS) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  int iw = (int)(i % W);
-  long r = i / W;
-  int ih = (int)(r % H);
-  long bc = r / H;
+  int iw, ih;
+  long bc;
+  split3(i, total, W, H, dv, iw, ih, bc);
   float acc = 0.f;
-  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (oh_lo + S - 1) / S : 0;
-  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (ow_lo + S - 1) / S : 0;
-  int oh_hi = min(ih / S, OH - 1), ow_hi = min(iw / S, OW - 1);
+  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (int)dS.div((unsigned)(oh_lo + S - 1)) : 0;
+  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (int)dS.div((unsigned)(ow_lo + S - 1)) : 0;
+  int oh_hi = min((int)dS.div((unsigned)ih), OH - 1), ow_hi = min((int)dS.div((unsigned)iw), OW - 1);
   for (int oh = oh_lo; oh <= oh_hi; ++oh)
     for (int ow = ow_lo; ow <= ow_hi; ++ow) {
       long o = (bc * OH + oh) * OW + ow;
@@ -186,13 +200,12 @@ __global__ void conv_col2im_kernel(const float *__restrict__ cols, const float *
 // Average pool (Appendix B, CIFAR10 network): the plain mean of a KH x KW window, no padding.  A window that
 // covers the whole plane is the global average pool.
 __global__ void avgpool_fwd_kernel(const float *__restrict__ in, float *__restrict__ out, long total, int H, int W,
-                                   int OH, int OW, int KH, int KW, int S) {
+                                   int OH, int OW, int KH, int KW, int S, Split3 dv) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  int ow = (int)(i % OW);
-  long r = i / OW;
-  int oh = (int)(r % OH);
-  long bc = r / OH;
+  int ow, oh;
+  long bc;
+  split3(i, total, OW, OH, dv, ow, oh, bc);
   const float *p = in + (bc * H + (long)oh * S) * W + (long)ow * S;
   float acc = 0.f;
   for (int kh = 0; kh < KH; ++kh)
@@ -204,17 +217,16 @@ __global__ void avgpool_fwd_kernel(const float *__restrict__ in, float *__restri
 // holds it, then applies the derivative of the activation that produced the pool's input.
 __global__ void avgpool_bwd_kernel(const float *__restrict__ gout, const float *__restrict__ a_in,
                                    float *__restrict__ gin, long total, int H, int W, int OH, int OW, int KH, int KW,
-                                   int S, int act) {
+                                   int S, int act, Split3 dv, FastDiv dS) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  int iw = (int)(i % W);
-  long r = i / W;
-  int ih = (int)(r % H);
-  long bc = r / H;
+  int iw, ih;
+  long bc;
+  split3(i, total, W, H, dv, iw, ih, bc);
   float acc = 0.f;
-  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (oh_lo + S - 1) / S : 0;
-  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (ow_lo + S - 1) / S : 0;
-  int oh_hi = min(ih / S, OH - 1), ow_hi = min(iw / S, OW - 1);
+  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (int)dS.div((unsigned)(oh_lo + S - 1)) : 0;
+  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (int)dS.div((unsigned)(ow_lo + S - 1)) : 0;
+  int oh_hi = min((int)dS.div((unsigned)ih), OH - 1), ow_hi = min((int)dS.div((unsigned)iw), OW - 1);
   for (int oh = oh_lo; oh <= oh_hi; ++oh)
     for (int ow = ow_lo; ow <= ow_hi; ++ow) acc += gout[(bc * OH + oh) * OW + ow];
   gin[i] = acc / (float)(KH * KW) * act_deriv_from_out(act, a_in[i]);
