@@ -17,6 +17,7 @@
 // so the transposing store of k-contiguous operands is conflict-free as well.
 // Global loads for tile t+1 are issued into registers before the MFMAs of tile t.
 #pragma once
+#include <algorithm>
 #include <cstdlib>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -387,6 +388,9 @@ static inline int launch_gemm_split(P p, int max_split, Launcher &&L, const char
   if (by_k > max_split) by_k = max_split;
   GemmShape s = pick_tile(p.M, p.N, by_k);
   long tiles = (long)s.tiles_m * s.tiles_n;
+  // a handful of tiles: the launch is one serial chain of loads per workgroup, so the shortest chunks the kernel
+  // takes (32) halve its duration
+  if (tiles <= 4 && p.K / 32 > by_k) by_k = std::min<long>(p.K / 32, max_split);
   long want = (1024 + tiles - 1) / tiles;
   int nsplit = (int)(want < by_k ? want : by_k);
   p.k_chunk = ceil_div(ceil_div(p.K, nsplit), 32) * 32;
