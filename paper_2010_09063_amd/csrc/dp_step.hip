@@ -967,8 +967,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         } else
         Ln(LL("maxpool_fwd"), grid, block, [&](hipStream_t st) {
           Split3 dv; dv.dX.init(l.outW); dv.dY.init(l.outH);
-          hipLaunchKernelGGL(maxpool_fwd_kernel, grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
-                             l.outW, l.d.kh, l.d.kw, l.d.stride, dv);
+          if (l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 1)
+            hipLaunchKernelGGL((maxpool_fwd_kernel<2, 1>), grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
+                               l.outW, l.d.kh, l.d.kw, l.d.stride, dv);
+          else
+            hipLaunchKernelGGL((maxpool_fwd_kernel<0, 0>), grid, block, 0, st, in, l.a, l.arg, total, l.inH, l.inW, l.outH,
+                               l.outW, l.d.kh, l.d.kw, l.d.stride, dv);
         });
       } break;
       case DP_EMBEDDING: {
@@ -1194,9 +1198,14 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         Ln(LL("maxpool_bwd"), grid, block, [&](hipStream_t st) {
           Split3 dv; dv.dX.init(l.inW); dv.dY.init(l.inH);
           FastDiv dS; dS.init(l.d.stride);
-          hipLaunchKernelGGL(maxpool_bwd_kernel, grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
-                             (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
-                             l.d.stride, prev_act, dv, dS);
+          if (l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 1)
+            hipLaunchKernelGGL((maxpool_bwd_kernel<2, 1>), grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
+                               (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
+                               l.d.stride, prev_act, dv, dS);
+          else
+            hipLaunchKernelGGL((maxpool_bwd_kernel<0, 0>), grid, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
+                               (const float *)prev->a, prev->g, total, l.inH, l.inW, l.outH, l.outW, l.d.kh, l.d.kw,
+                               l.d.stride, prev_act, dv, dS);
         });
       } break;
       case DP_AVGPOOL2D: {

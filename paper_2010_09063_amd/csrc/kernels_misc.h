@@ -67,10 +67,13 @@ __global__ void softmax_xent_grad_kernel(const float *__restrict__ logits, const
   for (int k = 0; k < K; ++k) g[(long)b * K + k] = expf(z[k] - mx) * inv - (k == yy ? 1.f : 0.f);
 }
 
-// max-pool forward; arg = window offset kh*KW+kw of the first maximum
+// max-pool forward; arg = window offset kh*KW+kw of the first maximum.  K_ / S_: window and stride as compile-time
+// constants for the common 2x2 / stride-1 pool (0: taken from the arguments).
+template <int K_, int S_>
 __global__ void maxpool_fwd_kernel(const float *__restrict__ in, float *__restrict__ out,
                                    uint8_t *__restrict__ arg, long total, int H, int W, int OH, int OW,
-                                   int KH, int KW, int S, Split3 dv) {
+                                   int KH_, int KW_, int Sa, Split3 dv) {
+  const int KH = K_ ? K_ : KH_, KW = K_ ? K_ : KW_, S = S_ ? S_ : Sa;
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   int ow, oh;
@@ -79,7 +82,9 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ in, float *__restri
   const float *p = in + (bc * H + (long)oh * S) * W + (long)ow * S;
   float best = p[0];
   int bi = 0;
+#pragma unroll
   for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
     for (int kw = 0; kw < KW; ++kw) {
       float v = p[kh * W + kw];
       if (v > best) { best = v; bi = kh * KW + kw; }
@@ -91,21 +96,24 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ in, float *__restri
 // max-pool backward in gather form (no atomics): every input position sums the
 // output gradients of the windows whose recorded maximum it is, then applies the
 // derivative of the activation that produced the pool's input.
+template <int K_, int S_>
 __global__ void maxpool_bwd_kernel(const float *__restrict__ gout, const uint8_t *__restrict__ arg,
                                    const float *__restrict__ a_in, float *__restrict__ gin, long total, int H,
-                                   int W, int OH, int OW, int KH, int KW, int S, int act, Split3 dv, FastDiv dS) {
+                                   int W, int OH, int OW, int KH_, int KW_, int Sa, int act, Split3 dv, FastDiv dS) {
+  const int KH = K_ ? K_ : KH_, KW = K_ ? K_ : KW_, S = S_ ? S_ : Sa;
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   int iw, ih;
   long bc;
   split3(i, total, W, H, dv, iw, ih, bc);
   float acc = 0.f;
-  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (int)dS.div((unsigned)(oh_lo + S - 1)) : 0;
-  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (int)dS.div((unsigned)(ow_lo + S - 1)) : 0;
-  int oh_hi = min((int)dS.div((unsigned)ih), OH - 1), ow_hi = min((int)dS.div((unsigned)iw), OW - 1);
+  int oh_lo = ih - KH + 1; oh_lo = oh_lo > 0 ? (S_ == 1 ? oh_lo : (int)dS.div((unsigned)(oh_lo + S - 1))) : 0;
+  int ow_lo = iw - KW + 1; ow_lo = ow_lo > 0 ? (S_ == 1 ? ow_lo : (int)dS.div((unsigned)(ow_lo + S - 1))) : 0;
+  int oh_hi = min(S_ == 1 ? ih : (int)dS.div((unsigned)ih), OH - 1), ow_hi = min(S_ == 1 ? iw : (int)dS.div((unsigned)iw), OW - 1);
+  const long obase = bc * OH * OW; // (windows of one plane: 32-bit offsets from here)
   for (int oh = oh_lo; oh <= oh_hi; ++oh)
     for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-      long o = (bc * OH + oh) * OW + ow;
+      const long o = obase + oh * OW + ow;
       int want = (ih - oh * S) * KW + (iw - ow * S);
       if ((int)arg[o] == want) acc += gout[o];
     }
