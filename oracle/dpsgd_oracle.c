@@ -471,6 +471,82 @@ double oracle_example_grad(const or_model *m, const double *theta, const void *x
   return l;
 }
 
+/* ---------------------------------------------------------------- exported: max-pool routing of near-tied windows
+ *
+ * A max-pool sends a window's gradient to its maximum (the first one in row-major order).  An fp32
+ * implementation decides that maximum on fp32 activations; where the two largest values of a window differ
+ * by less than the rounding error of the forward pass, either element is a valid choice of subgradient.
+ * The two functions below let a test enumerate every such choice on the CPU and check an fp32 result
+ * against the set of valid ones: the first lists, for one example, the window elements within tau of their
+ * window's maximum; the second computes the example's gradient with chosen windows routed to a listed
+ * element.  Forward values are never altered (the pool's output stays the fp64 maximum). */
+
+/* Flat input index of window element (kh, kw) of pool output oi. */
+static int pool_in_index(const or_layer *L, shp in, shp o, long oi, int kh, int kw) {
+  int ow = (int)(oi % o.w), oh = (int)((oi / o.w) % o.h), c = (int)(oi / ((long)o.w * o.h));
+  return (c * in.h + oh * L->stride + kh) * in.w + ow * L->stride + kw;
+}
+
+/* Lists up to cap entries (layer, out_idx, in_idx, gap): element in_idx of the window of output out_idx of
+ * max-pool layer `layer` lies 0 < gap <= tau below that window's maximum.  Exact ties are not listed: they
+ * follow the first-maximum rule on every implementation.  Returns the number of such elements (which may
+ * exceed cap; only the first cap are written). */
+long oracle_pool_near_ties(const or_model *m, const double *theta, const void *x, int y, double tau, long cap,
+                           int *layer, int *out_idx, int *in_idx, double *gap) {
+  scratch *s = scratch_new(m);
+  forward(m, theta, x, y, s);
+  long n = 0;
+  for (int l = 0; l < m->n_layers; ++l) {
+    const or_layer *L = &m->layers[l];
+    if (L->kind != OR_MAXPOOL2D) continue;
+    shp o = s->shape[l], in;
+    const double *av;
+    if (l > 0) { in = s->shape[l - 1]; av = s->a[l - 1]; }
+    else { in.c = m->in_c; in.h = m->in_h; in.w = m->in_w; av = s->in0; }
+    for (long oi = 0; oi < shp_size(o); ++oi) {
+      double bv = s->a[l][oi];
+      for (int kh = 0; kh < L->kh; ++kh)
+        for (int kw = 0; kw < L->kw; ++kw) {
+          int idx = pool_in_index(L, in, o, oi, kh, kw);
+          double d = bv - av[idx];
+          if (d > 0 && d <= tau) {
+            if (n < cap) { layer[n] = l; out_idx[n] = (int)oi; in_idx[n] = idx; gap[n] = d; }
+            ++n;
+          }
+        }
+    }
+  }
+  scratch_free(s);
+  return n;
+}
+
+/* Gradient of one example's loss with n_route pool windows routed by hand: the gradient of output out_idx[r]
+ * of max-pool layer layer[r] goes to input element in_idx[r], which must lie inside that window.  Returns the
+ * loss, or NaN if a route names no max-pool layer, an output out of range or an element outside the window. */
+double oracle_example_grad_routed(const or_model *m, const double *theta, const void *x, int y, long n_route,
+                                  const int *layer, const int *out_idx, const int *in_idx, double *g) {
+  scratch *s = scratch_new(m);
+  double loss = forward(m, theta, x, y, s);
+  for (long r = 0; r < n_route; ++r) {
+    int l = layer[r], ok = 0;
+    if (l >= 0 && l < m->n_layers && m->layers[l].kind == OR_MAXPOOL2D && out_idx[r] >= 0 &&
+        out_idx[r] < shp_size(s->shape[l])) {
+      const or_layer *L = &m->layers[l];
+      shp o = s->shape[l], in;
+      if (l > 0) in = s->shape[l - 1];
+      else { in.c = m->in_c; in.h = m->in_h; in.w = m->in_w; }
+      for (int kh = 0; kh < L->kh; ++kh)
+        for (int kw = 0; kw < L->kw; ++kw)
+          if (pool_in_index(L, in, o, out_idx[r], kh, kw) == in_idx[r]) ok = 1;
+    }
+    if (!ok) { scratch_free(s); return NAN; }
+    s->arg[l][out_idx[r]] = in_idx[r];
+  }
+  backward(m, theta, x, y, s, g);
+  scratch_free(s);
+  return loss;
+}
+
 /* ---------------------------------------------------------------- noise */
 
 void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {

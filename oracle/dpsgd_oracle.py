@@ -54,6 +54,12 @@ def lib():
         L.oracle_example_grad.restype = C.c_double
         L.oracle_example_grad.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                           C.POINTER(C.c_long)]
+        L.oracle_pool_near_ties.restype = C.c_long
+        L.oracle_pool_near_ties.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_int, C.c_double, C.c_long,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_example_grad_routed.restype = C.c_double
+        L.oracle_example_grad_routed.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_int, C.c_long,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_philox4x32_10.restype = None
         L.oracle_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_noise.restype = None
@@ -132,6 +138,40 @@ def example_grad(m, theta64, x_i, y_i):
     loss = lib().oracle_example_grad(C.byref(cm), th.ctypes.data, xi.ctypes.data, int(y_i), g.ctypes.data,
                                      C.byref(ties))
     return float(loss), g, int(ties.value)
+
+
+def pool_near_ties(m, theta64, x_i, y_i, tau):
+    """[(layer, out_idx, in_idx, gap)]: window elements of one example's max-pools that lie 0 < gap <= tau below
+    their window's maximum (the elements an fp32 forward pass may legitimately pick instead)."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(theta64, dtype=np.float64)
+    xi = _x_array(m, x_i)
+    cap = 64
+    while True:
+        la, oi, ii = (np.empty(cap, dtype=np.int32) for _ in range(3))
+        gp = np.empty(cap, dtype=np.float64)
+        n = int(lib().oracle_pool_near_ties(C.byref(cm), th.ctypes.data, xi.ctypes.data, int(y_i), float(tau), cap,
+                                            la.ctypes.data, oi.ctypes.data, ii.ctypes.data, gp.ctypes.data))
+        if n <= cap:
+            return [(int(la[k]), int(oi[k]), int(ii[k]), float(gp[k])) for k in range(n)]
+        cap = n
+
+
+def example_grad_routed(m, theta64, x_i, y_i, routes):
+    """(loss, g[P] fp64) of one example with the max-pool windows in `routes` = [(layer, out_idx, in_idx), ...]
+    sending their gradient to the named window element instead of the first maximum."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(theta64, dtype=np.float64)
+    xi = _x_array(m, x_i)
+    g = np.empty(th.size, dtype=np.float64)
+    la = np.asarray([r[0] for r in routes], dtype=np.int32)
+    oi = np.asarray([r[1] for r in routes], dtype=np.int32)
+    ii = np.asarray([r[2] for r in routes], dtype=np.int32)
+    loss = float(lib().oracle_example_grad_routed(C.byref(cm), th.ctypes.data, xi.ctypes.data, int(y_i), len(routes),
+                                                  la.ctypes.data, oi.ctypes.data, ii.ctypes.data, g.ctypes.data))
+    if loss != loss:
+        raise ValueError("route outside a max-pool window")
+    return loss, g
 
 
 def philox4x32_10(ctr, key):

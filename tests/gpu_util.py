@@ -1,7 +1,26 @@
-"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI binding."""
+"""Helpers shared by the GPU parity tests: run the HIP path through the C ABI binding, and compare its
+result with the oracle tensor by tensor, over the whole batch, allowing for the one decision that fp32 and
+fp64 may legitimately take differently (the arg-max of a max-pool window whose two largest values differ by
+less than the forward pass's rounding error)."""
+import itertools
 import math
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
+
+import dp_workloads as W
+from oracle import dpsgd_oracle as O
+
+TOL = 1e-4          # relative L2 of the aggregated gradient, whole vector and every parameter tensor
+TENSOR_FLOOR = 1e-6  # a tensor whose reference norm is below this share of the whole gradient's is held to
+#                      an absolute error of TOL * that floor (a tensor that is all rounding noise has no
+#                      meaningful relative error)
+NORM_RTOL = 1e-4    # per-example norms
+# Two window elements closer than TAU may be ordered differently by an fp32 forward pass: the kernels' forward
+# error on unit-scale activations is <= 3e-7 (direct convolution) to 2e-6 (minimal-filtering form), and both
+# elements carry it.  Every flip the tests accept is printed with its gap; none may exceed TAU by construction.
+TAU = 4e-6
+MAX_FLIPPED_FRACTION = 0.05
 
 
 def run_gpu(m, params, x, y, C, sigma, seed, private=True, max_batch=None, want_norms=True, stepper=None):
@@ -39,24 +58,125 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-POOL_MARGIN = 1e-5
+def tensor_errors(m, got, ref):
+    """[(label, error / bar)] for the whole vector and for every parameter tensor, where bar =
+    TOL * max(||ref_t||, TENSOR_FLOOR * ||ref||)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    whole = float(np.linalg.norm(ref))
+    rows = [("all", float(np.linalg.norm(got - ref)) / (TOL * max(whole, 1e-300)))]
+    for li, name, shp, off in W.param_tensors(m):
+        n = int(np.prod(shp))
+        r = ref[off:off + n]
+        bar = TOL * max(float(np.linalg.norm(r)), TENSOR_FLOOR * whole, 1e-300)
+        rows.append((f"L{li}.{name}", float(np.linalg.norm(got[off:off + n] - r)) / bar))
+    return rows
 
 
-def clear_pool_examples(m, params, x, y, oracle_step, tau=POOL_MARGIN):
-    """Max-pool routes a window's gradient to its maximum; the kernel decides that in fp32,
-    the oracle in fp64.  Where the two largest values of a window differ by rounding-level
-    amounts either choice is a valid (sub)gradient and the two sides may legitimately differ.
-    Parity is therefore checked on examples all of whose windows have a clear maximum (gap
-    > tau in the oracle's forward pass): the others are replaced by clear ones (cycled), so
-    the batch keeps its size.  Returns (x, y, number of examples replaced)."""
-    if not any(L["kind"] == "maxpool2d" for L in m["layers"]) or len(y) == 0:
-        return x, y, 0
-    mg = oracle_step(m, params, x, y, 1.0, 0.0, 0, clip=False)["pool_margin"]
-    clear = np.flatnonzero(mg > tau)
-    assert clear.size > 0, "no example with a clear pool maximum"
-    if clear.size == len(y):
-        return x, y, 0
-    idx = np.arange(len(y))
-    bad = np.flatnonzero(mg <= tau)
-    idx[bad] = clear[np.arange(bad.size) % clear.size]
-    return x[idx], y[idx], int(bad.size)
+def assert_parity(m, got, ref, label):
+    """Aggregated gradient: relative L2 <= TOL on the whole vector AND on every parameter tensor."""
+    assert np.isfinite(got).all(), label
+    rows = tensor_errors(m, got, ref)
+    worst = max(rows, key=lambda r: r[1])
+    print(f"{label}: rel_l2 {rows[0][1] * TOL:.3e}; worst tensor {worst[0]} at {worst[1] * TOL:.3e}", flush=True)
+    bad = [(n, f"{e * TOL:.3e}") for n, e in rows if e > 1.0]
+    assert not bad, (label, bad)
+
+
+class TieAwareOracle:
+    """The oracle's step over the WHOLE batch, with every valid max-pool routing of the near-tied windows.
+
+    For each example that has a window element within TAU of its window's maximum, the oracle computes the
+    example's gradient for every combination of those windows' candidate elements (all on the CPU, from the
+    oracle's own forward pass).  `reference` then picks, per such example, the combination that best explains
+    the GPU's aggregate, and returns the oracle's sum and norms under that routing; the caller holds the GPU
+    to the usual tolerances against them.  Every example is therefore checked: a clear example against its
+    unique gradient, a near-tied one against the closest member of its finite set of valid gradients."""
+
+    def __init__(self, m, theta, x, y, margin, tau=TAU, max_combos=64):
+        self.m, self.theta, self.x, self.y, self.tau = m, theta, x, y, tau
+        self.cands = {}  # example -> (g0, [(routes, g, gap)])
+        if not any(L["kind"] == "maxpool2d" for L in m["layers"]) or len(y) == 0:
+            return
+        th64 = np.asarray(theta, dtype=np.float64)
+        near = [int(i) for i in np.flatnonzero(np.asarray(margin) <= tau)]
+
+        def work(i):
+            ent = O.pool_near_ties(m, th64, x[i], y[i], tau)
+            wins = {}
+            for l, oi, ii, gap in ent:
+                wins.setdefault((l, oi), []).append((ii, gap))
+            opts = [[None] + [(l, oi, ii, gap) for ii, gap in alts] for (l, oi), alts in sorted(wins.items())]
+            n_combos = int(np.prod([len(o) for o in opts]))
+            assert n_combos <= max_combos, f"example {i}: {n_combos} routings of near-tied windows"
+            g0 = O.example_grad(m, th64, x[i], y[i])[1]
+            out = []
+            for combo in itertools.product(*opts):
+                routes = [c for c in combo if c is not None]
+                if routes:
+                    g = O.example_grad_routed(m, th64, x[i], y[i], [r[:3] for r in routes])[1]
+                    out.append((routes, g, max(r[3] for r in routes)))
+            return i, g0, out
+
+        with ThreadPoolExecutor(8) as ex:
+            for i, g0, out in ex.map(work, near):
+                self.cands[i] = (g0, out)
+
+    @property
+    def n_near(self):
+        return len(self.cands)
+
+    def reference(self, ref, C, got, clip=True):
+        """ref: the oracle's dp_step result at this C (first-maximum routing).  Returns (clipped_sum, norms,
+        flips) under the valid routing closest to `got`; flips = [(example, largest gap among its re-routed
+        windows)]."""
+        csum = np.array(ref["clipped_sum"], dtype=np.float64)
+        norms = np.array(ref["norms"], dtype=np.float64)
+        if not self.cands:
+            return csum, norms, []
+
+        def scale(n):
+            return C / n if (clip and n > C) else 1.0
+
+        R = np.asarray(got, dtype=np.float64) - csum
+        choice = {i: -1 for i in self.cands}
+        deltas = {}
+        for i, (g0, cl) in self.cands.items():
+            n0 = float(np.linalg.norm(g0))
+            deltas[i] = [scale(float(np.linalg.norm(g))) * g - scale(n0) * g0 for _, g, _ in cl]
+        for _ in range(2):  # coordinate descent on ||got - (csum + sum of chosen deltas)||
+            for i, dl in deltas.items():
+                cur = dl[choice[i]] if choice[i] >= 0 else None
+                Ri = R + cur if cur is not None else R
+                best, best_score = -1, 0.0
+                for a, d in enumerate(dl):
+                    score = float(d @ d) - 2.0 * float(Ri @ d)
+                    if score < best_score:
+                        best, best_score = a, score
+                if best != choice[i]:
+                    R = Ri - dl[best] if best >= 0 else Ri
+                    choice[i] = best
+        flips = []
+        for i, a in choice.items():
+            if a >= 0:
+                csum += deltas[i][a]
+                norms[i] = float(np.linalg.norm(self.cands[i][1][a][1]))
+                flips.append((i, self.cands[i][1][a][2]))
+        return csum, norms, flips
+
+
+def check_step(m, theta, x, y, C, ref, label, tie=None, private=True, stepper=None):
+    """One GPU step against the oracle result `ref` (same C), whole batch, every tensor, every norm."""
+    out, gn = run_gpu(m, theta, x, y, C if private else 1.0, 0.0, 0, private=private, stepper=stepper)
+    if tie is None:
+        tie = TieAwareOracle(m, theta, x, y, ref["pool_margin"])
+    csum, norms, flips = tie.reference(ref, C, out, clip=private)
+    if tie.n_near:
+        print(f"{label}: {tie.n_near} of {len(y)} examples have a pool window with a gap <= {tie.tau:g}; the GPU "
+              f"routed {len(flips)} of them to the runner-up (largest gap {max([g for _, g in flips], default=0):.2e})",
+              flush=True)
+    assert len(flips) <= max(1, MAX_FLIPPED_FRACTION * len(y)), (label, len(flips))
+    assert_parity(m, out, csum, label)
+    if private and len(y) > 0:
+        assert np.allclose(gn, norms, rtol=NORM_RTOL, atol=1e-7), label
+    return out, gn, norms

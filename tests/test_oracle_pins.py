@@ -448,3 +448,61 @@ def test_sgd_step_reduces_to_plain_sgd(name):
     z = O.noise(9, theta.size)
     want = theta.astype(np.float64) - lr / 6 * (ref["clipped_sum"] + 1.1 * 0.5 * z)
     assert np.array_equal(new2, want.astype(np.float32))
+
+
+# ----------------------------------------------------------------- max-pool margins and routing (test aids of the oracle)
+
+def _pool_model():
+    # 2x2x6 image -> 1x1 convolution to 2 channels, tanh -> 2x2 / stride-2 max-pool (3 windows a channel) -> fc 2
+    return W.model(W.image_input(2, 2, 6), [W.conv2d(2, 2, 1, act="tanh"), W.maxpool2d(2, 2), W.dense(6, 2)], 2)
+
+
+def _pool_case():
+    m = _pool_model()
+    e = 2.0 ** -20
+    # v = sum of the two input planes; its windows (columns 0-1, 2-3, 4-5): clear maximum; runner-up 2^-20 below
+    # the maximum; exact tie.  All values are dyadic, so the sums are exact, and tied pixels differ in their planes.
+    v = np.array([[0.125, 0.875, 0.5 + e, 0.25, 0.75, 0.75],
+                  [0.3125, 0.25, 0.5, 0.125, 0.75, 0.375]])
+    p0 = np.array([[0.0625, 0.5, 0.125, 0.125, 0.25, 0.5],
+                   [0.25, 0.125, 0.375, 0.0625, 0.375, 0.125]])
+    x = np.stack([p0, v - p0])[None].astype(np.float32)
+    assert np.array_equal(x[0, 0].astype(np.float64) + x[0, 1], v)
+    theta = np.zeros(O.num_params(m), dtype=np.float32)
+    theta[0:2], theta[2:4] = 1.0, 0.5        # channel 0 = tanh(v), channel 1 = tanh(v / 2): both keep the order of v
+    theta[6:18] = np.linspace(-0.4, 0.5, 12)  # dense weights
+    return m, x, np.array([1], dtype=np.int32), theta
+
+
+def test_pool_margin_on_three_hand_built_windows():
+    m, x, y, theta = _pool_case()
+    r = O.dp_step(m, theta, x, y, 1.0, 0.0, 0, clip=False)
+    # smallest non-zero gap over both channels: tanh(0.5 (0.5 + e)) - tanh(0.25), the second channel's middle window
+    want = math.tanh(0.5 * (0.5 + 2.0 ** -20)) - math.tanh(0.25)
+    assert want < math.tanh(0.5 + 2.0 ** -20) - math.tanh(0.5)
+    assert r["pool_margin"][0] == pytest.approx(want, rel=1e-9)
+    assert r["ties"] == 2   # the third window of either channel holds 0.7 twice
+    ent = O.pool_near_ties(m, theta.astype(np.float64), x[0], y[0], 1e-5)
+    # one runner-up per channel, in the middle window (pool output 1 / 4), element (row 1, column 2) of that channel
+    assert [(l, oi, ii) for l, oi, ii, _ in ent] == [(1, 1, 8), (1, 4, 12 + 8)]
+    assert ent[0][3] == pytest.approx(math.tanh(0.5 + 2.0 ** -20) - math.tanh(0.5), rel=1e-9)
+    assert O.pool_near_ties(m, theta.astype(np.float64), x[0], y[0], 1e-8) == []
+    with pytest.raises(ValueError):
+        O.example_grad_routed(m, theta.astype(np.float64), x[0], y[0], [(1, 1, 0)])  # element of another window
+
+
+def test_routed_gradient_equals_the_gradient_after_a_nudge():
+    """Routing a near-tied window to its runner-up gives the gradient of the input in which that runner-up has been
+    nudged past the maximum (up to the size of the nudge), and differs from the first-maximum gradient."""
+    m, x, y, theta = _pool_case()
+    th64 = theta.astype(np.float64)
+    ent = O.pool_near_ties(m, th64, x[0], y[0], 1e-5)
+    routes = [e[:3] for e in ent]
+    g_first = O.example_grad(m, th64, x[0], y[0])[1]
+    g_routed = O.example_grad_routed(m, th64, x[0], y[0], routes)[1]
+    x2 = x.copy()
+    x2[0, 0, 1, 2] += 2.0 ** -18            # v at (row 1, column 2) now exceeds (row 0, column 2) in both channels
+    g_nudged = O.example_grad(m, th64, x2[0], y[0])[1]
+    assert np.abs(g_routed - g_nudged).max() <= 1e-5 * np.abs(g_nudged).max()
+    assert np.abs(g_routed - g_first).max() >= 1e-3 * np.abs(g_first).max()
+    assert np.array_equal(O.example_grad_routed(m, th64, x[0], y[0], [])[1], g_first)
