@@ -584,12 +584,14 @@ void oracle_noise(uint64_t seed, long n, double *z) {
  *   norms[B]  unclipped ||g_i||;  clipped_sum[P] the fp64 sum before noise;  ties;
  *   pool_margin[B]  smallest non-zero gap between the maximum and the runner-up over the example's
  *   pool windows (+inf without pooling; exact ties go to the first maximum on every implementation): an fp32 implementation may route a window whose
- *   gap is at rounding level to the other element, so tests compare on clear examples.
+ *   gap is at rounding level to the other element (see oracle_pool_near_ties);
+ *   abs_sum[P]  sum_i |s_i g_i[j]|, the magnitude the terms of coordinate j had before they cancelled: rounding
+ *   errors of any summation scale with it, so tests state their per-tensor tolerance in terms of it.
  * C = +inf disables clipping; sigma = 0 adds exactly nothing.  clip = 0 skips the
  * clipping branch altogether (the non-private summed gradient).  Returns 0. */
 int oracle_dp_step(const or_model *m, const float *params, const void *x, const int32_t *y, int B, double C,
                    double sigma, uint64_t seed, int clip, float *out, double *norms, double *clipped_sum,
-                   long *ties, double *pool_margin, int n_threads) {
+                   long *ties, double *pool_margin, double *abs_sum, int n_threads) {
   long P = oracle_num_params(m);
   double *theta = (double *)malloc(sizeof(double) * P);
   for (long j = 0; j < P; ++j) theta[j] = (double)params[j];
@@ -600,6 +602,7 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
 #endif
   if (nt > B) nt = B > 0 ? B : 1;
   double **acc = (double **)calloc(nt, sizeof(double *));
+  double **mag = (double **)calloc(nt, sizeof(double *));
   long *tie_t = (long *)calloc(nt, sizeof(long));
 #ifdef _OPENMP
 #pragma omp parallel num_threads(nt)
@@ -613,6 +616,8 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
     double *g = (double *)malloc(sizeof(double) * P);
     scratch *s = scratch_new(m);
     acc[tid] = a;
+    double *ab = abs_sum ? (double *)calloc(P, sizeof(double)) : NULL;
+    mag[tid] = ab;
     /* contiguous block of examples per thread */
     int lo = (int)((long)B * tid / nt), hi = (int)((long)B * (tid + 1) / nt);
     for (int i = lo; i < hi; ++i) {
@@ -627,6 +632,7 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
       if (norms) norms[i] = n;
       if (pool_margin) pool_margin[i] = s->margin;
       for (long j = 0; j < P; ++j) a[j] += sc * g[j];
+      if (ab) for (long j = 0; j < P; ++j) ab[j] += fabs(sc * g[j]);
     }
     tie_t[tid] = s->ties;
     scratch_free(s);
@@ -634,8 +640,10 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
   }
   for (int t = 1; t < nt; ++t) {
     for (long j = 0; j < P; ++j) acc[0][j] += acc[t][j];
+    if (abs_sum) for (long j = 0; j < P; ++j) mag[0][j] += mag[t][j];
     tie_t[0] += tie_t[t];
   }
+  if (abs_sum) memcpy(abs_sum, mag[0], sizeof(double) * P);
   if (ties) *ties = tie_t[0];
   if (clipped_sum) memcpy(clipped_sum, acc[0], sizeof(double) * P);
   if (sigma > 0) {
@@ -646,8 +654,8 @@ int oracle_dp_step(const or_model *m, const float *params, const void *x, const 
   } else {
     for (long j = 0; j < P; ++j) out[j] = (float)acc[0][j];
   }
-  for (int t = 0; t < nt; ++t) free(acc[t]);
-  free(acc); free(tie_t); free(theta);
+  for (int t = 0; t < nt; ++t) { free(acc[t]); free(mag[t]); }
+  free(acc); free(mag); free(tie_t); free(theta);
   return 0;
 }
 
@@ -661,7 +669,7 @@ int oracle_sgd_step(const or_model *m, const float *params, const void *x, const
   double *csum = (double *)malloc(sizeof(double) * P);
   double *z = (double *)malloc(sizeof(double) * P);
   int rc = (out && csum && z) ? 0 : -1;
-  if (rc == 0) rc = oracle_dp_step(m, params, x, y, B, C, 0.0, seed, 1, out, NULL, csum, NULL, NULL, n_threads);
+  if (rc == 0) rc = oracle_dp_step(m, params, x, y, B, C, 0.0, seed, 1, out, NULL, csum, NULL, NULL, NULL, n_threads);
   if (rc == 0) {
     if (sigma > 0) oracle_noise(seed, P, z);
     for (long j = 0; j < P; ++j) {

@@ -67,7 +67,7 @@ def lib():
         L.oracle_dp_step.restype = C.c_int
         L.oracle_dp_step.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_double,
                                      C.c_double, C.c_uint64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
-                                     C.POINTER(C.c_long), C.c_void_p, C.c_int]
+                                     C.POINTER(C.c_long), C.c_void_p, C.c_void_p, C.c_int]
         L.oracle_sgd_step.restype = C.c_int
         L.oracle_sgd_step.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_double,
                                       C.c_double, C.c_uint64, C.c_double, C.c_void_p, C.c_int]
@@ -190,7 +190,8 @@ def noise(seed, n):
 
 
 def dp_step(m, params, x, y, clip_c, sigma, seed, clip=True, n_threads=0):
-    """One private step.  Returns dict(out fp32[P], norms fp64[B], clipped_sum fp64[P], ties, pool_margin fp64[B])."""
+    """One private step.  Returns dict(out fp32[P], norms fp64[B], clipped_sum fp64[P], ties, pool_margin fp64[B],
+    abs_sum fp64[P] = sum_i |s_i g_i| coordinate by coordinate)."""
     cm = _to_c_model(m)
     th = np.ascontiguousarray(params, dtype=np.float32)
     xa = _x_array(m, x)
@@ -202,11 +203,13 @@ def dp_step(m, params, x, y, clip_c, sigma, seed, clip=True, n_threads=0):
     csum = np.empty(P, dtype=np.float64)
     ties = C.c_long(0)
     margin = np.empty(B, dtype=np.float64)
+    mag = np.empty(P, dtype=np.float64)
     rc = lib().oracle_dp_step(C.byref(cm), th.ctypes.data, xa.ctypes.data, ya.ctypes.data, B, float(clip_c),
                               float(sigma), C.c_uint64(int(seed)), 1 if clip else 0, out.ctypes.data,
-                              norms.ctypes.data, csum.ctypes.data, C.byref(ties), margin.ctypes.data, int(n_threads))
+                              norms.ctypes.data, csum.ctypes.data, C.byref(ties), margin.ctypes.data, mag.ctypes.data,
+                              int(n_threads))
     assert rc == 0
-    return dict(out=out, norms=norms, clipped_sum=csum, ties=int(ties.value), pool_margin=margin)
+    return dict(out=out, norms=norms, clipped_sum=csum, ties=int(ties.value), pool_margin=margin, abs_sum=mag)
 
 
 def sgd_step(m, params, x, y, clip_c, sigma, seed, lr, n_threads=0):

@@ -11,15 +11,19 @@ import numpy as np
 import dp_workloads as W
 from oracle import dpsgd_oracle as O
 
-TOL = 1e-4          # relative L2 of the aggregated gradient, whole vector and every parameter tensor
-TENSOR_FLOOR = 1e-6  # a tensor whose reference norm is below this share of the whole gradient's is held to
-#                      an absolute error of TOL * that floor (a tensor that is all rounding noise has no
-#                      meaningful relative error)
+TOL = 1e-4          # relative L2 of the aggregated gradient: the whole vector, and every parameter tensor
+# Per tensor the bar is TOL * ||ref_t|| + ACC * ||abs_t||, abs_t = sum_i |s_i g_i| coordinate by coordinate (from the
+# oracle).  The second term is what any fp32 summation is entitled to: the terms of a tensor may cancel (the clipped
+# bias gradients of a small batch with mixed labels: sum of the terms' norms 1,800 times the norm of their sum), and
+# the rounding error of the terms, about 1e-7 of each, does not cancel with them.  For a tensor whose terms do not
+# cancel this adds 1 % to the bar.
+ACC = 1e-6
 NORM_RTOL = 1e-4    # per-example norms
 # Two window elements closer than TAU may be ordered differently by an fp32 forward pass: the kernels' forward
-# error on unit-scale activations is <= 3e-7 (direct convolution) to 2e-6 (minimal-filtering form), and both
-# elements carry it.  Every flip the tests accept is printed with its gap; none may exceed TAU by construction.
-TAU = 4e-6
+# error on unit-scale pre-activations is <= 3e-7 (direct convolution) to 2e-6 (minimal-filtering form) in the worst
+# case, and both elements carry it.  Every flip the tests accept is printed with its gap (the largest seen at full
+# size is 1.4e-7, on the CIFAR-shaped CNN); a flip at a gap above TAU is not a candidate and fails the comparison.
+TAU = 2e-6
 MAX_FLIPPED_FRACTION = 0.05
 
 
@@ -58,28 +62,27 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def tensor_errors(m, got, ref):
-    """[(label, error / bar)] for the whole vector and for every parameter tensor, where bar =
-    TOL * max(||ref_t||, TENSOR_FLOOR * ||ref||)."""
+def tensor_errors(m, got, ref, mag=None):
+    """[(label, error / bar)] for the whole vector (bar TOL * ||ref||) and for every parameter tensor (bar
+    TOL * ||ref_t|| + ACC * ||mag_t||, mag = the oracle's abs_sum)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
-    whole = float(np.linalg.norm(ref))
-    rows = [("all", float(np.linalg.norm(got - ref)) / (TOL * max(whole, 1e-300)))]
+    rows = [("all", float(np.linalg.norm(got - ref)) / (TOL * max(float(np.linalg.norm(ref)), 1e-300)))]
     for li, name, shp, off in W.param_tensors(m):
         n = int(np.prod(shp))
         r = ref[off:off + n]
-        bar = TOL * max(float(np.linalg.norm(r)), TENSOR_FLOOR * whole, 1e-300)
-        rows.append((f"L{li}.{name}", float(np.linalg.norm(got[off:off + n] - r)) / bar))
+        bar = TOL * float(np.linalg.norm(r)) + (ACC * float(np.linalg.norm(mag[off:off + n])) if mag is not None else 0.0)
+        rows.append((f"L{li}.{name}", float(np.linalg.norm(got[off:off + n] - r)) / max(bar, 1e-300)))
     return rows
 
 
-def assert_parity(m, got, ref, label):
-    """Aggregated gradient: relative L2 <= TOL on the whole vector AND on every parameter tensor."""
+def assert_parity(m, got, ref, label, mag=None):
+    """Aggregated gradient: relative L2 <= TOL on the whole vector AND every parameter tensor within its bar."""
     assert np.isfinite(got).all(), label
-    rows = tensor_errors(m, got, ref)
-    worst = max(rows, key=lambda r: r[1])
-    print(f"{label}: rel_l2 {rows[0][1] * TOL:.3e}; worst tensor {worst[0]} at {worst[1] * TOL:.3e}", flush=True)
-    bad = [(n, f"{e * TOL:.3e}") for n, e in rows if e > 1.0]
+    rows = tensor_errors(m, got, ref, mag)
+    worst = max(rows[1:], key=lambda r: r[1]) if len(rows) > 1 else rows[0]
+    print(f"{label}: rel_l2 {rows[0][1] * TOL:.3e}; worst tensor {worst[0]} at {worst[1]:.3f} of its bar", flush=True)
+    bad = [(n, f"{e:.3f}") for n, e in rows if e > 1.0]
     assert not bad, (label, bad)
 
 
@@ -107,8 +110,9 @@ class TieAwareOracle:
             for l, oi, ii, gap in ent:
                 wins.setdefault((l, oi), []).append((ii, gap))
             opts = [[None] + [(l, oi, ii, gap) for ii, gap in alts] for (l, oi), alts in sorted(wins.items())]
-            n_combos = int(np.prod([len(o) for o in opts]))
-            assert n_combos <= max_combos, f"example {i}: {n_combos} routings of near-tied windows"
+            n_combos = math.prod(len(o) for o in opts)
+            assert n_combos <= max_combos, (f"example {i}: {len(opts)} near-tied pool windows ({n_combos} routings): "
+                                            "degenerate test input (saturated activations?)")
             g0 = O.example_grad(m, th64, x[i], y[i])[1]
             out = []
             for combo in itertools.product(*opts):
@@ -176,7 +180,7 @@ def check_step(m, theta, x, y, C, ref, label, tie=None, private=True, stepper=No
               f"routed {len(flips)} of them to the runner-up (largest gap {max([g for _, g in flips], default=0):.2e})",
               flush=True)
     assert len(flips) <= max(1, MAX_FLIPPED_FRACTION * len(y)), (label, len(flips))
-    assert_parity(m, out, csum, label)
+    assert_parity(m, out, csum, label, ref["abs_sum"])
     if private and len(y) > 0:
         assert np.allclose(gn, norms, rtol=NORM_RTOL, atol=1e-7), label
     return out, gn, norms

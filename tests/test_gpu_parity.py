@@ -337,7 +337,7 @@ def test_unaligned_device_pointers():
         st.dp_step(tp, tx, ty, batch, 0.7, 0.0, 0, out)
         torch.cuda.synchronize()
         csum, _, _ = tie.reference(ref, 0.7, out.cpu().numpy())
-        assert_parity(m, out.cpu().numpy(), csum, f"unaligned/{name}")
+        assert_parity(m, out.cpu().numpy(), csum, f"unaligned/{name}", ref["abs_sum"])
         st.dp_step_free()
 
 
@@ -386,7 +386,10 @@ def test_fused_sgd_update(name, batch):
         wl = W.make_workload(name, batch=batch, seed=21, bias_scale=0.2)
         m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
     norms = O.dp_step(m, theta, x, y, 1.0, 0.0, 0)["norms"]
-    Cc, sigma, seed, lr = float(np.median(norms)), 0.7, 77, 0.25 * batch
+    # a step small enough that the parameters stay in the regime they were drawn for (a large one saturates every
+    # tanh, and a saturated plane is one big near-tie for the pool that follows it)
+    Cc, sigma, seed = float(np.median(norms)), 0.7, 77
+    lr = 0.01 * batch / Cc
 
     def want_after(th, sd, noised_sum):
         """The oracle's updated parameters; where the GPU routed a near-tied pool window to the runner-up, the

@@ -506,3 +506,20 @@ def test_routed_gradient_equals_the_gradient_after_a_nudge():
     assert np.abs(g_routed - g_nudged).max() <= 1e-5 * np.abs(g_nudged).max()
     assert np.abs(g_routed - g_first).max() >= 1e-3 * np.abs(g_first).max()
     assert np.array_equal(O.example_grad_routed(m, th64, x[0], y[0], [])[1], g_first)
+
+
+def test_abs_sum_is_the_sum_of_term_magnitudes():
+    """abs_sum (the yardstick of the per-tensor tolerance) against the per-example gradients: sum_i |s_i g_i|."""
+    m, x, y, theta = _tiny_case("tiny_conv2", 6)
+    th64 = theta.astype(np.float64)
+    n0 = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)["norms"]
+    Cc = float(np.median(n0))
+    r = O.dp_step(m, theta, x, y, Cc, 0.0, 0)
+    want = np.zeros(theta.size)
+    for i in range(6):
+        g = O.example_grad(m, th64, x[i], y[i])[1]
+        want += np.abs(g) * min(1.0, Cc / np.linalg.norm(g))
+    assert np.allclose(r["abs_sum"], want, rtol=1e-12, atol=0)
+    assert np.all(r["abs_sum"] >= np.abs(r["clipped_sum"]) * (1 - 1e-12))
+    one = O.dp_step(m, theta, x[:1], y[:1], Cc, 0.0, 0)
+    assert np.allclose(one["abs_sum"], np.abs(one["clipped_sum"]), rtol=1e-15, atol=0)
