@@ -1,0 +1,213 @@
+// Networks that are one or two dense layers: the whole per-example part of the private step in one launch.
+//
+// For a dense layer the example's gradient is the outer product a_i (x) delta_i (plus delta_i for the bias), so
+// its norm is sqrt((||a_i||^2 + 1) ||delta_i||^2) (Section 1: the per-example norm of fully connected layers)
+// and everything up to the clip factor depends on that example alone: logits, loss gradient, norm and clip factor
+// are computed by the wave that owns the example, and the workgroup then adds s_i a_i (x) delta_i of its examples
+// into one partial of the clipped sum (Section 1, items 2-3).  The final write (finalize_kernel) sums the partials
+// in a fixed order and adds the noise.  Two launches per step for softmax regression instead of four.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_tile.h" // FastDiv
+
+#define DENSE1_THREADS 1024  // 16 waves: one row of the [d_in + 1][N] tensor per thread
+#define DENSE1_MAX_IN 1023   // input features (+ the bias row): one row per thread
+#define DENSE1_MAX_CLASSES 15
+#define DENSE1_MAX_LDS_WORDS 15000 // in_features * (classes padded to 4 / 10 / 15 + DENSE1_EX): W transposed and one
+                                   // group of inputs in 64 KB of LDS
+#define DENSE1_EX 4          // examples per group
+#define DENSE1_MAX_TILES 256 // partials of the clipped sum (workgroups)
+
+struct Dense1Args {
+  const float *x;    // [B][d_in]
+  const float *W;    // [d_in][N]
+  const float *bias; // [N]
+  const int *y;      // [B]
+  float *part;       // [tiles][(d_in + 1) * N]: partial clipped sums in the parameter layout (W then bias)
+  float *norms;      // [B] unclipped norms (may be null)
+  float *s;          // [B] clip factors (may be null)
+  float *delta;      // [B][N] loss gradient (may be null)
+  int B, d_in, N;
+  int groups;        // groups of DENSE1_EX examples per workgroup
+  float C;           // clip norm (private step)
+  int priv;          // 0: plain sum (every factor 1)
+  FastDiv dN;        // division by N
+};
+
+static inline int dense1_ncp(int n_classes) { return n_classes <= 4 ? 4 : (n_classes <= 10 ? 10 : 15); }
+static inline bool dense1_fits(int d_in, int n_classes) {
+  return d_in >= 1 && n_classes >= 1 && d_in <= DENSE1_MAX_IN && n_classes <= DENSE1_MAX_CLASSES &&
+         (long)d_in * (dense1_ncp(n_classes) + DENSE1_EX) <= DENSE1_MAX_LDS_WORDS;
+}
+
+// Tiling shared by every caller: at most max_tiles partial rows, whole groups of DENSE1_EX examples per workgroup.
+static inline void dense1_tiling(int B, int max_tiles, int *groups, int *tiles) {
+  const int ngroups = (B + DENSE1_EX - 1) / DENSE1_EX;
+  int t = max_tiles < DENSE1_MAX_TILES ? max_tiles : DENSE1_MAX_TILES;
+  if (t < 1) t = 1;
+  const int g = ngroups > 0 ? (ngroups + t - 1) / t : 1;
+  *groups = g;
+  *tiles = ngroups > 0 ? (ngroups + g - 1) / g : 0;
+}
+
+// One workgroup of 16 waves per run of groups of four examples.  Per group:
+//   1. the four input rows go to LDS (the next group's are requested meanwhile);
+//   2. lane (e, j) of every wave multiplies example e with class j's weights over the wave's sixteenth of the
+//      features (lane (e, 15): with the example itself, for ||x_e||^2); the sixteen partial sums meet in LDS -- no
+//      cross-lane reduction of long vectors anywhere;
+//   3. wave 0 finishes the four examples: softmax, loss gradient, norm (dense identity), clip factor;
+//   4. thread k adds s_e x_e[k] delta_e (k = d_in: the bias row, x = 1) of the four examples to its row of the
+//      workgroup's partial clipped sum, which stays in registers over the whole run.
+template <int NCP>
+__global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dense1Args a) {
+  extern __shared__ float lds[];
+  const int d_in = a.d_in, N = a.N, ldw = d_in | 1; // odd row length: the classes' rows start on different banks
+  float *xs = lds;                    // [DENSE1_EX][d_in]: the group's inputs
+  float *wt = xs + DENSE1_EX * d_in;  // [NCP][ldw]: W transposed, zero rows for the padding classes
+  float *zp = wt + NCP * ldw;         // [16 waves][64 lanes]: partial dot products
+  float *dl = zp + 16 * 64;           // [DENSE1_EX][NCP]: s_e * delta_e
+  float *bs = dl + DENSE1_EX * NCP;   // [16]: bias, -inf for the padding classes (their softmax term is 0)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int e = lane >> 4, jj = lane & 15;
+  float acc[NCP];
+#pragma unroll
+  for (int j = 0; j < NCP; ++j) acc[j] = 0.f;
+
+  // the first group's inputs (HBM: the longest latency) are requested before the weights (L2)
+  const long x_total = (long)a.B * d_in;
+  const int x_group = DENSE1_EX * d_in; // the rows of a group's examples are contiguous
+  float xv[4];
+  {
+    const long base = (long)blockIdx.x * a.groups * x_group;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const int i = tid + DENSE1_THREADS * n;
+      const long g = base + i;
+      xv[n] = a.x[(i < x_group && g < x_total) ? g : 0]; // always a valid address; masked when stored
+    }
+  }
+  // every other global read of the prologue is in flight before the first one is waited for: the weights (L2),
+  // the bias and the first group's labels
+  const int b_first = blockIdx.x * a.groups * DENSE1_EX + e;
+  int yv = a.y[b_first < a.B ? b_first : 0];
+  const float bv = a.bias[tid < N ? tid : 0];
+  {
+    const int w_total = d_in * N;
+    float wv[16];
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const int i = tid + DENSE1_THREADS * n;
+      wv[n] = a.W[i < w_total ? i : 0];
+    }
+    for (int i = N * ldw + tid; i < NCP * ldw; i += DENSE1_THREADS) wt[i] = 0.f;
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const int i = tid + DENSE1_THREADS * n;
+      if (i < w_total) {
+        const int k = (int)a.dN.div((unsigned)i), j = i - k * N;
+        wt[j * ldw + k] = wv[n];
+      }
+    }
+  }
+  if (tid < 16) bs[tid] = tid < N ? bv : -INFINITY;
+  // the wave's sixteenth of the features
+  const int kc = (d_in + 15) >> 4;
+  const int k0 = wave * kc, k1 = min(d_in, k0 + kc);
+
+  for (int grp = 0; grp < a.groups; ++grp) {
+    const long gbase = ((long)blockIdx.x * a.groups + grp) * x_group;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const int i = tid + DENSE1_THREADS * n;
+      if (i < x_group) xs[i] = (gbase + i < x_total) ? xv[n] : 0.f;
+    }
+    __syncthreads();
+    const int yy = yv;
+    if (grp + 1 < a.groups) {
+      const long base = gbase + x_group;
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const int i = tid + DENSE1_THREADS * n;
+        const long g = base + i;
+        xv[n] = a.x[(i < x_group && g < x_total) ? g : 0];
+      }
+      const int bn = (blockIdx.x * a.groups + grp + 1) * DENSE1_EX + e;
+      yv = a.y[bn < a.B ? bn : 0];
+    }
+    // ---- 2. partial dot products
+    {
+      const float *ap = xs + e * d_in;
+      const float *bp = jj < NCP ? wt + jj * ldw : ap; // lane 15 of an example: the example with itself
+      float z = 0.f;
+#pragma unroll 8
+      for (int k = k0; k < k1; ++k) z = fmaf(ap[k], bp[k], z);
+      zp[wave * 64 + lane] = z;
+    }
+    __syncthreads();
+    // ---- 3. wave 0: the four examples' loss gradients, norms and clip factors
+    if (wave == 0) {
+      float z = 0.f;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) z += zp[w * 64 + lane];
+      const int b = (blockIdx.x * a.groups + grp) * DENSE1_EX + e;
+      const bool valid = b < a.B;
+      const float sa = __shfl(z, (lane & 48) + 15, 64); // ||x_e||^2
+      z = jj < 15 ? z + bs[jj] : -INFINITY;            // logits; padding lanes drop out of the softmax
+      float mx = z;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+      const float ex = expf(z - mx);
+      float se = ex;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+      const float dv = ex / se - (jj == yy ? 1.f : 0.f); // delta_e[jj] (padding lanes: 0)
+      float sd = dv * dv;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) sd += __shfl_xor(sd, o, 64);
+      const float n = sqrtf((sa + 1.f) * sd);
+      const float sc = a.priv ? fminf(1.f, a.C / n) : 1.f; // n == 0: C/0 = +inf -> 1
+      if (jj < NCP) dl[e * NCP + jj] = valid ? sc * dv : 0.f;
+      if (valid && jj == 0) {
+        if (a.norms) a.norms[b] = n;
+        if (a.s) a.s[b] = sc;
+      }
+      if (valid && a.delta && jj < N) a.delta[(long)b * N + jj] = dv;
+    }
+    __syncthreads();
+    // ---- 4. the group's examples added to the partial: thread = row tid of the [d_in + 1][N] tensor
+    if (tid <= d_in) {
+#pragma unroll
+      for (int q = 0; q < DENSE1_EX; ++q) {
+        const float v = tid < d_in ? xs[q * d_in + tid] : 1.f; // the bias row multiplies a constant 1
+#pragma unroll
+        for (int j = 0; j < NCP; ++j) acc[j] = fmaf(v, dl[q * NCP + j], acc[j]);
+      }
+    }
+    __syncthreads();
+  }
+  if (tid <= d_in) {
+    float *pr = a.part + (long)blockIdx.x * ((long)(d_in + 1) * N) + (long)tid * N;
+#pragma unroll
+    for (int j = 0; j < NCP; ++j)
+      if (j < N) pr[j] = acc[j];
+  }
+}
+
+// Launches the kernel above on `st`; returns the number of partial rows written (0 for an empty batch).
+static inline int launch_dense1_fused(hipStream_t st, Dense1Args a, int max_tiles) {
+  int groups = 1, tiles = 0;
+  dense1_tiling(a.B, max_tiles, &groups, &tiles);
+  if (tiles == 0) return 0;
+  a.groups = groups;
+  a.dN.init(a.N);
+  dim3 grid(tiles), block(DENSE1_THREADS);
+  const int ncp = dense1_ncp(a.N);
+  const size_t smem = sizeof(float) * ((size_t)DENSE1_EX * a.d_in + (size_t)ncp * (a.d_in | 1) + 16 * 64 + DENSE1_EX * ncp + 16);
+  if (ncp == 4) hipLaunchKernelGGL(dense1_fused_kernel<4>, grid, block, smem, st, a);
+  else if (ncp == 10) hipLaunchKernelGGL(dense1_fused_kernel<10>, grid, block, smem, st, a);
+  else hipLaunchKernelGGL(dense1_fused_kernel<15>, grid, block, smem, st, a);
+  return tiles;
+}

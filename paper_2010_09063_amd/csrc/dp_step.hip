@@ -17,6 +17,7 @@
 #include "conv_direct.h"
 #include "conv_gram.h"
 #include "conv_wino.h"
+#include "dense_fused.h"
 #include "kernels_misc.h"
 #include "kernels_seq.h"
 #include "operands.h"
@@ -187,6 +188,7 @@ struct dp_ctx {
   float *norms = nullptr, *s = nullptr;
   float *ones = nullptr; // [maxB] of 1.0: the clip factors of a step that clips nothing
   int last_batch = -1;
+  bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   // profiling
   bool prof = false;
   std::vector<const char *> labels; // string literals
@@ -611,6 +613,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   }
   c->P = off;
   c->max_slots = total_slots;
+  c->fused1 = c->L.size() == 1 && c->L[0].d.kind == DP_DENSE && dense1_fits(c->L[0].d.in_features, c->L[0].d.out_features);
   for (size_t i = 0; i < c->L.size(); ++i) {
     c->L[i].lab.reserve(sizeof(kLayerLabels) / sizeof(kLayerLabels[0]));
     for (const char *nm : kLayerLabels) c->L[i].lab.push_back(std::string(nm) + "#" + std::to_string(i));
@@ -817,7 +820,20 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
   // the network ends in a dense layer of at most 64 classes: its bias, the loss gradient and its norm share a launch
   const bool fused_head = c->L[nL - 1].d.kind == DP_DENSE && c->L[nL - 1].d.out_features <= 64;
   int head_ns = 0; // forward split-K partials of the last layer still to be summed (0: its output is complete)
-  if (B > 0) {
+  if (B > 0 && c->fused1) {
+    // softmax regression: logits, loss gradient, norm, clip factor and the clipped partial sums in one launch
+    Layer &l = c->L[0];
+    Dense1Args a{};
+    a.x = (const float *)x; a.W = params; a.bias = params + (long)l.d.in_features * l.d.out_features; a.y = (const int *)y;
+    a.part = l.part; a.norms = priv ? c->norms : nullptr; a.s = priv ? c->s : nullptr; a.delta = nullptr;
+    a.B = B; a.d_in = l.d.in_features; a.N = l.d.out_features; a.C = C; a.priv = priv ? 1 : 0;
+    int tiles = 0;
+    Ln("dense1_fused", dim3(1), dim3(256), [&](hipStream_t st) {
+      tiles = launch_dense1_fused(st, a, std::min(DENSE1_MAX_TILES, l.max_split));
+    });
+    FinalizeSeg &sg = fa.seg[fa.nseg++];
+    sg.p_off = 0; sg.n = l.p_count; sg.part = l.part; sg.stride = l.p_count; sg.nsplit = tiles;
+  } else if (B > 0) {
     // ------------------------------------------------------------ re-laid weights of the direct convolutions
     {
       ConvLayoutArgs la{};
@@ -1542,3 +1558,4 @@ extern "C" int dp_step_profile_read(dp_ctx *c, int cap, const char **labels, int
     for (int i = 0; i < n; ++i) { c->label_launches[i] = 0; c->label_ms[i] = 0.f; }
   return n;
 }
+
