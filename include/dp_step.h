@@ -43,7 +43,8 @@ typedef enum {
   DP_EINVAL = -1, /* null pointer, bad shape, batch > max_batch, C <= 0, sigma < 0, NaN */
   DP_ENOMEM = -2, /* workspace allocation failed */
   DP_EHIP = -3,   /* a HIP runtime call failed; see dp_step_strerror */
-  DP_EUNSUPPORTED = -4 /* layer sequence the kernels do not cover */
+  DP_EUNSUPPORTED = -4, /* layer sequence the kernels do not cover */
+  DP_ETOOBIG = -5       /* dp_step_dense1_static: sizes beyond its fixed scratch */
 } dp_status;
 
 typedef enum {
@@ -140,6 +141,26 @@ int dp_step_sgd(dp_ctx *ctx, float *params, const void *x, const int32_t *y, int
  */
 int dp_step_nonprivate(dp_ctx *ctx, const float *params, const void *x, const int32_t *y, int batch,
                        float *out_grad);
+
+/*
+ * dp_step_dense1_static -- dp_step for a model that is ONE dense layer (softmax regression: logits = x W + b),
+ * for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It needs no context and calls no allocating routine: its scratch (partial clipped sums and clip
+ * factors) is a fixed 8 MiB array in the library's device image, one copy per GPU for the life of the process.
+ *   params     device fp32[(in_features + 1) * n_classes]: W[in_features][n_classes] row-major, then b
+ *   x, y       device fp32[batch, in_features], int32[batch]
+ *   norms_out  device fp32[batch] or NULL: receives the unclipped per-example norms
+ *   hip_stream a hipStream_t (NULL = the default stream) the two launches are enqueued on
+ *   C, sigma, seed, out_grad: as for dp_step; results equal dp_step's on the same model to rounding.
+ * Limits: in_features <= 1023, n_classes <= 15, in_features * (n_classes rounded up to 4, 10 or
+ * 15, + 4) <= 15000, batch <= 65536; beyond
+ * them DP_ETOOBIG and nothing is launched.
+ * Every call on one GPU uses that GPU's one scratch array: calls that overlap in time on one GPU (two streams,
+ * two threads) race on it; serialise them.  Nothing in the array needs clearing between calls.
+ */
+int dp_step_dense1_static(const float *params, const float *x, const int32_t *y, int batch, int in_features,
+                          int n_classes, float C, float sigma, uint64_t seed, float *out_grad, float *norms_out,
+                          void *hip_stream);
 
 /*
  * dp_step_last_norms -- copies the unclipped per-example norms ||g_i|| of the

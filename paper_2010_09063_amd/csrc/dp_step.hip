@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <type_traits>
 #include <vector>
@@ -764,6 +765,8 @@ extern "C" const char *dp_step_strerror(int code) {
   case DP_ENOMEM: return g_hip_err[0] ? g_hip_err : "out of device memory";
   case DP_EHIP: return g_hip_err[0] ? g_hip_err : "HIP runtime error";
   case DP_EUNSUPPORTED: return "layer sequence or size not supported by the kernels";
+  case DP_ETOOBIG: return "sizes beyond the limits of the allocation-free entry point (in_features <= 1023, n_classes <= 15, "
+                          "in_features * (n_classes rounded up to 4, 10 or 15, + 4) <= 15000, batch <= 65536)";
   default: return "unknown status";
   }
 }
@@ -1559,3 +1562,67 @@ extern "C" int dp_step_profile_read(dp_ctx *c, int cap, const char **labels, int
   return n;
 }
 
+// ---------------------------------------------------------------- allocation-free entry point
+
+// Scratch of dp_step_dense1_static: the partial clipped sums [tiles][P] and the clip factors [batch].  Every GPU
+// the library is loaded on holds its own copy of this array until the process ends; host code reaches it only
+// through the per-device address that hipGetSymbolAddress returns (the array's name is not a device address).
+#define DP_STATIC_FLOATS (2l << 20) // 8 MiB
+#define DP_STATIC_MAX_BATCH 65536
+#define DP_STATIC_MAX_DEVICES 64
+static __device__ __align__(256) float dp_static_scratch[DP_STATIC_FLOATS];
+static std::mutex g_static_mu;
+static float *g_static_ptr[DP_STATIC_MAX_DEVICES] = {};
+
+static int static_scratch_ptr(float **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= DP_STATIC_MAX_DEVICES) return DP_EINVAL;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (g_static_ptr[dev] == nullptr) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(dp_static_scratch)));
+    if (p == nullptr) return DP_EHIP;
+    g_static_ptr[dev] = (float *)p;
+  }
+  *out = g_static_ptr[dev];
+  return DP_OK;
+}
+
+extern "C" int dp_step_dense1_static(const float *params, const float *x, const int32_t *y, int batch, int in_features,
+                                     int n_classes, float C, float sigma, uint64_t seed, float *out_grad,
+                                     float *norms_out, void *hip_stream) {
+  if (!params || !out_grad || batch < 0 || in_features < 1 || n_classes < 1) return DP_EINVAL;
+  if (batch > 0 && (!x || !y)) return DP_EINVAL;
+  if (!(C > 0.f) || !(sigma >= 0.f) || std::isnan(C) || std::isinf(sigma)) return DP_EINVAL;
+  if (std::isinf(C) && sigma > 0.f) return DP_EINVAL;
+  if (!dense1_fits(in_features, n_classes) || batch > DP_STATIC_MAX_BATCH) return DP_ETOOBIG;
+  const long P = (long)(in_features + 1) * n_classes;
+  const long max_tiles = (DP_STATIC_FLOATS - DP_STATIC_MAX_BATCH) / P; // the clip factors take the last 65,536 floats
+  if (max_tiles < 1) return DP_ETOOBIG;
+  float *scratch = nullptr;
+  int rc = static_scratch_ptr(&scratch);
+  if (rc != DP_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  FinalizeArgs fa;
+  fa.nseg = 1;
+  FinalizeSeg &sg = fa.seg[0];
+  sg.p_off = 0; sg.n = P; sg.part = scratch; sg.stride = P; sg.nsplit = 0;
+  if (batch > 0) {
+    Dense1Args a{};
+    a.x = x; a.W = params; a.bias = params + (long)in_features * n_classes; a.y = (const int *)y;
+    a.part = scratch; a.norms = norms_out; a.s = scratch + (DP_STATIC_FLOATS - DP_STATIC_MAX_BATCH); a.delta = nullptr;
+    a.B = batch; a.d_in = in_features; a.N = n_classes; a.C = C; a.priv = 1;
+    sg.nsplit = launch_dense1_fused(st, a, (int)std::min<long>(DENSE1_MAX_TILES, max_tiles));
+  }
+  const float noise_std = sigma > 0.f ? sigma * C : 0.f;
+  dim3 grid = grid1d(P, DP_FIN_CO), block(256);
+  hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out_grad, P, noise_std, (uint32_t)seed, (uint32_t)(seed >> 32),
+                     (float *)nullptr, 0.f);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "kernel launch: %s", hipGetErrorString(e));
+    return DP_EHIP;
+  }
+  return DP_OK;
+}

@@ -12,13 +12,13 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdpstep.so")
 
-DP_OK, DP_EINVAL, DP_ENOMEM, DP_EHIP, DP_EUNSUPPORTED = 0, -1, -2, -3, -4
+DP_OK, DP_EINVAL, DP_ENOMEM, DP_EHIP, DP_EUNSUPPORTED, DP_ETOOBIG = 0, -1, -2, -3, -4, -5
 _KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4, "seq_mean": 5,
          "lstm_seq": 6, "avgpool2d": 7}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 EXPORTS = ["dp_step_init", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
-           "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
+           "dp_step_dense1_static", "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
 
 
 class dp_layer_desc(C.Structure):
@@ -56,6 +56,9 @@ def load_library():
                                   C.c_uint64, C.c_float, C.c_void_p]
         L.dp_step_nonprivate.restype = C.c_int
         L.dp_step_nonprivate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.dp_step_dense1_static.restype = C.c_int
+        L.dp_step_dense1_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                            C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
         L.dp_step_last_norms.restype = C.c_int
         L.dp_step_last_norms.argtypes = [C.c_void_p, C.c_void_p]
         L.dp_step_profile.restype = C.c_int
@@ -117,6 +120,17 @@ def model_desc(m):
 
 def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+# -- include/dp_step.h: dp_step_dense1_static (no context, no allocation)
+def dp_step_dense1_static(params, x, y, batch, in_features, n_classes, C_, sigma, seed, out_grad, norms_out=None,
+                          stream=None):
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().dp_step_dense1_static(_ptr(params), _ptr(x), _ptr(y), int(batch), int(in_features),
+                                                int(n_classes), float(C_), float(sigma),
+                                                C.c_uint64(int(seed) & (2**64 - 1)), _ptr(out_grad), _ptr(norms_out),
+                                                C.c_void_p(st.cuda_stream)))
 
 
 class DpStep:
