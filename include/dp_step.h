@@ -91,18 +91,54 @@ typedef struct {
  * before the first step so nothing is allocated afterwards).
  *   model      host; copied.
  *   hip_stream a hipStream_t (NULL = the default stream); every later call
- *              enqueues its work there.
+ *              enqueues its work there.  Init itself returns with the workspace
+ *              ready for a step enqueued on that stream.
  *   out        host; receives the context.
  * Flat parameter layout: layers in order, each weight tensor then its bias, in
  * the layouts named at dp_layer_kind.
  */
 int dp_step_init(const dp_model_desc *model, int max_batch, void *hip_stream, dp_ctx **out);
 
-/* Number of fp32 parameters P of the model (0 if ctx is NULL). */
+/*
+ * Route switches (utility, no passage of the paper): every field 0 is the plan the library picks by itself.  A
+ * non-zero field keeps one family of kernels out (or forces one in) for tests and A/B measurements; the results
+ * are the same to rounding whichever route runs.  Read once by dp_step_init_ex; a context never changes its plan.
+ */
+typedef struct {
+  int generic_conv;               /* 3x3 stride-1 convolutions on the generic tiled contraction                   */
+  int no_minimal_filtering;       /* no kernel of the F(2x2,3x3) / F(3x3,2x2) family                              */
+  int no_minimal_filtering_wgrad; /* only that family's weight-gradient kernels off                               */
+  int minimal_filtering_all;      /* its forward / backward-data kernels for every eligible shape                 */
+  int no_pool_fusion;             /* 2x2 / stride-2 pools as launches of their own, not in the conv epilogue      */
+  int no_gram;                    /* small-plane convolution norms by the per-example contraction                 */
+  int no_stored_gradients;        /* never store per-example gradients: the clipped sum repeats the contraction   */
+  int no_columns;                 /* strided backward-data by the gathering contraction                           */
+  int no_specialised_waves;       /* weight gradient of wide layers on the single-buffer kernel                   */
+  int specialised_waves_all;      /* ... or the staging / multiplying wave split for every width                  */
+  int conv_min_blocks;            /* grid the direct forward kernel narrows its tiles for (0: 512)                */
+  int gemm_plain_tiles;           /* tile choice of the generic contraction without the padding-waste rule        */
+  int no_fused_dense;             /* one-dense-layer models on the generic kernels (four launches)                */
+  int reserved[7];                /* zero                                                                          */
+} dp_plan_options;
+
+/* dp_step_init with route switches; options == NULL is dp_step_init. */
+int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *hip_stream, const dp_plan_options *options,
+                    dp_ctx **out);
+
+/* Number of fp32 parameters P of the model (0 if ctx is NULL).  Utility, no passage. */
 size_t dp_step_num_params(const dp_ctx *ctx);
 
-/* Bytes of device workspace the context holds. */
+/* Bytes of device workspace the context holds (Section 4 discusses memory as what bounds the batch size). */
 size_t dp_step_workspace_bytes(const dp_ctx *ctx);
+
+/*
+ * dp_step_validate -- debug check of the integer inputs, which dp_step itself trusts: counts the labels outside
+ * [0, n_classes) and, for token models, the ids outside [0, vocab).  Utility, no passage.
+ *   x, y    device, as for dp_step (x is read only when the model takes token ids)
+ *   n_bad   host; receives the count (0 = the batch is safe to pass to dp_step)
+ * Synchronises the context's stream.
+ */
+int dp_step_validate(dp_ctx *ctx, const void *x, const int32_t *y, int batch, int *n_bad);
 
 /*
  * dp_step -- the private step (Section 1, DPSGD items 2-3).
@@ -123,9 +159,10 @@ int dp_step(dp_ctx *ctx, const float *params, const void *x, const int32_t *y, i
             uint64_t seed, float *out_grad);
 
 /*
- * dp_step_sgd -- dp_step followed by the parameter update of the same procedure (Section 1,
- * item 4: "update the parameters by a step against the noised aggregate"), fused into the
- * final write:   params[j] -= (lr / batch) * (clipped_sum[j] + sigma*C*z_j).
+ * dp_step_sgd -- dp_step followed by the parameter update of the same procedure (Section 1, DPSGD
+ * item 4), fused into the final write:   params[j] -= (lr / batch) * (clipped_sum[j] + sigma*C*z_j).
+ * (An extension: the step proper ends with the noised sum; dividing by the batch size and updating
+ * otherwise stay with the caller.)
  *   params     device, [num_params], read by the step and UPDATED IN PLACE by its last kernel.
  *   lr         learning rate; the aggregate is a sum over the batch, so the step uses lr / batch.
  *   out_grad   device, [num_params] or NULL: where given, also receives the noised sum as dp_step writes it.
@@ -165,12 +202,13 @@ int dp_step_dense1_static(const float *params, const float *x, const int32_t *y,
 /*
  * dp_step_last_norms -- copies the unclipped per-example norms ||g_i|| of the
  * most recent dp_step into norms_out (device fp32[batch of that step]);
- * enqueued on the context's stream.  Test hook for the clipping invariant.
+ * enqueued on the context's stream.  Test hook for the clipping invariant (Section 1, item 2b:
+ * after clipping no example's gradient is longer than C).
  */
 int dp_step_last_norms(dp_ctx *ctx, float *norms_out);
 
 /*
- * Per-kernel timing.  With profiling on, every kernel launch of later steps is
+ * Per-kernel timing (utility, no passage).  With profiling on, every kernel launch of later steps is
  * bracketed by HIP events on the context's stream.  dp_step_profile_read
  * synchronises the stream and returns, for up to `cap` distinct kernel labels
  * in launch order: the label (pointer into the context, valid until free), the
@@ -180,10 +218,10 @@ int dp_step_last_norms(dp_ctx *ctx, float *norms_out);
 int dp_step_profile(dp_ctx *ctx, int enable);
 int dp_step_profile_read(dp_ctx *ctx, int cap, const char **labels, int *launches, float *total_ms, int reset);
 
-/* Static description of a status code, plus the last HIP error text for DP_EHIP. */
+/* Static description of a status code, plus the last HIP error text for DP_EHIP.  Utility, no passage. */
 const char *dp_step_strerror(int code);
 
-/* Releases the context and its workspace (NULL is a no-op). */
+/* Releases the context and its workspace (NULL is a no-op).  Utility, no passage. */
 void dp_step_free(dp_ctx *ctx);
 
 #ifdef __cplusplus

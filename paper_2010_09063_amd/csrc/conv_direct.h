@@ -760,11 +760,16 @@ __global__ __launch_bounds__(512, 1) void conv_s1_wgrad_ws_kernel(const ConvWgAr
         dok = ok ? (dok | (1u << j)) : (dok & ~(1u << j));
       }
     };
-    auto flush_rows = [&](int par) { // this thread's row sums into rsum[par]
+    // The row sums into rsum[par], in a fixed order: the PQ threads that hold the pixels of one row are consecutive
+    // lanes of one wave (PQ is a power of two of at most 64: the host selects this kernel only then), so they are
+    // summed with exchanges inside the wave and the row's first lane is the only writer of its entry.
+    auto flush_rows = [&](int par) {
 #pragma unroll
       for (int j = 0; j < DV; ++j) {
         const int d = (int)a.dPQ.div(ptid + j * 256);
-        if (d_lds[j] >= 0) atomicAdd(&rsum[par][d], rowsum[j]);
+        float v = rowsum[j];
+        for (int o = PQ >> 1; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (d_lds[j] >= 0 && (ptid & (PQ - 1)) == 0) rsum[par][d] += v;
         rowsum[j] = 0.f;
       }
     };

@@ -189,6 +189,8 @@ struct dp_ctx {
   float *norms = nullptr, *s = nullptr;
   float *ones = nullptr; // [maxB] of 1.0: the clip factors of a step that clips nothing
   int last_batch = -1;
+  dp_plan_options opt{}; // route switches, read once at init
+  int *bad = nullptr;    // dp_step_validate: number of out-of-range ids / labels
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   // profiling
   bool prof = false;
@@ -213,6 +215,7 @@ static int label_id(dp_ctx *c, const char *name) {
 // Brackets a launch with events when profiling is on.
 struct Launcher {
   dp_ctx *c;
+  bool waste_aware() const { return c->opt.gemm_plain_tiles == 0; }
   template <class F>
   void operator()(const char *label, dim3, dim3, F &&f) const {
     if (c->prof && c->pool_used + 2 <= c->pool.size()) {
@@ -288,7 +291,8 @@ static int make_wino_region(ConvWinoRegion &rg, int H, int W) {
   return ceil_div(WINO_CC * rg.RS, 256);
 }
 
-static void plan_direct_conv(Layer &l, int maxB, bool allow) {
+static void plan_direct_conv(Layer &l, int maxB, const dp_plan_options &opt) {
+  const bool allow = opt.generic_conv == 0;
   const ConvGeom &g = l.geom;
   if (!allow || g.S != 1 || g.KH != 3 || g.KW != 3 || g.PAD > 2) return;
   if ((long)maxB * g.C * g.H * g.W >= (1l << 31) || (long)maxB * g.D * g.P >= (1l << 31)) return;
@@ -308,9 +312,9 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
   // channel instead of 36.  Measured against the direct kernel: ahead wherever a workgroup covers 64 output
   // channels; with 32 it is ahead only for short channel loops; the grid must still fill the chip.
   if (l.dir_fwd && l.dir_bwd && g.PAD == 1 && g.H == g.OH && g.W == g.OW && (g.H & 1) == 0 && (g.W & 1) == 0 &&
-      is_pow2(g.W / 2) && is_pow2((g.H / 2) * (g.W / 2)) && getenv("DP_STEP_NO_WINO") == nullptr) {
+      is_pow2(g.W / 2) && is_pow2((g.H / 2) * (g.W / 2)) && !opt.no_minimal_filtering) {
     l.u_f_planned = true;
-    const bool all = getenv("DP_STEP_WINO_ALL") != nullptr; // tests: the kernel for every eligible shape
+    const bool all = opt.minimal_filtering_all != 0; // tests: the kernel for every eligible shape
     ConvWinoRegion rg;
     const bool fits = make_wino_region(rg, g.H, g.W) <= 9; // staging items per thread the kernels are built for
     auto pick = [&](int Cin, int M) {
@@ -329,18 +333,18 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       return db;
     };
     // weight gradients in the same form with the roles exchanged (conv_wino_wgrad_unit_kernel): batch sums on 8x8 planes
-    l.wino_wg = g.H == 8 && g.W == 8 && g.C % 32 == 0 && g.D % 64 == 0 && getenv("DP_STEP_NO_WINO_WG") == nullptr;
+    l.wino_wg = g.H == 8 && g.W == 8 && g.C % 32 == 0 && g.D % 64 == 0 && !opt.no_minimal_filtering_wgrad;
     // and per band of 16 tiles on 16- and 32-wide planes: whole blocks of 32 input channels, 32 or 64 output channels
     l.wino_wgu = g.C % 32 == 0 && (g.D == 32 || g.D == 64) &&
                  ((g.W == 32 && g.D == 32 && g.H % 2 == 0) || (g.W == 16 && g.H % 4 == 0)) &&
-                 getenv("DP_STEP_NO_WINO_WG") == nullptr;
+                 !opt.no_minimal_filtering_wgrad;
     l.wino_f = pick(g.C, g.D);
     l.wino_b = pick(g.D, g.C);
   }
   // per-example norm from Gram matrices: P^2 (9C + D) multiply-adds instead of 9 C D P, for the two plane sizes
   // the kernel is built for (pad 1, so the input plane equals the output plane)
   if (g.PAD == 1 && g.H == g.OH && g.W == g.OW && ((g.OH == 8 && g.OW == 8) || (g.OH == 4 && g.OW == 4)) &&
-      (long)g.P * (g.CKK + g.D) < (long)g.D * g.CKK && getenv("DP_STEP_NO_GRAM") == nullptr)
+      (long)g.P * (g.CKK + g.D) < (long)g.D * g.CKK && !opt.no_gram)
     l.gram = true;
   // weight gradient
   const bool flat = g.C * 9 <= 32 && g.D <= 32;
@@ -366,9 +370,12 @@ static void plan_direct_conv(Layer &l, int maxB, bool allow) {
       if (fits) { l.dir_wg = true; l.wg_db = db; l.wg_flat = flat; }
       // specialised-wave variant: two staging buffers + the cross-wave area must fit one CU's LDS
       // (measured: pays where the single-buffer kernel runs one workgroup per CU, i.e. 128 output channels)
-      if (fits && (db == 4 || getenv("DP_STEP_WS_ALL") != nullptr)) {
+      if (fits && (db == 4 || opt.specialised_waves_all)) {
         const long ws = 2 * std::max(lds_n, lds_c) + xs + 64;
-        l.wg_ws = ws * 4 + 2048 <= 160 * 1024 && getenv("DP_STEP_NO_WS") == nullptr;
+        // its bias sums are exchanged inside a wave: the threads of one Delta row must be a power of two of lanes
+        const int pq_n = l.t_wgn.NIMG * l.t_wgn.TR * g.OW / 4, pq_c = l.t_wgc.NIMG * l.t_wgc.TR * g.OW / 4;
+        const bool rows_ok = is_pow2(pq_n) && pq_n <= 64 && is_pow2(pq_c) && pq_c <= 64;
+        l.wg_ws = ws * 4 + 2048 <= 160 * 1024 && rows_ok && !opt.no_specialised_waves;
       }
     }
   }
@@ -380,7 +387,7 @@ static void launch_conv_s1(const LN &Ln, const char *label, const ConvS1Args &a,
   const int cc = a.Cin <= 4 ? 4 : 8; // first layers: a chunk of four channels covers the whole input
   const int pix_blocks = a.t.NIMG > 1 ? ceil_div(a.B, a.t.NIMG) : a.B * a.t.row_tiles;
   // a small batch of small planes leaves CUs idle with wide output tiles: narrow them until the grid fills the chip
-  static const int min_blocks = getenv("DP_CONV_MINBLOCKS") ? atoi(getenv("DP_CONV_MINBLOCKS")) : 512;
+  const int min_blocks = Ln.c->opt.conv_min_blocks > 0 ? Ln.c->opt.conv_min_blocks : 512;
   while (dt > 32 && pix_blocks * ceil_div(a.M, dt) < min_blocks) dt >>= 1;
   dim3 grid(pix_blocks, ceil_div(a.M, dt)), block(256);
   size_t smem = sizeof(float) * ((size_t)cc * a.t.XPLANE + (size_t)cc * 9 * dt);
@@ -507,9 +514,15 @@ static ConvWgArgs make_wg_args(const Layer &l, const float *x, int B, const Conv
 // ---------------------------------------------------------------- init / free
 
 extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip_stream, dp_ctx **out) {
+  return dp_step_init_ex(model, max_batch, hip_stream, nullptr, out);
+}
+
+extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *hip_stream, const dp_plan_options *options,
+                               dp_ctx **out) {
   if (!model || !out || max_batch < 1 || model->n_layers < 1 || !model->layers) return DP_EINVAL;
   dp_ctx *c = new (std::nothrow) dp_ctx();
   if (!c) return DP_ENOMEM;
+  if (options) c->opt = *options;
   c->m = *model;
   c->m.layers = nullptr;
   c->maxB = max_batch;
@@ -587,8 +600,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     l.out_size = (long)l.outC * l.outH * l.outW;
     if (l.d.kind == DP_CONV2D) {
       l.geom = make_geom(l);
-      const char *env = getenv("DP_STEP_GENERIC_CONV"); // "1": keep every convolution on the generic contraction
-      plan_direct_conv(l, max_batch, !(env && env[0] == '1'));
+      plan_direct_conv(l, max_batch, c->opt);
     }
     off += l.p_count;
     total_slots += l.max_slots;
@@ -614,7 +626,8 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   }
   c->P = off;
   c->max_slots = total_slots;
-  c->fused1 = c->L.size() == 1 && c->L[0].d.kind == DP_DENSE && dense1_fits(c->L[0].d.in_features, c->L[0].d.out_features);
+  c->fused1 = c->L.size() == 1 && c->L[0].d.kind == DP_DENSE && dense1_fits(c->L[0].d.in_features, c->L[0].d.out_features) &&
+              !c->opt.no_fused_dense;
   for (size_t i = 0; i < c->L.size(); ++i) {
     c->L[i].lab.reserve(sizeof(kLayerLabels) / sizeof(kLayerLabels[0]));
     for (const char *nm : kLayerLabels) c->L[i].lab.push_back(std::string(nm) + "#" + std::to_string(i));
@@ -636,7 +649,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     }
     if (rc == DP_OK && l.d.kind == DP_DENSE) {
       // a small output with a long K would leave most CUs idle and expose every load's latency: split K
-      GemmShape sh = pick_tile(max_batch, l.d.out_features, 1);
+      GemmShape sh = pick_tile(max_batch, l.d.out_features, 1, c->opt.gemm_plain_tiles == 0);
       long tiles = (long)sh.tiles_m * sh.tiles_n;
       int by_k = l.d.in_features / 64;
       if (tiles < 512 && by_k >= 2) {
@@ -653,32 +666,32 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       const size_t nf = rf * ((l.geom.D + 3) & ~3) + 128, nb = rb * ((l.geom.C + 3) & ~3) + 128;
       rc = dev_alloc(c, &l.wt_f, nf);
       if (rc == DP_OK) rc = dev_alloc(c, &l.wt_b, nb);
-      if (rc == DP_OK && (hipMemset(l.wt_f, 0, nf * sizeof(float)) != hipSuccess ||
-                          hipMemset(l.wt_b, 0, nb * sizeof(float)) != hipSuccess)) rc = DP_EHIP;
+      if (rc == DP_OK && (hipMemsetAsync(l.wt_f, 0, nf * sizeof(float), c->stream) != hipSuccess ||
+                          hipMemsetAsync(l.wt_b, 0, nb * sizeof(float), c->stream) != hipSuccess)) rc = DP_EHIP;
     }
     if (rc == DP_OK && l.wino_f) {
       l.uf_cpad = ceil_div(l.geom.C, WINO_CC) * WINO_CC; l.uf_mpad = ceil_div(l.geom.D, 32 * l.wino_f) * 32 * l.wino_f;
       const size_t n = (size_t)16 * l.uf_cpad * l.uf_mpad;
       rc = dev_alloc(c, &l.u_f, n);
-      if (rc == DP_OK && hipMemset(l.u_f, 0, n * sizeof(float)) != hipSuccess) rc = DP_EHIP;
+      if (rc == DP_OK && hipMemsetAsync(l.u_f, 0, n * sizeof(float), c->stream) != hipSuccess) rc = DP_EHIP;
     }
     if (rc == DP_OK && l.wino_b && &l != &c->L.front()) {
       l.ub_cpad = ceil_div(l.geom.D, WINO_CC) * WINO_CC; l.ub_mpad = ceil_div(l.geom.C, 32 * l.wino_b) * 32 * l.wino_b;
       const size_t n = (size_t)16 * l.ub_cpad * l.ub_mpad;
       rc = dev_alloc(c, &l.u_b, n);
-      if (rc == DP_OK && hipMemset(l.u_b, 0, n * sizeof(float)) != hipSuccess) rc = DP_EHIP;
+      if (rc == DP_OK && hipMemsetAsync(l.u_b, 0, n * sizeof(float), c->stream) != hipSuccess) rc = DP_EHIP;
     }
     // Strided convolutions (no direct kernel): backward-data as a plain per-example product into columns followed
     // by a gather over the windows, instead of a contraction whose Delta operand is gathered element by element
     // with most of the strided taps empty
     if (rc == DP_OK && l.d.kind == DP_CONV2D && !l.dir_bwd && l.geom.S > 1 && &l != &c->L.front() &&
-        (size_t)mb * l.geom.CKK * l.geom.P <= ((size_t)1 << 28) && getenv("DP_STEP_NO_COLS") == nullptr)
+        (size_t)mb * l.geom.CKK * l.geom.P <= ((size_t)1 << 28) && !c->opt.no_columns)
       rc = dev_alloc(c, &l.cols, (size_t)mb * l.geom.CKK * l.geom.P);
     // Large planes: the norm pass writes each example's gradient (8 bytes of traffic per coordinate, written and
     // read once) and the clipped sum becomes a weighted sum of those rows; repeating the contraction instead costs
     // 2 P flops per coordinate, which is more from P = 256 pixels on.
     if (rc == DP_OK && l.d.kind == DP_CONV2D && l.dir_wg && !l.gram && !l.wg_ws && l.geom.D <= DP_WG_DSLICE &&
-        l.geom.P >= 256 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
+        l.geom.P >= 256 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && !c->opt.no_stored_gradients) {
       // the order in which conv_s1_wgrad_kernel<3, 3, wg_db, wg_flat, false> holds the gradient in its accumulators
       GradOrder &o = l.gorder;
       const ConvGeom &g = l.geom;
@@ -704,7 +717,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
     // the same route for convolutions on the generic contraction (other strides / filter sizes): its per-example
     // tile is [D][C*KK + 1], the last column being the bias gradient
     if (rc == DP_OK && l.d.kind == DP_CONV2D && !l.dir_wg && !l.gram && l.geom.P >= 128 &&
-        (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
+        (size_t)mb * l.p_count <= ((size_t)1 << 30) && !c->opt.no_stored_gradients) {
       GradOrder &o = l.gorder;
       o = GradOrder{};
       o.C = l.geom.C; o.D = l.geom.D; o.KK = l.geom.KH * l.geom.KW; o.flat = 3;
@@ -727,7 +740,7 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
       // long sequences: the norm contraction writes each example's gradient ([Din + H + 1][4H], which is the layer's
       // parameter layout) and the clipped sum is a weighted sum of those rows: 8 bytes of traffic per coordinate
       // against the 2 T flops of contracting it again
-      if (rc == DP_OK && l.T >= 128 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && getenv("DP_STEP_NO_GSTORE") == nullptr) {
+      if (rc == DP_OK && l.T >= 128 && (size_t)mb * l.p_count <= ((size_t)1 << 30) && !c->opt.no_stored_gradients) {
         l.gorder = GradOrder{};
         l.gorder.flat = 2; l.gorder.n_total = l.p_count;
         rc = dev_alloc(c, &l.gst, (size_t)mb * l.p_count);
@@ -738,10 +751,14 @@ extern "C" int dp_step_init(const dp_model_desc *model, int max_batch, void *hip
   if (rc == DP_OK) rc = dev_alloc(c, &c->norms, mb);
   if (rc == DP_OK) rc = dev_alloc(c, &c->s, mb);
   if (rc == DP_OK) rc = dev_alloc(c, &c->ones, mb);
+  if (rc == DP_OK) rc = dev_alloc(c, &c->bad, 1);
   if (rc == DP_OK) {
     std::vector<float> one(mb, 1.f);
     if (hipMemcpy(c->ones, one.data(), sizeof(float) * mb, hipMemcpyHostToDevice) != hipSuccess) rc = DP_EHIP;
   }
+  // the zero fills above were enqueued on the context's stream (which need not be ordered against the null
+  // stream): they are complete before the first step can be enqueued
+  if (rc == DP_OK && hipStreamSynchronize(c->stream) != hipSuccess) rc = DP_EHIP;
   if (rc != DP_OK) { dp_step_free(c); return rc; }
   *out = c;
   return DP_OK;
@@ -892,7 +909,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     // ------------------------------------------------------------ forward
     const float *in = (const float *)x;
     int fused_pool = -1;
-    static const bool no_pool_fusion = getenv("DP_STEP_NO_POOL_FUSION") != nullptr;
+    const bool no_pool_fusion = c->opt.no_pool_fusion != 0;
     for (int i = 0; i < nL; ++i) {
       Layer &l = c->L[i];
       const float *W = params + l.p_off;
@@ -1509,6 +1526,34 @@ extern "C" int dp_step_nonprivate(dp_ctx *c, const float *params, const void *x,
   if (!c || !params || !out_grad || batch < 0 || batch > c->maxB) return DP_EINVAL;
   if (batch > 0 && (!x || !y)) return DP_EINVAL;
   return run_step(c, params, x, y, batch, false, INFINITY, 0.f, 0, out_grad);
+}
+
+// counts labels outside [0, n_classes) and token ids outside [0, vocab)
+__global__ void validate_kernel(const int *__restrict__ y, int B, int n_classes, const int *__restrict__ tok, long n_tok,
+                                int vocab, int *__restrict__ bad) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  int mine = 0;
+  if (i < B) mine += (unsigned)y[i] >= (unsigned)n_classes;
+  if (i < n_tok) mine += (unsigned)tok[i] >= (unsigned)vocab;
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, 64);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(bad, mine);
+}
+__global__ void zero_int_kernel(int *p) { *p = 0; }
+
+extern "C" int dp_step_validate(dp_ctx *c, const void *x, const int32_t *y, int batch, int *n_bad) {
+  if (!c || !n_bad || batch < 0 || batch > c->maxB) return DP_EINVAL;
+  *n_bad = 0;
+  if (batch == 0) return DP_OK;
+  if (!x || !y) return DP_EINVAL;
+  const bool tok = c->m.seq_len > 0;
+  const long n_tok = tok ? (long)batch * c->m.seq_len : 0;
+  const long n = std::max<long>(batch, n_tok);
+  hipLaunchKernelGGL(zero_int_kernel, dim3(1), dim3(1), 0, c->stream, c->bad);
+  hipLaunchKernelGGL(validate_kernel, grid1d(n, 256), dim3(256), 0, c->stream, (const int *)y, batch, c->m.n_classes,
+                     tok ? (const int *)x : (const int *)nullptr, n_tok, tok ? c->L[0].d.vocab : 1, c->bad);
+  HIP_TRY(hipMemcpyAsync(n_bad, c->bad, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  return DP_OK;
 }
 
 extern "C" int dp_step_last_norms(dp_ctx *c, float *norms_out) {

@@ -312,7 +312,7 @@ static inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 
 // Picks the tile for an M x N output: the largest that does not waste more than
 // it must, shrinking while the launch would leave most of the 256 CUs idle.
-static inline GemmShape pick_tile(int M, int N, long other_blocks) {
+static inline GemmShape pick_tile(int M, int N, long other_blocks, bool waste_aware = true) {
   int bm = M <= 32 ? 32 : (M <= 64 ? 64 : 128);
   int bn = N <= 32 ? 32 : (N <= 64 ? 64 : 128);
   auto blocks = [&](int a, int b) { return (long)ceil_div(M, a) * ceil_div(N, b) * other_blocks; };
@@ -321,7 +321,6 @@ static inline GemmShape pick_tile(int M, int N, long other_blocks) {
   if (bm == 64 && bn == 32) bm = M <= 48 ? 32 : 128;
   if (bm == 128 && bn == 128) {
     // a 64-wide side where it cuts the padded area by more than the smaller tile costs (measured: about 10 %)
-    static const bool waste_aware = getenv("DP_GEMM_WASTE") == nullptr || getenv("DP_GEMM_WASTE")[0] != '0';
     if (waste_aware) {
       auto padded = [&](int a, int b) { return (double)ceil_div(M, a) * a * ceil_div(N, b) * b; };
       const double full = padded(128, 128);
@@ -374,7 +373,7 @@ static inline void launch_gemm_shape(P p, GemmShape s, int batch, int splits, La
 // one K range per block, `batch` independent problems
 template <class P, class Launcher>
 static inline GemmShape launch_gemm(P p, int batch, Launcher &&L, const char *label) {
-  GemmShape s = pick_tile(p.M, p.N, batch);
+  GemmShape s = pick_tile(p.M, p.N, batch, L.waste_aware());
   p.k_chunk = (p.K + 31) / 32 * 32;
   launch_gemm_shape(p, s, batch, 1, L, label);
   return s;
@@ -386,7 +385,7 @@ static inline int launch_gemm_split(P p, int max_split, Launcher &&L, const char
   long by_k = p.K / 64;
   if (by_k < 1) by_k = 1;
   if (by_k > max_split) by_k = max_split;
-  GemmShape s = pick_tile(p.M, p.N, by_k);
+  GemmShape s = pick_tile(p.M, p.N, by_k, L.waste_aware());
   long tiles = (long)s.tiles_m * s.tiles_n;
   // a handful of tiles: the launch is one serial chain of loads per workgroup, so the shortest chunks the kernel
   // takes (32) halve its duration

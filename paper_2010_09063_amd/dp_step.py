@@ -17,7 +17,7 @@ _KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4
          "lstm_seq": 6, "avgpool2d": 7}
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
-EXPORTS = ["dp_step_init", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
+EXPORTS = ["dp_step_init", "dp_step_init_ex", "dp_step_validate", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
            "dp_step_dense1_static", "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
 
 
@@ -29,6 +29,15 @@ class dp_layer_desc(C.Structure):
 class dp_model_desc(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("layers", C.POINTER(dp_layer_desc)), ("in_c", C.c_int), ("in_h", C.c_int),
                 ("in_w", C.c_int), ("seq_len", C.c_int), ("n_classes", C.c_int)]
+
+
+PLAN_OPTIONS = ("generic_conv", "no_minimal_filtering", "no_minimal_filtering_wgrad", "minimal_filtering_all",
+                "no_pool_fusion", "no_gram", "no_stored_gradients", "no_columns", "no_specialised_waves",
+                "specialised_waves_all", "conv_min_blocks", "gemm_plain_tiles", "no_fused_dense")
+
+
+class dp_plan_options(C.Structure):
+    _fields_ = [(n, C.c_int) for n in PLAN_OPTIONS] + [("reserved", C.c_int * 7)]
 
 
 _lib = None
@@ -44,6 +53,11 @@ def load_library():
         L = C.CDLL(LIB_PATH)
         L.dp_step_init.restype = C.c_int
         L.dp_step_init.argtypes = [C.POINTER(dp_model_desc), C.c_int, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.dp_step_init_ex.restype = C.c_int
+        L.dp_step_init_ex.argtypes = [C.POINTER(dp_model_desc), C.c_int, C.c_void_p, C.POINTER(dp_plan_options),
+                                      C.POINTER(C.c_void_p)]
+        L.dp_step_validate.restype = C.c_int
+        L.dp_step_validate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         L.dp_step_num_params.restype = C.c_size_t
         L.dp_step_num_params.argtypes = [C.c_void_p]
         L.dp_step_workspace_bytes.restype = C.c_size_t
@@ -134,9 +148,10 @@ def dp_step_dense1_static(params, x, y, batch, in_features, n_classes, C_, sigma
 
 
 class DpStep:
-    """Owns one dp_ctx.  `stream` is a torch.cuda.Stream (default: the current one)."""
+    """Owns one dp_ctx.  `stream` is a torch.cuda.Stream (default: the current one); keyword options are the fields
+    of dp_plan_options (route switches for tests and A/B measurements)."""
 
-    def __init__(self, m, max_batch, stream=None):
+    def __init__(self, m, max_batch, stream=None, **options):
         import torch
         self._lib = load_library()
         self._torch = torch
@@ -145,8 +160,17 @@ class DpStep:
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         md, keep = model_desc(m)
         ctx = C.c_void_p(0)
-        _check(self._lib.dp_step_init(C.byref(md), int(max_batch), C.c_void_p(self.stream.cuda_stream),
-                                      C.byref(ctx)))
+        if options:
+            opt = dp_plan_options()
+            for k, v in options.items():
+                if k not in PLAN_OPTIONS:
+                    raise TypeError(f"unknown plan option {k!r}")
+                setattr(opt, k, int(v))
+            _check(self._lib.dp_step_init_ex(C.byref(md), int(max_batch), C.c_void_p(self.stream.cuda_stream),
+                                             C.byref(opt), C.byref(ctx)))
+        else:
+            _check(self._lib.dp_step_init(C.byref(md), int(max_batch), C.c_void_p(self.stream.cuda_stream),
+                                          C.byref(ctx)))
         self._ctx = ctx
         self.num_params = int(self._lib.dp_step_num_params(ctx))
         self.workspace_bytes = int(self._lib.dp_step_workspace_bytes(ctx))
@@ -166,6 +190,12 @@ class DpStep:
     # -- dp_step_nonprivate
     def dp_step_nonprivate(self, params, x, y, batch, out_grad):
         _check(self._lib.dp_step_nonprivate(self._ctx, _ptr(params), _ptr(x), _ptr(y), int(batch), _ptr(out_grad)))
+
+    # -- dp_step_validate
+    def dp_step_validate(self, x, y, batch):
+        n = C.c_int(0)
+        _check(self._lib.dp_step_validate(self._ctx, _ptr(x), _ptr(y), int(batch), C.byref(n)))
+        return int(n.value)
 
     # -- dp_step_last_norms
     def dp_step_last_norms(self, norms_out):

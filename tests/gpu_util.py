@@ -27,12 +27,13 @@ TAU = 2e-6
 MAX_FLIPPED_FRACTION = 0.05
 
 
-def run_gpu(m, params, x, y, C, sigma, seed, private=True, max_batch=None, want_norms=True, stepper=None):
+def run_gpu(m, params, x, y, C, sigma, seed, private=True, max_batch=None, want_norms=True, stepper=None,
+            options=None):
     import torch
     from paper_2010_09063_amd import DpStep
     B = int(len(y))
     dev = torch.device("cuda:0")
-    st = stepper if stepper is not None else DpStep(m, max_batch or max(B, 1))
+    st = stepper if stepper is not None else DpStep(m, max_batch or max(B, 1), **(options or {}))
     P = st.num_params
     tp = torch.from_numpy(np.ascontiguousarray(params, dtype=np.float32)).to(dev)
     xdt = np.float32 if m["input"]["kind"] == "image" else np.int32
@@ -169,9 +170,10 @@ class TieAwareOracle:
         return csum, norms, flips
 
 
-def check_step(m, theta, x, y, C, ref, label, tie=None, private=True, stepper=None):
+def check_step(m, theta, x, y, C, ref, label, tie=None, private=True, stepper=None, options=None):
     """One GPU step against the oracle result `ref` (same C), whole batch, every tensor, every norm."""
-    out, gn = run_gpu(m, theta, x, y, C if private else 1.0, 0.0, 0, private=private, stepper=stepper)
+    out, gn = run_gpu(m, theta, x, y, C if private else 1.0, 0.0, 0, private=private, stepper=stepper,
+                      options=options)
     if tie is None:
         tie = TieAwareOracle(m, theta, x, y, ref["pool_margin"])
     csum, norms, flips = tie.reference(ref, C, out, clip=private)

@@ -22,7 +22,7 @@ def _case(m, batch, seed, x_dist="normal", bias=0.3, scale=1.0, zipf=0.3):
     return x, y, theta
 
 
-def _check_all_regimes(m, x, y, theta, label, stepper=None):
+def _check_all_regimes(m, x, y, theta, label, stepper=None, options=None):
     """Whole batch, every parameter tensor, every per-example norm, in the three clipping regimes and for the
     non-private sum (max-pool windows tied at rounding level: see tests/gpu_util.py)."""
     ref_inf = O.dp_step(m, theta, x, y, math.inf, 0.0, 0)
@@ -31,12 +31,14 @@ def _check_all_regimes(m, x, y, theta, label, stepper=None):
     regimes = [math.inf, float(np.median(n0)), 0.1 * float(n0.min())]
     for Cc in regimes:
         ref = ref_inf if math.isinf(Cc) else O.dp_step(m, theta, x, y, Cc, 0.0, 0)
-        out, gn, norms = check_step(m, theta, x, y, Cc, ref, f"{label} C={Cc:.4g}", tie=tie, stepper=stepper)
+        out, gn, norms = check_step(m, theta, x, y, Cc, ref, f"{label} C={Cc:.4g}", tie=tie, stepper=stepper,
+                                    options=options)
         if not math.isinf(Cc):
             s = np.minimum(1.0, Cc / gn.astype(np.float64))
             assert np.all(s * norms <= Cc * (1 + 1e-5))
     ref_np = O.dp_step(m, theta, x, y, 1.0, 0.0, 0, clip=False)
-    check_step(m, theta, x, y, 1.0, ref_np, f"{label} non-private", tie=tie, private=False, stepper=stepper)
+    check_step(m, theta, x, y, 1.0, ref_np, f"{label} non-private", tie=tie, private=False, stepper=stepper,
+               options=options)
 
 
 @pytest.mark.parametrize("name", sorted(TINY))
@@ -119,17 +121,16 @@ def test_context_reuse_and_smaller_batches():
     st.dp_step_free()
 
 
-def test_context_reuse_with_minimal_filtering_kernels(monkeypatch):
+def test_context_reuse_with_minimal_filtering_kernels():
     """One context planned for the largest batch serves smaller ones: the minimal-filtering kernels (forward,
     backward-data with the pool in the epilogue, weight gradients) size their grids and split counts from the batch
     of the call, the plan from the batch of the context."""
     from paper_2010_09063_amd import DpStep
-    monkeypatch.setenv("DP_STEP_WINO_ALL", "1")
     m = W.model(W.image_input(32, 16, 16), [
         W.conv2d(32, 32, 3, stride=1, pad=1, act="tanh"), W.conv2d(32, 64, 3, stride=1, pad=1, act="tanh"),
         W.maxpool2d(2, 2), W.conv2d(64, 64, 3, stride=1, pad=1, act="relu"), W.avgpool2d(2, 2),
         W.dense(64 * 4 * 4, 3)], 3)
-    st = DpStep(m, 9)
+    st = DpStep(m, 9, minimal_filtering_all=1)
     for batch in (9, 2, 7, 1):
         x, y, theta = _case(m, batch, seed=50 + batch)
         ref = O.dp_step(m, theta, x, y, 5.0, 0.0, 0)
@@ -162,15 +163,19 @@ def test_argument_errors():
         DpStep(bad, 4)
 
 
-def test_generic_convolution_path_matches_too(monkeypatch):
-    """DP_STEP_GENERIC_CONV=1 keeps 3x3 stride-1 convolutions on the functor contraction
-    (the path every other kernel size / stride takes)."""
-    monkeypatch.setenv("DP_STEP_GENERIC_CONV", "1")
+def test_generic_convolution_path_matches_too():
+    """generic_conv keeps 3x3 stride-1 convolutions on the functor contraction (the path every other kernel size /
+    stride takes); gemm_plain_tiles picks its tiles without the padding-waste rule."""
+    opt = dict(generic_conv=1)
     m = TINY["tiny_conv3"]
     x, y, theta = _case(m, 9, seed=21)
-    _check_all_regimes(m, x, y, theta, "tiny_conv3/generic")
+    _check_all_regimes(m, x, y, theta, "tiny_conv3/generic", options=opt)
     wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
-    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/generic")
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/generic", options=opt)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/generic, plain tiles",
+                       options=dict(generic_conv=1, gemm_plain_tiles=1))
+    wl = W.make_workload("cfg5_lstm", batch=5, seed=4, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg5/plain tiles", options=dict(gemm_plain_tiles=1))
 
 
 def test_many_examples_per_workgroup():
@@ -193,27 +198,25 @@ def test_many_examples_per_workgroup():
     assert rel_l2(out, ref_c["clipped_sum"]) <= TOL
 
 
-def test_recompute_routes_match_too(monkeypatch):
+def test_recompute_routes_match_too():
     """With the Gram norms, the stored-gradient route and the column route of strided backward-data switched off,
     the library takes the routes it otherwise keeps for shapes those do not cover (direct per-example contraction
     for the norm, a second contraction for the clipped sum, the gathering backward-data contraction)."""
-    monkeypatch.setenv("DP_STEP_NO_GRAM", "1")
-    monkeypatch.setenv("DP_STEP_NO_GSTORE", "1")
-    monkeypatch.setenv("DP_STEP_NO_COLS", "1")
+    opt = dict(no_gram=1, no_stored_gradients=1, no_columns=1)
     for name, batch in (("tiny_conv_gram", 9), ("tiny_conv_store", 6), ("tiny_conv_stride", 11), ("tiny_lstm_seq", 5)):
         m = TINY[name]
         x, y, theta = _case(m, batch, seed=41, scale=4.0 if m["input"]["kind"] == "tokens" else 1.0)
-        _check_all_regimes(m, x, y, theta, f"{name}/recompute")
+        _check_all_regimes(m, x, y, theta, f"{name}/recompute", options=opt)
     wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
-    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/recompute")
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/recompute", options=opt)
     m = W.paper_lstm(vocab=300, seq_len=140, dim=20, hidden=24)  # 140 steps: above the stored-gradient threshold
     rng = np.random.default_rng(9)
     x, y = W.make_inputs(m, 4, rng)
     theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
-    _check_all_regimes(m, x, y, theta, "lstm_seq/T140/recompute")
+    _check_all_regimes(m, x, y, theta, "lstm_seq/T140/recompute", options=opt)
 
 
-def test_minimal_filtering_route(monkeypatch):
+def test_minimal_filtering_route():
     """Forward and backward-data of the pad-1 3x3 convolutions through the F(2x2, 3x3) kernel at sizes the oracle
     covers element by element (the library keeps that kernel for launches that fill the chip; here it is forced):
     4x4, 8x8 and 16x16 planes, channel counts that are no multiples of the 8-channel chunk or of the 32 / 64 output
@@ -223,28 +226,28 @@ def test_minimal_filtering_route(monkeypatch):
     stored gradients on 16- and 32-wide planes, clipped sums on 8x8 planes, and the batch sums of the non-private
     step; the last part switches the whole family off at full batch."""
     cases = (("tiny_conv_gram", 9), ("tiny_conv_store", 6), ("tiny_conv_wide", 13), ("tiny_conv_wide", 1))
-    monkeypatch.setenv("DP_STEP_WINO_ALL", "1")
+    opt = dict(minimal_filtering_all=1)
     for name, batch in cases:
         m = TINY[name]
         x, y, theta = _case(m, batch, seed=43)
-        _check_all_regimes(m, x, y, theta, f"{name}/minimal-filtering")
+        _check_all_regimes(m, x, y, theta, f"{name}/minimal-filtering", options=opt)
     # 32x32 planes with 64 output channels per workgroup, forward (8 -> 40) and backward-data (16 -> 40)
     m = W.model(W.image_input(8, 32, 32), [
         W.conv2d(8, 40, 3, stride=1, pad=1, act="tanh"), W.conv2d(40, 16, 3, stride=1, pad=1, act="tanh"),
         W.avgpool2d(8, 8), W.dense(16 * 4 * 4, 3)], 3)
     x, y, theta = _case(m, 3, seed=44)
-    _check_all_regimes(m, x, y, theta, "planes32/minimal-filtering")
+    _check_all_regimes(m, x, y, theta, "planes32/minimal-filtering", options=opt)
     wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
-    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/minimal-filtering")
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/minimal-filtering", options=opt)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/minimal-filtering, pools apart",
+                       options=dict(minimal_filtering_all=1, no_pool_fusion=1))
     wl = W.make_workload("paper_cifar_cnn", batch=5, seed=6, bias_scale=0.2)
-    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "paper_cifar/minimal-filtering")
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "paper_cifar/minimal-filtering", options=opt)
     # full batch with that route switched off: the direct kernels in the launch shapes of the benchmark batch
-    monkeypatch.delenv("DP_STEP_WINO_ALL")
-    monkeypatch.setenv("DP_STEP_NO_WINO", "1")
     wl = W.make_workload("cfg4_cifar_cnn", seed=0)
     m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
     ref = O.dp_step(m, theta, x, y, wl["C"], 0.0, 0)
-    check_step(m, theta, x, y, wl["C"], ref, "cfg4 full batch, direct kernels")
+    check_step(m, theta, x, y, wl["C"], ref, "cfg4 full batch, direct kernels", options=dict(no_minimal_filtering=1))
 
 
 def test_weight_gradients_in_minimal_filtering_form():
@@ -260,14 +263,95 @@ def test_weight_gradients_in_minimal_filtering_form():
     _check_all_regimes(m, x, y, theta, "planes16x16+8x8/weight gradients")
 
 
-def test_weight_gradients_direct_kernels_on_the_same_network(monkeypatch):
-    monkeypatch.setenv("DP_STEP_NO_WINO_WG", "1")
+def test_weight_gradients_direct_kernels_on_the_same_network():
     m = W.model(W.image_input(32, 16, 16), [
         W.conv2d(32, 32, 3, stride=1, pad=1, act="tanh"), W.conv2d(32, 64, 3, stride=1, pad=1, act="tanh"),
         W.maxpool2d(2, 2), W.conv2d(64, 64, 3, stride=1, pad=1, act="relu"), W.avgpool2d(2, 2),
         W.dense(64 * 4 * 4, 3)], 3)
     x, y, theta = _case(m, 5, seed=46)
-    _check_all_regimes(m, x, y, theta, "planes16x16+8x8/direct weight gradients")
+    _check_all_regimes(m, x, y, theta, "planes16x16+8x8/direct weight gradients",
+                       options=dict(no_minimal_filtering_wgrad=1))
+
+
+def _wide_conv_net():
+    # 8x8 planes, 128 output channels: the weight-gradient kernels with 144 accumulator registers per lane
+    return W.model(W.image_input(32, 8, 8), [
+        W.conv2d(32, 128, 3, stride=1, pad=1, act="tanh"), W.conv2d(128, 128, 3, stride=1, pad=1, act="tanh"),
+        W.conv2d(128, 64, 3, stride=1, pad=1, act="tanh"), W.dense(64 * 8 * 8, 3)], 3)
+
+
+@pytest.mark.parametrize("opt", [dict(no_gram=1, no_minimal_filtering=1),
+                                 dict(no_gram=1, no_minimal_filtering=1, no_specialised_waves=1),
+                                 dict(no_gram=1, no_minimal_filtering=1, specialised_waves_all=1),
+                                 dict(no_gram=1, no_minimal_filtering=1, specialised_waves_all=1, no_stored_gradients=1)],
+                         ids=["ws-wide-only", "no-ws", "ws-all", "ws-all-recompute"])
+def test_specialised_wave_weight_gradients(opt):
+    """The weight-gradient kernel whose waves split into staging and multiplying ones (norm and clipped-sum modes),
+    for the 128-channel layers it is planned for, switched off, and forced for every width; batches that give a
+    workgroup several examples and a ragged last run."""
+    m = _wide_conv_net()
+    for batch in (3, 70):
+        x, y, theta = _case(m, batch, seed=60 + batch)
+        _check_all_regimes(m, x, y, theta, f"wide conv/B{batch}/{sorted(opt)}", options=opt)
+    if "specialised_waves_all" in opt:
+        m = TINY["tiny_conv_store"]
+        x, y, theta = _case(m, 6, seed=61)
+        _check_all_regimes(m, x, y, theta, f"tiny_conv_store/{sorted(opt)}", options=opt)
+
+
+def test_remaining_route_switches():
+    """conv_min_blocks (tile narrowing of the direct forward kernel, both extremes) and no_fused_dense (a one-layer
+    model on the generic kernels)."""
+    m = TINY["tiny_conv3"]
+    x, y, theta = _case(m, 9, seed=21)
+    for mb in (1, 1 << 20):
+        _check_all_regimes(m, x, y, theta, f"tiny_conv3/min_blocks={mb}", options=dict(conv_min_blocks=mb, no_minimal_filtering=1))
+    wl = W.make_workload("cfg1_logistic", batch=100, seed=2, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg1/generic kernels", options=dict(no_fused_dense=1))
+
+
+def test_one_layer_models_of_other_widths():
+    """The fused softmax-regression kernel at class counts that pad to 4, 10 and 15 lanes, feature counts below one
+    wave's share and at the limit, batches that end inside a group of four and that give a workgroup several groups."""
+    for d_in, k, batch in ((5, 2, 7), (9, 4, 1), (1023, 10, 33), (300, 15, 1100), (784, 10, 1026)):
+        m = W.model(W.image_input(d_in), [W.dense(d_in, k)], k)
+        x, y, theta = _case(m, batch, seed=d_in)
+        _check_all_regimes(m, x, y, theta, f"dense {d_in}->{k}/B{batch}")
+
+
+def test_side_stream_and_validate():
+    """A context on a non-default stream (its init-time fills must be ordered before the first step), and the debug
+    range check of labels and token ids."""
+    import torch
+    from paper_2010_09063_amd import DpStep
+    dev = torch.device("cuda:0")
+    side = torch.cuda.Stream()
+    wl = W.make_workload("cfg4_cifar_cnn", batch=4, seed=3, bias_scale=0.2)
+    m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    ref = O.dp_step(m, theta, x, y, 0.5, 0.0, 0)
+    tp, tx, ty = (torch.from_numpy(a).to(dev) for a in (theta, x, y))
+    out = torch.empty(theta.size, device=dev)
+    torch.cuda.synchronize()
+    st = DpStep(m, 4, stream=side)
+    st.dp_step(tp, tx, ty, 4, 0.5, 0.0, 0, out)   # enqueued right after init, on the side stream
+    side.synchronize()
+    tie = TieAwareOracle(m, theta, x, y, ref["pool_margin"])
+    csum, _, _ = tie.reference(ref, 0.5, out.cpu().numpy())
+    assert_parity(m, out.cpu().numpy(), csum, "side stream", ref["abs_sum"])
+    assert st.dp_step_validate(tx, ty, 4) == 0
+    bad_y = ty.clone()
+    bad_y[1], bad_y[3] = 10, -1
+    assert st.dp_step_validate(tx, bad_y, 4) == 2
+    st.dp_step_free()
+    wl = W.make_workload("cfg5_lstm", batch=3, seed=3)
+    st = DpStep(wl["model"], 3)
+    tx, ty = torch.from_numpy(wl["x"]).to(dev), torch.from_numpy(wl["y"]).to(dev)
+    assert st.dp_step_validate(tx, ty, 3) == 0
+    tx[0, 5], tx[2, 255], tx[1, 0] = 10000, -7, 9999
+    ty[0] = 2
+    assert st.dp_step_validate(tx, ty, 3) == 3
+    assert st.dp_step_validate(None, None, 0) == 0
+    st.dp_step_free()
 
 
 def test_long_sequence_stored_gradients():
@@ -369,6 +453,38 @@ def test_repeatable_and_profile_hook():
     st.dp_step(tp, tx, ty, 64, 1.0, 1.1, 8, o2)
     torch.cuda.synchronize()
     assert not torch.equal(o1, o2)
+    st.dp_step_free()
+
+
+@pytest.mark.parametrize("name,batch,opt", [("cfg4_cifar_cnn", None, {}), ("paper_cifar_cnn", None, {}), ("cfg2_mlp", None, {}),
+                                            ("cfg1_logistic", None, {}), ("cfg5_lstm", 64, {}), ("wide", 70, dict(no_gram=1, no_minimal_filtering=1))],
+                         ids=["cfg4", "paper_cifar", "cfg2", "cfg1", "cfg5-dense-tensors", "wide-ws"])
+def test_bit_identical_repeats_at_full_batch(name, batch, opt):
+    """Every reduction of the step runs in a fixed order: two steps on the same inputs agree bit for bit, at the
+    benchmark batch (the embedding tensor excepted: the chunks of a hot token meet through fp32 atomics)."""
+    import torch
+    from paper_2010_09063_amd import DpStep
+    dev = torch.device("cuda:0")
+    if name == "wide":
+        m = _wide_conv_net()
+        x, y, theta = _case(m, batch, seed=3)
+    else:
+        wl = W.make_workload(name, batch=batch, seed=0)
+        m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    B = len(y)
+    st = DpStep(m, B, **opt)
+    tp, tx, ty = (torch.from_numpy(a).to(dev) for a in (theta, x, y))
+    outs = []
+    for rep in range(3):
+        o = torch.empty(st.num_params, device=dev)
+        st.dp_step(tp, tx, ty, B, 1.0, 1.1, 5, o)
+        outs.append(o)
+    torch.cuda.synchronize()
+    lo = 0
+    for li, tname, shp, off in W.param_tensors(m):
+        n = int(np.prod(shp))
+        if tname != "E":
+            assert torch.equal(outs[0][off:off + n], outs[1][off:off + n]) and torch.equal(outs[0][off:off + n], outs[2][off:off + n]), (name, li, tname)
     st.dp_step_free()
 
 
