@@ -172,6 +172,29 @@ int dp_step_sgd(dp_ctx *ctx, float *params, const void *x, const int32_t *y, int
                 uint64_t seed, float lr, float *out_grad);
 
 /*
+ * dp_step_sample_indices -- the minibatch draw of the procedure (Section 1, DPSGD item 1; the paper leaves the
+ * draw open): `batch` indices drawn independently and uniformly from [0, n_examples), with replacement.  Index k
+ * is (word k%4 of the Philox4x32-10 block with key `seed` and counter (k/4, 0, 1, 0)) * n_examples >> 32; the
+ * third counter word keeps these blocks apart from the noise stream of the same seed.
+ *   indices    device int32[batch]; enqueued on hip_stream (NULL = the default stream); 1 <= n_examples < 2^31.
+ */
+int dp_step_sample_indices(uint64_t seed, int64_t n_examples, int batch, int32_t *indices, void *hip_stream);
+
+/*
+ * dp_step_loop -- `steps` iterations of the whole procedure (Section 1, DPSGD items 1-4) on a dataset resident in
+ * device memory, with no host work between the steps but kernel launches.  Step t (t = 0 ...) uses seed0 + t for
+ * its draw and its noise: draw `batch` indices (dp_step_sample_indices), gather those examples, take the private
+ * step on them and update:  params -= (lr / batch) * (sum_i clip(g_i) + sigma*C*z).
+ *   params           device fp32[P], updated in place after every step
+ *   data_x, data_y   device; fp32[n_examples, in_c, in_h, in_w] or int32[n_examples, seq_len]; int32[n_examples]
+ *   batch            1 .. max_batch of the context
+ * The first call on a context allocates room for one drawn minibatch (freed with the context); later calls
+ * allocate nothing.  Asynchronous like dp_step.  (An extension beyond the step proper, as dp_step_sgd is.)
+ */
+int dp_step_loop(dp_ctx *ctx, float *params, const void *data_x, const int32_t *data_y, int64_t n_examples, int steps,
+                 int batch, float C, float sigma, uint64_t seed0, float lr);
+
+/*
  * dp_step_nonprivate -- the ordinary summed gradient sum_i g_i with the same
  * forward / backward kernels and no norms, clipping or noise (the comparator of
  * the paper's private / non-private runtime ratio, Table 1).

@@ -681,6 +681,48 @@ int oracle_sgd_step(const or_model *m, const float *params, const void *x, const
   return rc;
 }
 
+/* DPSGD item 1 (Section 1): the minibatch.  The paper leaves the draw open; the reading taken is `batch` indices
+ * drawn independently and uniformly from [0, n) (with replacement), index k from lane k%4 of the Philox block
+ * with counter (k/4 lo, k/4 hi, 1, 0) -- third counter word 1, so the draw never shares a block with the noise
+ * stream of the same seed (third word 0) -- mapped to the range by the multiply-shift (r * n) >> 32. */
+void oracle_sample_indices(uint64_t seed, long n, int batch, int32_t *idx) {
+  uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  for (int k = 0; k < batch; ++k) {
+    uint64_t blk = (uint64_t)(k >> 2);
+    uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), 1u, 0u}, r[4];
+    oracle_philox4x32_10(ctr, key, r);
+    idx[k] = (int32_t)(((uint64_t)r[k & 3] * (uint64_t)n) >> 32);
+  }
+}
+
+/* `steps` iterations of the whole procedure (Section 1, items 1-4) on a dataset held in memory: step t draws its
+ * minibatch and its noise from seed0 + t, takes the private step on the drawn examples and updates the parameters.
+ * params_out receives the parameters after the last step (rounded to float after every step, as a caller that
+ * chains oracle_sgd_step would hold them). */
+int oracle_train(const or_model *m, const float *params, const void *data_x, const int32_t *data_y, long n, int steps,
+                 int B, double C, double sigma, uint64_t seed0, double lr, float *params_out, int n_threads) {
+  long P = oracle_num_params(m);
+  long xstride = m->seq_len > 0 ? m->seq_len : (long)m->in_c * m->in_h * m->in_w;
+  if (B < 1 || n < 1) return -1;
+  float *cur = (float *)malloc(sizeof(float) * P), *next = (float *)malloc(sizeof(float) * P);
+  int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * B), *yb = (int32_t *)malloc(sizeof(int32_t) * B);
+  char *xb = (char *)malloc((size_t)B * xstride * 4);
+  memcpy(cur, params, sizeof(float) * P);
+  int rc = 0;
+  for (int t = 0; t < steps && rc == 0; ++t) {
+    oracle_sample_indices(seed0 + (uint64_t)t, n, B, idx);
+    for (int k = 0; k < B; ++k) {
+      memcpy(xb + (size_t)k * xstride * 4, (const char *)data_x + (size_t)idx[k] * xstride * 4, (size_t)xstride * 4);
+      yb[k] = data_y[idx[k]];
+    }
+    rc = oracle_sgd_step(m, cur, xb, yb, B, C, sigma, seed0 + (uint64_t)t, lr, next, n_threads);
+    float *tmp = cur; cur = next; next = tmp;
+  }
+  memcpy(params_out, cur, sizeof(float) * P);
+  free(cur); free(next); free(idx); free(yb); free(xb);
+  return rc;
+}
+
 int oracle_max_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -71,6 +71,11 @@ def lib():
         L.oracle_sgd_step.restype = C.c_int
         L.oracle_sgd_step.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_double,
                                       C.c_double, C.c_uint64, C.c_double, C.c_void_p, C.c_int]
+        L.oracle_sample_indices.restype = None
+        L.oracle_sample_indices.argtypes = [C.c_uint64, C.c_long, C.c_int, C.c_void_p]
+        L.oracle_train.restype = C.c_int
+        L.oracle_train.argtypes = [C.POINTER(_Model), C.c_void_p, C.c_void_p, C.c_void_p, C.c_long, C.c_int, C.c_int,
+                                   C.c_double, C.c_double, C.c_uint64, C.c_double, C.c_void_p, C.c_int]
         L.oracle_max_threads.restype = C.c_int
         _lib = L
     return _lib
@@ -222,6 +227,27 @@ def sgd_step(m, params, x, y, clip_c, sigma, seed, lr, n_threads=0):
     rc = lib().oracle_sgd_step(C.byref(cm), th.ctypes.data, xa.ctypes.data, ya.ctypes.data, int(ya.shape[0]),
                                float(clip_c), float(sigma), C.c_uint64(int(seed)), float(lr), new.ctypes.data,
                                int(n_threads))
+    assert rc == 0
+    return new
+
+
+def sample_indices(seed, n, batch):
+    """The minibatch of a step: `batch` indices into a dataset of n examples (int32)."""
+    idx = np.empty(int(batch), dtype=np.int32)
+    lib().oracle_sample_indices(C.c_uint64(int(seed) & (2**64 - 1)), int(n), int(batch), idx.ctypes.data)
+    return idx
+
+
+def train(m, params, data_x, data_y, steps, batch, clip_c, sigma, seed0, lr, n_threads=0):
+    """`steps` iterations of draw / private step / update on the dataset (data_x, data_y); returns the parameters."""
+    cm = _to_c_model(m)
+    th = np.ascontiguousarray(params, dtype=np.float32)
+    xa = _x_array(m, data_x)
+    ya = np.ascontiguousarray(data_y, dtype=np.int32)
+    new = np.empty(th.size, dtype=np.float32)
+    rc = lib().oracle_train(C.byref(cm), th.ctypes.data, xa.ctypes.data, ya.ctypes.data, int(ya.shape[0]), int(steps),
+                            int(batch), float(clip_c), float(sigma), C.c_uint64(int(seed0) & (2**64 - 1)), float(lr),
+                            new.ctypes.data, int(n_threads))
     assert rc == 0
     return new
 

@@ -191,6 +191,7 @@ struct dp_ctx {
   int last_batch = -1;
   dp_plan_options opt{}; // route switches, read once at init
   int *bad = nullptr;    // dp_step_validate: number of out-of-range ids / labels
+  uint32_t *xb = nullptr; int *yb = nullptr, *idx = nullptr; // dp_step_loop: the drawn minibatch (allocated on its first call)
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   // profiling
   bool prof = false;
@@ -1560,6 +1561,69 @@ extern "C" int dp_step_last_norms(dp_ctx *c, float *norms_out) {
   if (!c || !norms_out || c->last_batch < 0) return DP_EINVAL;
   if (c->last_batch == 0) return DP_OK;
   HIP_TRY(hipMemcpyAsync(norms_out, c->norms, sizeof(float) * c->last_batch, hipMemcpyDeviceToDevice, c->stream));
+  return DP_OK;
+}
+
+// ---------------------------------------------------------------- minibatch draw and the training loop
+
+// DPSGD item 1: index k of the minibatch = (word k%4 of the Philox block with counter (k/4, 0, 1, 0)) * n >> 32 --
+// uniform over [0, n), with replacement; the third counter word keeps these blocks apart from the noise stream's.
+__global__ void sample_indices_kernel(uint32_t k0, uint32_t k1, long n, int batch, int *__restrict__ idx) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= batch) return;
+  uint32_t r[4];
+  philox4x32_10((uint32_t)(k >> 2), 0u, 1u, 0u, k0, k1, r);
+  idx[k] = (int)(((uint64_t)r[k & 3] * (uint64_t)n) >> 32);
+}
+
+// one workgroup per drawn example: its input row (fp32 features or int32 token ids: 4-byte words) and its label
+__global__ void gather_rows_kernel(const uint32_t *__restrict__ data_x, const int *__restrict__ data_y,
+                                   const int *__restrict__ idx, long row_words, uint32_t *__restrict__ xb,
+                                   int *__restrict__ yb) {
+  const long src = (long)idx[blockIdx.x] * row_words, dst = (long)blockIdx.x * row_words;
+  for (long i = threadIdx.x; i < row_words; i += blockDim.x) xb[dst + i] = data_x[src + i];
+  if (threadIdx.x == 0) yb[blockIdx.x] = data_y[idx[blockIdx.x]];
+}
+
+extern "C" int dp_step_sample_indices(uint64_t seed, int64_t n_examples, int batch, int32_t *indices, void *hip_stream) {
+  if (!indices || batch < 0 || n_examples < 1 || n_examples > 0x7fffffffl) return DP_EINVAL;
+  if (batch == 0) return DP_OK;
+  hipLaunchKernelGGL(sample_indices_kernel, grid1d(batch, 256), dim3(256), 0, (hipStream_t)hip_stream, (uint32_t)seed,
+                     (uint32_t)(seed >> 32), (long)n_examples, batch, (int *)indices);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "kernel launch: %s", hipGetErrorString(e));
+    return DP_EHIP;
+  }
+  return DP_OK;
+}
+
+extern "C" int dp_step_loop(dp_ctx *c, float *params, const void *data_x, const int32_t *data_y, int64_t n_examples,
+                            int steps, int batch, float C, float sigma, uint64_t seed0, float lr) {
+  if (!c || !params || !data_x || !data_y || steps < 0 || batch < 1 || batch > c->maxB || n_examples < 1 ||
+      n_examples > 0x7fffffffl)
+    return DP_EINVAL;
+  if (!(C > 0.f) || !(sigma >= 0.f) || std::isnan(C) || std::isinf(sigma) || std::isnan(lr) || std::isinf(lr)) return DP_EINVAL;
+  if (std::isinf(C) && sigma > 0.f) return DP_EINVAL;
+  const long row_words = c->m.seq_len > 0 ? c->m.seq_len : (long)c->m.in_c * c->m.in_h * c->m.in_w;
+  if (!c->xb) { // first call on this context: room for one drawn minibatch
+    int rc = dev_alloc(c, &c->xb, (size_t)c->maxB * row_words);
+    if (rc == DP_OK) rc = dev_alloc(c, &c->yb, c->maxB);
+    if (rc == DP_OK) rc = dev_alloc(c, &c->idx, c->maxB);
+    if (rc != DP_OK) { c->xb = nullptr; return rc; }
+  }
+  Launcher Ln{c};
+  for (int t = 0; t < steps; ++t) {
+    const uint64_t seed = seed0 + (uint64_t)t;
+    Ln("sample_minibatch", dim3(1), dim3(256), [&](hipStream_t st) {
+      hipLaunchKernelGGL(sample_indices_kernel, grid1d(batch, 256), dim3(256), 0, st, (uint32_t)seed, (uint32_t)(seed >> 32),
+                         (long)n_examples, batch, c->idx);
+      hipLaunchKernelGGL(gather_rows_kernel, dim3(batch), dim3(256), 0, st, (const uint32_t *)data_x, (const int *)data_y,
+                         (const int *)c->idx, row_words, c->xb, c->yb);
+    });
+    int rc = run_step(c, params, c->xb, c->yb, batch, true, C, sigma, seed, nullptr, params, lr / (float)batch);
+    if (rc != DP_OK) return rc;
+  }
   return DP_OK;
 }
 

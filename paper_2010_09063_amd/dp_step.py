@@ -18,7 +18,7 @@ _KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 EXPORTS = ["dp_step_init", "dp_step_init_ex", "dp_step_validate", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
-           "dp_step_dense1_static", "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
+           "dp_step_dense1_static", "dp_step_sample_indices", "dp_step_loop", "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
 
 
 class dp_layer_desc(C.Structure):
@@ -73,6 +73,11 @@ def load_library():
         L.dp_step_dense1_static.restype = C.c_int
         L.dp_step_dense1_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
                                             C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dp_step_sample_indices.restype = C.c_int
+        L.dp_step_sample_indices.argtypes = [C.c_uint64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]
+        L.dp_step_loop.restype = C.c_int
+        L.dp_step_loop.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                   C.c_float, C.c_float, C.c_uint64, C.c_float]
         L.dp_step_last_norms.restype = C.c_int
         L.dp_step_last_norms.argtypes = [C.c_void_p, C.c_void_p]
         L.dp_step_profile.restype = C.c_int
@@ -147,6 +152,14 @@ def dp_step_dense1_static(params, x, y, batch, in_features, n_classes, C_, sigma
                                                 C.c_void_p(st.cuda_stream)))
 
 
+# -- dp_step_sample_indices
+def dp_step_sample_indices(seed, n_examples, batch, indices, stream=None):
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(load_library().dp_step_sample_indices(C.c_uint64(int(seed) & (2**64 - 1)), int(n_examples), int(batch),
+                                                 _ptr(indices), C.c_void_p(st.cuda_stream)))
+
+
 class DpStep:
     """Owns one dp_ctx.  `stream` is a torch.cuda.Stream (default: the current one); keyword options are the fields
     of dp_plan_options (route switches for tests and A/B measurements)."""
@@ -186,6 +199,12 @@ class DpStep:
         _check(self._lib.dp_step_sgd(self._ctx, _ptr(params), _ptr(x), _ptr(y), int(batch), float(C_), float(sigma),
                                      C.c_uint64(int(seed) & (2**64 - 1)), float(lr),
                                      _ptr(out_grad) if out_grad is not None else None))
+
+    # -- dp_step_loop
+    def dp_step_loop(self, params, data_x, data_y, n_examples, steps, batch, C_, sigma, seed0, lr):
+        _check(self._lib.dp_step_loop(self._ctx, _ptr(params), _ptr(data_x), _ptr(data_y), int(n_examples), int(steps),
+                                      int(batch), float(C_), float(sigma), C.c_uint64(int(seed0) & (2**64 - 1)),
+                                      float(lr)))
 
     # -- dp_step_nonprivate
     def dp_step_nonprivate(self, params, x, y, batch, out_grad):

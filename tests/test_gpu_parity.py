@@ -539,3 +539,52 @@ def test_fused_sgd_update(name, batch):
     want2 = want_after(got, seed + 1, (got - got2) * batch / lr)
     assert rel_l2(got2 - got, want2 - got) <= 2e-4
     st.dp_step_free()
+
+
+def test_minibatch_draw_is_bit_exact():
+    """dp_step_sample_indices against the oracle's draw: integer work, compared bit for bit."""
+    import torch
+    from paper_2010_09063_amd import dp_step_sample_indices
+    dev = torch.device("cuda:0")
+    for seed, n, batch in ((0, 60000, 1024), (0x1234567887654321, 2**31 - 1, 777), (5, 1, 6), (7, 3, 1), (9, 50000, 0)):
+        idx = torch.full((max(batch, 1),), -1, dtype=torch.int32, device=dev)
+        dp_step_sample_indices(seed, n, batch, idx)
+        torch.cuda.synchronize()
+        assert np.array_equal(idx.cpu().numpy()[:batch], O.sample_indices(seed, n, batch))
+
+
+@pytest.mark.parametrize("name,n,batch,steps", [("tiny_dense", 50, 8, 4), ("tiny_lstm", 30, 5, 3), ("tiny_emb", 40, 7, 3),
+                                                ("tiny_avgpool", 30, 6, 3), ("cfg1_logistic", 300, 64, 5),
+                                                ("cfg2_mlp", 200, 33, 3)])
+def test_training_loop(name, n, batch, steps):
+    """dp_step_loop: draw, private step and update, `steps` times with no host work in between, against the oracle's
+    loop (models without max-pools, so every step has one valid result)."""
+    import torch
+    from paper_2010_09063_amd import DpStep
+    if name in TINY:
+        m = TINY[name]
+        x, y, theta = _case(m, n, seed=31, scale=4.0 if m["input"]["kind"] == "tokens" else 1.0)
+    else:
+        wl = W.make_workload(name, batch=n, seed=31, bias_scale=0.2)
+        m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    norms = O.dp_step(m, theta, x, y, 1.0, 0.0, 0)["norms"]
+    Cc, sigma, seed0 = float(np.median(norms)), 0.7, 2**33 + 5
+    lr = 0.02 * batch / Cc
+    want = O.train(m, theta, x, y, steps, batch, Cc, sigma, seed0, lr).astype(np.float64)
+    dev = torch.device("cuda:0")
+    st = DpStep(m, batch)
+    tp = torch.from_numpy(theta.copy()).to(dev)
+    tx, ty = torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)
+    st.dp_step_loop(tp, tx, ty, n, steps, batch, Cc, sigma, seed0, lr)
+    torch.cuda.synchronize()
+    got = tp.cpu().numpy().astype(np.float64)
+    err = rel_l2(got - theta, want - theta)
+    print(f"{name}: {steps} steps, total update rel_l2 {err:.2e}", flush=True)
+    assert err <= 3e-4   # every step within the 1e-4 bar of its own sum, carried through the following steps
+    # the loop is dp_step_sgd on the drawn examples: one more step by hand from where the loop stopped
+    idx = O.sample_indices(seed0 + steps, n, batch)
+    nxt = O.sgd_step(m, got.astype(np.float32), x[idx], y[idx], Cc, sigma, seed0 + steps, lr).astype(np.float64)
+    st.dp_step_loop(tp, tx, ty, n, 1, batch, Cc, sigma, seed0 + steps, lr)
+    torch.cuda.synchronize()
+    assert rel_l2(tp.cpu().numpy().astype(np.float64) - got, nxt - got) <= 2e-4
+    st.dp_step_free()

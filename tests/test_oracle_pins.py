@@ -523,3 +523,35 @@ def test_abs_sum_is_the_sum_of_term_magnitudes():
     assert np.all(r["abs_sum"] >= np.abs(r["clipped_sum"]) * (1 - 1e-12))
     one = O.dp_step(m, theta, x[:1], y[:1], Cc, 0.0, 0)
     assert np.allclose(one["abs_sum"], np.abs(one["clipped_sum"]), rtol=1e-15, atol=0)
+
+
+# ----------------------------------------------------------------- minibatch draw and the training loop (Section 1, items 1 and 4)
+
+def test_sample_indices_against_the_philox_words():
+    """Index k = (word k%4 of block (k/4, 0, 1, 0) times n) >> 32, written out with Python integers on top of the
+    Philox function the known-answer vectors pin; the blocks differ from the noise stream's (third counter word)."""
+    for seed, n, batch in ((0, 60000, 37), (0x1234567887654321, 2**31 - 1, 9), (5, 1, 6), (7, 3, 1000)):
+        got = O.sample_indices(seed, n, batch)
+        key = [seed & 0xffffffff, seed >> 32]
+        want = [(int(O.philox4x32_10([k // 4, 0, 1, 0], key)[k % 4]) * n) >> 32 for k in range(batch)]
+        assert got.tolist() == want
+        assert got.min() >= 0 and got.max() < n
+    assert not np.array_equal(O.philox4x32_10([0, 0, 1, 0], [0, 0]), O.philox4x32_10([0, 0, 0, 0], [0, 0]))
+    # uniform over the range: every cell of a 16-cell histogram within 5 sigma of its expectation
+    idx = O.sample_indices(11, 1600, 160000)
+    h = np.bincount(idx // 100, minlength=16)
+    assert np.all(np.abs(h - 10000) < 5 * math.sqrt(10000 * 15 / 16))
+    assert len(np.unique(O.sample_indices(11, 10**6, 1000))) > 990   # with replacement: a few repeats at most
+
+
+def test_train_is_the_chain_of_draw_step_update():
+    m, x, y, theta = _tiny_case("tiny_conv2", 40)
+    Cc, sigma, lr, B, seed0 = 0.8, 0.9, 0.3, 6, 2**40 + 3
+    got = O.train(m, theta, x, y, 3, B, Cc, sigma, seed0, lr)
+    cur = theta
+    for t in range(3):
+        idx = O.sample_indices(seed0 + t, len(y), B)
+        cur = O.sgd_step(m, cur, x[idx], y[idx], Cc, sigma, seed0 + t, lr)
+    assert np.array_equal(got, cur)
+    assert not np.array_equal(got, theta)
+    assert np.array_equal(O.train(m, theta, x, y, 0, B, Cc, sigma, seed0, lr), theta)
