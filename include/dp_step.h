@@ -213,7 +213,7 @@ int dp_step_nonprivate(dp_ctx *ctx, const float *params, const void *x, const in
  *   hip_stream a hipStream_t (NULL = the default stream) the two launches are enqueued on
  *   C, sigma, seed, out_grad: as for dp_step; results equal dp_step's on the same model to rounding.
  * Limits: in_features <= 1023, n_classes <= 15, in_features * (n_classes rounded up to 4, 10 or
- * 15, + 4) <= 15000, batch <= 65536; beyond
+ * 15, + 4) <= 14800, batch <= 65536; beyond
  * them DP_ETOOBIG and nothing is launched.
  * Every call on one GPU uses that GPU's one scratch array: calls that overlap in time on one GPU (two streams,
  * two threads) race on it; serialise them.  Nothing in the array needs clearing between calls.
@@ -240,6 +240,23 @@ int dp_step_last_norms(dp_ctx *ctx, float *norms_out);
  */
 int dp_step_profile(dp_ctx *ctx, int enable);
 int dp_step_profile_read(dp_ctx *ctx, int cap, const char **labels, int *launches, float *total_ms, int reset);
+
+/*
+ * dp_step_describe_plan -- which kernel family each parameter layer was planned on, as text
+ * "<layer>:fwd=..,bwd=..,norm=..,sum=..;" ("mf32"/"mf64"/"mf": minimal-filtering form, 16 multiplies where the
+ * direct form has 36; "gram"; "+store"/"weighted": stored per-example gradients).  Utility, no passage; the
+ * benchmark uses it to price each launch by the multiplies its route really issues.
+ *   buf, cap   host buffer; DP_EINVAL if the text does not fit.
+ */
+int dp_step_describe_plan(const dp_ctx *ctx, char *buf, size_t cap);
+
+/*
+ * dp_step_ceiling -- measured reference points for roofline figures (utility, no passage).  what = 0: a plain
+ * device copy of 256 MiB, GB/s read + written; 1: a register-only v_mfma_f32_32x32x2_f32 loop on every CU,
+ * TFLOP/s; 2: microseconds per launch of an empty kernel, 1000 launches back to back on the stream.  Allocates
+ * and frees its own buffers and synchronises; *value (host) receives the figure.
+ */
+int dp_step_ceiling(int what, void *hip_stream, double *value);
 
 /* Static description of a status code, plus the last HIP error text for DP_EHIP.  Utility, no passage. */
 const char *dp_step_strerror(int code);

@@ -15,7 +15,7 @@
 #define DENSE1_THREADS 1024  // 16 waves: one row of the [d_in + 1][N] tensor per thread
 #define DENSE1_MAX_IN 1023   // input features (+ the bias row): one row per thread
 #define DENSE1_MAX_CLASSES 15
-#define DENSE1_MAX_LDS_WORDS 15000 // in_features * (classes padded to 4 / 10 / 15 + DENSE1_EX): W transposed and one
+#define DENSE1_MAX_LDS_WORDS 14800 // in_features * (classes padded to 4 / 10 / 15 + DENSE1_EX): W transposed and one
                                    // group of inputs in 64 KB of LDS
 #define DENSE1_EX 4          // examples per group
 #define DENSE1_MAX_TILES 256 // partials of the clipped sum (workgroups)
@@ -25,7 +25,7 @@ struct Dense1Args {
   const float *W;    // [d_in][N]
   const float *bias; // [N]
   const int *y;      // [B]
-  float *part;       // [tiles][(d_in + 1) * N]: partial clipped sums in the parameter layout (W then bias)
+  float *part;       // [tiles][dense1_part_stride]: partial clipped sums in the parameter layout (W then bias)
   float *norms;      // [B] unclipped norms (may be null)
   float *s;          // [B] clip factors (may be null)
   float *delta;      // [B][N] loss gradient (may be null)
@@ -33,9 +33,13 @@ struct Dense1Args {
   int groups;        // groups of DENSE1_EX examples per workgroup
   float C;           // clip norm (private step)
   int priv;          // 0: plain sum (every factor 1)
-  FastDiv dN;        // division by N
+  FastDiv dN, dD;    // division by N, by d_in
 };
 
+static inline __host__ __device__ int dense1_ldx(int d_in) { return (d_in + 3) & ~3; }
+static inline __host__ __device__ int dense1_ldw(int d_in) { const int q = (d_in + 3) >> 2; return 4 * (q | 1); }
+// partial rows start on 16-byte boundaries (the final write reads them with 16-byte loads)
+static inline __host__ __device__ long dense1_part_stride(int d_in, int N) { return ((long)(d_in + 1) * N + 3) & ~3l; }
 static inline int dense1_ncp(int n_classes) { return n_classes <= 4 ? 4 : (n_classes <= 10 ? 10 : 15); }
 static inline bool dense1_fits(int d_in, int n_classes) {
   return d_in >= 1 && n_classes >= 1 && d_in <= DENSE1_MAX_IN && n_classes <= DENSE1_MAX_CLASSES &&
@@ -63,9 +67,12 @@ static inline void dense1_tiling(int B, int max_tiles, int *groups, int *tiles) 
 template <int NCP>
 __global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dense1Args a) {
   extern __shared__ float lds[];
-  const int d_in = a.d_in, N = a.N, ldw = d_in | 1; // odd row length: the classes' rows start on different banks
-  float *xs = lds;                    // [DENSE1_EX][d_in]: the group's inputs
-  float *wt = xs + DENSE1_EX * d_in;  // [NCP][ldw]: W transposed, zero rows for the padding classes
+  const int d_in = a.d_in, N = a.N;
+  // rows of 4-float quads (16-byte LDS reads); an odd number of quads per weight row, so that the sixteen rows a
+  // 16-byte read touches start in different banks
+  const int ldx = dense1_ldx(d_in), ldw = dense1_ldw(d_in);
+  float *xs = lds;                    // [DENSE1_EX][ldx]: the group's inputs, zero beyond d_in
+  float *wt = xs + DENSE1_EX * ldx;   // [NCP][ldw]: W transposed, zero rows for the padding classes, zero beyond d_in
   float *zp = wt + NCP * ldw;         // [16 waves][64 lanes]: partial dot products
   float *dl = zp + 16 * 64;           // [DENSE1_EX][NCP]: s_e * delta_e
   float *bs = dl + DENSE1_EX * NCP;   // [16]: bias, -inf for the padding classes (their softmax term is 0)
@@ -102,7 +109,10 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dens
       const int i = tid + DENSE1_THREADS * n;
       wv[n] = a.W[i < w_total ? i : 0];
     }
-    for (int i = N * ldw + tid; i < NCP * ldw; i += DENSE1_THREADS) wt[i] = 0.f;
+      // zero first: the padding rows, and the tail of every row beyond d_in (the products below run over whole quads)
+    for (int i = tid; i < NCP * ldw; i += DENSE1_THREADS) wt[i] = 0.f;
+    for (int i = tid; i < DENSE1_EX * ldx; i += DENSE1_THREADS) xs[i] = 0.f;
+    __syncthreads();
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
       const int i = tid + DENSE1_THREADS * n;
@@ -113,16 +123,19 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dens
     }
   }
   if (tid < 16) bs[tid] = tid < N ? bv : -INFINITY;
-  // the wave's sixteenth of the features
-  const int kc = (d_in + 15) >> 4;
-  const int k0 = wave * kc, k1 = min(d_in, k0 + kc);
+  // the wave's sixteenth of the features, in whole quads
+  const int kc = ((ldx >> 2) + 15) >> 4;
+  const int k0 = 4 * wave * kc, k1 = min(ldx, k0 + 4 * kc);
 
   for (int grp = 0; grp < a.groups; ++grp) {
     const long gbase = ((long)blockIdx.x * a.groups + grp) * x_group;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
       const int i = tid + DENSE1_THREADS * n;
-      if (i < x_group) xs[i] = (gbase + i < x_total) ? xv[n] : 0.f;
+      if (i < x_group) {
+        const int q = (int)a.dD.div((unsigned)i); // example of the group, feature i - q * d_in
+        xs[q * ldx + (i - q * d_in)] = (gbase + i < x_total) ? xv[n] : 0.f;
+      }
     }
     __syncthreads();
     const int yy = yv;
@@ -139,12 +152,15 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dens
     }
     // ---- 2. partial dot products
     {
-      const float *ap = xs + e * d_in;
+      const float *ap = xs + e * ldx;
       const float *bp = jj < NCP ? wt + jj * ldw : ap; // lane 15 of an example: the example with itself
-      float z = 0.f;
-#pragma unroll 8
-      for (int k = k0; k < k1; ++k) z = fmaf(ap[k], bp[k], z);
-      zp[wave * 64 + lane] = z;
+      float z0 = 0.f, z1 = 0.f;
+#pragma unroll 4
+      for (int k = k0; k < k1; k += 4) {
+        const float4 u = *reinterpret_cast<const float4 *>(ap + k), v = *reinterpret_cast<const float4 *>(bp + k);
+        z0 = fmaf(u.x, v.x, z0); z1 = fmaf(u.y, v.y, z1); z0 = fmaf(u.z, v.z, z0); z1 = fmaf(u.w, v.w, z1);
+      }
+      zp[wave * 64 + lane] = z0 + z1;
     }
     __syncthreads();
     // ---- 3. wave 0: the four examples' loss gradients, norms and clip factors
@@ -181,7 +197,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dens
     if (tid <= d_in) {
 #pragma unroll
       for (int q = 0; q < DENSE1_EX; ++q) {
-        const float v = tid < d_in ? xs[q * d_in + tid] : 1.f; // the bias row multiplies a constant 1
+        const float v = tid < d_in ? xs[q * ldx + tid] : 1.f; // the bias row multiplies a constant 1
 #pragma unroll
         for (int j = 0; j < NCP; ++j) acc[j] = fmaf(v, dl[q * NCP + j], acc[j]);
       }
@@ -189,7 +205,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense1_fused_kernel(const Dens
     __syncthreads();
   }
   if (tid <= d_in) {
-    float *pr = a.part + (long)blockIdx.x * ((long)(d_in + 1) * N) + (long)tid * N;
+    float *pr = a.part + (long)blockIdx.x * dense1_part_stride(d_in, N) + (long)tid * N;
 #pragma unroll
     for (int j = 0; j < NCP; ++j)
       if (j < N) pr[j] = acc[j];
@@ -203,9 +219,11 @@ static inline int launch_dense1_fused(hipStream_t st, Dense1Args a, int max_tile
   if (tiles == 0) return 0;
   a.groups = groups;
   a.dN.init(a.N);
+  a.dD.init(a.d_in);
   dim3 grid(tiles), block(DENSE1_THREADS);
   const int ncp = dense1_ncp(a.N);
-  const size_t smem = sizeof(float) * ((size_t)DENSE1_EX * a.d_in + (size_t)ncp * (a.d_in | 1) + 16 * 64 + DENSE1_EX * ncp + 16);
+  const size_t smem = sizeof(float) * ((size_t)DENSE1_EX * dense1_ldx(a.d_in) + (size_t)ncp * dense1_ldw(a.d_in) + 16 * 64 +
+                                       DENSE1_EX * ncp + 16);
   if (ncp == 4) hipLaunchKernelGGL(dense1_fused_kernel<4>, grid, block, smem, st, a);
   else if (ncp == 10) hipLaunchKernelGGL(dense1_fused_kernel<10>, grid, block, smem, st, a);
   else hipLaunchKernelGGL(dense1_fused_kernel<15>, grid, block, smem, st, a);

@@ -17,6 +17,7 @@
 #include "gemm_tile.h"
 #include "conv_direct.h"
 #include "conv_gram.h"
+#include "ceilings.h"
 #include "conv_wino.h"
 #include "dense_fused.h"
 #include "kernels_misc.h"
@@ -127,6 +128,7 @@ struct Layer {
   int inC, inH, inW, outC, outH, outW; // chw view; vectors are C x 1 x 1; sequences: C = T, H = D
   long in_size, out_size;              // floats per example
   long p_off, p_count;
+  long pstride = 0; // floats between split-K partial rows: p_count rounded up to 16 bytes
   float *a = nullptr; // output activations [maxB, out_size]
   float *g = nullptr; // gradient w.r.t. pre-activation (w.r.t. output where the layer has no activation)
   uint8_t *arg = nullptr;
@@ -646,7 +648,8 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
         long ms = DP_MAX_PART_FLOATS / l.p_count;
         l.max_split = (int)(ms < 8 ? 8 : (ms > DP_MAX_SPLIT ? DP_MAX_SPLIT : ms));
       }
-      rc = dev_alloc(c, &l.part, (size_t)l.max_split * l.p_count);
+      l.pstride = (l.p_count + 3) & ~3l;
+      rc = dev_alloc(c, &l.part, (size_t)l.max_split * l.pstride);
     }
     if (rc == DP_OK && l.d.kind == DP_DENSE) {
       // a small output with a long K would leave most CUs idle and expose every load's latency: split K
@@ -784,7 +787,7 @@ extern "C" const char *dp_step_strerror(int code) {
   case DP_EHIP: return g_hip_err[0] ? g_hip_err : "HIP runtime error";
   case DP_EUNSUPPORTED: return "layer sequence or size not supported by the kernels";
   case DP_ETOOBIG: return "sizes beyond the limits of the allocation-free entry point (in_features <= 1023, n_classes <= 15, "
-                          "in_features * (n_classes rounded up to 4, 10 or 15, + 4) <= 15000, batch <= 65536)";
+                          "in_features * (n_classes rounded up to 4, 10 or 15, + 4) <= 14800, batch <= 65536)";
   default: return "unknown status";
   }
 }
@@ -850,10 +853,10 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     a.B = B; a.d_in = l.d.in_features; a.N = l.d.out_features; a.C = C; a.priv = priv ? 1 : 0;
     int tiles = 0;
     Ln("dense1_fused", dim3(1), dim3(256), [&](hipStream_t st) {
-      tiles = launch_dense1_fused(st, a, std::min(DENSE1_MAX_TILES, l.max_split));
+      tiles = launch_dense1_fused(st, a, std::min<long>(DENSE1_MAX_TILES, (long)l.max_split));
     });
     FinalizeSeg &sg = fa.seg[fa.nseg++];
-    sg.p_off = 0; sg.n = l.p_count; sg.part = l.part; sg.stride = l.p_count; sg.nsplit = tiles;
+    sg.p_off = 0; sg.n = l.p_count; sg.part = l.part; sg.stride = dense1_part_stride(a.d_in, a.N); sg.nsplit = tiles;
   } else if (B > 0) {
     // ------------------------------------------------------------ re-laid weights of the direct convolutions
     {
@@ -1348,7 +1351,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.M = l.d.in_features + 1; p.N = l.d.out_features; p.K = B;
           p.a.set(lin, l.d.in_features); p.a.scale = sc; p.a.ones_row = 1;
           p.b.set(l.g, l.d.out_features);
-          p.part = l.part; p.stride = l.p_count; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
+          p.part = l.part; p.stride = l.pstride; p.ldm = l.d.out_features; p.bias_col = -1; p.bias_off = 0;
           nsplit = launch_gemm_split(p, l.max_split, Ln, LL("dense_clipped_sum"));
         };
         vec_dispatch(OpKMajor<true, true>::can_vec(lin, l.d.in_features, 0, l.d.in_features) &&
@@ -1365,7 +1368,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           dim3 grid((unsigned)ceil_div(gstride, 256), nsplit), block(256);
           Ln(LL("conv_weighted_sum"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(weighted_sum_kernel, grid, block, 0, st, (const float *)l.gst, gstride, sc, l.part,
-                               l.p_count, l.gorder, B, eps);
+                               l.pstride, l.gorder, B, eps);
           });
           break;
         }
@@ -1377,7 +1380,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           const int eps = ceil_div(B, want);
           nsplit = ceil_div(B, eps);
           ConvWinoWgUnitArgs a{};
-          a.x = lin; a.dy = l.g; a.scale = sc; a.part = l.part; a.part_stride = l.p_count;
+          a.x = lin; a.dy = l.g; a.scale = sc; a.part = l.part; a.part_stride = l.pstride;
           a.B = B; a.C = g.C; a.D = g.D; a.H = g.H; a.ex_per_block = eps;
           dim3 grid(g.C / 32, nsplit, g.D / (32 * db)), block(256);
           Ln(LL("conv_clipped_sum"), grid, block, [&](hipStream_t st) {
@@ -1400,7 +1403,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           nsplit = ceil_div(B, epb);
           for (int d0 = 0; d0 < g.D; d0 += DP_WG_DSLICE) {
             ConvWgArgs a = make_wg_args(l, lin, B, l.t_wgc, d0);
-            a.scale = sc; a.out = l.part + (long)d0 * g.CKK; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.p_count;
+            a.scale = sc; a.out = l.part + (long)d0 * g.CKK; a.mode = 1; a.ex_per_block = epb; a.part_stride = l.pstride;
             launch_conv_wgrad(Ln, LL("conv_clipped_sum"), a, l.wg_db, l.wg_flat, l.wg_ws, nsplit);
           }
           break;
@@ -1410,7 +1413,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         p.M = g.D; p.N = g.CKK + 1; p.K = B * g.P;
         p.a.t = l.g; p.a.scale = sc; p.a.D = g.D; p.a.P = g.P; p.a.by_z = 0; p.a.dP = g.dP;
         p.b.x = lin; p.b.g = g; p.b.has_ones = 1; p.b.by_z = 0;
-        p.part = l.part; p.stride = l.p_count; p.ldm = g.CKK; p.bias_col = g.CKK; p.bias_off = (long)g.D * g.CKK;
+        p.part = l.part; p.stride = l.pstride; p.ldm = g.CKK; p.bias_col = g.CKK; p.bias_off = (long)g.D * g.CKK;
         nsplit = launch_gemm_split(p, l.max_split, Ln, LL("conv_clipped_sum"));
       } break;
       case DP_LSTM_LAST:
@@ -1423,7 +1426,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           dim3 grid((unsigned)ceil_div(l.p_count, 256), nsplit), block(256);
           Ln(LL("lstm_weighted_sum"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(weighted_sum_kernel, grid, block, 0, st, (const float *)l.gst, l.p_count, sc, l.part,
-                               l.p_count, l.gorder, B, eps);
+                               l.pstride, l.gorder, B, eps);
           });
           break;
         }
@@ -1434,7 +1437,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           p.M = l.Din + l.H + 1; p.N = G; p.K = B * l.T;
           p.a.set(lin, l.hs, sc, l.Din, l.H, l.T, 0);
           p.b.set(l.gates, G);
-          p.part = l.part; p.stride = l.p_count; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
+          p.part = l.part; p.stride = l.pstride; p.ldm = G; p.bias_col = -1; p.bias_off = 0;
           nsplit = launch_gemm_split(p, l.max_split, Ln, LL("lstm_clipped_sum"));
         };
         vec_dispatch(OpLstmIn<true>::can_vec(lin, l.hs, l.Din, l.H) && OpKMajor<true, false>::can_vec(l.gates, G, 0, G), run);
@@ -1477,22 +1480,21 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       default: break;
       }
       FinalizeSeg &sg = fa.seg[fa.nseg++];
-      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = l.part; sg.stride = l.p_count; sg.nsplit = nsplit;
+      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = l.part; sg.stride = l.pstride; sg.nsplit = nsplit;
     }
   } else {
     for (auto &l : c->L) {
       if (l.p_count == 0) continue;
       FinalizeSeg &sg = fa.seg[fa.nseg++];
-      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = l.part; sg.stride = l.p_count; sg.nsplit = 0;
+      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = l.part; sg.stride = l.pstride; sg.nsplit = 0;
     }
   }
   // ------------------------------------------------------------ final write with fused noise
   {
     const float noise_std = (priv && sigma > 0.f) ? sigma * C : 0.f;
-    dim3 grid = grid1d(c->P, DP_FIN_CO), block(256);
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
-    Ln("finalize_noise", grid, block, [&](hipStream_t st) {
-      hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, c->P, noise_std, k0, k1, theta_update, update_step);
+    Ln("finalize_noise", dim3(1), dim3(256), [&](hipStream_t st) {
+      launch_finalize(st, fa, out, c->P, noise_std, k0, k1, theta_update, update_step);
     });
   }
   hipError_t e = hipGetLastError();
@@ -1627,6 +1629,109 @@ extern "C" int dp_step_loop(dp_ctx *c, float *params, const void *data_x, const 
   return DP_OK;
 }
 
+// ---------------------------------------------------------------- plan description and measured ceilings
+
+extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
+  if (!c || !buf || cap == 0) return DP_EINVAL;
+  std::string o;
+  for (size_t i = 0; i < c->L.size(); ++i) {
+    const Layer &l = c->L[i];
+    if (l.p_count == 0) continue;
+    std::string fwd = "-", bwd = "-", norm = "-", sum = "-";
+    switch (l.d.kind) {
+    case DP_DENSE:
+      fwd = c->fused1 ? "fused" : "generic"; bwd = i > 0 ? "generic" : "-";
+      norm = c->fused1 ? "fused" : "identity"; sum = c->fused1 ? "fused" : "generic";
+      break;
+    case DP_CONV2D:
+      fwd = l.u_f ? (l.wino_f == 2 ? "mf64" : "mf32") : (l.dir_fwd ? "direct" : "generic");
+      bwd = i == 0 ? "-" : (l.u_b ? (l.wino_b == 2 ? "mf64" : "mf32") : (l.dir_bwd ? "direct" : (l.cols ? "columns" : "generic")));
+      norm = l.gram ? "gram" : ((l.wino_norm && l.gst) ? "mf+store" : (l.dir_wg ? (l.gst ? "direct+store" : (l.wg_ws ? "ws" : "direct"))
+                                                                                : (l.gst ? "generic+store" : "generic")));
+      sum = l.gst ? "weighted" : ((l.wino_wgu || l.wino_wg) ? "mf" : (l.dir_wg ? (l.wg_ws ? "ws" : "direct") : "generic"));
+      break;
+    case DP_EMBEDDING: fwd = "gather"; norm = "sorted-segments"; sum = "scatter"; break;
+    case DP_LSTM_LAST:
+    case DP_LSTM_SEQ: fwd = "recurrence"; bwd = "recurrence"; norm = l.gst ? "generic+store" : "generic"; sum = l.gst ? "weighted" : "generic"; break;
+    default: break;
+    }
+    o += std::to_string(i) + ":fwd=" + fwd + ",bwd=" + bwd + ",norm=" + norm + ",sum=" + sum + ";";
+  }
+  if (o.size() + 1 > cap) return DP_EINVAL;
+  memcpy(buf, o.c_str(), o.size() + 1);
+  return DP_OK;
+}
+
+extern "C" int dp_step_ceiling(int what, void *hip_stream, double *value) {
+  if (!value || what < 0 || what > 2) return DP_EINVAL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  float ms = 0.f;
+  int rc = DP_OK;
+  auto fail = [&](hipError_t e, const char *what_) {
+    snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what_, hipGetErrorString(e));
+    rc = DP_EHIP;
+  };
+  if (what == 0) { // copy of 256 MiB: bytes read + bytes written per second
+    const size_t bytes = (size_t)256 << 20;
+    void *a = nullptr, *b = nullptr;
+    hipError_t e = hipMalloc(&a, bytes);
+    if (e == hipSuccess) e = hipMalloc(&b, bytes);
+    if (e == hipSuccess) e = hipMemsetAsync(a, 0, bytes, st);
+    if (e != hipSuccess) { fail(e, "hipMalloc"); }
+    else {
+      double best = 1e30;
+      for (int rep = 0; rep < 6 && rc == DP_OK; ++rep) {
+        (void)hipEventRecord(e0, st);
+        hipLaunchKernelGGL(ceiling_copy_kernel, dim3(256 * 16), dim3(256), 0, st, (const float4 *)a, (float4 *)b, (long)(bytes / 16));
+        (void)hipEventRecord(e1, st);
+        e = hipEventSynchronize(e1);
+        if (e != hipSuccess) { fail(e, "copy"); break; }
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        if (rep > 0 && ms < best) best = ms;
+      }
+      *value = 2.0 * (double)bytes / (best * 1e-3) / 1e9; // GB/s
+    }
+    if (a) (void)hipFree(a);
+    if (b) (void)hipFree(b);
+  } else if (what == 1) { // fp32 MFMA: 2048 workgroups x 4 waves x iters x 4 tiles x 4096 flops
+    const int blocks = 2048, iters = 20000;
+    void *o = nullptr;
+    hipError_t e = hipMalloc(&o, (size_t)blocks * 256 * 4);
+    if (e != hipSuccess) { fail(e, "hipMalloc"); }
+    else {
+      hipLaunchKernelGGL(ceiling_mfma_kernel, dim3(blocks), dim3(256), 0, st, (float *)o, 100, 1.f, 2.f);
+      (void)hipEventRecord(e0, st);
+      hipLaunchKernelGGL(ceiling_mfma_kernel, dim3(blocks), dim3(256), 0, st, (float *)o, iters, 1.f, 2.f);
+      (void)hipEventRecord(e1, st);
+      e = hipEventSynchronize(e1);
+      if (e != hipSuccess) fail(e, "mfma loop");
+      else {
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        *value = (double)blocks * 4 * iters * 4 * 4096.0 / (ms * 1e-3) / 1e12; // TFLOP/s
+      }
+      (void)hipFree(o);
+    }
+  } else { // microseconds per launch of an empty kernel, 1000 launches back to back
+    const int n = 1000;
+    for (int i = 0; i < 50; ++i) hipLaunchKernelGGL(ceiling_empty_kernel, dim3(1), dim3(64), 0, st);
+    (void)hipEventRecord(e0, st);
+    for (int i = 0; i < n; ++i) hipLaunchKernelGGL(ceiling_empty_kernel, dim3(1), dim3(64), 0, st);
+    (void)hipEventRecord(e1, st);
+    hipError_t e = hipEventSynchronize(e1);
+    if (e != hipSuccess) fail(e, "empty launches");
+    else {
+      (void)hipEventElapsedTime(&ms, e0, e1);
+      *value = ms * 1e3 / n;
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return rc;
+}
+
 // ---------------------------------------------------------------- profiling
 
 static int drain_profile(dp_ctx *c) {
@@ -1707,7 +1812,7 @@ extern "C" int dp_step_dense1_static(const float *params, const float *x, const 
   if (std::isinf(C) && sigma > 0.f) return DP_EINVAL;
   if (!dense1_fits(in_features, n_classes) || batch > DP_STATIC_MAX_BATCH) return DP_ETOOBIG;
   const long P = (long)(in_features + 1) * n_classes;
-  const long max_tiles = (DP_STATIC_FLOATS - DP_STATIC_MAX_BATCH) / P; // the clip factors take the last 65,536 floats
+  const long max_tiles = (DP_STATIC_FLOATS - DP_STATIC_MAX_BATCH) / dense1_part_stride(in_features, n_classes); // the clip factors take the last 65,536 floats
   if (max_tiles < 1) return DP_ETOOBIG;
   float *scratch = nullptr;
   int rc = static_scratch_ptr(&scratch);
@@ -1716,7 +1821,8 @@ extern "C" int dp_step_dense1_static(const float *params, const float *x, const 
   FinalizeArgs fa;
   fa.nseg = 1;
   FinalizeSeg &sg = fa.seg[0];
-  sg.p_off = 0; sg.n = P; sg.part = scratch; sg.stride = P; sg.nsplit = 0;
+  const long pstride = dense1_part_stride(in_features, n_classes);
+  sg.p_off = 0; sg.n = P; sg.part = scratch; sg.stride = pstride; sg.nsplit = 0;
   if (batch > 0) {
     Dense1Args a{};
     a.x = x; a.W = params; a.bias = params + (long)in_features * n_classes; a.y = (const int *)y;
@@ -1725,9 +1831,7 @@ extern "C" int dp_step_dense1_static(const float *params, const float *x, const 
     sg.nsplit = launch_dense1_fused(st, a, (int)std::min<long>(DENSE1_MAX_TILES, max_tiles));
   }
   const float noise_std = sigma > 0.f ? sigma * C : 0.f;
-  dim3 grid = grid1d(P, DP_FIN_CO), block(256);
-  hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out_grad, P, noise_std, (uint32_t)seed, (uint32_t)(seed >> 32),
-                     (float *)nullptr, 0.f);
+  launch_finalize(st, fa, out_grad, P, noise_std, (uint32_t)seed, (uint32_t)(seed >> 32), (float *)nullptr, 0.f);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     snprintf(g_hip_err, sizeof(g_hip_err), "kernel launch: %s", hipGetErrorString(e));

@@ -460,12 +460,11 @@ __device__ __forceinline__ void normal4(uint64_t blk, uint32_t k0, uint32_t k1, 
   z[2] = r1 * c; z[3] = r1 * s;
 }
 
-// Final write (DPSGD item 3): out[j] = sum over split-K partials of the clipped
-// sum + sigma*C*z_j.  A workgroup owns 32 consecutive coordinates (one 128-byte line
-// per partial row, eight Philox blocks); its 256 threads split the partials 8 ways, so a
-// tensor cut into many splits is still reduced with short dependent chains, in a fixed order.
-#define DP_FIN_CO 32
-#define DP_FIN_SG 8
+// Final write (DPSGD item 3): out[j] = sum over split-K partials of the clipped sum + sigma*C*z_j.
+// A thread owns the four coordinates of one Philox block (all four normals of the block are used, 16-byte loads
+// and stores where the rows allow); a workgroup owns 256 / SG blocks and splits the partial rows SG ways (4 for
+// long parameter vectors, 16 for short ones, which would otherwise leave most CUs without a workgroup), so a
+// tensor cut into many splits is still reduced with short dependent chains.  Every sum runs in a fixed order.
 #define DP_MAX_SEG 24
 struct FinalizeSeg {
   long p_off, n;     // segment [p_off, p_off + n) of the flat parameter vector
@@ -480,40 +479,94 @@ struct FinalizeArgs {
 
 // theta != null: the parameter update of DPSGD item 4 is fused into the same write,
 // theta[j] -= step * (sum + noise) with step = learning rate / batch; out may then be null.
+template <int DP_FIN_SG>
 __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P,
                                                         float noise_std, uint32_t k0, uint32_t k1,
                                                         float *__restrict__ theta, float step) {
-  __shared__ float red[DP_FIN_SG][DP_FIN_CO + 1];
-  const int cj = threadIdx.x % DP_FIN_CO, sg = threadIdx.x / DP_FIN_CO;
-  const long j = (long)blockIdx.x * DP_FIN_CO + cj;
-  float acc = 0.f;
-  if (j < P) {
+  constexpr int DP_FIN_BLK = 256 / DP_FIN_SG;
+  __shared__ float4 red[DP_FIN_SG - 1][DP_FIN_BLK];
+  const int cb = threadIdx.x & (DP_FIN_BLK - 1);
+  const int sg = threadIdx.x / DP_FIN_BLK;
+  const long blk = (long)blockIdx.x * DP_FIN_BLK + cb, j0 = blk * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (j0 < P) {
     int si = 0;
-    while (si < fa.nseg - 1 && j >= fa.seg[si].p_off + fa.seg[si].n) ++si;
+    while (si < fa.nseg - 1 && j0 >= fa.seg[si].p_off + fa.seg[si].n) ++si;
     const FinalizeSeg &g = fa.seg[si];
-    const float *p = g.part + (j - g.p_off);
+    const float *p = g.part + (j0 - g.p_off);
     const long st = g.stride;
     const int ns = g.nsplit;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    int s = sg;
-    for (; s + 3 * DP_FIN_SG < ns; s += 4 * DP_FIN_SG) {
-      a0 += p[s * st]; a1 += p[(s + DP_FIN_SG) * st]; a2 += p[(s + 2 * DP_FIN_SG) * st]; a3 += p[(s + 3 * DP_FIN_SG) * st];
-    }
-    for (; s < ns; s += DP_FIN_SG) a0 += p[s * st];
-    acc = (a0 + a1) + (a2 + a3);
-  }
-  red[sg][cj] = acc;
-  __syncthreads();
-  if (threadIdx.x < DP_FIN_CO && j < P) {
-    float tot = 0.f;
+    if (j0 + 3 < g.p_off + g.n && (((uintptr_t)p | (uintptr_t)(st * 4)) & 15) == 0) {
+      // the block lies inside one tensor and its rows are 16-byte aligned
+      float4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0;
+      int s = sg;
+      for (; s + DP_FIN_SG < ns; s += 2 * DP_FIN_SG) {
+        const float4 v0 = *reinterpret_cast<const float4 *>(p + s * st);
+        const float4 v1 = *reinterpret_cast<const float4 *>(p + (s + DP_FIN_SG) * st);
+        a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+        a1.x += v1.x; a1.y += v1.y; a1.z += v1.z; a1.w += v1.w;
+      }
+      if (s < ns) {
+        const float4 v0 = *reinterpret_cast<const float4 *>(p + s * st);
+        a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
+      }
+      acc[0] = a0.x + a1.x; acc[1] = a0.y + a1.y; acc[2] = a0.z + a1.z; acc[3] = a0.w + a1.w;
+    } else {
+      // a block that straddles two tensors, or unaligned rows: coordinate by coordinate
 #pragma unroll
-    for (int q = 0; q < DP_FIN_SG; ++q) tot += red[q][cj];
+      for (int q = 0; q < 4; ++q) {
+        const long j = j0 + q;
+        if (j >= P) break;
+        int sj = si;
+        while (sj < fa.nseg - 1 && j >= fa.seg[sj].p_off + fa.seg[sj].n) ++sj;
+        const FinalizeSeg &h = fa.seg[sj];
+        const float *pj = h.part + (j - h.p_off);
+        float a0 = 0.f, a1 = 0.f;
+        int s = sg;
+        for (; s + DP_FIN_SG < h.nsplit; s += 2 * DP_FIN_SG) { a0 += pj[s * h.stride]; a1 += pj[(s + DP_FIN_SG) * h.stride]; }
+        if (s < h.nsplit) a0 += pj[s * h.stride];
+        acc[q] = a0 + a1;
+      }
+    }
+  }
+  if (sg > 0) red[sg - 1][cb] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  __syncthreads();
+  if (sg == 0 && j0 < P) {
+#pragma unroll
+    for (int q = 0; q < DP_FIN_SG - 1; ++q) {
+      const float4 v = red[q][cb];
+      acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+    }
     if (noise_std > 0.f) {
       float z[4];
-      normal4((uint64_t)(j >> 2), k0, k1, z);
-      tot += noise_std * z[j & 3];
+      normal4((uint64_t)blk, k0, k1, z);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[q] = fmaf(noise_std, z[q], acc[q]);
     }
-    if (out) out[j] = tot;
-    if (theta) theta[j] -= step * tot;
+    const bool whole = j0 + 3 < P;
+    if (out) {
+      if (whole && ((uintptr_t)(out + j0) & 15) == 0) *reinterpret_cast<float4 *>(out + j0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      else
+        for (int q = 0; q < 4 && j0 + q < P; ++q) out[j0 + q] = acc[q];
+    }
+    if (theta) {
+      if (whole && ((uintptr_t)(theta + j0) & 15) == 0) {
+        float4 t = *reinterpret_cast<float4 *>(theta + j0);
+        t.x -= step * acc[0]; t.y -= step * acc[1]; t.z -= step * acc[2]; t.w -= step * acc[3];
+        *reinterpret_cast<float4 *>(theta + j0) = t;
+      } else {
+        for (int q = 0; q < 4 && j0 + q < P; ++q) theta[j0 + q] -= step * acc[q];
+      }
+    }
   }
+}
+
+// coordinates per workgroup for a parameter vector of P floats, and the launch
+static inline int finalize_coords_per_block(long P) { return P < 100000 ? 64 : 256; }
+static inline void launch_finalize(hipStream_t st, const FinalizeArgs &fa, float *out, long P, float noise_std, uint32_t k0,
+                                   uint32_t k1, float *theta, float step) {
+  const int co = finalize_coords_per_block(P);
+  dim3 grid((unsigned)((P + co - 1) / co)), block(256);
+  if (co == 64) hipLaunchKernelGGL(finalize_kernel<16>, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);
+  else hipLaunchKernelGGL(finalize_kernel<4>, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);
 }

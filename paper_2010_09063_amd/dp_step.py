@@ -18,7 +18,7 @@ _KIND = {"dense": 0, "conv2d": 1, "maxpool2d": 2, "embedding": 3, "lstm_last": 4
 _ACT = {"none": 0, "relu": 1, "tanh": 2}
 
 EXPORTS = ["dp_step_init", "dp_step_init_ex", "dp_step_validate", "dp_step_num_params", "dp_step_workspace_bytes", "dp_step", "dp_step_sgd", "dp_step_nonprivate",
-           "dp_step_dense1_static", "dp_step_sample_indices", "dp_step_loop", "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_strerror", "dp_step_free"]
+           "dp_step_dense1_static", "dp_step_sample_indices", "dp_step_loop", "dp_step_last_norms", "dp_step_profile", "dp_step_profile_read", "dp_step_describe_plan", "dp_step_ceiling", "dp_step_strerror", "dp_step_free"]
 
 
 class dp_layer_desc(C.Structure):
@@ -85,6 +85,10 @@ def load_library():
         L.dp_step_profile_read.restype = C.c_int
         L.dp_step_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int),
                                            C.POINTER(C.c_float), C.c_int]
+        L.dp_step_describe_plan.restype = C.c_int
+        L.dp_step_describe_plan.argtypes = [C.c_void_p, C.c_char_p, C.c_size_t]
+        L.dp_step_ceiling.restype = C.c_int
+        L.dp_step_ceiling.argtypes = [C.c_int, C.c_void_p, C.POINTER(C.c_double)]
         L.dp_step_strerror.restype = C.c_char_p
         L.dp_step_strerror.argtypes = [C.c_int]
         L.dp_step_free.restype = None
@@ -150,6 +154,15 @@ def dp_step_dense1_static(params, x, y, batch, in_features, n_classes, C_, sigma
                                                 int(n_classes), float(C_), float(sigma),
                                                 C.c_uint64(int(seed) & (2**64 - 1)), _ptr(out_grad), _ptr(norms_out),
                                                 C.c_void_p(st.cuda_stream)))
+
+
+# -- dp_step_ceiling
+def dp_step_ceiling(what, stream=None):
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    v = C.c_double(0.0)
+    _check(load_library().dp_step_ceiling(int(what), C.c_void_p(st.cuda_stream), C.byref(v)))
+    return float(v.value)
 
 
 # -- dp_step_sample_indices
@@ -233,6 +246,17 @@ class DpStep:
         if n < 0:
             raise DpStepError(n)
         return [(labels[i].decode(), int(launches[i]), float(ms[i])) for i in range(min(n, cap))]
+
+    # -- dp_step_describe_plan
+    def dp_step_describe_plan(self):
+        buf = C.create_string_buffer(4096)
+        _check(self._lib.dp_step_describe_plan(self._ctx, buf, 4096))
+        plan = {}
+        for item in buf.value.decode().split(";"):
+            if item:
+                li, rest = item.split(":")
+                plan[int(li)] = dict(kv.split("=") for kv in rest.split(","))
+        return plan
 
     # -- dp_step_free
     def dp_step_free(self):
