@@ -60,8 +60,13 @@ def label_work(m, B, plan=None):
         if k == "dense":
             di, do = L["d_in"], L["d_out"]
             fl = 2.0 * B * di * do
-            if r.get("fwd") == "fused":   # one-layer model: forward, loss, norm, clip factor and partial sums in one launch
+            if r.get("fwd") == "fused" and li == 0:   # one-layer model: forward, loss, norm, clip factor and partial sums in one launch
                 add("dense1_fused", 2 * fl + 2.0 * B * (di + do), 4.0 * (B * di + di * do + (B // 4) * (di + 1) * do))
+            elif r.get("fwd") == "fused":  # logit layer of a two-layer model: forward, backward-data, both norms, partial sums
+                add("dense2_mid", 3 * fl + 2.0 * B * (di + do), 4.0 * (3 * B * di + di * do + (B // 4) * (di + 1) * do))
+            elif r.get("norm") == "fused":  # hidden layer of the same model: its two batch-wide contractions remain
+                add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))
+                add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
             else:
                 add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))
                 if li > 0:

@@ -11,6 +11,7 @@
 #include <stdint.h>
 
 #include "gemm_tile.h" // FastDiv
+#include "kernels_misc.h" // act_apply, act_deriv_from_out
 
 #define DENSE1_THREADS 1024  // 16 waves: one row of the [d_in + 1][N] tensor per thread
 #define DENSE1_MAX_IN 1023   // input features (+ the bias row): one row per thread
@@ -227,5 +228,237 @@ static inline int launch_dense1_fused(hipStream_t st, Dense1Args a, int max_tile
   if (ncp == 4) hipLaunchKernelGGL(dense1_fused_kernel<4>, grid, block, smem, st, a);
   else if (ncp == 10) hipLaunchKernelGGL(dense1_fused_kernel<10>, grid, block, smem, st, a);
   else hipLaunchKernelGGL(dense1_fused_kernel<15>, grid, block, smem, st, a);
+  return tiles;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Two dense layers (hidden layer with an activation, then the logits).  The hidden layer's forward product is a
+// batch-wide contraction and stays a launch of its own; everything between it and the two clipped sums depends on
+// one example alone and runs here, one workgroup of 16 waves per run of groups of four examples:
+//   A. hidden activations a1 = act(sum of the forward split-K partials + b1) into LDS (or read as they are);
+//      partial sums of ||x_e||^2;
+//   B. logits by the lane (e, j) scheme of dense1_fused_kernel over sixteenths of the hidden units, lane (e, 15)
+//      taking ||a1_e||^2; wave 0 finishes softmax, delta2 and the logit layer's squared norm (dense identity);
+//   C. delta1 = act'(a1) * (W2 delta2), its squared norm and the hidden layer's squared norm, the clip factor;
+//      s_e * delta1 goes to memory for the hidden layer's clipped sum (a plain contraction afterwards);
+//   D. thread h adds s_e a1_e[h] delta2_e (h = H: the bias row) of the four examples to its row of the
+//      workgroup's partial of the logit layer's clipped sum.
+struct Dense2Args {
+  const float *x;      // [B][d_in]
+  const float *hpart;  // forward partials of the hidden layer [ns][hstride] (ns > 0), or its finished output (ns = 0)
+  long hstride; int ns;
+  const float *b1;     // [H]
+  const float *W2;     // [H][N]
+  const float *b2;     // [N]
+  const int *y;        // [B]
+  float *sdelta1;      // [B][H]: s_e * delta1_e
+  float *part2;        // [tiles][dense1_part_stride(H, N)]
+  float *norms, *s;    // [B] (may be null)
+  int B, d_in, H, N, act;
+  int groups;
+  float C; int priv;
+  FastDiv dN;
+};
+
+template <int NCP>
+__global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2Args a) {
+  extern __shared__ float lds[];
+  const int H = a.H, N = a.N, d_in = a.d_in;
+  const int ldh = dense1_ldx(H), ldw = dense1_ldw(H);
+  float *a1s = lds;                   // [DENSE1_EX][ldh]: hidden activations, zero beyond H
+  float *wt = a1s + DENSE1_EX * ldh;  // [NCP][ldw]: W2 transposed, zero rows / tails as in dense1_fused_kernel
+  float *zp = wt + NCP * ldw;         // [16 waves][64 lanes]
+  float *d2 = zp + 16 * 64;           // [DENSE1_EX][16]: delta2, then s * delta2
+  float *bs = d2 + DENSE1_EX * 16;    // [16]: b2, -inf for the padding classes
+  float *red = bs + 16;               // [16 waves][2]: partial ||delta1||^2, ||x||^2
+  float *n2s = red + 32;              // [DENSE1_EX]: squared norm of the logit layer's gradient
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int e = lane >> 4, jj = lane & 15;
+  const int q = wave >> 2, hh = tid & 255;  // phases A and C: example of the group, first hidden unit of the thread
+  float acc[NCP];
+#pragma unroll
+  for (int j = 0; j < NCP; ++j) acc[j] = 0.f;
+
+  const float bv = a.b2[tid < N ? tid : 0];
+  {
+    const int w_total = H * N;
+    float wv[16];
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const int i = tid + DENSE1_THREADS * n;
+      wv[n] = a.W2[i < w_total ? i : 0];
+    }
+    for (int i = tid; i < NCP * ldw; i += DENSE1_THREADS) wt[i] = 0.f;
+    for (int i = tid; i < DENSE1_EX * ldh; i += DENSE1_THREADS) a1s[i] = 0.f;
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < 16; ++n) {
+      const int i = tid + DENSE1_THREADS * n;
+      if (i < w_total) {
+        const int k = (int)a.dN.div((unsigned)i), j = i - k * N;
+        wt[j * ldw + k] = wv[n];
+      }
+    }
+  }
+  if (tid < 16) bs[tid] = tid < N ? bv : -INFINITY;
+  float b1v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b1v[i] = a.b1[hh + 256 * i < H ? hh + 256 * i : 0];
+  const int kc = ((ldh >> 2) + 15) >> 4;
+  const int k0 = 4 * wave * kc, k1 = min(ldh, k0 + 4 * kc);
+
+  for (int grp = 0; grp < a.groups; ++grp) {
+    const int b0 = (blockIdx.x * a.groups + grp) * DENSE1_EX;
+    const int bq = b0 + q;            // this thread's example in phases A and C (wave-uniform)
+    const bool vq = bq < a.B;
+    // ---- A. hidden activations of example bq, units hh + 256 i; ||x||^2 partial
+    float a1v[4];
+    {
+      const long row = (long)(vq ? bq : 0) * H;
+      float pre[4] = {0.f, 0.f, 0.f, 0.f};
+      if (a.ns > 0) {
+        for (int s = 0; s < a.ns; ++s) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int h = hh + 256 * i;
+            pre[i] += a.hpart[s * a.hstride + row + (h < H ? h : 0)];
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a1v[i] = act_apply(a.act, pre[i] + b1v[i]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int h = hh + 256 * i;
+          a1v[i] = a.hpart[row + (h < H ? h : 0)];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = hh + 256 * i;
+        if (h < H) a1s[q * ldh + h] = vq ? a1v[i] : 0.f;
+      }
+    }
+    float sx = 0.f;
+    {
+      const float *xr = a.x + (long)(vq ? bq : 0) * d_in;
+      for (int k = hh; k < d_in; k += 256) { const float v = xr[k]; sx = fmaf(v, v, sx); }
+    }
+    __syncthreads();
+    // ---- B. logits (partial dot products over the wave's sixteenth of the hidden units)
+    {
+      const float *ap = a1s + e * ldh;
+      const float *bp = jj < NCP ? wt + jj * ldw : ap;
+      float z0 = 0.f, z1 = 0.f;
+#pragma unroll 4
+      for (int k = k0; k < k1; k += 4) {
+        const float4 u = *reinterpret_cast<const float4 *>(ap + k), v = *reinterpret_cast<const float4 *>(bp + k);
+        z0 = fmaf(u.x, v.x, z0); z1 = fmaf(u.y, v.y, z1); z0 = fmaf(u.z, v.z, z0); z1 = fmaf(u.w, v.w, z1);
+      }
+      zp[wave * 64 + lane] = z0 + z1;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      float z = 0.f;
+#pragma unroll
+      for (int w = 0; w < 16; ++w) z += zp[w * 64 + lane];
+      const int b = b0 + e;
+      const bool valid = b < a.B;
+      const float sa = __shfl(z, (lane & 48) + 15, 64); // ||a1_e||^2
+      z = jj < 15 ? z + bs[jj] : -INFINITY;
+      float mx = z;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+      const float ex = expf(z - mx);
+      float se = ex;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+      const int yy = a.y[valid ? b : 0];
+      const float dv = ex / se - (jj == yy ? 1.f : 0.f);
+      float sd = dv * dv;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) sd += __shfl_xor(sd, o, 64);
+      d2[e * 16 + jj] = valid ? dv : 0.f;
+      if (jj == 0) n2s[e] = (sa + 1.f) * sd;
+    }
+    __syncthreads();
+    // ---- C. delta1 of example bq, its norm, the clip factor
+    float d1v[4];
+    float sq = 0.f;
+    {
+      float dq[NCP];
+#pragma unroll
+      for (int j = 0; j < NCP; ++j) dq[j] = d2[q * 16 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = hh + 256 * i;
+        const int hc = h < H ? h : 0;
+        float t = 0.f;
+#pragma unroll
+        for (int j = 0; j < NCP; ++j) t = fmaf(wt[j * ldw + hc], dq[j], t);
+        t *= act_deriv_from_out(a.act, a1s[q * ldh + hc]);
+        d1v[i] = h < H ? t : 0.f;
+        sq = fmaf(d1v[i], d1v[i], sq);
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { sq += __shfl_xor(sq, o, 64); sx += __shfl_xor(sx, o, 64); }
+    if (lane == 0) { red[wave * 2] = sq; red[wave * 2 + 1] = sx; }
+    __syncthreads();
+    float sc;
+    {
+      const int w0 = 4 * q;
+      const float sd1 = (red[w0 * 2] + red[w0 * 2 + 2]) + (red[w0 * 2 + 4] + red[w0 * 2 + 6]);
+      const float sxx = (red[w0 * 2 + 1] + red[w0 * 2 + 3]) + (red[w0 * 2 + 5] + red[w0 * 2 + 7]);
+      const float n = sqrtf((sxx + 1.f) * sd1 + n2s[q]);
+      sc = a.priv ? fminf(1.f, a.C / n) : 1.f; // n == 0: C/0 = +inf -> 1
+      if (vq && hh == 0) {
+        if (a.norms) a.norms[bq] = n;
+        if (a.s) a.s[bq] = sc;
+      }
+      if (vq) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int h = hh + 256 * i;
+          if (h < H) a.sdelta1[(long)bq * H + h] = sc * d1v[i];
+        }
+      }
+    }
+    __syncthreads(); // every thread has read delta2 before it is scaled in place
+    if (hh < 16) d2[q * 16 + hh] *= sc;
+    __syncthreads();
+    // ---- D. the logit layer's clipped partial: thread = row tid of [H + 1][N]
+    if (tid <= H) {
+#pragma unroll
+      for (int p = 0; p < DENSE1_EX; ++p) {
+        const float v = tid < H ? a1s[p * ldh + tid] : 1.f;
+#pragma unroll
+        for (int j = 0; j < NCP; ++j) acc[j] = fmaf(v, d2[p * 16 + j], acc[j]);
+      }
+    }
+    __syncthreads();
+  }
+  if (tid <= H) {
+    float *pr = a.part2 + (long)blockIdx.x * dense1_part_stride(H, N) + (long)tid * N;
+#pragma unroll
+    for (int j = 0; j < NCP; ++j)
+      if (j < N) pr[j] = acc[j];
+  }
+}
+
+static inline int launch_dense2_mid(hipStream_t st, Dense2Args a, int max_tiles) {
+  int groups = 1, tiles = 0;
+  dense1_tiling(a.B, max_tiles, &groups, &tiles);
+  if (tiles == 0) return 0;
+  a.groups = groups;
+  a.dN.init(a.N);
+  dim3 grid(tiles), block(DENSE1_THREADS);
+  const int ncp = dense1_ncp(a.N);
+  const size_t smem = sizeof(float) * ((size_t)DENSE1_EX * dense1_ldx(a.H) + (size_t)ncp * dense1_ldw(a.H) + 16 * 64 +
+                                       DENSE1_EX * 16 + 16 + 32 + DENSE1_EX);
+  if (ncp == 4) hipLaunchKernelGGL(dense2_mid_kernel<4>, grid, block, smem, st, a);
+  else if (ncp == 10) hipLaunchKernelGGL(dense2_mid_kernel<10>, grid, block, smem, st, a);
+  else hipLaunchKernelGGL(dense2_mid_kernel<15>, grid, block, smem, st, a);
   return tiles;
 }

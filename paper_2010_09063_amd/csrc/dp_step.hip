@@ -195,6 +195,7 @@ struct dp_ctx {
   int *bad = nullptr;    // dp_step_validate: number of out-of-range ids / labels
   uint32_t *xb = nullptr; int *yb = nullptr, *idx = nullptr; // dp_step_loop: the drawn minibatch (allocated on its first call)
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
+  bool fused2 = false; // two dense layers: everything between the hidden layer's forward product and the clipped sums in dense2_mid_kernel
   // profiling
   bool prof = false;
   std::vector<const char *> labels; // string literals
@@ -631,6 +632,8 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
   c->max_slots = total_slots;
   c->fused1 = c->L.size() == 1 && c->L[0].d.kind == DP_DENSE && dense1_fits(c->L[0].d.in_features, c->L[0].d.out_features) &&
               !c->opt.no_fused_dense;
+  c->fused2 = c->L.size() == 2 && c->L[0].d.kind == DP_DENSE && c->L[1].d.kind == DP_DENSE &&
+              dense1_fits(c->L[1].d.in_features, c->L[1].d.out_features) && !c->opt.no_fused_dense;
   for (size_t i = 0; i < c->L.size(); ++i) {
     c->L[i].lab.reserve(sizeof(kLayerLabels) / sizeof(kLayerLabels[0]));
     for (const char *nm : kLayerLabels) c->L[i].lab.push_back(std::string(nm) + "#" + std::to_string(i));
@@ -914,7 +917,10 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     const float *in = (const float *)x;
     int fused_pool = -1;
     const bool no_pool_fusion = c->opt.no_pool_fusion != 0;
+    const bool f2 = c->fused2;
+    int mid_ns = 0, mid_tiles = 0;
     for (int i = 0; i < nL; ++i) {
+      if (f2 && i == 1) break; // the logits are computed by the kernel that follows the hidden layer
       Layer &l = c->L[i];
       const float *W = params + l.p_off;
       switch (l.d.kind) {
@@ -935,6 +941,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           vec_dispatch(OpRowMajor<true>::can_vec(in, l.d.in_features, 0, l.d.in_features) &&
                               OpKMajor<true, false>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
           if (i == nL - 1 && fused_head) { head_ns = ns; break; } // bias + loss gradient + norm in one launch below
+          if (f2) { mid_ns = ns; break; }                         // bias + activation where the partials are consumed
           const long total = (long)B * l.out_size;
           dim3 grid = grid1d(total, 256), block(256);
           const float *bias = W + (long)l.d.in_features * l.d.out_features;
@@ -1065,8 +1072,24 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       }
       in = l.a;
     }
+    if (f2) {
+      // two dense layers: logits, loss gradient, both layers' norms, the clip factor, s * delta of the hidden layer and
+      // the partial clipped sums of the logit layer, all per example, in one launch
+      Layer &l0 = c->L[0], &l1 = c->L[1];
+      Dense2Args a{};
+      a.x = (const float *)x; a.hpart = mid_ns > 0 ? l0.fpart : l0.a; a.hstride = (long)c->maxB * l0.out_size; a.ns = mid_ns;
+      a.b1 = params + l0.p_off + (long)l0.d.in_features * l0.d.out_features;
+      a.W2 = params + l1.p_off; a.b2 = a.W2 + (long)l1.d.in_features * l1.d.out_features; a.y = (const int *)y;
+      a.sdelta1 = l0.g; a.part2 = l1.part; a.norms = priv ? c->norms : nullptr; a.s = priv ? c->s : nullptr;
+      a.B = B; a.d_in = l0.d.in_features; a.H = l1.d.in_features; a.N = l1.d.out_features; a.act = l0.d.act;
+      a.C = C; a.priv = priv ? 1 : 0;
+      Ln("dense2_mid", dim3(1), dim3(256), [&](hipStream_t st) {
+        mid_tiles = launch_dense2_mid(st, a, std::min(DENSE1_MAX_TILES, l1.max_split));
+      });
+    }
     // ------------------------------------------------------------ loss gradient
-    if (fused_head) {
+    if (f2) {
+    } else if (fused_head) {
       // the last dense layer's bias, the loss gradient and that layer's norm (the first slot of the backward
       // pass) in one launch, one wave per example
       Layer &l = c->L[nL - 1];
@@ -1092,7 +1115,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       });
     }
     // ------------------------------------------------------------ backward: data gradients and per-example norms
-    for (int i = nL - 1; i >= 0; --i) {
+    for (int i = f2 ? -1 : nL - 1; i >= 0; --i) {
       Layer &l = c->L[i];
       const float *W = params + l.p_off;
       const float *lin = i > 0 ? c->L[i - 1].a : (const float *)x;
@@ -1327,7 +1350,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       }
     }
     // ------------------------------------------------------------ clip factors
-    if (priv && !(fused_head && nL == 1)) {
+    if (priv && !(fused_head && nL == 1) && !f2) {
       dim3 grid = grid1d(B, 128), block(128);
       const int ns = slot_next;
       Ln("clip_factor", grid, block, [&](hipStream_t st) {
@@ -1335,7 +1358,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
                            c->norms, c->s, B);
       });
     }
-    const float *sc = priv ? c->s : c->ones;
+    // (two fused dense layers: the hidden layer's delta already carries the clip factors)
+    const float *sc = (priv && !f2) ? c->s : c->ones;
     // ------------------------------------------------------------ clipped sums (split-K partials)
     for (int i = 0; i < nL; ++i) {
       Layer &l = c->L[i];
@@ -1344,6 +1368,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       int nsplit = 1;
       switch (l.d.kind) {
       case DP_DENSE: {
+        if (f2 && i == 1) { nsplit = mid_tiles; break; } // its partials were written by dense2_mid_kernel
         auto run = [&](auto vt) {
           constexpr bool V = decltype(vt)::value;
           typedef ProbPartial<OpKMajor<V, true>, OpKMajor<V, false>> Pb;
@@ -1642,6 +1667,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
     case DP_DENSE:
       fwd = c->fused1 ? "fused" : "generic"; bwd = i > 0 ? "generic" : "-";
       norm = c->fused1 ? "fused" : "identity"; sum = c->fused1 ? "fused" : "generic";
+      if (c->fused2) { norm = "fused"; if (i == 1) fwd = bwd = sum = "fused"; }
       break;
     case DP_CONV2D:
       fwd = l.u_f ? (l.wino_f == 2 ? "mf64" : "mf32") : (l.dir_fwd ? "direct" : "generic");

@@ -498,18 +498,24 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, fl
     const int ns = g.nsplit;
     if (j0 + 3 < g.p_off + g.n && (((uintptr_t)p | (uintptr_t)(st * 4)) & 15) == 0) {
       // the block lies inside one tensor and its rows are 16-byte aligned
-      float4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0;
+      float4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
       int s = sg;
-      for (; s + DP_FIN_SG < ns; s += 2 * DP_FIN_SG) {
+      for (; s + 3 * DP_FIN_SG < ns; s += 4 * DP_FIN_SG) { // four rows in flight
         const float4 v0 = *reinterpret_cast<const float4 *>(p + s * st);
         const float4 v1 = *reinterpret_cast<const float4 *>(p + (s + DP_FIN_SG) * st);
+        const float4 v2 = *reinterpret_cast<const float4 *>(p + (s + 2 * DP_FIN_SG) * st);
+        const float4 v3 = *reinterpret_cast<const float4 *>(p + (s + 3 * DP_FIN_SG) * st);
         a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
         a1.x += v1.x; a1.y += v1.y; a1.z += v1.z; a1.w += v1.w;
+        a2.x += v2.x; a2.y += v2.y; a2.z += v2.z; a2.w += v2.w;
+        a3.x += v3.x; a3.y += v3.y; a3.z += v3.z; a3.w += v3.w;
       }
-      if (s < ns) {
+      for (; s < ns; s += DP_FIN_SG) {
         const float4 v0 = *reinterpret_cast<const float4 *>(p + s * st);
         a0.x += v0.x; a0.y += v0.y; a0.z += v0.z; a0.w += v0.w;
       }
+      a0.x += a2.x; a0.y += a2.y; a0.z += a2.z; a0.w += a2.w;
+      a1.x += a3.x; a1.y += a3.y; a1.z += a3.z; a1.w += a3.w;
       acc[0] = a0.x + a1.x; acc[1] = a0.y + a1.y; acc[2] = a0.z + a1.z; acc[3] = a0.w + a1.w;
     } else {
       // a block that straddles two tensors, or unaligned rows: coordinate by coordinate
@@ -561,11 +567,13 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, fl
   }
 }
 
-// coordinates per workgroup for a parameter vector of P floats, and the launch
-static inline int finalize_coords_per_block(long P) { return P < 100000 ? 64 : 256; }
+// The launch: sixteen split groups (64 coordinates per workgroup) where a tensor has many partial rows or the
+// vector is short, four (256 coordinates) otherwise.
 static inline void launch_finalize(hipStream_t st, const FinalizeArgs &fa, float *out, long P, float noise_std, uint32_t k0,
                                    uint32_t k1, float *theta, float step) {
-  const int co = finalize_coords_per_block(P);
+  int max_ns = 0;
+  for (int i = 0; i < fa.nseg; ++i) max_ns = fa.seg[i].nsplit > max_ns ? fa.seg[i].nsplit : max_ns;
+  const int co = (P < 100000 || max_ns > 24) ? 64 : 256;
   dim3 grid((unsigned)((P + co - 1) / co)), block(256);
   if (co == 64) hipLaunchKernelGGL(finalize_kernel<16>, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);
   else hipLaunchKernelGGL(finalize_kernel<4>, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);

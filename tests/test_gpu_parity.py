@@ -319,6 +319,21 @@ def test_one_layer_models_of_other_widths():
         _check_all_regimes(m, x, y, theta, f"dense {d_in}->{k}/B{batch}")
 
 
+def test_two_layer_models_of_other_widths():
+    """The fused kernel of two-dense-layer models: hidden widths below one wave's share, not a multiple of four, at
+    the limit; both activations; class counts that pad to 4, 10 and 15 lanes; a hidden layer wide enough that its
+    forward product is split over K and one that is not; batches with a ragged last group and several groups per
+    workgroup; then the same models on the generic kernels."""
+    cases = ((7, 5, 3, "tanh", 9), (784, 512, 10, "relu", 37), (64, 1023, 10, "tanh", 6), (300, 50, 15, "relu", 1100),
+             (2000, 33, 2, "tanh", 70))
+    for d_in, H, k, act, batch in cases:
+        m = W.model(W.image_input(d_in), [W.dense(d_in, H, act=act), W.dense(H, k)], k)
+        x, y, theta = _case(m, batch, seed=H)
+        _check_all_regimes(m, x, y, theta, f"dense {d_in}->{H}->{k}/{act}/B{batch}")
+    wl = W.make_workload("cfg2_mlp", batch=77, seed=2, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/generic kernels", options=dict(no_fused_dense=1))
+
+
 def test_side_stream_and_validate():
     """A context on a non-default stream (its init-time fills must be ordered before the first step), and the debug
     range check of labels and token ids."""
