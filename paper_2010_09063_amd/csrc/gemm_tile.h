@@ -192,7 +192,10 @@ struct TileLoader<Op, ROWS, THREADS, BK, LOAD_VEC_F> {
 //   kReduce == false:  void store(int z, int split, int m, int n, float acc) const;
 //   kReduce == true:   float contrib(int z, int m, int n, float acc) const;
 //                      void store_tile(int z, int tile, float sum) const;
-template <class Cfg, class P>
+// TAIL: the K range of a block may end inside a tile (K or the split length is no multiple of 32); the last tile then
+// multiplies only the k pairs that hold data.  (A separate instantiation: the extra branch costs the full-tile loop
+// of the other one some of its scheduling.)
+template <class Cfg, class P, bool TAIL = false>
 __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
   typedef TileLoader<typename P::A, Cfg::BM, Cfg::THREADS, Cfg::BK> LoadA;
   typedef TileLoader<typename P::B, Cfg::BN, Cfg::THREADS, Cfg::BK> LoadB;
@@ -258,8 +261,7 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
       la.fetch(p.a, z, k0 + BK, kend);
       lb.fetch(p.b, z, k0 + BK, kend);
     }
-#pragma unroll
-    for (int ks = 0; ks < BK; ks += 2) {
+    auto kstep = [&](int ks) {
       float av[Cfg::MB], bv[Cfg::NB];
 #pragma unroll
       for (int i = 0; i < Cfg::MB; ++i) av[i] = As[(ks + lk) * LDA + wm * Cfg::TM + i * 32 + li];
@@ -270,6 +272,15 @@ __global__ __launch_bounds__(Cfg::THREADS) void gemm_tile_kernel(const P p) {
 #pragma unroll
         for (int j = 0; j < Cfg::NB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+    };
+    if (!TAIL || k0 + BK <= kend) {
+#pragma unroll
+      for (int ks = 0; ks < BK; ks += 2) kstep(ks);
+    } else {
+      // the last, partial tile of K: only the k pairs that hold data (the rest of the tile is zeros), so a K of
+      // 100 costs 3 1/8 tiles of multiplies, not 4
+      const int kl = kend - k0;
+      for (int ks = 0; ks < kl; ks += 2) kstep(ks);
     }
     __syncthreads();
   }
@@ -352,11 +363,13 @@ static inline void launch_gemm_shape(P p, GemmShape s, int batch, int splits, La
   const long nblk = p.groups >= 8 ? (long)ceil_div(p.groups, 8) * 8 * p.tiles
                                   : (long)p.groups * 8 * ceil_div(p.tiles, 8);
   dim3 grid((unsigned)nblk);
+  const bool tail = (p.K % 32) != 0; // (k_chunk is a multiple of 32: only the end of K can fall inside a tile)
 #define DP_GEMM_CASE(bm_, bn_, wm_, wn_)                                                    \
   if (s.bm == bm_ && s.bn == bn_) {                                                         \
     typedef TileCfg<bm_, bn_, wm_, wn_> Cfg;                                                \
     L(label, grid, dim3(Cfg::THREADS), [&](hipStream_t st) {                                \
-      hipLaunchKernelGGL((gemm_tile_kernel<Cfg, P>), grid, dim3(Cfg::THREADS), 0, st, p);   \
+      if (tail) hipLaunchKernelGGL((gemm_tile_kernel<Cfg, P, true>), grid, dim3(Cfg::THREADS), 0, st, p);  \
+      else hipLaunchKernelGGL((gemm_tile_kernel<Cfg, P, false>), grid, dim3(Cfg::THREADS), 0, st, p);      \
     });                                                                                     \
     return;                                                                                 \
   }
