@@ -118,7 +118,8 @@ typedef struct {
   int conv_min_blocks;            /* grid the direct forward kernel narrows its tiles for (0: 512)                */
   int gemm_plain_tiles;           /* tile choice of the generic contraction without the padding-waste rule        */
   int no_fused_dense;             /* one-dense-layer models on the generic kernels (four launches)                */
-  int reserved[7];                /* zero                                                                          */
+  int no_fused_cnn;               /* the small MNIST-shaped CNN layer by layer instead of in one launch            */
+  int reserved[6];                /* zero                                                                          */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

@@ -18,6 +18,7 @@
 #include "conv_direct.h"
 #include "conv_gram.h"
 #include "ceilings.h"
+#include "cnn_fused.h"
 #include "conv_wino.h"
 #include "dense_fused.h"
 #include "kernels_misc.h"
@@ -195,6 +196,7 @@ struct dp_ctx {
   int *bad = nullptr;    // dp_step_validate: number of out-of-range ids / labels
   uint32_t *xb = nullptr; int *yb = nullptr, *idx = nullptr; // dp_step_loop: the drawn minibatch (allocated on its first call)
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
+  bool fusedcnn = false; float *cnn_part = nullptr; // the small MNIST-shaped CNN in one launch (cnn_small_fused_kernel)
   bool fused2 = false; // two dense layers: everything between the hidden layer's forward product and the clipped sums in dense2_mid_kernel
   // profiling
   bool prof = false;
@@ -632,6 +634,23 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
   c->max_slots = total_slots;
   c->fused1 = c->L.size() == 1 && c->L[0].d.kind == DP_DENSE && dense1_fits(c->L[0].d.in_features, c->L[0].d.out_features) &&
               !c->opt.no_fused_dense;
+  {
+    // the network cnn_small_fused_kernel is written for, layer by layer
+    auto conv_is = [&](const Layer &l, int ci, int co, int k, int st, int pad) {
+      return l.d.kind == DP_CONV2D && l.d.in_ch == ci && l.d.out_ch == co && l.d.kh == k && l.d.kw == k && l.d.stride == st && l.d.pad == pad;
+    };
+    auto pool_is = [&](const Layer &l) { return l.d.kind == DP_MAXPOOL2D && l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 1; };
+    c->fusedcnn = c->L.size() == 6 && model->in_c == 1 && model->in_h == 28 && model->in_w == 28 && model->n_classes == 10 &&
+                  conv_is(c->L[0], 1, 16, 8, 2, 3) && pool_is(c->L[1]) && conv_is(c->L[2], 16, 32, 4, 2, 0) && pool_is(c->L[3]) &&
+                  c->L[4].d.kind == DP_DENSE && c->L[4].d.in_features == 512 && c->L[4].d.out_features == 32 &&
+                  c->L[5].d.kind == DP_DENSE && c->L[5].d.in_features == 32 && c->L[5].d.out_features == 10 &&
+                  c->L[5].d.act == DP_ACT_NONE && off == cnnf::NPARAM && !c->opt.no_fused_cnn;
+    if (c->fusedcnn && hipFuncSetAttribute((const void *)cnn_small_fused_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)cnnf::LDS_BYTES) != hipSuccess) {
+      (void)hipGetLastError();
+      c->fusedcnn = false;
+    }
+  }
   c->fused2 = c->L.size() == 2 && c->L[0].d.kind == DP_DENSE && c->L[1].d.kind == DP_DENSE &&
               dense1_fits(c->L[1].d.in_features, c->L[1].d.out_features) && !c->opt.no_fused_dense;
   for (size_t i = 0; i < c->L.size(); ++i) {
@@ -759,6 +778,7 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
   if (rc == DP_OK) rc = dev_alloc(c, &c->s, mb);
   if (rc == DP_OK) rc = dev_alloc(c, &c->ones, mb);
   if (rc == DP_OK) rc = dev_alloc(c, &c->bad, 1);
+  if (rc == DP_OK && c->fusedcnn) rc = dev_alloc(c, &c->cnn_part, (size_t)256 * ((cnnf::NPARAM + 3) & ~3));
   if (rc == DP_OK) {
     std::vector<float> one(mb, 1.f);
     if (hipMemcpy(c->ones, one.data(), sizeof(float) * mb, hipMemcpyHostToDevice) != hipSuccess) rc = DP_EHIP;
@@ -847,7 +867,23 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
   // the network ends in a dense layer of at most 64 classes: its bias, the loss gradient and its norm share a launch
   const bool fused_head = c->L[nL - 1].d.kind == DP_DENSE && c->L[nL - 1].d.out_features <= 64;
   int head_ns = 0; // forward split-K partials of the last layer still to be summed (0: its output is complete)
-  if (B > 0 && c->fused1) {
+  if (B > 0 && c->fusedcnn && aligned16(params)) {
+    // the small CNN: forward, backward, every example's gradient, norm, clip factor and the partial clipped sums in
+    // one launch; a workgroup walks through its examples
+    CnnFusedArgs a{};
+    a.params = params; a.x = (const float *)x; a.y = (const int *)y; a.part = c->cnn_part; a.pstride = (cnnf::NPARAM + 3) & ~3;
+    a.norms = priv ? c->norms : nullptr; a.s = priv ? c->s : nullptr; a.B = B;
+    a.act1 = c->L[0].d.act; a.act2 = c->L[2].d.act; a.act3 = c->L[4].d.act; a.C = C; a.priv = priv ? 1 : 0;
+    const int tiles = std::min(B, 256);
+    Ln("cnn_small_fused", dim3(tiles), dim3(cnnf::THREADS), [&](hipStream_t st) {
+      hipLaunchKernelGGL(cnn_small_fused_kernel, dim3(tiles), dim3(cnnf::THREADS), cnnf::LDS_BYTES, st, a);
+    });
+    for (auto &l : c->L) {
+      if (l.p_count == 0) continue;
+      FinalizeSeg &sg = fa.seg[fa.nseg++];
+      sg.p_off = l.p_off; sg.n = l.p_count; sg.part = c->cnn_part + l.p_off; sg.stride = a.pstride; sg.nsplit = tiles;
+    }
+  } else if (B > 0 && c->fused1) {
     // softmax regression: logits, loss gradient, norm, clip factor and the clipped partial sums in one launch
     Layer &l = c->L[0];
     Dense1Args a{};
@@ -1668,6 +1704,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
       fwd = c->fused1 ? "fused" : "generic"; bwd = i > 0 ? "generic" : "-";
       norm = c->fused1 ? "fused" : "identity"; sum = c->fused1 ? "fused" : "generic";
       if (c->fused2) { norm = "fused"; if (i == 1) fwd = bwd = sum = "fused"; }
+      if (c->fusedcnn) fwd = bwd = norm = sum = "fused-net";
       break;
     case DP_CONV2D:
       fwd = l.u_f ? (l.wino_f == 2 ? "mf64" : "mf32") : (l.dir_fwd ? "direct" : "generic");
@@ -1675,6 +1712,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
       norm = l.gram ? "gram" : ((l.wino_norm && l.gst) ? "mf+store" : (l.dir_wg ? (l.gst ? "direct+store" : (l.wg_ws ? "ws" : "direct"))
                                                                                 : (l.gst ? "generic+store" : "generic")));
       sum = l.gst ? "weighted" : ((l.wino_wgu || l.wino_wg) ? "mf" : (l.dir_wg ? (l.wg_ws ? "ws" : "direct") : "generic"));
+      if (c->fusedcnn) fwd = bwd = norm = sum = "fused-net";
       break;
     case DP_EMBEDDING: fwd = "gather"; norm = "sorted-segments"; sum = "scatter"; break;
     case DP_LSTM_LAST:

@@ -97,7 +97,7 @@ class TieAwareOracle:
     to the usual tolerances against them.  Every example is therefore checked: a clear example against its
     unique gradient, a near-tied one against the closest member of its finite set of valid gradients."""
 
-    def __init__(self, m, theta, x, y, margin, tau=TAU, max_combos=64):
+    def __init__(self, m, theta, x, y, margin, tau=TAU, max_combos=1024):
         self.m, self.theta, self.x, self.y, self.tau = m, theta, x, y, tau
         self.cands = {}  # example -> (g0, [(routes, g, gap)])
         if not any(L["kind"] == "maxpool2d" for L in m["layers"]) or len(y) == 0:

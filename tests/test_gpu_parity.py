@@ -334,6 +334,36 @@ def test_two_layer_models_of_other_widths():
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/generic kernels", options=dict(no_fused_dense=1))
 
 
+def test_small_cnn_layer_by_layer_and_fused():
+    """The MNIST-shaped CNN takes one fused launch by default; no_fused_cnn keeps it on the per-layer kernels.  Both
+    routes at batches below, at and above one example per workgroup (a workgroup of the fused kernel walks through
+    several examples from batch 257 on), both activation sets."""
+    for name in ("cfg3_small_cnn", "paper_mnist_cnn"):
+        for batch in (1, 37, 300):
+            wl = W.make_workload(name, batch=batch, seed=batch, bias_scale=0.2)
+            _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/B{batch}/fused")
+        wl = W.make_workload(name, batch=37, seed=2, bias_scale=0.2)
+        _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/B37/layer by layer", options=dict(no_fused_cnn=1))
+    # parameters that are not 16-byte aligned: the fused kernel reads weight rows with 16-byte loads, so the step
+    # takes the per-layer route
+    import torch
+    from paper_2010_09063_amd import DpStep
+    dev = torch.device("cuda:0")
+    wl = W.make_workload("cfg3_small_cnn", batch=9, seed=3, bias_scale=0.2)
+    m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
+    ref = O.dp_step(m, theta, x, y, 0.7, 0.0, 0)
+    st = DpStep(m, 9)
+    pbuf = torch.zeros(theta.size + 1, device=dev)
+    pbuf[1:] = torch.from_numpy(theta).to(dev)
+    out = torch.empty(theta.size, device=dev)
+    st.dp_step(pbuf[1:], torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev), 9, 0.7, 0.0, 0, out)
+    torch.cuda.synchronize()
+    tie = TieAwareOracle(m, theta, x, y, ref["pool_margin"])
+    csum, _, _ = tie.reference(ref, 0.7, out.cpu().numpy())
+    assert_parity(m, out.cpu().numpy(), csum, "cfg3/unaligned parameters", ref["abs_sum"])
+    st.dp_step_free()
+
+
 def test_side_stream_and_validate():
     """A context on a non-default stream (its init-time fills must be ordered before the first step), and the debug
     range check of labels and token ids."""
@@ -448,7 +478,7 @@ def test_repeatable_and_profile_hook():
     wl = W.make_workload("cfg3_small_cnn", batch=64, seed=9)
     m = wl["model"]
     dev = torch.device("cuda:0")
-    st = DpStep(m, 64)
+    st = DpStep(m, 64, no_fused_cnn=1)   # layer by layer, so that every kernel kind shows up in the table
     tp = torch.from_numpy(wl["params"]).to(dev)
     tx = torch.from_numpy(wl["x"]).to(dev)
     ty = torch.from_numpy(wl["y"]).to(dev)
@@ -472,8 +502,9 @@ def test_repeatable_and_profile_hook():
 
 
 @pytest.mark.parametrize("name,batch,opt", [("cfg4_cifar_cnn", None, {}), ("paper_cifar_cnn", None, {}), ("cfg2_mlp", None, {}),
-                                            ("cfg1_logistic", None, {}), ("cfg5_lstm", 64, {}), ("wide", 70, dict(no_gram=1, no_minimal_filtering=1))],
-                         ids=["cfg4", "paper_cifar", "cfg2", "cfg1", "cfg5-dense-tensors", "wide-ws"])
+                                            ("cfg1_logistic", None, {}), ("cfg5_lstm", 64, {}), ("wide", 70, dict(no_gram=1, no_minimal_filtering=1)),
+                                            ("cfg3_small_cnn", None, {}), ("cfg3_small_cnn", None, dict(no_fused_cnn=1))],
+                         ids=["cfg4", "paper_cifar", "cfg2", "cfg1", "cfg5-dense-tensors", "wide-ws", "cfg3", "cfg3-layerwise"])
 def test_bit_identical_repeats_at_full_batch(name, batch, opt):
     """Every reduction of the step runs in a fixed order: two steps on the same inputs agree bit for bit, at the
     benchmark batch (the embedding tensor excepted: the chunks of a hot token meet through fp32 atomics)."""
