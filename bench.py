@@ -57,6 +57,20 @@ def label_work(m, B, plan=None):
         o = shapes[li]
         k = L["kind"]
         r = plan.get(li, {})
+        if r.get("fwd") == "fused-net":
+            # the whole network in one launch (cnn_small_fused): forward, backward-data and ONE weight-gradient
+            # contraction per layer (the example's gradient serves the norm and, scaled, the clipped sum)
+            if k == "dense":
+                fl, pc = 2.0 * B * L["d_in"] * L["d_out"], L["d_in"] * L["d_out"] + L["d_out"]
+            else:
+                fl = 2.0 * B * o[1] * cur[1] * L["kh"] * L["kw"] * o[2] * o[3]
+                pc = o[1] * cur[1] * L["kh"] * L["kw"] + o[1]
+            nb = 4.0 * (B * int(np.prod(cur[1:])) if li == 0 else 0) + 4.0 * pc * (1 + min(B, 256))
+            for key in ("cnn_small_fused",):
+                f, b, e = out.get(key, (0.0, 0.0, 0.0))
+                out[key] = (f + fl * (3 if li > 0 else 2), b + nb, e + fl * (3 if li > 0 else 2))
+            cur = o
+            continue
         if k == "dense":
             di, do = L["d_in"], L["d_out"]
             fl = 2.0 * B * di * do

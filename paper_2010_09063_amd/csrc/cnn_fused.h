@@ -76,22 +76,20 @@ __global__ __launch_bounds__(cnnf::THREADS) void cnn_small_fused_kernel(const Cn
   float *w2s = lds + L_W2, *bb = lds + L_B, *cols = lds + L_COLS, *w1s = lds + L_W1;
   uint8_t *arg1 = reinterpret_cast<uint8_t *>(lds + L_ARG1), *arg2 = reinterpret_cast<uint8_t *>(lds + L_ARG2);
   const float *b1 = bb, *b2 = bb + 16, *b3 = bb + 48, *b4 = bb + 80, *w4 = bb + 96; // W4[n][j] at w4[n * 10 + j]
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i16 = lane & 15, kq = lane >> 4;
+  const int tid0 = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
 
   // ---- once per workgroup: weights into LDS / registers, zero border of the padded input
-  for (int i = tid; i < XP * XP; i += THREADS) xp[i] = 0.f;
-  for (int i = tid; i < D2 * CK2; i += THREADS) w2s[(i >> 8) * LW2 + (i & 255)] = a.params[OFF_W2 + i];
-  if (tid < 16) bb[tid] = a.params[OFF_B1 + tid];
-  if (tid < 32) { bb[16 + tid] = a.params[OFF_B2 + tid]; bb[48 + tid] = a.params[OFF_B3 + tid]; }
-  if (tid < 10) bb[80 + tid] = a.params[OFF_B4 + tid];
-  if (tid < 320) bb[96 + tid] = a.params[OFF_W4 + tid];
-  w1s[(tid >> 6) * 65 + (tid & 63)] = a.params[OFF_W1 + tid];
-  const int fn = tid & 31, fk = tid >> 5; // fc1: output unit, block of 16 input features
+  for (int i = tid0; i < XP * XP; i += THREADS) xp[i] = 0.f;
+  for (int i = tid0; i < D2 * CK2; i += THREADS) w2s[(i >> 8) * LW2 + (i & 255)] = a.params[OFF_W2 + i];
+  if (tid0 < 16) bb[tid0] = a.params[OFF_B1 + tid0];
+  if (tid0 < 32) { bb[16 + tid0] = a.params[OFF_B2 + tid0]; bb[48 + tid0] = a.params[OFF_B3 + tid0]; }
+  if (tid0 < 10) bb[80 + tid0] = a.params[OFF_B4 + tid0];
+  if (tid0 < 320) bb[96 + tid0] = a.params[OFF_W4 + tid0];
+  w1s[(tid0 >> 6) * 65 + (tid0 & 63)] = a.params[OFF_W1 + tid0];
 
   // partial clipped sum of this workgroup's examples, by owner thread
-  float acc1 = 0.f, accb = 0.f, acc4 = 0.f; // conv1 weight (d = tid / 64, tap = tid % 64); one bias (see the end); fc2 weight
+  float acc1 = 0.f, accb = 0.f, acc4 = 0.f; // conv1 weight (d = tid0 / 64, tap = tid0 % 64); one bias (see the end); fc2 weight
   float acc2[2][4], acc3[16];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -101,17 +99,21 @@ __global__ __launch_bounds__(cnnf::THREADS) void cnn_small_fused_kernel(const Cn
   for (int i = 0; i < 16; ++i) acc3[i] = 0.f;
   float accb2 = 0.f, accb3 = 0.f, accb4 = 0.f;
 
-  float xnext = (tid < H0 * H0 && (int)blockIdx.x < a.B) ? a.x[(long)blockIdx.x * (H0 * H0) + tid] : 0.f;
+  float xnext = (tid0 < H0 * H0 && (int)blockIdx.x < a.B) ? a.x[(long)blockIdx.x * (H0 * H0) + tid0] : 0.f;
+  int ynext = a.y[(int)blockIdx.x < a.B ? blockIdx.x : 0];
   __syncthreads();
 
   for (int ex = blockIdx.x; ex < a.B; ex += gridDim.x) {
+    // The thread index is made opaque once per example: every phase derives its indices from it again (a few integer
+    // operations) instead of the compiler keeping dozens of loop-invariant addresses alive across the whole loop,
+    // which spilled registers to scratch memory -- and every barrier waits for outstanding scratch traffic.
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, i16 = lane & 15, kq = lane >> 4;
+    const int fn = tid & 31, fk = tid >> 5; // fc1: output unit, block of 16 input features
     // ---- input into the padded plane; the next example's pixels are requested now
     if (tid < H0 * H0) xp[(tid / H0 + 3) * XP + tid % H0 + 3] = xnext;
-    {
-      const int nx = ex + gridDim.x;
-      xnext = a.x[(tid < H0 * H0 && nx < a.B) ? (long)nx * (H0 * H0) + tid : 0];
-    }
-    const int yy = a.y[ex];
+    const int yy = ynext;
     __syncthreads();
     // ---- conv1 forward: [16 x 64] x [64 x 196]; wave = block of 16 positions
     if (wave < 13) {
@@ -235,17 +237,26 @@ __global__ __launch_bounds__(cnnf::THREADS) void cnn_small_fused_kernel(const Cn
       if (lane == 0) scl[1] = (sp2 + 1.f) * sd3 + (sa3 + 1.f) * sd4; // dense identity, both layers
     }
     __syncthreads();
-    // ---- fc1 backward-data: dp2[k] = sum_n W3[k][n] delta3[n]   (W3 row from memory: 128 contiguous bytes)
-    if (tid < F) {
-      const float4 *wr = reinterpret_cast<const float4 *>(a.params + OFF_W3 + tid * HID);
-      float t0 = 0.f, t1 = 0.f;
+    // ---- fc1 backward-data: dp2[k] = sum_n W3[k][n] delta3[n] from the weights the thread already holds: thread
+    // (unit fn, features fk*16 ..) has the sixteen products W3[k][fn] delta3[fn]; the 32 lanes of a feature block
+    // add them up by a halving exchange (16 + 8 + 4 + 2 + 1 lanes apart: each step a lane keeps half of its values
+    // and receives the partner's sums for them), 16 exchanges instead of 80, in a fixed order
+    {
+      const float dn = d3[fn];
+      const bool b4 = lane & 16, b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
+      float u8[8], u4[4], u2[2];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const float4 w = wr[q];
-        t0 = fmaf(w.x, d3[4 * q], t0); t1 = fmaf(w.y, d3[4 * q + 1], t1);
-        t0 = fmaf(w.z, d3[4 * q + 2], t0); t1 = fmaf(w.w, d3[4 * q + 3], t1);
+      for (int j = 0; j < 8; ++j) {
+        const float lo = w3r[j] * dn, hi = w3r[8 + j] * dn;
+        u8[j] = (b4 ? hi : lo) + __shfl_xor(b4 ? lo : hi, 16, 64);
       }
-      dp2[tid] = t0 + t1;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) u4[j] = (b3 ? u8[4 + j] : u8[j]) + __shfl_xor(b3 ? u8[j] : u8[4 + j], 8, 64);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) u2[j] = (b2 ? u4[2 + j] : u4[j]) + __shfl_xor(b2 ? u4[j] : u4[2 + j], 4, 64);
+      float u1 = (b1 ? u2[1] : u2[0]) + __shfl_xor(b1 ? u2[0] : u2[1], 2, 64);
+      u1 += __shfl_xor(u1, 1, 64);
+      if ((lane & 1) == 0) dp2[fk * 16 + (b4 ? 8 : 0) + (b3 ? 4 : 0) + (b2 ? 2 : 0) + (b1 ? 1 : 0)] = u1;
     }
     __syncthreads();
     // ---- pool2 backward (gather over the windows that hold the position) and conv2's activation derivative
@@ -315,15 +326,30 @@ __global__ __launch_bounds__(cnnf::THREADS) void cnn_small_fused_kernel(const Cn
       a1[i] = g * act_deriv_from_out(a.act1, a1[i]);
     }
     __syncthreads();
+    // the next example's pixels and label are requested here, ahead of the longest phase: every barrier waits for
+    // outstanding loads, so a request made at the top of the example would be waited for at once
+    {
+      const int nx = ex + gridDim.x;
+      xnext = a.x[(tid < H0 * H0 && nx < a.B) ? (long)nx * (H0 * H0) + tid : 0];
+      ynext = a.y[nx < a.B ? nx : 0];
+    }
     // ---- conv1 weight gradient: [16 x 196] x [196 x 64]; wave = (block of 16 taps, quarter of the positions)
     {
       const int nb = wave & 3, kp = wave >> 2;
       const int tap = nb * 16 + i16, tbase = (tap >> 3) * XP + (tap & 7);
-      const int ks0 = kp == 0 ? 0 : 1 + 12 * kp, ks1 = 13 + 12 * kp; // 13, 12, 12, 12 of the 49 steps
+      const int ks0 = kp == 0 ? 0 : 1 + 12 * kp; // 13, 12, 12, 12 of the 49 steps: 13 issued, the last one empty for three quarters
+      const int last = kp == 0 ? 13 : 12;
+      int p = 4 * ks0 + kq, oh = p / O1, ow = p - oh * O1;
       cnn_f32x4 d = {0.f, 0.f, 0.f, 0.f};
-      for (int ks = ks0; ks < ks1; ++ks) {
-        const int p = 4 * ks + kq; // < 196
-        d = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i16 * P1 + p], xp[(2 * (p / O1)) * XP + 2 * (p % O1) + tbase], d, 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < 13; ++j) {
+        const bool on = j < last;
+        const int pc = on ? p : 0;
+        const float av = a1[i16 * P1 + pc], bv = xp[(2 * oh) * XP + 2 * ow + tbase];
+        d = __builtin_amdgcn_mfma_f32_16x16x4f32(on ? av : 0.f, bv, d, 0, 0, 0);
+        p += 4; ow += 4;
+        if (ow >= O1) { ow -= O1; ++oh; }
+        if (!on) { oh = 0; ow = 0; }
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) cols[kp * 1024 + (4 * kq + r) * 64 + tap] = d[r];
@@ -408,6 +434,7 @@ __global__ __launch_bounds__(cnnf::THREADS) void cnn_small_fused_kernel(const Cn
     __syncthreads(); // before the next example overwrites the LDS images
   }
   // ---- the workgroup's partial, in the parameter layout
+  const int tid = tid0, lane = tid & 63, i16 = lane & 15, kq = lane >> 4, fn = tid & 31, fk = tid >> 5;
   float *pr = a.part + (long)blockIdx.x * a.pstride;
   pr[OFF_W1 + tid] = acc1;
   if (lane == 0) pr[OFF_B1 + wave] = accb;
