@@ -119,7 +119,8 @@ typedef struct {
   int gemm_plain_tiles;           /* tile choice of the generic contraction without the padding-waste rule        */
   int no_fused_dense;             /* one-dense-layer models on the generic kernels (four launches)                */
   int no_fused_cnn;               /* the small MNIST-shaped CNN layer by layer instead of in one launch            */
-  int reserved[6];                /* zero                                                                          */
+  int no_lstm_wgrad;              /* the LSTM's per-example weight gradient on the generic tiled contraction       */
+  int reserved[5];                /* zero                                                                          */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

@@ -23,6 +23,7 @@
 #include "dense_fused.h"
 #include "kernels_misc.h"
 #include "kernels_seq.h"
+#include "lstm_wgrad.h"
 #include "operands.h"
 
 static thread_local char g_hip_err[256] = "";
@@ -161,6 +162,7 @@ struct Layer {
   // embedding: counting-sort workspace of the clipped sum
   int *e_count = nullptr, *e_start = nullptr, *e_chunk0 = nullptr, *e_cursor = nullptr, *e_list = nullptr;
   // lstm
+  bool lstm_wg = false; // per-example weight gradient by lstm_wgrad_kernel (16x16 MFMA blocks, one example per two workgroups)
   float *gates = nullptr, *cs = nullptr, *hs = nullptr;
   int T = 0, Din = 0, H = 0;
 };
@@ -582,6 +584,7 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
       if (!is_seq || l.d.hidden < 1 || l.d.in_features != curH) { rc = DP_EINVAL; break; }
       if (l.d.hidden > 128 || i == 0 || model->layers[i - 1].kind != DP_EMBEDDING) { rc = DP_EUNSUPPORTED; break; }
       l.T = curC; l.Din = curH; l.H = l.d.hidden;
+      l.lstm_wg = lstm_wgrad_fits(l.Din, l.H, l.T) && !c->opt.no_lstm_wgrad;
       l.p_count = (long)l.Din * 4 * l.H + (long)l.H * 4 * l.H + 4 * l.H;
       l.max_slots = ceil_div(l.Din + l.H + 1, 32) * ceil_div(4 * l.H, 32);
       if (l.d.kind == DP_LSTM_SEQ) {
@@ -622,6 +625,15 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
     if (nparam > DP_MAX_SEG) rc = DP_EUNSUPPORTED;
   }
   if (rc != DP_OK) { delete c; return rc; }
+  {
+    bool any = false;
+    for (auto &l : c->L) any = any || l.lstm_wg;
+    if (any && hipFuncSetAttribute((const void *)lstm_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lstm_wgrad_lds_bytes()) != hipSuccess) {
+      (void)hipGetLastError();
+      for (auto &l : c->L) l.lstm_wg = false;
+    }
+  }
   {
     bool any_ws = false;
     for (auto &l : c->L) any_ws = any_ws || l.wg_ws;
@@ -1331,7 +1343,17 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         const int G = 4 * l.H;
         const float *Whh = W + (long)l.Din * G;
         LSTM_DISPATCH(launch_lstm_bwd, l.H, Ln, l, Whh, B, LL("lstm_bwd"));
-        if (priv) {
+        if (priv && l.lstm_wg && aligned16(lin) && aligned16(l.hs) && aligned16(l.gates)) {
+          LstmWgArgs a{};
+          a.x = lin; a.hs = l.hs; a.dg = l.gates; a.slots = c->slots; a.slot_stride = slot_stride; a.slot0 = slot_next;
+          a.gstore = l.gst; a.gstride = l.p_count; a.B = B; a.T = l.T; a.Din = l.Din; a.H = l.H;
+          const int halves = G > LWG_NH * 16 ? 2 : 1;
+          slot_next += halves;
+          dim3 grid(B, halves), block(LWG_THREADS);
+          Ln(LL("lstm_wgrad_norm"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(lstm_wgrad_kernel, grid, block, lstm_wgrad_lds_bytes(), st, a);
+          });
+        } else if (priv) {
           auto run = [&](auto vt) {
             constexpr bool V = decltype(vt)::value;
             typedef ProbSqNorm<OpLstmIn<V>, OpKMajor<V, false>> Pb;

@@ -440,6 +440,22 @@ def test_lstm_hidden_sizes(hidden, build):
     _check_all_regimes(m, x, y, theta, f"lstm/H{hidden}")
 
 
+def test_lstm_weight_gradient_routes():
+    """The per-example LSTM weight gradient on 16x16 MFMA blocks (one example per two workgroups) at shapes other
+    than the benchmark's: one and two column halves, row counts that end inside a block, sequences shorter than one
+    chunk of 32 steps, ending inside a chunk, and of several chunks (with and without stored gradients); then the
+    benchmark shape on the generic contraction."""
+    rng = np.random.default_rng(12)
+    for build in (W.cfg5_lstm, W.paper_lstm):
+        for dim, hidden, T, batch in ((12, 8, 5, 7), (20, 24, 140, 4), (100, 100, 70, 3), (36, 52, 33, 5), (4, 104, 64, 2)):
+            m = build(vocab=60, seq_len=T, dim=dim, hidden=hidden)
+            x, y = W.make_inputs(m, batch, rng, zipf_exponent=0.5)
+            theta = W.init_params(m, rng, bias_scale=0.2) * np.float32(3)
+            _check_all_regimes(m, x, y, theta, f"{build.__name__}/D{dim}/H{hidden}/T{T}")
+    wl = W.make_workload("cfg5_lstm", batch=6, seed=2, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg5/generic weight gradient", options=dict(no_lstm_wgrad=1))
+
+
 def test_unaligned_device_pointers():
     """params / x that are not 16-byte aligned fall back to scalar operand staging."""
     import torch
