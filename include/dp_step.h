@@ -120,7 +120,8 @@ typedef struct {
   int no_fused_dense;             /* one-dense-layer models on the generic kernels (four launches)                */
   int no_fused_cnn;               /* the small MNIST-shaped CNN layer by layer instead of in one launch            */
   int no_lstm_wgrad;              /* the LSTM's per-example weight gradient on the generic tiled contraction       */
-  int reserved[5];                /* zero                                                                          */
+  int no_rows_gemm;               /* the LSTM's input projection / input gradient on the generic tiled contraction */
+  int reserved[4];                /* zero                                                                          */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

@@ -454,6 +454,7 @@ def test_lstm_weight_gradient_routes():
             _check_all_regimes(m, x, y, theta, f"{build.__name__}/D{dim}/H{hidden}/T{T}")
     wl = W.make_workload("cfg5_lstm", batch=6, seed=2, bias_scale=0.2)
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg5/generic weight gradient", options=dict(no_lstm_wgrad=1))
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg5/generic projections", options=dict(no_rows_gemm=1))
 
 
 def test_unaligned_device_pointers():
