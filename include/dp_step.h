@@ -121,7 +121,8 @@ typedef struct {
   int no_fused_cnn;               /* the small MNIST-shaped CNN layer by layer instead of in one launch            */
   int no_lstm_wgrad;              /* the LSTM's per-example weight gradient on the generic tiled contraction       */
   int no_rows_gemm;               /* the LSTM's input projection / input gradient on the generic tiled contraction */
-  int reserved[4];                /* zero                                                                          */
+  int no_single_bucket;           /* the embedding's counting sort as three launches, whatever the batch           */
+  int reserved[3];                /* zero                                                                          */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

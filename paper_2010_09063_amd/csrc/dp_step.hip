@@ -1560,7 +1560,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count, (float *)l.e_count, (long)(V + 1));
           });
         }
-        {
+        if (V <= EMB_LDS_V && rows <= EMB_ONE_MAX_ROWS && !c->opt.no_single_bucket) {
+          Ln(LL("emb_bucket"), dim3(1), dim3(1024), [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_bucket_one_kernel, dim3(1), dim3(1024), sizeof(int) * V, st, (const int *)x, l.e_start,
+                               l.e_chunk0, l.e_list, (int)rows, V);
+          });
+        } else {
           dim3 grid = grid1d(rows, 1024), block(1024);
           const size_t smem = V <= EMB_LDS_V ? sizeof(int) * V : 0;
           Ln(LL("emb_bucket"), grid, block, [&](hipStream_t st) {

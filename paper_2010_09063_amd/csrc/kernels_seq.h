@@ -467,6 +467,58 @@ __global__ __launch_bounds__(1024) void emb_fill_kernel(const int *__restrict__ 
   if (i < n) list[start[t] + bins[t] + old] = (int)i;
 }
 
+// The three kernels above in one launch, for small batches (up to 2^15 steps, vocabularies that fit the LDS
+// histogram): count in LDS, scan, then hand out the positions of every bucket from LDS cursors.  One workgroup walks
+// through all the steps twice, so its time grows with the batch -- measured 98 us at 131,072 Zipf-distributed steps
+// (the hot tokens serialise the LDS atomics) against 57 us for the three launches -- while three launches cost
+// 15-20 us each however small the batch; hence the limit.  The order of the steps inside a bucket depends on the
+// order in which the LDS atomics retire, as it does with the three-kernel route.
+#define EMB_ONE_MAX_ROWS (1 << 15)
+__global__ __launch_bounds__(1024) void emb_bucket_one_kernel(const int *__restrict__ tok, int *__restrict__ start,
+                                                               int *__restrict__ chunk0, int *__restrict__ list, int n,
+                                                               int V) {
+  extern __shared__ int bins[]; // [V]
+  __shared__ int wa[16], wb[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int v = tid; v < V; v += 1024) bins[v] = 0;
+  __syncthreads();
+  for (int i = tid; i < n; i += 1024) atomicAdd(&bins[tok[i]], 1);
+  __syncthreads();
+  // exclusive scans of the counts and of the chunk counts; every thread owns a run of consecutive tokens
+  const int per = (V + 1023) / 1024;
+  const int lo = min(V, tid * per), hi = min(V, lo + per);
+  int a = 0, b = 0;
+  for (int v = lo; v < hi; ++v) { const int c = bins[v]; a += c; b += (c + EMB_CH - 1) / EMB_CH; }
+  int ia = a, ib = b;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int xa = __shfl_up(ia, o, 64), xb = __shfl_up(ib, o, 64);
+    if (lane >= o) { ia += xa; ib += xb; }
+  }
+  if (lane == 63) { wa[wave] = ia; wb[wave] = ib; }
+  __syncthreads();
+  if (wave == 0) {
+    int ta = lane < 16 ? wa[lane] : 0, tb = lane < 16 ? wb[lane] : 0;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      const int xa = __shfl_up(ta, o, 64), xb = __shfl_up(tb, o, 64);
+      if (lane >= o) { ta += xa; tb += xb; }
+    }
+    if (lane < 16) { wa[lane] = ta; wb[lane] = tb; }
+  }
+  __syncthreads();
+  int ra = (wave > 0 ? wa[wave - 1] : 0) + ia - a, rb = (wave > 0 ? wb[wave - 1] : 0) + ib - b;
+  for (int v = lo; v < hi; ++v) {
+    const int c = bins[v];
+    start[v] = ra; chunk0[v] = rb;
+    bins[v] = ra; // the bucket's cursor for the fill pass
+    ra += c; rb += (c + EMB_CH - 1) / EMB_CH;
+  }
+  if (tid == 1023) { start[V] = wa[15]; chunk0[V] = wb[15]; }
+  __syncthreads();
+  for (int i = tid; i < n; i += 1024) list[atomicAdd(&bins[tok[i]], 1)] = i;
+}
+
 // one workgroup per chunk; workgroups past the last chunk exit.  acc must be zero
 // on entry (rows of tokens that do not occur stay zero).
 __global__ __launch_bounds__(256) void emb_reduce_kernel(const int *__restrict__ start, const int *__restrict__ chunk0,
