@@ -122,7 +122,9 @@ typedef struct {
   int no_lstm_wgrad;              /* the LSTM's per-example weight gradient on the generic tiled contraction       */
   int no_rows_gemm;               /* the LSTM's input projection / input gradient on the generic tiled contraction */
   int no_single_bucket;           /* the embedding's counting sort as three launches, whatever the batch           */
-  int reserved[3];                /* zero                                                                          */
+  int small_gemm;                 /* two-layer networks: both batch-wide products with K split inside the workgroup
+                                     (measured slower than the split-K contraction; kept for comparison)           */
+  int reserved[2];                /* zero                                                                          */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

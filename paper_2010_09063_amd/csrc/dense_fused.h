@@ -272,43 +272,47 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
   float *bs = d2 + DENSE1_EX * 16;    // [16]: b2, -inf for the padding classes
   float *red = bs + 16;               // [16 waves][2]: partial ||delta1||^2, ||x||^2
   float *n2s = red + 32;              // [DENSE1_EX]: squared norm of the logit layer's gradient
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int e = lane >> 4, jj = lane & 15;
-  const int q = wave >> 2, hh = tid & 255;  // phases A and C: example of the group, first hidden unit of the thread
+  const int tid0 = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
+  const int q = wave >> 2; // phases A and C: the wave's example of the group
   float acc[NCP];
 #pragma unroll
   for (int j = 0; j < NCP; ++j) acc[j] = 0.f;
 
-  const float bv = a.b2[tid < N ? tid : 0];
+  const float bv = a.b2[tid0 < N ? tid0 : 0];
   {
     const int w_total = H * N;
     float wv[16];
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
-      const int i = tid + DENSE1_THREADS * n;
+      const int i = tid0 + DENSE1_THREADS * n;
       wv[n] = a.W2[i < w_total ? i : 0];
     }
-    for (int i = tid; i < NCP * ldw; i += DENSE1_THREADS) wt[i] = 0.f;
-    for (int i = tid; i < DENSE1_EX * ldh; i += DENSE1_THREADS) a1s[i] = 0.f;
+    for (int i = tid0; i < NCP * ldw; i += DENSE1_THREADS) wt[i] = 0.f;
+    for (int i = tid0; i < DENSE1_EX * ldh; i += DENSE1_THREADS) a1s[i] = 0.f;
     __syncthreads();
 #pragma unroll
     for (int n = 0; n < 16; ++n) {
-      const int i = tid + DENSE1_THREADS * n;
+      const int i = tid0 + DENSE1_THREADS * n;
       if (i < w_total) {
         const int k = (int)a.dN.div((unsigned)i), j = i - k * N;
         wt[j * ldw + k] = wv[n];
       }
     }
   }
-  if (tid < 16) bs[tid] = tid < N ? bv : -INFINITY;
+  if (tid0 < 16) bs[tid0] = tid0 < N ? bv : -INFINITY;
   float b1v[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b1v[i] = a.b1[hh + 256 * i < H ? hh + 256 * i : 0];
+  for (int i = 0; i < 4; ++i) b1v[i] = a.b1[(tid0 & 255) + 256 * i < H ? (tid0 & 255) + 256 * i : 0];
   const int kc = ((ldh >> 2) + 15) >> 4;
   const int k0 = 4 * wave * kc, k1 = min(ldh, k0 + 4 * kc);
 
   for (int grp = 0; grp < a.groups; ++grp) {
+    // indices re-derived from an opaque copy of the thread index per group: the compiler otherwise keeps the
+    // addresses of every phase alive across the loop and spills (and every barrier waits for scratch traffic)
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, e = lane >> 4, jj = lane & 15, hh = tid & 255;
     const int b0 = (blockIdx.x * a.groups + grp) * DENSE1_EX;
     const int bq = b0 + q;            // this thread's example in phases A and C (wave-uniform)
     const bool vq = bq < a.B;
@@ -439,6 +443,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
     }
     __syncthreads();
   }
+  const int tid = tid0;
   if (tid <= H) {
     float *pr = a.part2 + (long)blockIdx.x * dense1_part_stride(H, N) + (long)tid * N;
 #pragma unroll
@@ -461,4 +466,95 @@ static inline int launch_dense2_mid(hipStream_t st, Dense2Args a, int max_tiles)
   else if (ncp == 10) hipLaunchKernelGGL(dense2_mid_kernel<10>, grid, block, smem, st, a);
   else hipLaunchKernelGGL(dense2_mid_kernel<15>, grid, block, smem, st, a);
   return tiles;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The two batch-wide contractions of a two-layer network -- the hidden layer's forward product and its clipped sum
+// -- at sizes where the whole output is a few hundred 32 x 32 tiles (512 x 512 x 784: 0.4 GFLOP, 5 us of the chip).
+// Split-K partials and the launch that sums them cost more than the product itself there, so the K range is split
+// INSIDE the workgroup: its four waves take a quarter of K each for the same 32 x 32 tile, with operands loaded
+// straight from memory into the lanes of v_mfma_f32_16x16x4_f32 (no LDS staging, no barrier in the loop; an
+// operand element is base + row * row_stride + k * k_stride, so row-major and k-major operands are the same code),
+// and add their four partial tiles through LDS at the end.  The output is complete: bias and activation (forward) or
+// the single partial row the final write reads (clipped sum) are applied by the same kernel.
+struct SmallGemmArgs {
+  const float *A; long a_sr, a_sk; // element (m, k) = A[m * a_sr + k * a_sk]
+  const float *B; long b_sr, b_sk; // element (n, k) = B[n * b_sr + k * b_sk]
+  const float *bias;               // [N] or null
+  float *C; long c_sm, c_sn;       // C[m * c_sm + n * c_sn]
+  float *C_ones;                   // row M of the output when a_ones (the bias gradient), indexed by n
+  int M, N, K, act;
+  int a_ones;                      // 1: A has one more row, m = M, that is constant 1 (then the grid covers M + 1 rows)
+};
+
+__global__ __launch_bounds__(256) void dense_small_gemm_kernel(const SmallGemmArgs a) {
+  __shared__ float red[4][32 * 32 + 32];
+  const int tid = threadIdx.x, lane = tid & 63, i16 = lane & 15, kq = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+  const int Mtot = a.M + (a.a_ones ? 1 : 0);
+  // the wave's quarter of K, in whole k-steps of 4
+  const int ksteps = (a.K + 3) >> 2, per = (ksteps + 3) >> 2;
+  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
+  // per lane: two rows of A (blocks 0 / 1), two columns of B
+  long arow[2], brow[2];
+  bool aok[2], bok[2], aone[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = m0 + 16 * i + i16, n = n0 + 16 * i + i16;
+    aok[i] = m < a.M; aone[i] = a.a_ones && m == a.M;
+    bok[i] = n < a.N;
+    arow[i] = aok[i] ? (long)m * a.a_sr : 0;
+    brow[i] = bok[i] ? (long)n * a.b_sr : 0;
+  }
+  typedef float sg_f32x4 __attribute__((ext_vector_type(4)));
+  sg_f32x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = (sg_f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+  for (int ks = ks0; ks < ks1; ++ks) {
+    const int k = 4 * ks + kq;
+    const bool kok = k < a.K;
+    const long ka = kok ? (long)k * a.a_sk : 0, kb = kok ? (long)k * a.b_sk : 0;
+    float av[2], bv[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const float x = a.A[arow[i] + ka], w = a.B[brow[i] + kb]; // always valid addresses
+      av[i] = kok ? (aok[i] ? x : (aone[i] ? 1.f : 0.f)) : 0.f;
+      bv[i] = (kok && bok[i]) ? w : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+  }
+  // the four quarter sums meet in LDS: element (m, n) of the tile at red[wave][m * 33 + n]
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[wave][(16 * i + 4 * kq + r) * 33 + 16 * j + i16] = acc[i][j][r];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int e = tid + 256 * q, ml = e >> 5, nl = e & 31; // consecutive threads: consecutive n
+    const int m = m0 + ml, n = n0 + nl;
+    if (m < Mtot && n < a.N) {
+      const int o = ml * 33 + nl;
+      float v = (red[0][o] + red[1][o]) + (red[2][o] + red[3][o]);
+      if (a.bias) v += a.bias[n];
+      v = act_apply(a.act, v);
+      if (m < a.M) a.C[(long)m * a.c_sm + (long)n * a.c_sn] = v;
+      else a.C_ones[n] = v;
+    }
+  }
+}
+
+static inline void launch_dense_small_gemm(hipStream_t st, const SmallGemmArgs &a) {
+  const int Mtot = a.M + (a.a_ones ? 1 : 0);
+  dim3 grid((Mtot + 31) / 32, (a.N + 31) / 32), block(256);
+  hipLaunchKernelGGL(dense_small_gemm_kernel, grid, block, 0, st, a);
 }

@@ -338,6 +338,10 @@ def test_two_layer_models_of_other_widths():
         _check_all_regimes(m, x, y, theta, f"dense {d_in}->{H}->{k}/{act}/B{batch}")
     wl = W.make_workload("cfg2_mlp", batch=77, seed=2, bias_scale=0.2)
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/generic kernels", options=dict(no_fused_dense=1))
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/K split inside the workgroup", options=dict(small_gemm=1))
+    m = W.model(W.image_input(37), [W.dense(37, 45, act="tanh"), W.dense(45, 3)], 3)
+    x, y, theta = _case(m, 70, seed=5)
+    _check_all_regimes(m, x, y, theta, "dense 37->45->3/K split inside the workgroup", options=dict(small_gemm=1))
 
 
 def test_small_cnn_layer_by_layer_and_fused():
