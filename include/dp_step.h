@@ -124,7 +124,9 @@ typedef struct {
   int no_single_bucket;           /* the embedding's counting sort as three launches, whatever the batch           */
   int small_gemm;                 /* two-layer networks: both batch-wide products with K split inside the workgroup
                                      (measured slower than the split-K contraction; kept for comparison)           */
-  int reserved[2];                /* zero                                                                          */
+  int no_resident_weights;        /* minimal-filtering form, 32 -> (at most) 32 channels: the per-group kernel instead of
+                                     the persistent one that keeps the transformed weights in registers              */
+  int reserved[1];                /* zero                                                                          */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

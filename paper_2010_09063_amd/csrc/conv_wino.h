@@ -491,6 +491,210 @@ typedef WinoGeom<16, 8, 1, 24> WinoG16;
 typedef WinoGeom<8, 8, 2, 12> WinoG8;
 
 // ---------------------------------------------------------------------------------------------------------------
+// Variant for exactly 32 input channels and at most 32 output channels, where the channel loop is only four chunks
+// long and the kernels above spend more time on what surrounds it (index arithmetic, weight reloads with every
+// chunk, filling and draining the pipeline once per 32 tiles) than on the multiplies.  Here the wave's share of the
+// transformed weights -- 4 components x 32 channels x 32 output channels = 64 registers a lane, already laid out as
+// MFMA A operands -- stays in registers for the life of a PERSISTENT workgroup, which walks over a run of groups of
+// 32 tiles: the chunk pipeline (raw chunk n+1 from registers into LDS, barrier, loads of chunk n+3 into the registers
+// just freed, transform of chunk n+1 interleaved with the multiplies of chunk n) runs on across group borders, so
+// the first chunks of the next group are on their way while the current one is finished.  Loads are issued two
+// chunks before they are needed: with two waves per SIMD one chunk of multiplies is shorter than a trip to HBM.
+// The epilogue has an LDS area of its own and one barrier; the activation values backward-data needs are requested
+// before the last chunk's multiplies.
+// FAST selects what is fixed at compile time: 0 nothing (forward or backward-data, any pool, M <= 32, stores under
+// their bounds checks); 1 forward with the 2x2 max-pool, 2 backward-data through an activation, 3 forward without a
+// pool, all three for M = 32 exactly: every store is then unconditional, so the number of stores between a load and
+// its use is a constant and the wait for that load does not have to drain the stores as well.
+template <class G, int FAST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int groups_per_wg) {
+  constexpr int CC = WINO_CC, RS = G::RS, LDW = G::LDW, XSZ = CC * RS, NCH = 4, W = G::W;
+  static_assert(G::NIMG == 1 && G::REAL <= 256, "a group is a band of one image; one position per thread");
+  __shared__ __attribute__((aligned(16))) float smem[2 * XSZ + 8192]; // raw buffers [2][CC * RS]; epilogue [4][2][16][64]
+  float *Xr = smem, *Tl = smem + 2 * XSZ;
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int HW = a.H * W;
+  const int g_begin = blockIdx.x * groups_per_wg, g_end = min(n_groups, g_begin + groups_per_wg);
+  if (g_begin >= g_end) return;
+  const bool fwd = FAST == 0 ? a.bias != nullptr : FAST != 2;
+  const bool need_side = FAST == 0 ? (!fwd && a.act) : FAST == 2;
+  const int pool = FAST == 0 ? a.pool : (FAST == 1 ? 1 : 0);
+
+  // this lane's tile inside a group
+  const int tyl = li / G::TW, tx = li % G::TW;
+  const float *pat = Xr + lk * RS + 2 * tyl * LDW + 2 * tx;
+  const int r1 = wave == 0 ? 0 : (wave == 2 ? 2 : 1);
+  const int r2 = wave == 0 ? 2 : (wave == 1 ? 2 : (wave == 2 ? 1 : 3));
+  const float s2 = wave == 1 ? 1.f : -1.f;
+
+  // staging: thread tid owns position tid of the haloed band for the 8 channels of a chunk
+  const int s_rr = tid / (W + 2), s_col = tid % (W + 2);
+  const bool s_in = tid < G::REAL && (unsigned)(s_col - 1) < (unsigned)W;
+  const int s_off = 4 * ((s_rr - 1) * W + s_col - 1); // bytes from the band's first pixel row
+  const int xl = tid < G::REAL ? s_rr * LDW + s_col : -1;
+  const int per = a.H / G::ROWS; // bands per image
+  struct Grp { const float *xblk; int xg; bool ok; int img, row0; };
+  auto setup = [&](int g) {
+    Grp q;
+    q.img = g / per; q.row0 = (g - q.img * per) * G::ROWS;
+    const int ih = q.row0 + s_rr - 1;
+    q.ok = s_in && (unsigned)ih < (unsigned)a.H;
+    q.xg = q.ok ? s_off : 0;
+    q.xblk = a.x + (long)q.img * a.Cin * HW + q.row0 * W;
+    return q;
+  };
+
+  float xrA[CC], xrB[CC];
+  auto fetch_raw = [&](const Grp &q, int c0, float *dst) { // unconditional loads: positions without input read the band's first word
+    const float *xc0 = q.xblk + (long)c0 * HW;
+#pragma unroll
+    for (int c = 0; c < CC; ++c)
+      dst[c] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xc0 + (long)c * HW) + q.xg);
+  };
+  auto store_raw = [&](float *xbuf, bool ok, const float *src) {
+    if (xl >= 0) {
+#pragma unroll
+      for (int c = 0; c < CC; ++c) xbuf[xl + c * RS] = ok ? src[c] : 0.f;
+    }
+  };
+  auto transform = [&](const float *xbuf, float (*bv)[4]) {
+    const float *p = pat + (xbuf - Xr);
+#pragma unroll
+    for (int cp = 0; cp < CC / 2; ++cp) {
+      const float *q = p + 2 * cp * RS;
+      const float2 a0 = *reinterpret_cast<const float2 *>(q + r1 * LDW);
+      const float2 a1 = *reinterpret_cast<const float2 *>(q + r1 * LDW + 2);
+      const float2 b0 = *reinterpret_cast<const float2 *>(q + r2 * LDW);
+      const float2 b1 = *reinterpret_cast<const float2 *>(q + r2 * LDW + 2);
+      const float t0 = fmaf(s2, b0.x, a0.x), t1 = fmaf(s2, b0.y, a0.y), t2 = fmaf(s2, b1.x, a1.x), t3 = fmaf(s2, b1.y, a1.y);
+      bv[cp][0] = t0 - t2;
+      bv[cp][1] = t1 + t2;
+      bv[cp][2] = t2 - t1;
+      bv[cp][3] = t1 - t3;
+    }
+  };
+
+  Grp cur = setup(g_begin);
+  fetch_raw(cur, 0, xrA);
+  fetch_raw(cur, CC, xrB);
+  // the wave's weights: wr[jj][channel pair] = u[(4*wave + jj)*Cpad + 2*cp + lk][li]   (Cpad = 32, Mpad = 32)
+  float wr[4][NCH * CC / 2];
+  {
+    const float *ub = a.u + ((long)(4 * wave) * a.Cpad + lk) * a.Mpad + li;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+      for (int cp = 0; cp < NCH * CC / 2; ++cp) wr[jj][cp] = ub[((long)jj * a.Cpad + 2 * cp) * a.Mpad];
+  }
+  float bias_r[4];
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) bias_r[rr] = fwd ? a.bias[min(8 * wave + 4 * lk + rr, a.M - 1)] : 0.f;
+
+  store_raw(Xr, cur.ok, xrA);
+  __syncthreads();
+  fetch_raw(cur, 2 * CC, xrA);
+  float bA[CC / 2][4], bB[CC / 2][4];
+  transform(Xr, bA);
+
+  // At the top of a group: its chunk 0 is transformed (bA), chunk 1 sits in xrB, chunk 2 is on its way into xrA.
+  f32x16 acc[4];
+  for (int g = g_begin; g < g_end; ++g) {
+    const Grp nxt = setup(min(g + 1, g_end - 1)); // past the run's last group: re-read it (unused)
+    const int img = cur.img, ty = cur.row0 / 2 + tyl;
+    const long obase = ((long)img * a.M) * HW + (2 * ty) * W + 2 * tx;
+    float2 sd0[4], sd1[4];
+
+    auto load_side = [&]() {
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        const long o = obase + (long)min(8 * wave + 4 * lk + rr, a.M - 1) * HW;
+        sd0[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o);
+        sd1[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
+      }
+    };
+    // chunk KC of the group: the chunk after it goes from registers (src_regs) to LDS, the chunk three ahead (chunk
+    // c_next of group `from`) is requested into the same registers
+    auto chunk = [&](auto kc_, float *xbuf, bool ok, float *regs, const Grp &from, int c_next, float (*bcur)[4],
+                     float (*bnext)[4]) {
+      constexpr int KC = decltype(kc_)::value;
+      store_raw(xbuf, ok, regs);
+      __syncthreads(); // the next raw chunk is in place; every wave has finished reading the buffer written after this
+      fetch_raw(from, c_next, regs);
+      transform(xbuf, bnext);
+      if (KC == NCH - 1 && FAST == 2) load_side();
+#pragma unroll
+      for (int cp = 0; cp < CC / 2; ++cp)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          if (KC == 0 && cp == 0) {
+            const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[jj][KC * (CC / 2) + cp], bcur[cp][jj], z, 0, 0, 0);
+          } else {
+            acc[jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[jj][KC * (CC / 2) + cp], bcur[cp][jj], acc[jj], 0, 0, 0);
+          }
+        }
+    };
+    chunk(std::integral_constant<int, 0>{}, Xr + XSZ, cur.ok, xrB, cur, 3 * CC, bA, bB);
+    chunk(std::integral_constant<int, 1>{}, Xr, cur.ok, xrA, nxt, 0, bB, bA);
+    chunk(std::integral_constant<int, 2>{}, Xr + XSZ, cur.ok, xrB, nxt, CC, bA, bB);
+    chunk(std::integral_constant<int, 3>{}, Xr, nxt.ok, xrA, nxt, 2 * CC, bB, bA);
+
+    // ---- output transform: each wave folds its own row, the four rows meet in LDS (written here, last read four
+    // barriers ago), wave w finishes accumulator rows 4w .. 4w+3
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      Tl[((wave * 2 + 0) * 16 + r) * 64 + lane] = acc[0][r] + acc[1][r] + acc[2][r];
+      Tl[((wave * 2 + 1) * 16 + r) * 64 + lane] = acc[1][r] - acc[2][r] - acc[3][r];
+    }
+    if (FAST == 0 && need_side) load_side(); // (the general variant has no registers to hold them any earlier)
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int r = 4 * wave + rr;
+      const int m = 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+      if (FAST == 0 && m >= a.M) continue;
+      float T[4][2];
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
+      float2 y0, y1;
+      y0.x = T[0][0] + T[1][0] + T[2][0];
+      y0.y = T[0][1] + T[1][1] + T[2][1];
+      y1.x = T[1][0] - T[2][0] - T[3][0];
+      y1.y = T[1][1] - T[2][1] - T[3][1];
+      const long o = obase + (long)m * HW;
+      if (fwd) {
+        const float bv = bias_r[rr];
+        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
+        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
+        if (pool) {
+          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
+          if (pool == 1) {
+            float best = y0.x; int bi = 0;
+            if (y0.y > best) { best = y0.y; bi = 1; }
+            if (y1.x > best) { best = y1.x; bi = 2; }
+            if (y1.y > best) { best = y1.y; bi = 3; }
+            a.pool_out[po] = best;
+            a.pool_arg[po] = (uint8_t)bi;
+          } else {
+            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+          }
+        }
+      } else if (need_side) {
+        y0.x *= act_deriv_from_out(a.act, sd0[rr].x); y0.y *= act_deriv_from_out(a.act, sd0[rr].y);
+        y1.x *= act_deriv_from_out(a.act, sd1[rr].x); y1.y *= act_deriv_from_out(a.act, sd1[rr].y);
+      }
+      *reinterpret_cast<float2 *>(a.out + o) = y0;
+      *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+    }
+    cur = nxt;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
 // Weight gradients of a 3x3 / stride-1 / pad-1 layer in the minimal-filtering form with the roles exchanged,
 // F(3x3, 2x2): per tile the 3x3 block  G[ky][kx] = sum_{a,b} dy[a][b] xpatch[ky+a][kx+b]  is
 //   A^T [ (G' dy G'^T) (.) (B^T xpatch B) ] A    with the same B^T as above and

@@ -425,6 +425,26 @@ static void launch_conv_wino(const LN &Ln, const char *label, ConvWinoArgs a, in
   const int xi = need <= 6 ? 6 : (need <= 7 ? 7 : 9);
   const long tiles = (long)a.B * (a.H / 2) * (a.W / 2);
   dim3 grid((unsigned)((tiles + 31) / 32), a.Mpad / (32 * db)), block(256);
+  // 32 input and at most 32 output channels: persistent workgroups that keep the transformed weights in registers
+  if (db == 1 && a.Cin == 32 && a.Cpad == 32 && a.Mpad == 32 && !Ln.c->opt.no_resident_weights) {
+    // what the kernel fixes at compile time for 32 output channels (every store unconditional)
+    const int fast = a.M != 32 ? 0 : (a.bias != nullptr ? (a.pool == 1 ? 1 : (a.pool == 0 ? 3 : 0)) : (a.act != 0 ? 2 : 0));
+#define DP_WINOR_CASE(G_, cond_)                                                                  \
+  if (a.W == G_::W && (cond_)) {                                                                  \
+    const int n_groups = a.B * (a.H / G_::ROWS);                                                  \
+    const int per_wg = ceil_div(n_groups, 512); /* two workgroups per CU, all resident */         \
+    dim3 rgrid(ceil_div(n_groups, per_wg));                                                       \
+    Ln(label, rgrid, block, [&](hipStream_t st) {                                                 \
+      if (fast == 1) hipLaunchKernelGGL((conv_wino_res_kernel<G_, 1>), rgrid, block, 0, st, a, n_groups, per_wg);      \
+      else if (fast == 2) hipLaunchKernelGGL((conv_wino_res_kernel<G_, 2>), rgrid, block, 0, st, a, n_groups, per_wg); \
+      else if (fast == 3) hipLaunchKernelGGL((conv_wino_res_kernel<G_, 3>), rgrid, block, 0, st, a, n_groups, per_wg); \
+      else hipLaunchKernelGGL((conv_wino_res_kernel<G_, 0>), rgrid, block, 0, st, a, n_groups, per_wg);                \
+    });                                                                                           \
+    return;                                                                                       \
+  }
+    DP_WINOR_CASE(WinoG32, a.H % 4 == 0) DP_WINOR_CASE(WinoG16, a.H % 8 == 0)
+#undef DP_WINOR_CASE
+  }
   // 64 output channels per workgroup, whole chunks of input channels, one of the plane shapes the register-operand
   // kernel is built for
   if (db == 2 && a.Cin % WINO_CC == 0) {

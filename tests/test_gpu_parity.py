@@ -243,11 +243,34 @@ def test_minimal_filtering_route():
                        options=dict(minimal_filtering_all=1, no_pool_fusion=1))
     wl = W.make_workload("paper_cifar_cnn", batch=5, seed=6, bias_scale=0.2)
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "paper_cifar/minimal-filtering", options=opt)
+    # 32 -> 32 channels without the persistent kernel that keeps the transformed weights in registers
+    wl = W.make_workload("cfg4_cifar_cnn", batch=3, seed=4, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/minimal-filtering, per-group kernel",
+                       options=dict(minimal_filtering_all=1, no_resident_weights=1))
     # full batch with that route switched off: the direct kernels in the launch shapes of the benchmark batch
     wl = W.make_workload("cfg4_cifar_cnn", seed=0)
     m, x, y, theta = wl["model"], wl["x"], wl["y"], wl["params"]
     ref = O.dp_step(m, theta, x, y, wl["C"], 0.0, 0)
     check_step(m, theta, x, y, wl["C"], ref, "cfg4 full batch, direct kernels", options=dict(no_minimal_filtering=1))
+
+
+def test_resident_weight_minimal_filtering_kernel():
+    """The persistent F(2x2, 3x3) kernel for 32 input and at most 32 output channels (weights in registers, a run of
+    tile groups per workgroup): 32-wide planes with forward into 32 channels with the fused pool, forward into 20
+    channels on 16-wide planes, backward-data into 8 and into 32 channels (through tanh and ReLU); batches that give a
+    workgroup one group, two groups, and three with a shorter run for the last workgroup."""
+    m = W.model(W.image_input(8, 32, 32), [
+        W.conv2d(8, 32, 3, stride=1, pad=1, act="tanh"), W.conv2d(32, 32, 3, stride=1, pad=1, act="relu"),
+        W.maxpool2d(2, 2), W.conv2d(32, 20, 3, stride=1, pad=1, act="tanh"), W.avgpool2d(4, 4), W.dense(20 * 4 * 4, 3)], 3)
+    for batch in (2, 65, 130):
+        x, y, theta = _case(m, batch, seed=batch)
+        _check_all_regimes(m, x, y, theta, f"planes32 8->32->32->20/B{batch}", options=dict(minimal_filtering_all=1))
+    m = W.model(W.image_input(32, 16, 16), [
+        W.conv2d(32, 32, 3, stride=1, pad=1, act="relu"), W.conv2d(32, 32, 3, stride=1, pad=1, act="tanh"),
+        W.maxpool2d(2, 2), W.dense(32 * 8 * 8, 3)], 3)
+    for batch in (3, 514):
+        x, y, theta = _case(m, batch, seed=batch)
+        _check_all_regimes(m, x, y, theta, f"planes16 32->32->32/B{batch}", options=dict(minimal_filtering_all=1))
 
 
 def test_weight_gradients_in_minimal_filtering_form():
