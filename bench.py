@@ -81,11 +81,17 @@ def label_work(m, B, plan=None):
             elif r.get("norm") == "fused":  # hidden layer of the same model: its two batch-wide contractions remain
                 add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))
                 add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
+            elif r.get("fwd") == "head":  # logit layer of a deeper network: forward, backward-data and both dense norms in one launch
+                add("dense2_head", 2 * fl + 2.0 * B * (di + do), 4.0 * (3 * B * di + di * do + B * do))
+                add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
             else:
                 add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))
                 if li > 0:
                     add("dense_bwd_data", fl, 4.0 * (B * do + di * do + 2 * B * di))
-                add("dense_norm", 2.0 * B * (di + do), 4.0 * B * (di + do))
+                if r.get("norm") == "head":  # hidden layer of that head: its norm (one pass over its input) is taken by the same launch
+                    add("dense2_head", 2.0 * B * (di + do), 4.0 * B * di)
+                else:
+                    add("dense_norm", 2.0 * B * (di + do), 4.0 * B * (di + do))
                 add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
         elif k == "conv2d":
             C_, H_, W_ = cur[1], cur[2], cur[3]

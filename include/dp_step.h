@@ -117,7 +117,7 @@ typedef struct {
   int specialised_waves_all;      /* ... or the staging / multiplying wave split for every width                  */
   int conv_min_blocks;            /* grid the direct forward kernel narrows its tiles for (0: 512)                */
   int gemm_plain_tiles;           /* tile choice of the generic contraction without the padding-waste rule        */
-  int no_fused_dense;             /* one-dense-layer models on the generic kernels (four launches)                */
+  int no_fused_dense;             /* one- / two-dense-layer models and dense two-layer heads on the generic kernels */
   int no_fused_cnn;               /* the small MNIST-shaped CNN layer by layer instead of in one launch            */
   int no_lstm_wgrad;              /* the LSTM's per-example weight gradient on the generic tiled contraction       */
   int no_rows_gemm;               /* the LSTM's input projection / input gradient on the generic tiled contraction */

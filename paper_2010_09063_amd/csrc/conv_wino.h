@@ -529,34 +529,38 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
   const int r2 = wave == 0 ? 2 : (wave == 1 ? 2 : (wave == 2 ? 1 : 3));
   const float s2 = wave == 1 ? 1.f : -1.f;
 
-  // staging: thread tid owns position tid of the haloed band for the 8 channels of a chunk
+  // staging: thread tid owns position tid of the haloed band for the 8 channels of a chunk.  The loads are buffer
+  // loads: a resource descriptor per band (it starts one pixel row above the band, so lane offsets are never
+  // negative; only addresses of real pixels are ever formed from it), the channel in the scalar offset, and a lane
+  // offset beyond the descriptor's range for positions that hold no input -- those read as zero without touching
+  // memory, so nothing has to be masked on the way to LDS.
   const int s_rr = tid / (W + 2), s_col = tid % (W + 2);
   const bool s_in = tid < G::REAL && (unsigned)(s_col - 1) < (unsigned)W;
-  const int s_off = 4 * ((s_rr - 1) * W + s_col - 1); // bytes from the band's first pixel row
+  const unsigned s_off = 4u * (unsigned)(s_rr * W + (s_in ? s_col - 1 : 0)); // bytes from the descriptor's base
   const int xl = tid < G::REAL ? s_rr * LDW + s_col : -1;
   const int per = a.H / G::ROWS; // bands per image
-  struct Grp { const float *xblk; int xg; bool ok; int img, row0; };
+  constexpr unsigned OUTSIDE = 0x80000000u;
+  struct Grp { __amdgpu_buffer_rsrc_t rs; unsigned xg; int img, row0; };
   auto setup = [&](int g) {
     Grp q;
     q.img = g / per; q.row0 = (g - q.img * per) * G::ROWS;
     const int ih = q.row0 + s_rr - 1;
-    q.ok = s_in && (unsigned)ih < (unsigned)a.H;
-    q.xg = q.ok ? s_off : 0;
-    q.xblk = a.x + (long)q.img * a.Cin * HW + q.row0 * W;
+    q.xg = (s_in && (unsigned)ih < (unsigned)a.H) ? s_off : OUTSIDE;
+    const float *base = a.x + (long)q.img * a.Cin * HW + (q.row0 - 1) * W;
+    q.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0, 4 * (a.Cin * HW + W), 0x00020000);
     return q;
   };
 
   float xrA[CC], xrB[CC];
-  auto fetch_raw = [&](const Grp &q, int c0, float *dst) { // unconditional loads: positions without input read the band's first word
-    const float *xc0 = q.xblk + (long)c0 * HW;
+  auto fetch_raw = [&](const Grp &q, int c0, float *dst) {
 #pragma unroll
     for (int c = 0; c < CC; ++c)
-      dst[c] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xc0 + (long)c * HW) + q.xg);
+      dst[c] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(q.rs, q.xg, 4 * (c0 + c) * HW, 0));
   };
-  auto store_raw = [&](float *xbuf, bool ok, const float *src) {
+  auto store_raw = [&](float *xbuf, const float *src) {
     if (xl >= 0) {
 #pragma unroll
-      for (int c = 0; c < CC; ++c) xbuf[xl + c * RS] = ok ? src[c] : 0.f;
+      for (int c = 0; c < CC; ++c) xbuf[xl + c * RS] = src[c];
     }
   };
   auto transform = [&](const float *xbuf, float (*bv)[4]) {
@@ -592,7 +596,7 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
 #pragma unroll
   for (int rr = 0; rr < 4; ++rr) bias_r[rr] = fwd ? a.bias[min(8 * wave + 4 * lk + rr, a.M - 1)] : 0.f;
 
-  store_raw(Xr, cur.ok, xrA);
+  store_raw(Xr, xrA);
   __syncthreads();
   fetch_raw(cur, 2 * CC, xrA);
   float bA[CC / 2][4], bB[CC / 2][4];
@@ -616,10 +620,10 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
     };
     // chunk KC of the group: the chunk after it goes from registers (src_regs) to LDS, the chunk three ahead (chunk
     // c_next of group `from`) is requested into the same registers
-    auto chunk = [&](auto kc_, float *xbuf, bool ok, float *regs, const Grp &from, int c_next, float (*bcur)[4],
+    auto chunk = [&](auto kc_, float *xbuf, float *regs, const Grp &from, int c_next, float (*bcur)[4],
                      float (*bnext)[4]) {
       constexpr int KC = decltype(kc_)::value;
-      store_raw(xbuf, ok, regs);
+      store_raw(xbuf, regs);
       __syncthreads(); // the next raw chunk is in place; every wave has finished reading the buffer written after this
       fetch_raw(from, c_next, regs);
       transform(xbuf, bnext);
@@ -636,10 +640,10 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
           }
         }
     };
-    chunk(std::integral_constant<int, 0>{}, Xr + XSZ, cur.ok, xrB, cur, 3 * CC, bA, bB);
-    chunk(std::integral_constant<int, 1>{}, Xr, cur.ok, xrA, nxt, 0, bB, bA);
-    chunk(std::integral_constant<int, 2>{}, Xr + XSZ, cur.ok, xrB, nxt, CC, bA, bB);
-    chunk(std::integral_constant<int, 3>{}, Xr, nxt.ok, xrA, nxt, 2 * CC, bB, bA);
+    chunk(std::integral_constant<int, 0>{}, Xr + XSZ, xrB, cur, 3 * CC, bA, bB);
+    chunk(std::integral_constant<int, 1>{}, Xr, xrA, nxt, 0, bB, bA);
+    chunk(std::integral_constant<int, 2>{}, Xr + XSZ, xrB, nxt, CC, bA, bB);
+    chunk(std::integral_constant<int, 3>{}, Xr, xrA, nxt, 2 * CC, bB, bA);
 
     // ---- output transform: each wave folds its own row, the four rows meet in LDS (written here, last read four
     // barriers ago), wave w finishes accumulator rows 4w .. 4w+3

@@ -258,6 +258,14 @@ struct Dense2Args {
   int groups;
   float C; int priv;
   FastDiv dN;
+  // head = 1: the two layers close a deeper network.  The clip factor is not known yet (the layers below add to the
+  // norm), so the kernel stops after phase C: it leaves both layers' squared norms in their slots, delta1 unscaled in
+  // sdelta1, the hidden activations in a1_out (when they arrived as partials) and delta2 in delta2_out for the
+  // clipped sums that follow once the clip factors exist.
+  int head;
+  float *slot1, *slot2; // [B] squared norms of the hidden / logit layer's gradient (may be null)
+  float *a1_out;        // [B][H] or null
+  float *delta2_out;    // [B][N]
 };
 
 template <int NCP>
@@ -416,8 +424,21 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
       const float sd1 = (red[w0 * 2] + red[w0 * 2 + 2]) + (red[w0 * 2 + 4] + red[w0 * 2 + 6]);
       const float sxx = (red[w0 * 2 + 1] + red[w0 * 2 + 3]) + (red[w0 * 2 + 5] + red[w0 * 2 + 7]);
       const float n = sqrtf((sxx + 1.f) * sd1 + n2s[q]);
-      sc = a.priv ? fminf(1.f, a.C / n) : 1.f; // n == 0: C/0 = +inf -> 1
-      if (vq && hh == 0) {
+      sc = (a.priv && !a.head) ? fminf(1.f, a.C / n) : 1.f; // n == 0: C/0 = +inf -> 1
+      if (a.head) {
+        if (vq && hh == 0) {
+          if (a.slot1) a.slot1[bq] = (sxx + 1.f) * sd1;
+          if (a.slot2) a.slot2[bq] = n2s[q];
+        }
+        if (vq && hh < N) a.delta2_out[(long)bq * N + hh] = d2[q * 16 + hh];
+        if (vq && a.a1_out) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int h = hh + 256 * i;
+            if (h < H) a.a1_out[(long)bq * H + h] = a1v[i];
+          }
+        }
+      } else if (vq && hh == 0) {
         if (a.norms) a.norms[bq] = n;
         if (a.s) a.s[bq] = sc;
       }
@@ -430,6 +451,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
       }
     }
     __syncthreads(); // every thread has read delta2 before it is scaled in place
+    if (a.head) continue; // (uniform; the barrier above also separates this group's LDS reads from the next group's writes)
     if (hh < 16) d2[q * 16 + hh] *= sc;
     __syncthreads();
     // ---- D. the logit layer's clipped partial: thread = row tid of [H + 1][N]
@@ -444,7 +466,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
     __syncthreads();
   }
   const int tid = tid0;
-  if (tid <= H) {
+  if (!a.head && tid <= H) {
     float *pr = a.part2 + (long)blockIdx.x * dense1_part_stride(H, N) + (long)tid * N;
 #pragma unroll
     for (int j = 0; j < NCP; ++j)

@@ -201,6 +201,7 @@ struct dp_ctx {
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   bool fusedcnn = false; float *cnn_part = nullptr; // the small MNIST-shaped CNN in one launch (cnn_small_fused_kernel)
   bool fused2 = false; // two dense layers: everything between the hidden layer's forward product and the clipped sums in dense2_mid_kernel
+  bool head2 = false;  // a deeper network that ends in two dense layers: the same kernel up to both layers' norms and delta1
   // profiling
   bool prof = false;
   std::vector<const char *> labels; // string literals
@@ -686,6 +687,11 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
   }
   c->fused2 = c->L.size() == 2 && c->L[0].d.kind == DP_DENSE && c->L[1].d.kind == DP_DENSE &&
               dense1_fits(c->L[1].d.in_features, c->L[1].d.out_features) && !c->opt.no_fused_dense;
+  {
+    const size_t n = c->L.size();
+    c->head2 = n >= 3 && c->L[n - 2].d.kind == DP_DENSE && c->L[n - 1].d.kind == DP_DENSE &&
+               dense1_fits(c->L[n - 1].d.in_features, c->L[n - 1].d.out_features) && !c->fusedcnn && !c->opt.no_fused_dense;
+  }
   for (size_t i = 0; i < c->L.size(); ++i) {
     c->L[i].lab.reserve(sizeof(kLayerLabels) / sizeof(kLayerLabels[0]));
     for (const char *nm : kLayerLabels) c->L[i].lab.push_back(std::string(nm) + "#" + std::to_string(i));
@@ -986,10 +992,10 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     const float *in = (const float *)x;
     int fused_pool = -1;
     const bool no_pool_fusion = c->opt.no_pool_fusion != 0;
-    const bool f2 = c->fused2;
+    const bool f2 = c->fused2, h2 = c->head2;
     int mid_ns = 0, mid_tiles = 0;
     for (int i = 0; i < nL; ++i) {
-      if (f2 && i == 1) break; // the logits are computed by the kernel that follows the hidden layer
+      if ((f2 && i == 1) || (h2 && i == nL - 1)) break; // the logits are computed by the kernel that follows the hidden layer
       Layer &l = c->L[i];
       const float *W = params + l.p_off;
       switch (l.d.kind) {
@@ -1023,7 +1029,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           vec_dispatch(OpRowMajor<true>::can_vec(in, l.d.in_features, 0, l.d.in_features) &&
                               OpKMajor<true, false>::can_vec(W, l.d.out_features, 0, l.d.out_features), run);
           if (i == nL - 1 && fused_head) { head_ns = ns; break; } // bias + loss gradient + norm in one launch below
-          if (f2) { mid_ns = ns; break; }                         // bias + activation where the partials are consumed
+          if (f2 || (h2 && i == nL - 2)) { mid_ns = ns; break; }  // bias + activation where the partials are consumed
           const long total = (long)B * l.out_size;
           dim3 grid = grid1d(total, 256), block(256);
           const float *bias = W + (long)l.d.in_features * l.d.out_features;
@@ -1181,8 +1187,28 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         mid_tiles = launch_dense2_mid(st, a, std::min(DENSE1_MAX_TILES, l1.max_split));
       });
     }
+    if (h2) {
+      // a deeper network that ends in two dense layers: logits, loss gradient, both layers' norms and the hidden layer's
+      // backprop, per example, in one launch (the clip factors need the other layers' norms and come later)
+      Layer &l0 = c->L[nL - 2], &l1 = c->L[nL - 1];
+      Dense2Args a{};
+      a.x = nL > 2 ? (const float *)c->L[nL - 3].a : (const float *)x;
+      a.hpart = mid_ns > 0 ? l0.fpart : l0.a; a.hstride = (long)c->maxB * l0.out_size; a.ns = mid_ns;
+      a.b1 = params + l0.p_off + (long)l0.d.in_features * l0.d.out_features;
+      a.W2 = params + l1.p_off; a.b2 = a.W2 + (long)l1.d.in_features * l1.d.out_features; a.y = (const int *)y;
+      a.sdelta1 = l0.g; a.part2 = nullptr; a.norms = nullptr; a.s = nullptr;
+      a.B = B; a.d_in = l0.d.in_features; a.H = l1.d.in_features; a.N = l1.d.out_features; a.act = l0.d.act;
+      a.C = C; a.priv = priv ? 1 : 0;
+      a.head = 1; a.a1_out = mid_ns > 0 ? l0.a : nullptr; a.delta2_out = l1.g;
+      if (priv) {
+        a.slot2 = c->slots + (long)slot_next * slot_stride;
+        a.slot1 = c->slots + (long)(slot_next + 1) * slot_stride;
+        slot_next += 2;
+      }
+      Ln("dense2_head", dim3(1), dim3(256), [&](hipStream_t st) { (void)launch_dense2_mid(st, a, DENSE1_MAX_TILES); });
+    }
     // ------------------------------------------------------------ loss gradient
-    if (f2) {
+    if (f2 || h2) {
     } else if (fused_head) {
       // the last dense layer's bias, the loss gradient and that layer's norm (the first slot of the backward
       // pass) in one launch, one wave per example
@@ -1209,7 +1235,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       });
     }
     // ------------------------------------------------------------ backward: data gradients and per-example norms
-    for (int i = f2 ? -1 : nL - 1; i >= 0; --i) {
+    for (int i = f2 ? -1 : (h2 ? nL - 2 : nL - 1); i >= 0; --i) {
       Layer &l = c->L[i];
       const float *W = params + l.p_off;
       const float *lin = i > 0 ? c->L[i - 1].a : (const float *)x;
@@ -1217,7 +1243,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       const int prev_act = (prev && (prev->d.kind == DP_DENSE || prev->d.kind == DP_CONV2D)) ? prev->d.act : DP_ACT_NONE;
       switch (l.d.kind) {
       case DP_DENSE: {
-        if (priv && !(i == nL - 1 && fused_head)) {
+        if (priv && !(i == nL - 1 && fused_head) && !(h2 && i == nL - 2)) {
           dim3 grid = grid1d((long)B * 64, 256), block(256);
           float *slot = c->slots + (long)slot_next * slot_stride;
           slot_next += 1;
@@ -1803,6 +1829,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
       fwd = c->fused1 ? "fused" : "generic"; bwd = i > 0 ? "generic" : "-";
       norm = c->fused1 ? "fused" : "identity"; sum = c->fused1 ? "fused" : "generic";
       if (c->fused2) { norm = "fused"; if (i == 1) fwd = bwd = sum = "fused"; }
+      if (c->head2 && i + 2 >= c->L.size()) { norm = "head"; if (i + 1 == c->L.size()) fwd = bwd = "head"; }
       if (c->fusedcnn) fwd = bwd = norm = sum = "fused-net";
       break;
     case DP_CONV2D:

@@ -331,6 +331,12 @@ def test_remaining_route_switches():
         _check_all_regimes(m, x, y, theta, f"tiny_conv3/min_blocks={mb}", options=dict(conv_min_blocks=mb, no_minimal_filtering=1))
     wl = W.make_workload("cfg1_logistic", batch=100, seed=2, bias_scale=0.2)
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg1/generic kernels", options=dict(no_fused_dense=1))
+    # deeper networks that end in two dense layers take one launch for logits, loss gradient, both dense norms and the
+    # hidden layer's backprop; the same switch keeps them on the generic kernels
+    for name, batch in (("cfg4_cifar_cnn", 5), ("cfg6_embedding", 45), ("paper_lstm", 7)):
+        wl = W.make_workload(name, batch=batch, seed=3, bias_scale=0.2)
+        _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/dense head on the generic kernels",
+                           options=dict(no_fused_dense=1))
     # the embedding's counting sort as three launches with per-workgroup LDS histograms (the default for batches of
     # more than 2^15 steps; smaller ones take the single-workgroup kernel)
     for name, batch in (("cfg6_embedding", 45), ("cfg5_lstm", 6)):
