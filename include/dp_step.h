@@ -126,7 +126,8 @@ typedef struct {
                                      (measured slower than the split-K contraction; kept for comparison)           */
   int no_resident_weights;        /* minimal-filtering form, 32 -> (at most) 32 channels: the per-group kernel instead of
                                      the persistent one that keeps the transformed weights in registers              */
-  int reserved[1];                /* zero                                                                          */
+  int no_side_stream;             /* the embedding's counting sort in line on the caller's stream instead of beside the
+                                     forward pass on a stream of the library's own                                 */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

@@ -201,6 +201,9 @@ struct dp_ctx {
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   bool fusedcnn = false; float *cnn_part = nullptr; // the small MNIST-shaped CNN in one launch (cnn_small_fused_kernel)
   bool fused2 = false; // two dense layers: everything between the hidden layer's forward product and the clipped sums in dense2_mid_kernel
+  // The embedding layer's counting sort of the batch's tokens depends on the inputs alone: it runs on a stream of the
+  // library's own (fork / join by events) beside the forward pass.
+  hipStream_t side = nullptr; hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool head2 = false;  // a deeper network that ends in two dense layers: the same kernel up to both layers' norms and delta1
   // profiling
   bool prof = false;
@@ -687,6 +690,14 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
   }
   c->fused2 = c->L.size() == 2 && c->L[0].d.kind == DP_DENSE && c->L[1].d.kind == DP_DENSE &&
               dense1_fits(c->L[1].d.in_features, c->L[1].d.out_features) && !c->opt.no_fused_dense;
+  if (rc == DP_OK && !c->L.empty() && c->L[0].d.kind == DP_EMBEDDING && !c->opt.no_side_stream) {
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      if (c->side) { (void)hipStreamDestroy(c->side); c->side = nullptr; } // (the step then keeps everything on one stream)
+    }
+  }
   {
     const size_t n = c->L.size();
     c->head2 = n >= 3 && c->L[n - 2].d.kind == DP_DENSE && c->L[n - 1].d.kind == DP_DENSE &&
@@ -833,6 +844,9 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
 extern "C" void dp_step_free(dp_ctx *c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
+  if (c->side) { (void)hipStreamSynchronize(c->side); (void)hipStreamDestroy(c->side); }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   for (void *p : c->allocs) (void)hipFree(p);
   for (hipEvent_t e : c->pool) (void)hipEventDestroy(e);
   delete c;
@@ -936,6 +950,52 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     FinalizeSeg &sg = fa.seg[fa.nseg++];
     sg.p_off = 0; sg.n = l.p_count; sg.part = l.part; sg.stride = dense1_part_stride(a.d_in, a.N); sg.nsplit = tiles;
   } else if (B > 0) {
+    // The embedding layer's token lists for its clipped sum (a counting sort of the batch by token id) and its zeroed
+    // partial: inputs of emb_reduce_kernel that depend on x alone.
+    auto emb_prepare = [&](Layer &l, int i, auto &&launch) {
+      const long rows = (long)B * l.outC;
+      const int V = l.d.vocab;
+      (void)i;
+        {
+          dim3 grid = grid1d(l.p_count + V + 1, 256), block(256);
+          launch(LL("fill_zero"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count, (float *)l.e_count, (long)(V + 1));
+          });
+        }
+        if (V <= EMB_LDS_V && rows <= EMB_ONE_MAX_ROWS && !c->opt.no_single_bucket) {
+          launch(LL("emb_bucket"), dim3(1), dim3(1024), [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_bucket_one_kernel, dim3(1), dim3(1024), sizeof(int) * V, st, (const int *)x, l.e_start,
+                               l.e_chunk0, l.e_list, (int)rows, V);
+          });
+        } else {
+          dim3 grid = grid1d(rows, 1024), block(1024);
+          const size_t smem = V <= EMB_LDS_V ? sizeof(int) * V : 0;
+          launch(LL("emb_bucket"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_count_kernel, grid, block, smem, st, (const int *)x, l.e_count, rows, V);
+          });
+          launch(LL("emb_bucket"), dim3(1), dim3(1024), [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, st, (const int *)l.e_count, l.e_start,
+                               l.e_chunk0, l.e_cursor, V);
+          });
+          launch(LL("emb_bucket"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_fill_kernel, grid, block, smem, st, (const int *)x, (const int *)l.e_start,
+                               l.e_cursor, l.e_list, rows, V);
+          });
+        }
+    };
+    bool emb_early = false;
+    // The token lists are built on the library's second stream from the start of the step (measured: forked here the
+    // embedding network's step is 12 us shorter; forked at the start of the backward pass it is not, and the LSTM
+    // network gains the same 15 us either way -- the sort's launches slow the launches they run beside, and each event
+    // wait costs the waiting stream about 6 us).
+    if (c->side && !c->prof && c->L[0].d.kind == DP_EMBEDDING && c->L[0].p_count > 0) {
+      auto on_side = [&](const char *, dim3, dim3, auto &&f) { f(c->side); };
+      (void)hipEventRecord(c->ev_fork, c->stream);
+      (void)hipStreamWaitEvent(c->side, c->ev_fork, 0);
+      emb_prepare(c->L[0], 0, on_side);
+      (void)hipEventRecord(c->ev_join, c->side);
+      emb_early = true;
+    }
     // ------------------------------------------------------------ re-laid weights of the direct convolutions
     {
       ConvLayoutArgs la{};
@@ -1112,11 +1172,19 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       } break;
       case DP_EMBEDDING: {
         const long n = (long)B * l.out_size;
-        dim3 grid = grid1d(n, 256), block(256);
-        Ln(LL("emb_gather"), grid, block, [&](hipStream_t st) {
-          hipLaunchKernelGGL(emb_gather_kernel, grid, block, 0, st, (const int *)x, W, l.a, (long)B * l.outC,
-                             l.d.embed_dim);
-        });
+        if ((l.d.embed_dim & 3) == 0 && aligned16(W) && aligned16(l.a)) {
+          dim3 grid = grid1d(n / 4, 256), block(256);
+          Ln(LL("emb_gather"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_gather4_kernel, grid, block, 0, st, (const int *)x, (const float4 *)W, (float4 *)l.a,
+                               (long)B * l.outC, l.d.embed_dim / 4);
+          });
+        } else {
+          dim3 grid = grid1d(n, 256), block(256);
+          Ln(LL("emb_gather"), grid, block, [&](hipStream_t st) {
+            hipLaunchKernelGGL(emb_gather_kernel, grid, block, 0, st, (const int *)x, W, l.a, (long)B * l.outC,
+                               l.d.embed_dim);
+          });
+        }
       } break;
       case DP_SEQ_MEAN: {
         dim3 grid(B), block(256);
@@ -1626,32 +1694,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       case DP_EMBEDDING: {
         const long rows = (long)B * l.outC;
         const int V = l.d.vocab;
-        {
-          dim3 grid = grid1d(l.p_count + V + 1, 256), block(256);
-          Ln(LL("fill_zero"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(fill_zero_kernel, grid, block, 0, st, l.part, l.p_count, (float *)l.e_count, (long)(V + 1));
-          });
-        }
-        if (V <= EMB_LDS_V && rows <= EMB_ONE_MAX_ROWS && !c->opt.no_single_bucket) {
-          Ln(LL("emb_bucket"), dim3(1), dim3(1024), [&](hipStream_t st) {
-            hipLaunchKernelGGL(emb_bucket_one_kernel, dim3(1), dim3(1024), sizeof(int) * V, st, (const int *)x, l.e_start,
-                               l.e_chunk0, l.e_list, (int)rows, V);
-          });
-        } else {
-          dim3 grid = grid1d(rows, 1024), block(1024);
-          const size_t smem = V <= EMB_LDS_V ? sizeof(int) * V : 0;
-          Ln(LL("emb_bucket"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(emb_count_kernel, grid, block, smem, st, (const int *)x, l.e_count, rows, V);
-          });
-          Ln(LL("emb_bucket"), dim3(1), dim3(1024), [&](hipStream_t st) {
-            hipLaunchKernelGGL(emb_scan_kernel, dim3(1), dim3(1024), 0, st, (const int *)l.e_count, l.e_start,
-                               l.e_chunk0, l.e_cursor, V);
-          });
-          Ln(LL("emb_bucket"), grid, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(emb_fill_kernel, grid, block, smem, st, (const int *)x, (const int *)l.e_start,
-                               l.e_cursor, l.e_list, rows, V);
-          });
-        }
+        if (emb_early) (void)hipStreamWaitEvent(c->stream, c->ev_join, 0); // the token lists were built beside the forward pass
+        else emb_prepare(l, i, Ln);
         {
           // every token has at most ceil(count/EMB_CH) chunks: rows/EMB_CH + V bounds their number
           dim3 grid((unsigned)(rows / EMB_CH + V + 1)), block(256);

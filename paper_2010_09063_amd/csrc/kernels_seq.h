@@ -31,6 +31,17 @@ __global__ void emb_gather_kernel(const int *__restrict__ tok, const float *__re
   xseq[i] = table[(long)tok[r] * D + e];
 }
 
+// The same lookup for rows that are whole 16-byte groups (D a multiple of 4, both pointers 16-byte aligned): a thread
+// copies four coordinates, a row's groups lie in consecutive threads.
+__global__ void emb_gather4_kernel(const int *__restrict__ tok, const float4 *__restrict__ table,
+                                   float4 *__restrict__ xseq, long rows, int D4) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * D4) return;
+  const long r = i / D4;
+  const int e = (int)(i - r * D4);
+  xseq[i] = table[(long)tok[r] * D4 + e];
+}
+
 __device__ __forceinline__ float sigmoidf_(float v) { return fast_sigmoid(v); }
 
 // Mean over the T step vectors of a sequence (embedding network, Appendix B): out[b, e] = (1/T) sum_t in[b, t, e].

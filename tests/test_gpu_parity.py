@@ -343,6 +343,9 @@ def test_remaining_route_switches():
         wl = W.make_workload(name, batch=batch, seed=2, bias_scale=0.2)
         _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/three-launch buckets",
                            options=dict(no_single_bucket=1))
+        # the same lists built in line on the caller's stream (by default they are built beside the forward pass)
+        _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/buckets on the caller's stream",
+                           options=dict(no_side_stream=1))
 
 
 def test_one_layer_models_of_other_widths():
