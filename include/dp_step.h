@@ -128,6 +128,7 @@ typedef struct {
                                      the persistent one that keeps the transformed weights in registers              */
   int no_side_stream;             /* the embedding's counting sort in line on the caller's stream instead of beside the
                                      forward pass on a stream of the library's own                                 */
+  int no_first_layer_kernel;      /* an RGB first layer's forward pass on the generic direct kernel                  */
 } dp_plan_options;
 
 /* dp_step_init with route switches; options == NULL is dp_step_init. */

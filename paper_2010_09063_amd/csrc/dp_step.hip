@@ -20,6 +20,7 @@
 #include "ceilings.h"
 #include "cnn_fused.h"
 #include "conv_wino.h"
+#include "conv_first.h"
 #include "dense_fused.h"
 #include "kernels_misc.h"
 #include "kernels_seq.h"
@@ -142,6 +143,7 @@ struct Layer {
   ConvGeom geom;
   // stride-1 3x3 convolutions: LDS-staged direct kernels (otherwise the generic contraction)
   bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
+  bool first_fwd = false; // the network's first layer, at most 3 input channels: forward by conv_first_kernel
   bool wg_ws = false; // weight gradient with specialised staging / multiplying waves (two LDS buffers)
   bool gram = false;  // per-example norm from the P x P Gram matrices (small planes)
   float *cols = nullptr; // strided convolutions, backward-data: [maxB][C*KH*KW][OH*OW] products W^T Delta
@@ -635,6 +637,9 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
     if (l.d.kind == DP_CONV2D) {
       l.geom = make_geom(l);
       plan_direct_conv(l, max_batch, c->opt);
+      const ConvGeom &g = l.geom;
+      l.first_fwd = c->L.empty() && !l.wino_f && !c->opt.generic_conv && !c->opt.no_first_layer_kernel &&
+                    conv_first_fits(g.C, g.H, g.W, g.D, g.KH, g.KW, g.S, g.PAD) && (long)max_batch * g.D * g.H * g.W < (1l << 31);
     }
     off += l.p_count;
     total_slots += l.max_slots;
@@ -1012,7 +1017,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         Layer &l = c->L[i];
         if (l.d.kind != DP_CONV2D || !(l.dir_fwd || l.dir_bwd)) continue;
         // only the layouts a direct kernel of this step reads (the minimal-filtering kernels have their own)
-        float *need_f = (l.dir_fwd && !l.u_f) ? l.wt_f : nullptr;
+        float *need_f = (l.dir_fwd && !l.u_f && !l.first_fwd) ? l.wt_f : nullptr;
         float *need_b = (l.dir_bwd && !l.u_b && i > 0) ? l.wt_b : nullptr;
         if (!need_f && !need_b) continue;
         const ConvGeom &g = l.geom;
@@ -1126,6 +1131,21 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             fused_pool = i + 1;
           }
           launch_conv_wino(Ln, LL("conv_fwd"), a, l.wino_f);
+          break;
+        }
+        if (l.first_fwd) {
+          // an RGB first layer: persistent workgroups, weights in registers, the next tile's loads under the current stores
+          const ConvGeom &g = l.geom;
+          ConvFirstArgs a{};
+          a.x = in; a.w = W; a.bias = W + (long)g.D * g.CKK; a.out = l.a;
+          a.B = B; a.Cin = g.C; a.H = g.H; a.M = g.D; a.act = l.d.act;
+          a.n_tiles = B * (g.H / CF_TR);
+          a.tiles_per_wg = ceil_div(a.n_tiles, 1024);
+          dim3 grid(ceil_div(a.n_tiles, a.tiles_per_wg)), block(256);
+          Ln(LL("conv_fwd"), grid, block, [&](hipStream_t st) {
+            if (g.D == 32) hipLaunchKernelGGL(conv_first_kernel<true>, grid, block, 0, st, a);
+            else hipLaunchKernelGGL(conv_first_kernel<false>, grid, block, 0, st, a);
+          });
           break;
         }
         if (l.dir_fwd) {
@@ -1877,7 +1897,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
       if (c->fusedcnn) fwd = bwd = norm = sum = "fused-net";
       break;
     case DP_CONV2D:
-      fwd = l.u_f ? (l.wino_f == 2 ? "mf64" : "mf32") : (l.dir_fwd ? "direct" : "generic");
+      fwd = l.u_f ? (l.wino_f == 2 ? "mf64" : "mf32") : (l.first_fwd ? "first" : (l.dir_fwd ? "direct" : "generic"));
       bwd = i == 0 ? "-" : (l.u_b ? (l.wino_b == 2 ? "mf64" : "mf32") : (l.dir_bwd ? "direct" : (l.cols ? "columns" : "generic")));
       norm = l.gram ? "gram" : ((l.wino_norm && l.gst) ? "mf+store" : (l.dir_wg ? (l.gst ? "direct+store" : (l.wg_ws ? "ws" : "direct"))
                                                                                 : (l.gst ? "generic+store" : "generic")));

@@ -254,6 +254,20 @@ def test_minimal_filtering_route():
     check_step(m, theta, x, y, wl["C"], ref, "cfg4 full batch, direct kernels", options=dict(no_minimal_filtering=1))
 
 
+def test_first_layer_forward_kernel():
+    """The persistent forward kernel of an RGB first layer (3x3, pad 1, 32-wide planes): 3 and 1 input channels, 32 and
+    fewer output channels, planes of 8, 16 and 32 rows, every activation, batches that give a workgroup one tile and
+    several with a shorter run for the last workgroup; then the same layer on the generic direct kernel."""
+    for cin, d, h, act, batch in ((3, 32, 32, "relu", 3), (3, 20, 16, "tanh", 5), (1, 7, 8, "relu", 9), (2, 32, 32, "tanh", 300)):
+        m = W.model(W.image_input(cin, h, 32), [
+            W.conv2d(cin, d, 3, stride=1, pad=1, act=act), W.avgpool2d(8, 8), W.dense(d * (h // 8) * 4, 3)], 3)
+        x, y, theta = _case(m, batch, seed=cin + d)
+        _check_all_regimes(m, x, y, theta, f"first layer {cin}->{d}/H{h}/{act}/B{batch}")
+    wl = W.make_workload("cfg4_cifar_cnn", batch=4, seed=5, bias_scale=0.2)
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg4/first layer on the direct kernel",
+                       options=dict(no_first_layer_kernel=1))
+
+
 def test_resident_weight_minimal_filtering_kernel():
     """The persistent F(2x2, 3x3) kernel for 32 input and at most 32 output channels (weights in registers, a run of
     tile groups per workgroup): 32-wide planes with forward into 32 channels with the fused pool, forward into 20
