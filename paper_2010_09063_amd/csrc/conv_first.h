@@ -139,3 +139,160 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const ConvFirstArgs a) 
     buf ^= 1;
   }
 }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Per-example weight gradient of the same layer (Section 1, item 2a): G_b[d][(c, tap)] = sum over pixels p of
+// Delta_b[d][p] x_b[c][p + tap], its squared norm (item 2b: the layer's slot of the example) and, optionally, the
+// gradient itself for the weighted sum that forms the clipped sum (item 3), plus the bias gradient sum_p Delta_b[d][p].
+// 32 x 27 outputs and 1024 pixels per example: the work is reading Delta (B x 32 x H x 32 floats) once.
+// MFMA roles: M = output channel d, N = (channel, tap) index k, K = pixel.  The Delta operand never passes through
+// LDS: lane (d, half) loads 16 bytes = four consecutive pixels of row d of the plane straight from memory (lanes of a
+// d beyond D are zeroed) and feeds them to four k-steps -- a k-step pairs pixel 8 s + e of the lower
+// half-wave with pixel 8 s + 4 + e of the upper, and the x operand, read from the example's zero-haloed image in LDS
+// at [c][row + kh][column + kw], follows the same pairing.  A workgroup owns whole examples, one after the other
+// (persistent); wave w takes the pixel rows w, w + 4, ... and keeps Delta rows four row-steps ahead in registers (a
+// trip to memory is longer than the sixteen multiplies of a row), the next example's image travels meanwhile.  Per
+// example the four waves' accumulators meet in LDS, wave 0 squares, stores and reduces.  The stored row has the
+// accumulator order [register][lane] of conv_s1_wgrad_kernel's flattened variant, so either kernel can write it.
+#define CFW_LDW 40                          // LDS row length: interior at columns 4 .. 35 (16-byte aligned), halo at 3 and 36
+#define CFW_PLANE ((CF_W + 2) * CFW_LDW)    // 34 rows
+#define CFW_XI 3                            // float4 items per thread: 3 channels x 32 rows x 8 groups / 256
+
+struct ConvFirstWgArgs {
+  const float *x;      // [B][Cin][H][32]
+  const float *dy;     // [B][D][H][32]
+  float *slots;        // squared norms: slots[b]
+  float *gstore;       // [B][gstride] or null
+  long gstride, gbias_off;
+  int B, Cin, H, D;
+  int ex_per_wg;
+};
+
+static inline bool conv_first_wgrad_fits(int Cin, int H, int W, int D, int KH, int KW, int S, int PAD) {
+  return conv_first_fits(Cin, H, W, D, KH, KW, S, PAD) && H % 16 == 0 && H <= 32;
+}
+
+// FULL: D = 32 (no lane of the Delta operand is masked)
+template <bool FULL>
+__global__ __launch_bounds__(256) void conv_first_wgrad_kernel(const ConvFirstWgArgs a) {
+  __shared__ __attribute__((aligned(16))) float Xl[2][3 * CFW_PLANE];
+  __shared__ float xs[3][16][64];
+  __shared__ float bs[4][32];
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int H = a.H, HW = H * CF_W, Cin = a.Cin, D = a.D, K = Cin * 9;
+  const int b_begin = blockIdx.x * a.ex_per_wg, b_end = min(a.B, b_begin + a.ex_per_wg);
+  if (b_begin >= b_end) return;
+  const int RPW = H / 4; // pixel rows per wave and example: a multiple of 4
+
+  for (int i = tid; i < 2 * 3 * CFW_PLANE; i += 256) (&Xl[0][0])[i] = 0.f; // halos stay zero: only interiors are written
+
+  // x operand: byte offset of (c, kh, kw) of this lane's k in the image, plus the upper half-wave's four pixels
+  int kbase;
+  {
+    const int k = min(li, K - 1), c = k / 9, tap = k - 9 * c, kh = tap / 3, kw = tap - 3 * kh;
+    kbase = 4 * (c * CFW_PLANE + kh * CFW_LDW + kw + 3 + 4 * lk); // pixel column 0 with kw = 0 is LDS column 3 (the halo)
+  }
+  // Delta operand: lane byte offset in the example's Delta block (a lane of a d beyond D reads row 0 and is zeroed);
+  // every load below is (wave-uniform pointer) + (unsigned lane offset), so its address costs no vector instruction
+  const bool d_ok = li < D;
+  const unsigned d_lane = 4u * (unsigned)((d_ok ? li : 0) * HW + 4 * lk);
+  // x staging: item (c, row, group of four columns)
+  unsigned xs_off[CFW_XI];
+  int xs_lds[CFW_XI];
+#pragma unroll
+  for (int q = 0; q < CFW_XI; ++q) {
+    const int it = tid + 256 * q, c = it / (H * 8), rem = it - c * (H * 8), row = rem >> 3, g = rem & 7;
+    const bool ok = c < Cin;
+    xs_off[q] = ok ? 4u * (unsigned)(c * HW + row * CF_W + 4 * g) : 0u;
+    xs_lds[q] = ok ? c * CFW_PLANE + (row + 1) * CFW_LDW + 4 + 4 * g : -1;
+  }
+  float4 xv[CFW_XI];
+  auto fetch_x = [&](int b) {
+    const char *xb = reinterpret_cast<const char *>(a.x + (long)b * Cin * HW);
+#pragma unroll
+    for (int q = 0; q < CFW_XI; ++q) xv[q] = *reinterpret_cast<const float4 *>(xb + xs_off[q]);
+  };
+  // Delta rows in flight: ring of four row-steps, four float4 each (pixels 8 s + 4 lk .. + 3 of the row)
+  float4 dr[4][4];
+  auto fetch_d = [&](int b, int row, float4 (&dst)[4]) {
+    const char *db = reinterpret_cast<const char *>(a.dy + (long)b * D * HW + row * CF_W);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const float4 v = *reinterpret_cast<const float4 *>(db + 32 * s + d_lane);
+      dst[s] = FULL ? v : make_float4(d_ok ? v.x : 0.f, d_ok ? v.y : 0.f, d_ok ? v.z : 0.f, d_ok ? v.w : 0.f);
+    }
+  };
+  // row-step t of the run: example b_begin + t / RPW, pixel row wave + 4 (t % RPW); past the run: the last one again
+  const int n_steps = (b_end - b_begin) * RPW;
+  auto fetch_step = [&](int t, float4 (&dst)[4]) {
+    const int tt = min(t, n_steps - 1), e = tt / RPW, j = tt - e * RPW;
+    fetch_d(b_begin + e, wave + 4 * j, dst);
+  };
+
+  fetch_x(b_begin);
+  fetch_step(0, dr[0]); fetch_step(1, dr[1]); fetch_step(2, dr[2]); fetch_step(3, dr[3]);
+  __syncthreads(); // the zeros are in place
+  int buf = 0, t = 0;
+  for (int b = b_begin; b < b_end; ++b) {
+#pragma unroll
+    for (int q = 0; q < CFW_XI; ++q)
+      if (xs_lds[q] >= 0) *reinterpret_cast<float4 *>(&Xl[buf][xs_lds[q]]) = xv[q];
+    __syncthreads(); // the image is staged (the other buffer was last read before the previous example's second barrier)
+    fetch_x(min(b + 1, b_end - 1));
+    cf_f32x16 acc;
+    float bsum = 0.f;
+    const char *xb = reinterpret_cast<const char *>(&Xl[buf][0]) + kbase;
+    for (int j0 = 0; j0 < RPW; j0 += 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const char *xrow = xb + 4 * (wave + 4 * (j0 + u)) * CFW_LDW;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const float dv[4] = {dr[u][s].x, dr[u][s].y, dr[u][s].z, dr[u][s].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float bv = *reinterpret_cast<const float *>(xrow + 4 * (8 * s + e));
+            if (j0 == 0 && u == 0 && s == 0 && e == 0) {
+              const cf_f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+              acc = __builtin_amdgcn_mfma_f32_32x32x2f32(dv[e], bv, z, 0, 0, 0);
+            } else {
+              acc = __builtin_amdgcn_mfma_f32_32x32x2f32(dv[e], bv, acc, 0, 0, 0);
+            }
+            bsum += dv[e];
+          }
+        }
+        fetch_step(t + 4, dr[u]);
+        ++t;
+      }
+    }
+    // ---- the example is complete: accumulators of waves 1 .. 3 and the bias sums meet in LDS
+    bsum += __shfl_xor(bsum, 32, 64);
+    if (lk == 0) bs[wave][li] = bsum;
+    if (wave > 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) xs[wave - 1][r][lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+      float *gb = a.gstore ? a.gstore + (long)b * a.gstride : nullptr;
+      float part = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[r] + ((xs[0][r][lane] + xs[1][r][lane]) + xs[2][r][lane]);
+        v = li < K ? v : 0.f; // lanes past the last (channel, tap) pair multiplied a duplicate of it
+        part = fmaf(v, v, part);
+        if (gb) gb[r * 64 + lane] = v;
+      }
+      if (lane < 32) {
+        const float bd = lane < D ? (bs[0][lane] + bs[1][lane]) + (bs[2][lane] + bs[3][lane]) : 0.f;
+        part = fmaf(bd, bd, part);
+        if (gb && lane < D) gb[a.gbias_off + lane] = bd;
+      }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+      if (lane == 0) a.slots[b] = part;
+    }
+    buf ^= 1;
+  }
+}

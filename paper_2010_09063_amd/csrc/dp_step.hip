@@ -144,6 +144,7 @@ struct Layer {
   // stride-1 3x3 convolutions: LDS-staged direct kernels (otherwise the generic contraction)
   bool dir_fwd = false, dir_bwd = false, dir_wg = false, wg_flat = false;
   bool first_fwd = false; // the network's first layer, at most 3 input channels: forward by conv_first_kernel
+  bool first_wg = false;  // ... and its per-example weight gradient (norm pass) by conv_first_wgrad_kernel
   bool wg_ws = false; // weight gradient with specialised staging / multiplying waves (two LDS buffers)
   bool gram = false;  // per-example norm from the P x P Gram matrices (small planes)
   float *cols = nullptr; // strided convolutions, backward-data: [maxB][C*KH*KW][OH*OW] products W^T Delta
@@ -640,6 +641,9 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
       const ConvGeom &g = l.geom;
       l.first_fwd = c->L.empty() && !l.wino_f && !c->opt.generic_conv && !c->opt.no_first_layer_kernel &&
                     conv_first_fits(g.C, g.H, g.W, g.D, g.KH, g.KW, g.S, g.PAD) && (long)max_batch * g.D * g.H * g.W < (1l << 31);
+      // (the stored row keeps the accumulator order of the flattened direct kernel, which stays the fallback)
+      l.first_wg = c->L.empty() && l.dir_wg && l.wg_flat && !c->opt.generic_conv && !c->opt.no_first_layer_kernel &&
+                   conv_first_wgrad_fits(g.C, g.H, g.W, g.D, g.KH, g.KW, g.S, g.PAD);
     }
     off += l.p_count;
     total_slots += l.max_slots;
@@ -1385,6 +1389,18 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
             if (g.W == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<32, 1, 1, true>), grid, block, 0, st, a);
             else if (g.D == 32) hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 1, true>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((conv_wino_wgrad_unit_kernel<16, 2, 2, true>), grid, block, 0, st, a);
+          });
+        } else if (priv && l.first_wg && aligned16(lin) && aligned16(l.g)) {
+          ConvFirstWgArgs a{};
+          a.x = lin; a.dy = l.g; a.slots = c->slots + (long)slot_next * slot_stride;
+          a.gstore = l.gst; a.gstride = l.gorder.n_total; a.gbias_off = l.gorder.n_w;
+          a.B = B; a.Cin = g.C; a.H = g.H; a.D = g.D;
+          a.ex_per_wg = ceil_div(B, 512); // two workgroups per CU (one example per workgroup measured 56 us against 45)
+          slot_next += 1;
+          dim3 grid(ceil_div(B, a.ex_per_wg)), block(256);
+          Ln(LL("conv_wgrad_norm"), grid, block, [&](hipStream_t st) {
+            if (g.D == 32) hipLaunchKernelGGL(conv_first_wgrad_kernel<true>, grid, block, 0, st, a);
+            else hipLaunchKernelGGL(conv_first_wgrad_kernel<false>, grid, block, 0, st, a);
           });
         } else if (priv && l.dir_wg && aligned16(lin)) {
           // one round of resident workgroups, each walking through its run of examples: the next

@@ -255,10 +255,12 @@ def test_minimal_filtering_route():
 
 
 def test_first_layer_forward_kernel():
-    """The persistent forward kernel of an RGB first layer (3x3, pad 1, 32-wide planes): 3 and 1 input channels, 32 and
-    fewer output channels, planes of 8, 16 and 32 rows, every activation, batches that give a workgroup one tile and
-    several with a shorter run for the last workgroup; then the same layer on the generic direct kernel."""
-    for cin, d, h, act, batch in ((3, 32, 32, "relu", 3), (3, 20, 16, "tanh", 5), (1, 7, 8, "relu", 9), (2, 32, 32, "tanh", 300)):
+    """The persistent forward and per-example weight-gradient kernels of an RGB first layer (3x3, pad 1, 32-wide planes):
+    3, 2 and 1 input channels, 32 and fewer output channels, planes of 8 (forward only), 16 and 32 rows, both
+    activations, batches that give a workgroup one tile / example and several with a shorter run for the last
+    workgroup; then the same layer on the generic direct kernels."""
+    for cin, d, h, act, batch in ((3, 32, 32, "relu", 3), (3, 20, 16, "tanh", 5), (1, 7, 8, "relu", 9), (2, 32, 32, "tanh", 300),
+                                  (3, 32, 16, "relu", 1100)):
         m = W.model(W.image_input(cin, h, 32), [
             W.conv2d(cin, d, 3, stride=1, pad=1, act=act), W.avgpool2d(8, 8), W.dense(d * (h // 8) * 4, 3)], 3)
         x, y, theta = _case(m, batch, seed=cin + d)
