@@ -367,21 +367,23 @@ void conv_wino_reg_kernel(const ConvWinoArgs a) {
   const float s2 = wave == 1 ? 1.f : -1.f;
 
   // staging: thread tid owns position tid of the region (image, row, column of the haloed plane) for all 8 channels
-  // of a chunk: one lane offset into x (the channel moves the uniform pointer) and one LDS word (the channel is an
-  // immediate).  Positions that hold no input read word 0 and are zeroed.
+  // of a chunk.  Buffer loads: one resource descriptor for the workgroup's images (it starts one pixel row above the
+  // region, so lane offsets are never negative; only addresses of real pixels are formed from it), the channel in the
+  // scalar offset, and a lane offset beyond the descriptor's range for positions that hold no input -- those read as
+  // zero without touching memory, so nothing is masked on the way to LDS.
   static_assert(G::REAL <= 256, "one position per thread");
   unsigned xg;
   int xl;
-  bool xok;
   {
     const int im = tid / G::REAL_IMG, rem = tid % G::REAL_IMG;
     const int rr = rem / (G::W + 2), col = rem % (G::W + 2);
     const int ih = row0 + rr - 1, iw = col - 1;
-    xok = tid < G::REAL && (img0 + im) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)G::W;
-    xg = xok ? 4u * (unsigned)(im * a.Cin * HW + ih * G::W + iw) : 0u;
+    const bool xok = tid < G::REAL && (img0 + im) < a.B && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)G::W;
+    xg = xok ? 4u * (unsigned)(im * a.Cin * HW + rr * G::W + iw) : 0x80000000u;
     xl = tid < G::REAL ? im * G::IMGPL + rr * LDW + col : -1;
   }
-  const float *xblk = a.x + (long)img0 * a.Cin * HW;
+  const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<float *>(a.x + (long)img0 * a.Cin * HW + (row0 - 1) * G::W), 0, 4 * (G::NIMG * a.Cin * HW + G::W), 0x00020000);
 
   const unsigned wlane = 4u * (unsigned)(lk * a.Mpad + li);
   const float *ubase = a.u + ((long)(4 * wave) * a.Cpad) * a.Mpad + m0;
@@ -401,15 +403,15 @@ void conv_wino_reg_kernel(const ConvWinoArgs a) {
   float xr[CC];
   float wr[4][CC / 2][DB];
   auto fetch_raw = [&](int c0) {
-    const float *xc0 = xblk + (long)min(c0, a.Cin - CC) * HW; // (past the last chunk: re-reads it, unused)
+    const int cc0 = min(c0, a.Cin - CC); // (past the last chunk: re-reads it, unused)
 #pragma unroll
     for (int c = 0; c < CC; ++c)
-      xr[c] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(xc0 + (long)c * HW) + xg);
+      xr[c] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(xrs, xg, 4 * (cc0 + c) * HW, 0));
   };
   auto store_raw = [&](float *xbuf) {
     if (xl >= 0) {
 #pragma unroll
-      for (int c = 0; c < CC; ++c) xbuf[xl + c * RS] = xok ? xr[c] : 0.f;
+      for (int c = 0; c < CC; ++c) xbuf[xl + c * RS] = xr[c];
     }
   };
   // B operands of one chunk from a raw buffer: bv[cp][jj] = component (wave, jj) of channel 2*cp + lk
