@@ -53,9 +53,9 @@ struct ConvLayoutArgs {
   int n;
   struct { long w_off; float *wt_f, *wt_b; int D, C, Dp, Cp; } l[CONV_LAYOUT_MAX];
 };
-__global__ void conv_weight_layout_kernel(const float *__restrict__ params, const ConvLayoutArgs a) {
+__device__ __forceinline__ void conv_weight_layout_body(const float *__restrict__ params, const ConvLayoutArgs &a, int layer) {
   constexpr int KK = 9;
-  const auto &L = a.l[blockIdx.y];
+  const auto &L = a.l[layer];
   const int total = L.D * L.C * KK;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
     const int d = i / (L.C * KK), r = i - d * L.C * KK;
@@ -64,6 +64,9 @@ __global__ void conv_weight_layout_kernel(const float *__restrict__ params, cons
     if (L.wt_f) L.wt_f[((long)c * KK + tap) * L.Dp + d] = v; // (null: that correlation runs on another kernel)
     if (L.wt_b) L.wt_b[((long)d * KK + (KK - 1 - tap)) * L.Cp + c] = v;
   }
+}
+__global__ void conv_weight_layout_kernel(const float *__restrict__ params, const ConvLayoutArgs a) {
+  conv_weight_layout_body(params, a, blockIdx.y);
 }
 
 #define CONV_XPLANE_MAX 448 // staged floats per channel: a thread stages at most CC*448/256 elements per chunk

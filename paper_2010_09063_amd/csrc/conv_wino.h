@@ -54,8 +54,8 @@ struct WinoLayoutArgs {
   int n;
   struct { long w_off; float *uf, *ub; int D, C, Cfp, Dfp, Dbp, Cbp; } l[16];
 };
-__global__ void wino_weight_kernel(const float *__restrict__ params, const WinoLayoutArgs a) {
-  const auto &L = a.l[blockIdx.y];
+DEVI void wino_weight_body(const float *__restrict__ params, const WinoLayoutArgs &a, int layer) {
+  const auto &L = a.l[layer];
   const int total = L.D * L.C;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
     const int d = i / L.C, c = i - d * L.C;
@@ -89,6 +89,14 @@ __global__ void wino_weight_kernel(const float *__restrict__ params, const WinoL
       }
     }
   }
+}
+__global__ void wino_weight_kernel(const float *__restrict__ params, const WinoLayoutArgs a) {
+  wino_weight_body(params, a, blockIdx.y);
+}
+// Both weight preparations of a step in one launch: blockIdx.y walks the direct kernels' layouts, then the transforms.
+__global__ void conv_weights_kernel(const float *__restrict__ params, const ConvLayoutArgs ca, const WinoLayoutArgs wa) {
+  if ((int)blockIdx.y < ca.n) conv_weight_layout_body(params, ca, blockIdx.y);
+  else wino_weight_body(params, wa, blockIdx.y - ca.n);
 }
 
 // Output stage shared by the forward / backward-data kernels.  Row w of  M A:  t0 = m0 + m1 + m2,  t1 = m1 - m2 - m3

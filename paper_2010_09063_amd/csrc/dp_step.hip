@@ -1005,55 +1005,43 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       (void)hipEventRecord(c->ev_join, c->side);
       emb_early = true;
     }
-    // ------------------------------------------------------------ re-laid weights of the direct convolutions
+    // ------------------------------------------------------------ re-laid weights of the direct convolutions and
+    // transformed weights of the minimal-filtering kernels: one launch for both (two where a table overflows)
     {
       ConvLayoutArgs la{};
-      int biggest = 0;
+      WinoLayoutArgs wa{};
+      int big_l = 0, big_w = 0;
       auto flush = [&]() {
-        if (la.n == 0) return;
-        dim3 grid((unsigned)std::min(64, ceil_div(biggest, 256)), la.n), block(256);
+        if (la.n == 0 && wa.n == 0) return;
+        const int biggest = std::max(big_l, big_w);
+        dim3 grid((unsigned)std::min(64, ceil_div(biggest, 256)), la.n + wa.n), block(256);
         Ln("conv_weight_layout", grid, block, [&](hipStream_t st) {
-          hipLaunchKernelGGL(conv_weight_layout_kernel, grid, block, 0, st, params, la);
+          hipLaunchKernelGGL(conv_weights_kernel, grid, block, 0, st, params, la, wa);
         });
-        la.n = 0; biggest = 0;
+        la.n = 0; wa.n = 0; big_l = 0; big_w = 0;
       };
       for (int i = 0; i < nL; ++i) {
         Layer &l = c->L[i];
-        if (l.d.kind != DP_CONV2D || !(l.dir_fwd || l.dir_bwd)) continue;
-        // only the layouts a direct kernel of this step reads (the minimal-filtering kernels have their own)
-        float *need_f = (l.dir_fwd && !l.u_f && !l.first_fwd) ? l.wt_f : nullptr;
-        float *need_b = (l.dir_bwd && !l.u_b && i > 0) ? l.wt_b : nullptr;
-        if (!need_f && !need_b) continue;
+        if (l.d.kind != DP_CONV2D) continue;
         const ConvGeom &g = l.geom;
-        auto &e = la.l[la.n++];
-        e.w_off = l.p_off; e.wt_f = need_f; e.wt_b = need_b; e.D = g.D; e.C = g.C;
-        e.Dp = (g.D + 3) & ~3; e.Cp = (g.C + 3) & ~3;
-        biggest = std::max(biggest, g.D * g.CKK);
-        if (la.n == CONV_LAYOUT_MAX) flush();
-      }
-      flush();
-    }
-    // ------------------------------------------------------------ transformed weights of the minimal-filtering kernels
-    {
-      WinoLayoutArgs la{};
-      int biggest = 0;
-      auto flush = [&]() {
-        if (la.n == 0) return;
-        dim3 grid((unsigned)std::min(64, ceil_div(biggest, 256)), la.n), block(256);
-        Ln("conv_weight_layout", grid, block, [&](hipStream_t st) {
-          hipLaunchKernelGGL(wino_weight_kernel, grid, block, 0, st, params, la);
-        });
-        la.n = 0; biggest = 0;
-      };
-      for (int i = 0; i < nL; ++i) {
-        Layer &l = c->L[i];
-        if (l.d.kind != DP_CONV2D || !(l.u_f || l.u_b)) continue;
-        const ConvGeom &g = l.geom;
-        auto &e = la.l[la.n++];
-        e.w_off = l.p_off; e.uf = l.u_f; e.ub = l.u_b; e.D = g.D; e.C = g.C;
-        e.Cfp = l.uf_cpad; e.Dfp = l.uf_mpad; e.Dbp = l.ub_cpad; e.Cbp = l.ub_mpad;
-        biggest = std::max(biggest, g.D * g.C);
-        if (la.n == 16) flush();
+        if (l.dir_fwd || l.dir_bwd) {
+          // only the layouts a direct kernel of this step reads (the minimal-filtering kernels have their own)
+          float *need_f = (l.dir_fwd && !l.u_f && !l.first_fwd) ? l.wt_f : nullptr;
+          float *need_b = (l.dir_bwd && !l.u_b && i > 0) ? l.wt_b : nullptr;
+          if (need_f || need_b) {
+            auto &e = la.l[la.n++];
+            e.w_off = l.p_off; e.wt_f = need_f; e.wt_b = need_b; e.D = g.D; e.C = g.C;
+            e.Dp = (g.D + 3) & ~3; e.Cp = (g.C + 3) & ~3;
+            big_l = std::max(big_l, g.D * g.CKK);
+          }
+        }
+        if (l.u_f || l.u_b) {
+          auto &e = wa.l[wa.n++];
+          e.w_off = l.p_off; e.uf = l.u_f; e.ub = l.u_b; e.D = g.D; e.C = g.C;
+          e.Cfp = l.uf_cpad; e.Dfp = l.uf_mpad; e.Dbp = l.ub_cpad; e.Cbp = l.ub_mpad;
+          big_w = std::max(big_w, g.D * g.C);
+        }
+        if (la.n == CONV_LAYOUT_MAX || wa.n == 16) flush();
       }
       flush();
     }
