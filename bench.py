@@ -115,7 +115,7 @@ def label_work(m, B, plan=None):
         elif k == "maxpool2d":
             n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]
             add("maxpool_fwd", 0.0, 4.0 * n_in + 5.0 * n_out)
-            add("maxpool_bwd", 0.0, 8.0 * n_in + 5.0 * n_out)
+            add("maxpool_bwd", 0.0, 4.0 * n_in + 9.0 * n_out)  # writes the plane; reads pooled gradient, pooled plane, arg-max byte
         elif k == "avgpool2d":
             n_in, n_out = B * cur[1] * cur[2] * cur[3], B * o[1] * o[2] * o[3]
             add("avgpool_fwd", 1.0 * n_in, 4.0 * (n_in + n_out))

@@ -136,7 +136,8 @@ typedef struct {
   double *d_a, *d_b; /* two gradient buffers of the largest size  */
   long max_act;
   long ties;      /* number of pool windows whose maximum is not unique */
-  double margin;  /* smallest (maximum - runner-up) over the pool windows of the current example */
+  double margin;  /* smallest distance of the current example from a decision an fp32 forward pass may take the other
+                   * way: (maximum - runner-up) over its max-pool windows, |z| over its non-zero ReLU pre-activations */
 } scratch;
 
 static scratch *scratch_new(const or_model *m) {
@@ -202,6 +203,7 @@ static double forward(const or_model *m, const double *theta, const void *x, int
         for (int k = 0; k < L->d_in; ++k) acc += in[k] * W[(long)k * L->d_out + j];
         s->z[l][j] = acc;
         a[j] = act_f(L->act, acc);
+        if (L->act == OR_ACT_RELU && acc != 0 && fabs(acc) < s->margin) s->margin = fabs(acc);
       }
     } break;
     case OR_CONV2D: {
@@ -221,6 +223,7 @@ static double forward(const or_model *m, const double *theta, const void *x, int
             long oi = ((long)d * o.h + oh) * o.w + ow;
             s->z[l][oi] = acc;
             a[oi] = act_f(L->act, acc);
+            if (L->act == OR_ACT_RELU && acc != 0 && fabs(acc) < s->margin) s->margin = fabs(acc);
           }
     } break;
     case OR_MAXPOOL2D: {
@@ -489,8 +492,12 @@ static int pool_in_index(const or_layer *L, shp in, shp o, long oi, int kh, int 
 
 /* Lists up to cap entries (layer, out_idx, in_idx, gap): element in_idx of the window of output out_idx of
  * max-pool layer `layer` lies 0 < gap <= tau below that window's maximum.  Exact ties are not listed: they
- * follow the first-maximum rule on every implementation.  Returns the number of such elements (which may
- * exceed cap; only the first cap are written). */
+ * follow the first-maximum rule on every implementation.
+ * The ReLU has the same kind of decision: its subgradient is 1 for z > 0 and 0 otherwise, and an fp32 forward
+ * pass may put a pre-activation with |z| below its rounding error on the other side of zero (the forward value
+ * changes by nothing that matters, the backward factor by 1).  Such units of dense / convolution layers are
+ * listed as (layer, unit index, -1, |z|) for 0 < |z| <= tau; z = 0 exactly is on the 0 side everywhere.
+ * Returns the number of entries (which may exceed cap; only the first cap are written). */
 long oracle_pool_near_ties(const or_model *m, const double *theta, const void *x, int y, double tau, long cap,
                            int *layer, int *out_idx, int *in_idx, double *gap) {
   scratch *s = scratch_new(m);
@@ -498,6 +505,16 @@ long oracle_pool_near_ties(const or_model *m, const double *theta, const void *x
   long n = 0;
   for (int l = 0; l < m->n_layers; ++l) {
     const or_layer *L = &m->layers[l];
+    if ((L->kind == OR_DENSE || L->kind == OR_CONV2D) && L->act == OR_ACT_RELU) {
+      for (long oi = 0; oi < shp_size(s->shape[l]); ++oi) {
+        double z = fabs(s->z[l][oi]);
+        if (z > 0 && z <= tau) {
+          if (n < cap) { layer[n] = l; out_idx[n] = (int)oi; in_idx[n] = -1; gap[n] = z; }
+          ++n;
+        }
+      }
+      continue;
+    }
     if (L->kind != OR_MAXPOOL2D) continue;
     shp o = s->shape[l], in;
     const double *av;
@@ -520,15 +537,28 @@ long oracle_pool_near_ties(const or_model *m, const double *theta, const void *x
   return n;
 }
 
-/* Gradient of one example's loss with n_route pool windows routed by hand: the gradient of output out_idx[r]
- * of max-pool layer layer[r] goes to input element in_idx[r], which must lie inside that window.  Returns the
- * loss, or NaN if a route names no max-pool layer, an output out of range or an element outside the window. */
+/* Gradient of one example's loss with n_route decisions taken by hand: the gradient of output out_idx[r] of
+ * max-pool layer layer[r] goes to input element in_idx[r], which must lie inside that window; or, with
+ * in_idx[r] = -1, unit out_idx[r] of the ReLU dense / convolution layer layer[r] takes the subgradient of the
+ * other side of zero.  Returns the loss, or NaN if a route names a layer of another kind, an output out of range
+ * or an element outside the window. */
 double oracle_example_grad_routed(const or_model *m, const double *theta, const void *x, int y, long n_route,
                                   const int *layer, const int *out_idx, const int *in_idx, double *g) {
   scratch *s = scratch_new(m);
   double loss = forward(m, theta, x, y, s);
   for (long r = 0; r < n_route; ++r) {
     int l = layer[r], ok = 0;
+    if (in_idx[r] == -1) {
+      if (l >= 0 && l < m->n_layers && (m->layers[l].kind == OR_DENSE || m->layers[l].kind == OR_CONV2D) &&
+          m->layers[l].act == OR_ACT_RELU && out_idx[r] >= 0 && out_idx[r] < shp_size(s->shape[l])) {
+        /* the backward pass reads the pre-activation only through the activation's derivative */
+        double z = s->z[l][out_idx[r]];
+        s->z[l][out_idx[r]] = z > 0 ? -1.0 : 1.0;
+        continue;
+      }
+      scratch_free(s);
+      return NAN;
+    }
     if (l >= 0 && l < m->n_layers && m->layers[l].kind == OR_MAXPOOL2D && out_idx[r] >= 0 &&
         out_idx[r] < shp_size(s->shape[l])) {
       const or_layer *L = &m->layers[l];
@@ -582,7 +612,8 @@ void oracle_noise(uint64_t seed, long n, double *z) {
 /* params fp32[P]; x fp32[B, in_c*in_h*in_w] or int32[B, seq_len]; y int32[B] (all host).
  * out fp32[P] = sum_i clip(g_i) + sigma*C*z.  Optional outputs (may be NULL):
  *   norms[B]  unclipped ||g_i||;  clipped_sum[P] the fp64 sum before noise;  ties;
- *   pool_margin[B]  smallest non-zero gap between the maximum and the runner-up over the example's
+ *   pool_margin[B]  (also: smallest non-zero |z| over the example's ReLU pre-activations)
+ *                   smallest non-zero gap between the maximum and the runner-up over the example's
  *   pool windows (+inf without pooling; exact ties go to the first maximum on every implementation): an fp32 implementation may route a window whose
  *   gap is at rounding level to the other element (see oracle_pool_near_ties);
  *   abs_sum[P]  sum_i |s_i g_i[j]|, the magnitude the terms of coordinate j had before they cancelled: rounding

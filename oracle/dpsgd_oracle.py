@@ -147,7 +147,9 @@ def example_grad(m, theta64, x_i, y_i):
 
 def pool_near_ties(m, theta64, x_i, y_i, tau):
     """[(layer, out_idx, in_idx, gap)]: window elements of one example's max-pools that lie 0 < gap <= tau below
-    their window's maximum (the elements an fp32 forward pass may legitimately pick instead)."""
+    their window's maximum (the elements an fp32 forward pass may legitimately pick instead), and, as
+    (layer, unit, -1, |z|), the ReLU units of dense / convolution layers with 0 < |z| <= tau (whose subgradient an
+    fp32 forward pass may legitimately take from the other side of zero)."""
     cm = _to_c_model(m)
     th = np.ascontiguousarray(theta64, dtype=np.float64)
     xi = _x_array(m, x_i)
@@ -164,7 +166,8 @@ def pool_near_ties(m, theta64, x_i, y_i, tau):
 
 def example_grad_routed(m, theta64, x_i, y_i, routes):
     """(loss, g[P] fp64) of one example with the max-pool windows in `routes` = [(layer, out_idx, in_idx), ...]
-    sending their gradient to the named window element instead of the first maximum."""
+    sending their gradient to the named window element instead of the first maximum; a route (layer, unit, -1)
+    gives that ReLU unit the subgradient of the other side of zero."""
     cm = _to_c_model(m)
     th = np.ascontiguousarray(theta64, dtype=np.float64)
     xi = _x_array(m, x_i)
@@ -175,7 +178,7 @@ def example_grad_routed(m, theta64, x_i, y_i, routes):
     loss = float(lib().oracle_example_grad_routed(C.byref(cm), th.ctypes.data, xi.ctypes.data, int(y_i), len(routes),
                                                   la.ctypes.data, oi.ctypes.data, ii.ctypes.data, g.ctypes.data))
     if loss != loss:
-        raise ValueError("route outside a max-pool window")
+        raise ValueError("route outside a max-pool window, or no ReLU unit")
     return loss, g
 
 

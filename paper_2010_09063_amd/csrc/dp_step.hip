@@ -1464,11 +1464,20 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
         const bool p22 = l.d.kh == 2 && l.d.kw == 2 && l.d.stride == 2 && (l.inH & 1) == 0 && (l.inW & 1) == 0;
         if (p22) {
           const long nwin = (long)B * l.out_size;
-          dim3 g2 = grid1d(nwin, 256);
-          Ln(LL("maxpool_bwd"), g2, block, [&](hipStream_t st) {
-            hipLaunchKernelGGL(maxpool2x2_bwd_kernel, g2, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
-                               (const float *)prev->a, prev->g, nwin, l.outW, l.inW, prev_act);
-          });
+          // (the pooled plane l.a stands in for the activation plane: the derivative is taken at the window's maximum)
+          if ((l.outW & 1) == 0 && (l.inW & 3) == 0 && aligned16(prev->g) && aligned16(l.g) && aligned16(l.a)) {
+            dim3 g2 = grid1d(nwin / 2, 256);
+            Ln(LL("maxpool_bwd"), g2, block, [&](hipStream_t st) {
+              hipLaunchKernelGGL(maxpool2x2_bwd2_kernel, g2, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
+                                 (const float *)l.a, prev->g, nwin / 2, l.outW / 2, l.inW, prev_act);
+            });
+          } else {
+            dim3 g2 = grid1d(nwin, 256);
+            Ln(LL("maxpool_bwd"), g2, block, [&](hipStream_t st) {
+              hipLaunchKernelGGL(maxpool2x2_bwd_kernel, g2, block, 0, st, (const float *)l.g, (const uint8_t *)l.arg,
+                                 (const float *)l.a, prev->g, nwin, l.outW, l.inW, prev_act);
+            });
+          }
         } else
         Ln(LL("maxpool_bwd"), grid, block, [&](hipStream_t st) {
           Split3 dv; dv.dX.init(l.inW); dv.dY.init(l.inH);

@@ -138,25 +138,47 @@ __global__ void maxpool2x2_fwd_kernel(const float *__restrict__ in, float *__res
   arg[i] = (uint8_t)bi;
 }
 
+// Backward: the gradient of a window goes to the position of its (first) maximum, times the derivative of the
+// activation that produced the pooled plane.  That derivative is a function of the activation's OUTPUT at that
+// position, which is the pooled value itself -- so the kernel reads the pooled plane (a quarter of the words) instead
+// of the activation plane: bit-identical, and a third less memory traffic.
 __global__ void maxpool2x2_bwd_kernel(const float *__restrict__ gout, const uint8_t *__restrict__ arg,
-                                      const float *__restrict__ a_in, float *__restrict__ gin, long total, int OW,
+                                      const float *__restrict__ pooled, float *__restrict__ gin, long total, int OW,
                                       int W, int act) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   const long row = i / OW;
   const int ow = (int)(i - row * OW);
-  const float g = gout[i];
+  const float g = gout[i] * act_deriv_from_out(act, pooled[i]);
   const int bi = arg[i];
   const long o0 = (2 * row) * W + 2 * ow, o1 = o0 + W;
-  const float2 t = *reinterpret_cast<const float2 *>(a_in + o0);
-  const float2 u = *reinterpret_cast<const float2 *>(a_in + o1);
   float2 r0, r1;
-  r0.x = bi == 0 ? g * act_deriv_from_out(act, t.x) : 0.f;
-  r0.y = bi == 1 ? g * act_deriv_from_out(act, t.y) : 0.f;
-  r1.x = bi == 2 ? g * act_deriv_from_out(act, u.x) : 0.f;
-  r1.y = bi == 3 ? g * act_deriv_from_out(act, u.y) : 0.f;
+  r0.x = bi == 0 ? g : 0.f;
+  r0.y = bi == 1 ? g : 0.f;
+  r1.x = bi == 2 ? g : 0.f;
+  r1.y = bi == 3 ? g : 0.f;
   *reinterpret_cast<float2 *>(gin + o0) = r0;
   *reinterpret_cast<float2 *>(gin + o1) = r1;
+}
+// The same for an even number of windows per row: a thread takes two neighbouring windows (8-byte reads, 16-byte stores).
+__global__ void maxpool2x2_bwd2_kernel(const float *__restrict__ gout, const uint8_t *__restrict__ arg,
+                                       const float *__restrict__ pooled, float *__restrict__ gin, long pairs, int OW2,
+                                       int W, int act) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= pairs) return;
+  const long row = i / OW2;
+  const int op = (int)(i - row * OW2);
+  const float2 gg = *reinterpret_cast<const float2 *>(gout + 2 * i);
+  const float2 pv = *reinterpret_cast<const float2 *>(pooled + 2 * i);
+  const unsigned short ab = *reinterpret_cast<const unsigned short *>(arg + 2 * i);
+  const float g0 = gg.x * act_deriv_from_out(act, pv.x), g1 = gg.y * act_deriv_from_out(act, pv.y);
+  const int b0 = ab & 255, b1 = ab >> 8;
+  const long o0 = (2 * row) * W + 4 * op, o1 = o0 + W;
+  float4 r0, r1;
+  r0.x = b0 == 0 ? g0 : 0.f; r0.y = b0 == 1 ? g0 : 0.f; r0.z = b1 == 0 ? g1 : 0.f; r0.w = b1 == 1 ? g1 : 0.f;
+  r1.x = b0 == 2 ? g0 : 0.f; r1.y = b0 == 3 ? g0 : 0.f; r1.z = b1 == 2 ? g1 : 0.f; r1.w = b1 == 3 ? g1 : 0.f;
+  *reinterpret_cast<float4 *>(gin + o0) = r0;
+  *reinterpret_cast<float4 *>(gin + o1) = r1;
 }
 
 // Backward-data of a strided convolution, second half: the first half is the per-example product

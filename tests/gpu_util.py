@@ -1,7 +1,8 @@
 """Helpers shared by the GPU parity tests: run the HIP path through the C ABI binding, and compare its
-result with the oracle tensor by tensor, over the whole batch, allowing for the one decision that fp32 and
-fp64 may legitimately take differently (the arg-max of a max-pool window whose two largest values differ by
-less than the forward pass's rounding error)."""
+result with the oracle tensor by tensor, over the whole batch, allowing for the two decisions that fp32 and
+fp64 may legitimately take differently: the arg-max of a max-pool window whose two largest values differ by
+less than the forward pass's rounding error, and the ReLU subgradient of a pre-activation closer to zero than
+that error."""
 import itertools
 import math
 from concurrent.futures import ThreadPoolExecutor
@@ -19,7 +20,8 @@ TOL = 1e-4          # relative L2 of the aggregated gradient: the whole vector, 
 # cancel this adds 1 % to the bar.
 ACC = 1e-6
 NORM_RTOL = 1e-4    # per-example norms
-# Two window elements closer than TAU may be ordered differently by an fp32 forward pass: the kernels' forward
+# Two window elements closer than TAU may be ordered differently by an fp32 forward pass (and a ReLU pre-activation
+# closer than TAU to zero may land on the other side of it): the kernels' forward
 # error on unit-scale pre-activations is <= 3e-7 (direct convolution) to 2e-6 (minimal-filtering form) in the worst
 # case, and both elements carry it.  Every flip the tests accept is printed with its gap (the largest seen at full
 # size is 1.4e-7, on the CIFAR-shaped CNN); a flip at a gap above TAU is not a candidate and fails the comparison.
@@ -88,11 +90,12 @@ def assert_parity(m, got, ref, label, mag=None):
 
 
 class TieAwareOracle:
-    """The oracle's step over the WHOLE batch, with every valid max-pool routing of the near-tied windows.
+    """The oracle's step over the WHOLE batch, with every valid max-pool routing of the near-tied windows and every
+    valid subgradient of the ReLU units whose pre-activation is within TAU of zero.
 
-    For each example that has a window element within TAU of its window's maximum, the oracle computes the
-    example's gradient for every combination of those windows' candidate elements (all on the CPU, from the
-    oracle's own forward pass).  `reference` then picks, per such example, the combination that best explains
+    For each example that has a window element within TAU of its window's maximum (or such a ReLU unit), the oracle
+    computes the example's gradient for every combination of those windows' candidate elements and those units' two
+    subgradients (all on the CPU, from the oracle's own forward pass).  `reference` then picks, per such example, the combination that best explains
     the GPU's aggregate, and returns the oracle's sum and norms under that routing; the caller holds the GPU
     to the usual tolerances against them.  Every example is therefore checked: a clear example against its
     unique gradient, a near-tied one against the closest member of its finite set of valid gradients."""
@@ -100,7 +103,9 @@ class TieAwareOracle:
     def __init__(self, m, theta, x, y, margin, tau=TAU, max_combos=1024):
         self.m, self.theta, self.x, self.y, self.tau = m, theta, x, y, tau
         self.cands = {}  # example -> (g0, [(routes, g, gap)])
-        if not any(L["kind"] == "maxpool2d" for L in m["layers"]) or len(y) == 0:
+        decides = any(L["kind"] == "maxpool2d" or (L["kind"] in ("dense", "conv2d") and L.get("act") == "relu")
+                      for L in m["layers"])
+        if not decides or len(y) == 0:
             return
         th64 = np.asarray(theta, dtype=np.float64)
         near = [int(i) for i in np.flatnonzero(np.asarray(margin) <= tau)]
@@ -112,7 +117,7 @@ class TieAwareOracle:
                 wins.setdefault((l, oi), []).append((ii, gap))
             opts = [[None] + [(l, oi, ii, gap) for ii, gap in alts] for (l, oi), alts in sorted(wins.items())]
             n_combos = math.prod(len(o) for o in opts)
-            assert n_combos <= max_combos, (f"example {i}: {len(opts)} near-tied pool windows ({n_combos} routings): "
+            assert n_combos <= max_combos, (f"example {i}: {len(opts)} near-tied pool windows / ReLU units ({n_combos} routings): "
                                             "degenerate test input (saturated activations?)")
             g0 = O.example_grad(m, th64, x[i], y[i])[1]
             out = []

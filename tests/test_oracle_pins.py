@@ -508,6 +508,59 @@ def test_routed_gradient_equals_the_gradient_after_a_nudge():
     assert np.array_equal(O.example_grad_routed(m, th64, x[0], y[0], [])[1], g_first)
 
 
+def _relu_case():
+    # fc 3 -> 3 with ReLU, then fc 3 -> 2.  Dyadic inputs and weights: the hidden pre-activations are exactly
+    # (0.75, 2^-24, -2^-24): one clear unit, one just above zero, one just below.
+    m = W.model(W.image_input(3), [W.dense(3, 3, act="relu"), W.dense(3, 2)], 2)
+    e = 2.0 ** -24
+    x = np.array([[1.0, 0.5, 0.25]], dtype=np.float32)
+    theta = np.zeros(O.num_params(m), dtype=np.float32)
+    W1 = np.array([[0.5, 0.0, 0.0], [0.5, 0.0, 0.0], [0.0, 0.0, 0.0]])   # [d_in][d_out]
+    theta[0:9] = W1.reshape(-1)
+    theta[9:12] = [0.0, e, -e]                                            # b1
+    theta[12:18] = [0.5, -0.25, 0.125, 0.75, -0.5, 0.25]                  # W2 [3][2]
+    theta[18:20] = [0.125, -0.125]
+    return m, x, np.array([0], dtype=np.int32), theta
+
+
+def test_relu_units_next_to_zero_are_listed_and_flipped():
+    """A ReLU pre-activation within tau of zero is a decision like a near-tied pool window.  Hand-built case with
+    pre-activations (0.75, +2^-24, -2^-24): the margin is 2^-24, both small units are listed, and flipping one
+    gives the gradient of the input in which its bias has been nudged across zero."""
+    m, x, y, theta = _relu_case()
+    th64 = theta.astype(np.float64)
+    r = O.dp_step(m, theta, x, y, 1.0, 0.0, 0, clip=False)
+    assert r["pool_margin"][0] == 2.0 ** -24
+    ent = O.pool_near_ties(m, th64, x[0], y[0], 1e-6)
+    assert [(l, oi, ii) for l, oi, ii, _ in ent] == [(0, 1, -1), (0, 2, -1)]
+    assert [g for *_, g in ent] == [2.0 ** -24, 2.0 ** -24]
+    assert O.pool_near_ties(m, th64, x[0], y[0], 1e-8) == []
+    g0 = O.example_grad(m, th64, x[0], y[0])[1]
+    # unit 1 (z = +2^-24, subgradient 1) switched off: the gradient after its bias is nudged below zero
+    g_off = O.example_grad_routed(m, th64, x[0], y[0], [(0, 1, -1)])[1]
+    th2 = th64.copy(); th2[10] = -2.0 ** -24
+    g_nudged = O.example_grad(m, th2, x[0], y[0])[1]
+    assert np.abs(g_off - g_nudged).max() <= 1e-6
+    assert g_off[10] == 0.0 and g0[10] != 0.0          # its bias gradient: delta_1 * 1 before, * 0 after
+    # unit 2 (z = -2^-24, subgradient 0) switched on: the gradient after its bias is nudged above zero
+    g_on = O.example_grad_routed(m, th64, x[0], y[0], [(0, 2, -1)])[1]
+    th3 = th64.copy(); th3[11] = 2.0 ** -24
+    g_nudged = O.example_grad(m, th3, x[0], y[0])[1]
+    assert np.abs(g_on - g_nudged).max() <= 1e-6
+    assert g_on[11] != 0.0 and g0[11] == 0.0
+    # closed form of the hidden bias gradients: delta_1[j] = relu'(z_j) * sum_k W2[j][k] (softmax_k - onehot_k)
+    a1 = np.array([0.75, 2.0 ** -24, 0.0])
+    logits = a1 @ th64[12:18].reshape(3, 2) + th64[18:20]
+    p = np.exp(logits - logits.max()); p /= p.sum()
+    d2 = p - np.array([1.0, 0.0])
+    back = th64[12:18].reshape(3, 2) @ d2
+    assert np.allclose(g0[9:12], back * np.array([1.0, 1.0, 0.0]), rtol=1e-12, atol=0)
+    assert np.allclose(g_on[9:12], back * np.array([1.0, 1.0, 1.0]), rtol=1e-12, atol=0)
+    assert np.allclose(g_off[9:12], back * np.array([1.0, 0.0, 0.0]), rtol=1e-12, atol=0)
+    with pytest.raises(ValueError):
+        O.example_grad_routed(m, th64, x[0], y[0], [(1, 0, -1)])   # the logit layer has no ReLU
+
+
 def test_abs_sum_is_the_sum_of_term_magnitudes():
     """abs_sum (the yardstick of the per-tensor tolerance) against the per-example gradients: sum_i |s_i g_i|."""
     m, x, y, theta = _tiny_case("tiny_conv2", 6)
