@@ -501,7 +501,7 @@ typedef WinoGeom<16, 8, 1, 24> WinoG16;
 typedef WinoGeom<8, 8, 2, 12> WinoG8;
 
 // ---------------------------------------------------------------------------------------------------------------
-// Variant for exactly 32 input channels and at most 32 output channels, where the channel loop is only four chunks
+// Variant for exactly 32 input channels (output channels in blocks of 32, one run of workgroups per block), where the channel loop is only four chunks
 // long and the kernels above spend more time on what surrounds it (index arithmetic, weight reloads with every
 // chunk, filling and draining the pipeline once per 32 tiles) than on the multiplies.  Here the wave's share of the
 // transformed weights -- 4 components x 32 channels x 32 output channels = 64 registers a lane, already laid out as
@@ -514,7 +514,7 @@ typedef WinoGeom<8, 8, 2, 12> WinoG8;
 // before the last chunk's multiplies.
 // FAST selects what is fixed at compile time: 0 nothing (forward or backward-data, any pool, M <= 32, stores under
 // their bounds checks); 1 forward with the 2x2 max-pool, 2 backward-data through an activation, 3 forward without a
-// pool, all three for M = 32 exactly: every store is then unconditional, so the number of stores between a load and
+// pool, all three for M a multiple of 32: every store is then unconditional, so the number of stores between a load and
 // its use is a constant and the wait for that load does not have to drain the stores as well.
 template <class G, int FAST>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -526,6 +526,7 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int HW = a.H * W;
+  const int m0 = blockIdx.y * 32; // block of 32 output channels (wider layers: one run of workgroups per block)
   const int g_begin = blockIdx.x * groups_per_wg, g_end = min(n_groups, g_begin + groups_per_wg);
   if (g_begin >= g_end) return;
   const bool fwd = FAST == 0 ? a.bias != nullptr : FAST != 2;
@@ -593,10 +594,10 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
   Grp cur = setup(g_begin);
   fetch_raw(cur, 0, xrA);
   fetch_raw(cur, CC, xrB);
-  // the wave's weights: wr[jj][channel pair] = u[(4*wave + jj)*Cpad + 2*cp + lk][li]   (Cpad = 32, Mpad = 32)
+  // the wave's weights: wr[jj][channel pair] = u[(4*wave + jj)*Cpad + 2*cp + lk][m0 + li]   (Cpad = 32)
   float wr[4][NCH * CC / 2];
   {
-    const float *ub = a.u + ((long)(4 * wave) * a.Cpad + lk) * a.Mpad + li;
+    const float *ub = a.u + ((long)(4 * wave) * a.Cpad + lk) * a.Mpad + m0 + li;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
@@ -604,7 +605,7 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
   }
   float bias_r[4];
 #pragma unroll
-  for (int rr = 0; rr < 4; ++rr) bias_r[rr] = fwd ? a.bias[min(8 * wave + 4 * lk + rr, a.M - 1)] : 0.f;
+  for (int rr = 0; rr < 4; ++rr) bias_r[rr] = fwd ? a.bias[min(m0 + 8 * wave + 4 * lk + rr, a.M - 1)] : 0.f;
 
   store_raw(Xr, xrA);
   __syncthreads();
@@ -623,7 +624,7 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
     auto load_side = [&]() {
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        const long o = obase + (long)min(8 * wave + 4 * lk + rr, a.M - 1) * HW;
+        const long o = obase + (long)min(m0 + 8 * wave + 4 * lk + rr, a.M - 1) * HW;
         sd0[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o);
         sd1[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
       }
@@ -667,7 +668,7 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
       const int r = 4 * wave + rr;
-      const int m = 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+      const int m = m0 + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
       if (FAST == 0 && m >= a.M) continue;
       float T[4][2];
 #pragma unroll

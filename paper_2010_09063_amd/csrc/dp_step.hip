@@ -433,14 +433,16 @@ static void launch_conv_wino(const LN &Ln, const char *label, ConvWinoArgs a, in
   const long tiles = (long)a.B * (a.H / 2) * (a.W / 2);
   dim3 grid((unsigned)((tiles + 31) / 32), a.Mpad / (32 * db)), block(256);
   // 32 input and at most 32 output channels: persistent workgroups that keep the transformed weights in registers
-  if (db == 1 && a.Cin == 32 && a.Cpad == 32 && a.Mpad == 32 && !Ln.c->opt.no_resident_weights) {
-    // what the kernel fixes at compile time for 32 output channels (every store unconditional)
-    const int fast = a.M != 32 ? 0 : (a.bias != nullptr ? (a.pool == 1 ? 1 : (a.pool == 0 ? 3 : 0)) : (a.act != 0 ? 2 : 0));
+  // (wider layers run it once per block of 32 output channels: the transform is repeated per block, which costs less
+  // than the per-group prologue of the kernels below at four chunks per group)
+  if (a.Cin == 32 && a.Cpad == 32 && a.Mpad % 32 == 0 && a.Mpad <= 64 && !Ln.c->opt.no_resident_weights) {
+    // what the kernel fixes at compile time for whole blocks of 32 output channels (every store unconditional)
+    const int fast = a.M % 32 != 0 ? 0 : (a.bias != nullptr ? (a.pool == 1 ? 1 : (a.pool == 0 ? 3 : 0)) : (a.act != 0 ? 2 : 0));
 #define DP_WINOR_CASE(G_, cond_)                                                                  \
   if (a.W == G_::W && (cond_)) {                                                                  \
     const int n_groups = a.B * (a.H / G_::ROWS);                                                  \
-    const int per_wg = ceil_div(n_groups, 512); /* two workgroups per CU, all resident */         \
-    dim3 rgrid(ceil_div(n_groups, per_wg));                                                       \
+    const int per_wg = ceil_div(n_groups * (a.Mpad / 32), 512); /* two workgroups per CU, all resident */ \
+    dim3 rgrid(ceil_div(n_groups, per_wg), a.Mpad / 32);                                          \
     Ln(label, rgrid, block, [&](hipStream_t st) {                                                 \
       if (fast == 1) hipLaunchKernelGGL((conv_wino_res_kernel<G_, 1>), rgrid, block, 0, st, a, n_groups, per_wg);      \
       else if (fast == 2) hipLaunchKernelGGL((conv_wino_res_kernel<G_, 2>), rgrid, block, 0, st, a, n_groups, per_wg); \

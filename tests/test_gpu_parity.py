@@ -287,6 +287,14 @@ def test_resident_weight_minimal_filtering_kernel():
     for batch in (3, 514):
         x, y, theta = _case(m, batch, seed=batch)
         _check_all_regimes(m, x, y, theta, f"planes16 32->32->32/B{batch}", options=dict(minimal_filtering_all=1))
+    # wider layers take the same kernel once per block of 32 output channels: 64 (two full blocks) and 40 (the second
+    # block partly empty), forward; backward-data from 64 channels does not (its channel loop is longer)
+    m = W.model(W.image_input(32, 16, 16), [
+        W.conv2d(32, 64, 3, stride=1, pad=1, act="relu"), W.conv2d(64, 32, 3, stride=1, pad=1, act="tanh"),
+        W.conv2d(32, 40, 3, stride=1, pad=1, act="tanh"), W.maxpool2d(2, 2), W.dense(40 * 8 * 8, 3)], 3)
+    for batch in (3, 300):
+        x, y, theta = _case(m, batch, seed=batch)
+        _check_all_regimes(m, x, y, theta, f"planes16 32->64->32->40/B{batch}", options=dict(minimal_filtering_all=1))
 
 
 def test_weight_gradients_in_minimal_filtering_form():
