@@ -39,8 +39,10 @@ static inline bool conv_first_fits(int Cin, int H, int W, int M, int KH, int KW,
          PAD == 1;
 }
 
-// FULL: M = 32, every store unconditional
-template <bool FULL>
+// FULL: M = 32, every store unconditional.  ACT: the activation, fixed at compile time -- with a run-time switch
+// around every output value the compiler no longer counts the stores between a load and its use and drains all of
+// them before the next tile is staged.
+template <bool FULL, int ACT>
 __global__ __launch_bounds__(256) void conv_first_kernel(const ConvFirstArgs a) {
   __shared__ float Xl[2][CF_NI * 256];
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
@@ -101,15 +103,18 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const ConvFirstArgs a) 
     }
   };
 
+  // The first tile is staged before the loop and every iteration stages the next one AFTER its own stores: the loads
+  // it waits for are then always followed by exactly the 32 stores of one tile, on the first pass as on every other,
+  // so the wait is for "all but the last 32" and never for the stores themselves.
   Tile cur = setup(t_begin);
   fetch(cur);
+#pragma unroll
+  for (int i = 0; i < CF_NI; ++i) Xl[0][tid + 256 * i] = xr[i];
+  __syncthreads();
+  Tile nxt = setup(min(t_begin + 1, t_end - 1)); // (past the run's last tile: it is read again, unused)
+  fetch(nxt);
   int buf = 0;
   for (int t = t_begin; t < t_end; ++t) {
-#pragma unroll
-    for (int i = 0; i < CF_NI; ++i) Xl[buf][tid + 256 * i] = xr[i];
-    __syncthreads(); // the tile is staged; the buffer written next was last read before the previous barrier
-    const Tile nxt = setup(min(t + 1, t_end - 1)); // (past the run's last tile: it is read again, unused)
-    fetch(nxt);
     __amdgpu_buffer_rsrc_t ors =
         __builtin_amdgcn_make_buffer_rsrc(a.out + (long)cur.img * a.M * HW, 0, 4 * a.M * HW, 0x00020000);
     const char *xb = reinterpret_cast<const char *>(&Xl[buf][0]);
@@ -130,12 +135,18 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const ConvFirstArgs a) 
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int mu = 8 * (r >> 2) + (r & 3); // output channel mu + 4 lk
-        const float v = act_apply(a.act, acc[r] + bias_r[r]);
+        const float v = act_apply(ACT, acc[r] + bias_r[r]);
         const unsigned off = (FULL || mu + 4 * lk < a.M) ? o_row : OUTSIDE;
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), ors, off, 4 * mu * HW, 0);
       }
     }
+    // the next tile into the other buffer (last read before the previous barrier), then its successor's loads
+#pragma unroll
+    for (int i = 0; i < CF_NI; ++i) Xl[buf ^ 1][tid + 256 * i] = xr[i];
+    __syncthreads();
     cur = nxt;
+    nxt = setup(min(t + 2, t_end - 1));
+    fetch(nxt);
     buf ^= 1;
   }
 }
@@ -152,7 +163,7 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const ConvFirstArgs a) 
 // at [c][row + kh][column + kw], follows the same pairing.  A workgroup owns whole examples, one after the other
 // (persistent); wave w takes the pixel rows w, w + 4, ... and keeps Delta rows four row-steps ahead in registers (a
 // trip to memory is longer than the sixteen multiplies of a row), the next example's image travels meanwhile.  Per
-// example the four waves' accumulators meet in LDS, wave 0 squares, stores and reduces.  The stored row has the
+// example the four waves' accumulators meet in LDS and each wave squares, stores and reduces a quarter of them.  The stored row has the
 // accumulator order [register][lane] of conv_s1_wgrad_kernel's flattened variant, so either kernel can write it.
 #define CFW_LDW 40                          // LDS row length: interior at columns 4 .. 35 (16-byte aligned), halo at 3 and 36
 #define CFW_PLANE ((CF_W + 2) * CFW_LDW)    // 34 rows
@@ -161,7 +172,8 @@ __global__ __launch_bounds__(256) void conv_first_kernel(const ConvFirstArgs a) 
 struct ConvFirstWgArgs {
   const float *x;      // [B][Cin][H][32]
   const float *dy;     // [B][D][H][32]
-  float *slots;        // squared norms: slots[b]
+  float *slots;        // squared norms, one partial per wave: slots[w * slot_stride + b], w = 0 .. 3
+  long slot_stride;
   float *gstore;       // [B][gstride] or null
   long gstride, gbias_off;
   int B, Cin, H, D;
@@ -172,18 +184,21 @@ static inline bool conv_first_wgrad_fits(int Cin, int H, int W, int D, int KH, i
   return conv_first_fits(Cin, H, W, D, KH, KW, S, PAD) && H % 16 == 0 && H <= 32;
 }
 
-// FULL: D = 32 (no lane of the Delta operand is masked)
-template <bool FULL>
+// FULL: D = 32 (no lane of the Delta operand is masked); STORE: the gradients are written out; H_: rows of the plane.
+// All three are compile-time so that one example is straight-line code in which every wave issues the same memory
+// instructions: the compiler can then wait for "all but the last n" of them, instead of draining the Delta rows in
+// flight and the stores whenever it needs the oldest load.
+template <bool FULL, bool STORE, int H_>
 __global__ __launch_bounds__(256) void conv_first_wgrad_kernel(const ConvFirstWgArgs a) {
   __shared__ __attribute__((aligned(16))) float Xl[2][3 * CFW_PLANE];
-  __shared__ float xs[3][16][64];
+  __shared__ float xs[4][16][64];
   __shared__ float bs[4][32];
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int H = a.H, HW = H * CF_W, Cin = a.Cin, D = a.D, K = Cin * 9;
+  constexpr int H = H_, HW = H * CF_W, RPW = H / 4; // RPW: pixel rows per wave and example, a multiple of 4
+  const int Cin = a.Cin, D = a.D, K = Cin * 9;
   const int b_begin = blockIdx.x * a.ex_per_wg, b_end = min(a.B, b_begin + a.ex_per_wg);
   if (b_begin >= b_end) return;
-  const int RPW = H / 4; // pixel rows per wave and example: a multiple of 4
 
   for (int i = tid; i < 2 * 3 * CFW_PLANE; i += 256) (&Xl[0][0])[i] = 0.f; // halos stay zero: only interiors are written
 
@@ -207,11 +222,13 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_kernel(const ConvFirstWg
     xs_off[q] = ok ? 4u * (unsigned)(c * HW + row * CF_W + 4 * g) : 0u;
     xs_lds[q] = ok ? c * CFW_PLANE + (row + 1) * CFW_LDW + 4 + 4 * g : -1;
   }
-  float4 xv[CFW_XI];
+  static_assert(CFW_XI == 3, "three staged items, held in three named registers (an array of them ended up in scratch memory)");
+  float4 xv0, xv1, xv2;
   auto fetch_x = [&](int b) {
     const char *xb = reinterpret_cast<const char *>(a.x + (long)b * Cin * HW);
-#pragma unroll
-    for (int q = 0; q < CFW_XI; ++q) xv[q] = *reinterpret_cast<const float4 *>(xb + xs_off[q]);
+    xv0 = *reinterpret_cast<const float4 *>(xb + xs_off[0]);
+    xv1 = *reinterpret_cast<const float4 *>(xb + xs_off[1]);
+    xv2 = *reinterpret_cast<const float4 *>(xb + xs_off[2]);
   };
   // Delta rows in flight: ring of four row-steps, four float4 each (pixels 8 s + 4 lk .. + 3 of the row)
   float4 dr[4][4];
@@ -235,14 +252,15 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_kernel(const ConvFirstWg
   __syncthreads(); // the zeros are in place
   int buf = 0, t = 0;
   for (int b = b_begin; b < b_end; ++b) {
-#pragma unroll
-    for (int q = 0; q < CFW_XI; ++q)
-      if (xs_lds[q] >= 0) *reinterpret_cast<float4 *>(&Xl[buf][xs_lds[q]]) = xv[q];
+    if (xs_lds[0] >= 0) *reinterpret_cast<float4 *>(&Xl[buf][xs_lds[0]]) = xv0;
+    if (xs_lds[1] >= 0) *reinterpret_cast<float4 *>(&Xl[buf][xs_lds[1]]) = xv1;
+    if (xs_lds[2] >= 0) *reinterpret_cast<float4 *>(&Xl[buf][xs_lds[2]]) = xv2;
     __syncthreads(); // the image is staged (the other buffer was last read before the previous example's second barrier)
     fetch_x(min(b + 1, b_end - 1));
     cf_f32x16 acc;
     float bsum = 0.f;
     const char *xb = reinterpret_cast<const char *>(&Xl[buf][0]) + kbase;
+#pragma unroll
     for (int j0 = 0; j0 < RPW; j0 += 4) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -266,32 +284,34 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_kernel(const ConvFirstWg
         ++t;
       }
     }
-    // ---- the example is complete: accumulators of waves 1 .. 3 and the bias sums meet in LDS
+    // ---- the example is complete: the four waves' accumulators and bias sums meet in LDS; wave w finishes registers
+    // 4 w .. 4 w + 3 (and eight of the bias gradients), with stores that every lane of every wave executes
     bsum += __shfl_xor(bsum, 32, 64);
     if (lk == 0) bs[wave][li] = bsum;
-    if (wave > 0) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) xs[wave - 1][r][lane] = acc[r];
-    }
+    for (int r = 0; r < 16; ++r) xs[wave][r][lane] = acc[r];
     __syncthreads();
-    if (wave == 0) {
-      float *gb = a.gstore ? a.gstore + (long)b * a.gstride : nullptr;
+    {
+      float *gb = STORE ? a.gstore + (long)b * a.gstride : nullptr;
       float part = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = acc[r] + ((xs[0][r][lane] + xs[1][r][lane]) + xs[2][r][lane]);
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = 4 * wave + rr;
+        float v = (xs[0][r][lane] + xs[1][r][lane]) + (xs[2][r][lane] + xs[3][r][lane]);
         v = li < K ? v : 0.f; // lanes past the last (channel, tap) pair multiplied a duplicate of it
         part = fmaf(v, v, part);
-        if (gb) gb[r * 64 + lane] = v;
+        if (STORE) gb[r * 64 + lane] = v;
       }
-      if (lane < 32) {
-        const float bd = lane < D ? (bs[0][lane] + bs[1][lane]) + (bs[2][lane] + bs[3][lane]) : 0.f;
-        part = fmaf(bd, bd, part);
-        if (gb && lane < D) gb[a.gbias_off + lane] = bd;
+      {
+        // bias gradient d = 8 w + lane % 8 (every lane of the wave takes part: lanes with the same d store the same word)
+        const int d = 8 * wave + (lane & 7), dc = min(d, D - 1);
+        const float bd = (bs[0][dc] + bs[1][dc]) + (bs[2][dc] + bs[3][dc]);
+        part = (lane < 8 && d < D) ? fmaf(bd, bd, part) : part;
+        if (STORE) gb[a.gbias_off + dc] = bd;
       }
 #pragma unroll
       for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
-      if (lane == 0) a.slots[b] = part;
+      a.slots[(long)wave * a.slot_stride + b] = part; // one slot per wave; the clip factor adds them in a fixed order
     }
     buf ^= 1;
   }

@@ -646,6 +646,7 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
       // (the stored row keeps the accumulator order of the flattened direct kernel, which stays the fallback)
       l.first_wg = c->L.empty() && l.dir_wg && l.wg_flat && !c->opt.generic_conv && !c->opt.no_first_layer_kernel &&
                    conv_first_wgrad_fits(g.C, g.H, g.W, g.D, g.KH, g.KW, g.S, g.PAD);
+      if (l.first_wg) l.max_slots = std::max(l.max_slots, 4); // its norm comes as one partial per wave
     }
     off += l.p_count;
     total_slots += l.max_slots;
@@ -1137,8 +1138,11 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           a.tiles_per_wg = ceil_div(a.n_tiles, 1024);
           dim3 grid(ceil_div(a.n_tiles, a.tiles_per_wg)), block(256);
           Ln(LL("conv_fwd"), grid, block, [&](hipStream_t st) {
-            if (g.D == 32) hipLaunchKernelGGL(conv_first_kernel<true>, grid, block, 0, st, a);
-            else hipLaunchKernelGGL(conv_first_kernel<false>, grid, block, 0, st, a);
+#define DP_CF_CASE(full_, act_)                                                                                   \
+  if ((g.D == 32) == full_ && a.act == act_) hipLaunchKernelGGL((conv_first_kernel<full_, act_>), grid, block, 0, st, a);
+            DP_CF_CASE(true, DP_ACT_NONE) DP_CF_CASE(true, DP_ACT_RELU) DP_CF_CASE(true, DP_ACT_TANH)
+            DP_CF_CASE(false, DP_ACT_NONE) DP_CF_CASE(false, DP_ACT_RELU) DP_CF_CASE(false, DP_ACT_TANH)
+#undef DP_CF_CASE
           });
           break;
         }
@@ -1382,15 +1386,19 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           });
         } else if (priv && l.first_wg && aligned16(lin) && aligned16(l.g)) {
           ConvFirstWgArgs a{};
-          a.x = lin; a.dy = l.g; a.slots = c->slots + (long)slot_next * slot_stride;
+          a.x = lin; a.dy = l.g; a.slots = c->slots + (long)slot_next * slot_stride; a.slot_stride = slot_stride;
           a.gstore = l.gst; a.gstride = l.gorder.n_total; a.gbias_off = l.gorder.n_w;
           a.B = B; a.Cin = g.C; a.H = g.H; a.D = g.D;
           a.ex_per_wg = ceil_div(B, 512); // two workgroups per CU (one example per workgroup measured 56 us against 45)
-          slot_next += 1;
+          slot_next += 4;                 // one partial per wave
           dim3 grid(ceil_div(B, a.ex_per_wg)), block(256);
           Ln(LL("conv_wgrad_norm"), grid, block, [&](hipStream_t st) {
-            if (g.D == 32) hipLaunchKernelGGL(conv_first_wgrad_kernel<true>, grid, block, 0, st, a);
-            else hipLaunchKernelGGL(conv_first_wgrad_kernel<false>, grid, block, 0, st, a);
+#define DP_CFW_CASE(full_, store_, h_)                                                                             \
+  if ((g.D == 32) == full_ && (l.gst != nullptr) == store_ && g.H == h_)                                           \
+    hipLaunchKernelGGL((conv_first_wgrad_kernel<full_, store_, h_>), grid, block, 0, st, a);
+            DP_CFW_CASE(true, true, 32) DP_CFW_CASE(true, false, 32) DP_CFW_CASE(false, true, 32) DP_CFW_CASE(false, false, 32)
+            DP_CFW_CASE(true, true, 16) DP_CFW_CASE(true, false, 16) DP_CFW_CASE(false, true, 16) DP_CFW_CASE(false, false, 16)
+#undef DP_CFW_CASE
           });
         } else if (priv && l.dir_wg && aligned16(lin)) {
           // one round of resident workgroups, each walking through its run of examples: the next
