@@ -253,15 +253,17 @@ void conv_wino_kernel(const ConvWinoArgs a, const ConvWinoRegion rg) {
   };
 
   fetch_raw(0, xr);
+  store_raw(0, xr, Xr);
+  __syncthreads();
+  fetch_raw(CC, xr);
+  __builtin_amdgcn_sched_barrier(0);
+  // (weights after the second chunk's raw loads, as in every later chunk: see conv_wino_reg_kernel)
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
     for (int cp = 0; cp < CC / 2; ++cp)
 #pragma unroll
       for (int i = 0; i < DB; ++i) wr[jj][cp][i] = *w_ptr(ubase, wlane, jj, cp, i);
-  store_raw(0, xr, Xr);
-  __syncthreads();
-  fetch_raw(CC, xr);
 
   int buf = 0;
   for (int c0 = 0; c0 < a.Cin; c0 += CC) {
@@ -440,17 +442,20 @@ void conv_wino_reg_kernel(const ConvWinoArgs a) {
     }
   };
 
+  // (the first weight loads are issued AFTER the second chunk's raw loads, as in every later chunk: the wait for a raw
+  // chunk is then "all but the 32 weight loads behind it" on every path into the loop, not a drain of everything)
   fetch_raw(0);
+  // (padding words of the rows are never read; halo words are rewritten as zeros with every chunk)
+  store_raw(Xr);
+  __syncthreads();
+  fetch_raw(CC);
+  __builtin_amdgcn_sched_barrier(0); // (the scheduler would put the weight loads first)
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
     for (int cp = 0; cp < CC / 2; ++cp)
 #pragma unroll
       for (int i = 0; i < DB; ++i) wr[jj][cp][i] = *w_ptr(ubase, wlane, jj, cp, i);
-  // (padding words of the rows are never read; halo words are rewritten as zeros with every chunk)
-  store_raw(Xr);
-  __syncthreads();
-  fetch_raw(CC);
   float bA[CC / 2][4], bB[CC / 2][4];
   transform(Xr, bA);
 
