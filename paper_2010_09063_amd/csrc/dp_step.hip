@@ -617,6 +617,7 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
       l.lstm_wg = lstm_wgrad_fits(l.Din, l.H, l.T) && !c->opt.no_lstm_wgrad;
       l.p_count = (long)l.Din * 4 * l.H + (long)l.H * 4 * l.H + 4 * l.H;
       l.max_slots = ceil_div(l.Din + l.H + 1, 32) * ceil_div(4 * l.H, 32);
+      if (l.lstm_wg) l.max_slots = std::max(l.max_slots, LWG_SLOTS);
       if (l.d.kind == DP_LSTM_SEQ) {
         if (i + 1 >= model->n_layers || model->layers[i + 1].kind != DP_SEQ_MEAN) { rc = DP_EUNSUPPORTED; break; }
         l.outC = l.T; l.outH = l.H; l.outW = 1; // stays a sequence
@@ -1531,8 +1532,9 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
           a.x = lin; a.hs = l.hs; a.dg = l.gates; a.slots = c->slots; a.slot_stride = slot_stride; a.slot0 = slot_next;
           a.gstore = l.gst; a.gstride = l.p_count; a.B = B; a.T = l.T; a.Din = l.Din; a.H = l.H;
           const int halves = G > LWG_NH * 16 ? 2 : 1;
-          slot_next += halves;
-          dim3 grid(B, halves), block(LWG_THREADS);
+          slot_next += halves * 8; // one partial per wave
+          // persistent workgroups, one per CU (their LDS leaves room for no second one): 128 x 2 halves
+          dim3 grid(std::min(B, 256 / halves), halves), block(LWG_THREADS);
           Ln(LL("lstm_wgrad_norm"), grid, block, [&](hipStream_t st) {
             hipLaunchKernelGGL(lstm_wgrad_kernel, grid, block, lstm_wgrad_lds_bytes(), st, a);
           });

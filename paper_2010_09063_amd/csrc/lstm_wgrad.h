@@ -9,6 +9,12 @@
 // walked in chunks of 32 steps staged in LDS ([t][row] for both operands, row lengths that put the four k-lanes of
 // an MFMA operand on different banks), two buffers, one barrier per chunk; the next chunk travels in registers
 // meanwhile.  Staging addresses are fixed per thread and computed once.
+// A workgroup is PERSISTENT: it keeps its half of the columns and walks over examples blockIdx.x, blockIdx.x +
+// gridDim.x, ...; the chunk pipeline runs on across examples (the next example's first chunk is on its way during the
+// current one's last), and the stores of an example's gradient are issued after the next chunk has been staged and
+// its successor requested, right before that chunk's multiplies -- so the wait that precedes the following staging,
+// which the compiler cannot make finer than "everything", comes a whole chunk of multiplies after them.  The squared
+// norm leaves the kernel as one partial per wave (16 slots per example), which needs no barrier.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -30,7 +36,7 @@ struct LstmWgArgs {
   const float *x;      // [B][T][Din]
   const float *hs;     // [B][T][H]   h_t; row t of the operand uses h_{t-1} (zero for t = 0)
   const float *dg;     // [B][T][4H]  gate gradients
-  float *slots;        // squared norms: slots[(slot0 + half) * slot_stride + b]
+  float *slots;        // squared norms, one partial per wave: slots[(slot0 + half * 8 + wave) * slot_stride + b]
   long slot_stride; int slot0;
   float *gstore;       // [B][gstride] or null
   long gstride;
@@ -40,7 +46,8 @@ struct LstmWgArgs {
 static inline bool lstm_wgrad_fits(int Din, int H, int T) {
   return Din >= 4 && H >= 4 && (Din & 3) == 0 && (H & 3) == 0 && Din + H + 1 <= LWG_MB * 16 && 4 * H <= 2 * LWG_NH * 16 && T >= 1;
 }
-static inline size_t lstm_wgrad_lds_bytes() { return sizeof(float) * (2 * LWG_BK * 2 * LWG_LD + 16); }
+static inline size_t lstm_wgrad_lds_bytes() { return sizeof(float) * (2 * LWG_BK * 2 * LWG_LD); }
+#define LWG_SLOTS 16 // slots per example: 2 halves x 8 waves
 
 __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArgs a) {
   extern __shared__ float lds[];
@@ -49,7 +56,7 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
   // waves w and w + 4 share a SIMD: the second row of waves takes the column groups in rotated order, so that the
   // SIMD that hosts the widest group of the upper rows hosts a narrow one of the lower rows
   const int wm = wave >> 2, wn = (wave + 2 * wm) & 3;
-  const int b = blockIdx.x, half = blockIdx.y;
+  const int half = blockIdx.y;
   const int Din = a.Din, H = a.H, T = a.T, G = 4 * H, M = Din + H + 1;
   const int n_half0 = half * (LWG_NH * 16);              // first column of this workgroup
   const int n_cols = min(G - n_half0, LWG_NH * 16);      // its columns (a multiple of 4)
@@ -57,7 +64,6 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
   // the half's column blocks dealt to the four column groups: 13 -> 4, 3, 3, 3; 12 -> 3, 3, 3, 3; ...
   const int nb_total = (n_cols + 15) >> 4, nb_base = nb_total >> 2, nb_rem = nb_total & 3;
   const int n_cnt = nb_base + (wn < nb_rem ? 1 : 0), n_blk0 = wn * nb_base + min(wn, nb_rem);
-  float *red = lds + 2 * LWG_BK * 2 * LWG_LD;
 
   // staging items, fixed per thread: (step tt of the chunk, group g of four floats).  A: x, then h of the step
   // before, then the group that starts with the constant 1.  B: this half's columns of the gate gradients.
@@ -82,11 +88,11 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
     }
   }
   float4 ra[LWG_ITEMS], rb[LWG_ITEMS];
-  const float *xb = a.x + (long)b * T * Din, *hb = a.hs + (long)b * T * H, *gb = a.dg + (long)b * T * G;
 
   // fetch only issues loads, every one unconditional and from a valid address (a load under a branch would be waited
   // for at the join, one memory latency per item); what an item is worth is decided when it is written to LDS
-  auto fetch = [&](int t0) {
+  auto fetch = [&](int b, int t0) {
+    const float *xb = a.x + (long)b * T * Din, *hb = a.hs + (long)b * T * H, *gb = a.dg + (long)b * T * G;
 #pragma unroll
     for (int q = 0; q < LWG_ITEMS; ++q) {
       const int tt = a_tk[q] & 255, kind = a_tk[q] >> 8, t = t0 + tt;
@@ -129,10 +135,11 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
     }
   }
   __syncthreads();
-  fetch(0);
   const int n_chunks = (T + LWG_BK - 1) / LWG_BK;
-  float *gs = a.gstore ? a.gstore + (long)b * a.gstride : nullptr;
-  float q2 = 0.f;
+  const int b_first = blockIdx.x, b_step = gridDim.x;
+  if (b_first >= a.B) return;
+  const int n_items = (a.B - b_first + b_step - 1) / b_step;
+  fetch(b_first, 0);
   // The multiply loop and the epilogue, compiled for each of the four wave tiles (7 or 6 row blocks x 4 or 3 column
   // blocks): with the block counts as constants the loop body is branch-free, so the LDS reads of one k-step are
   // issued under the multiplies of the one before.  A wave with fewer than three column blocks of real data runs the
@@ -144,11 +151,48 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
     for (int i = 0; i < MC; ++i)
 #pragma unroll
       for (int j = 0; j < NC; ++j) acc[i][j] = (lwg_f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < n_chunks; ++c) {
-      float *As = lds + (c & 1) * LWG_BK * 2 * LWG_LD, *Bs = As + LWG_BK * LWG_LD;
+    // the example's gradient (optional) and this wave's share of its squared norm; accumulator register r of a lane
+    // is row 4 kq + r, column i16 of its block.  Leaves the accumulators at zero for the next example.
+    auto finish = [&](int b) {
+      // (lane indices from an opaque copy of the thread index: the compiler would otherwise keep the 112 store
+      // addresses alive across the chunk loop and spill)
+      int t_ = tid;
+      asm volatile("" : "+v"(t_));
+      const int i16_ = t_ & 15, kq_ = (t_ >> 4) & 3;
+      float *gs = a.gstore ? a.gstore + (long)b * a.gstride : nullptr;
+      const int m_lane = m_blk0 * 16 + 4 * kq_, nl_lane = n_blk0 * 16 + i16_;
+      float *gl = gs ? gs + (long)m_lane * G + n_half0 + nl_lane : nullptr;
+      float q2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < MC; ++i)
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+          const int nl = nl_lane + j * 16;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int m = m_lane + i * 16 + r;
+            if (j < n_cnt && m < M && nl < n_cols) {
+              const float v = acc[i][j][r];
+              q2 = fmaf(v, v, q2);
+              if (gl) gl[(long)(i * 16 + r) * G + j * 16] = v;
+            }
+          }
+          acc[i][j] = (lwg_f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) q2 += __shfl_xor(q2, o, 64);
+      if ((t_ & 63) == 0) a.slots[(long)(a.slot0 + half * 8 + wave) * a.slot_stride + b] = q2;
+    };
+    int b_cur = b_first, c = 0, b_done = -1;
+    const int total = n_items * n_chunks;
+    for (int g = 0; g < total; ++g) {
+      float *As = lds + (g & 1) * LWG_BK * 2 * LWG_LD, *Bs = As + LWG_BK * LWG_LD;
       stash(As, Bs, c * LWG_BK);
-      __syncthreads(); // chunk c is staged; every wave has finished chunk c - 1 (it stashed c after its multiplies)
-      if (c + 1 < n_chunks) fetch((c + 1) * LWG_BK);
+      __syncthreads(); // chunk g is staged; every wave has finished chunk g - 1 (it stashed g after its multiplies)
+      int b_next = b_cur, c_next = c + 1;
+      if (c_next == n_chunks) { c_next = 0; b_next += b_step; }
+      if (g + 1 < total) fetch(b_next, c_next * LWG_BK);
+      if (b_done >= 0) { finish(b_done); b_done = -1; } // the example completed by the previous chunk
       const float *ap = As + kq * LWG_LD + m_blk0 * 16 + i16, *bp = Bs + kq * LWG_LD + n_blk0 * 16 + i16;
 #pragma unroll
       for (int ks = 0; ks < LWG_BK / 4; ++ks) {
@@ -162,24 +206,10 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
 #pragma unroll
           for (int j = 0; j < NC; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[j], acc[i][j], 0, 0, 0);
       }
+      if (c == n_chunks - 1) b_done = b_cur;
+      b_cur = b_next; c = c_next;
     }
-    // the example's gradient (optional) and this half's share of its squared norm; accumulator register r of a lane
-    // is row 4 kq + r, column i16 of its block
-#pragma unroll
-    for (int i = 0; i < MC; ++i)
-#pragma unroll
-      for (int j = 0; j < NC; ++j) {
-        const int nl = (n_blk0 + j) * 16 + i16, n = n_half0 + nl;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int m = (m_blk0 + i) * 16 + 4 * kq + r;
-          if (j < n_cnt && m < M && nl < n_cols) {
-            const float v = acc[i][j][r];
-            q2 = fmaf(v, v, q2);
-            if (gs) gs[(long)m * G + n] = v;
-          }
-        }
-      }
+    if (b_done >= 0) finish(b_done);
   };
   if (m_cnt == 7) {
     if (n_cnt == 4) run(std::integral_constant<int, 7>{}, std::integral_constant<int, 4>{});
@@ -187,15 +217,5 @@ __global__ __launch_bounds__(LWG_THREADS) void lstm_wgrad_kernel(const LstmWgArg
   } else {
     if (n_cnt == 4) run(std::integral_constant<int, 6>{}, std::integral_constant<int, 4>{});
     else run(std::integral_constant<int, 6>{}, std::integral_constant<int, 3>{});
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) q2 += __shfl_xor(q2, o, 64);
-  if (lane == 0) red[wave] = q2;
-  __syncthreads();
-  if (tid == 0) {
-    float s = 0.f;
-#pragma unroll
-    for (int w = 0; w < LWG_THREADS / 64; ++w) s += red[w];
-    a.slots[(long)(a.slot0 + half) * a.slot_stride + b] = s;
   }
 }
