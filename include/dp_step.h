@@ -122,8 +122,8 @@ typedef struct {
   int no_lstm_wgrad;              /* the LSTM's per-example weight gradient on the generic tiled contraction       */
   int no_rows_gemm;               /* the LSTM's input projection / input gradient on the generic tiled contraction */
   int no_single_bucket;           /* the embedding's counting sort as three launches, whatever the batch           */
-  int small_gemm;                 /* two-layer networks: both batch-wide products with K split inside the workgroup
-                                     (measured slower than the split-K contraction; kept for comparison)           */
+  int no_small_gemm;              /* two-layer networks: both batch-wide products on the split-K contraction, not
+                                     on the kernel that splits K inside the workgroup                               */
   int no_resident_weights;        /* minimal-filtering form, 32 -> (at most) 32 channels: the per-group kernel instead of
                                      the persistent one that keeps the transformed weights in registers              */
   int no_side_stream;             /* the embedding's counting sort in line on the caller's stream instead of beside the

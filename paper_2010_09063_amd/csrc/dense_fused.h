@@ -492,16 +492,19 @@ static inline int launch_dense2_mid(hipStream_t st, Dense2Args a, int max_tiles)
 
 // ---------------------------------------------------------------------------------------------------------------
 // The two batch-wide contractions of a two-layer network -- the hidden layer's forward product and its clipped sum
-// -- at sizes where the whole output is a few hundred 32 x 32 tiles (512 x 512 x 784: 0.4 GFLOP, 5 us of the chip).
+// -- at sizes where the whole output is a few hundred 32 x 32 tiles (512 x 512 x 784: 0.4 GFLOP, 3 us of the chip).
 // Split-K partials and the launch that sums them cost more than the product itself there, so the K range is split
-// INSIDE the workgroup: its four waves take a quarter of K each for the same 32 x 32 tile, with operands loaded
-// straight from memory into the lanes of v_mfma_f32_16x16x4_f32 (no LDS staging, no barrier in the loop; an
-// operand element is base + row * row_stride + k * k_stride, so row-major and k-major operands are the same code),
-// and add their four partial tiles through LDS at the end.  The output is complete: bias and activation (forward) or
-// the single partial row the final write reads (clipped sum) are applied by the same kernel.
+// INSIDE the workgroup: its four waves take every fourth 32-deep slice of K for the same 32 x 32 tile and add their
+// four partial tiles through LDS at the end.  The output is complete: bias and activation (forward) or the single
+// partial row the final write reads (clipped sum) are applied by the same kernel.
+// A wave works alone until that last sum -- no workgroup barrier in the K loop: it loads its slice of both operands
+// with 16-byte loads along whichever index is contiguous in memory (k for a row-major operand, the row for a k-major
+// one), keeps the next slice in registers while the current one is multiplied, and passes the slice through an LDS
+// area of its own ([k][row], row length 33), from which the lanes of v_mfma_f32_32x32x2_f32 read their operands.
+// LDS operations of one wave complete in order, so one area per wave needs no double buffer.
 struct SmallGemmArgs {
-  const float *A; long a_sr, a_sk; // element (m, k) = A[m * a_sr + k * a_sk]
-  const float *B; long b_sr, b_sk; // element (n, k) = B[n * b_sr + k * b_sk]
+  const float *A; long a_sr, a_sk; // element (m, k) = A[m * a_sr + k * a_sk]; one of the two strides is 1
+  const float *B; long b_sr, b_sk; // element (n, k) = B[n * b_sr + k * b_sk]; one of the two strides is 1
   const float *bias;               // [N] or null
   float *C; long c_sm, c_sn;       // C[m * c_sm + n * c_sn]
   float *C_ones;                   // row M of the output when a_ones (the bias gradient), indexed by n
@@ -509,56 +512,92 @@ struct SmallGemmArgs {
   int a_ones;                      // 1: A has one more row, m = M, that is constant 1 (then the grid covers M + 1 rows)
 };
 
+typedef float sg_f32x16 __attribute__((ext_vector_type(16)));
+#define SG_LD 33
+
+// 16-byte alignment of every vector the kernel loads: base pointers, the non-unit strides, K and (for operands whose
+// rows are the contiguous index) the row counts must be multiples of 4 floats
+static inline bool dense_small_gemm_fits(const SmallGemmArgs &a) {
+  auto al = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  const bool a_kc = a.a_sk == 1, b_kc = a.b_sk == 1;
+  if (!al(a.A) || !al(a.B) || a.K < 1 || ((a_kc || b_kc) && (a.K & 3) != 0)) return false;
+  if (a_kc ? (a.a_sr & 3) != 0 : (a.a_sr != 1 || (a.a_sk & 3) != 0 || (a.M & 3) != 0)) return false;
+  if (b_kc ? (a.b_sr & 3) != 0 : (a.b_sr != 1 || (a.b_sk & 3) != 0 || (a.N & 3) != 0)) return false;
+  return true;
+}
+
+// One operand slice: rows r0 .. r0 + 31 (R real rows, row R the constant 1 if ONES), k0 .. k0 + 31, as four 16-byte
+// items per lane.  KC: k is the contiguous index (item = row, four k); otherwise the row is (item = k, four rows).
+template <bool KC>
+__device__ __forceinline__ void sg_fetch(const float *P, long sr, long sk, int r0, int R, int K, int k0, int lane, float4 (&v)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int it = lane + 64 * q; // 256 items
+    if (KC) {
+      const int row = r0 + (it >> 3), k = k0 + 4 * (it & 7);
+      const bool ok = row < R && k < K;
+      v[q] = *reinterpret_cast<const float4 *>(P + (ok ? (long)row * sr + k : 0));
+    } else {
+      const int k = k0 + (it >> 3), row = r0 + 4 * (it & 7);
+      const bool ok = row + 3 < R + 0 && k < K; // (R is a multiple of 4: a group is inside or outside)
+      v[q] = *reinterpret_cast<const float4 *>(P + (ok ? (long)k * sk + row : 0));
+    }
+  }
+}
+template <bool KC>
+__device__ __forceinline__ void sg_stash(float *T, int r0, int R, bool ones, int K, int k0, int lane, const float4 (&v)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int it = lane + 64 * q;
+    float e[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+    if (KC) {
+      const int rl = it >> 3, kl = 4 * (it & 7), row = r0 + rl;
+      const bool ok = row < R && k0 + kl < K, one = ones && row == R && k0 + kl < K;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) T[(kl + j) * SG_LD + rl] = ok ? e[j] : (one ? 1.f : 0.f);
+    } else {
+      const int kl = it >> 3, rl = 4 * (it & 7), row = r0 + rl;
+      const bool kin = k0 + kl < K, ok = row + 3 < R && kin;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) T[kl * SG_LD + rl + j] = ok ? e[j] : ((ones && kin && row + j == R) ? 1.f : 0.f);
+    }
+  }
+}
+
+template <bool A_KC, bool B_KC>
 __global__ __launch_bounds__(256) void dense_small_gemm_kernel(const SmallGemmArgs a) {
-  __shared__ float red[4][32 * 32 + 32];
-  const int tid = threadIdx.x, lane = tid & 63, i16 = lane & 15, kq = lane >> 4;
+  __shared__ float stage[4][2 * 32 * SG_LD]; // per wave: A slice [k][m], B slice [k][n]
+  __shared__ float red[4][32 * 33];
+  const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
   const int Mtot = a.M + (a.a_ones ? 1 : 0);
-  // the wave's quarter of K, in whole k-steps of 4
-  const int ksteps = (a.K + 3) >> 2, per = (ksteps + 3) >> 2;
-  const int ks0 = wave * per, ks1 = min(ksteps, ks0 + per);
-  // per lane: two rows of A (blocks 0 / 1), two columns of B
-  long arow[2], brow[2];
-  bool aok[2], bok[2], aone[2];
+  float *As = stage[wave], *Bs = As + 32 * SG_LD;
+  const int n_slices = (a.K + 31) >> 5;
+  sg_f32x16 acc;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = m0 + 16 * i + i16, n = n0 + 16 * i + i16;
-    aok[i] = m < a.M; aone[i] = a.a_ones && m == a.M;
-    bok[i] = n < a.N;
-    arow[i] = aok[i] ? (long)m * a.a_sr : 0;
-    brow[i] = bok[i] ? (long)n * a.b_sr : 0;
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  float4 va[4], vb[4];
+  int sl = wave;
+  if (sl < n_slices) {
+    sg_fetch<A_KC>(a.A, a.a_sr, a.a_sk, m0, a.M, a.K, 32 * sl, lane, va);
+    sg_fetch<B_KC>(a.B, a.b_sr, a.b_sk, n0, a.N, a.K, 32 * sl, lane, vb);
   }
-  typedef float sg_f32x4 __attribute__((ext_vector_type(4)));
-  sg_f32x4 acc[2][2];
+  for (; sl < n_slices; sl += 4) {
+    sg_stash<A_KC>(As, m0, a.M, a.a_ones != 0, a.K, 32 * sl, lane, va);
+    sg_stash<B_KC>(Bs, n0, a.N, false, a.K, 32 * sl, lane, vb);
+    __builtin_amdgcn_wave_barrier(); // (the slice is read by other lanes of this wave: LDS operations of a wave complete in order)
+    const int nx = min(sl + 4, n_slices - 1); // (past the wave's last slice: one is read again, unused)
+    sg_fetch<A_KC>(a.A, a.a_sr, a.a_sk, m0, a.M, a.K, 32 * nx, lane, va);
+    sg_fetch<B_KC>(a.B, a.b_sr, a.b_sk, n0, a.N, a.K, 32 * nx, lane, vb);
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = (sg_f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-  for (int ks = ks0; ks < ks1; ++ks) {
-    const int k = 4 * ks + kq;
-    const bool kok = k < a.K;
-    const long ka = kok ? (long)k * a.a_sk : 0, kb = kok ? (long)k * a.b_sk : 0;
-    float av[2], bv[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const float x = a.A[arow[i] + ka], w = a.B[brow[i] + kb]; // always valid addresses
-      av[i] = kok ? (aok[i] ? x : (aone[i] ? 1.f : 0.f)) : 0.f;
-      bv[i] = (kok && bok[i]) ? w : 0.f;
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+    for (int s2 = 0; s2 < 16; ++s2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[(2 * s2 + lk) * SG_LD + li], Bs[(2 * s2 + lk) * SG_LD + li], acc, 0, 0, 0);
+    __builtin_amdgcn_wave_barrier();
   }
-  // the four quarter sums meet in LDS: element (m, n) of the tile at red[wave][m * 33 + n]
+  // the four partial tiles meet in LDS: accumulator register r of a lane is row 8 (r / 4) + 4 lk + r % 4, column li
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) red[wave][(16 * i + 4 * kq + r) * 33 + 16 * j + i16] = acc[i][j][r];
+  for (int r = 0; r < 16; ++r) red[wave][(8 * (r >> 2) + 4 * lk + (r & 3)) * 33 + li] = acc[r];
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
@@ -578,5 +617,9 @@ __global__ __launch_bounds__(256) void dense_small_gemm_kernel(const SmallGemmAr
 static inline void launch_dense_small_gemm(hipStream_t st, const SmallGemmArgs &a) {
   const int Mtot = a.M + (a.a_ones ? 1 : 0);
   dim3 grid((Mtot + 31) / 32, (a.N + 31) / 32), block(256);
-  hipLaunchKernelGGL(dense_small_gemm_kernel, grid, block, 0, st, a);
+  const bool a_kc = a.a_sk == 1, b_kc = a.b_sk == 1;
+  if (a_kc && b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, true>), grid, block, 0, st, a);
+  else if (a_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, false>), grid, block, 0, st, a);
+  else if (b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<false, true>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((dense_small_gemm_kernel<false, false>), grid, block, 0, st, a);
 }

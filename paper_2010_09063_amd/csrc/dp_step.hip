@@ -1061,18 +1061,18 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       const float *W = params + l.p_off;
       switch (l.d.kind) {
       case DP_DENSE: {
-        if (f2 && c->opt.small_gemm) {
+        if (f2 && !c->opt.no_small_gemm) {
           // the hidden layer's forward product, complete (bias and activation applied): K split inside the workgroup
-          // (off by default: with operands loaded lane by lane from memory it measured 35 us on 512 x 512 x 784
-          // against 16 us for the split-K contraction that stages float4 tiles in LDS)
           SmallGemmArgs g{};
           g.A = in; g.a_sr = l.d.in_features; g.a_sk = 1;
           g.B = W; g.b_sr = 1; g.b_sk = l.d.out_features;
           g.bias = W + (long)l.d.in_features * l.d.out_features; g.act = l.d.act;
           g.C = l.a; g.c_sm = l.d.out_features; g.c_sn = 1; g.C_ones = nullptr;
           g.M = B; g.N = l.d.out_features; g.K = l.d.in_features; g.a_ones = 0;
-          Ln(LL("dense_fwd"), dim3(1), dim3(256), [&](hipStream_t st) { launch_dense_small_gemm(st, g); });
-          break;
+          if (dense_small_gemm_fits(g)) {
+            Ln(LL("dense_fwd"), dim3(1), dim3(256), [&](hipStream_t st) { launch_dense_small_gemm(st, g); });
+            break;
+          }
         }
         if (l.fsplit > 1) {
           const long stride = (long)c->maxB * l.out_size;
@@ -1625,18 +1625,20 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       switch (l.d.kind) {
       case DP_DENSE: {
         if (f2 && i == 1) { nsplit = mid_tiles; break; } // its partials were written by dense2_mid_kernel
-        if (f2 && c->opt.small_gemm) {
+        if (f2 && !c->opt.no_small_gemm) {
           // X^T (s Delta) and the column sums of s Delta, complete in one partial row: K (= the batch) split inside
-          // the workgroup (off by default: 24 us against 13 us)
+          // the workgroup
           SmallGemmArgs g{};
           g.A = lin; g.a_sr = 1; g.a_sk = l.d.in_features; g.a_ones = 1;
           g.B = l.g; g.b_sr = 1; g.b_sk = l.d.out_features;
           g.bias = nullptr; g.act = DP_ACT_NONE;
           g.C = l.part; g.c_sm = l.d.out_features; g.c_sn = 1; g.C_ones = l.part + (long)l.d.in_features * l.d.out_features;
           g.M = l.d.in_features; g.N = l.d.out_features; g.K = B;
-          Ln(LL("dense_clipped_sum"), dim3(1), dim3(256), [&](hipStream_t st) { launch_dense_small_gemm(st, g); });
-          nsplit = 1;
-          break;
+          if (dense_small_gemm_fits(g)) {
+            Ln(LL("dense_clipped_sum"), dim3(1), dim3(256), [&](hipStream_t st) { launch_dense_small_gemm(st, g); });
+            nsplit = 1;
+            break;
+          }
         }
         auto run = [&](auto vt) {
           constexpr bool V = decltype(vt)::value;

@@ -33,7 +33,7 @@ class dp_model_desc(C.Structure):
 
 PLAN_OPTIONS = ("generic_conv", "no_minimal_filtering", "no_minimal_filtering_wgrad", "minimal_filtering_all",
                 "no_pool_fusion", "no_gram", "no_stored_gradients", "no_columns", "no_specialised_waves",
-                "specialised_waves_all", "conv_min_blocks", "gemm_plain_tiles", "no_fused_dense", "no_fused_cnn", "no_lstm_wgrad", "no_rows_gemm", "no_single_bucket", "small_gemm", "no_resident_weights", "no_side_stream", "no_first_layer_kernel")
+                "specialised_waves_all", "conv_min_blocks", "gemm_plain_tiles", "no_fused_dense", "no_fused_cnn", "no_lstm_wgrad", "no_rows_gemm", "no_single_bucket", "no_small_gemm", "no_resident_weights", "no_side_stream", "no_first_layer_kernel")
 
 
 class dp_plan_options(C.Structure):

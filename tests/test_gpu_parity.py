@@ -387,17 +387,20 @@ def test_two_layer_models_of_other_widths():
     forward product is split over K and one that is not; batches with a ragged last group and several groups per
     workgroup; then the same models on the generic kernels."""
     cases = ((7, 5, 3, "tanh", 9), (784, 512, 10, "relu", 37), (64, 1023, 10, "tanh", 6), (300, 50, 15, "relu", 1100),
-             (2000, 33, 2, "tanh", 70))
+             (2000, 33, 2, "tanh", 70),
+             # widths in whole groups of four floats take the kernel that splits K inside the workgroup: ragged 32 x 32
+             # tiles in both directions, K below one slice, K that ends inside a slice, K of several slices per wave
+             (100, 36, 4, "tanh", 70), (8, 4, 2, "relu", 5), (1000, 68, 10, "relu", 333))
     for d_in, H, k, act, batch in cases:
         m = W.model(W.image_input(d_in), [W.dense(d_in, H, act=act), W.dense(H, k)], k)
         x, y, theta = _case(m, batch, seed=H)
         _check_all_regimes(m, x, y, theta, f"dense {d_in}->{H}->{k}/{act}/B{batch}")
     wl = W.make_workload("cfg2_mlp", batch=77, seed=2, bias_scale=0.2)
     _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/generic kernels", options=dict(no_fused_dense=1))
-    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/K split inside the workgroup", options=dict(small_gemm=1))
+    _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], "cfg2/split-K contraction", options=dict(no_small_gemm=1))
     m = W.model(W.image_input(37), [W.dense(37, 45, act="tanh"), W.dense(45, 3)], 3)
     x, y, theta = _case(m, 70, seed=5)
-    _check_all_regimes(m, x, y, theta, "dense 37->45->3/K split inside the workgroup", options=dict(small_gemm=1))
+    _check_all_regimes(m, x, y, theta, "dense 37->45->3/split-K contraction", options=dict(no_small_gemm=1))
 
 
 def test_small_cnn_layer_by_layer_and_fused():
