@@ -564,15 +564,15 @@ __device__ __forceinline__ void sg_stash(float *T, int r0, int R, bool ones, int
   }
 }
 
-template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(256) void dense_small_gemm_kernel(const SmallGemmArgs a) {
-  __shared__ float stage[4][2 * 32 * SG_LD]; // per wave: A slice [k][m], B slice [k][n]
-  __shared__ float red[4][32 * 33];
+// NW waves per workgroup (the K split); LDS: NW areas of 2 x 32 x 33 floats, passed as dynamic shared memory
+template <bool A_KC, bool B_KC, int NW>
+__global__ __launch_bounds__(64 * NW) void dense_small_gemm_kernel(const SmallGemmArgs a) {
+  extern __shared__ float sg_lds[]; // per wave: A slice [k][m], B slice [k][n]; after the K loop: the wave's partial tile
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
   const int Mtot = a.M + (a.a_ones ? 1 : 0);
-  float *As = stage[wave], *Bs = As + 32 * SG_LD;
+  float *As = sg_lds + wave * (2 * 32 * SG_LD), *Bs = As + 32 * SG_LD;
   const int n_slices = (a.K + 31) >> 5;
   sg_f32x16 acc;
 #pragma unroll
@@ -583,11 +583,11 @@ __global__ __launch_bounds__(256) void dense_small_gemm_kernel(const SmallGemmAr
     sg_fetch<A_KC>(a.A, a.a_sr, a.a_sk, m0, a.M, a.K, 32 * sl, lane, va);
     sg_fetch<B_KC>(a.B, a.b_sr, a.b_sk, n0, a.N, a.K, 32 * sl, lane, vb);
   }
-  for (; sl < n_slices; sl += 4) {
+  for (; sl < n_slices; sl += NW) {
     sg_stash<A_KC>(As, m0, a.M, a.a_ones != 0, a.K, 32 * sl, lane, va);
     sg_stash<B_KC>(Bs, n0, a.N, false, a.K, 32 * sl, lane, vb);
     __builtin_amdgcn_wave_barrier(); // (the slice is read by other lanes of this wave: LDS operations of a wave complete in order)
-    const int nx = min(sl + 4, n_slices - 1); // (past the wave's last slice: one is read again, unused)
+    const int nx = min(sl + NW, n_slices - 1); // (past the wave's last slice: one is read again, unused)
     sg_fetch<A_KC>(a.A, a.a_sr, a.a_sk, m0, a.M, a.K, 32 * nx, lane, va);
     sg_fetch<B_KC>(a.B, a.b_sr, a.b_sk, n0, a.N, a.K, 32 * nx, lane, vb);
 #pragma unroll
@@ -595,31 +595,52 @@ __global__ __launch_bounds__(256) void dense_small_gemm_kernel(const SmallGemmAr
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[(2 * s2 + lk) * SG_LD + li], Bs[(2 * s2 + lk) * SG_LD + li], acc, 0, 0, 0);
     __builtin_amdgcn_wave_barrier();
   }
-  // the four partial tiles meet in LDS: accumulator register r of a lane is row 8 (r / 4) + 4 lk + r % 4, column li
+  // the partial tiles meet in LDS, each in its wave's own area (the wave is done with its slices): accumulator
+  // register r of a lane is row 8 (r / 4) + 4 lk + r % 4, column li
 #pragma unroll
-  for (int r = 0; r < 16; ++r) red[wave][(8 * (r >> 2) + 4 * lk + (r & 3)) * 33 + li] = acc[r];
+  for (int r = 0; r < 16; ++r) As[(8 * (r >> 2) + 4 * lk + (r & 3)) * SG_LD + li] = acc[r];
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int e = tid + 256 * q, ml = e >> 5, nl = e & 31; // consecutive threads: consecutive n
+  for (int q = 0; q < 16 / NW; ++q) {
+    const int e = tid + 64 * NW * q, ml = e >> 5, nl = e & 31; // consecutive threads: consecutive n
     const int m = m0 + ml, n = n0 + nl;
     if (m < Mtot && n < a.N) {
-      const int o = ml * 33 + nl;
-      float v = (red[0][o] + red[1][o]) + (red[2][o] + red[3][o]);
-      if (a.bias) v += a.bias[n];
-      v = act_apply(a.act, v);
-      if (m < a.M) a.C[(long)m * a.c_sm + (long)n * a.c_sn] = v;
-      else a.C_ones[n] = v;
+      const float *rp = sg_lds + ml * SG_LD + nl;
+      float v[NW];
+#pragma unroll
+      for (int w = 0; w < NW; ++w) v[w] = rp[w * (2 * 32 * SG_LD)];
+#pragma unroll
+      for (int h = 1; h < NW; h *= 2) // a fixed tree: (0+1) + (2+3) ...
+#pragma unroll
+        for (int w = 0; w + h < NW; w += 2 * h) v[w] += v[w + h];
+      float r = v[0];
+      if (a.bias) r += a.bias[n];
+      r = act_apply(a.act, r);
+      if (m < a.M) a.C[(long)m * a.c_sm + (long)n * a.c_sn] = r;
+      else a.C_ones[n] = r;
     }
   }
 }
 
+#define SG_WAVES 8
+static inline size_t dense_small_gemm_lds_bytes() { return sizeof(float) * SG_WAVES * 2 * 32 * SG_LD; }
+// once per device before the first launch (the LDS areas of eight waves exceed the default 64 KB limit)
+static inline bool dense_small_gemm_prepare() {
+  const int bytes = (int)dense_small_gemm_lds_bytes();
+  const hipFuncAttribute at = hipFuncAttributeMaxDynamicSharedMemorySize;
+  return hipFuncSetAttribute((const void *)dense_small_gemm_kernel<true, true, SG_WAVES>, at, bytes) == hipSuccess &&
+         hipFuncSetAttribute((const void *)dense_small_gemm_kernel<true, false, SG_WAVES>, at, bytes) == hipSuccess &&
+         hipFuncSetAttribute((const void *)dense_small_gemm_kernel<false, true, SG_WAVES>, at, bytes) == hipSuccess &&
+         hipFuncSetAttribute((const void *)dense_small_gemm_kernel<false, false, SG_WAVES>, at, bytes) == hipSuccess;
+}
+
 static inline void launch_dense_small_gemm(hipStream_t st, const SmallGemmArgs &a) {
   const int Mtot = a.M + (a.a_ones ? 1 : 0);
-  dim3 grid((Mtot + 31) / 32, (a.N + 31) / 32), block(256);
+  dim3 grid((Mtot + 31) / 32, (a.N + 31) / 32), block(64 * SG_WAVES);
+  const size_t lds = dense_small_gemm_lds_bytes();
   const bool a_kc = a.a_sk == 1, b_kc = a.b_sk == 1;
-  if (a_kc && b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, true>), grid, block, 0, st, a);
-  else if (a_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, false>), grid, block, 0, st, a);
-  else if (b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<false, true>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((dense_small_gemm_kernel<false, false>), grid, block, 0, st, a);
+  if (a_kc && b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, true, SG_WAVES>), grid, block, lds, st, a);
+  else if (a_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, false, SG_WAVES>), grid, block, lds, st, a);
+  else if (b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<false, true, SG_WAVES>), grid, block, lds, st, a);
+  else hipLaunchKernelGGL((dense_small_gemm_kernel<false, false, SG_WAVES>), grid, block, lds, st, a);
 }

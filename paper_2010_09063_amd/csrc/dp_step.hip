@@ -703,6 +703,10 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
   }
   c->fused2 = c->L.size() == 2 && c->L[0].d.kind == DP_DENSE && c->L[1].d.kind == DP_DENSE &&
               dense1_fits(c->L[1].d.in_features, c->L[1].d.out_features) && !c->opt.no_fused_dense;
+  if (c->fused2 && !c->opt.no_small_gemm && !dense_small_gemm_prepare()) { // its LDS size refused: the tiled contraction
+    (void)hipGetLastError();
+    c->opt.no_small_gemm = 1;
+  }
   if (rc == DP_OK && !c->L.empty() && c->L[0].d.kind == DP_EMBEDDING && !c->opt.no_side_stream) {
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||

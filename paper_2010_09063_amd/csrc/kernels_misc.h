@@ -484,9 +484,10 @@ __device__ __forceinline__ void normal4(uint64_t blk, uint32_t k0, uint32_t k1, 
 
 // Final write (DPSGD item 3): out[j] = sum over split-K partials of the clipped sum + sigma*C*z_j.
 // A thread owns the four coordinates of one Philox block (all four normals of the block are used, 16-byte loads
-// and stores where the rows allow); a workgroup owns 256 / SG blocks and splits the partial rows SG ways (4 for
-// long parameter vectors, 16 for short ones, which would otherwise leave most CUs without a workgroup), so a
-// tensor cut into many splits is still reduced with short dependent chains.  Every sum runs in a fixed order.
+// and stores where the rows allow).  The parameter vector is cut into regions of consecutive tensors whose partial
+// rows are summed the same way: a workgroup of a region owns 256 / SG blocks and splits the partial rows SG ways
+// -- 16 for tensors cut into many splits (short dependent chains), 4 for a few rows, 1 (every lane draws noise, no
+// LDS pass) where a tensor arrives complete.  Every sum runs in a fixed order.
 #define DP_MAX_SEG 24
 struct FinalizeSeg {
   long p_off, n;     // segment [p_off, p_off + n) of the flat parameter vector
@@ -494,25 +495,33 @@ struct FinalizeSeg {
   long stride;
   int nsplit;
 };
+struct FinalizeRegion {
+  long blk0, blk1; // Philox blocks [blk0, blk1): those whose first coordinate lies in the region's tensors
+  int wg0;         // first workgroup of the region
+  int sg;          // split groups of its workgroups: 1, 4 or 16
+  int seg0;        // first tensor of the region
+};
 struct FinalizeArgs {
   int nseg;
   FinalizeSeg seg[DP_MAX_SEG];
+  int nreg;
+  FinalizeRegion reg[DP_MAX_SEG];
 };
 
 // theta != null: the parameter update of DPSGD item 4 is fused into the same write,
 // theta[j] -= step * (sum + noise) with step = learning rate / batch; out may then be null.
 template <int DP_FIN_SG>
-__global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P,
-                                                        float noise_std, uint32_t k0, uint32_t k1,
-                                                        float *__restrict__ theta, float step) {
+__device__ __forceinline__ void finalize_body(const FinalizeArgs &fa, const FinalizeRegion &rg, float4 *red,
+                                              float *__restrict__ out, long P, float noise_std, uint32_t k0, uint32_t k1,
+                                              float *__restrict__ theta, float step) {
   constexpr int DP_FIN_BLK = 256 / DP_FIN_SG;
-  __shared__ float4 red[DP_FIN_SG - 1][DP_FIN_BLK];
   const int cb = threadIdx.x & (DP_FIN_BLK - 1);
   const int sg = threadIdx.x / DP_FIN_BLK;
-  const long blk = (long)blockIdx.x * DP_FIN_BLK + cb, j0 = blk * 4;
+  const long blk = rg.blk0 + (long)((int)blockIdx.x - rg.wg0) * DP_FIN_BLK + cb, j0 = blk * 4;
+  const bool live = blk < rg.blk1; // (blk1 * 4 < P + 4: a live block has at least one coordinate)
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  if (j0 < P) {
-    int si = 0;
+  if (live) {
+    int si = rg.seg0;
     while (si < fa.nseg - 1 && j0 >= fa.seg[si].p_off + fa.seg[si].n) ++si;
     const FinalizeSeg &g = fa.seg[si];
     const float *p = g.part + (j0 - g.p_off);
@@ -557,12 +566,14 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, fl
       }
     }
   }
-  if (sg > 0) red[sg - 1][cb] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-  __syncthreads();
-  if (sg == 0 && j0 < P) {
+  if (DP_FIN_SG > 1) {
+    if (sg > 0) red[(sg - 1) * DP_FIN_BLK + cb] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    __syncthreads();
+  }
+  if (sg == 0 && live) {
 #pragma unroll
     for (int q = 0; q < DP_FIN_SG - 1; ++q) {
-      const float4 v = red[q][cb];
+      const float4 v = red[q * DP_FIN_BLK + cb];
       acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
     if (noise_std > 0.f) {
@@ -589,14 +600,44 @@ __global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, fl
   }
 }
 
-// The launch: sixteen split groups (64 coordinates per workgroup) where a tensor has many partial rows or the
-// vector is short, four (256 coordinates) otherwise.
-static inline void launch_finalize(hipStream_t st, const FinalizeArgs &fa, float *out, long P, float noise_std, uint32_t k0,
+__global__ __launch_bounds__(256) void finalize_kernel(const FinalizeArgs fa, float *__restrict__ out, long P,
+                                                        float noise_std, uint32_t k0, uint32_t k1,
+                                                        float *__restrict__ theta, float step) {
+  __shared__ float4 red[240];
+  int r = 0;
+  while (r < fa.nreg - 1 && (int)blockIdx.x >= fa.reg[r + 1].wg0) ++r; // (the same for the whole workgroup)
+  const FinalizeRegion &rg = fa.reg[r];
+  if (rg.sg == 16) finalize_body<16>(fa, rg, red, out, P, noise_std, k0, k1, theta, step);
+  else if (rg.sg == 4) finalize_body<4>(fa, rg, red, out, P, noise_std, k0, k1, theta, step);
+  else finalize_body<1>(fa, rg, red, out, P, noise_std, k0, k1, theta, step);
+}
+
+// The launch: the regions (runs of tensors that take the same number of split groups) and their workgroups.  The
+// tensors of fa lie one after the other in [0, P).  Sixteen split groups (64 coordinates per workgroup) where a
+// tensor has many partial rows, or a few in a short vector (which would otherwise leave most CUs without a
+// workgroup); four for a few rows; one (1,024 coordinates) for a tensor that arrives in at most two rows.
+static inline void launch_finalize(hipStream_t st, FinalizeArgs &fa, float *out, long P, float noise_std, uint32_t k0,
                                    uint32_t k1, float *theta, float step) {
-  int max_ns = 0;
-  for (int i = 0; i < fa.nseg; ++i) max_ns = fa.seg[i].nsplit > max_ns ? fa.seg[i].nsplit : max_ns;
-  const int co = (P < 100000 || max_ns > 24) ? 64 : 256;
-  dim3 grid((unsigned)((P + co - 1) / co)), block(256);
-  if (co == 64) hipLaunchKernelGGL(finalize_kernel<16>, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);
-  else hipLaunchKernelGGL(finalize_kernel<4>, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);
+  fa.nreg = 0;
+  int wg = 0;
+  for (int i = 0; i < fa.nseg; ++i) {
+    const FinalizeSeg &g = fa.seg[i];
+    const int ns = g.nsplit;
+    const int sg = (ns >= 24 || (P < 100000 && ns >= 3)) ? 16 : ns >= 3 ? 4 : 1;
+    const long b0 = (g.p_off + 3) / 4, b1 = i == fa.nseg - 1 ? (P + 3) / 4 : (g.p_off + g.n + 3) / 4;
+    if (fa.nreg > 0 && fa.reg[fa.nreg - 1].sg == sg) { fa.reg[fa.nreg - 1].blk1 = b1; continue; }
+    if (fa.nreg > 0) {
+      const FinalizeRegion &q = fa.reg[fa.nreg - 1];
+      wg += (int)((q.blk1 - q.blk0 + 256 / q.sg - 1) / (256 / q.sg));
+    }
+    FinalizeRegion &r = fa.reg[fa.nreg++];
+    r.blk0 = fa.nreg == 1 ? 0 : b0; r.blk1 = b1; r.wg0 = wg; r.sg = sg; r.seg0 = i;
+  }
+  if (fa.nreg > 0) {
+    const FinalizeRegion &q = fa.reg[fa.nreg - 1];
+    wg += (int)((q.blk1 - q.blk0 + 256 / q.sg - 1) / (256 / q.sg));
+  }
+  if (wg == 0) return;
+  dim3 grid((unsigned)wg), block(256);
+  hipLaunchKernelGGL(finalize_kernel, grid, block, 0, st, fa, out, P, noise_std, k0, k1, theta, step);
 }
