@@ -47,9 +47,9 @@ def label_work(m, B, plan=None):
     cur = ("chw", inp["c"], inp["h"], inp["w"]) if inp["kind"] == "image" else ("tok", inp["seq_len"])
     out = {}
 
-    def add(label, flops, nbytes, executed=None):
+    def add(label, flops, nbytes, executed=None, layer=None):
         ex = flops if executed is None else executed
-        for key in (label, f"{label}#{li}"):   # per kernel kind and per (kind, layer)
+        for key in (label, f"{label}#{li if layer is None else layer}"):   # per kernel kind and per (kind, layer)
             f, b, e = out.get(key, (0.0, 0.0, 0.0))
             out[key] = (f + flops, b + nbytes, e + ex)
 
@@ -76,7 +76,12 @@ def label_work(m, B, plan=None):
             fl = 2.0 * B * di * do
             if r.get("fwd") == "fused" and li == 0:   # one-layer model: forward, loss, norm, clip factor and partial sums in one launch
                 add("dense1_fused", 2 * fl + 2.0 * B * (di + do), 4.0 * (B * di + di * do + (B // 4) * (di + 1) * do))
-            elif r.get("fwd") == "fused":  # logit layer of a two-layer model: forward, backward-data, both norms, partial sums
+            elif r.get("fwd") == "fused" and r.get("sum") == "joint":
+                # logit layer of a two-layer model: forward, backward-data and both norms in one launch; its clipped
+                # sum rides in the hidden layer's launch (s * delta in rows of 16 floats)
+                add("dense2_mid", 2 * fl + 2.0 * B * (di + do), 4.0 * (3 * B * di + di * do + 16 * B))
+                add("dense_clipped_sum", fl, 4.0 * (B * di + 16 * B + di * do), layer=li - 1)
+            elif r.get("fwd") == "fused":  # the same with the logit layer's partial clipped sums written by that launch
                 add("dense2_mid", 3 * fl + 2.0 * B * (di + do), 4.0 * (3 * B * di + di * do + (B // 4) * (di + 1) * do))
             elif r.get("norm") == "fused":  # hidden layer of the same model: its two batch-wide contractions remain
                 add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))

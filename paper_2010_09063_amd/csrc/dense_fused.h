@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <algorithm>
 
 #include "gemm_tile.h" // FastDiv
 #include "kernels_misc.h" // act_apply, act_deriv_from_out
@@ -262,10 +263,13 @@ struct Dense2Args {
   // norm), so the kernel stops after phase C: it leaves both layers' squared norms in their slots, delta1 unscaled in
   // sdelta1, the hidden activations in a1_out (when they arrived as partials) and delta2 in delta2_out for the
   // clipped sums that follow once the clip factors exist.
+  // head = 2: a two-layer network whose logit layer's clipped sum is a contraction of its own, like the hidden
+  // layer's: the kernel stops after phase C as well, with the clip factor applied: s * delta1 in sdelta1 and
+  // s * delta2 in delta2_out, in rows of 16 floats (zero beyond N).
   int head;
   float *slot1, *slot2; // [B] squared norms of the hidden / logit layer's gradient (may be null)
   float *a1_out;        // [B][H] or null
-  float *delta2_out;    // [B][N]
+  float *delta2_out;    // [B][N] (head = 1), [B][16] (head = 2)
 };
 
 template <int NCP>
@@ -287,6 +291,23 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
 #pragma unroll
   for (int j = 0; j < NCP; ++j) acc[j] = 0.f;
 
+  // What a group reads from memory -- its rows of the hidden layer's output and of x, its labels -- is requested one
+  // group ahead (the first group's before W2 is staged), so that no phase starts with a round trip to memory.
+  float hp[4], xv[4];
+  int yv;
+  auto request = [&](int grp, float (&hp_)[4], float (&xv_)[4], int &yv_) {
+    const int b0 = (blockIdx.x * a.groups + grp) * DENSE1_EX, hh = tid0 & 255;
+    const int bq = min(b0 + q, a.B - 1);
+    const float *hr = a.hpart + (long)bq * H, *xr = a.x + (long)bq * d_in;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int h = hh + 256 * i;
+      hp_[i] = hr[h < H ? h : 0];
+      xv_[i] = xr[h < d_in ? h : 0];
+    }
+    yv_ = a.y[min(b0 + ((tid0 & 63) >> 4), a.B - 1)];
+  };
+  request(0, hp, xv, yv);
   const float bv = a.b2[tid0 < N ? tid0 : 0];
   {
     const int w_total = H * N;
@@ -328,9 +349,9 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
     float a1v[4];
     {
       const long row = (long)(vq ? bq : 0) * H;
-      float pre[4] = {0.f, 0.f, 0.f, 0.f};
       if (a.ns > 0) {
-        for (int s = 0; s < a.ns; ++s) {
+        float pre[4] = {hp[0], hp[1], hp[2], hp[3]}; // (partial 0; the sum runs in the order of the partials)
+        for (int s = 1; s < a.ns; ++s) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int h = hh + 256 * i;
@@ -341,10 +362,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
         for (int i = 0; i < 4; ++i) a1v[i] = act_apply(a.act, pre[i] + b1v[i]);
       } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int h = hh + 256 * i;
-          a1v[i] = a.hpart[row + (h < H ? h : 0)];
-        }
+        for (int i = 0; i < 4; ++i) a1v[i] = hp[i];
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -354,9 +372,13 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
     }
     float sx = 0.f;
     {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sx = fmaf(hh + 256 * i < d_in ? xv[i] : 0.f, xv[i], sx);
       const float *xr = a.x + (long)(vq ? bq : 0) * d_in;
-      for (int k = hh; k < d_in; k += 256) { const float v = xr[k]; sx = fmaf(v, v, sx); }
+      for (int k = hh + 1024; k < d_in; k += 256) { const float v = xr[k]; sx = fmaf(v, v, sx); }
     }
+    const int yy = yv;
+    if (grp + 1 < a.groups) request(grp + 1, hp, xv, yv);
     __syncthreads();
     // ---- B. logits (partial dot products over the wave's sixteenth of the hidden units)
     {
@@ -386,7 +408,6 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
       float se = ex;
 #pragma unroll
       for (int o = 8; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
-      const int yy = a.y[valid ? b : 0];
       const float dv = ex / se - (jj == yy ? 1.f : 0.f);
       float sd = dv * dv;
 #pragma unroll
@@ -424,8 +445,9 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
       const float sd1 = (red[w0 * 2] + red[w0 * 2 + 2]) + (red[w0 * 2 + 4] + red[w0 * 2 + 6]);
       const float sxx = (red[w0 * 2 + 1] + red[w0 * 2 + 3]) + (red[w0 * 2 + 5] + red[w0 * 2 + 7]);
       const float n = sqrtf((sxx + 1.f) * sd1 + n2s[q]);
-      sc = (a.priv && !a.head) ? fminf(1.f, a.C / n) : 1.f; // n == 0: C/0 = +inf -> 1
-      if (a.head) {
+      sc = (a.priv && a.head != 1) ? fminf(1.f, a.C / n) : 1.f; // n == 0: C/0 = +inf -> 1
+      if (a.head == 2 && vq && hh < 16) a.delta2_out[(long)bq * 16 + hh] = sc * d2[q * 16 + hh];
+      if (a.head == 1) {
         if (vq && hh == 0) {
           if (a.slot1) a.slot1[bq] = (sxx + 1.f) * sd1;
           if (a.slot2) a.slot2[bq] = n2s[q];
@@ -515,14 +537,15 @@ struct SmallGemmArgs {
 typedef float sg_f32x16 __attribute__((ext_vector_type(16)));
 #define SG_LD 33
 
-// 16-byte alignment of every vector the kernel loads: base pointers, the non-unit strides, K and (for operands whose
-// rows are the contiguous index) the row counts must be multiples of 4 floats
+// 16-byte alignment of every vector the kernel loads: base pointers, the non-unit strides and K must be multiples of
+// 4 floats; an operand whose rows are the contiguous index has a row count that is one too, or rows of memory padded
+// to the next multiple (its k stride covers it), so that the last group of four may be read whole
 static inline bool dense_small_gemm_fits(const SmallGemmArgs &a) {
   auto al = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   const bool a_kc = a.a_sk == 1, b_kc = a.b_sk == 1;
   if (!al(a.A) || !al(a.B) || a.K < 1 || ((a_kc || b_kc) && (a.K & 3) != 0)) return false;
-  if (a_kc ? (a.a_sr & 3) != 0 : (a.a_sr != 1 || (a.a_sk & 3) != 0 || (a.M & 3) != 0)) return false;
-  if (b_kc ? (a.b_sr & 3) != 0 : (a.b_sr != 1 || (a.b_sk & 3) != 0 || (a.N & 3) != 0)) return false;
+  if (a_kc ? (a.a_sr & 3) != 0 : (a.a_sr != 1 || (a.a_sk & 3) != 0 || a.a_sk < ((a.M + 3) & ~3))) return false;
+  if (b_kc ? (a.b_sr & 3) != 0 : (a.b_sr != 1 || (a.b_sk & 3) != 0 || a.b_sk < ((a.N + 3) & ~3))) return false;
   return true;
 }
 
@@ -539,7 +562,7 @@ __device__ __forceinline__ void sg_fetch(const float *P, long sr, long sk, int r
       v[q] = *reinterpret_cast<const float4 *>(P + (ok ? (long)row * sr + k : 0));
     } else {
       const int k = k0 + (it >> 3), row = r0 + 4 * (it & 7);
-      const bool ok = row + 3 < R + 0 && k < K; // (R is a multiple of 4: a group is inside or outside)
+      const bool ok = row < R && k < K; // (a group that crosses R reads the row's padding: see dense_small_gemm_fits)
       v[q] = *reinterpret_cast<const float4 *>(P + (ok ? (long)k * sk + row : 0));
     }
   }
@@ -557,21 +580,26 @@ __device__ __forceinline__ void sg_stash(float *T, int r0, int R, bool ones, int
       for (int j = 0; j < 4; ++j) T[(kl + j) * SG_LD + rl] = ok ? e[j] : (one ? 1.f : 0.f);
     } else {
       const int kl = it >> 3, rl = 4 * (it & 7), row = r0 + rl;
-      const bool kin = k0 + kl < K, ok = row + 3 < R && kin;
+      const bool kin = k0 + kl < K;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) T[kl * SG_LD + rl + j] = ok ? e[j] : ((ones && kin && row + j == R) ? 1.f : 0.f);
+      for (int j = 0; j < 4; ++j) T[kl * SG_LD + rl + j] = (kin && row + j < R) ? e[j] : ((ones && kin && row + j == R) ? 1.f : 0.f);
     }
   }
 }
 
 // NW waves per workgroup (the K split); LDS: NW areas of 2 x 32 x 33 floats, passed as dynamic shared memory
+// A launch may carry a second product of the same operand layouts (the two clipped sums of a two-layer network):
+// rows ny0 and up of the grid are its tiles.
 template <bool A_KC, bool B_KC, int NW>
-__global__ __launch_bounds__(64 * NW) void dense_small_gemm_kernel(const SmallGemmArgs a) {
+__global__ __launch_bounds__(64 * NW) void dense_small_gemm_kernel(const SmallGemmArgs p0, const SmallGemmArgs p1, int ny0) {
   extern __shared__ float sg_lds[]; // per wave: A slice [k][m], B slice [k][n]; after the K loop: the wave's partial tile
   const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lk = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int m0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+  const bool second = (int)blockIdx.y >= ny0;
+  const SmallGemmArgs &a = second ? p1 : p0;
+  const int m0 = blockIdx.x * 32, n0 = ((int)blockIdx.y - (second ? ny0 : 0)) * 32;
   const int Mtot = a.M + (a.a_ones ? 1 : 0);
+  if (m0 >= Mtot) return; // (the grid is as wide as the larger of the two products; uniform, before any barrier)
   float *As = sg_lds + wave * (2 * 32 * SG_LD), *Bs = As + 32 * SG_LD;
   const int n_slices = (a.K + 31) >> 5;
   sg_f32x16 acc;
@@ -634,13 +662,16 @@ static inline bool dense_small_gemm_prepare() {
          hipFuncSetAttribute((const void *)dense_small_gemm_kernel<false, false, SG_WAVES>, at, bytes) == hipSuccess;
 }
 
-static inline void launch_dense_small_gemm(hipStream_t st, const SmallGemmArgs &a) {
-  const int Mtot = a.M + (a.a_ones ? 1 : 0);
-  dim3 grid((Mtot + 31) / 32, (a.N + 31) / 32), block(64 * SG_WAVES);
+// b: a second product in the same launch, or null; both must have the same contiguous indices
+static inline void launch_dense_small_gemm(hipStream_t st, const SmallGemmArgs &a, const SmallGemmArgs *b = nullptr) {
+  const int Mtot = a.M + (a.a_ones ? 1 : 0), Mtot2 = b ? b->M + (b->a_ones ? 1 : 0) : 0;
+  const int ny0 = (a.N + 31) / 32, ny1 = b ? (b->N + 31) / 32 : 0;
+  dim3 grid((std::max(Mtot, Mtot2) + 31) / 32, ny0 + ny1), block(64 * SG_WAVES);
   const size_t lds = dense_small_gemm_lds_bytes();
   const bool a_kc = a.a_sk == 1, b_kc = a.b_sk == 1;
-  if (a_kc && b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, true, SG_WAVES>), grid, block, lds, st, a);
-  else if (a_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, false, SG_WAVES>), grid, block, lds, st, a);
-  else if (b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<false, true, SG_WAVES>), grid, block, lds, st, a);
-  else hipLaunchKernelGGL((dense_small_gemm_kernel<false, false, SG_WAVES>), grid, block, lds, st, a);
+  const SmallGemmArgs &a2 = b ? *b : a;
+  if (a_kc && b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, true, SG_WAVES>), grid, block, lds, st, a, a2, ny0);
+  else if (a_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<true, false, SG_WAVES>), grid, block, lds, st, a, a2, ny0);
+  else if (b_kc) hipLaunchKernelGGL((dense_small_gemm_kernel<false, true, SG_WAVES>), grid, block, lds, st, a, a2, ny0);
+  else hipLaunchKernelGGL((dense_small_gemm_kernel<false, false, SG_WAVES>), grid, block, lds, st, a, a2, ny0);
 }

@@ -203,6 +203,7 @@ struct dp_ctx {
   uint32_t *xb = nullptr; int *yb = nullptr, *idx = nullptr; // dp_step_loop: the drawn minibatch (allocated on its first call)
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   bool fusedcnn = false; float *cnn_part = nullptr; // the small MNIST-shaped CNN in one launch (cnn_small_fused_kernel)
+  bool joint2 = false; // fused2 and both clipped sums in one dense_small_gemm_kernel launch
   bool fused2 = false; // two dense layers: everything between the hidden layer's forward product and the clipped sums in dense2_mid_kernel
   // The embedding layer's counting sort of the batch's tokens depends on the inputs alone: it runs on a stream of the
   // library's own (fork / join by events) beside the forward pass.
@@ -707,6 +708,8 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
     (void)hipGetLastError();
     c->opt.no_small_gemm = 1;
   }
+  // both clipped sums of the two-layer network in one launch of that kernel (widths in whole groups of four floats)
+  c->joint2 = c->fused2 && !c->opt.no_small_gemm && c->L[0].d.in_features % 4 == 0 && c->L[0].d.out_features % 4 == 0;
   if (rc == DP_OK && !c->L.empty() && c->L[0].d.kind == DP_EMBEDDING && !c->opt.no_side_stream) {
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
@@ -729,7 +732,7 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
     if (rc != DP_OK) break;
     const bool emb = l.d.kind == DP_EMBEDDING;
     rc = dev_alloc(c, &l.a, mb * l.out_size); // embedding: the gathered rows x[B, T, D]
-    if (rc == DP_OK) rc = dev_alloc(c, &l.g, mb * l.out_size);
+    if (rc == DP_OK) rc = dev_alloc(c, &l.g, mb * std::max<long>(l.out_size, &l == &c->L.back() ? 16 : 0)); // (the loss gradient: rows of up to 16 floats)
     if (rc == DP_OK && l.d.kind == DP_MAXPOOL2D) rc = dev_alloc(c, &l.arg, mb * l.out_size);
     if (rc == DP_OK && l.p_count > 0) {
       l.max_split = 1;
@@ -1059,6 +1062,8 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
     const bool no_pool_fusion = c->opt.no_pool_fusion != 0;
     const bool f2 = c->fused2, h2 = c->head2;
     int mid_ns = 0, mid_tiles = 0;
+    SmallGemmArgs joint_g[2] = {};
+    bool joint = false;
     for (int i = 0; i < nL; ++i) {
       if ((f2 && i == 1) || (h2 && i == nL - 1)) break; // the logits are computed by the kernel that follows the hidden layer
       Layer &l = c->L[i];
@@ -1274,6 +1279,21 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       a.sdelta1 = l0.g; a.part2 = l1.part; a.norms = priv ? c->norms : nullptr; a.s = priv ? c->s : nullptr;
       a.B = B; a.d_in = l0.d.in_features; a.H = l1.d.in_features; a.N = l1.d.out_features; a.act = l0.d.act;
       a.C = C; a.priv = priv ? 1 : 0;
+      if (c->joint2 && mid_ns == 0) {
+        // X^T (s Delta1) and a1^T (s Delta2), each with the column sums of its s Delta (the row of ones): complete in
+        // one partial row, K (= the batch) split inside the workgroup
+        SmallGemmArgs &g0 = joint_g[0], &g1 = joint_g[1];
+        g0.A = (const float *)x; g0.a_sr = 1; g0.a_sk = l0.d.in_features; g0.a_ones = 1;
+        g0.B = l0.g; g0.b_sr = 1; g0.b_sk = l0.d.out_features;
+        g0.C = l0.part; g0.c_sm = l0.d.out_features; g0.c_sn = 1; g0.C_ones = l0.part + (long)l0.d.in_features * l0.d.out_features;
+        g0.M = l0.d.in_features; g0.N = l0.d.out_features; g0.K = B; g0.act = DP_ACT_NONE;
+        g1.A = l0.a; g1.a_sr = 1; g1.a_sk = l1.d.in_features; g1.a_ones = 1;
+        g1.B = l1.g; g1.b_sr = 1; g1.b_sk = 16;
+        g1.C = l1.part; g1.c_sm = l1.d.out_features; g1.c_sn = 1; g1.C_ones = l1.part + (long)l1.d.in_features * l1.d.out_features;
+        g1.M = l1.d.in_features; g1.N = l1.d.out_features; g1.K = B; g1.act = DP_ACT_NONE;
+        joint = dense_small_gemm_fits(g0) && dense_small_gemm_fits(g1);
+        if (joint) { a.head = 2; a.delta2_out = l1.g; a.part2 = nullptr; }
+      }
       Ln("dense2_mid", dim3(1), dim3(256), [&](hipStream_t st) {
         mid_tiles = launch_dense2_mid(st, a, std::min(DENSE1_MAX_TILES, l1.max_split));
       });
@@ -1628,6 +1648,12 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       int nsplit = 1;
       switch (l.d.kind) {
       case DP_DENSE: {
+        if (joint) {
+          if (i == 0)
+            Ln(LL("dense_clipped_sum"), dim3(1), dim3(256), [&](hipStream_t st) { launch_dense_small_gemm(st, joint_g[0], &joint_g[1]); });
+          nsplit = 1;
+          break;
+        }
         if (f2 && i == 1) { nsplit = mid_tiles; break; } // its partials were written by dense2_mid_kernel
         if (f2 && !c->opt.no_small_gemm) {
           // X^T (s Delta) and the column sums of s Delta, complete in one partial row: K (= the batch) split inside
@@ -1923,7 +1949,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
     case DP_DENSE:
       fwd = c->fused1 ? "fused" : "generic"; bwd = i > 0 ? "generic" : "-";
       norm = c->fused1 ? "fused" : "identity"; sum = c->fused1 ? "fused" : "generic";
-      if (c->fused2) { norm = "fused"; if (i == 1) fwd = bwd = sum = "fused"; }
+      if (c->fused2) { norm = "fused"; if (i == 1) { fwd = bwd = "fused"; sum = c->joint2 ? "joint" : "fused"; } }
       if (c->head2 && i + 2 >= c->L.size()) { norm = "head"; if (i + 1 == c->L.size()) fwd = bwd = "head"; }
       if (c->fusedcnn) fwd = bwd = norm = sum = "fused-net";
       break;
