@@ -597,7 +597,19 @@ __global__ __launch_bounds__(64 * NW) void dense_small_gemm_kernel(const SmallGe
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool second = (int)blockIdx.y >= ny0;
   const SmallGemmArgs &a = second ? p1 : p0;
-  const int m0 = blockIdx.x * 32, n0 = ((int)blockIdx.y - (second ? ny0 : 0)) * 32;
+  int tm = blockIdx.x, tn = (int)blockIdx.y - (second ? ny0 : 0);
+  if (!second) {
+    // Workgroups go to the eight XCDs in turn, each with an L2 of its own: XCD x takes a run of consecutive tiles of
+    // the list "panels of eight tile columns, row by row inside a panel", a compact block of the output, so that it
+    // reads a few row strips of A and column strips of B instead of all of one operand.
+    const int gx = gridDim.x, T = gx * ny0, L = blockIdx.x + gx * blockIdx.y;
+    const int xcd = L & 7, i = L >> 3, qn = T >> 3, rn = T & 7;
+    const int t = xcd * qn + min(xcd, rn) + i;
+    const int p = t / (gx * 8), rem = t - p * (gx * 8), w = min(8, ny0 - 8 * p);
+    tm = rem / w;
+    tn = 8 * p + (rem - tm * w);
+  }
+  const int m0 = tm * 32, n0 = tn * 32;
   const int Mtot = a.M + (a.a_ones ? 1 : 0);
   if (m0 >= Mtot) return; // (the grid is as wide as the larger of the two products; uniform, before any barrier)
   float *As = sg_lds + wave * (2 * 32 * SG_LD), *Bs = As + 32 * SG_LD;
