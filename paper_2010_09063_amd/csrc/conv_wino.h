@@ -781,14 +781,9 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
     xs_rr[j] = rr;
     xs_g[j] = 4u * (unsigned)(ch * HW + 4 * qq); // + row * W per unit
   }
-  int ds_l[DN];
-  unsigned ds_g[DN];
-#pragma unroll
-  for (int j = 0; j < DN; ++j) {
-    const int q = tid + j * 256, ch = q >> 4, part = q & 15;
-    ds_l[j] = XSZ + ch * DS + 4 * part;
-    ds_g[j] = 4u * (unsigned)(ch * HW + 4 * part);
-  }
+  // (item j of a thread: channel (tid >> 4) + 16 j, the same part: one LDS and one memory offset serve all DN items)
+  const int ds_l0 = XSZ + (tid >> 4) * DS + 4 * (tid & 15);
+  const unsigned ds_g0 = 4u * (unsigned)((tid >> 4) * HW + 4 * (tid & 15));
   float4 xv[XN], dv[DN];
   float sv = 1.f; // clip factor of the example whose unit is in the registers
   // unit u = example u / UPI, band u % UPI
@@ -805,7 +800,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
       xv[j] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int j = 0; j < DN; ++j) dv[j] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(db) + ds_g[j]);
+    for (int j = 0; j < DN; ++j) dv[j] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(db + (long)j * 16 * HW) + ds_g0);
   };
   float bsum[DN];
 #pragma unroll
@@ -829,7 +824,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
     for (int j = 0; j < DN; ++j) {
       const float4 v = NORM ? dv[j] : make_float4(dv[j].x * sv, dv[j].y * sv, dv[j].z * sv, dv[j].w * sv);
       bsum[j] += (v.x + v.y) + (v.z + v.w);
-      float *p = st + ds_l[j];
+      float *p = st + ds_l0 + j * 16 * DS;
       *reinterpret_cast<float2 *>(p) = make_float2(v.x, v.y);
       *reinterpret_cast<float2 *>(p + 2) = make_float2(v.z, v.w);
     }
@@ -864,29 +859,54 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
         fetch(nb, nband);
       }
       const float *xp = xlane + stage * STAGE, *dp = dlane + stage * STAGE;
-#pragma unroll
-      for (int kp = 0; kp < 8; ++kp) {
+      // Tile pairs in a three-deep software pipeline, spelled out for the scheduler: while the MFMAs of pair kp run,
+      // the operands of pair kp + 1 are transformed and the raw values of pair kp + 2 are read from LDS (left to
+      // itself the compiler reads, waits, transforms and then issues two pairs' MFMAs in a row, and the matrix unit
+      // idles through every read and transform).
+      float2 rx[2][4], rd[2][DB][2];
+      float bv[2][4], av[2][DB][4];
+      auto rd_raw = [&](int kp, float2 (&x4)[4], float2 (&d2)[DB][2]) {
         const int tyl = (2 * kp) / TW, cx = 2 * ((2 * kp) % TW);
-        float bv[4], av[DB][4];
-        {
-          const float2 p0 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r1) * LDW + cx);
-          const float2 p1 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r1) * LDW + cx + 2);
-          const float2 q0 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r2) * LDW + cx);
-          const float2 q1 = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r2) * LDW + cx + 2);
-          const float t0 = fmaf(s2, q0.x, p0.x), t1 = fmaf(s2, q0.y, p0.y), t2 = fmaf(s2, q1.x, p1.x), t3 = fmaf(s2, q1.y, p1.y);
-          bv[0] = t0 - t2; bv[1] = t1 + t2; bv[2] = t2 - t1; bv[3] = t1 - t3;
-        }
+        x4[0] = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r1) * LDW + cx);
+        x4[1] = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r1) * LDW + cx + 2);
+        x4[2] = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r2) * LDW + cx);
+        x4[3] = *reinterpret_cast<const float2 *>(xp + (2 * tyl + r2) * LDW + cx + 2);
 #pragma unroll
         for (int i = 0; i < DB; ++i) {
-          const float2 u0 = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * tyl) * W + cx);
-          const float2 u1 = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * tyl + 1) * W + cx);
-          const float e0 = fmaf(gb, u1.x, ga * u0.x), e1 = fmaf(gb, u1.y, ga * u0.y);
-          av[i][0] = e0; av[i][1] = e0 + e1; av[i][2] = e0 - e1; av[i][3] = -e1;
+          d2[i][0] = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * tyl) * W + cx);
+          d2[i][1] = *reinterpret_cast<const float2 *>(dp + 32 * i * DS + (2 * tyl + 1) * W + cx);
         }
+      };
+      auto transform = [&](const float2 (&x4)[4], const float2 (&d2)[DB][2], float (&b4)[4], float (&a4)[DB][4]) {
+        const float t0 = fmaf(s2, x4[2].x, x4[0].x), t1 = fmaf(s2, x4[2].y, x4[0].y);
+        const float t2 = fmaf(s2, x4[3].x, x4[1].x), t3 = fmaf(s2, x4[3].y, x4[1].y);
+        b4[0] = t0 - t2; b4[1] = t1 + t2; b4[2] = t2 - t1; b4[3] = t1 - t3;
+#pragma unroll
+        for (int i = 0; i < DB; ++i) {
+          const float e0 = fmaf(gb, d2[i][1].x, ga * d2[i][0].x), e1 = fmaf(gb, d2[i][1].y, ga * d2[i][0].y);
+          a4[i][0] = e0; a4[i][1] = e0 + e1; a4[i][2] = e0 - e1; a4[i][3] = -e1;
+        }
+      };
+      rd_raw(0, rx[0], rd[0]);
+      rd_raw(1, rx[1], rd[1]);
+      transform(rx[0], rd[0], bv[0], av[0]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kp = 0; kp < 8; ++kp) {
+        const int cur = kp & 1, nxt = cur ^ 1;
+        if (kp + 1 < 8) transform(rx[nxt], rd[nxt], bv[nxt], av[nxt]);
+        if (kp + 2 < 8) rd_raw(kp + 2, rx[cur], rd[cur]);
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-          for (int i = 0; i < DB; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i][jj], bv[jj], acc[jj][i], 0, 0, 0);
+          for (int i = 0; i < DB; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i][jj], bv[cur][jj], acc[jj][i], 0, 0, 0);
+#pragma unroll
+        for (int g = 0; g < 4 * DB; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one MFMA
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // one LDS read
+          __builtin_amdgcn_sched_group_barrier(0x002, 3, 0); // three vector-ALU instructions
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
       stage ^= 1;
     }
