@@ -105,7 +105,14 @@ def label_work(m, B, plan=None):
             fl = 2.0 * B * D_ * ckk * OH * OW
             xin, xout, wts = B * C_ * H_ * W_, B * D_ * OH * OW, D_ * ckk
             mf = lambda route: MF if route.startswith("mf") else 1.0
-            add("conv_fwd", fl, 4.0 * (xin + wts + xout), fl * mf(r.get("fwd", "")))
+            fwd_route = r.get("fwd", "")
+            if fwd_route.endswith("+maxpool"):    # pooled plane + arg-max byte instead of the plane before the pool
+                out_bytes = 5.0 * (xout // 4)
+            elif fwd_route.endswith("+avgpool"):  # both planes
+                out_bytes = 4.0 * (xout + xout // 4)
+            else:
+                out_bytes = 4.0 * xout
+            add("conv_fwd", fl, 4.0 * (xin + wts) + out_bytes, fl * mf(fwd_route))
             if li > 0:
                 add("conv_bwd_data", fl, 4.0 * (xout + wts + 2 * xin), fl * mf(r.get("bwd", "")))
             Pp = OH * OW

@@ -111,6 +111,9 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
   const int HW = a.H * W;
   const bool fwd = a.bias != nullptr;
   const bool need_side = !fwd && a.act;
+  // The plane before a fused max-pool is never read again: the next layer and the pool's backward pass (which takes
+  // the activation's derivative at the window's maximum, the pooled value) read the pooled plane.
+  const bool keep = !(fwd && a.pool == 1);
 #pragma unroll
   for (int i = 0; i < DB; ++i) {
     __syncthreads(); // every wave is done with the LDS contents of the previous phase
@@ -160,8 +163,10 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
         y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
         y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
       }
-      *reinterpret_cast<float2 *>(a.out + o) = y0;
-      *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+      if (keep) {
+        *reinterpret_cast<float2 *>(a.out + o) = y0;
+        *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+      }
     }
   }
 }
@@ -655,6 +660,18 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
             acc[jj] = __builtin_amdgcn_mfma_f32_32x32x2f32(wr[jj][KC * (CC / 2) + cp], bcur[cp][jj], acc[jj], 0, 0, 0);
           }
         }
+      // instruction order: the raw loads first, then per multiply step one LDS read and two vector operations of the
+      // next chunk's transform (left alone the compiler issues the sixteen multiplies in a row and the transform
+      // after them, and a wave's own transform never runs in the shadow of its multiplies)
+      if (FAST != 0) { // (the general variant has no registers to spare for the longer live ranges)
+        __builtin_amdgcn_sched_group_barrier(0x020, CC, 0);
+#pragma unroll
+        for (int k = 0; k < 4 * (CC / 2); ++k) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+        }
+      }
     };
     chunk(std::integral_constant<int, 0>{}, Xr + XSZ, xrB, cur, 3 * CC, bA, bB);
     chunk(std::integral_constant<int, 1>{}, Xr, xrA, nxt, 0, bB, bA);
@@ -707,8 +724,10 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
         y0.x *= act_deriv_from_out(a.act, sd0[rr].x); y0.y *= act_deriv_from_out(a.act, sd0[rr].y);
         y1.x *= act_deriv_from_out(a.act, sd1[rr].x); y1.y *= act_deriv_from_out(a.act, sd1[rr].y);
       }
-      *reinterpret_cast<float2 *>(a.out + o) = y0;
-      *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+      if (!(fwd && pool == 1)) { // (the plane before a fused max-pool is never read again)
+        *reinterpret_cast<float2 *>(a.out + o) = y0;
+        *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+      }
     }
     cur = nxt;
   }

@@ -1955,6 +1955,11 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
       break;
     case DP_CONV2D:
       fwd = l.u_f ? (l.wino_f == 2 ? "mf64" : "mf32") : (l.first_fwd ? "first" : (l.dir_fwd ? "direct" : "generic"));
+      if (l.u_f && i + 1 < c->L.size() && !c->opt.no_pool_fusion) { // the pool after the layer is taken in its epilogue
+        const dp_layer_desc &n = c->L[i + 1].d;
+        if ((n.kind == DP_MAXPOOL2D || n.kind == DP_AVGPOOL2D) && n.kh == 2 && n.kw == 2 && n.stride == 2)
+          fwd += n.kind == DP_MAXPOOL2D ? "+maxpool" : "+avgpool";
+      }
       bwd = i == 0 ? "-" : (l.u_b ? (l.wino_b == 2 ? "mf64" : "mf32") : (l.dir_bwd ? "direct" : (l.cols ? "columns" : "generic")));
       norm = l.gram ? "gram" : ((l.wino_norm && l.gst) ? "mf+store" : (l.dir_wg ? (l.gst ? "direct+store" : (l.wg_ws ? "ws" : "direct"))
                                                                                 : (l.gst ? "generic+store" : "generic")));
