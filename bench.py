@@ -88,7 +88,10 @@ def label_work(m, B, plan=None):
                 add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
             elif r.get("fwd") == "head":  # logit layer of a deeper network: forward, backward-data and both dense norms in one launch
                 add("dense2_head", 2 * fl + 2.0 * B * (di + do), 4.0 * (3 * B * di + di * do + B * do))
-                add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
+                if r.get("sum") == "joint":  # its clipped sum rides in the hidden layer's launch (delta in rows of 16 floats)
+                    add("dense_clipped_sum", fl, 4.0 * (B * di + 16 * B + di * do), layer=li - 1)
+                else:
+                    add("dense_clipped_sum", fl, 4.0 * (B * di + B * do + di * do))
             else:
                 add("dense_fwd", fl, 4.0 * (B * di + di * do + B * do))
                 if li > 0:

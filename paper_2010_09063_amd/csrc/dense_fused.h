@@ -269,7 +269,8 @@ struct Dense2Args {
   int head;
   float *slot1, *slot2; // [B] squared norms of the hidden / logit layer's gradient (may be null)
   float *a1_out;        // [B][H] or null
-  float *delta2_out;    // [B][N] (head = 1), [B][16] (head = 2)
+  float *delta2_out;    // [B][d2_ld] (head = 1), [B][16] (head = 2)
+  int d2_ld;            // head = 1: row length of delta2_out, N or 16 (zero beyond N)
 };
 
 template <int NCP>
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(DENSE1_THREADS) void dense2_mid_kernel(const Dense2
           if (a.slot1) a.slot1[bq] = (sxx + 1.f) * sd1;
           if (a.slot2) a.slot2[bq] = n2s[q];
         }
-        if (vq && hh < N) a.delta2_out[(long)bq * N + hh] = d2[q * 16 + hh];
+        if (vq && hh < a.d2_ld) a.delta2_out[(long)bq * a.d2_ld + hh] = d2[q * 16 + hh];
         if (vq && a.a1_out) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -532,6 +533,8 @@ struct SmallGemmArgs {
   float *C_ones;                   // row M of the output when a_ones (the bias gradient), indexed by n
   int M, N, K, act;
   int a_ones;                      // 1: A has one more row, m = M, that is constant 1 (then the grid covers M + 1 rows)
+  const float *k_scale;            // [K] or null: B's element (n, k) is multiplied by k_scale[k] (the clip factors of a
+                                   // clipped sum whose delta is not scaled yet); B's rows must be the contiguous index
 };
 
 typedef float sg_f32x16 __attribute__((ext_vector_type(16)));
@@ -544,6 +547,7 @@ static inline bool dense_small_gemm_fits(const SmallGemmArgs &a) {
   auto al = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
   const bool a_kc = a.a_sk == 1, b_kc = a.b_sk == 1;
   if (!al(a.A) || !al(a.B) || a.K < 1 || ((a_kc || b_kc) && (a.K & 3) != 0)) return false;
+  if (a.k_scale && b_kc) return false;
   if (a_kc ? (a.a_sr & 3) != 0 : (a.a_sr != 1 || (a.a_sk & 3) != 0 || a.a_sk < ((a.M + 3) & ~3))) return false;
   if (b_kc ? (a.b_sr & 3) != 0 : (a.b_sr != 1 || (a.b_sk & 3) != 0 || a.b_sk < ((a.N + 3) & ~3))) return false;
   return true;
@@ -618,18 +622,34 @@ __global__ __launch_bounds__(64 * NW) void dense_small_gemm_kernel(const SmallGe
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
   float4 va[4], vb[4];
+  float sb[4] = {1.f, 1.f, 1.f, 1.f}; // k_scale of vb's four items (an item of a row-contiguous operand has one k)
+  auto fetch_scale = [&](int k0) {
+    if (!B_KC && a.k_scale) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sb[q] = a.k_scale[min(k0 + ((lane + 64 * q) >> 3), a.K - 1)];
+    }
+  };
+  auto apply_scale = [&]() {
+    if (!B_KC && a.k_scale) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { vb[q].x *= sb[q]; vb[q].y *= sb[q]; vb[q].z *= sb[q]; vb[q].w *= sb[q]; }
+    }
+  };
   int sl = wave;
   if (sl < n_slices) {
     sg_fetch<A_KC>(a.A, a.a_sr, a.a_sk, m0, a.M, a.K, 32 * sl, lane, va);
     sg_fetch<B_KC>(a.B, a.b_sr, a.b_sk, n0, a.N, a.K, 32 * sl, lane, vb);
+    fetch_scale(32 * sl);
   }
   for (; sl < n_slices; sl += NW) {
+    apply_scale();
     sg_stash<A_KC>(As, m0, a.M, a.a_ones != 0, a.K, 32 * sl, lane, va);
     sg_stash<B_KC>(Bs, n0, a.N, false, a.K, 32 * sl, lane, vb);
     __builtin_amdgcn_wave_barrier(); // (the slice is read by other lanes of this wave: LDS operations of a wave complete in order)
     const int nx = min(sl + NW, n_slices - 1); // (past the wave's last slice: one is read again, unused)
     sg_fetch<A_KC>(a.A, a.a_sr, a.a_sk, m0, a.M, a.K, 32 * nx, lane, va);
     sg_fetch<B_KC>(a.B, a.b_sr, a.b_sk, n0, a.N, a.K, 32 * nx, lane, vb);
+    fetch_scale(32 * nx);
 #pragma unroll
     for (int s2 = 0; s2 < 16; ++s2)
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(As[(2 * s2 + lk) * SG_LD + li], Bs[(2 * s2 + lk) * SG_LD + li], acc, 0, 0, 0);

@@ -203,7 +203,7 @@ struct dp_ctx {
   uint32_t *xb = nullptr; int *yb = nullptr, *idx = nullptr; // dp_step_loop: the drawn minibatch (allocated on its first call)
   bool fused1 = false; // the model is one dense layer small enough for dense1_fused_kernel
   bool fusedcnn = false; float *cnn_part = nullptr; // the small MNIST-shaped CNN in one launch (cnn_small_fused_kernel)
-  bool joint2 = false; // fused2 and both clipped sums in one dense_small_gemm_kernel launch
+  bool joint2 = false; // fused2 / head2 and both clipped sums in one dense_small_gemm_kernel launch
   bool fused2 = false; // two dense layers: everything between the hidden layer's forward product and the clipped sums in dense2_mid_kernel
   // The embedding layer's counting sort of the batch's tokens depends on the inputs alone: it runs on a stream of the
   // library's own (fork / join by events) beside the forward pass.
@@ -702,14 +702,23 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
       c->fusedcnn = false;
     }
   }
+  {
+    const size_t n = c->L.size();
+    c->head2 = n >= 3 && c->L[n - 2].d.kind == DP_DENSE && c->L[n - 1].d.kind == DP_DENSE &&
+               dense1_fits(c->L[n - 1].d.in_features, c->L[n - 1].d.out_features) && !c->fusedcnn && !c->opt.no_fused_dense;
+  }
   c->fused2 = c->L.size() == 2 && c->L[0].d.kind == DP_DENSE && c->L[1].d.kind == DP_DENSE &&
               dense1_fits(c->L[1].d.in_features, c->L[1].d.out_features) && !c->opt.no_fused_dense;
-  if (c->fused2 && !c->opt.no_small_gemm && !dense_small_gemm_prepare()) { // its LDS size refused: the tiled contraction
+  if ((c->fused2 || c->head2) && !c->opt.no_small_gemm && !dense_small_gemm_prepare()) { // its LDS size refused: the tiled contraction
     (void)hipGetLastError();
     c->opt.no_small_gemm = 1;
   }
   // both clipped sums of the two-layer network in one launch of that kernel (widths in whole groups of four floats)
   c->joint2 = c->fused2 && !c->opt.no_small_gemm && c->L[0].d.in_features % 4 == 0 && c->L[0].d.out_features % 4 == 0;
+  if (c->head2 && !c->opt.no_small_gemm) { // the same for the two dense layers that close a deeper network
+    const dp_layer_desc &h = c->L[c->L.size() - 2].d;
+    c->joint2 = h.in_features % 4 == 0 && h.out_features % 4 == 0;
+  }
   if (rc == DP_OK && !c->L.empty() && c->L[0].d.kind == DP_EMBEDDING && !c->opt.no_side_stream) {
     if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
@@ -717,11 +726,6 @@ extern "C" int dp_step_init_ex(const dp_model_desc *model, int max_batch, void *
       (void)hipGetLastError();
       if (c->side) { (void)hipStreamDestroy(c->side); c->side = nullptr; } // (the step then keeps everything on one stream)
     }
-  }
-  {
-    const size_t n = c->L.size();
-    c->head2 = n >= 3 && c->L[n - 2].d.kind == DP_DENSE && c->L[n - 1].d.kind == DP_DENSE &&
-               dense1_fits(c->L[n - 1].d.in_features, c->L[n - 1].d.out_features) && !c->fusedcnn && !c->opt.no_fused_dense;
   }
   for (size_t i = 0; i < c->L.size(); ++i) {
     c->L[i].lab.reserve(sizeof(kLayerLabels) / sizeof(kLayerLabels[0]));
@@ -1070,7 +1074,7 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       const float *W = params + l.p_off;
       switch (l.d.kind) {
       case DP_DENSE: {
-        if (f2 && !c->opt.no_small_gemm) {
+        if ((f2 || (h2 && i == nL - 2)) && !c->opt.no_small_gemm) {
           // the hidden layer's forward product, complete (bias and activation applied): K split inside the workgroup
           SmallGemmArgs g{};
           g.A = in; g.a_sr = l.d.in_features; g.a_sk = 1;
@@ -1310,7 +1314,21 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       a.sdelta1 = l0.g; a.part2 = nullptr; a.norms = nullptr; a.s = nullptr;
       a.B = B; a.d_in = l0.d.in_features; a.H = l1.d.in_features; a.N = l1.d.out_features; a.act = l0.d.act;
       a.C = C; a.priv = priv ? 1 : 0;
-      a.head = 1; a.a1_out = mid_ns > 0 ? l0.a : nullptr; a.delta2_out = l1.g;
+      a.head = 1; a.a1_out = mid_ns > 0 ? l0.a : nullptr; a.delta2_out = l1.g; a.d2_ld = a.N;
+      if (c->joint2 && mid_ns == 0) {
+        // both layers' clipped sums in one launch later on (delta1, delta2 scaled by the clip factors as they are staged)
+        SmallGemmArgs &g0 = joint_g[0], &g1 = joint_g[1];
+        g0.A = a.x; g0.a_sr = 1; g0.a_sk = l0.d.in_features; g0.a_ones = 1;
+        g0.B = l0.g; g0.b_sr = 1; g0.b_sk = l0.d.out_features;
+        g0.C = l0.part; g0.c_sm = l0.d.out_features; g0.c_sn = 1; g0.C_ones = l0.part + (long)l0.d.in_features * l0.d.out_features;
+        g0.M = l0.d.in_features; g0.N = l0.d.out_features; g0.K = B; g0.act = DP_ACT_NONE;
+        g1.A = l0.a; g1.a_sr = 1; g1.a_sk = l1.d.in_features; g1.a_ones = 1;
+        g1.B = l1.g; g1.b_sr = 1; g1.b_sk = 16;
+        g1.C = l1.part; g1.c_sm = l1.d.out_features; g1.c_sn = 1; g1.C_ones = l1.part + (long)l1.d.in_features * l1.d.out_features;
+        g1.M = l1.d.in_features; g1.N = l1.d.out_features; g1.K = B; g1.act = DP_ACT_NONE;
+        joint = dense_small_gemm_fits(g0) && dense_small_gemm_fits(g1);
+        if (joint) a.d2_ld = 16;
+      }
       if (priv) {
         a.slot2 = c->slots + (long)slot_next * slot_stride;
         a.slot1 = c->slots + (long)(slot_next + 1) * slot_stride;
@@ -1648,9 +1666,11 @@ static int run_step(dp_ctx *c, const float *params, const void *x, const int32_t
       int nsplit = 1;
       switch (l.d.kind) {
       case DP_DENSE: {
-        if (joint) {
-          if (i == 0)
+        if (joint && i >= nL - 2) {
+          if (i == nL - 2) {
+            if (h2) joint_g[0].k_scale = joint_g[1].k_scale = sc; // (the head kernel could not scale: the clip factors came later)
             Ln(LL("dense_clipped_sum"), dim3(1), dim3(256), [&](hipStream_t st) { launch_dense_small_gemm(st, joint_g[0], &joint_g[1]); });
+          }
           nsplit = 1;
           break;
         }
@@ -1950,7 +1970,7 @@ extern "C" int dp_step_describe_plan(const dp_ctx *c, char *buf, size_t cap) {
       fwd = c->fused1 ? "fused" : "generic"; bwd = i > 0 ? "generic" : "-";
       norm = c->fused1 ? "fused" : "identity"; sum = c->fused1 ? "fused" : "generic";
       if (c->fused2) { norm = "fused"; if (i == 1) { fwd = bwd = "fused"; sum = c->joint2 ? "joint" : "fused"; } }
-      if (c->head2 && i + 2 >= c->L.size()) { norm = "head"; if (i + 1 == c->L.size()) fwd = bwd = "head"; }
+      if (c->head2 && i + 2 >= c->L.size()) { norm = "head"; if (i + 1 == c->L.size()) { fwd = bwd = "head"; if (c->joint2) sum = "joint"; } }
       if (c->fusedcnn) fwd = bwd = norm = sum = "fused-net";
       break;
     case DP_CONV2D:

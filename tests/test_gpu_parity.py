@@ -361,6 +361,10 @@ def test_remaining_route_switches():
         wl = W.make_workload(name, batch=batch, seed=3, bias_scale=0.2)
         _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/dense head on the generic kernels",
                            options=dict(no_fused_dense=1))
+        # the head's batch-wide contractions (hidden layer forward, both clipped sums in one launch with the clip
+        # factors applied while delta is staged) on the split-K kernels instead
+        _check_all_regimes(wl["model"], wl["x"], wl["y"], wl["params"], f"{name}/dense head, split-K contractions",
+                           options=dict(no_small_gemm=1))
     # the embedding's counting sort as three launches with per-workgroup LDS histograms (the default for batches of
     # more than 2^15 steps; smaller ones take the single-workgroup kernel)
     for name, batch in (("cfg6_embedding", 45), ("cfg5_lstm", 6)):
