@@ -407,6 +407,32 @@ def test_two_layer_models_of_other_widths():
     _check_all_regimes(m, x, y, theta, "dense 37->45->3/split-K contraction", options=dict(no_small_gemm=1))
 
 
+def test_deeper_dense_stacks():
+    """Three and four dense layers: the last two run in the head kernel.  Widths in whole groups of four floats take
+    the small contraction for the hidden layer's forward product and for both clipped sums (clip factors applied to
+    delta as it is staged: the layers below contribute to the norm, so most examples are clipped), at batches with a
+    ragged last tile; odd widths keep the split-K kernels, and every tensor boundary then falls inside a Philox block
+    of the final write."""
+    from paper_2010_09063_amd import DpStep
+    cases = (((64, 48, 36, 10), "tanh", 45), ((100, 64, 128, 32, 4), "relu", 133), ((37, 45, 33, 7, 3), "tanh", 21),
+             ((784, 256, 128, 10), "relu", 300))
+    for widths, act, batch in cases:
+        layers = [W.dense(a, b, act=act) for a, b in zip(widths[:-2], widths[1:-1])] + [W.dense(widths[-2], widths[-1])]
+        m = W.model(W.image_input(widths[0]), layers, widths[-1])
+        x, y, theta = _case(m, batch, seed=widths[1])
+        _check_all_regimes(m, x, y, theta, f"dense {'->'.join(map(str, widths))}/{act}/B{batch}")
+        st = DpStep(m, batch)
+        plan = st.dp_step_describe_plan()
+        st.dp_step_free()
+        last = plan[max(plan)]
+        assert last["fwd"] == "head" and (last["sum"] == "joint") == (widths[-3] % 4 == 0 and widths[-2] % 4 == 0), plan
+    widths = (100, 64, 128, 32, 4)
+    layers = [W.dense(a, b, act="tanh") for a, b in zip(widths[:-2], widths[1:-1])] + [W.dense(widths[-2], widths[-1])]
+    m = W.model(W.image_input(widths[0]), layers, widths[-1])
+    x, y, theta = _case(m, 57, seed=3)
+    _check_all_regimes(m, x, y, theta, "dense stack/split-K contractions", options=dict(no_small_gemm=1))
+
+
 def test_small_cnn_layer_by_layer_and_fused():
     """The MNIST-shaped CNN takes one fused launch by default; no_fused_cnn keeps it on the per-layer kernels.  Both
     routes at batches below, at and above one example per workgroup (a workgroup of the fused kernel walks through
