@@ -821,6 +821,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
 #pragma unroll
     for (int j = 0; j < DN; ++j) dv[j] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(db + (long)j * 16 * HW) + ds_g0);
   };
+  const bool bias_block = blockIdx.x == 0; // the bias gradient is taken by the workgroups of the first channel block
   float bsum[DN];
 #pragma unroll
   for (int j = 0; j < DN; ++j) bsum[j] = 0.f;
@@ -842,7 +843,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
 #pragma unroll
     for (int j = 0; j < DN; ++j) {
       const float4 v = NORM ? dv[j] : make_float4(dv[j].x * sv, dv[j].y * sv, dv[j].z * sv, dv[j].w * sv);
-      bsum[j] += (v.x + v.y) + (v.z + v.w);
+      if (bias_block) bsum[j] += (v.x + v.y) + (v.z + v.w);
       float *p = st + ds_l0 + j * 16 * DS;
       *reinterpret_cast<float2 *>(p) = make_float2(v.x, v.y);
       *reinterpret_cast<float2 *>(p + 2) = make_float2(v.z, v.w);
@@ -857,13 +858,17 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
   const float *xlane = smem + li * XS + 2 * lk;
   const float *dlane = smem + XSZ + li * DS + 2 * lk;
 
+  // (norm mode: the first tile pair of an example multiplies into a zero accumulator, so nothing is cleared here or
+  // between examples)
   f32x16 acc[4][DB];
+  if (!NORM) {
 #pragma unroll
-  for (int jj = 0; jj < 4; ++jj)
+    for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-    for (int i = 0; i < DB; ++i)
+      for (int i = 0; i < DB; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[jj][i][r] = 0.f;
+  }
 
   float *Tl = smem; // epilogue: [wave][k][r][lane]
   if (b0 < b1) fetch(b0, 0);
@@ -903,7 +908,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
 #pragma unroll
         for (int i = 0; i < DB; ++i) {
           const float e0 = fmaf(gb, d2[i][1].x, ga * d2[i][0].x), e1 = fmaf(gb, d2[i][1].y, ga * d2[i][0].y);
-          a4[i][0] = e0; a4[i][1] = e0 + e1; a4[i][2] = e0 - e1; a4[i][3] = -e1;
+          a4[i][0] = e0; a4[i][1] = e0 + e1; a4[i][2] = e0 - e1; a4[i][3] = e1; // (component 3 is -e1: the sign is taken back in the inverse transform)
         }
       };
       rd_raw(0, rx[0], rd[0]);
@@ -915,15 +920,26 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
         const int cur = kp & 1, nxt = cur ^ 1;
         if (kp + 1 < 8) transform(rx[nxt], rd[nxt], bv[nxt], av[nxt]);
         if (kp + 2 < 8) rd_raw(kp + 2, rx[cur], rd[cur]);
+        if (NORM && kp == 0 && band == 0) {
+          // the unit opens an example: its first multiplies start from zero
+          const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
+          for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-          for (int i = 0; i < DB; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i][jj], bv[cur][jj], acc[jj][i], 0, 0, 0);
+            for (int i = 0; i < DB; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i][jj], bv[cur][jj], z, 0, 0, 0);
+        } else {
 #pragma unroll
-        for (int g = 0; g < 4 * DB; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one MFMA
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // one LDS read
-          __builtin_amdgcn_sched_group_barrier(0x002, 3, 0); // three vector-ALU instructions
+          for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int i = 0; i < DB; ++i) acc[jj][i] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i][jj], bv[cur][jj], acc[jj][i], 0, 0, 0);
+        }
+        if (!(NORM && kp == 0)) {
+#pragma unroll
+          for (int g = 0; g < 4 * DB; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // one LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0); // three vector-ALU instructions
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -942,8 +958,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
         const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
         Tl[((wave * 3 + 0) * 16 + r) * 64 + lane] = m0 + hs;
         Tl[((wave * 3 + 1) * 16 + r) * 64 + lane] = hd;
-        Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs + m3;
-        acc[0][i][r] = 0.f; acc[1][i][r] = 0.f; acc[2][i][r] = 0.f; acc[3][i][r] = 0.f;
+        Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs - m3;
       }
       __syncthreads();
 #pragma unroll
@@ -992,7 +1007,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
       const float hs = 0.5f * (m1 + m2), hd = 0.5f * (m1 - m2);
       Tl[((wave * 3 + 0) * 16 + r) * 64 + lane] = m0 + hs;
       Tl[((wave * 3 + 1) * 16 + r) * 64 + lane] = hd;
-      Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs + m3;
+      Tl[((wave * 3 + 2) * 16 + r) * 64 + lane] = hs - m3;
     }
     __syncthreads();
 #pragma unroll
