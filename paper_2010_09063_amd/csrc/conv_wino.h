@@ -124,50 +124,57 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
     }
     __syncthreads();
     if (!img_ok) continue;
+    // (the activation is fixed for the launch: one branch here instead of two around every value)
+    auto finish = [&](auto act_c) {
+      constexpr int ACT = decltype(act_c)::value;
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = 4 * wave + rr;
-      const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
-      if (m >= a.M) continue;
-      float T[4][2];
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = 4 * wave + rr;
+        const int m = m0 + 32 * i + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+        if (m >= a.M) continue;
+        float T[4][2];
 #pragma unroll
-      for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
-      float2 y0, y1;
-      y0.x = T[0][0] + T[1][0] + T[2][0];
-      y0.y = T[0][1] + T[1][1] + T[2][1];
-      y1.x = T[1][0] - T[2][0] - T[3][0];
-      y1.y = T[1][1] - T[2][1] - T[3][1];
-      const long o = ((long)img * a.M + m) * HW + (2 * ty) * W + 2 * tx;
-      if (fwd) {
-        const float bv = a.bias[m];
-        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
-        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
-        if (a.pool) {
-          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
-          if (a.pool == 1) {
-            float best = y0.x; int bi = 0;
-            if (y0.y > best) { best = y0.y; bi = 1; }
-            if (y1.x > best) { best = y1.x; bi = 2; }
-            if (y1.y > best) { best = y1.y; bi = 3; }
-            a.pool_out[po] = best;
-            a.pool_arg[po] = (uint8_t)bi;
-          } else {
-            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+          for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
+        float2 y0, y1;
+        y0.x = T[0][0] + T[1][0] + T[2][0];
+        y0.y = T[0][1] + T[1][1] + T[2][1];
+        y1.x = T[1][0] - T[2][0] - T[3][0];
+        y1.y = T[1][1] - T[2][1] - T[3][1];
+        const long o = ((long)img * a.M + m) * HW + (2 * ty) * W + 2 * tx;
+        if (fwd) {
+          const float bv = a.bias[m];
+          y0.x = act_apply(ACT, y0.x + bv); y0.y = act_apply(ACT, y0.y + bv);
+          y1.x = act_apply(ACT, y1.x + bv); y1.y = act_apply(ACT, y1.y + bv);
+          if (a.pool) {
+            const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
+            if (a.pool == 1) {
+              float best = y0.x; int bi = 0;
+              if (y0.y > best) { best = y0.y; bi = 1; }
+              if (y1.x > best) { best = y1.x; bi = 2; }
+              if (y1.y > best) { best = y1.y; bi = 3; }
+              a.pool_out[po] = best;
+              a.pool_arg[po] = (uint8_t)bi;
+            } else {
+              a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+            }
           }
+        } else if (need_side) {
+          const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
+          const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
+          y0.x *= act_deriv_from_out(ACT, s0.x); y0.y *= act_deriv_from_out(ACT, s0.y);
+          y1.x *= act_deriv_from_out(ACT, s1.x); y1.y *= act_deriv_from_out(ACT, s1.y);
         }
-      } else if (need_side) {
-        const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
-        const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
-        y0.x *= act_deriv_from_out(a.act, s0.x); y0.y *= act_deriv_from_out(a.act, s0.y);
-        y1.x *= act_deriv_from_out(a.act, s1.x); y1.y *= act_deriv_from_out(a.act, s1.y);
+        if (keep) {
+          *reinterpret_cast<float2 *>(a.out + o) = y0;
+          *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+        }
       }
-      if (keep) {
-        *reinterpret_cast<float2 *>(a.out + o) = y0;
-        *reinterpret_cast<float2 *>(a.out + o + W) = y1;
-      }
-    }
+    };
+    if (a.act == DP_ACT_TANH_) finish(std::integral_constant<int, DP_ACT_TANH_>{});
+    else if (a.act == DP_ACT_RELU_) finish(std::integral_constant<int, DP_ACT_RELU_>{});
+    else finish(std::integral_constant<int, DP_ACT_NONE_>{});
   }
 }
 
@@ -687,48 +694,55 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
     }
     if (FAST == 0 && need_side) load_side(); // (the general variant has no registers to hold them any earlier)
     __syncthreads();
+    // (the activation is fixed for the launch: one branch per group instead of two around every value)
+    auto finish = [&](auto act_c) {
+      constexpr int ACT = decltype(act_c)::value;
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int r = 4 * wave + rr;
-      const int m = m0 + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
-      if (FAST == 0 && m >= a.M) continue;
-      float T[4][2];
+      for (int rr = 0; rr < 4; ++rr) {
+        const int r = 4 * wave + rr;
+        const int m = m0 + 8 * wave + 4 * lk + rr; // accumulator row r of a lane: 8*(r/4) + 4*lk + r%4
+        if (FAST == 0 && m >= a.M) continue;
+        float T[4][2];
 #pragma unroll
-      for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < 4; ++w)
 #pragma unroll
-        for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
-      float2 y0, y1;
-      y0.x = T[0][0] + T[1][0] + T[2][0];
-      y0.y = T[0][1] + T[1][1] + T[2][1];
-      y1.x = T[1][0] - T[2][0] - T[3][0];
-      y1.y = T[1][1] - T[2][1] - T[3][1];
-      const long o = obase + (long)m * HW;
-      if (fwd) {
-        const float bv = bias_r[rr];
-        y0.x = act_apply(a.act, y0.x + bv); y0.y = act_apply(a.act, y0.y + bv);
-        y1.x = act_apply(a.act, y1.x + bv); y1.y = act_apply(a.act, y1.y + bv);
-        if (pool) {
-          const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
-          if (pool == 1) {
-            float best = y0.x; int bi = 0;
-            if (y0.y > best) { best = y0.y; bi = 1; }
-            if (y1.x > best) { best = y1.x; bi = 2; }
-            if (y1.y > best) { best = y1.y; bi = 3; }
-            a.pool_out[po] = best;
-            a.pool_arg[po] = (uint8_t)bi;
-          } else {
-            a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+          for (int k = 0; k < 2; ++k) T[w][k] = Tl[((w * 2 + k) * 16 + r) * 64 + lane];
+        float2 y0, y1;
+        y0.x = T[0][0] + T[1][0] + T[2][0];
+        y0.y = T[0][1] + T[1][1] + T[2][1];
+        y1.x = T[1][0] - T[2][0] - T[3][0];
+        y1.y = T[1][1] - T[2][1] - T[3][1];
+        const long o = obase + (long)m * HW;
+        if (fwd) {
+          const float bv = bias_r[rr];
+          y0.x = act_apply(ACT, y0.x + bv); y0.y = act_apply(ACT, y0.y + bv);
+          y1.x = act_apply(ACT, y1.x + bv); y1.y = act_apply(ACT, y1.y + bv);
+          if (pool) {
+            const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
+            if (pool == 1) {
+              float best = y0.x; int bi = 0;
+              if (y0.y > best) { best = y0.y; bi = 1; }
+              if (y1.x > best) { best = y1.x; bi = 2; }
+              if (y1.y > best) { best = y1.y; bi = 3; }
+              a.pool_out[po] = best;
+              a.pool_arg[po] = (uint8_t)bi;
+            } else {
+              a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+            }
           }
+        } else if (need_side) {
+          y0.x *= act_deriv_from_out(ACT, sd0[rr].x); y0.y *= act_deriv_from_out(ACT, sd0[rr].y);
+          y1.x *= act_deriv_from_out(ACT, sd1[rr].x); y1.y *= act_deriv_from_out(ACT, sd1[rr].y);
         }
-      } else if (need_side) {
-        y0.x *= act_deriv_from_out(a.act, sd0[rr].x); y0.y *= act_deriv_from_out(a.act, sd0[rr].y);
-        y1.x *= act_deriv_from_out(a.act, sd1[rr].x); y1.y *= act_deriv_from_out(a.act, sd1[rr].y);
+        if (!(fwd && pool == 1)) { // (the plane before a fused max-pool is never read again)
+          *reinterpret_cast<float2 *>(a.out + o) = y0;
+          *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+        }
       }
-      if (!(fwd && pool == 1)) { // (the plane before a fused max-pool is never read again)
-        *reinterpret_cast<float2 *>(a.out + o) = y0;
-        *reinterpret_cast<float2 *>(a.out + o + W) = y1;
-      }
-    }
+    };
+    if (a.act == DP_ACT_TANH_) finish(std::integral_constant<int, DP_ACT_TANH_>{});
+    else if (a.act == DP_ACT_RELU_) finish(std::integral_constant<int, DP_ACT_RELU_>{});
+    else finish(std::integral_constant<int, DP_ACT_NONE_>{});
     cur = nxt;
   }
 }
