@@ -557,6 +557,12 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
   const int r2 = wave == 0 ? 2 : (wave == 1 ? 2 : (wave == 2 ? 1 : 3));
   const float s2 = wave == 1 ? 1.f : -1.f;
 
+  // Epilogue addresses (FAST variants): a uniform pointer per group and accumulator row + the lane's byte offset, so
+  // that no 64-bit vector arithmetic is left in the epilogue.  Lane part: output channel 8 wave + 4 lk of the block,
+  // tile (tyl, tx) of the band.
+  const unsigned lane_o = 4u * (unsigned)((8 * wave + 4 * lk) * HW + (2 * tyl) * W + 2 * tx);
+  const unsigned lane_p = 4u * (unsigned)((8 * wave + 4 * lk) * (HW >> 2) + tyl * (W >> 1) + tx);
+
   // staging: thread tid owns position tid of the haloed band for the 8 channels of a chunk.  The loads are buffer
   // loads: a resource descriptor per band (it starts one pixel row above the band, so lane offsets are never
   // negative; only addresses of real pixels are ever formed from it), the channel in the scalar offset, and a lane
@@ -636,14 +642,23 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
     const Grp nxt = setup(min(g + 1, g_end - 1)); // past the run's last group: re-read it (unused)
     const int img = cur.img, ty = cur.row0 / 2 + tyl;
     const long obase = ((long)img * a.M) * HW + (2 * ty) * W + 2 * tx;
+    // the group's origin in the output / activation planes and in the pooled planes (uniform; FAST variants)
+    const long og0 = ((long)img * a.M + m0) * HW + (long)cur.row0 * W;
+    const long pg0 = ((long)img * a.M + m0) * (HW >> 2) + (long)(cur.row0 >> 1) * (W >> 1);
     float2 sd0[4], sd1[4];
 
     auto load_side = [&]() {
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
-        const long o = obase + (long)min(m0 + 8 * wave + 4 * lk + rr, a.M - 1) * HW;
-        sd0[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o);
-        sd1[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
+        if (FAST != 0) {
+          const char *sp = reinterpret_cast<const char *>(a.a_prev + og0 + (long)rr * HW);
+          sd0[rr] = *reinterpret_cast<const float2 *>(sp + lane_o);
+          sd1[rr] = *reinterpret_cast<const float2 *>(sp + lane_o + 4u * W);
+        } else {
+          const long o = obase + (long)min(m0 + 8 * wave + 4 * lk + rr, a.M - 1) * HW;
+          sd0[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o);
+          sd1[rr] = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
+        }
       }
     };
     // chunk KC of the group: the chunk after it goes from registers (src_regs) to LDS, the chunk three ahead (chunk
@@ -718,16 +733,19 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
           y0.x = act_apply(ACT, y0.x + bv); y0.y = act_apply(ACT, y0.y + bv);
           y1.x = act_apply(ACT, y1.x + bv); y1.y = act_apply(ACT, y1.y + bv);
           if (pool) {
+            const long pg = pg0 + (long)rr * (HW >> 2); // (uniform)
             const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
+            float *pout = FAST != 0 ? reinterpret_cast<float *>(reinterpret_cast<char *>(a.pool_out + pg) + lane_p) : a.pool_out + po;
             if (pool == 1) {
               float best = y0.x; int bi = 0;
               if (y0.y > best) { best = y0.y; bi = 1; }
               if (y1.x > best) { best = y1.x; bi = 2; }
               if (y1.y > best) { best = y1.y; bi = 3; }
-              a.pool_out[po] = best;
-              a.pool_arg[po] = (uint8_t)bi;
+              *pout = best;
+              if (FAST != 0) *(a.pool_arg + pg + (lane_p >> 2)) = (uint8_t)bi;
+              else a.pool_arg[po] = (uint8_t)bi;
             } else {
-              a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
+              *pout = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
             }
           }
         } else if (need_side) {
@@ -735,8 +753,14 @@ void conv_wino_res_kernel(const ConvWinoArgs a, const int n_groups, const int gr
           y1.x *= act_deriv_from_out(ACT, sd1[rr].x); y1.y *= act_deriv_from_out(ACT, sd1[rr].y);
         }
         if (!(fwd && pool == 1)) { // (the plane before a fused max-pool is never read again)
-          *reinterpret_cast<float2 *>(a.out + o) = y0;
-          *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+          if (FAST != 0) {
+            char *op = reinterpret_cast<char *>(a.out + og0 + (long)rr * HW); // (uniform)
+            *reinterpret_cast<float2 *>(op + lane_o) = y0;
+            *reinterpret_cast<float2 *>(op + lane_o + 4u * W) = y1;
+          } else {
+            *reinterpret_cast<float2 *>(a.out + o) = y0;
+            *reinterpret_cast<float2 *>(a.out + o + W) = y1;
+          }
         }
       }
     };
