@@ -111,9 +111,8 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
   const int HW = a.H * W;
   const bool fwd = a.bias != nullptr;
   const bool need_side = !fwd && a.act;
-  // The plane before a fused max-pool is never read again: the next layer and the pool's backward pass (which takes
-  // the activation's derivative at the window's maximum, the pooled value) read the pooled plane.
-  const bool keep = !(fwd && a.pool == 1);
+  // (The plane before a fused max-pool is never read again: the next layer and the pool's backward pass, which takes
+  // the activation's derivative at the window's maximum, the pooled value, read the pooled plane.)
 #pragma unroll
   for (int i = 0; i < DB; ++i) {
     __syncthreads(); // every wave is done with the LDS contents of the previous phase
@@ -124,9 +123,11 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
     }
     __syncthreads();
     if (!img_ok) continue;
-    // (the activation is fixed for the launch: one branch here instead of two around every value)
-    auto finish = [&](auto act_c) {
-      constexpr int ACT = decltype(act_c)::value;
+    // (activation, direction and pool are fixed for the launch: the body is compiled per combination and chosen once
+    // here, instead of uniform branches around every value.  MODE: 0 forward, 1 forward + max-pool, 2 forward +
+    // average pool, 3 backward-data through an activation, 4 backward-data)
+    auto finish = [&](auto act_c, auto mode_c) {
+      constexpr int ACT = decltype(act_c)::value, MODE = decltype(mode_c)::value;
 #pragma unroll
       for (int rr = 0; rr < 4; ++rr) {
         const int r = 4 * wave + rr;
@@ -143,13 +144,13 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
         y1.x = T[1][0] - T[2][0] - T[3][0];
         y1.y = T[1][1] - T[2][1] - T[3][1];
         const long o = ((long)img * a.M + m) * HW + (2 * ty) * W + 2 * tx;
-        if (fwd) {
+        if (MODE <= 2) {
           const float bv = a.bias[m];
           y0.x = act_apply(ACT, y0.x + bv); y0.y = act_apply(ACT, y0.y + bv);
           y1.x = act_apply(ACT, y1.x + bv); y1.y = act_apply(ACT, y1.y + bv);
-          if (a.pool) {
+          if (MODE == 1 || MODE == 2) {
             const long po = ((long)img * a.M + m) * (HW >> 2) + ty * (W >> 1) + tx;
-            if (a.pool == 1) {
+            if (MODE == 1) {
               float best = y0.x; int bi = 0;
               if (y0.y > best) { best = y0.y; bi = 1; }
               if (y1.x > best) { best = y1.x; bi = 2; }
@@ -160,21 +161,32 @@ DEVI void wino_store_tiles(const ConvWinoArgs &a, float *Tl, const f32x16 (&acc)
               a.pool_out[po] = ((y0.x + y0.y) + (y1.x + y1.y)) * 0.25f;
             }
           }
-        } else if (need_side) {
+        } else if (MODE == 3) {
           const float2 s0 = *reinterpret_cast<const float2 *>(a.a_prev + o);
           const float2 s1 = *reinterpret_cast<const float2 *>(a.a_prev + o + W);
           y0.x *= act_deriv_from_out(ACT, s0.x); y0.y *= act_deriv_from_out(ACT, s0.y);
           y1.x *= act_deriv_from_out(ACT, s1.x); y1.y *= act_deriv_from_out(ACT, s1.y);
         }
-        if (keep) {
+        if (MODE != 1) { // (the plane before a fused max-pool is never read again)
           *reinterpret_cast<float2 *>(a.out + o) = y0;
           *reinterpret_cast<float2 *>(a.out + o + W) = y1;
         }
       }
     };
-    if (a.act == DP_ACT_TANH_) finish(std::integral_constant<int, DP_ACT_TANH_>{});
-    else if (a.act == DP_ACT_RELU_) finish(std::integral_constant<int, DP_ACT_RELU_>{});
-    else finish(std::integral_constant<int, DP_ACT_NONE_>{});
+    auto with_mode = [&](auto act_c) {
+      if (fwd) {
+        if (a.pool == 1) finish(act_c, std::integral_constant<int, 1>{});
+        else if (a.pool) finish(act_c, std::integral_constant<int, 2>{});
+        else finish(act_c, std::integral_constant<int, 0>{});
+      } else if (need_side) {
+        finish(act_c, std::integral_constant<int, 3>{});
+      } else {
+        finish(act_c, std::integral_constant<int, 4>{});
+      }
+    };
+    if (a.act == DP_ACT_TANH_) with_mode(std::integral_constant<int, DP_ACT_TANH_>{});
+    else if (a.act == DP_ACT_RELU_) with_mode(std::integral_constant<int, DP_ACT_RELU_>{});
+    else with_mode(std::integral_constant<int, DP_ACT_NONE_>{});
   }
 }
 
