@@ -864,7 +864,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
 #pragma unroll
     for (int j = 0; j < XN; ++j) {
       const int ih = r0 - 1 + xs_rr[j];
-      const bool ok = xs_l[j] >= 0 && (unsigned)ih < (unsigned)a.H;
+      const bool ok = (XITEMS % 256 == 0 || xs_l[j] >= 0) && (unsigned)ih < (unsigned)a.H;
       const float4 v = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(xb) + (ok ? xs_g[j] + 4u * (unsigned)(ih * W) : 0u));
       xv[j] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -878,7 +878,7 @@ void conv_wino_wgrad_unit_kernel(const ConvWinoWgUnitArgs a) {
   auto store = [&](float *st) {
 #pragma unroll
     for (int j = 0; j < XN; ++j)
-      if (xs_l[j] >= 0) {
+      if (XITEMS % 256 == 0 || xs_l[j] >= 0) { // (whole rounds of the workgroup: every item is real)
         float *p = st + xs_l[j];
         p[0] = xv[j].x; p[1] = xv[j].y; p[2] = xv[j].z; p[3] = xv[j].w;
       }
