@@ -433,6 +433,50 @@ def test_deeper_dense_stacks():
     _check_all_regimes(m, x, y, theta, "dense stack/split-K contractions", options=dict(no_small_gemm=1))
 
 
+def test_seeded_random_architectures():
+    """Architectures drawn from a seeded generator, within the documented limits: dense stacks of two to four layers
+    (widths in whole groups of four floats or not, up to 900 inputs, 2 to 14 classes) and pad-1 3x3 convolution
+    stacks on 8-, 16- and 32-wide planes with max- and average-pools between them (3 to 64 channels, one or two dense
+    layers at the end), each with the planner's own routes or with the minimal-filtering kernels forced."""
+    rng = np.random.default_rng(2024)
+    for it in range(14):
+        depth = int(rng.integers(2, 5))
+        mult4 = rng.random() < 0.7
+        def width(lo, hi):
+            w = int(rng.integers(lo, hi))
+            return max(4, (w // 4) * 4) if mult4 else w
+        widths = [width(4, 900)] + [width(4, 300) for _ in range(depth - 1)] + [int(rng.integers(2, 15))]
+        act = ["tanh", "relu"][int(rng.integers(0, 2))]
+        batch = int(rng.integers(1, 400))
+        layers = [W.dense(a, b, act=act) for a, b in zip(widths[:-2], widths[1:-1])] + [W.dense(widths[-2], widths[-1])]
+        m = W.model(W.image_input(widths[0]), layers, widths[-1])
+        x, y, theta = _case(m, batch, seed=it)
+        _check_all_regimes(m, x, y, theta, f"random dense {widths} {act} B{batch}")
+    rng = np.random.default_rng(77)
+    for it in range(12):
+        plane = int(rng.choice([8, 16, 32]))
+        chans = [int(rng.choice([3, 8, 16, 32]))]
+        layers, h = [], plane
+        for _ in range(int(rng.integers(2, 5))):
+            co = int(rng.choice([8, 20, 32, 40, 64] if plane * plane * max(chans) <= 32768 else [8, 16, 32]))
+            layers.append(W.conv2d(chans[-1], co, 3, stride=1, pad=1, act=["tanh", "relu"][int(rng.integers(0, 2))]))
+            chans.append(co)
+            if h >= 8 and rng.random() < 0.6:
+                layers.append(W.maxpool2d(2, 2) if rng.random() < 0.75 else W.avgpool2d(2, 2))
+                h //= 2
+        feat, k = chans[-1] * h * h, int(rng.integers(2, 11))
+        if rng.random() < 0.5:
+            hid = int(rng.choice([16, 30, 64]))
+            layers += [W.dense(feat, hid, act="tanh"), W.dense(hid, k)]
+        else:
+            layers += [W.dense(feat, k)]
+        m = W.model(W.image_input(chans[0], plane, plane), layers, k)
+        batch = int(rng.integers(1, 40))
+        opts = [None, dict(minimal_filtering_all=1)][int(rng.integers(0, 2))]
+        x, y, theta = _case(m, batch, seed=it)
+        _check_all_regimes(m, x, y, theta, f"random conv {it}: plane {plane}, channels {chans}, B{batch}", options=opts)
+
+
 def test_small_cnn_layer_by_layer_and_fused():
     """The MNIST-shaped CNN takes one fused launch by default; no_fused_cnn keeps it on the per-layer kernels.  Both
     routes at batches below, at and above one example per workgroup (a workgroup of the fused kernel walks through
